@@ -1,0 +1,165 @@
+"""ctypes front end of the CPU oracle (oracle/rd_oracle.c).  TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import this
+package.  It takes and returns numpy arrays, never touches a GPU, and imports
+nothing from the HIP package.  bf16 tensors travel as uint16 bit patterns.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "rd_oracle.c")
+_LIB = os.path.join(_HERE, "librd_oracle.so")
+
+DTYPES = {"f32": 0, "bf16": 1}
+
+
+def build(force: bool = False) -> str:
+    """Compile rd_oracle.c with gcc (-O2, OpenMP) into oracle/librd_oracle.so."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall",
+                               "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.orc_num_threads.restype = ctypes.c_int
+    return _lib
+
+
+def num_threads() -> int:
+    return int(lib().orc_num_threads())
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def dedup(beams: np.ndarray, ctx_len: Optional[np.ndarray] = None) -> dict:
+    """dedup_prefix + pack_beam + tree structure for beams [B,W,L] (or [W,L])."""
+    beams = _i32(beams)
+    squeeze = beams.ndim == 2
+    if squeeze:
+        beams = beams[None]
+    B, W, L = beams.shape
+    N = W * L
+    words = (N + 63) // 64
+    ctx = None if ctx_len is None else _i32(np.reshape(ctx_len, (B,)))
+    out = dict(
+        prefix_tree=np.empty((B, W, L), np.int32),
+        packed_tokens=np.empty((B, N), np.int32),
+        n_packed=np.empty((B,), np.int32),
+        unpack_index=np.empty((B, W, L), np.int32),
+        parent=np.empty((B, N), np.int32),
+        position_ids=np.empty((B, N), np.int32),
+        tree_mask=np.empty((B, N, N), np.uint8),
+        tree_mask_bits=np.empty((B, N, words), np.uint64),
+    )
+    lib().orc_dedup(_p(beams), _p(ctx), B, W, L, _p(out["prefix_tree"]), _p(out["packed_tokens"]),
+                    _p(out["n_packed"]), _p(out["unpack_index"]), _p(out["parent"]),
+                    _p(out["position_ids"]), _p(out["tree_mask"]), _p(out["tree_mask_bits"]))
+    if squeeze:
+        out = {k: v[0] for k, v in out.items()}
+    return out
+
+
+def _check_attn(q, k_cache, v_cache, k_new, v_new, dtype):
+    want = np.uint16 if dtype == "bf16" else np.float32
+    arrs = []
+    for a in (q, k_cache, v_cache, k_new, v_new):
+        a = np.ascontiguousarray(a)
+        assert a.dtype == want, (a.dtype, want)
+        arrs.append(a)
+    B, H, N, D = arrs[0].shape
+    Cmax = arrs[1].shape[2]
+    assert arrs[1].shape == (B, H, Cmax, D) and arrs[2].shape == (B, H, Cmax, D)
+    assert arrs[3].shape == (B, H, N, D) and arrs[4].shape == (B, H, N, D)
+    return arrs, (B, H, N, D, Cmax)
+
+
+def tree_attn(q, k_cache, v_cache, ctx_len, k_new, v_new, n_packed, tree_mask,
+              dtype: str, scale: float) -> np.ndarray:
+    """Tree-masked attention, whole tensor; returns [B,H,N,D] in the storage dtype."""
+    (q, k_cache, v_cache, k_new, v_new), (B, H, N, D, Cmax) = _check_attn(
+        q, k_cache, v_cache, k_new, v_new, dtype)
+    ctx_len, n_packed = _i32(ctx_len), _i32(n_packed)
+    tree_mask = np.ascontiguousarray(tree_mask, dtype=np.uint8)
+    assert tree_mask.shape == (B, N, N)
+    out = np.empty_like(q)
+    lib().orc_tree_attn(_p(q), _p(k_cache), _p(v_cache), _p(ctx_len), _p(k_new), _p(v_new),
+                        _p(n_packed), _p(tree_mask), B, H, N, D, Cmax, DTYPES[dtype],
+                        ctypes.c_float(scale), _p(out))
+    return out
+
+
+def tree_attn_rows(q, k_cache, v_cache, ctx_len, k_new, v_new, n_packed, tree_mask,
+                   dtype: str, scale: float, rows) -> np.ndarray:
+    """Attention output of selected (b, h, p) rows as unrounded float64 [n_rows, D]."""
+    (q, k_cache, v_cache, k_new, v_new), (B, H, N, D, Cmax) = _check_attn(
+        q, k_cache, v_cache, k_new, v_new, dtype)
+    ctx_len, n_packed = _i32(ctx_len), _i32(n_packed)
+    tree_mask = np.ascontiguousarray(tree_mask, dtype=np.uint8)
+    rows = _i32(rows).reshape(-1, 3)
+    for b, h, p in rows:
+        assert 0 <= b < B and 0 <= h < H and 0 <= p < n_packed[b]
+    out = np.empty((rows.shape[0], D), np.float64)
+    lib().orc_tree_attn_rows(_p(q), _p(k_cache), _p(v_cache), _p(ctx_len), _p(k_new), _p(v_new),
+                             _p(n_packed), _p(tree_mask), B, H, N, D, Cmax, DTYPES[dtype],
+                             ctypes.c_float(scale), _p(rows), rows.shape[0], _p(out))
+    return out
+
+
+def argmax(logits: np.ndarray, n_packed: np.ndarray) -> np.ndarray:
+    logits = np.ascontiguousarray(logits, dtype=np.float32)
+    B, N, V = logits.shape
+    n_packed = _i32(n_packed)
+    out = np.empty((B, N), np.int32)
+    lib().orc_argmax(_p(logits), _p(n_packed), B, N, V, _p(out))
+    return out
+
+
+def accept(beams, unpack_index, argmax_in, root_token=None) -> dict:
+    beams, unpack_index, argmax_in = _i32(beams), _i32(unpack_index), _i32(argmax_in)
+    B, W, L = beams.shape
+    root = None if root_token is None else _i32(root_token)
+    out = dict(
+        n_accept=np.empty((B, W), np.int32),
+        best_beam=np.empty((B,), np.int32),
+        best_len=np.empty((B,), np.int32),
+        next_token=np.empty((B,), np.int32),
+        accepted_idx=np.empty((B, L), np.int32),
+    )
+    lib().orc_accept(_p(beams), _p(unpack_index), _p(argmax_in), _p(root), B, W, L,
+                     _p(out["n_accept"]), _p(out["best_beam"]), _p(out["best_len"]),
+                     _p(out["next_token"]), _p(out["accepted_idx"]))
+    return out
+
+
+def verify_step(beams, ctx_len, q, k_cache, v_cache, k_new, v_new, logits, dtype, scale,
+                root_token=None) -> dict:
+    """The whole path in order: dedup -> tree attention -> argmax -> accept."""
+    d = dedup(beams, ctx_len)
+    out = dict(d)
+    out["attn_out"] = tree_attn(q, k_cache, v_cache, ctx_len, k_new, v_new, d["n_packed"],
+                                d["tree_mask"], dtype, scale)
+    out["argmax"] = argmax(logits, d["n_packed"])
+    out.update(accept(beams, d["unpack_index"], out["argmax"], root_token))
+    return out

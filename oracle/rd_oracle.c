@@ -1,0 +1,368 @@
+/*
+ * CPU oracle for the ReDrafter verification step.  TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, definition-level implementation of what the verification step
+ * computes (dynamic tree attention, Sec. 3.3 and App. A.1; verification and greedy
+ * acceptance, Sec. 3.4).  It exists so that the HIP path can be checked against
+ * something that is easy to compare with the paper by eye.  It shares no code
+ * with the HIP path and must never be called from it; only tests, the smoke
+ * check and the benchmark's CPU-baseline leg use it.
+ *
+ * Everything here is per sequence; a batch is B independent sequences
+ * (App. A.1: a batch dimension is simply prepended).
+ *
+ * Floating point: inputs are upcast exactly to double, all arithmetic is double,
+ * the result is rounded once (round-to-nearest-even) to the storage type.
+ *
+ * Every function in this file is pinned by tests that do not use this file's
+ * own arithmetic (the worked example of App. A.1, a literal prefix trie, closed
+ * forms, per-beam causal attention in numpy, library argmax, a toy greedy LM).
+ *
+ * OpenMP (if enabled at compile time) parallelises only over independent
+ * (sequence, head) pairs or logit rows; the arithmetic per output is unchanged.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORC_F32 0
+#define ORC_BF16 1
+
+int orc_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* ------------------------------------------------------------------------- */
+/* dedup_prefix (App. A.1): prefix_tree[i][j] is the smallest candidate index k
+ * whose first j+1 tokens equal candidate i's first j+1 tokens.               */
+/* ------------------------------------------------------------------------- */
+void orc_dedup_prefix(const int32_t *beam, int W, int L, int32_t *prefix_tree)
+{
+    for (int i = 0; i < W; ++i) {
+        for (int j = 0; j < L; ++j) {
+            int found = i;
+            for (int k = 0; k <= i; ++k) {
+                int same = 1;
+                for (int t = 0; t <= j; ++t)
+                    if (beam[k * L + t] != beam[i * L + t]) same = 0;
+                if (same) { found = k; break; }
+            }
+            prefix_tree[i * L + j] = found;
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------- */
+/* pack_beam (Sec. 3.3, App. A.1): a token can be condensed away when
+ * prefix_tree[i][j] < i, so the kept ones are those with prefix_tree[i][j] == i.
+ * Kept tokens are numbered in row-major (candidate, position) order.
+ * Outputs (N = W*L entries each, padded with -1 beyond the packed count P):
+ *   packed_tokens[p], src_beam[p], depth[p];  unpack_index[i][j] = packed slot
+ *   that holds candidate i's j-th token.  Returns P.                          */
+/* ------------------------------------------------------------------------- */
+int orc_pack_beam(const int32_t *beam, const int32_t *prefix_tree, int W, int L,
+                  int32_t *packed_tokens, int32_t *src_beam, int32_t *depth,
+                  int32_t *unpack_index)
+{
+    const int N = W * L;
+    int32_t *slot = (int32_t *)malloc(sizeof(int32_t) * (size_t)N);
+    int P = 0;
+    for (int i = 0; i < W; ++i)
+        for (int j = 0; j < L; ++j) {
+            if (prefix_tree[i * L + j] == i) {
+                slot[i * L + j] = P;
+                packed_tokens[P] = beam[i * L + j];
+                src_beam[P] = i;
+                depth[P] = j;
+                ++P;
+            } else {
+                slot[i * L + j] = -1;
+            }
+        }
+    for (int p = P; p < N; ++p) {
+        packed_tokens[p] = -1;
+        src_beam[p] = -1;
+        depth[p] = -1;
+    }
+    for (int i = 0; i < W; ++i)
+        for (int j = 0; j < L; ++j)
+            unpack_index[i * L + j] = slot[prefix_tree[i * L + j] * L + j];
+    free(slot);
+    return P;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Tree structure of the packed beam (Sec. 3.3, Fig. 3): a packed token depends
+ * on the packed tokens that hold the earlier positions of its own candidate,
+ * and on itself.  ctx_len < 0 means "no context": position ids are depths.    */
+/* ------------------------------------------------------------------------- */
+void orc_tree_structure(const int32_t *unpack_index, const int32_t *src_beam,
+                        const int32_t *depth, int P, int W, int L, int ctx_len,
+                        int32_t *parent, int32_t *position_ids,
+                        uint8_t *tree_mask /* [N,N] */,
+                        uint64_t *tree_mask_bits /* [N, ceil(N/64)] */)
+{
+    const int N = W * L;
+    const int words = (N + 63) / 64;
+    memset(tree_mask, 0, (size_t)N * (size_t)N);
+    memset(tree_mask_bits, 0, sizeof(uint64_t) * (size_t)N * (size_t)words);
+    for (int p = 0; p < N; ++p) {
+        if (p >= P) { parent[p] = -1; position_ids[p] = -1; continue; }
+        const int i = src_beam[p];
+        const int j = depth[p];
+        parent[p] = (j == 0) ? -1 : unpack_index[i * L + (j - 1)];
+        position_ids[p] = (ctx_len < 0 ? 0 : ctx_len) + j;
+        for (int t = 0; t <= j; ++t) {
+            const int q = unpack_index[i * L + t];
+            tree_mask[(size_t)p * N + q] = 1;
+            tree_mask_bits[(size_t)p * words + (q >> 6)] |= (uint64_t)1 << (q & 63);
+        }
+    }
+}
+
+/* Batched front end for the three integer steps above. */
+void orc_dedup(const int32_t *beams /*[B,W,L]*/, const int32_t *ctx_len /*[B] or NULL*/,
+               int B, int W, int L,
+               int32_t *prefix_tree, int32_t *packed_tokens, int32_t *n_packed,
+               int32_t *unpack_index, int32_t *parent, int32_t *position_ids,
+               uint8_t *tree_mask, uint64_t *tree_mask_bits)
+{
+    const int N = W * L;
+    const int words = (N + 63) / 64;
+    int32_t *src_beam = (int32_t *)malloc(sizeof(int32_t) * (size_t)N);
+    int32_t *depth = (int32_t *)malloc(sizeof(int32_t) * (size_t)N);
+    for (int b = 0; b < B; ++b) {
+        const int32_t *beam = beams + (size_t)b * N;
+        int32_t *pt = prefix_tree + (size_t)b * N;
+        int32_t *ui = unpack_index + (size_t)b * N;
+        orc_dedup_prefix(beam, W, L, pt);
+        const int P = orc_pack_beam(beam, pt, W, L, packed_tokens + (size_t)b * N,
+                                    src_beam, depth, ui);
+        n_packed[b] = P;
+        orc_tree_structure(ui, src_beam, depth, P, W, L, ctx_len ? ctx_len[b] : -1,
+                           parent + (size_t)b * N, position_ids + (size_t)b * N,
+                           tree_mask + (size_t)b * N * N,
+                           tree_mask_bits + (size_t)b * N * words);
+    }
+    free(src_beam);
+    free(depth);
+}
+
+/* ------------------------------------------------------------------------- */
+/* storage formats                                                             */
+/* ------------------------------------------------------------------------- */
+static double load_elem(const void *base, size_t idx, int dtype)
+{
+    if (dtype == ORC_BF16) {
+        uint32_t u = (uint32_t)((const uint16_t *)base)[idx] << 16;
+        float f;
+        memcpy(&f, &u, 4);
+        return (double)f;
+    }
+    return (double)((const float *)base)[idx];
+}
+
+static uint16_t double_to_bf16(double x)
+{
+    /* one rounding, ties to even, from the double straight to 8 significand bits */
+    if (isnan(x)) return 0x7FC0;
+    float f;
+    if (isinf(x) || x == 0.0) {
+        f = (float)x;
+    } else {
+        int e;
+        (void)frexp(fabs(x), &e);          /* |x| = m * 2^e with m in [0.5, 1) */
+        int qexp = e - 8;                  /* exponent of the last kept bit */
+        if (qexp < -133) qexp = -133;      /* bf16 subnormal spacing */
+        const double r = nearbyint(ldexp(x, -qexp));   /* default mode: ties to even */
+        f = (float)ldexp(r, qexp);         /* exact, or +-inf on overflow */
+    }
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    return (uint16_t)(u >> 16);
+}
+
+static void store_elem(void *base, size_t idx, int dtype, double x)
+{
+    if (dtype == ORC_BF16) ((uint16_t *)base)[idx] = double_to_bf16(x);
+    else ((float *)base)[idx] = (float)x;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Tree-masked attention of one packed token (Sec. 3.3/3.4): softmax over all
+ * context keys c < ctx_len and over the packed keys its mask row allows, of
+ * scale * <q_p, k>, applied to the values.  Masked keys are absent from the
+ * softmax.  Result in out_row[0..D).                                          */
+/* ------------------------------------------------------------------------- */
+static void attn_row(const void *q, const void *k_cache, const void *v_cache,
+                     const void *k_new, const void *v_new, const uint8_t *mask_row,
+                     int ctx, int P, int N, int D, int Cmax, int dtype, double scale,
+                     size_t bh, int p, double *s /* [Cmax+N] */, double *out_row)
+{
+    const size_t qoff = (bh * (size_t)N + (size_t)p) * (size_t)D;
+    const size_t cbase = bh * (size_t)Cmax * (size_t)D;
+    const size_t nbase = bh * (size_t)N * (size_t)D;
+    int n = 0;
+    double m = -INFINITY;
+    for (int c = 0; c < ctx; ++c) {
+        double dot = 0.0;
+        for (int d = 0; d < D; ++d)
+            dot += load_elem(q, qoff + d, dtype) * load_elem(k_cache, cbase + (size_t)c * D + d, dtype);
+        s[n] = scale * dot;
+        if (s[n] > m) m = s[n];
+        ++n;
+    }
+    for (int t = 0; t < P; ++t) {
+        if (!mask_row[t]) continue;
+        double dot = 0.0;
+        for (int d = 0; d < D; ++d)
+            dot += load_elem(q, qoff + d, dtype) * load_elem(k_new, nbase + (size_t)t * D + d, dtype);
+        s[n] = scale * dot;
+        if (s[n] > m) m = s[n];
+        ++n;
+    }
+    double denom = 0.0;
+    for (int d = 0; d < D; ++d) out_row[d] = 0.0;
+    n = 0;
+    for (int c = 0; c < ctx; ++c) {
+        const double w = exp(s[n++] - m);
+        denom += w;
+        for (int d = 0; d < D; ++d)
+            out_row[d] += w * load_elem(v_cache, cbase + (size_t)c * D + d, dtype);
+    }
+    for (int t = 0; t < P; ++t) {
+        if (!mask_row[t]) continue;
+        const double w = exp(s[n++] - m);
+        denom += w;
+        for (int d = 0; d < D; ++d)
+            out_row[d] += w * load_elem(v_new, nbase + (size_t)t * D + d, dtype);
+    }
+    for (int d = 0; d < D; ++d) out_row[d] /= denom;
+}
+
+static int clampi(int x, int lo, int hi) { return x < lo ? lo : (x > hi ? hi : x); }
+
+/* Whole tensor: out [B,H,N,D] in the storage dtype; rows p >= n_packed[b] are zero. */
+void orc_tree_attn(const void *q, const void *k_cache, const void *v_cache,
+                   const int32_t *ctx_len, const void *k_new, const void *v_new,
+                   const int32_t *n_packed, const uint8_t *tree_mask /*[B,N,N]*/,
+                   int B, int H, int N, int D, int Cmax, int dtype, float scale, void *out)
+{
+    const int BH = B * H;
+#pragma omp parallel
+    {
+        double *s = (double *)malloc(sizeof(double) * (size_t)(Cmax + N));
+        double *row = (double *)malloc(sizeof(double) * (size_t)D);
+#pragma omp for schedule(dynamic, 1)
+        for (int bh = 0; bh < BH; ++bh) {
+            const int b = bh / H;
+            const int ctx = clampi(ctx_len[b], 0, Cmax);
+            const int P = clampi(n_packed[b], 0, N);
+            for (int p = 0; p < N; ++p) {
+                const size_t ooff = ((size_t)bh * N + p) * (size_t)D;
+                if (p >= P) {
+                    for (int d = 0; d < D; ++d) store_elem(out, ooff + d, dtype, 0.0);
+                    continue;
+                }
+                attn_row(q, k_cache, v_cache, k_new, v_new,
+                         tree_mask + ((size_t)b * N + p) * N, ctx, P, N, D, Cmax, dtype,
+                         (double)scale, (size_t)bh, p, s, row);
+                for (int d = 0; d < D; ++d) store_elem(out, ooff + d, dtype, row[d]);
+            }
+        }
+        free(s);
+        free(row);
+    }
+}
+
+/* Selected rows only: rows[r] = (b, h, p) with p < n_packed[b]; out_f64 [n_rows, D]
+ * holds the unrounded double results (for spot checks on tensors too large to do whole). */
+void orc_tree_attn_rows(const void *q, const void *k_cache, const void *v_cache,
+                        const int32_t *ctx_len, const void *k_new, const void *v_new,
+                        const int32_t *n_packed, const uint8_t *tree_mask,
+                        int B, int H, int N, int D, int Cmax, int dtype, float scale,
+                        const int32_t *rows, int n_rows, double *out_f64)
+{
+    (void)B;
+#pragma omp parallel
+    {
+        double *s = (double *)malloc(sizeof(double) * (size_t)(Cmax + N));
+#pragma omp for schedule(dynamic, 1)
+        for (int r = 0; r < n_rows; ++r) {
+            const int b = rows[3 * r], h = rows[3 * r + 1], p = rows[3 * r + 2];
+            const int ctx = clampi(ctx_len[b], 0, Cmax);
+            const int P = clampi(n_packed[b], 0, N);
+            attn_row(q, k_cache, v_cache, k_new, v_new, tree_mask + ((size_t)b * N + p) * N,
+                     ctx, P, N, D, Cmax, dtype, (double)scale, (size_t)b * H + h, p, s,
+                     out_f64 + (size_t)r * D);
+        }
+        free(s);
+    }
+}
+
+/* ------------------------------------------------------------------------- */
+/* Greedy verification (Sec. 3.4, temperature 0): the LLM's prediction after a
+ * packed token is the arg max of that token's logit row (smallest index among
+ * equal maxima); rows beyond the packed count give -1.                        */
+/* ------------------------------------------------------------------------- */
+void orc_argmax(const float *logits /*[B,N,V]*/, const int32_t *n_packed, int B, int N, int V,
+                int32_t *argmax_out /*[B,N]*/)
+{
+    const int rows = B * N;
+#pragma omp parallel for schedule(static)
+    for (int r = 0; r < rows; ++r) {
+        const int b = r / N, p = r % N;
+        if (p >= n_packed[b]) { argmax_out[r] = -1; continue; }
+        const float *row = logits + (size_t)r * V;
+        int best = 0;
+        for (int v = 1; v < V; ++v)
+            if (row[v] > row[best]) best = v;
+        argmax_out[r] = best;
+    }
+}
+
+/* Token-match acceptance (Sec. 3.4, Fig. 2): candidate w's token j is accepted when
+ * all earlier tokens were and the LLM's prediction after token j-1 equals it.  Token 0
+ * is checked against root_token[b] (the LLM's already known next token) or, when
+ * root_token is NULL, taken as given.  The best candidate has the longest accepted
+ * prefix (smallest index among equals); next_token is the LLM's prediction after the
+ * last accepted token.                                                         */
+void orc_accept(const int32_t *beams, const int32_t *unpack_index, const int32_t *argmax_in,
+                const int32_t *root_token, int B, int W, int L,
+                int32_t *n_accept /*[B,W]*/, int32_t *best_beam, int32_t *best_len,
+                int32_t *next_token, int32_t *accepted_idx /*[B,L]*/)
+{
+    const int N = W * L;
+    for (int b = 0; b < B; ++b) {
+        const int32_t *beam = beams + (size_t)b * N;
+        const int32_t *ui = unpack_index + (size_t)b * N;
+        const int32_t *am = argmax_in + (size_t)b * N;
+        int bw = 0, bl = -1;
+        for (int w = 0; w < W; ++w) {
+            int len = 0;
+            for (int j = 0; j < L; ++j) {
+                int ok;
+                if (j == 0) ok = (root_token == NULL) || (beam[w * L] == root_token[b]);
+                else ok = (am[ui[w * L + j - 1]] == beam[w * L + j]);
+                if (!ok) break;
+                ++len;
+            }
+            n_accept[b * W + w] = len;
+            if (len > bl) { bl = len; bw = w; }
+        }
+        best_beam[b] = bw;
+        best_len[b] = bl;
+        for (int t = 0; t < L; ++t)
+            accepted_idx[b * L + t] = (t < bl) ? ui[bw * L + t] : -1;
+        next_token[b] = (bl > 0) ? am[ui[bw * L + bl - 1]] : root_token[b];
+    }
+}
