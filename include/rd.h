@@ -1,0 +1,153 @@
+/*
+ * rd.h — C ABI of the ReDrafter verification step on AMD MI355X (gfx950).
+ *
+ * One speculative-decoding step of ReDrafter (arXiv 2403.09919, Sec. 3.4) verifies the
+ * drafter's beam with the LLM.  This library implements the three parts of that step
+ * that are not the LLM's dense layers:
+ *
+ *   rd_dedup      dynamic tree attention construction (Sec. 3.3, App. A.1): remove the
+ *                 duplicated prefixes of W candidates of length L, giving a packed token
+ *                 set plus the tree mask, parents, position ids and the unpack index;
+ *   rd_tree_attn  the attention core of the LLM's forward pass over the packed tokens
+ *                 with that mask, against the KV cache (Sec. 3.3, 3.4);
+ *   rd_accept     greedy "token match" acceptance (Sec. 3.4, Fig. 2): arg max of the
+ *                 LLM's logits per packed token, longest accepted prefix per candidate,
+ *                 best candidate, next token.
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers to dense row-major arrays (last index
+ *     fastest).  The caller owns every buffer; the library never allocates, frees or
+ *     synchronises.  A call only enqueues kernels on `stream` (a hipStream_t passed as
+ *     void*; NULL = the default stream); outputs are valid once the stream reaches
+ *     that point.  Calls may be captured into a HIP graph.
+ *   - A batch is B independent sequences (App. A.1).  N = W*L is the padded packed
+ *     length; sequence b has n_packed[b] <= N packed tokens.
+ *   - Return value: RD_OK or a negative rd_status.  Nothing is thrown, printed or
+ *     aborted.  Argument errors that the host can see (NULL required pointer,
+ *     non-positive or unsupported sizes, unknown dtype, misaligned pointer, workspace
+ *     too small) are rejected before anything is launched.  Data preconditions that
+ *     live on the device (0 <= ctx_len[b] <= Cmax, n_packed[b] <= N, logits free of
+ *     NaN) are not checked; ctx_len and n_packed are clamped into range.
+ *   - Limits: 1 <= W <= 64, L >= 1, N = W*L <= 128, D in {64, 128}.
+ */
+#ifndef RD_H
+#define RD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { RD_F32 = 0, RD_BF16 = 1 } rd_dtype;
+
+typedef enum {
+    RD_OK = 0,
+    RD_ERR_INVALID_ARG = -1, /* NULL required pointer, size <= 0, bad alignment */
+    RD_ERR_UNSUPPORTED = -2, /* size or dtype outside the limits above */
+    RD_ERR_WORKSPACE = -3,   /* workspace NULL or smaller than rd_*_workspace() */
+    RD_ERR_HIP = -4          /* a kernel launch failed (hipGetLastError) */
+} rd_status;
+
+#define RD_MAX_W 64
+#define RD_MAX_N 128
+
+/* Static description of a status code; never NULL. */
+const char *rd_strerror(int code);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int rd_version(void);
+
+/*
+ * rd_dedup — dedup_prefix + pack_beam + tree structure (Sec. 3.3, App. A.1).
+ *
+ *   prefix_tree[b][i][j]  smallest candidate index k whose first j+1 tokens equal
+ *                         candidate i's (the App. A.1 definition).
+ *   A token (i,j) is kept iff prefix_tree[b][i][j] == i ("condense tokens where
+ *   prefix_tree[i][j] < i").  Kept tokens get packed slots 0..n_packed[b]-1 in
+ *   row-major (i, j) order.
+ *   packed_tokens[b][p]   token at slot p                                 (pad -1)
+ *   unpack_index[b][i][j] slot holding candidate i's j-th token
+ *   parent[b][p]          slot of the previous token on p's path, -1 at depth 0 (pad -1)
+ *   position_ids[b][p]    ctx_len[b] + depth of p; depth alone if ctx_len == NULL (pad -1)
+ *   tree_mask[b][p][q]    1 iff q == p or q is an ancestor of p (what p may attend
+ *                         to among the packed tokens); pad rows and columns 0
+ *   tree_mask_bits[b][p][w] bit (q & 63) of word (q >> 6) = tree_mask[b][p][q]
+ *
+ * beams: int32 [B,W,L], any token values.  Outputs: int32 [B,W,L] / [B,N] / [B];
+ * tree_mask uint8 [B,N,N]; tree_mask_bits uint64 [B,N,ceil(N/64)].  prefix_tree,
+ * tree_mask and tree_mask_bits may each be NULL (not written); the others are required.
+ */
+int rd_dedup(const int32_t *beams, const int32_t *ctx_len, int B, int W, int L,
+             int32_t *prefix_tree, int32_t *packed_tokens, int32_t *n_packed,
+             int32_t *unpack_index, int32_t *parent, int32_t *position_ids,
+             uint8_t *tree_mask, uint64_t *tree_mask_bits, void *stream);
+
+/*
+ * rd_tree_attn — tree-masked attention of the packed candidates (Sec. 3.3, 3.4).
+ *
+ * For every sequence b, head h and packed row p < n_packed[b]:
+ *   out[b,h,p,:] = softmax over { context keys c < ctx_len[b] } U { packed keys q with
+ *   tree_mask bit (p,q) set } of scale * <q[b,h,p,:], key>, applied to the values.
+ * Keys outside that set do not take part (they are excluded, not biased).  Rows
+ * p >= n_packed[b] of `out` are written as zero.  Cache entries at positions
+ * >= ctx_len[b] and packed rows >= n_packed[b] are never read.
+ *
+ *   q, k_new, v_new, out : [B,H,N,D]      k_cache, v_cache : [B,H,Cmax,D]
+ *   element type by `dt`: RD_F32 (float) or RD_BF16 (bfloat16 bit patterns); scores and
+ *   accumulation are fp32 in both; all tensor pointers 16-byte aligned.
+ *   ctx_len, n_packed : int32 [B];  tree_mask_bits : uint64 [B,N,ceil(N/64)] (rd_dedup's).
+ *   Cmax >= 0 (k_cache/v_cache may be NULL when Cmax == 0).
+ *
+ * workspace: device scratch of at least rd_tree_attn_workspace(...) bytes, 256-byte
+ * aligned.  It holds per-split partial results and completion counters.  The counters
+ * must be zero before the first call that uses a workspace (hipMemsetAsync it once);
+ * every call leaves them zero again, so a workspace can be reused by successive calls
+ * on one stream without clearing.  Concurrent calls need separate workspaces.
+ */
+size_t rd_tree_attn_workspace(int B, int H, int N, int D, int Cmax, rd_dtype dt);
+
+int rd_tree_attn(const void *q, const void *k_cache, const void *v_cache,
+                 const int32_t *ctx_len, const void *k_new, const void *v_new,
+                 const int32_t *n_packed, const uint64_t *tree_mask_bits,
+                 int B, int H, int N, int D, int Cmax, rd_dtype dt, float scale,
+                 void *out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * rd_accept — greedy verification (Sec. 3.4, Fig. 2; temperature 0).
+ *
+ *   argmax_out[b][p] = arg max_v logits[b][p][v] for p < n_packed[b] (smallest v among
+ *                      equal maxima), -1 for p >= n_packed[b].  Row p is the LLM's
+ *                      output at packed token p, i.e. its prediction of the token
+ *                      that follows p on p's path.
+ *   Candidate w's token j is accepted iff tokens 0..j-1 were and
+ *       j == 0: root_token == NULL (the first token is the LLM's guaranteed one), or
+ *               beams[b][w][0] == root_token[b];
+ *       j >= 1: argmax_out[b][unpack_index[b][w][j-1]] == beams[b][w][j].
+ *   n_accept[b][w]  length of candidate w's accepted prefix
+ *   best_len[b]     max over w;  best_beam[b] = smallest w reaching it
+ *   accepted_idx[b][t] = unpack_index[b][best_beam][t] for t < best_len (pad -1)
+ *   next_token[b]   argmax_out at the last accepted slot; root_token[b] if best_len == 0
+ *
+ * logits: float [B,N,V], free of NaN (-inf allowed).  beams, unpack_index: int32
+ * [B,W,L]; n_packed: int32 [B]; root_token: int32 [B] or NULL.  Outputs int32:
+ * argmax_out [B,N], n_accept [B,W], best_beam/best_len/next_token [B],
+ * accepted_idx [B,L].  logits must be 16-byte aligned.
+ *
+ * workspace: as for rd_tree_attn (at least rd_accept_workspace(...) bytes, 256-byte
+ * aligned, counters zero before first use, left zero by every call).
+ */
+size_t rd_accept_workspace(int B, int W, int L, int V);
+
+int rd_accept(const float *logits, const int32_t *beams, const int32_t *unpack_index,
+              const int32_t *n_packed, const int32_t *root_token,
+              int B, int W, int L, int V,
+              int32_t *argmax_out, int32_t *n_accept, int32_t *best_beam,
+              int32_t *best_len, int32_t *next_token, int32_t *accepted_idx,
+              void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RD_H */

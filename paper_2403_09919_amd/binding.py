@@ -1,0 +1,199 @@
+"""Thin ctypes binding of librd.so (the C ABI declared in include/rd.h).
+
+Argument marshalling only: torch tensors supply device memory and the current stream;
+every step of the verification path runs in the library's HIP kernels.  There is no CPU
+fallback: importing this module fails if the library has not been built
+(`python -m paper_2403_09919_amd.build`).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librd.so")
+
+RD_F32, RD_BF16 = 0, 1
+RD_OK = 0
+RD_MAX_W, RD_MAX_N = 64, 128
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError("librd.so is not built: run `python -m paper_2403_09919_amd.build` "
+                      "(hipcc, gfx950); there is no fallback path")
+
+_lib = ctypes.CDLL(LIB_PATH)
+
+_vp, _i, _sz, _f = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t, ctypes.c_float
+
+EXPORTS = {
+    "rd_strerror": (ctypes.c_char_p, [_i]),
+    "rd_version": (_i, []),
+    "rd_dedup": (_i, [_vp, _vp, _i, _i, _i] + [_vp] * 8 + [_vp]),
+    "rd_tree_attn_workspace": (_sz, [_i, _i, _i, _i, _i, _i]),
+    "rd_tree_attn": (_i, [_vp] * 8 + [_i, _i, _i, _i, _i, _i, _f, _vp, _vp, _sz, _vp]),
+    "rd_accept_workspace": (_sz, [_i, _i, _i, _i]),
+    "rd_accept": (_i, [_vp] * 5 + [_i, _i, _i, _i] + [_vp] * 6 + [_vp, _sz, _vp]),
+}
+for _name, (_res, _args) in EXPORTS.items():
+    _fn = getattr(_lib, _name)
+    _fn.restype = _res
+    _fn.argtypes = _args
+
+
+class RdError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__("%s: %s (%d)" % (where, rd_strerror(code), code))
+
+
+def rd_strerror(code: int) -> str:
+    return _lib.rd_strerror(int(code)).decode()
+
+
+def rd_version() -> int:
+    return int(_lib.rd_version())
+
+
+def raw():
+    """The ctypes library handle (for tests of the C ABI's argument checks)."""
+    return _lib
+
+
+def _ptr(t: Optional[torch.Tensor], dtype=None, shape=None, name="tensor"):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("%s must live in device memory" % name)
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError("%s must be %s, got %s" % (name, dtype, t.dtype))
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError("%s must have shape %s, got %s" % (name, tuple(shape), tuple(t.shape)))
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(code: int, where: str):
+    if code != RD_OK:
+        raise RdError(code, where)
+
+
+def new_workspace(nbytes: int, device) -> torch.Tensor:
+    """Zero-filled scratch buffer (the completion counters must start at zero)."""
+    return torch.zeros(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+# ------------------------------------------------------------------------------------------
+def rd_dedup(beams: torch.Tensor, ctx_len: Optional[torch.Tensor] = None, *,
+             want_prefix_tree: bool = True, want_mask: bool = True, out: Optional[dict] = None) -> dict:
+    """beams int32 [B,W,L] -> dict of device tensors (see include/rd.h, rd_dedup)."""
+    B, W, L = beams.shape
+    N = W * L
+    words = (N + 63) // 64
+    dev = beams.device
+    i32 = torch.int32
+    if out is None:
+        out = dict(
+            prefix_tree=torch.empty((B, W, L), dtype=i32, device=dev) if want_prefix_tree else None,
+            packed_tokens=torch.empty((B, N), dtype=i32, device=dev),
+            n_packed=torch.empty((B,), dtype=i32, device=dev),
+            unpack_index=torch.empty((B, W, L), dtype=i32, device=dev),
+            parent=torch.empty((B, N), dtype=i32, device=dev),
+            position_ids=torch.empty((B, N), dtype=i32, device=dev),
+            tree_mask=torch.empty((B, N, N), dtype=torch.uint8, device=dev) if want_mask else None,
+            tree_mask_bits=torch.empty((B, N, words), dtype=torch.int64, device=dev),
+        )
+    code = _lib.rd_dedup(
+        _ptr(beams, i32, (B, W, L), "beams"), _ptr(ctx_len, i32, (B,), "ctx_len"), B, W, L,
+        _ptr(out["prefix_tree"], i32, (B, W, L), "prefix_tree"),
+        _ptr(out["packed_tokens"], i32, (B, N), "packed_tokens"),
+        _ptr(out["n_packed"], i32, (B,), "n_packed"),
+        _ptr(out["unpack_index"], i32, (B, W, L), "unpack_index"),
+        _ptr(out["parent"], i32, (B, N), "parent"),
+        _ptr(out["position_ids"], i32, (B, N), "position_ids"),
+        _ptr(out["tree_mask"], torch.uint8, (B, N, N), "tree_mask"),
+        _ptr(out["tree_mask_bits"], torch.int64, (B, N, words), "tree_mask_bits"),
+        _stream())
+    _check(code, "rd_dedup")
+    return out
+
+
+def _dt_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return RD_F32
+    if t.dtype == torch.bfloat16:
+        return RD_BF16
+    raise ValueError("unsupported element type %s (float32 or bfloat16)" % t.dtype)
+
+
+def rd_tree_attn_workspace(B: int, H: int, N: int, D: int, Cmax: int, dt: int) -> int:
+    return int(_lib.rd_tree_attn_workspace(B, H, N, D, Cmax, dt))
+
+
+def rd_tree_attn(q, k_cache, v_cache, ctx_len, k_new, v_new, n_packed, tree_mask_bits, scale: float,
+                 out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """q/k_new/v_new [B,H,N,D], k_cache/v_cache [B,H,Cmax,D] -> out [B,H,N,D] (see include/rd.h)."""
+    B, H, N, D = q.shape
+    Cmax = k_cache.shape[2]
+    dt = _dt_code(q)
+    words = (N + 63) // 64
+    if out is None:
+        out = torch.empty_like(q)
+    if workspace is None:
+        workspace = new_workspace(rd_tree_attn_workspace(B, H, N, D, Cmax, dt), q.device)
+    code = _lib.rd_tree_attn(
+        _ptr(q, q.dtype, (B, H, N, D), "q"),
+        _ptr(k_cache, q.dtype, (B, H, Cmax, D), "k_cache") if Cmax > 0 else None,
+        _ptr(v_cache, q.dtype, (B, H, Cmax, D), "v_cache") if Cmax > 0 else None,
+        _ptr(ctx_len, torch.int32, (B,), "ctx_len"),
+        _ptr(k_new, q.dtype, (B, H, N, D), "k_new"), _ptr(v_new, q.dtype, (B, H, N, D), "v_new"),
+        _ptr(n_packed, torch.int32, (B,), "n_packed"),
+        _ptr(tree_mask_bits, torch.int64, (B, N, words), "tree_mask_bits"),
+        B, H, N, D, Cmax, dt, float(scale),
+        _ptr(out, q.dtype, (B, H, N, D), "out"),
+        _ptr(workspace, torch.uint8, None, "workspace"), workspace.numel(), _stream())
+    _check(code, "rd_tree_attn")
+    return out
+
+
+def rd_accept_workspace(B: int, W: int, L: int, V: int) -> int:
+    return int(_lib.rd_accept_workspace(B, W, L, V))
+
+
+def rd_accept(logits, beams, unpack_index, n_packed, root_token: Optional[torch.Tensor] = None,
+              out: Optional[dict] = None, workspace: Optional[torch.Tensor] = None) -> dict:
+    """logits float32 [B,N,V] -> dict(argmax, n_accept, best_beam, best_len, next_token, accepted_idx)."""
+    B, W, L = beams.shape
+    N = W * L
+    V = logits.shape[2]
+    dev = logits.device
+    i32 = torch.int32
+    if out is None:
+        out = dict(
+            argmax=torch.empty((B, N), dtype=i32, device=dev),
+            n_accept=torch.empty((B, W), dtype=i32, device=dev),
+            best_beam=torch.empty((B,), dtype=i32, device=dev),
+            best_len=torch.empty((B,), dtype=i32, device=dev),
+            next_token=torch.empty((B,), dtype=i32, device=dev),
+            accepted_idx=torch.empty((B, L), dtype=i32, device=dev),
+        )
+    if workspace is None:
+        workspace = new_workspace(rd_accept_workspace(B, W, L, V), dev)
+    code = _lib.rd_accept(
+        _ptr(logits, torch.float32, (B, N, V), "logits"), _ptr(beams, i32, (B, W, L), "beams"),
+        _ptr(unpack_index, i32, (B, W, L), "unpack_index"), _ptr(n_packed, i32, (B,), "n_packed"),
+        _ptr(root_token, i32, (B,), "root_token"), B, W, L, V,
+        _ptr(out["argmax"], i32, (B, N), "argmax"), _ptr(out["n_accept"], i32, (B, W), "n_accept"),
+        _ptr(out["best_beam"], i32, (B,), "best_beam"), _ptr(out["best_len"], i32, (B,), "best_len"),
+        _ptr(out["next_token"], i32, (B,), "next_token"),
+        _ptr(out["accepted_idx"], i32, (B, L), "accepted_idx"),
+        _ptr(workspace, torch.uint8, None, "workspace"), workspace.numel(), _stream())
+    _check(code, "rd_accept")
+    return out

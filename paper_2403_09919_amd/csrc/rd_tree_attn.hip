@@ -1,0 +1,50 @@
+// rd_tree_attn host entry: argument checks, split plan, dispatch to the bf16 (MFMA) or
+// fp32 kernel.  See rd_attn_common.h for the decomposition.
+#include "rd_attn_common.h"
+
+namespace rd {
+int tree_attn_bf16(const AttnArgs &a, int D, hipStream_t stream);
+int tree_attn_f32(const AttnArgs &a, int D, hipStream_t stream);
+}  // namespace rd
+
+static int attn_check_shape(int B, int H, int N, int D, int Cmax, rd_dtype dt)
+{
+    if (B <= 0 || H <= 0 || N <= 0 || D <= 0 || Cmax < 0) return RD_ERR_INVALID_ARG;
+    if (dt != RD_F32 && dt != RD_BF16) return RD_ERR_UNSUPPORTED;
+    if (N > RD_MAX_N) return RD_ERR_UNSUPPORTED;
+    if (D != 64 && D != 128) return RD_ERR_UNSUPPORTED;
+    if ((long long)B * H > (1ll << 24)) return RD_ERR_UNSUPPORTED;
+    return RD_OK;
+}
+
+extern "C" size_t rd_tree_attn_workspace(int B, int H, int N, int D, int Cmax, rd_dtype dt)
+{
+    if (attn_check_shape(B, H, N, D, Cmax, dt) != RD_OK) return 0;
+    return rd::attn_plan(B, H, N, D, Cmax).total_bytes;
+}
+
+extern "C" int rd_tree_attn(const void *q, const void *k_cache, const void *v_cache,
+                            const int32_t *ctx_len, const void *k_new, const void *v_new,
+                            const int32_t *n_packed, const uint64_t *tree_mask_bits,
+                            int B, int H, int N, int D, int Cmax, rd_dtype dt, float scale,
+                            void *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    const int st = attn_check_shape(B, H, N, D, Cmax, dt);
+    if (st != RD_OK) return st;
+    if (!q || !k_new || !v_new || !ctx_len || !n_packed || !tree_mask_bits || !out) return RD_ERR_INVALID_ARG;
+    if (Cmax > 0 && (!k_cache || !v_cache)) return RD_ERR_INVALID_ARG;
+    if (!rd_aligned(q, 16) || !rd_aligned(k_cache, 16) || !rd_aligned(v_cache, 16) || !rd_aligned(k_new, 16) ||
+        !rd_aligned(v_new, 16) || !rd_aligned(out, 16) || !rd_aligned(tree_mask_bits, 8))
+        return RD_ERR_INVALID_ARG;
+    const rd::AttnPlan plan = rd::attn_plan(B, H, N, D, Cmax);
+    if (!workspace || !rd_aligned(workspace, 256) || workspace_bytes < plan.total_bytes) return RD_ERR_WORKSPACE;
+
+    rd::AttnArgs a;
+    a.q = q; a.k_cache = k_cache; a.v_cache = v_cache; a.k_new = k_new; a.v_new = v_new;
+    a.ctx_len = ctx_len; a.n_packed = n_packed; a.mask_bits = tree_mask_bits; a.out = out;
+    a.counters = static_cast<uint32_t *>(workspace);
+    a.partials = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + plan.counters_bytes);
+    a.B = B; a.H = H; a.N = N; a.Cmax = Cmax; a.S = plan.S; a.words = (N + 63) / 64; a.rows_pad = plan.rows_pad;
+    a.scale_log2e = scale * 1.44269504088896340736f;
+    return dt == RD_BF16 ? rd::tree_attn_bf16(a, D, (hipStream_t)stream) : rd::tree_attn_f32(a, D, (hipStream_t)stream);
+}

@@ -1,0 +1,123 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol that
+include/rd.h declares, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2403_09919_amd", "librd.so")
+HDR = os.path.join(ROOT, "include", "rd.h")
+
+OK, INVALID, UNSUPPORTED, WORKSPACE = 0, -1, -2, -3
+FAKE = 0x10000   # never dereferenced on the host: all these calls must fail before any launch
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        pytest.fail("librd.so missing: run `python -m paper_2403_09919_amd.build`")
+    from paper_2403_09919_amd import binding
+    return binding.raw()
+
+
+def _declared_symbols():
+    src = open(HDR).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(rd_[a-z_]+)\s*\(", src)))
+
+
+def test_header_symbols_exported(lib):
+    names = _declared_symbols()
+    assert names == sorted(["rd_strerror", "rd_version", "rd_dedup", "rd_tree_attn_workspace",
+                            "rd_tree_attn", "rd_accept_workspace", "rd_accept"])
+    raw = ctypes.CDLL(LIB)
+    for n in names:
+        assert hasattr(raw, n), n
+    from paper_2403_09919_amd import binding
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_version_and_strerror(lib):
+    assert lib.rd_version() >= 100
+    seen = set()
+    for code in (0, -1, -2, -3, -4, -99):
+        s = lib.rd_strerror(code)
+        assert s and len(s) > 1
+        seen.add(s)
+    assert len(seen) == 6
+
+
+def _dedup(lib, B, W, L, beams=FAKE, req=FAKE, mask=FAKE, bits=FAKE):
+    return lib.rd_dedup(beams, None, B, W, L, FAKE, req, req, req, req, req, mask, bits, None)
+
+
+def test_dedup_argument_errors(lib):
+    assert _dedup(lib, 0, 4, 4) == INVALID
+    assert _dedup(lib, 1, 0, 4) == INVALID
+    assert _dedup(lib, 1, 4, -1) == INVALID
+    assert _dedup(lib, 1, 65, 1) == UNSUPPORTED
+    assert _dedup(lib, 1, 16, 9) == UNSUPPORTED          # N = 144 > 128
+    assert _dedup(lib, 1, 4, 4, beams=None) == INVALID
+    assert _dedup(lib, 1, 4, 4, req=None) == INVALID
+    assert _dedup(lib, 1, 4, 4, bits=FAKE + 4) == INVALID   # uint64 rows need 8-byte alignment
+
+
+def _attn(lib, B=1, H=2, N=16, D=64, Cmax=32, dt=0, q=FAKE, kc=FAKE, ws=FAKE, ws_bytes=None, out=FAKE):
+    need = lib.rd_tree_attn_workspace(B, H, N, D, Cmax, dt)
+    if ws_bytes is None:
+        ws_bytes = need
+    return lib.rd_tree_attn(q, kc, kc, FAKE, FAKE, FAKE, FAKE, FAKE, B, H, N, D, Cmax, dt, 0.125,
+                            out, ws, ws_bytes, None)
+
+
+def test_tree_attn_argument_errors(lib):
+    assert lib.rd_tree_attn_workspace(1, 2, 16, 64, 32, 0) > 0
+    assert lib.rd_tree_attn_workspace(1, 2, 16, 96, 32, 0) == 0
+    assert _attn(lib, B=0) == INVALID
+    assert _attn(lib, Cmax=-1) == INVALID
+    assert _attn(lib, D=96) == UNSUPPORTED
+    assert _attn(lib, N=129) == UNSUPPORTED
+    assert _attn(lib, dt=7) == UNSUPPORTED
+    assert _attn(lib, q=None) == INVALID
+    assert _attn(lib, kc=None) == INVALID
+    assert _attn(lib, q=FAKE + 8) == INVALID              # 16-byte alignment
+    assert _attn(lib, out=None) == INVALID
+    assert _attn(lib, ws=None) == WORKSPACE
+    assert _attn(lib, ws=FAKE + 16) == WORKSPACE          # 256-byte alignment
+    assert _attn(lib, ws_bytes=16) == WORKSPACE
+
+
+def test_workspace_sizes_grow_with_problem(lib):
+    a = lib.rd_tree_attn_workspace(1, 32, 40, 128, 1024, 1)
+    b = lib.rd_tree_attn_workspace(8, 32, 40, 128, 2048, 1)
+    assert 0 < a < b
+    assert lib.rd_accept_workspace(1, 8, 5, 32000) < lib.rd_accept_workspace(16, 16, 5, 32000)
+    assert lib.rd_accept_workspace(1, 65, 1, 10) == 0
+
+
+def _accept(lib, B=1, W=4, L=4, V=100, logits=FAKE, req=FAKE, ws=FAKE, ws_bytes=None):
+    need = lib.rd_accept_workspace(B, W, L, V)
+    if ws_bytes is None:
+        ws_bytes = need
+    return lib.rd_accept(logits, FAKE, FAKE, FAKE, None, B, W, L, V, req, req, req, req, req, req,
+                         ws, ws_bytes, None)
+
+
+def test_accept_argument_errors(lib):
+    assert _accept(lib, B=0) == INVALID
+    assert _accept(lib, V=0) == INVALID
+    assert _accept(lib, W=65, L=1) == UNSUPPORTED
+    assert _accept(lib, logits=None) == INVALID
+    assert _accept(lib, logits=FAKE + 4) == INVALID
+    assert _accept(lib, req=None) == INVALID
+    assert _accept(lib, ws=None) == WORKSPACE
+    assert _accept(lib, ws_bytes=8) == WORKSPACE
+
+
+def test_binding_rejects_host_tensors():
+    import torch
+    from paper_2403_09919_amd import binding
+    with pytest.raises(ValueError):
+        binding.rd_dedup(torch.zeros((1, 2, 2), dtype=torch.int32))

@@ -1,0 +1,176 @@
+"""GPU parity, tree attention: rd_tree_attn against the CPU oracle.
+
+Tolerances (stated by the benchmark spec, written here): fp32 -> max|gpu-ref| <= 1e-5 * max|ref| over
+the tensor; bf16 -> max|gpu-ref| <= 2e-2."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import announce, dev, host
+from paper_2403_09919_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+F32_REL = 1e-5
+BF16_ABS = 2e-2
+
+
+@pytest.fixture(scope="module")
+def rd():
+    assert torch.cuda.is_available(), "GPU tests need a device"
+    from paper_2403_09919_amd import binding
+    return binding
+
+
+def gpu_attn(rd, t, d, dtype, scale, workspace=None):
+    out = rd.rd_tree_attn(dev(t["q"]), dev(t["k_cache"]), dev(t["v_cache"]), dev(t["ctx_len"]),
+                          dev(t["k_new"]), dev(t["v_new"]), dev(d["n_packed"]), dev(d["tree_mask_bits"]),
+                          scale, workspace=workspace)
+    torch.cuda.synchronize()
+    return host(out)
+
+
+def compare(got, ref, dtype, what=""):
+    g, r = synth.to_f64(got, dtype), synth.to_f64(ref, dtype)
+    assert np.isfinite(g).all(), "non-finite output " + what
+    err = np.abs(g - r).max()
+    if dtype == "f32":
+        assert err <= F32_REL * max(np.abs(r).max(), 1e-30), (what, err, np.abs(r).max())
+    else:
+        assert err <= BF16_ABS, (what, err)
+    return err
+
+
+def make_case(B, H, D, W, L, ctx, dtype, seed, V=6, share="uniform", poison=True):
+    ctx = np.asarray(ctx, np.int32)
+    Cmax = int(max(ctx.max(), 0))
+    t = dict(ctx_len=ctx, beams=synth.make_beams(B, W, L, V, seed, share))
+    t["q"], t["k_new"], t["v_new"] = synth.make_qkv_new(B, H, W * L, D, dtype, seed)
+    t["k_cache"], t["v_cache"] = synth.make_kv_cache(B, H, Cmax, D, dtype, seed, ctx, poison)
+    return t
+
+
+def full_check(rd, t, dtype, scale=None, what=""):
+    B, H, N, D = t["q"].shape
+    scale = float(1.0 / np.sqrt(D)) if scale is None else scale
+    d = oracle.dedup(t["beams"], t["ctx_len"])
+    ref = oracle.tree_attn(t["q"], t["k_cache"], t["v_cache"], t["ctx_len"], t["k_new"], t["v_new"],
+                           d["n_packed"], d["tree_mask"], dtype, scale)
+    got = gpu_attn(rd, t, d, dtype, scale)
+    for b in range(B):                                   # rows beyond the packed count are exactly zero
+        assert (synth.to_f64(got, dtype)[b, :, int(d["n_packed"][b]):] == 0).all()
+    return compare(got, ref, dtype, what)
+
+
+def test_config1_tiny_fp32(rd):
+    cfg = synth.CONFIGS[1]
+    announce("attn config 1 (fp32)")
+    t = synth.make_attn_inputs(cfg)
+    full_check(rd, t, "f32", what="cfg1")
+
+
+def test_config2_vicuna7b_full(rd):
+    cfg = synth.CONFIGS[2]
+    announce("attn config 2 (bf16, whole tensor)")
+    t = synth.make_attn_inputs(cfg)
+    err = full_check(rd, t, "bf16", what="cfg2")
+    print("cfg2 max abs err", err)
+
+
+@pytest.mark.parametrize("idx", [3, 4, 5])
+def test_full_size_configs_sampled(rd, idx):
+    """Full-size tensors in the launch configuration the benchmark uses; the oracle
+    computes a sample of output rows one by one (every sequence, spread of heads/rows)."""
+    cfg = synth.CONFIGS[idx]
+    announce("attn config %d (bf16, full size, sampled rows)" % idx)
+    t = synth.make_attn_inputs(cfg)
+    d = oracle.dedup(t["beams"], t["ctx_len"])
+    scale = float(1.0 / np.sqrt(cfg.D))
+    got = synth.to_f64(gpu_attn(rd, t, d, cfg.dtype, scale), cfg.dtype)
+    assert np.isfinite(got).all()
+    rng = np.random.default_rng(idx)
+    rows = []
+    for b in range(cfg.B):
+        P = int(d["n_packed"][b])
+        assert (got[b, :, P:] == 0).all()
+        for h in rng.choice(cfg.H, size=3, replace=False):
+            for p in sorted(set([0, P - 1] + rng.integers(0, P, size=3).tolist())):
+                rows.append((b, int(h), int(p)))
+    ref = oracle.tree_attn_rows(t["q"], t["k_cache"], t["v_cache"], t["ctx_len"], t["k_new"], t["v_new"],
+                                d["n_packed"], d["tree_mask"], cfg.dtype, scale, rows)
+    err = max(np.abs(got[b, h, p] - ref[n]).max() for n, (b, h, p) in enumerate(rows))
+    print("cfg%d sampled max abs err %.3e over %d rows" % (idx, err, len(rows)))
+    assert err <= BF16_ABS + 2.0 ** -9     # the sampled reference is unrounded: allow half a bf16 ulp at |x|<1
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("W,L", [(1, 1), (1, 5), (3, 5), (4, 4), (7, 5), (8, 8), (13, 6), (16, 6), (16, 7), (64, 2), (1, 128)])
+def test_shapes(rd, dtype, D, W, L):
+    """Every packed-row tile count (N = 1 .. 128), both head sizes, ragged contexts that end
+    inside a tile, inside a block, at zero, and beyond several blocks."""
+    announce("attn shapes dtype=%s D=%d W=%d L=%d" % (dtype, D, W, L))
+    ctx = [0, 1, 31, 129, 300, 517]
+    t = make_case(len(ctx), 2, D, W, L, ctx, dtype, seed=W * 131 + L)
+    full_check(rd, t, dtype, what="shapes")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_degenerate_beams_and_scales(rd, dtype):
+    announce("attn degenerate beams dtype=%s" % dtype)
+    B, H, D, W, L = 2, 3, 128, 8, 5
+    t = make_case(B, H, D, W, L, [200, 77], dtype, seed=5)
+    t["beams"][:] = np.array([4, 3, 2, 1, 0], np.int32)           # all identical -> P = L
+    full_check(rd, t, dtype, what="identical")
+    t["beams"] = np.arange(B * W * L, dtype=np.int32).reshape(B, W, L)   # all distinct -> P = W*L
+    full_check(rd, t, dtype, what="distinct")
+    full_check(rd, t, dtype, scale=0.0, what="scale0")            # uniform average of visible values
+    full_check(rd, t, dtype, scale=1.0, what="scale1")            # peaked softmax
+
+
+def test_many_splits_long_context(rd):
+    announce("attn long ragged context, many splits")
+    t = make_case(2, 4, 128, 8, 5, [5000, 2311], "bf16", seed=21, V=3)
+    full_check(rd, t, "bf16", what="long")
+
+
+def test_workspace_reuse_and_determinism(rd):
+    announce("attn workspace reuse, run-twice determinism")
+    cfg = synth.CONFIGS[2]
+    t = make_case(2, 8, 128, 8, 5, [700, 1024], "bf16", seed=3)
+    d = oracle.dedup(t["beams"], t["ctx_len"])
+    ws = rd.new_workspace(rd.rd_tree_attn_workspace(2, 8, 40, 128, 1024, rd.RD_BF16), "cuda")
+    a = gpu_attn(rd, t, d, "bf16", 0.1, ws)
+    b = gpu_attn(rd, t, d, "bf16", 0.1, ws)
+    assert np.array_equal(a, b)
+    nctr = 2 * 8
+    assert int(ws[: 4 * nctr].sum()) == 0
+    ref = oracle.tree_attn(t["q"], t["k_cache"], t["v_cache"], t["ctx_len"], t["k_new"], t["v_new"],
+                           d["n_packed"], d["tree_mask"], "bf16", 0.1)
+    compare(a, ref, "bf16")
+
+
+def test_whole_path_chained_on_device(rd):
+    """rd_dedup -> rd_tree_attn -> rd_accept with device-resident intermediates equals the oracle chain."""
+    cfg = synth.CONFIGS[2]
+    announce("whole path, config 2")
+    t = synth.make_attn_inputs(cfg)
+    scale = float(1.0 / np.sqrt(cfg.D))
+    dref = oracle.dedup(t["beams"], t["ctx_len"])
+    logits = synth.make_logits(cfg.B, cfg.N, cfg.V, cfg.seed, dref["packed_tokens"], dref["parent"],
+                               dref["n_packed"], cfg.p_plant)
+    ref = oracle.verify_step(t["beams"], t["ctx_len"], t["q"], t["k_cache"], t["v_cache"], t["k_new"],
+                             t["v_new"], logits, cfg.dtype, scale)
+    beams_d, ctx_d = dev(t["beams"]), dev(t["ctx_len"])
+    dd = rd.rd_dedup(beams_d, ctx_d)
+    out = rd.rd_tree_attn(dev(t["q"]), dev(t["k_cache"]), dev(t["v_cache"]), ctx_d, dev(t["k_new"]),
+                          dev(t["v_new"]), dd["n_packed"], dd["tree_mask_bits"], scale)
+    acc = rd.rd_accept(dev(logits), beams_d, dd["unpack_index"], dd["n_packed"])
+    torch.cuda.synchronize()
+    for k in ("packed_tokens", "n_packed", "unpack_index", "parent", "position_ids", "tree_mask"):
+        assert np.array_equal(host(dd[k]), ref[k]), k
+    compare(host(out), ref["attn_out"], cfg.dtype, "chain")
+    assert np.array_equal(host(acc["argmax"]), ref["argmax"])
+    for k in ("n_accept", "best_beam", "best_len", "next_token", "accepted_idx"):
+        assert np.array_equal(host(acc[k]), ref[k]), k
