@@ -1,0 +1,256 @@
+#!/usr/bin/env python3
+"""Benchmark of the ReDrafter verification step on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic batch:
+rd_dedup -> rd_tree_attn (one layer's attention core) -> rd_accept, back to back on one
+stream with all inputs resident in HBM.  The default workload is the Vicuna-7B-shaped
+configuration (B=1, context 1024, H=32, D=128, bf16 KV, W=8, L=5, vocab 32000).
+
+To keep the infinity cache from serving the KV stream, the step rotates over R
+independent copies of the inputs whose K/V total exceeds 512 MiB.  The R steps are
+captured once into a HIP graph (the library only enqueues kernels, so a caller can do
+that) and the graph is replayed, which removes the Python/ctypes launch cost from the
+timed region; --no-graph times eager launches instead.
+
+Prints one JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=6400)
+    ap.add_argument("--warmup", type=int, default=640)
+    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2: Vicuna-7B-shaped layer)")
+    ap.add_argument("--copies", type=int, default=0, help="rotating input copies (0 = enough for > 512 MiB of K/V)")
+    ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of graph replays")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time budget of the oracle baseline")
+    return ap.parse_args()
+
+
+def build_copies(cfg, R, rd, synth, torch):
+    """R independent synthetic batches on the device, plus their dedup results (from the HIP path)."""
+    dev = torch.device("cuda:0")
+    tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(cfg.seed)
+    copies = []
+    for r in range(R):
+        seed = cfg.seed + 7919 * r
+        beams = torch.from_numpy(synth.make_beams(cfg.B, cfg.W, cfg.L, cfg.V, seed, cfg.share)).to(dev)
+        ctx_np = synth.make_ctx_len(cfg.B, cfg.ctx_lo, cfg.ctx_hi, seed)
+        ctx = torch.from_numpy(ctx_np).to(dev)
+        c = dict(beams=beams, ctx_len=ctx, ctx_np=ctx_np)
+        for name, n in (("q", cfg.N), ("k_new", cfg.N), ("v_new", cfg.N), ("k_cache", cfg.Cmax), ("v_cache", cfg.Cmax)):
+            c[name] = torch.randn((cfg.B, cfg.H, n, cfg.D), generator=gen, device=dev, dtype=torch.float32).to(tdt)
+        c["dedup"] = rd.rd_dedup(beams, ctx)
+        torch.cuda.synchronize()
+        d = c["dedup"]
+        c["n_packed_np"] = d["n_packed"].cpu().numpy()
+        logits = synth.make_logits(cfg.B, cfg.N, cfg.V, seed, d["packed_tokens"].cpu().numpy(),
+                                   d["parent"].cpu().numpy(), c["n_packed_np"], cfg.p_plant)
+        c["logits"] = torch.from_numpy(logits).to(dev)
+        c["attn_out"] = torch.empty_like(c["q"])
+        c["accept"] = None
+        copies.append(c)
+    return copies
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the verification step shards over sequences and "
+              "heads without communication; no multi-GPU path exists). Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2403_09919_amd import binding as rd
+    from paper_2403_09919_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.config]
+    esz = 4 if cfg.dtype == "f32" else 2
+    kv_bytes = 2 * cfg.B * cfg.H * cfg.Cmax * cfg.D * esz
+    R = args.copies if args.copies > 0 else max(2, -(-(512 << 20) // kv_bytes) + 1)
+    scale = float(1.0 / np.sqrt(cfg.D))
+    dt_code = rd.RD_F32 if cfg.dtype == "f32" else rd.RD_BF16
+
+    copies = build_copies(cfg, R, rd, synth, torch)
+    ws_attn = rd.new_workspace(rd.rd_tree_attn_workspace(cfg.B, cfg.H, cfg.N, cfg.D, cfg.Cmax, dt_code), "cuda")
+    ws_acc = rd.new_workspace(rd.rd_accept_workspace(cfg.B, cfg.W, cfg.L, cfg.V), "cuda")
+
+    def attn(c):
+        d = c["dedup"]
+        rd.rd_tree_attn(c["q"], c["k_cache"], c["v_cache"], c["ctx_len"], c["k_new"], c["v_new"],
+                        d["n_packed"], d["tree_mask_bits"], scale, out=c["attn_out"], workspace=ws_attn)
+
+    def step(c):
+        d = rd.rd_dedup(c["beams"], c["ctx_len"], out=c["dedup"])
+        attn(c)
+        c["accept"] = rd.rd_accept(c["logits"], c["beams"], d["unpack_index"], d["n_packed"],
+                                   out=c["accept"], workspace=ws_acc)
+
+    # algorithmic bytes of one rd_tree_attn launch: every visible K/V element once, packed q/k/v/out once, mask bits
+    words = (cfg.N + 63) // 64
+    attn_bytes = []
+    packed_total = []
+    for c in copies:
+        P = c["n_packed_np"].astype(np.int64)
+        C = c["ctx_np"].astype(np.int64)
+        attn_bytes.append(esz * cfg.H * cfg.D * int((2 * C + 4 * P).sum()) + int(P.sum()) * words * 8)
+        packed_total.append(int(P.sum()))
+    attn_bytes_mean = float(np.mean(attn_bytes))
+    packed_mean = float(np.mean(packed_total))
+
+    for c in copies:                      # eager pass: allocates outputs, sets kernel attributes
+        step(c)
+    torch.cuda.synchronize()
+
+    use_graph = not args.no_graph
+    stream = torch.cuda.Stream()          # default priority; capture needs a non-default stream
+    if use_graph:
+        with torch.cuda.stream(stream):
+            g_step = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g_step, stream=stream):
+                for c in copies:
+                    step(c)
+            g_attn = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g_attn, stream=stream):
+                for c in copies:
+                    attn(c)
+        torch.cuda.synchronize()
+
+    def run_steps(n):
+        """n steps on `stream` (graph replays of R steps each, remainder eagerly rotated)."""
+        with torch.cuda.stream(stream):
+            if use_graph:
+                for _ in range(n // R):
+                    g_step.replay()
+                for i in range(n % R):
+                    step(copies[i])
+            else:
+                for i in range(n):
+                    step(copies[i % R])
+
+    def run_attn(n):
+        with torch.cuda.stream(stream):
+            if use_graph:
+                for _ in range(n // R):
+                    g_attn.replay()
+                for i in range(n % R):
+                    attn(copies[i])
+            else:
+                for i in range(n):
+                    attn(copies[i % R])
+
+    # ---- timed region 1: whole steps -------------------------------------------------------------
+    run_steps(args.warmup)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    with torch.cuda.stream(stream):
+        e0.record(stream)
+    run_steps(args.steps)
+    with torch.cuda.stream(stream):
+        e1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    step_ms = e0.elapsed_time(e1) / args.steps
+    ms_per_step = max(step_ms, 0.0)
+    steps_per_s = 1e3 / ms_per_step
+
+    # ---- timed region 2: the dominant kernel alone (rd_tree_attn), events on its own stream --------
+    run_attn(args.warmup)
+    torch.cuda.synchronize()
+    a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    with torch.cuda.stream(stream):
+        a0.record(stream)
+    run_attn(args.steps)
+    with torch.cuda.stream(stream):
+        a1.record(stream)
+    torch.cuda.synchronize()
+    attn_us = a0.elapsed_time(a1) * 1e3 / args.steps
+    achieved = attn_bytes_mean / (attn_us * 1e-6) / 1e9
+
+    result = {
+        "metric": "verify_steps_per_sec",
+        "value": round(steps_per_s, 2),
+        "unit": "steps/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 6),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": cfg.dtype,
+        "data": "synthetic",
+        "config": {
+            "workload": "%s: B=%d ctx=%s H=%d D=%d %s KV, W=%d L=%d V=%d" % (
+                cfg.name, cfg.B, cfg.ctx_lo if cfg.ctx_lo == cfg.ctx_hi else "U{%d..%d}" % (cfg.ctx_lo, cfg.ctx_hi),
+                cfg.H, cfg.D, cfg.dtype, cfg.W, cfg.L, cfg.V),
+            "rotating_copies": R,
+            "launch": "hip_graph_replay" if use_graph else "eager",
+            "step": "rd_dedup + rd_tree_attn + rd_accept",
+        },
+        "packed_tokens_per_sec": round(packed_mean * steps_per_s, 1),
+        "packed_tokens_per_step": round(packed_mean, 2),
+        "wall_ms_timed_region": round(wall_ms, 3),
+        "roofline": {
+            "kernel": "rd_tree_attn",
+            "bound": "hbm",
+            "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "traffic": None,
+            "algorithmic_bytes_per_launch": round(attn_bytes_mean, 1),
+            "us_per_launch": round(attn_us, 3),
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, synth, args.cpu_seconds)
+    print(json.dumps(result), flush=True)
+
+
+def cpu_baseline(cfg, synth, budget_s):
+    """The CPU oracle as it stands, timed on this host on whole steps of the same workload."""
+    import oracle                               # baseline leg only; the timed GPU path never touches it
+    cpu_cfg = cfg
+    t = synth.make_attn_inputs(cpu_cfg, poison=False)
+    scale = float(1.0 / np.sqrt(cpu_cfg.D))
+    d = oracle.dedup(t["beams"], t["ctx_len"])
+    logits = synth.make_logits(cpu_cfg.B, cpu_cfg.N, cpu_cfg.V, cpu_cfg.seed, d["packed_tokens"], d["parent"],
+                               d["n_packed"], cpu_cfg.p_plant)
+    reps, t0 = 0, time.perf_counter()
+    while True:
+        oracle.verify_step(t["beams"], t["ctx_len"], t["q"], t["k_cache"], t["v_cache"], t["k_new"], t["v_new"],
+                           logits, cpu_cfg.dtype, scale)
+        reps += 1
+        el = time.perf_counter() - t0
+        if el >= budget_s or (reps >= 3 and el >= 0.5 * budget_s):
+            break
+    return {"value": round(reps / el, 4), "unit": "steps/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "%d whole steps of the same workload (%s), %.1f s" % (reps, cpu_cfg.name, el)}
+
+
+if __name__ == "__main__":
+    main()

@@ -33,7 +33,7 @@ AccPlan acc_plan(int B, int N, int V)
     p.chunk_len = len;
     p.chunks = (V + len - 1) / len;
     p.counters_bytes = ((size_t)B * sizeof(uint32_t) + 255) / 256 * 256;
-    p.total_bytes = p.counters_bytes + (size_t)B * N * p.chunks * sizeof(float2);
+    p.total_bytes = p.counters_bytes + (size_t)B * N * p.chunks * sizeof(unsigned long long);
     return p;
 }
 
@@ -49,7 +49,7 @@ __global__ __launch_bounds__(kAccThreads) void rd_accept_kernel(
     const int32_t *__restrict__ root_token, int W, int L, int V, int chunks, int chunk_len,
     int32_t *__restrict__ argmax_out, int32_t *__restrict__ n_accept, int32_t *__restrict__ best_beam,
     int32_t *__restrict__ best_len, int32_t *__restrict__ next_token, int32_t *__restrict__ accepted_idx,
-    uint32_t *counters, float2 *partial)
+    uint32_t *counters, unsigned long long *partial)
 {
     __shared__ float s_val[kAccThreads / 64];
     __shared__ int s_idx[kAccThreads / 64];
@@ -94,26 +94,32 @@ __global__ __launch_bounds__(kAccThreads) void rd_accept_kernel(
     if (tid == 0) {
         for (int w = 1; w < kAccThreads / 64; ++w)
             if (better(s_val[w], s_idx[w], bv, bi)) { bv = s_val[w]; bi = s_idx[w]; }
-        partial[((size_t)b * N + p) * chunks + chunk] = make_float2(bv, __int_as_float(bi));
-        __threadfence();                                  // release the partial
-        const uint32_t prev = atomicAdd(counters + b, 1u);
+        // The chunk result crosses workgroups (possibly XCDs, each with its own L2): store and
+        // later load it with device-scope accesses and wait for the store before the counter
+        // moves; a device-wide fence per workgroup would flush whole L2s and dominate the kernel.
+        const unsigned long long packed = (unsigned long long)__float_as_uint(bv) | ((unsigned long long)(uint32_t)bi << 32);
+        __hip_atomic_store(partial + ((size_t)b * N + p) * chunks + chunk, packed, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        const uint32_t prev = __hip_atomic_fetch_add(counters + b, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         s_last = (prev == (uint32_t)(P * chunks) - 1u) ? 1u : 0u;
     }
     __syncthreads();
     if (!s_last) return;
-    __threadfence();                                      // acquire the other workgroups' partials
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
 
     // ---- phase 2: row arg max, then token matching ---------------------------------------------------
     for (int r = tid; r < N; r += kAccThreads) {
         int am = -1;
         if (r < P) {
-            const float2 *pr = partial + ((size_t)b * N + r) * chunks;
+            const unsigned long long *pr = partial + ((size_t)b * N + r) * chunks;
             float rv = -INFINITY;
             int ri = 0x7fffffff;
             for (int c = 0; c < chunks; ++c) {
-                const float2 x = pr[c];
-                const int xi = __float_as_int(x.y);
-                if (better(x.x, xi, rv, ri)) { rv = x.x; ri = xi; }
+                const unsigned long long x = __hip_atomic_load(pr + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const float xv = __uint_as_float((uint32_t)x);
+                const int xi = (int)(uint32_t)(x >> 32);
+                if (better(xv, xi, rv, ri)) { rv = xv; ri = xi; }
             }
             am = ri;
         }
@@ -182,7 +188,7 @@ extern "C" int rd_accept(const float *logits, const int32_t *beams, const int32_
     const AccPlan plan = acc_plan(B, N, V);
     if (!workspace || !rd_aligned(workspace, 256) || workspace_bytes < plan.total_bytes) return RD_ERR_WORKSPACE;
     uint32_t *counters = static_cast<uint32_t *>(workspace);
-    float2 *partial = reinterpret_cast<float2 *>(static_cast<unsigned char *>(workspace) + plan.counters_bytes);
+    unsigned long long *partial = reinterpret_cast<unsigned long long *>(static_cast<unsigned char *>(workspace) + plan.counters_bytes);
     hipLaunchKernelGGL(rd_accept_kernel, dim3(plan.chunks, N, B), dim3(kAccThreads), 0, (hipStream_t)stream,
                        logits, beams, unpack_index, n_packed, root_token, W, L, V, plan.chunks, plan.chunk_len,
                        argmax_out, n_accept, best_beam, best_len, next_token, accepted_idx, counters, partial);

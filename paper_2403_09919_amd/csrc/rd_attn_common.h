@@ -19,6 +19,7 @@ constexpr int kAttnThreads = 256;
 constexpr int kBlockKeys = 128;   // keys handled per workgroup iteration
 
 struct AttnPlan {
+    int waves;         // waves per workgroup of the bf16 kernel (4 or 8); a block is 32*waves keys
     int S;             // context splits per (sequence, head); partials per head = S + 1
     int rows_pad;      // packed rows padded to a multiple of 16
     size_t counters_bytes;
@@ -32,15 +33,25 @@ static inline int env_int(const char *name, int dflt)
     return (v && *v) ? atoi(v) : dflt;
 }
 
-// How many context splits: enough workgroups to cover the 256 compute units a few times
-// over, never more than one split per 128-key block.
-static inline AttnPlan attn_plan(int B, int H, int N, int D, int Cmax)
+// How many context splits per (sequence, head).  Streaming needs enough workgroups in flight
+// (about 128 already reach the HBM rate of a small working set; large ones want a few per
+// compute unit), but every extra split adds a partial result that the merge has to read, and
+// no split is shorter than one 128-key block.
+static inline AttnPlan attn_plan(int B, int H, int N, int D, int Cmax, size_t elem_bytes)
 {
     AttnPlan p;
     const long long BH = (long long)B * H;
-    const int nblk = (Cmax + kBlockKeys - 1) / kBlockKeys;
-    static const int target_wgs = env_int("RD_ATTN_TARGET_WGS", 1024);
-    long long S = (target_wgs + BH - 1) / BH - 1;
+    const double kv_bytes = 2.0 * (double)BH * Cmax * D * (double)elem_bytes;
+    const bool small = kv_bytes < 64e6;          // latency-bound: few blocks per range
+    static const int waves_env = env_int("RD_ATTN_WAVES", 0);
+    p.waves = (elem_bytes == 2 && D == 128 && N <= 80 && small) ? 8 : 4;
+    if (waves_env == 4 || (waves_env == 8 && elem_bytes == 2 && D == 128 && N <= 80)) p.waves = waves_env;
+    const int block_keys = elem_bytes == 2 ? 32 * p.waves : kBlockKeys;
+    const int nblk = (Cmax + block_keys - 1) / block_keys;
+    static const int target_small = env_int("RD_ATTN_TARGET_WGS_SMALL", 128);
+    static const int target_large = env_int("RD_ATTN_TARGET_WGS", 512);
+    const int target = small ? target_small : target_large;
+    long long S = (target + BH - 1) / BH;
     if (S > nblk) S = nblk;
     if (S < 1) S = 1;
     static const int forced = env_int("RD_ATTN_SPLITS", 0);
@@ -61,20 +72,21 @@ struct AttnArgs {
     uint32_t *counters;
     float *partials;
     int B, H, N, Cmax, S, words, rows_pad;
+    int xcd_remap; // 1: workgroup i serves XCD i%8's share of the heads (needs B*H % 8 == 0)
     float scale_log2e;
 };
 
 __device__ __forceinline__ int clampi(int x, int lo, int hi) { return x < lo ? lo : (x > hi ? hi : x); }
 
 // Context key range [k_begin, k_end) of split s out of S for a context of C keys: whole
-// 128-key blocks, spread as evenly as whole blocks allow.
-__device__ __forceinline__ void ctx_range(int C, int S, int s, int *k_begin, int *k_end)
+// blocks of block_keys keys, spread as evenly as whole blocks allow.
+__device__ __forceinline__ void ctx_range(int C, int S, int s, int block_keys, int *k_begin, int *k_end)
 {
-    const int nblk = (C + kBlockKeys - 1) / kBlockKeys;
+    const int nblk = (C + block_keys - 1) / block_keys;
     const int per = (nblk + S - 1) / S;
-    const int kb = s * per * kBlockKeys;
+    const int kb = s * per * block_keys;
     *k_begin = kb < C ? kb : C;
-    const int ke = kb + per * kBlockKeys;
+    const int ke = kb + per * block_keys;
     *k_end = ke < C ? ke : C;
 }
 
@@ -90,21 +102,67 @@ __device__ __forceinline__ void store_out4(__bf16 *dst, float a, float b, float 
     *reinterpret_cast<bf16x4 *>(dst) = v;
 }
 
-// Signals that this workgroup's partial is stored; returns true in every thread of the
-// workgroup that arrives last among `expected` for this (sequence, head).
-__device__ __forceinline__ bool arrive_is_last(uint32_t *counter, uint32_t expected)
+// ---- exchange of partial results between workgroups -------------------------------------------
+// The partials are written by one workgroup and read by another that may sit on a different
+// XCD (each XCD has its own L2).  A device-wide release/acquire fence would write back and
+// invalidate whole L2s on every workgroup, which costs far more than the kernel itself, so the
+// exchange uses device-scope (write-through / cache-bypassing) relaxed atomic accesses for the
+// data itself, made complete with a wait for outstanding memory operations before the counter
+// is bumped.  Only these few KB per workgroup travel that way; the K/V stream uses plain loads.
+__device__ __forceinline__ void st_dev(float *p, float v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_dev2(float *p, float a, float b)
+{
+    unsigned long long u = (unsigned long long)__float_as_uint(a) | ((unsigned long long)__float_as_uint(b) << 32);
+    __hip_atomic_store(reinterpret_cast<unsigned long long *>(p), u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_dev(const float *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float2 ld_dev2(const float *p)
+{
+    const unsigned long long u =
+        __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return make_float2(__uint_as_float((unsigned)u), __uint_as_float((unsigned)(u >> 32)));
+}
+
+// 16-byte device-scope store (write-through); the caller must call wait_dev_stores() before it
+// signals completion, because the compiler does not count this store as outstanding.
+__device__ __forceinline__ void st_dev4(float *p, float a, float b, float c, float d)
+{
+    typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+    const f32x4_t v = {a, b, c, d};
+    asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void wait_dev_stores() { asm volatile("s_waitcnt vmcnt(0)" : : : "memory"); }
+
+// XCD this workgroup runs on (hardware register XCC_ID).
+__device__ __forceinline__ uint32_t xcc_id() { return __builtin_amdgcn_s_getreg((31 << 11) | 20) & 0xfu; }
+
+enum { kNotLast = 0, kLastClean = 1, kLastMixed = 2 };
+
+// Signals that this workgroup's partial is stored (with st_dev*); tells every thread of the
+// workgroup whether it arrived last among `expected` for this (sequence, head).  `off_xcd` is
+// nonzero if this workgroup found itself on another XCD than the work mapping assumes; the last
+// arriver learns (kLastMixed) if that happened to any of them, and must then read the partials
+// with ld_dev* rather than through its own L2.
+__device__ __forceinline__ int arrive_is_last(uint32_t *counter, uint32_t expected, uint32_t off_xcd = 0)
 {
     __shared__ uint32_t s_last;
-    __threadfence();          // release: partial stores become visible device-wide
+    wait_dev_stores();
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // waits until this thread's stores are acknowledged
     __syncthreads();
     if (threadIdx.x == 0) {
-        const uint32_t prev = atomicAdd(counter, 1u);
-        s_last = (prev == expected - 1u) ? 1u : 0u;
+        const uint32_t add = 1u + (off_xcd ? 0x10000u : 0u);
+        const uint32_t now = __hip_atomic_fetch_add(counter, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + add;
+        s_last = ((now & 0xffffu) == expected) ? ((now >> 16) ? kLastMixed : kLastClean) : kNotLast;
     }
     __syncthreads();
-    const bool last = s_last != 0u;
-    if (last) __threadfence();   // acquire: see the other workgroups' partials
-    return last;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");   // later loads stay after the counter update
+    return (int)s_last;
 }
 
 // Merge of the S+1 partial softmax states of one (sequence, head) and final store:
@@ -123,16 +181,17 @@ __device__ __forceinline__ void combine_partials(const float *part /* first part
         float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
         if (p < P) {
             float M = -INFINITY;
-            for (int s = 0; s < n_part; ++s) M = fmaxf(M, part[s * partial_floats + p]);
+            for (int s = 0; s < n_part; ++s) M = fmaxf(M, ld_dev(part + s * partial_floats + p));
             float denom = 0.f;
             for (int s = 0; s < n_part; ++s) {
                 const float *ps = part + s * partial_floats;
-                const float m = ps[p];
+                const float m = ld_dev(ps + p);
                 if (m == -INFINITY) continue;          // that range held no visible key for row p
                 const float w = __builtin_amdgcn_exp2f(m - M);
-                denom += w * ps[rows_pad + p];
-                const float4 o = *reinterpret_cast<const float4 *>(ps + 2 * rows_pad + (size_t)p * D + 4 * v);
-                a0 += w * o.x; a1 += w * o.y; a2 += w * o.z; a3 += w * o.w;
+                denom += w * ld_dev(ps + rows_pad + p);
+                const float *po = ps + 2 * rows_pad + (size_t)p * D + 4 * v;
+                const float2 o01 = ld_dev2(po), o23 = ld_dev2(po + 2);
+                a0 += w * o01.x; a1 += w * o01.y; a2 += w * o23.x; a3 += w * o23.y;
             }
             const float inv = 1.0f / denom;
             a0 *= inv; a1 *= inv; a2 *= inv; a3 *= inv;

@@ -3,7 +3,7 @@
 #include "rd_attn_common.h"
 
 namespace rd {
-int tree_attn_bf16(const AttnArgs &a, int D, hipStream_t stream);
+int tree_attn_bf16(const AttnArgs &a, int D, int waves, hipStream_t stream);
 int tree_attn_f32(const AttnArgs &a, int D, hipStream_t stream);
 }  // namespace rd
 
@@ -20,7 +20,7 @@ static int attn_check_shape(int B, int H, int N, int D, int Cmax, rd_dtype dt)
 extern "C" size_t rd_tree_attn_workspace(int B, int H, int N, int D, int Cmax, rd_dtype dt)
 {
     if (attn_check_shape(B, H, N, D, Cmax, dt) != RD_OK) return 0;
-    return rd::attn_plan(B, H, N, D, Cmax).total_bytes;
+    return rd::attn_plan(B, H, N, D, Cmax, dt == RD_BF16 ? 2 : 4).total_bytes;
 }
 
 extern "C" int rd_tree_attn(const void *q, const void *k_cache, const void *v_cache,
@@ -36,7 +36,7 @@ extern "C" int rd_tree_attn(const void *q, const void *k_cache, const void *v_ca
     if (!rd_aligned(q, 16) || !rd_aligned(k_cache, 16) || !rd_aligned(v_cache, 16) || !rd_aligned(k_new, 16) ||
         !rd_aligned(v_new, 16) || !rd_aligned(out, 16) || !rd_aligned(tree_mask_bits, 8))
         return RD_ERR_INVALID_ARG;
-    const rd::AttnPlan plan = rd::attn_plan(B, H, N, D, Cmax);
+    const rd::AttnPlan plan = rd::attn_plan(B, H, N, D, Cmax, dt == RD_BF16 ? 2 : 4);
     if (!workspace || !rd_aligned(workspace, 256) || workspace_bytes < plan.total_bytes) return RD_ERR_WORKSPACE;
 
     rd::AttnArgs a;
@@ -46,5 +46,6 @@ extern "C" int rd_tree_attn(const void *q, const void *k_cache, const void *v_ca
     a.partials = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + plan.counters_bytes);
     a.B = B; a.H = H; a.N = N; a.Cmax = Cmax; a.S = plan.S; a.words = (N + 63) / 64; a.rows_pad = plan.rows_pad;
     a.scale_log2e = scale * 1.44269504088896340736f;
-    return dt == RD_BF16 ? rd::tree_attn_bf16(a, D, (hipStream_t)stream) : rd::tree_attn_f32(a, D, (hipStream_t)stream);
+    a.xcd_remap = (((long long)B * H) % 8 == 0) ? 1 : 0;
+    return dt == RD_BF16 ? rd::tree_attn_bf16(a, D, plan.waves, (hipStream_t)stream) : rd::tree_attn_f32(a, D, (hipStream_t)stream);
 }

@@ -6,14 +6,15 @@
 // organised around the stream:
 //   * a workgroup (4 waves) owns a contiguous key range of one (sequence, head) and walks
 //     it in blocks of 128 keys; wave w loads rows 32w..32w+31 of the block for K and for V
-//     with fully coalesced 16-byte-per-lane loads (a wave instruction covers whole 256-byte
-//     rows), one block ahead of the arithmetic, and parks them in LDS;
+//     with fully coalesced 16-byte-per-lane loads (a wave instruction covers 1 KB of
+//     consecutive rows), one block ahead of the arithmetic, and parks them in LDS;
 //   * scores are produced transposed, S^T = K Q^T, with v_mfma_f32_16x16x32_bf16: the wave
 //     reads its own K tile back from LDS in the A-operand layout (XOR-swizzled, conflict
 //     free) and Q (resident in LDS for the whole kernel) as the B operand;
 //   * tree mask (bit test against tree_mask_bits) and range limits are applied to the
-//     accumulators in registers; the four waves exchange their per-row tile maxima through
-//     LDS so the block has one running maximum per packed row (online softmax, log2 units);
+//     accumulators in registers, only in tiles that need them; the four waves exchange their
+//     per-row tile maxima through LDS so the block has one running maximum per packed row
+//     (online softmax, log2 units);
 //   * the probabilities, rounded to bf16, are written to LDS already in B-operand layout;
 //     the accumulator layout of S^T makes each lane's eight values exactly one B operand
 //     once the 32 keys of a tile are taken in the order (4g+i, 16+4g+i);
@@ -23,13 +24,28 @@
 //     the same key order.  The output accumulators therefore need no cross-wave reduction.
 //   * the partial state goes to the workspace and the last workgroup of the head merges.
 #include "rd_attn_common.h"
+#include <type_traits>
+
+// Optional phase timestamps for tuning builds (-DRD_TRACE): thread 0 of every workgroup
+// stores the constant-rate wall clock at a few points into a caller-supplied buffer.
+#ifdef RD_TRACE
+__device__ unsigned long long *rd_trace_buf = nullptr;
+extern "C" int rd_debug_set_trace(unsigned long long *p)
+{
+    return hipMemcpyToSymbol(HIP_SYMBOL(rd_trace_buf), &p, sizeof(p)) == hipSuccess ? 0 : -4;
+}
+#define RD_TR(i) do { if (threadIdx.x == 0 && rd_trace_buf) rd_trace_buf[(size_t)blockIdx.x * 16 + (i)] = wall_clock64(); } while (0)
+#else
+#define RD_TR(i) do { } while (0)
+#endif
 
 namespace rd {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
 template <int D>
 struct Geo {
@@ -55,304 +71,540 @@ template <int D> __device__ __forceinline__ int vswz(int row, int c)
 
 __device__ __forceinline__ uint4 ldg16(const void *p) { return *reinterpret_cast<const uint4 *>(p); }
 
-template <int D, int NQ>
-__global__ __launch_bounds__(kAttnThreads, 2) void rd_tree_attn_bf16_kernel(AttnArgs a)
+// Synchronisation that orders LDS traffic only.  __syncthreads() also waits for every global
+// load in flight, which would drain the K/V prefetch at each of the three barriers per block.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+// Orders this wave's own LDS writes before its own later LDS reads (tiles private to a wave).
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// NW = waves per workgroup (4 or 8).  A block is 32*NW keys; eight waves halve the number of
+// sequential blocks of a range, which is what counts when a range is only one or two blocks long.
+// max / sum over the four lanes l, l^16, l^32, l^48 (the four 8-key groups of a score tile
+// column) with the gfx950 lane-swap instructions: each gives a lane the pair {x[l], x[l^k]}.
+__device__ __forceinline__ float quad_max(float x)
+{
+    auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float quad_sum(float x)
+{
+    auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+    auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
+template <int D, int NQ, int NW>
+__global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs a)
 {
     using G = Geo<D>;
+    constexpr int kThreads = NW * 64;
+    constexpr int kBlock = NW * G::kTileKeys;                   // keys per block
     constexpr int kRows = NQ * 16;
+    constexpr int kDTW = G::kDTiles / NW;                       // d-tiles of the output owned by a wave
+    static_assert(kDTW >= 1, "more waves than output d-tiles");
+    constexpr int kPF = kRows * (2 + D);                        // floats per partial
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     unsigned char *sQ = smem;                                   // [kRows][kRowBytes]
-    unsigned char *sKV = sQ + kRows * G::kRowBytes;             // 4 tiles [32][kRowBytes]
-    unsigned char *sP = sKV + 4 * G::kTileBytes;                // [4 kt][NQ][64 lanes] x 16 B
-    float *sM = reinterpret_cast<float *>(sP + 4 * NQ * 64 * 16);   // [4 waves][kRows]
+    unsigned char *sKV = sQ + kRows * G::kRowBytes;             // NW tiles [32][kRowBytes]
+    unsigned char *sP = sKV + NW * G::kTileBytes;               // [NW kt][NQ][64 lanes] x 16 B
+    float *sM = reinterpret_cast<float *>(sP + NW * NQ * 64 * 16);  // [NW waves][kRows]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int r16 = lane & 15;
     const int g = lane >> 4;
+    RD_TR(0);
 
+    // ---- which (sequence, head, key range) -------------------------------------------------------
+    // Workgroups are dealt round-robin to the 8 XCDs; when the head count allows, all ranges of a
+    // head go to one XCD so that Q and the partial results stay in that XCD's L2.
     const int n_part = a.S + 1;
-    const int bh = blockIdx.x / n_part;
-    const int split = blockIdx.x % n_part;
+    int bh, split;
+    if (a.xcd_remap) {
+        const int xcd = blockIdx.x & 7, k = blockIdx.x >> 3;
+        bh = (k / n_part) * 8 + xcd;
+        split = k % n_part;
+    } else {
+        bh = blockIdx.x / n_part;
+        split = blockIdx.x % n_part;
+    }
     const int b = bh / a.H;
     const int C = clampi(a.ctx_len[b], 0, a.Cmax);
     const int P = clampi(a.n_packed[b], 0, a.N);
     const bool is_tree = (split == a.S);
 
     int k_begin, k_end;
-    const __bf16 *Kb, *Vb;
+    const unsigned char *Kb, *Vb;                 // byte address of key 0 of the tensor this range reads
     if (is_tree) {
         k_begin = 0;
         k_end = P;
-        Kb = static_cast<const __bf16 *>(a.k_new) + (size_t)bh * a.N * D;
-        Vb = static_cast<const __bf16 *>(a.v_new) + (size_t)bh * a.N * D;
+        Kb = static_cast<const unsigned char *>(a.k_new) + (size_t)bh * a.N * G::kRowBytes;
+        Vb = static_cast<const unsigned char *>(a.v_new) + (size_t)bh * a.N * G::kRowBytes;
     } else {
-        ctx_range(C, a.S, split, &k_begin, &k_end);
-        Kb = static_cast<const __bf16 *>(a.k_cache) + (size_t)bh * a.Cmax * D;
-        Vb = static_cast<const __bf16 *>(a.v_cache) + (size_t)bh * a.Cmax * D;
+        ctx_range(C, a.S, split, kBlock, &k_begin, &k_end);
+        Kb = static_cast<const unsigned char *>(a.k_cache) + (size_t)bh * a.Cmax * G::kRowBytes;
+        Vb = static_cast<const unsigned char *>(a.v_cache) + (size_t)bh * a.Cmax * G::kRowBytes;
     }
 
-    // ---- this wave's slice of a block: guarded, coalesced loads into registers -------------
-    uint4 kreg[G::kLoads], vreg[G::kLoads];
-    const int ld_row = lane / G::kChunks;        // row within one load
-    const int ld_chunk = lane % G::kChunks;
-    auto load_tile = [&](const __bf16 *base, int tile0, uint4 (&reg)[G::kLoads]) {
+    // ---- all first loads, without branches so that the waits on them stay exact --------------------
+    // Order: Q and the tree-mask words (they gate the first score tile), then K, then V.
+    constexpr int kQRowsPerPass = kThreads / G::kChunks;
+    constexpr int kQPasses = (kRows + kQRowsPerPass - 1) / kQRowsPerPass;
+    const unsigned char *Qb = static_cast<const unsigned char *>(a.q) + (size_t)bh * a.N * G::kRowBytes;
+    uint4 qreg[kQPasses];
 #pragma unroll
-        for (int s = 0; s < G::kLoads; ++s) {
-            const int key = tile0 + s * G::kRowsPerLoad + ld_row;
-            reg[s] = (key < k_end) ? ldg16(base + (size_t)key * D + ld_chunk * 8) : make_uint4(0, 0, 0, 0);
-        }
-    };
-    load_tile(Kb, k_begin + wave * G::kTileKeys, kreg);
-    load_tile(Vb, k_begin + wave * G::kTileKeys, vreg);
-
-    // ---- Q of this head into LDS (rows >= P zeroed) ------------------------------------------
+    for (int i = 0; i < kQPasses; ++i) {
+        const int row = min(i * kQRowsPerPass + tid / G::kChunks, P - 1);    // rows >= P are zeroed below
+        qreg[i] = ldg16(Qb + max(row, 0) * G::kRowBytes + (tid % G::kChunks) * 16);
+    }
+    // Visibility of this wave's 32 keys for the packed rows this lane scores (row 16*qt + r16).
+    // Context keys are visible to every row; the packed keys (one block, since N <= 128) are
+    // visible per the tree mask: wave w holds keys 32w..32w+31, i.e. half of mask word w/2.
+    // (Loaded by context workgroups too, and ignored there.)
+    uint64_t mword[NQ];
     {
-        const __bf16 *Qb = static_cast<const __bf16 *>(a.q) + (size_t)bh * a.N * D;
-        constexpr int kRowsPerPass = kAttnThreads / G::kChunks;
-        const int c = tid % G::kChunks;
+        const int word = min(wave >> 1, a.words - 1);
 #pragma unroll
-        for (int r0 = 0; r0 < kRows; r0 += kRowsPerPass) {
-            const int row = r0 + tid / G::kChunks;
-            if (row < kRows) {
-                const uint4 v = (row < P) ? ldg16(Qb + (size_t)row * D + c * 8) : make_uint4(0, 0, 0, 0);
-                *reinterpret_cast<uint4 *>(sQ + row * G::kRowBytes + kswz<D>(row, c) * 16) = v;
-            }
-        }
+        for (int qt = 0; qt < NQ; ++qt)
+            mword[qt] = a.mask_bits[((size_t)b * a.N + min(qt * 16 + r16, a.N - 1)) * a.words + word];
     }
 
-    // ---- tree mask rows of the packed rows this lane scores (row 16*qt + r16) ------------------
-    uint64_t mw[NQ][2];
+    // This wave's slice of a block: coalesced 16-byte loads into registers; a wave-wide load
+    // covers 1 KB of consecutive rows.  Rows past the end of the range are redirected to the last
+    // valid row (their scores are masked and their probabilities are zero), so the loads carry no
+    // predicate.  An empty range reads (and ignores) the first row of Q instead.
+    uint4 kreg[G::kLoads], vreg[G::kLoads];
+    const int ld_row = lane / G::kChunks;
+    const int ld_chunk = lane % G::kChunks;
+    const bool any_keys = k_end > k_begin;                                   // uniform
+    const uint32_t last_off = (any_keys ? (uint32_t)(k_end - 1) * G::kRowBytes : 0u) + ld_chunk * 16;
+    auto load_tile = [&](const unsigned char *base, int tile0, uint4 (&reg)[G::kLoads]) __attribute__((always_inline)) {
+        const uint32_t off0 = (uint32_t)(tile0 + ld_row) * G::kRowBytes + ld_chunk * 16;
+#pragma unroll
+        for (int s = 0; s < G::kLoads; ++s) reg[s] = ldg16(base + min(off0 + s * 1024u, last_off));
+    };
+    load_tile(any_keys ? Kb : Qb, k_begin + wave * G::kTileKeys, kreg);
+    load_tile(any_keys ? Vb : Qb, k_begin + wave * G::kTileKeys, vreg);
+
+    uint32_t vis[NQ];
 #pragma unroll
     for (int qt = 0; qt < NQ; ++qt) {
-        mw[qt][0] = 0;
-        mw[qt][1] = 0;
-        const int qrow = qt * 16 + r16;
-        if (is_tree && qrow < P) {
-            const uint64_t *mrow = a.mask_bits + ((size_t)b * a.N + qrow) * a.words;
-            mw[qt][0] = mrow[0];
-            if (a.words > 1) mw[qt][1] = mrow[1];
+        vis[qt] = 0xffffffffu;
+        if (is_tree) {
+            const bool real = (qt * 16 + r16 < P) && ((wave >> 1) < a.words);
+            vis[qt] = real ? (uint32_t)(mword[qt] >> ((wave & 1) * 32)) : 0u;
         }
+    }
+
+#pragma unroll
+    for (int i = 0; i < kQPasses; ++i) {
+        const int row = i * kQRowsPerPass + tid / G::kChunks;
+        if (row < kRows)
+            *reinterpret_cast<uint4 *>(sQ + row * G::kRowBytes + kswz<D>(row, tid % G::kChunks) * 16) =
+                (row < P) ? qreg[i] : make_uint4(0, 0, 0, 0);
     }
 
     float m_run[NQ], l_run[NQ];
-    f32x4 oacc[G::kDTilesPerWave][NQ];
+    f32x4 oacc[kDTW][NQ];
 #pragma unroll
     for (int qt = 0; qt < NQ; ++qt) {
         m_run[qt] = -INFINITY;
         l_run[qt] = 0.f;
 #pragma unroll
-        for (int j = 0; j < G::kDTilesPerWave; ++j) oacc[j][qt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < kDTW; ++j) oacc[j][qt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
     unsigned char *my_tile = sKV + wave * G::kTileBytes;
-
-    for (int blk0 = k_begin; blk0 < k_end; blk0 += kBlockKeys) {
-        const int tile0 = blk0 + wave * G::kTileKeys;
-        const bool more = blk0 + kBlockKeys < k_end;
-
-        // K registers -> own LDS tile (K swizzle); then fetch the next block's K
+    // lane-constant LDS offsets
+    int k_wr[G::kLoads], v_wr[G::kLoads];
 #pragma unroll
-        for (int s = 0; s < G::kLoads; ++s) {
-            const int row = s * G::kRowsPerLoad + ld_row;
-            *reinterpret_cast<uint4 *>(my_tile + row * G::kRowBytes + kswz<D>(row, ld_chunk) * 16) = kreg[s];
-        }
-        if (more) load_tile(Kb, tile0 + kBlockKeys, kreg);
-        __syncthreads();      // K tile (and, first time round, Q) visible
-
-        // S^T tile pair: keys (16 mt + r) x packed rows (16 qt + c)
-        f32x4 sacc[2][NQ];
-#pragma unroll
-        for (int qt = 0; qt < NQ; ++qt) {
-            sacc[0][qt] = f32x4{0.f, 0.f, 0.f, 0.f};
-            sacc[1][qt] = f32x4{0.f, 0.f, 0.f, 0.f};
-        }
-#pragma unroll
-        for (int t = 0; t < G::kKSteps; ++t) {
-            const int c = 4 * t + g;
-            const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(my_tile + r16 * G::kRowBytes + kswz<D>(r16, c) * 16);
-            const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(my_tile + (16 + r16) * G::kRowBytes + kswz<D>(16 + r16, c) * 16);
-#pragma unroll
-            for (int qt = 0; qt < NQ; ++qt) {
-                const int qrow = qt * 16 + r16;
-                const bf16x8 bq = *reinterpret_cast<const bf16x8 *>(sQ + qrow * G::kRowBytes + kswz<D>(qrow, c) * 16);
-                sacc[0][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, bq, sacc[0][qt], 0, 0, 0);
-                sacc[1][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, bq, sacc[1][qt], 0, 0, 0);
-            }
-        }
-
-        // mask + scale (log2 units) + per-row maximum over this wave's 32 keys
-#pragma unroll
-        for (int qt = 0; qt < NQ; ++qt) {
-            float tmax = -INFINITY;
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int key = tile0 + 16 * mt + 4 * g + i;
-                    bool ok = key < k_end;
-                    if (is_tree) ok = ok && ((((key & 64) ? mw[qt][1] : mw[qt][0]) >> (key & 63)) & 1ull);
-                    const float s = ok ? sacc[mt][qt][i] * a.scale_log2e : -INFINITY;
-                    sacc[mt][qt][i] = s;
-                    tmax = fmaxf(tmax, s);
-                }
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-            if (g == 0) sM[wave * kRows + qt * 16 + r16] = tmax;
-        }
-
-        // V registers -> own LDS tile (V swizzle), replacing K which this wave has consumed
-        __syncthreads();      // every wave is done reading its K tile
-#pragma unroll
-        for (int s = 0; s < G::kLoads; ++s) {
-            const int row = s * G::kRowsPerLoad + ld_row;
-            *reinterpret_cast<uint4 *>(my_tile + row * G::kRowBytes + vswz<D>(row, ld_chunk) * 16) = vreg[s];
-        }
-        if (more) load_tile(Vb, tile0 + kBlockKeys, vreg);
-
-        // online softmax with the block-wide maximum; P^T to LDS in B-operand layout
-#pragma unroll
-        for (int qt = 0; qt < NQ; ++qt) {
-            const int qrow = qt * 16 + r16;
-            float mb = fmaxf(fmaxf(sM[qrow], sM[kRows + qrow]), fmaxf(sM[2 * kRows + qrow], sM[3 * kRows + qrow]));
-            const float m_new = fmaxf(m_run[qt], mb);
-            const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - m_safe);
-            m_run[qt] = m_new;
-            float psum = 0.f;
-            bf16x8 pb;
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float p = __builtin_amdgcn_exp2f(sacc[mt][qt][i] - m_safe);
-                    psum += p;
-                    pb[4 * mt + i] = (__bf16)p;
-                }
-            l_run[qt] = l_run[qt] * alpha + psum;
-            *reinterpret_cast<bf16x8 *>(sP + ((wave * NQ + qt) * 64 + lane) * 16) = pb;
-#pragma unroll
-            for (int j = 0; j < G::kDTilesPerWave; ++j) oacc[j][qt] *= alpha;
-        }
-        __syncthreads();      // V tiles and P^T of all four waves visible
-
-        // O^T += V^T P^T over the block's four key tiles, for this wave's d-tiles
-#pragma unroll
-        for (int kt = 0; kt < 4; ++kt) {
-            if (blk0 + kt * G::kTileKeys >= k_end) break;     // tile beyond the range: P^T is zero
-            const unsigned char *vt = sKV + kt * G::kTileBytes;
-            bf16x8 pB[NQ];
-#pragma unroll
-            for (int qt = 0; qt < NQ; ++qt)
-                pB[qt] = *reinterpret_cast<const bf16x8 *>(sP + ((kt * NQ + qt) * 64 + lane) * 16);
-#pragma unroll
-            for (int j = 0; j < G::kDTilesPerWave; ++j) {
-                const int dt = wave * G::kDTilesPerWave + j;
-                const int c = 2 * dt + ((r16 & 3) >> 1);
-                const int ra = 4 * g + (r16 >> 2);
-                const int rb = 16 + ra;
-                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (__attribute__((address_space(3))) s16x4 *)(vt + ra * G::kRowBytes + vswz<D>(ra, c) * 16 + (r16 & 1) * 8));
-                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (__attribute__((address_space(3))) s16x4 *)(vt + rb * G::kRowBytes + vswz<D>(rb, c) * 16 + (r16 & 1) * 8));
-                typedef __attribute__((ext_vector_type(8))) short s16x8;
-                const s16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                const bf16x8 aV = __builtin_bit_cast(bf16x8, av);
-#pragma unroll
-                for (int qt = 0; qt < NQ; ++qt)
-                    oacc[j][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aV, pB[qt], oacc[j][qt], 0, 0, 0);
-            }
-        }
-        __syncthreads();      // tiles and P^T free for the next block
+    for (int s = 0; s < G::kLoads; ++s) {
+        const int row = s * G::kRowsPerLoad + ld_row;
+        k_wr[s] = row * G::kRowBytes + kswz<D>(row, ld_chunk) * 16;
+        v_wr[s] = row * G::kRowBytes + vswz<D>(row, ld_chunk) * 16;
     }
+    int kq_rd[G::kKSteps];                       // row r16, chunk 4t+g (rows 16+r16, 16qt+r16 add constants)
+#pragma unroll
+    for (int t = 0; t < G::kKSteps; ++t) kq_rd[t] = r16 * G::kRowBytes + kswz<D>(r16, 4 * t + g) * 16;
+    int v_rd[kDTW];                              // transpose-read address of rows 4g+(r16>>2) for d-tile j
+#pragma unroll
+    for (int j = 0; j < kDTW; ++j) {
+        const int dt = wave * kDTW + j;
+        const int ra = 4 * g + (r16 >> 2);
+        v_rd[j] = ra * G::kRowBytes + vswz<D>(ra, 2 * dt + ((r16 & 3) >> 1)) * 16 + (r16 & 1) * 8;
+    }
+
+    lds_barrier();        // Q visible to all waves
+    RD_TR(1);
+
+    const int nqt = (P + 15) >> 4;            // row tiles that hold packed rows; the others are skipped
+    const float c_abs = fabsf(a.scale_log2e);
+    const bool c_neg = a.scale_log2e < 0.f;
+
+    // The block loop is instantiated twice: for all row tiles, and for the lower half when the
+    // packed rows fit there (a padded tile costs as much as a real one, and branches around it
+    // would stop the compiler from overlapping LDS reads with the matrix instructions).
+    auto block_loop = [&](auto nqa_tag) __attribute__((always_inline)) {
+        constexpr int NQA = decltype(nqa_tag)::value;
+        for (int blk0 = k_begin; blk0 < k_end; blk0 += kBlock) {
+            const int tile0 = blk0 + wave * G::kTileKeys;
+            const bool more = blk0 + kBlock < k_end;
+
+            // K registers -> own LDS tile (K swizzle); then fetch the next block's K
+#pragma unroll
+            for (int s = 0; s < G::kLoads; ++s) *reinterpret_cast<uint4 *>(my_tile + k_wr[s]) = kreg[s];
+            if (more) load_tile(Kb, tile0 + kBlock, kreg);
+            wave_lds_sync();
+
+            // S^T tile pair: keys (16 mt + r) x packed rows (16 qt + c), raw (unscaled) scores
+            f32x4 sacc[2][NQA];
+#pragma unroll
+            for (int qt = 0; qt < NQA; ++qt) {
+                sacc[0][qt] = f32x4{0.f, 0.f, 0.f, 0.f};
+                sacc[1][qt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int t = 0; t < G::kKSteps; ++t) {
+                const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(my_tile + kq_rd[t]);
+                const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(my_tile + kq_rd[t] + 16 * G::kRowBytes);
+#pragma unroll
+                for (int qt = 0; qt < NQA; ++qt) {
+                    {
+                        const bf16x8 bq = *reinterpret_cast<const bf16x8 *>(sQ + kq_rd[t] + qt * 16 * G::kRowBytes);
+                        sacc[0][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, bq, sacc[0][qt], 0, 0, 0);
+                        sacc[1][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, bq, sacc[1][qt], 0, 0, 0);
+                    }
+                }
+            }
+            if (blk0 == k_begin) RD_TR(8);
+
+            // per-row maximum over this wave's 32 keys, in log2 units (score * scale * log2 e).  An
+            // interior context tile keeps the raw scores (the scale is folded into the exponent
+            // later); a tile with masked or out-of-range keys is scaled here and its dead entries
+            // set to -inf.
+            const int rem = k_end - tile0;                         // keys of this tile inside the range
+            const bool plain = !is_tree && rem >= G::kTileKeys && !c_neg;
+            if (plain) {
+#pragma unroll
+                for (int qt = 0; qt < NQA; ++qt) {
+                    {
+                        float tmax = fmaxf(fmaxf(fmaxf(sacc[0][qt][0], sacc[0][qt][1]), fmaxf(sacc[0][qt][2], sacc[0][qt][3])),
+                                           fmaxf(fmaxf(sacc[1][qt][0], sacc[1][qt][1]), fmaxf(sacc[1][qt][2], sacc[1][qt][3])));
+                        tmax = quad_max(tmax) * c_abs;
+                        if (g == 0) sM[(qt * 16 + r16) * NW + wave] = tmax;
+                    }
+                }
+            } else {
+                const uint32_t tail = rem >= 32 ? 0xffffffffu : (rem <= 0 ? 0u : ((1u << rem) - 1u));
+#pragma unroll
+                for (int qt = 0; qt < NQA; ++qt) {
+                    {
+                        const uint32_t bits = (vis[qt] & tail) >> (4 * g);     // element (mt, i) at bit 16 mt + i
+                        float tmax = -INFINITY;
+#pragma unroll
+                        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                const float sv = ((bits >> (16 * mt + i)) & 1u) ? sacc[mt][qt][i] * a.scale_log2e : -INFINITY;
+                                sacc[mt][qt][i] = sv;
+                                tmax = fmaxf(tmax, sv);
+                            }
+                        tmax = quad_max(tmax);
+                        if (g == 0) sM[(qt * 16 + r16) * NW + wave] = tmax;
+                    }
+                }
+            }
+
+            lds_barrier();        // (A) tile maxima of all waves visible
+            if (blk0 == k_begin) RD_TR(9);
+
+            // V registers -> own LDS tile (V swizzle), replacing K which this wave has consumed
+#pragma unroll
+            for (int s = 0; s < G::kLoads; ++s) *reinterpret_cast<uint4 *>(my_tile + v_wr[s]) = vreg[s];
+            if (more) load_tile(Vb, tile0 + kBlock, vreg);
+
+            // online softmax with the block-wide maximum; P^T to LDS in B-operand layout
+#pragma unroll
+            for (int qt = 0; qt < NQA; ++qt) {
+                {
+                    const f32x4 *pm = reinterpret_cast<const f32x4 *>(sM + (qt * 16 + r16) * NW);
+                    f32x4 mv = pm[0];
+                    if (NW == 8) {
+                        const f32x4 mv2 = pm[1];
+                        mv[0] = fmaxf(mv[0], mv2[0]); mv[1] = fmaxf(mv[1], mv2[1]);
+                        mv[2] = fmaxf(mv[2], mv2[2]); mv[3] = fmaxf(mv[3], mv2[3]);
+                    }
+                    const float mb = fmaxf(fmaxf(mv[0], mv[1]), fmaxf(mv[2], mv[3]));
+                    const float m_new = fmaxf(m_run[qt], mb);
+                    const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+                    const float alpha = __builtin_amdgcn_exp2f(m_run[qt] - m_safe);
+                    m_run[qt] = m_new;
+                    float psum = 0.f;
+                    bf16x8 pb;
+#pragma unroll
+                    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const float e = plain ? __builtin_fmaf(sacc[mt][qt][i], c_abs, -m_safe) : sacc[mt][qt][i] - m_safe;
+                            const float pv = __builtin_amdgcn_exp2f(e);
+                            psum += pv;
+                            pb[4 * mt + i] = (__bf16)pv;
+                        }
+                    l_run[qt] = l_run[qt] * alpha + psum;
+                    *reinterpret_cast<bf16x8 *>(sP + ((wave * NQ + qt) * 64 + lane) * 16) = pb;
+                    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {      // the maximum moved for some row
+#pragma unroll
+                        for (int j = 0; j < kDTW; ++j) oacc[j][qt] *= alpha;
+                    }
+                }
+            }
+            lds_barrier();        // (B) V tiles and P^T of all waves visible
+            if (blk0 == k_begin) RD_TR(10);
+
+            // O^T += V^T P^T over the block's key tiles, for this wave's d-tiles.  Key tiles beyond
+            // the range were not loaded (their P^T is zero); only the last block of a range can have them.
+            auto pv_tile = [&](int kt) __attribute__((always_inline)) {
+                const unsigned char *vt = sKV + kt * G::kTileBytes;
+                bf16x8 aV[kDTW];
+#pragma unroll
+                for (int j = 0; j < kDTW; ++j) {
+                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(vt + v_rd[j]));
+                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(vt + v_rd[j] + 16 * G::kRowBytes));
+                    aV[j] = __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+                }
+#pragma unroll
+                for (int qt = 0; qt < NQA; ++qt) {
+                    const bf16x8 pB = *reinterpret_cast<const bf16x8 *>(sP + ((kt * NQ + qt) * 64 + lane) * 16);
+#pragma unroll
+                    for (int j = 0; j < kDTW; ++j)
+                        oacc[j][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aV[j], pB, oacc[j][qt], 0, 0, 0);
+                }
+            };
+            if (blk0 + kBlock <= k_end) {
+#pragma unroll
+                for (int kt = 0; kt < NW; ++kt) pv_tile(kt);
+            } else {
+#pragma unroll 1
+                for (int kt = 0; blk0 + kt * G::kTileKeys < k_end; ++kt) pv_tile(kt);
+            }
+            lds_barrier();        // (C) tiles and P^T free for the next block
+            if (blk0 == k_begin) RD_TR(2);
+        }
+    };
+    constexpr int kHalf = (NQ + 1) / 2;
+    if (NQ > 1 && nqt <= kHalf) block_loop(std::integral_constant<int, kHalf>{});
+    else block_loop(std::integral_constant<int, NQ>{});
+    RD_TR(3);
 
     // ---- partial state of this key range -> workspace ------------------------------------------
-    float *part = a.partials + ((size_t)bh * n_part + split) * ((size_t)a.rows_pad * (2 + D));
-    float *sL = sM;           // reuse: [4 waves][kRows]
+    // Layout of one partial: (m, l) pairs [kRows][2], then the output accumulators exactly as the
+    // lanes hold them, [wave][d-tile j][row tile qt][lane][4 floats], so that every wave store
+    // (and the merge's loads) covers 1 KB of contiguous memory.
+    float *part = a.partials + ((size_t)bh * n_part + split) * kPF;
+    const int frag_off = 2 * kRows + wave * kDTW * NQ * 256 + lane * 4;    // + (j*NQ + qt)*256
+    float *sL = sM;           // reuse: [NW waves][kRows]
 #pragma unroll
     for (int qt = 0; qt < NQ; ++qt) {
-        float l = l_run[qt];
-        l += __shfl_xor(l, 16, 64);
-        l += __shfl_xor(l, 32, 64);
-        if (g == 0) sL[wave * kRows + qt * 16 + r16] = l;
+        const float l = quad_sum(l_run[qt]);
+        if (g == 0) sL[(qt * 16 + r16) * NW + wave] = l;
     }
-    __syncthreads();
-    if (wave == 0) {
 #pragma unroll
-        for (int qt = 0; qt < NQ; ++qt) {
-            const int qrow = qt * 16 + r16;
-            if (g == 0 && qrow < P) {
-                part[qrow] = m_run[qt];
-                part[a.rows_pad + qrow] = sL[qrow] + sL[kRows + qrow] + sL[2 * kRows + qrow] + sL[3 * kRows + qrow];
+    for (int qt = 0; qt < NQ; ++qt) {
+        if (qt < nqt) {
+#pragma unroll
+            for (int j = 0; j < kDTW; ++j) {
+                const f32x4 o = oacc[j][qt];
+                st_dev4(part + frag_off + (j * NQ + qt) * 256, o[0], o[1], o[2], o[3]);
             }
         }
     }
+    lds_barrier();
+    if (wave == 0 && g == 0) {
 #pragma unroll
-    for (int qt = 0; qt < NQ; ++qt) {
-        const int qrow = qt * 16 + r16;
-        if (qrow < P) {
+        for (int qt = 0; qt < NQ; ++qt) {
+            const int qrow = qt * 16 + r16;
+            float lsum = sL[qrow * NW];
 #pragma unroll
-            for (int j = 0; j < G::kDTilesPerWave; ++j) {
-                const int d0 = (wave * G::kDTilesPerWave + j) * 16 + 4 * g;
-                const f32x4 o = oacc[j][qt];
-                *reinterpret_cast<float4 *>(part + 2 * a.rows_pad + (size_t)qrow * D + d0) =
-                    make_float4(o[0], o[1], o[2], o[3]);
-            }
+            for (int w = 1; w < NW; ++w) lsum += sL[qrow * NW + w];
+            st_dev2(part + 2 * qrow, m_run[qt], lsum);
         }
     }
 
     // ---- last workgroup of this (sequence, head) merges and writes the output ---------------------
-    if (arrive_is_last(a.counters + bh, (uint32_t)n_part)) {
-        combine_partials<D, __bf16>(a.partials + (size_t)bh * n_part * ((size_t)a.rows_pad * (2 + D)), n_part,
-                                    (size_t)a.rows_pad * (2 + D), a.rows_pad, P, a.N,
-                                    static_cast<__bf16 *>(a.out) + (size_t)bh * a.N * D);
-        if (tid == 0) a.counters[bh] = 0;     // leave the workspace ready for the next call
+    // With the XCD-aligned mapping every producer of this head ran on this XCD, so their
+    // write-through stores also updated this XCD's L2 and plain (cached, 16-byte) loads see them.
+    // Each workgroup checks the XCD it really runs on; if any of them was elsewhere, or the mapping
+    // is off, the merge reads with device-scope loads instead.
+    RD_TR(4);
+    const uint32_t off_xcd = (!a.xcd_remap || xcc_id() != (blockIdx.x & 7u)) ? 1u : 0u;
+    const int last = arrive_is_last(a.counters + bh, (uint32_t)n_part, off_xcd);
+    RD_TR(5);
+    if (last == kNotLast) return;
+    const bool cached = (last == kLastClean);
+#ifdef RD_TRACE
+    if (tid == 0 && rd_trace_buf) rd_trace_buf[(size_t)blockIdx.x * 16 + 13] = 1000 + last * 10 + xcc_id();
+#endif
+
+    // Merge: out[q] = sum_s 2^(m_s - M) O_s[q] / sum_s 2^(m_s - M) l_s[q], M = max_s m_s (log2
+    // units).  Each thread merges the accumulator fragments it would own itself, two row tiles at
+    // a time; the loads of up to kChunk partials for both are issued together, then consumed (the
+    // read of a head's partials by one compute unit is what this phase costs, so it should be a
+    // single round trip whenever the partials are few).
+    constexpr int kChunk = 6;
+    const float *hp = a.partials + (size_t)bh * n_part * kPF;
+    __bf16 *outp = static_cast<__bf16 *>(a.out) + (size_t)bh * a.N * D;
+    const int nqt_out = (a.N + 15) >> 4;
+#pragma unroll 1
+    for (int qt0 = 0; qt0 < nqt_out; qt0 += 2) {
+        float M[2], den[2];
+        f32x4 acc[2][kDTW];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            M[u] = -INFINITY;
+            den[u] = 0.f;
+#pragma unroll
+            for (int j = 0; j < kDTW; ++j) acc[u][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+        if (qt0 < nqt) {
+            const bool two = qt0 + 1 < nqt;                                     // uniform
+#pragma unroll 1
+            for (int s0 = 0; s0 < n_part; s0 += kChunk) {
+                float2 ml[2][kChunk];
+                f32x4 f[2][kChunk][kDTW];
+#pragma unroll
+                for (int c = 0; c < kChunk; ++c) {
+                    const bool have = s0 + c < n_part;                          // uniform
+                    const float *ps = hp + (size_t)(s0 + c) * kPF;
+#pragma unroll
+                    for (int u = 0; u < 2; ++u) {
+                        ml[u][c] = make_float2(-INFINITY, 0.f);                 // absent: weight 2^-inf = 0
+#pragma unroll
+                        for (int j = 0; j < kDTW; ++j) f[u][c][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+                        if (have && (u == 0 || two)) {
+                            const int qt = qt0 + u;
+                            const float *pm = ps + 2 * (qt * 16 + r16);
+                            const float *pf = ps + frag_off + qt * 256;
+                            if (cached) {
+                                ml[u][c] = *reinterpret_cast<const float2 *>(pm);
+#pragma unroll
+                                for (int j = 0; j < kDTW; ++j)
+                                    f[u][c][j] = *reinterpret_cast<const f32x4 *>(pf + j * NQ * 256);
+                            } else {
+                                ml[u][c] = ld_dev2(pm);
+#pragma unroll
+                                for (int j = 0; j < kDTW; ++j) {
+                                    const float2 lo = ld_dev2(pf + j * NQ * 256);
+                                    const float2 hi = ld_dev2(pf + j * NQ * 256 + 2);
+                                    f[u][c][j] = f32x4{lo.x, lo.y, hi.x, hi.y};
+                                }
+                            }
+                        }
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    float Mn = M[u];
+#pragma unroll
+                    for (int c = 0; c < kChunk; ++c) Mn = fmaxf(Mn, ml[u][c].x);
+                    const float Ms = (Mn == -INFINITY) ? 0.f : Mn;
+                    const float resc = __builtin_amdgcn_exp2f(M[u] - Ms);
+                    den[u] *= resc;
+#pragma unroll
+                    for (int j = 0; j < kDTW; ++j) acc[u][j] *= resc;
+#pragma unroll
+                    for (int c = 0; c < kChunk; ++c) {
+                        const float w = __builtin_amdgcn_exp2f(ml[u][c].x - Ms);     // 0 for an empty or absent range
+                        den[u] += w * ml[u][c].y;
+#pragma unroll
+                        for (int j = 0; j < kDTW; ++j) acc[u][j] += w * f[u][c][j];
+                    }
+                    M[u] = Mn;
+                }
+            }
+        }
+        if (qt0 == 0) RD_TR(7);
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int qrow = (qt0 + u) * 16 + r16;
+            if (qrow < a.N) {
+                const bool keep = qrow < P;                               // rows beyond the packed count are zero
+                const float inv = keep ? 1.0f / den[u] : 0.f;
+#pragma unroll
+                for (int j = 0; j < kDTW; ++j) {
+                    const int d0 = (wave * kDTW + j) * 16 + 4 * g;
+                    store_out4(outp + (size_t)qrow * D + d0, keep ? acc[u][j][0] * inv : 0.f, keep ? acc[u][j][1] * inv : 0.f,
+                               keep ? acc[u][j][2] * inv : 0.f, keep ? acc[u][j][3] * inv : 0.f);
+                }
+            }
+        }
     }
+    if (tid == 0) a.counters[bh] = 0;     // leave the workspace ready for the next call
+    RD_TR(6);
 }
 
-template <int D, int NQ>
+template <int D, int NQ, int NW>
 static size_t bf16_smem_bytes()
 {
-    return (size_t)NQ * 16 * Geo<D>::kRowBytes + 4 * Geo<D>::kTileBytes + (size_t)4 * NQ * 64 * 16 +
-           (size_t)4 * NQ * 16 * sizeof(float);
+    return (size_t)NQ * 16 * Geo<D>::kRowBytes + NW * Geo<D>::kTileBytes + (size_t)NW * NQ * 64 * 16 +
+           (size_t)NW * NQ * 16 * sizeof(float);
 }
 
-template <int D, int NQ>
+template <int D, int NQ, int NW>
 static int launch_bf16(const AttnArgs &a, hipStream_t stream)
 {
-    const size_t smem = bf16_smem_bytes<D, NQ>();
+    const size_t smem = bf16_smem_bytes<D, NQ, NW>();
     static bool configured = false;          // raising the dynamic LDS limit is per kernel, once
     if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&rd_tree_attn_bf16_kernel<D, NQ>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&rd_tree_attn_bf16_kernel<D, NQ, NW>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
             return RD_ERR_HIP;
         configured = true;
     }
     const unsigned grid = (unsigned)((size_t)a.B * a.H * (a.S + 1));
-    hipLaunchKernelGGL((rd_tree_attn_bf16_kernel<D, NQ>), dim3(grid), dim3(kAttnThreads), smem, stream, a);
+    hipLaunchKernelGGL((rd_tree_attn_bf16_kernel<D, NQ, NW>), dim3(grid), dim3(NW * 64), smem, stream, a);
     return rd_check_launch();
 }
 
-template <int D>
+template <int D, int NW>
 static int dispatch_nq(const AttnArgs &a, hipStream_t stream)
 {
     switch ((a.N + 15) / 16) {
-    case 1: return launch_bf16<D, 1>(a, stream);
-    case 2: return launch_bf16<D, 2>(a, stream);
-    case 3: return launch_bf16<D, 3>(a, stream);
-    case 4: return launch_bf16<D, 4>(a, stream);
-    case 5: return launch_bf16<D, 5>(a, stream);
-    case 6: return launch_bf16<D, 6>(a, stream);
-    case 7: return launch_bf16<D, 7>(a, stream);
-    case 8: return launch_bf16<D, 8>(a, stream);
-    default: return RD_ERR_UNSUPPORTED;
+    case 1: return launch_bf16<D, 1, NW>(a, stream);
+    case 2: return launch_bf16<D, 2, NW>(a, stream);
+    case 3: return launch_bf16<D, 3, NW>(a, stream);
+    case 4: return launch_bf16<D, 4, NW>(a, stream);
+    case 5: return launch_bf16<D, 5, NW>(a, stream);
+    default: break;
     }
+    if constexpr (NW == 4) {
+        switch ((a.N + 15) / 16) {
+        case 6: return launch_bf16<D, 6, 4>(a, stream);
+        case 7: return launch_bf16<D, 7, 4>(a, stream);
+        case 8: return launch_bf16<D, 8, 4>(a, stream);
+        default: break;
+        }
+    }
+    return RD_ERR_UNSUPPORTED;
 }
 
-int tree_attn_bf16(const AttnArgs &a, int D, hipStream_t stream)
+int tree_attn_bf16(const AttnArgs &a, int D, int waves, hipStream_t stream)
 {
-    return D == 128 ? dispatch_nq<128>(a, stream) : dispatch_nq<64>(a, stream);
+    if (D == 128) return waves == 8 ? dispatch_nq<128, 8>(a, stream) : dispatch_nq<128, 4>(a, stream);
+    return dispatch_nq<64, 4>(a, stream);
 }
 
 }  // namespace rd

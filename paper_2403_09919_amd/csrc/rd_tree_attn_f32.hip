@@ -46,7 +46,7 @@ __global__ __launch_bounds__(kAttnThreads) void rd_tree_attn_f32_kernel(AttnArgs
         Kb = static_cast<const float *>(a.k_new) + (size_t)bh * a.N * D;
         Vb = static_cast<const float *>(a.v_new) + (size_t)bh * a.N * D;
     } else {
-        ctx_range(C, a.S, split, &k_begin, &k_end);
+        ctx_range(C, a.S, split, kBlockKeys, &k_begin, &k_end);
         Kb = static_cast<const float *>(a.k_cache) + (size_t)bh * a.Cmax * D;
         Vb = static_cast<const float *>(a.v_cache) + (size_t)bh * a.Cmax * D;
     }
@@ -60,16 +60,16 @@ __global__ __launch_bounds__(kAttnThreads) void rd_tree_attn_f32_kernel(AttnArgs
         }
     }
 
-    uint64_t mw[4][2];
+    uint64_t mlo[4], mhi[4];             // tree-mask words 0 and 1 of this wave's four rows
     float m_run[4], l_run[4], o[4][kCols];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int qrow = row0 + wave * 4 + r;
-        mw[r][0] = mw[r][1] = 0;
+        mlo[r] = mhi[r] = 0;
         if (is_tree && qrow < P) {
             const uint64_t *mrow = a.mask_bits + ((size_t)b * a.N + qrow) * a.words;
-            mw[r][0] = mrow[0];
-            if (a.words > 1) mw[r][1] = mrow[1];
+            mlo[r] = mrow[0];
+            if (a.words > 1) mhi[r] = mrow[1];
         }
         m_run[r] = -INFINITY;
         l_run[r] = 0.f;
@@ -110,7 +110,7 @@ __global__ __launch_bounds__(kAttnThreads) void rd_tree_attn_f32_kernel(AttnArgs
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             bool ok = key < k_end;
-            if (is_tree) ok = ok && ((((key & 64) ? mw[r][1] : mw[r][0]) >> (key & 63)) & 1ull);
+            if (is_tree) ok = ok && (((t0 ? mhi[r] : mlo[r]) >> lane) & 1ull);   // packed keys: t0 is 0 or 64
             const float sv = ok ? s[r] * a.scale_log2e : -INFINITY;
             float tmax = sv;
 #pragma unroll
@@ -152,15 +152,15 @@ __global__ __launch_bounds__(kAttnThreads) void rd_tree_attn_f32_kernel(AttnArgs
         const int qrow = row0 + wave * 4 + r;
         if (qrow < P) {
             if (lane == 0) {
-                part[qrow] = m_run[r];
-                part[a.rows_pad + qrow] = l_run[r];
+                st_dev(part + qrow, m_run[r]);
+                st_dev(part + a.rows_pad + qrow, l_run[r]);
             }
 #pragma unroll
-            for (int c = 0; c < kCols; ++c) part[2 * a.rows_pad + (size_t)qrow * D + c * 64 + lane] = o[r][c];
+            for (int c = 0; c < kCols; ++c) st_dev(part + 2 * a.rows_pad + (size_t)qrow * D + c * 64 + lane, o[r][c]);
         }
     }
 
-    if (arrive_is_last(a.counters + bh, (uint32_t)(n_part * row_groups))) {
+    if (arrive_is_last(a.counters + bh, (uint32_t)(n_part * row_groups)) != kNotLast) {
         combine_partials<D, float>(a.partials + (size_t)bh * n_part * pf, n_part, pf, a.rows_pad, P, a.N,
                                    static_cast<float *>(a.out) + (size_t)bh * a.N * D);
         if (tid == 0) a.counters[bh] = 0;

@@ -174,3 +174,48 @@ def test_whole_path_chained_on_device(rd):
     assert np.array_equal(host(acc["argmax"]), ref["argmax"])
     for k in ("n_accept", "best_beam", "best_len", "next_token", "accepted_idx"):
         assert np.array_equal(host(acc[k]), ref[k]), k
+
+
+def test_graph_replay_matches_eager(rd):
+    """The library only enqueues kernels, so a caller may capture a step into a HIP graph.
+    Replays (with eager work and synchronisations in between) must reproduce the eager result."""
+    announce("whole path captured in a HIP graph, 3 replays")
+    t = make_case(2, 4, 128, 8, 5, [300, 1000], "bf16", seed=17, poison=False)
+    B, W, L, H, D, N, V = 2, 8, 5, 4, 128, 40, 2000
+    dref = oracle.dedup(t["beams"], t["ctx_len"])
+    logits = synth.make_logits(B, N, V, 17, dref["packed_tokens"], dref["parent"], dref["n_packed"], 0.7)
+    td = {k: dev(v) for k, v in t.items()}
+    lg = dev(logits)
+    ws_a = rd.new_workspace(rd.rd_tree_attn_workspace(B, H, N, D, 1000, rd.RD_BF16), "cuda")
+    ws_c = rd.new_workspace(rd.rd_accept_workspace(B, W, L, V), "cuda")
+    state = {}
+
+    def step():
+        state["d"] = rd.rd_dedup(td["beams"], td["ctx_len"], out=state.get("d"))
+        d = state["d"]
+        state["o"] = rd.rd_tree_attn(td["q"], td["k_cache"], td["v_cache"], td["ctx_len"], td["k_new"], td["v_new"],
+                                     d["n_packed"], d["tree_mask_bits"], 0.09, out=state.get("o"), workspace=ws_a)
+        state["a"] = rd.rd_accept(lg, td["beams"], d["unpack_index"], d["n_packed"], out=state.get("a"), workspace=ws_c)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        s = {k: host(v) for k, v in state["d"].items()}
+        s["o"] = host(state["o"])
+        s.update({"acc_" + k: host(v) for k, v in state["a"].items()})
+        return s
+
+    step()
+    eager = snapshot()
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        with torch.cuda.graph(graph, stream=stream):
+            step()
+    for rep in range(3):
+        for v in list(state["d"].values()) + [state["o"]] + list(state["a"].values()):
+            v.fill_(0) if v.dtype != torch.bfloat16 else v.zero_()      # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        got = snapshot()
+        for k in eager:
+            assert np.array_equal(got[k], eager[k]), (rep, k)
