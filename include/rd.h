@@ -101,10 +101,12 @@ int rd_dedup(const int32_t *beams, const int32_t *ctx_len, int B, int W, int L,
  *   Cmax >= 0 (k_cache/v_cache may be NULL when Cmax == 0).
  *
  * workspace: device scratch of at least rd_tree_attn_workspace(...) bytes, 256-byte
- * aligned.  It holds per-split partial results and completion counters.  The counters
- * must be zero before the first call that uses a workspace (hipMemsetAsync it once);
- * every call leaves them zero again, so a workspace can be reused by successive calls
- * on one stream without clearing.  Concurrent calls need separate workspaces.
+ * aligned.  It holds per-split partial results and completion counters.  The workspace
+ * must be all zero before the first call that uses it (hipMemsetAsync it once); every
+ * call leaves the counters zero again, so successive calls WITH THE SAME SHAPE ARGUMENTS
+ * on one stream can reuse it without clearing.  Its layout depends on the shape: clear it
+ * again before using it with other shape arguments.  Concurrent calls need separate
+ * workspaces.  If a call fails or is aborted, clear the workspace before reusing it.
  */
 size_t rd_tree_attn_workspace(int B, int H, int N, int D, int Cmax, rd_dtype dt);
 
@@ -136,7 +138,8 @@ int rd_tree_attn(const void *q, const void *k_cache, const void *v_cache,
  * accepted_idx [B,L].  logits must be 16-byte aligned.
  *
  * workspace: as for rd_tree_attn (at least rd_accept_workspace(...) bytes, 256-byte
- * aligned, counters zero before first use, left zero by every call).
+ * aligned, all zero before first use, counters left zero by every call, tied to the
+ * shape arguments).
  */
 size_t rd_accept_workspace(int B, int W, int L, int V);
 

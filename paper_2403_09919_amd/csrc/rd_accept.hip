@@ -1,13 +1,18 @@
 // rd_accept: greedy verification (Sec. 3.4, Fig. 2) for gfx950 in one launch.
 //
 // Phase 1 (all workgroups): the valid logit rows (p < n_packed[b]) are cut into chunks of
-// a few thousand floats; a workgroup streams one chunk with 16-byte loads and reduces it to
-// (max value, smallest index attaining it), which it stores in the workspace.  This phase
-// is a pure HBM stream over the valid logits.
-// Phase 2 (the workgroup that finishes last for a sequence, found with a device-scope
-// counter): reduces the chunk results of every row to the row's arg max, then wave 0 runs
-// the per-candidate prefix match with lane w = candidate w, picks the best candidate with a
+// a few thousand floats; a workgroup streams one chunk with 16-byte loads, reduces it to
+// (max value, smallest index attaining it) and folds that into the row's 64-bit key in the
+// workspace with one device-scope atomic max.  The key orders (value, -index), so the row's
+// final key is its arg max with the smallest-index tie rule.  This phase is a pure HBM stream
+// over the valid logits.
+// Phase 2 (the workgroup that completes a sequence, found with a per-row and then a
+// per-sequence counter): decodes the row keys, writes the arg maxes, and wave 0 runs the
+// per-candidate prefix match with lane w = candidate w, picks the best candidate with a
 // wave-wide max on (length, -w) and writes the accepted slots and the next token.
+// Two counter levels keep the number of atomics that hit one address small (chunks per row,
+// rows per sequence); hundreds of increments of a single word would serialise and cost more
+// than the stream itself.
 #include "rd_internal.h"
 
 namespace {
@@ -18,8 +23,8 @@ constexpr int kMaxChunks = 64;
 struct AccPlan {
     int chunks;       // chunks per logit row
     int chunk_len;    // floats per chunk (multiple of 4)
-    size_t counters_bytes;
-    size_t total_bytes;
+    size_t row_counters_off, keys_off;   // byte offsets in the workspace (sequence counters at 0)
+    size_t total_bytes;                  // all of it must be zero between calls (and is left so)
 };
 
 AccPlan acc_plan(int B, int N, int V)
@@ -32,8 +37,10 @@ AccPlan acc_plan(int B, int N, int V)
     len = (len + 3) / 4 * 4;
     p.chunk_len = len;
     p.chunks = (V + len - 1) / len;
-    p.counters_bytes = ((size_t)B * sizeof(uint32_t) + 255) / 256 * 256;
-    p.total_bytes = p.counters_bytes + (size_t)B * N * p.chunks * sizeof(unsigned long long);
+    auto up = [](size_t x) { return (x + 255) / 256 * 256; };
+    p.row_counters_off = up((size_t)B * sizeof(uint32_t));
+    p.keys_off = p.row_counters_off + up((size_t)B * N * sizeof(uint32_t));
+    p.total_bytes = p.keys_off + up((size_t)B * N * sizeof(unsigned long long));
     return p;
 }
 
@@ -43,18 +50,38 @@ __device__ __forceinline__ bool better(float v, int i, float bv, int bi)
     return v > bv || (v == bv && i < bi);
 }
 
+// Order-preserving 64-bit key of (value, index): larger value first, then smaller index.
+// Every key of a real element is greater than 0, the cleared state of the workspace.
+__device__ __forceinline__ unsigned long long encode_key(float v, int i)
+{
+    const uint32_t u = __float_as_uint(v);
+    const uint32_t mono = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+    return ((unsigned long long)mono << 32) | (uint32_t)~(uint32_t)i;
+}
+__device__ __forceinline__ int key_index(unsigned long long k) { return (int)~(uint32_t)k; }
+
+// Device-scope arrival: true for the thread whose increment brought the counter to `expected`.
+__device__ __forceinline__ bool arrive(uint32_t *counter, uint32_t expected)
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");          // own atomics and stores acknowledged
+    const uint32_t prev = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    return prev + 1u == expected;
+}
+
 __global__ __launch_bounds__(kAccThreads) void rd_accept_kernel(
     const float *__restrict__ logits, const int32_t *__restrict__ beams,
     const int32_t *__restrict__ unpack_index, const int32_t *__restrict__ n_packed,
     const int32_t *__restrict__ root_token, int W, int L, int V, int chunks, int chunk_len,
     int32_t *__restrict__ argmax_out, int32_t *__restrict__ n_accept, int32_t *__restrict__ best_beam,
     int32_t *__restrict__ best_len, int32_t *__restrict__ next_token, int32_t *__restrict__ accepted_idx,
-    uint32_t *counters, unsigned long long *partial)
+    uint32_t *seq_counters, uint32_t *row_counters, unsigned long long *row_keys)
 {
     __shared__ float s_val[kAccThreads / 64];
     __shared__ int s_idx[kAccThreads / 64];
     __shared__ int s_am[RD_MAX_N];
-    __shared__ uint32_t s_last;
+    __shared__ int s_beam[RD_MAX_N], s_slot[RD_MAX_N];
+    __shared__ uint32_t s_seq_last;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int chunk = blockIdx.x, p = blockIdx.y, b = blockIdx.z;
@@ -63,7 +90,18 @@ __global__ __launch_bounds__(kAccThreads) void rd_accept_kernel(
     P = P < 1 ? 1 : (P > N ? N : P);
     if (p >= P) return;                                   // whole workgroup: row is padding
 
-    // ---- phase 1: this chunk's (max, first index) ------------------------------------------------
+    // The candidates and their slots are only needed by the workgroup that ends up finishing the
+    // sequence, but nobody knows which one that is: every workgroup fetches them now (a few
+    // hundred bytes, overlapped with the logit stream) instead of paying two dependent round
+    // trips to memory per accepted token at the very end.
+    int my_beam = 0, my_slot = 0, my_root = 0;
+    if (tid < N) {
+        my_beam = beams[(size_t)b * N + tid];
+        my_slot = unpack_index[(size_t)b * N + tid];
+    }
+    if (root_token != nullptr) my_root = root_token[b];
+
+    // ---- phase 1: this chunk's (max, first index) -> the row's key ---------------------------------
     const float *row = logits + ((size_t)b * N + p) * V;
     const int v0 = chunk * chunk_len;
     const int v1 = min(V, v0 + chunk_len);
@@ -91,58 +129,51 @@ __global__ __launch_bounds__(kAccThreads) void rd_accept_kernel(
     }
     if (lane == 0) { s_val[wave] = bv; s_idx[wave] = bi; }
     __syncthreads();
+    const size_t rowid = (size_t)b * N + p;
     if (tid == 0) {
         for (int w = 1; w < kAccThreads / 64; ++w)
             if (better(s_val[w], s_idx[w], bv, bi)) { bv = s_val[w]; bi = s_idx[w]; }
-        // The chunk result crosses workgroups (possibly XCDs, each with its own L2): store and
-        // later load it with device-scope accesses and wait for the store before the counter
-        // moves; a device-wide fence per workgroup would flush whole L2s and dominate the kernel.
-        const unsigned long long packed = (unsigned long long)__float_as_uint(bv) | ((unsigned long long)(uint32_t)bi << 32);
-        __hip_atomic_store(partial + ((size_t)b * N + p) * chunks + chunk, packed, __ATOMIC_RELAXED,
-                           __HIP_MEMORY_SCOPE_AGENT);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        const uint32_t prev = __hip_atomic_fetch_add(counters + b, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        s_last = (prev == (uint32_t)(P * chunks) - 1u) ? 1u : 0u;
+        uint32_t last = 0;
+        if (bi != 0x7fffffff)                               // (an empty chunk cannot occur, but would add nothing)
+            __hip_atomic_fetch_max(row_keys + rowid, encode_key(bv, bi), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (arrive(row_counters + rowid, (uint32_t)chunks)) {        // this row is complete
+            row_counters[rowid] = 0;                                   // ready for the next call
+            last = arrive(seq_counters + b, (uint32_t)P) ? 1u : 0u;    // ... and so is the sequence
+        }
+        s_seq_last = last;
     }
     __syncthreads();
-    if (!s_last) return;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    if (!s_seq_last) return;
 
-    // ---- phase 2: row arg max, then token matching ---------------------------------------------------
+    // ---- phase 2 (last workgroup of the sequence): arg maxes, then token matching -----------------------
     for (int r = tid; r < N; r += kAccThreads) {
         int am = -1;
         if (r < P) {
-            const unsigned long long *pr = partial + ((size_t)b * N + r) * chunks;
-            float rv = -INFINITY;
-            int ri = 0x7fffffff;
-            for (int c = 0; c < chunks; ++c) {
-                const unsigned long long x = __hip_atomic_load(pr + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                const float xv = __uint_as_float((uint32_t)x);
-                const int xi = (int)(uint32_t)(x >> 32);
-                if (better(xv, xi, rv, ri)) { rv = xv; ri = xi; }
-            }
-            am = ri;
+            const unsigned long long *kp = row_keys + (size_t)b * N + r;
+            am = key_index(__hip_atomic_load(kp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
         }
         s_am[r] = am;
         argmax_out[(size_t)b * N + r] = am;
     }
-    __syncthreads();
-    if (tid == 0) counters[b] = 0;                        // workspace ready for the next call
+    if (tid < N) {
+        s_beam[tid] = my_beam;
+        s_slot[tid] = min(max(my_slot, 0), N - 1);
+    }
+    __syncthreads();                                      // every key has been read
+    for (int r = tid; r < P; r += kAccThreads) row_keys[(size_t)b * N + r] = 0;   // ready for the next call
+    if (tid == 0) seq_counters[b] = 0;
     if (wave != 0) return;
 
     const int w = lane;
     int len = 0;
     if (w < W) {
-        const int32_t *bm = beams + ((size_t)b * W + w) * L;
-        const int32_t *ui = unpack_index + ((size_t)b * W + w) * L;
-        bool ok = (root_token == nullptr) || (bm[0] == root_token[b]);
-        int prev_slot = ui[0];
+        const int *bm = s_beam + w * L;
+        const int *ui = s_slot + w * L;
+        bool ok = (root_token == nullptr) || (bm[0] == my_root);
         while (ok) {
             ++len;
             if (len == L) break;
-            const int slot = min(max(prev_slot, 0), N - 1);
-            ok = (s_am[slot] == bm[len]);
-            prev_slot = ui[len];
+            ok = (s_am[ui[len - 1]] == bm[len]);
         }
         n_accept[(size_t)b * W + w] = len;
     }
@@ -152,12 +183,12 @@ __global__ __launch_bounds__(kAccThreads) void rd_accept_kernel(
     for (int off = 32; off > 0; off >>= 1) key = max(key, __shfl_xor(key, off, 64));
     const int bl = key >> 8;
     const int bw = 255 - (key & 255);
-    const int32_t *bui = unpack_index + ((size_t)b * W + bw) * L;
+    const int *bui = s_slot + bw * L;
     for (int t = lane; t < L; t += 64) accepted_idx[(size_t)b * L + t] = (t < bl) ? bui[t] : -1;
     if (lane == 0) {
         best_beam[b] = bw;
         best_len[b] = bl;
-        next_token[b] = (bl > 0) ? s_am[min(max(bui[bl - 1], 0), N - 1)] : root_token[b];
+        next_token[b] = (bl > 0) ? s_am[bui[bl - 1]] : my_root;
     }
 }
 
@@ -187,10 +218,11 @@ extern "C" int rd_accept(const float *logits, const int32_t *beams, const int32_
     const int N = W * L;
     const AccPlan plan = acc_plan(B, N, V);
     if (!workspace || !rd_aligned(workspace, 256) || workspace_bytes < plan.total_bytes) return RD_ERR_WORKSPACE;
-    uint32_t *counters = static_cast<uint32_t *>(workspace);
-    unsigned long long *partial = reinterpret_cast<unsigned long long *>(static_cast<unsigned char *>(workspace) + plan.counters_bytes);
+    unsigned char *ws = static_cast<unsigned char *>(workspace);
     hipLaunchKernelGGL(rd_accept_kernel, dim3(plan.chunks, N, B), dim3(kAccThreads), 0, (hipStream_t)stream,
                        logits, beams, unpack_index, n_packed, root_token, W, L, V, plan.chunks, plan.chunk_len,
-                       argmax_out, n_accept, best_beam, best_len, next_token, accepted_idx, counters, partial);
+                       argmax_out, n_accept, best_beam, best_len, next_token, accepted_idx,
+                       reinterpret_cast<uint32_t *>(ws), reinterpret_cast<uint32_t *>(ws + plan.row_counters_off),
+                       reinterpret_cast<unsigned long long *>(ws + plan.keys_off));
     return rd_check_launch();
 }

@@ -48,6 +48,7 @@ __global__ __launch_bounds__(kDedupThreads) void rd_dedup_kernel(
     const int N = W * L;
     const int words = (N + 63) >> 6;
     const size_t seq = (size_t)b * N;
+    const int ctx = ctx_len ? ctx_len[b] : 0;      // fetched with the candidates, not after them
 
     for (int i = tid; i < N; i += kDedupThreads) {
         s_beam[i] = beams[seq + i];
@@ -60,7 +61,6 @@ __global__ __launch_bounds__(kDedupThreads) void rd_dedup_kernel(
         const int lane = tid;
         const bool active = lane < W;
         const int row = active ? lane : 0;          // idle lanes shadow candidate 0, write nothing
-        const int ctx = ctx_len ? ctx_len[b] : 0;
 
         uint64_t alive = (W == 64) ? ~0ull : ((1ull << W) - 1ull);
         int first_kept = L;
@@ -68,9 +68,9 @@ __global__ __launch_bounds__(kDedupThreads) void rd_dedup_kernel(
             const int tok = s_beam[row * L + j];
             uint64_t same = 0;
             for (int k = 0; k < W; ++k) {
-                const int tk = __shfl(tok, k, RD_WAVE);
-                const uint64_t eq = __ballot(tok == tk);   // lanes whose token equals candidate k's
-                if (lane == k) same = eq;
+                const int tk = __builtin_amdgcn_readlane(tok, k);               // candidate k's token (k is uniform)
+                const uint64_t eq = __builtin_amdgcn_ballot_w64(tok == tk);     // lanes whose token equals it
+                same = (lane == k) ? eq : same;
             }
             alive &= same;
             const int owner = __ffsll((unsigned long long)alive) - 1;   // >= 0: the lane itself is in alive

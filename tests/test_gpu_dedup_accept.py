@@ -123,16 +123,18 @@ def test_accept_vocab_sizes_and_ties(rd, V):
 
 
 def test_accept_shapes_and_workspace_reuse(rd):
-    announce("accept shapes + one workspace reused by successive calls")
-    ws = rd.new_workspace(rd.rd_accept_workspace(16, 64, 2, 5000), "cuda")
+    announce("accept shapes + one workspace reused by successive calls of the same shape")
+    up = lambda x: (x + 255) // 256 * 256
     for (B, W, L, V, seed) in [(1, 1, 1, 10, 0), (2, 1, 9, 300, 1), (4, 64, 2, 5000, 2), (16, 16, 5, 640, 3),
                                (3, 25, 5, 1200, 4), (2, 2, 64, 100, 5)]:
-        beams = synth.make_beams(B, W, L, 4, seed, "high")
-        d = oracle.dedup(beams)
-        logits = synth.make_logits(B, W * L, V, seed, d["packed_tokens"], d["parent"], d["n_packed"], 0.8, 6.0)
-        check_accept(rd, logits, beams, None, ws)
-        check_accept(rd, logits, beams, beams[:, 0, 0].copy(), ws)
-    assert int(ws[:256].sum()) == 0                        # counters are left at zero
+        ws = rd.new_workspace(rd.rd_accept_workspace(B, W, L, V), "cuda")
+        for rep in range(3):
+            beams = synth.make_beams(B, W, L, 4, seed + 10 * rep, "high")
+            d = oracle.dedup(beams)
+            logits = synth.make_logits(B, W * L, V, seed + rep, d["packed_tokens"], d["parent"], d["n_packed"], 0.8, 6.0)
+            check_accept(rd, logits, beams, None, ws)
+            check_accept(rd, logits, beams, beams[:, 0, 0].copy(), ws)
+            assert int(ws.sum()) == 0                      # counters and row keys are left at zero
 
 
 def test_accept_full_and_none(rd):
