@@ -15,6 +15,8 @@
 // than the stream itself.
 #include "rd_internal.h"
 
+RD_TRACE_DEFINE(rd_debug_set_trace_accept)
+
 namespace {
 
 constexpr int kAccThreads = 256;
@@ -89,6 +91,7 @@ __global__ __launch_bounds__(kAccThreads) void rd_accept_kernel(
     int P = n_packed[b];
     P = P < 1 ? 1 : (P > N ? N : P);
     if (p >= P) return;                                   // whole workgroup: row is padding
+    RD_TR(0);
 
     // The candidates and their slots are only needed by the workgroup that ends up finishing the
     // sequence, but nobody knows which one that is: every workgroup fetches them now (a few
@@ -127,6 +130,7 @@ __global__ __launch_bounds__(kAccThreads) void rd_accept_kernel(
         const int oi = __shfl_xor(bi, off, 64);
         if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
     }
+    RD_TR(1);
     if (lane == 0) { s_val[wave] = bv; s_idx[wave] = bi; }
     __syncthreads();
     const size_t rowid = (size_t)b * N + p;
@@ -142,8 +146,10 @@ __global__ __launch_bounds__(kAccThreads) void rd_accept_kernel(
         }
         s_seq_last = last;
     }
+    RD_TR(2);
     __syncthreads();
     if (!s_seq_last) return;
+    RD_TR(3);
 
     // ---- phase 2 (last workgroup of the sequence): arg maxes, then token matching -----------------------
     for (int r = tid; r < N; r += kAccThreads) {
@@ -160,6 +166,7 @@ __global__ __launch_bounds__(kAccThreads) void rd_accept_kernel(
         s_slot[tid] = min(max(my_slot, 0), N - 1);
     }
     __syncthreads();                                      // every key has been read
+    RD_TR(4);
     for (int r = tid; r < P; r += kAccThreads) row_keys[(size_t)b * N + r] = 0;   // ready for the next call
     if (tid == 0) seq_counters[b] = 0;
     if (wave != 0) return;
@@ -190,6 +197,7 @@ __global__ __launch_bounds__(kAccThreads) void rd_accept_kernel(
         best_len[b] = bl;
         next_token[b] = (bl > 0) ? s_am[bui[bl - 1]] : my_root;
     }
+    RD_TR(5);
 }
 
 }  // namespace

@@ -1,35 +1,27 @@
 // rd_dedup: dynamic tree attention construction (Sec. 3.3, App. A.1) for gfx950.
 //
-// One workgroup per sequence.  Wave 0 does the whole prefix analysis with lane i
-// owning candidate i (W <= 64):
-//   * the lane keeps a 64-bit set `alive` of the candidates whose prefix so far
-//     equals its own; at position j it is intersected with the ballot of lanes
-//     holding the same token.  prefix_tree[i][j] is the lowest set bit.  This is the
-//     equal-length property the paper exploits: no trie, no data-dependent walks.
-//   * a token is kept iff its lane is that lowest bit; kept tokens of a lane are a
-//     suffix of its row, so a lane's kept count is L - first_kept and one wave
-//     exclusive scan gives every lane its first packed slot (row-major slot order).
-//   * a second sweep over j turns (owner, j) into slots and carries the ancestor
-//     bit set along the row, which is the tree-mask row of every kept token.
-// The mask rows are staged in LDS; all four waves then write the dense and the
-// bit-packed masks and the paddings with coalesced stores.
+// One workgroup per sequence, everything in LDS, data-parallel phases separated by barriers
+// (the whole input is a few hundred bytes; what costs time is dependent latency, so no phase
+// is a serial walk over positions):
+//   A  stage the W x L candidates; owner[i][j] = i.
+//   B  one thread per ordered pair (i, k < i): walk their common prefix and lower owner[i][j]
+//      to k (LDS atomic min) for every j inside it.  Afterwards owner[i][j] is the smallest
+//      candidate sharing i's first j+1 tokens, i.e. prefix_tree — the equal-length property
+//      the paper exploits, with no trie and no data-dependent pointer chasing.
+//   C  a token is kept iff owner == i; kept tokens of a candidate are a suffix of its row, so
+//      each row's first kept position and a prefix sum of the kept counts give every row
+//      its first packed slot (row-major slot order).
+//   D  one thread per token: slot of its owner's copy -> unpack_index.
+//   E  one thread per kept token: packed token, parent, position id, and the mask row as the
+//      OR of the slots on its path.
+//   F  paddings, the bit-packed and the dense mask, with coalesced stores.
 #include "rd_internal.h"
+
+RD_TRACE_DEFINE(rd_debug_set_trace_dedup)
 
 namespace {
 
 constexpr int kDedupThreads = 256;
-
-__device__ __forceinline__ int wave_excl_scan(int v, int lane, int *total)
-{
-    int incl = v;
-#pragma unroll
-    for (int off = 1; off < RD_WAVE; off <<= 1) {
-        const int up = __shfl_up(incl, off, RD_WAVE);
-        if (lane >= off) incl += up;
-    }
-    *total = __shfl(incl, RD_WAVE - 1, RD_WAVE);
-    return incl - v;
-}
 
 __global__ __launch_bounds__(kDedupThreads) void rd_dedup_kernel(
     const int32_t *__restrict__ beams, const int32_t *__restrict__ ctx_len, int W, int L,
@@ -40,6 +32,8 @@ __global__ __launch_bounds__(kDedupThreads) void rd_dedup_kernel(
 {
     __shared__ int32_t s_beam[RD_MAX_N];
     __shared__ int32_t s_owner[RD_MAX_N];          // prefix_tree of this sequence
+    __shared__ int32_t s_slot[RD_MAX_N];           // unpack_index of this sequence
+    __shared__ int32_t s_base[RD_MAX_W + 1], s_first[RD_MAX_W + 1];
     __shared__ uint64_t s_bits[RD_MAX_N][2];       // mask row of each packed slot
     __shared__ int s_P;
 
@@ -48,64 +42,78 @@ __global__ __launch_bounds__(kDedupThreads) void rd_dedup_kernel(
     const int N = W * L;
     const int words = (N + 63) >> 6;
     const size_t seq = (size_t)b * N;
+    RD_TR(0);
     const int ctx = ctx_len ? ctx_len[b] : 0;      // fetched with the candidates, not after them
 
+    // ---- A: stage -----------------------------------------------------------------------------------
     for (int i = tid; i < N; i += kDedupThreads) {
         s_beam[i] = beams[seq + i];
+        s_owner[i] = i / L;
         s_bits[i][0] = 0;
         s_bits[i][1] = 0;
     }
+    if (tid < W) s_first[tid] = L;
     __syncthreads();
+    RD_TR(1);
 
-    if (tid < RD_WAVE) {
-        const int lane = tid;
-        const bool active = lane < W;
-        const int row = active ? lane : 0;          // idle lanes shadow candidate 0, write nothing
-
-        uint64_t alive = (W == 64) ? ~0ull : ((1ull << W) - 1ull);
-        int first_kept = L;
-        for (int j = 0; j < L; ++j) {
-            const int tok = s_beam[row * L + j];
-            uint64_t same = 0;
-            for (int k = 0; k < W; ++k) {
-                const int tk = __builtin_amdgcn_readlane(tok, k);               // candidate k's token (k is uniform)
-                const uint64_t eq = __builtin_amdgcn_ballot_w64(tok == tk);     // lanes whose token equals it
-                same = (lane == k) ? eq : same;
-            }
-            alive &= same;
-            const int owner = __ffsll((unsigned long long)alive) - 1;   // >= 0: the lane itself is in alive
-            if (active) {
-                s_owner[lane * L + j] = owner;
-                if (owner == lane && first_kept == L) first_kept = j;
-            }
-        }
-        int P;
-        const int base = wave_excl_scan(active ? L - first_kept : 0, lane, &P);
-        if (lane == 0) { s_P = P; n_packed[b] = P; }
-
-        uint64_t anc0 = 0, anc1 = 0;                // slots on the path from the root to (lane, j)
-        int prev = -1;
-        for (int j = 0; j < L; ++j) {
-            const int owner = active ? s_owner[lane * L + j] : 0;
-            // (owner, j) is a kept token: j >= first_kept[owner]
-            const int slot = __shfl(base, owner, RD_WAVE) + j - __shfl(first_kept, owner, RD_WAVE);
-            if (slot < 64) anc0 |= 1ull << slot; else anc1 |= 1ull << (slot - 64);
-            if (active) {
-                unpack_index[seq + lane * L + j] = slot;
-                if (prefix_tree) prefix_tree[seq + lane * L + j] = owner;
-                if (owner == lane) {
-                    packed_tokens[seq + slot] = s_beam[lane * L + j];
-                    parent[seq + slot] = prev;
-                    position_ids[seq + slot] = ctx + j;
-                    s_bits[slot][0] = anc0;
-                    s_bits[slot][1] = anc1;
-                }
-            }
-            prev = slot;
+    // ---- B: common prefixes of all pairs ----------------------------------------------------------------
+    for (int pr = tid; pr < W * W; pr += kDedupThreads) {
+        const int i = pr / W, k = pr % W;
+        if (k < i) {
+            for (int j = 0; j < L && s_beam[i * L + j] == s_beam[k * L + j]; ++j) atomicMin(&s_owner[i * L + j], k);
         }
     }
     __syncthreads();
+    RD_TR(2);
 
+    // ---- C: first kept position per row (kept tokens are a suffix of their row) ---------------------------
+    for (int e = tid; e < N; e += kDedupThreads) {
+        const int i = e / L;
+        if (s_owner[e] == i) atomicMin(&s_first[i], e % L);
+    }
+    __syncthreads();
+    // exclusive prefix sum of the kept counts = first packed slot of each row (row-major slot order)
+    if (tid <= W) {                                 // thread W computes the total
+        int base = 0;
+        for (int k = 0; k < tid; ++k) base += L - s_first[k];
+        if (tid < W) s_base[tid] = base;
+        else { s_P = base; n_packed[b] = base; }
+    }
+    __syncthreads();
+    RD_TR(3);
+
+    // ---- D: one thread per token: slot of its owner's copy -> unpack_index -----------------------------------
+    for (int e = tid; e < N; e += kDedupThreads) {
+        const int j = e % L;
+        const int owner = s_owner[e];              // (owner, j) is a kept token: j >= first_kept[owner]
+        const int slot = s_base[owner] + j - s_first[owner];
+        s_slot[e] = slot;
+        unpack_index[seq + e] = slot;
+        if (prefix_tree) prefix_tree[seq + e] = owner;
+    }
+    __syncthreads();
+
+    // ---- E: one thread per kept token ---------------------------------------------------------------------------
+    for (int e = tid; e < N; e += kDedupThreads) {
+        const int i = e / L, j = e % L;
+        if (s_owner[e] == i) {
+            const int slot = s_slot[e];
+            packed_tokens[seq + slot] = s_beam[e];
+            parent[seq + slot] = j ? s_slot[e - 1] : -1;
+            position_ids[seq + slot] = ctx + j;
+            uint64_t a0 = 0, a1 = 0;               // slots on the path from the root to (i, j)
+            for (int t = 0; t <= j; ++t) {
+                const int q = s_slot[i * L + t];
+                if (q < 64) a0 |= 1ull << q; else a1 |= 1ull << (q - 64);
+            }
+            s_bits[slot][0] = a0;
+            s_bits[slot][1] = a1;
+        }
+    }
+    __syncthreads();
+    RD_TR(4);
+
+    // ---- F: paddings and masks ---------------------------------------------------------------------------------
     const int P = s_P;
     for (int p = P + tid; p < N; p += kDedupThreads) {
         packed_tokens[seq + p] = -1;
@@ -134,6 +142,7 @@ __global__ __launch_bounds__(kDedupThreads) void rd_dedup_kernel(
             }
         }
     }
+    RD_TR(5);
 }
 
 }  // namespace

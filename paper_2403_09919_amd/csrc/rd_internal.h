@@ -21,3 +21,22 @@ static inline int rd_check_beam_shape(int B, int W, int L)
     if ((long long)W * (long long)L > RD_MAX_N) return RD_ERR_UNSUPPORTED;
     return RD_OK;
 }
+
+// Optional phase timestamps for tuning builds (-DRD_TRACE): thread 0 of every workgroup stores
+// the constant-rate wall clock at a few points into a caller-supplied buffer (one per source file).
+#ifdef RD_TRACE
+#define RD_TRACE_DEFINE(setter)                                                                   \
+    __device__ unsigned long long *rd_trace_buf = nullptr;                                        \
+    extern "C" int setter(unsigned long long *p)                                                  \
+    {                                                                                             \
+        return hipMemcpyToSymbol(HIP_SYMBOL(rd_trace_buf), &p, sizeof(p)) == hipSuccess ? 0 : -4; \
+    }
+#define RD_TR(i)                                                                                                   \
+    do {                                                                                                           \
+        if (threadIdx.x == 0 && rd_trace_buf)                                                                      \
+            rd_trace_buf[((size_t)blockIdx.x + (size_t)gridDim.x * (blockIdx.y + (size_t)gridDim.y * blockIdx.z)) * 16 + (i)] = wall_clock64(); \
+    } while (0)
+#else
+#define RD_TRACE_DEFINE(setter)
+#define RD_TR(i) do { } while (0)
+#endif

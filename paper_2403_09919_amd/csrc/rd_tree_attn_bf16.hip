@@ -26,18 +26,7 @@
 #include "rd_attn_common.h"
 #include <type_traits>
 
-// Optional phase timestamps for tuning builds (-DRD_TRACE): thread 0 of every workgroup
-// stores the constant-rate wall clock at a few points into a caller-supplied buffer.
-#ifdef RD_TRACE
-__device__ unsigned long long *rd_trace_buf = nullptr;
-extern "C" int rd_debug_set_trace(unsigned long long *p)
-{
-    return hipMemcpyToSymbol(HIP_SYMBOL(rd_trace_buf), &p, sizeof(p)) == hipSuccess ? 0 : -4;
-}
-#define RD_TR(i) do { if (threadIdx.x == 0 && rd_trace_buf) rd_trace_buf[(size_t)blockIdx.x * 16 + (i)] = wall_clock64(); } while (0)
-#else
-#define RD_TR(i) do { } while (0)
-#endif
+RD_TRACE_DEFINE(rd_debug_set_trace)
 
 namespace rd {
 
