@@ -29,6 +29,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per rd_tree_attn launch from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, each scaled
+# by what the same counter reads for a 64 MiB copy); see profiles/bench_vicuna7b_layer_rocprofv3.md.
+# Keyed by workload; None where no counter run has been made.
+MEASURED_TRAFFIC_BYTES = {2: 22684533}
 
 
 def parse():
@@ -41,6 +45,9 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of graph replays")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time budget of the oracle baseline")
+    ap.add_argument("--pmc-calib", action="store_true",
+                    help="also run plain device copies of 64 MiB (reference dispatches for scaling rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -122,6 +129,13 @@ def main():
     for c in copies:                      # eager pass: allocates outputs, sets kernel attributes
         step(c)
     torch.cuda.synchronize()
+
+    if args.pmc_calib:                    # known traffic: each copy reads 64 MiB and writes 64 MiB
+        src = torch.empty(32 << 20, dtype=torch.bfloat16, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     use_graph = not args.no_graph
     stream = torch.cuda.Stream()          # default priority; capture needs a non-default stream
@@ -220,7 +234,7 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(args.config),
             "algorithmic_bytes_per_launch": round(attn_bytes_mean, 1),
             "us_per_launch": round(attn_us, 3),
         },
