@@ -33,10 +33,12 @@ static inline int env_int(const char *name, int dflt)
     return (v && *v) ? atoi(v) : dflt;
 }
 
-// How many context splits per (sequence, head).  Streaming needs enough workgroups in flight
-// (about 128 already reach the HBM rate of a small working set; large ones want a few per
-// compute unit), but every extra split adds a partial result that the merge has to read, and
-// no split is shorter than one 128-key block.
+// How many context splits per (sequence, head).  The launch runs in waves of `slots` resident
+// workgroups (256 compute units, two workgroups each when LDS and registers allow), new
+// workgroups only start as old ones retire, and every workgroup pays a fixed cost (first loads,
+// partial store, merge) worth about three blocks of streaming.  S minimises the resulting
+// makespan estimate  ceil(BH*S / slots) * (ceil(nblk / S) + 3) + S/8  in units of one block; the
+// last term is the merge reading one more partial per split.
 static inline AttnPlan attn_plan(int B, int H, int N, int D, int Cmax, size_t elem_bytes)
 {
     AttnPlan p;
@@ -48,15 +50,18 @@ static inline AttnPlan attn_plan(int B, int H, int N, int D, int Cmax, size_t el
     if (waves_env == 4 || (waves_env == 8 && elem_bytes == 2 && D == 128 && N <= 80)) p.waves = waves_env;
     const int block_keys = elem_bytes == 2 ? 32 * p.waves : kBlockKeys;
     const int nblk = (Cmax + block_keys - 1) / block_keys;
-    static const int target_small = env_int("RD_ATTN_TARGET_WGS_SMALL", 128);
-    static const int target_large = env_int("RD_ATTN_TARGET_WGS", 512);
-    const int target = small ? target_small : target_large;
-    long long S = (target + BH - 1) / BH;
-    if (S > nblk) S = nblk;
-    if (S < 1) S = 1;
+    const int nq = (N + 15) / 16;
+    const long long slots = (elem_bytes == 2 && p.waves == 4 && nq <= 5) ? 512 : 256;
+    int best_S = 1;
+    double best_T = 1e30;
+    for (int S = 1; S <= nblk && S <= 64; ++S) {
+        const long long rounds = (BH * S + slots - 1) / slots;
+        const double T = (double)rounds * ((nblk + S - 1) / S + 3.0) + S / 8.0;
+        if (T < best_T - 1e-9) { best_T = T; best_S = S; }
+    }
     static const int forced = env_int("RD_ATTN_SPLITS", 0);
-    if (forced > 0) S = forced < nblk ? forced : (nblk > 0 ? nblk : 1);
-    p.S = (int)S;
+    if (forced > 0) best_S = forced < nblk ? forced : (nblk > 0 ? nblk : 1);
+    p.S = best_S;
     p.rows_pad = (N + 15) / 16 * 16;
     p.counters_bytes = ((size_t)BH * sizeof(uint32_t) + 255) / 256 * 256;
     p.partial_floats = (size_t)p.rows_pad * (2 + D);
@@ -135,7 +140,8 @@ __device__ __forceinline__ void st_dev4(float *p, float a, float b, float c, flo
 {
     typedef __attribute__((ext_vector_type(4))) float f32x4_t;
     const f32x4_t v = {a, b, c, d};
-    asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
+    // the leading s_nop covers register-write hazards the compiler cannot see into the asm for
+    asm volatile("s_nop 4\n\tglobal_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
 }
 __device__ __forceinline__ void wait_dev_stores() { asm volatile("s_waitcnt vmcnt(0)" : : : "memory"); }
 

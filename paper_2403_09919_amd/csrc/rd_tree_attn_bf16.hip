@@ -120,16 +120,31 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
 
     // ---- which (sequence, head, key range) -------------------------------------------------------
     // Workgroups are dealt round-robin to the 8 XCDs; when the head count allows, all ranges of a
-    // head go to one XCD so that Q and the partial results stay in that XCD's L2.
+    // head go to one XCD so that Q and the partial results stay in that XCD's L2.  Within an XCD
+    // the long context ranges come first and the short packed-key ranges last, so that the
+    // compute units are filled with long-running workgroups from the start.
     const int n_part = a.S + 1;
     int bh, split;
     if (a.xcd_remap) {
         const int xcd = blockIdx.x & 7, k = blockIdx.x >> 3;
-        bh = (k / n_part) * 8 + xcd;
-        split = k % n_part;
+        const int heads_here = (a.B * a.H) >> 3;          // heads served by each XCD
+        const int n_ctx = heads_here * a.S;
+        if (k < n_ctx) {
+            bh = (k / a.S) * 8 + xcd;
+            split = k % a.S;
+        } else {
+            bh = (k - n_ctx) * 8 + xcd;
+            split = a.S;
+        }
     } else {
-        bh = blockIdx.x / n_part;
-        split = blockIdx.x % n_part;
+        const int n_ctx = a.B * a.H * a.S;
+        if ((int)blockIdx.x < n_ctx) {
+            bh = blockIdx.x / a.S;
+            split = blockIdx.x % a.S;
+        } else {
+            bh = blockIdx.x - n_ctx;
+            split = a.S;
+        }
     }
     const int b = bh / a.H;
     const int C = clampi(a.ctx_len[b], 0, a.Cmax);
