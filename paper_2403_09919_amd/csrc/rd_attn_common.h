@@ -20,7 +20,9 @@ constexpr int kBlockKeys = 128;   // keys handled per workgroup iteration
 
 struct AttnPlan {
     int waves;         // waves per workgroup of the bf16 kernel (4 or 8); a block is 32*waves keys
-    int S;             // context splits per (sequence, head); partials per head = S + 1
+    int S;             // context splits per (sequence, head)
+    int fuse_tree;     // 1: the packed keys are the last block of the last context range, not a range of their own
+    int n_part;        // workgroups (and partial results) per head: S, or S + 1 with a separate packed-key range
     int rows_pad;      // packed rows padded to a multiple of 16
     size_t counters_bytes;
     size_t partial_floats;   // floats per partial: m[rows_pad] + l[rows_pad] + O[rows_pad][D]
@@ -62,10 +64,16 @@ static inline AttnPlan attn_plan(int B, int H, int N, int D, int Cmax, size_t el
     static const int forced = env_int("RD_ATTN_SPLITS", 0);
     if (forced > 0) best_S = forced < nblk ? forced : (nblk > 0 ? nblk : 1);
     p.S = best_S;
+    // Long context ranges absorb the packed keys as one more block; short ones (a block or two)
+    // would be lengthened too much, so there the packed keys stay a range of their own.
+    static const int fuse_env = env_int("RD_ATTN_FUSE", -1);
+    p.fuse_tree = (elem_bytes == 2 && nblk > 0 && (nblk + p.S - 1) / p.S >= 4) ? 1 : 0;
+    if (fuse_env >= 0 && elem_bytes == 2 && nblk > 0) p.fuse_tree = fuse_env ? 1 : 0;
+    p.n_part = p.S + (p.fuse_tree ? 0 : 1);
     p.rows_pad = (N + 15) / 16 * 16;
     p.counters_bytes = ((size_t)BH * sizeof(uint32_t) + 255) / 256 * 256;
     p.partial_floats = (size_t)p.rows_pad * (2 + D);
-    p.total_bytes = p.counters_bytes + (size_t)BH * (p.S + 1) * p.partial_floats * sizeof(float);
+    p.total_bytes = p.counters_bytes + (p.n_part > 1 ? (size_t)BH * p.n_part * p.partial_floats * sizeof(float) : 0);
     return p;
 }
 
@@ -77,6 +85,7 @@ struct AttnArgs {
     uint32_t *counters;
     float *partials;
     int B, H, N, Cmax, S, words, rows_pad;
+    int fuse_tree; // 1: packed keys walked by the workgroup of the last context range (see AttnPlan)
     int xcd_remap; // 1: workgroup i serves XCD i%8's share of the heads (needs B*H % 8 == 0)
     float scale_log2e;
 };

@@ -47,5 +47,6 @@ extern "C" int rd_tree_attn(const void *q, const void *k_cache, const void *v_ca
     a.B = B; a.H = H; a.N = N; a.Cmax = Cmax; a.S = plan.S; a.words = (N + 63) / 64; a.rows_pad = plan.rows_pad;
     a.scale_log2e = scale * 1.44269504088896340736f;
     a.xcd_remap = (((long long)B * H) % 8 == 0) ? 1 : 0;
+    a.fuse_tree = plan.fuse_tree;
     return dt == RD_BF16 ? rd::tree_attn_bf16(a, D, plan.waves, (hipStream_t)stream) : rd::tree_attn_f32(a, D, (hipStream_t)stream);
 }

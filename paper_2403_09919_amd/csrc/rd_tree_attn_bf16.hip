@@ -113,7 +113,7 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform, kept in a scalar register
     const int r16 = lane & 15;
     const int g = lane >> 4;
     RD_TR(0);
@@ -123,7 +123,10 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
     // head go to one XCD so that Q and the partial results stay in that XCD's L2.  Within an XCD
     // the long context ranges come first and the short packed-key ranges last, so that the
     // compute units are filled with long-running workgroups from the start.
-    const int n_part = a.S + 1;
+    // The packed keys are either a range of their own (split == S, one more workgroup per head) or,
+    // when the context ranges are long (a.fuse_tree), one more block at the end of the last context
+    // range; with a single context range the head then has one workgroup and needs no merge.
+    const int n_part = a.S + (a.fuse_tree ? 0 : 1);
     int bh, split;
     if (a.xcd_remap) {
         const int xcd = blockIdx.x & 7, k = blockIdx.x >> 3;
@@ -149,26 +152,24 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
     const int b = bh / a.H;
     const int C = clampi(a.ctx_len[b], 0, a.Cmax);
     const int P = clampi(a.n_packed[b], 0, a.N);
-    const bool is_tree = (split == a.S);
 
-    int k_begin, k_end;
-    const unsigned char *Kb, *Vb;                 // byte address of key 0 of the tensor this range reads
-    if (is_tree) {
-        k_begin = 0;
-        k_end = P;
-        Kb = static_cast<const unsigned char *>(a.k_new) + (size_t)bh * a.N * G::kRowBytes;
-        Vb = static_cast<const unsigned char *>(a.v_new) + (size_t)bh * a.N * G::kRowBytes;
-    } else {
-        ctx_range(C, a.S, split, kBlock, &k_begin, &k_end);
-        Kb = static_cast<const unsigned char *>(a.k_cache) + (size_t)bh * a.Cmax * G::kRowBytes;
-        Vb = static_cast<const unsigned char *>(a.v_cache) + (size_t)bh * a.Cmax * G::kRowBytes;
-    }
-
+    // Blocks this workgroup walks: nA blocks of context keys [k_begin, k_end), then nB (0 or 1)
+    // block of packed keys [0, P).  All of this is wave-uniform.
+    int k_begin = 0, k_end = 0;
+    if (split < a.S) ctx_range(C, a.S, split, kBlock, &k_begin, &k_end);
+    const bool has_tree = (split == a.S) || (a.fuse_tree && split == a.S - 1);
+    const int nA = (k_end - k_begin + kBlock - 1) / kBlock;
+    const int nB = (has_tree && P > 0) ? 1 : 0;
+    const int nb = nA + nB;
+    const unsigned char *Qb = static_cast<const unsigned char *>(a.q) + (size_t)bh * a.N * G::kRowBytes;
+    const unsigned char *Kc = static_cast<const unsigned char *>(a.k_cache) + (size_t)bh * a.Cmax * G::kRowBytes;
+    const unsigned char *Vc = static_cast<const unsigned char *>(a.v_cache) + (size_t)bh * a.Cmax * G::kRowBytes;
+    const unsigned char *Kn = static_cast<const unsigned char *>(a.k_new) + (size_t)bh * a.N * G::kRowBytes;
+    const unsigned char *Vn = static_cast<const unsigned char *>(a.v_new) + (size_t)bh * a.N * G::kRowBytes;
     // ---- all first loads, without branches so that the waits on them stay exact --------------------
     // Order: Q and the tree-mask words (they gate the first score tile), then K, then V.
     constexpr int kQRowsPerPass = kThreads / G::kChunks;
     constexpr int kQPasses = (kRows + kQRowsPerPass - 1) / kQRowsPerPass;
-    const unsigned char *Qb = static_cast<const unsigned char *>(a.q) + (size_t)bh * a.N * G::kRowBytes;
     uint4 qreg[kQPasses];
 #pragma unroll
     for (int i = 0; i < kQPasses; ++i) {
@@ -178,7 +179,7 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
     // Visibility of this wave's 32 keys for the packed rows this lane scores (row 16*qt + r16).
     // Context keys are visible to every row; the packed keys (one block, since N <= 128) are
     // visible per the tree mask: wave w holds keys 32w..32w+31, i.e. half of mask word w/2.
-    // (Loaded by context workgroups too, and ignored there.)
+    // (Loaded by every workgroup; those without a packed-key block ignore it.)
     uint64_t mword[NQ];
     {
         const int word = min(wave >> 1, a.words - 1);
@@ -190,28 +191,32 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
     // This wave's slice of a block: coalesced 16-byte loads into registers; a wave-wide load
     // covers 1 KB of consecutive rows.  Rows past the end of the range are redirected to the last
     // valid row (their scores are masked and their probabilities are zero), so the loads carry no
-    // predicate.  An empty range reads (and ignores) the first row of Q instead.
+    // predicate.
     uint4 kreg[G::kLoads], vreg[G::kLoads];
     const int ld_row = lane / G::kChunks;
     const int ld_chunk = lane % G::kChunks;
-    const bool any_keys = k_end > k_begin;                                   // uniform
-    const uint32_t last_off = (any_keys ? (uint32_t)(k_end - 1) * G::kRowBytes : 0u) + ld_chunk * 16;
-    auto load_tile = [&](const unsigned char *base, int tile0, uint4 (&reg)[G::kLoads]) __attribute__((always_inline)) {
-        const uint32_t off0 = (uint32_t)(tile0 + ld_row) * G::kRowBytes + ld_chunk * 16;
+    auto load_tile = [&](const unsigned char *base, int key0, int end, uint4 (&reg)[G::kLoads]) __attribute__((always_inline)) {
+        const uint32_t off0 = (uint32_t)(key0 + wave * G::kTileKeys + ld_row) * G::kRowBytes + ld_chunk * 16;
+        const uint32_t last_off = (uint32_t)(end - 1) * G::kRowBytes + ld_chunk * 16;
 #pragma unroll
         for (int s = 0; s < G::kLoads; ++s) reg[s] = ldg16(base + min(off0 + s * 1024u, last_off));
     };
-    load_tile(any_keys ? Kb : Qb, k_begin + wave * G::kTileKeys, kreg);
-    load_tile(any_keys ? Vb : Qb, k_begin + wave * G::kTileKeys, vreg);
+    {   // first block; a workgroup with no block at all reads (and ignores) the first row of Q
+        const bool ctx = nA > 0;
+        const unsigned char *kb = nb == 0 ? Qb : (ctx ? Kc : Kn);
+        const unsigned char *vb = nb == 0 ? Qb : (ctx ? Vc : Vn);
+        const int key0 = ctx ? k_begin : 0;
+        const int end = nb == 0 ? 1 : (ctx ? k_end : P);
+        load_tile(kb, key0, end, kreg);
+        load_tile(vb, key0, end, vreg);
+    }
 
+    // visibility of this wave's packed keys (used in the packed-key block only)
     uint32_t vis[NQ];
 #pragma unroll
     for (int qt = 0; qt < NQ; ++qt) {
-        vis[qt] = 0xffffffffu;
-        if (is_tree) {
-            const bool real = (qt * 16 + r16 < P) && ((wave >> 1) < a.words);
-            vis[qt] = real ? (uint32_t)(mword[qt] >> ((wave & 1) * 32)) : 0u;
-        }
+        const bool real = (qt * 16 + r16 < P) && ((wave >> 1) < a.words);
+        vis[qt] = real ? (uint32_t)(mword[qt] >> ((wave & 1) * 32)) : 0u;
     }
 
 #pragma unroll
@@ -233,24 +238,26 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
     }
 
     unsigned char *my_tile = sKV + wave * G::kTileBytes;
-    // lane-constant LDS offsets
-    int k_wr[G::kLoads], v_wr[G::kLoads];
-#pragma unroll
-    for (int s = 0; s < G::kLoads; ++s) {
-        const int row = s * G::kRowsPerLoad + ld_row;
-        k_wr[s] = row * G::kRowBytes + kswz<D>(row, ld_chunk) * 16;
-        v_wr[s] = row * G::kRowBytes + vswz<D>(row, ld_chunk) * 16;
-    }
-    int kq_rd[G::kKSteps];                       // row r16, chunk 4t+g (rows 16+r16, 16qt+r16 add constants)
-#pragma unroll
-    for (int t = 0; t < G::kKSteps; ++t) kq_rd[t] = r16 * G::kRowBytes + kswz<D>(r16, 4 * t + g) * 16;
-    int v_rd[kDTW];                              // transpose-read address of rows 4g+(r16>>2) for d-tile j
-#pragma unroll
-    for (int j = 0; j < kDTW; ++j) {
-        const int dt = wave * kDTW + j;
-        const int ra = 4 * g + (r16 >> 2);
-        v_rd[j] = ra * G::kRowBytes + vswz<D>(ra, 2 * dt + ((r16 & 3) >> 1)) * 16 + (r16 & 1) * 8;
-    }
+    // Lane-constant LDS offsets.  The XOR swizzles make the offset of load s / k-step t / d-tile dt
+    // the XOR of one lane-dependent value with a compile-time constant, so one register serves each
+    // family instead of one per member.
+    const int k_base = ld_row * G::kRowBytes + kswz<D>(ld_row, ld_chunk) * 16;
+    const int v_base = ld_row * G::kRowBytes + vswz<D>(ld_row, ld_chunk) * 16;
+    auto k_wr = [&](int s) __attribute__((always_inline)) {    // row s*kRowsPerLoad + ld_row, K swizzle
+        return s * 1024 + (k_base ^ (((s * G::kRowsPerLoad) & (G::kChunks - 1)) * 16));
+    };
+    auto v_wr = [&](int s) __attribute__((always_inline)) {    // same row, V swizzle
+        return s * 1024 + (v_base ^ (((s * G::kRowsPerLoad) & (G::kChunks / 2 - 1)) * 32));
+    };
+    const int kq_base = r16 * G::kRowBytes + kswz<D>(r16, g) * 16;
+    auto kq_rd = [&](int t) __attribute__((always_inline)) {   // row r16, chunk 4t+g (rows 16+r16, 16qt+r16 add constants)
+        return kq_base ^ (((4 * t) & (G::kChunks - 1)) * 16);
+    };
+    const int vt_row = 4 * g + (r16 >> 2);
+    const int vt_base = vt_row * G::kRowBytes + vswz<D>(vt_row, (r16 & 3) >> 1) * 16 + (r16 & 1) * 8;
+    auto vt_rd = [&](int dt) __attribute__((always_inline)) {  // transpose-read address of rows 4g+(r16>>2), d-tile dt
+        return vt_base ^ ((dt & (G::kChunks / 2 - 1)) * 32);
+    };
 
     lds_barrier();        // Q visible to all waves
     RD_TR(1);
@@ -264,14 +271,26 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
     // would stop the compiler from overlapping LDS reads with the matrix instructions).
     auto block_loop = [&](auto nqa_tag) __attribute__((always_inline)) {
         constexpr int NQA = decltype(nqa_tag)::value;
-        for (int blk0 = k_begin; blk0 < k_end; blk0 += kBlock) {
-            const int tile0 = blk0 + wave * G::kTileKeys;
-            const bool more = blk0 + kBlock < k_end;
+        for (int ib = 0; ib < nb; ++ib) {
+            // this block and the one to prefetch: tensors, first key, end of the key range.  After
+            // the last block the prefetch repeats it (issued and ignored).
+            const bool cur_tree = ib >= nA;
+            const int cur_key0 = cur_tree ? 0 : k_begin + ib * kBlock;
+            const int cur_end = cur_tree ? P : k_end;
+            const int inext = ib + 1 < nb ? ib + 1 : ib;
+            const bool next_tree = inext >= nA;
+            const unsigned char *next_kb = next_tree ? Kn : Kc;
+            const unsigned char *next_vb = next_tree ? Vn : Vc;
+            const int next_key0 = next_tree ? 0 : k_begin + inext * kBlock;
+            const int next_end = next_tree ? P : k_end;
+            const int tile0 = cur_key0 + wave * G::kTileKeys;
 
-            // K registers -> own LDS tile (K swizzle); then fetch the next block's K
+            // K registers -> own LDS tile (K swizzle); then fetch the next block's K.  The prefetch
+            // is issued after the last block too (and ignored): a branch around it would make the
+            // compiler wait for all loads in flight wherever it waits for one of them.
 #pragma unroll
-            for (int s = 0; s < G::kLoads; ++s) *reinterpret_cast<uint4 *>(my_tile + k_wr[s]) = kreg[s];
-            if (more) load_tile(Kb, tile0 + kBlock, kreg);
+            for (int s = 0; s < G::kLoads; ++s) *reinterpret_cast<uint4 *>(my_tile + k_wr(s)) = kreg[s];
+            load_tile(next_kb, next_key0, next_end, kreg);
             wave_lds_sync();
 
             // S^T tile pair: keys (16 mt + r) x packed rows (16 qt + c), raw (unscaled) scores
@@ -283,25 +302,25 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
             }
 #pragma unroll
             for (int t = 0; t < G::kKSteps; ++t) {
-                const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(my_tile + kq_rd[t]);
-                const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(my_tile + kq_rd[t] + 16 * G::kRowBytes);
+                const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(my_tile + kq_rd(t));
+                const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(my_tile + kq_rd(t) + 16 * G::kRowBytes);
 #pragma unroll
                 for (int qt = 0; qt < NQA; ++qt) {
                     {
-                        const bf16x8 bq = *reinterpret_cast<const bf16x8 *>(sQ + kq_rd[t] + qt * 16 * G::kRowBytes);
+                        const bf16x8 bq = *reinterpret_cast<const bf16x8 *>(sQ + kq_rd(t) + qt * 16 * G::kRowBytes);
                         sacc[0][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, bq, sacc[0][qt], 0, 0, 0);
                         sacc[1][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, bq, sacc[1][qt], 0, 0, 0);
                     }
                 }
             }
-            if (blk0 == k_begin) RD_TR(8);
+            if (ib == 0) RD_TR(8);
 
             // per-row maximum over this wave's 32 keys, in log2 units (score * scale * log2 e).  An
             // interior context tile keeps the raw scores (the scale is folded into the exponent
             // later); a tile with masked or out-of-range keys is scaled here and its dead entries
             // set to -inf.
-            const int rem = k_end - tile0;                         // keys of this tile inside the range
-            const bool plain = !is_tree && rem >= G::kTileKeys && !c_neg;
+            const int rem = cur_end - tile0;                       // keys of this tile inside the range
+            const bool plain = !cur_tree && rem >= G::kTileKeys && !c_neg;
             if (plain) {
 #pragma unroll
                 for (int qt = 0; qt < NQA; ++qt) {
@@ -317,7 +336,7 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
 #pragma unroll
                 for (int qt = 0; qt < NQA; ++qt) {
                     {
-                        const uint32_t bits = (vis[qt] & tail) >> (4 * g);     // element (mt, i) at bit 16 mt + i
+                        const uint32_t bits = ((cur_tree ? vis[qt] : 0xffffffffu) & tail) >> (4 * g);     // element (mt, i) at bit 16 mt + i
                         float tmax = -INFINITY;
 #pragma unroll
                         for (int mt = 0; mt < 2; ++mt)
@@ -334,12 +353,12 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
             }
 
             lds_barrier();        // (A) tile maxima of all waves visible
-            if (blk0 == k_begin) RD_TR(9);
+            if (ib == 0) RD_TR(9);
 
             // V registers -> own LDS tile (V swizzle), replacing K which this wave has consumed
 #pragma unroll
-            for (int s = 0; s < G::kLoads; ++s) *reinterpret_cast<uint4 *>(my_tile + v_wr[s]) = vreg[s];
-            if (more) load_tile(Vb, tile0 + kBlock, vreg);
+            for (int s = 0; s < G::kLoads; ++s) *reinterpret_cast<uint4 *>(my_tile + v_wr(s)) = vreg[s];
+            load_tile(next_vb, next_key0, next_end, vreg);
 
             // online softmax with the block-wide maximum; P^T to LDS in B-operand layout
 #pragma unroll
@@ -377,7 +396,7 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
                 }
             }
             lds_barrier();        // (B) V tiles and P^T of all waves visible
-            if (blk0 == k_begin) RD_TR(10);
+            if (ib == 0) RD_TR(10);
 
             // O^T += V^T P^T over the block's key tiles, for this wave's d-tiles.  Key tiles beyond
             // the range were not loaded (their P^T is zero); only the last block of a range can have them.
@@ -386,8 +405,8 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
                 bf16x8 aV[kDTW];
 #pragma unroll
                 for (int j = 0; j < kDTW; ++j) {
-                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(vt + v_rd[j]));
-                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(vt + v_rd[j] + 16 * G::kRowBytes));
+                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(vt + vt_rd(wave * kDTW + j)));
+                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(vt + vt_rd(wave * kDTW + j) + 16 * G::kRowBytes));
                     aV[j] = __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
                 }
 #pragma unroll
@@ -398,21 +417,52 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
                         oacc[j][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aV[j], pB, oacc[j][qt], 0, 0, 0);
                 }
             };
-            if (blk0 + kBlock <= k_end) {
+            if (cur_key0 + kBlock <= cur_end) {
 #pragma unroll
                 for (int kt = 0; kt < NW; ++kt) pv_tile(kt);
             } else {
 #pragma unroll 1
-                for (int kt = 0; blk0 + kt * G::kTileKeys < k_end; ++kt) pv_tile(kt);
+                for (int kt = 0; cur_key0 + kt * G::kTileKeys < cur_end; ++kt) pv_tile(kt);
             }
             lds_barrier();        // (C) tiles and P^T free for the next block
-            if (blk0 == k_begin) RD_TR(2);
+            if (ib == 0) RD_TR(2);
         }
     };
     constexpr int kHalf = (NQ + 1) / 2;
     if (NQ > 1 && nqt <= kHalf) block_loop(std::integral_constant<int, kHalf>{});
     else block_loop(std::integral_constant<int, NQ>{});
     RD_TR(3);
+
+    // ---- a head served by this workgroup alone: normalise and write the output -------------------
+    if (n_part == 1) {
+        float *sL1 = sM;          // [kRows][NW]
+#pragma unroll
+        for (int qt = 0; qt < NQ; ++qt) {
+            const float l = quad_sum(l_run[qt]);
+            if (g == 0) sL1[(qt * 16 + r16) * NW + wave] = l;
+        }
+        lds_barrier();
+        __bf16 *outp = static_cast<__bf16 *>(a.out) + (size_t)bh * a.N * D;
+#pragma unroll
+        for (int qt = 0; qt < NQ; ++qt) {
+            const int qrow = qt * 16 + r16;
+            if (qrow < a.N) {
+                float lsum = sL1[qrow * NW];
+#pragma unroll
+                for (int w = 1; w < NW; ++w) lsum += sL1[qrow * NW + w];
+                const bool keep = qrow < P;                               // rows beyond the packed count are zero
+                const float inv = keep ? 1.0f / lsum : 0.f;
+#pragma unroll
+                for (int j = 0; j < kDTW; ++j) {
+                    const f32x4 o = oacc[j][qt];
+                    store_out4(outp + (size_t)qrow * D + (wave * kDTW + j) * 16 + 4 * g, keep ? o[0] * inv : 0.f,
+                               keep ? o[1] * inv : 0.f, keep ? o[2] * inv : 0.f, keep ? o[3] * inv : 0.f);
+                }
+            }
+        }
+        RD_TR(6);
+        return;
+    }
 
     // ---- partial state of this key range -> workspace ------------------------------------------
     // Layout of one partial: (m, l) pairs [kRows][2], then the output accumulators exactly as the
@@ -578,7 +628,7 @@ static int launch_bf16(const AttnArgs &a, hipStream_t stream)
             return RD_ERR_HIP;
         configured = true;
     }
-    const unsigned grid = (unsigned)((size_t)a.B * a.H * (a.S + 1));
+    const unsigned grid = (unsigned)((size_t)a.B * a.H * (a.S + (a.fuse_tree ? 0 : 1)));
     hipLaunchKernelGGL((rd_tree_attn_bf16_kernel<D, NQ, NW>), dim3(grid), dim3(NW * 64), smem, stream, a);
     return rd_check_launch();
 }
