@@ -35,12 +35,16 @@ static inline int env_int(const char *name, int dflt)
     return (v && *v) ? atoi(v) : dflt;
 }
 
-// How many context splits per (sequence, head).  The launch runs in waves of `slots` resident
-// workgroups (256 compute units, two workgroups each when LDS and registers allow), new
-// workgroups only start as old ones retire, and every workgroup pays a fixed cost (first loads,
-// partial store, merge) worth about three blocks of streaming.  S minimises the resulting
-// makespan estimate  ceil(BH*S / slots) * (ceil(nblk / S) + 3) + S/8  in units of one block; the
-// last term is the merge reading one more partial per split.
+// How many context splits per (sequence, head), and whether the packed keys ride on the last
+// context range.  Measured behaviour of the kernel on MI355X that the estimate encodes:
+//   * a compute unit streams K/V through this kernel at about 27 GB/s whether it holds one
+//     workgroup or two, so the blocks of the workgroups that share a compute unit add up; the
+//     launch as a whole cannot exceed about 5.5 TB/s;
+//   * workgroups beyond the resident capacity (`slots`) start only as earlier ones retire;
+//   * more than one workgroup per head costs a merge: about 3 us of latency plus the partial
+//     results written and read back once (at roughly 4 TB/s).
+// Long ranges (four blocks or more) take the packed keys as one more block; a head with a single
+// such range needs no workspace traffic at all.  S minimises the estimated time.
 static inline AttnPlan attn_plan(int B, int H, int N, int D, int Cmax, size_t elem_bytes)
 {
     AttnPlan p;
@@ -54,21 +58,30 @@ static inline AttnPlan attn_plan(int B, int H, int N, int D, int Cmax, size_t el
     const int nblk = (Cmax + block_keys - 1) / block_keys;
     const int nq = (N + 15) / 16;
     const long long slots = (elem_bytes == 2 && p.waves == 4 && nq <= 5) ? 512 : 256;
+    const bool can_fuse = elem_bytes == 2;
+    const double blk_bytes = 2.0 * block_keys * D * (double)elem_bytes;      // K and V of one block of one head
+    const double t_blk = blk_bytes / 27e9;
+    const double t_hbm = (double)BH * nblk * blk_bytes / 5.5e12;
+    const double part_bytes = (double)nq * 16 * (2 + D) * sizeof(float);
     int best_S = 1;
     double best_T = 1e30;
     for (int S = 1; S <= nblk && S <= 64; ++S) {
-        const long long rounds = (BH * S + slots - 1) / slots;
-        const double T = (double)rounds * ((nblk + S - 1) / S + 3.0) + S / 8.0;
-        if (T < best_T - 1e-9) { best_T = T; best_S = S; }
+        const int per = (nblk + S - 1) / S;
+        const bool fuse = can_fuse && per >= 4;
+        const int n_part = S + (fuse ? 0 : 1);
+        const long long wg = BH * S;
+        const long long rounds = wg <= slots ? (wg + 255) / 256 : (wg + slots - 1) / slots * (slots / 256);
+        double T = (double)rounds * (per + (fuse ? 1 : 0)) * t_blk;
+        if (T < t_hbm) T = t_hbm;
+        if (n_part > 1) T += 3e-6 + 2.0 * (double)BH * n_part * part_bytes / 4e12;
+        if (T < best_T * (1.0 - 1e-9)) { best_T = T; best_S = S; }
     }
     static const int forced = env_int("RD_ATTN_SPLITS", 0);
     if (forced > 0) best_S = forced < nblk ? forced : (nblk > 0 ? nblk : 1);
     p.S = best_S;
-    // Long context ranges absorb the packed keys as one more block; short ones (a block or two)
-    // would be lengthened too much, so there the packed keys stay a range of their own.
     static const int fuse_env = env_int("RD_ATTN_FUSE", -1);
-    p.fuse_tree = (elem_bytes == 2 && nblk > 0 && (nblk + p.S - 1) / p.S >= 4) ? 1 : 0;
-    if (fuse_env >= 0 && elem_bytes == 2 && nblk > 0) p.fuse_tree = fuse_env ? 1 : 0;
+    p.fuse_tree = (can_fuse && nblk > 0 && (nblk + p.S - 1) / p.S >= 4) ? 1 : 0;
+    if (fuse_env >= 0 && can_fuse && nblk > 0) p.fuse_tree = fuse_env ? 1 : 0;
     p.n_part = p.S + (p.fuse_tree ? 0 : 1);
     p.rows_pad = (N + 15) / 16 * 16;
     p.counters_bytes = ((size_t)BH * sizeof(uint32_t) + 255) / 256 * 256;
