@@ -45,33 +45,59 @@ __global__ __launch_bounds__(kDedupThreads) void rd_dedup_kernel(
     RD_TR(0);
     const int ctx = ctx_len ? ctx_len[b] : 0;      // fetched with the candidates, not after them
 
+    // N <= RD_MAX_N <= kDedupThreads: thread e owns token e = (i, j) in every per-token phase.
+    static_assert(RD_MAX_N <= kDedupThreads, "one thread per token");
+    const int e = tid;
+    const bool tok = e < N;
+    const int i = tok ? e / L : 0, j = tok ? e - i * L : 0;
+
     // ---- A: stage -----------------------------------------------------------------------------------
-    for (int i = tid; i < N; i += kDedupThreads) {
-        s_beam[i] = beams[seq + i];
-        s_owner[i] = i / L;
-        s_bits[i][0] = 0;
-        s_bits[i][1] = 0;
+    if (tok) {
+        s_beam[e] = beams[seq + e];
+        s_owner[e] = i;
+        s_bits[e][0] = 0;
+        s_bits[e][1] = 0;
     }
     if (tid < W) s_first[tid] = L;
     __syncthreads();
     RD_TR(1);
 
     // ---- B: common prefixes of all pairs ----------------------------------------------------------------
+    // Both rows are read eight tokens at a time (independent LDS reads), the match length follows
+    // in registers, and the atomics that lower the owners are issued without waiting on each other.
     for (int pr = tid; pr < W * W; pr += kDedupThreads) {
-        const int i = pr / W, k = pr % W;
-        if (k < i) {
-            for (int j = 0; j < L && s_beam[i * L + j] == s_beam[k * L + j]; ++j) atomicMin(&s_owner[i * L + j], k);
+        const int pi = pr / W, pk = pr - pi * W;
+        if (pk < pi) {
+            const int32_t *ri = s_beam + pi * L, *rk = s_beam + pk * L;
+            for (int j0 = 0; j0 < L; j0 += 8) {
+                int32_t a[8], c[8];
+#pragma unroll
+                for (int t = 0; t < 8; ++t) {
+                    const int jj = min(j0 + t, L - 1);
+                    a[t] = ri[jj];
+                    c[t] = rk[jj];
+                }
+                int m = 0;                          // matching tokens at the head of this group
+                bool run = true;
+#pragma unroll
+                for (int t = 0; t < 8; ++t) {
+                    run = run && (j0 + t < L) && (a[t] == c[t]);
+                    m += run ? 1 : 0;
+                }
+#pragma unroll
+                for (int t = 0; t < 8; ++t)
+                    if (t < m) atomicMin(&s_owner[pi * L + j0 + t], pk);
+                if (m < 8) break;
+            }
         }
     }
-    __syncthreads();
+    rd_lds_barrier();
     RD_TR(2);
 
     // ---- C: first kept position per row (kept tokens are a suffix of their row) ---------------------------
-    for (int e = tid; e < N; e += kDedupThreads) {
-        const int i = e / L;
-        if (s_owner[e] == i) atomicMin(&s_first[i], e % L);
-    }
-    __syncthreads();
+    const int owner = tok ? s_owner[e] : 0;        // prefix_tree[i][j]
+    if (tok && owner == i) atomicMin(&s_first[i], j);
+    rd_lds_barrier();
     // exclusive prefix sum of the kept counts = first packed slot of each row (row-major slot order)
     if (tid <= W) {                                 // thread W computes the total
         int base = 0;
@@ -79,38 +105,33 @@ __global__ __launch_bounds__(kDedupThreads) void rd_dedup_kernel(
         if (tid < W) s_base[tid] = base;
         else { s_P = base; n_packed[b] = base; }
     }
-    __syncthreads();
+    rd_lds_barrier();
     RD_TR(3);
 
     // ---- D: one thread per token: slot of its owner's copy -> unpack_index -----------------------------------
-    for (int e = tid; e < N; e += kDedupThreads) {
-        const int j = e % L;
-        const int owner = s_owner[e];              // (owner, j) is a kept token: j >= first_kept[owner]
-        const int slot = s_base[owner] + j - s_first[owner];
+    if (tok) {
+        const int slot = s_base[owner] + j - s_first[owner];   // (owner, j) is a kept token: j >= first_kept[owner]
         s_slot[e] = slot;
         unpack_index[seq + e] = slot;
         if (prefix_tree) prefix_tree[seq + e] = owner;
     }
-    __syncthreads();
+    rd_lds_barrier();
 
     // ---- E: one thread per kept token ---------------------------------------------------------------------------
-    for (int e = tid; e < N; e += kDedupThreads) {
-        const int i = e / L, j = e % L;
-        if (s_owner[e] == i) {
-            const int slot = s_slot[e];
-            packed_tokens[seq + slot] = s_beam[e];
-            parent[seq + slot] = j ? s_slot[e - 1] : -1;
-            position_ids[seq + slot] = ctx + j;
-            uint64_t a0 = 0, a1 = 0;               // slots on the path from the root to (i, j)
-            for (int t = 0; t <= j; ++t) {
-                const int q = s_slot[i * L + t];
-                if (q < 64) a0 |= 1ull << q; else a1 |= 1ull << (q - 64);
-            }
-            s_bits[slot][0] = a0;
-            s_bits[slot][1] = a1;
+    if (tok && owner == i) {
+        const int slot = s_slot[e];
+        packed_tokens[seq + slot] = s_beam[e];
+        parent[seq + slot] = j ? s_slot[e - 1] : -1;
+        position_ids[seq + slot] = ctx + j;
+        uint64_t a0 = 0, a1 = 0;               // slots on the path from the root to (i, j)
+        for (int t = 0; t <= j; ++t) {
+            const int q = s_slot[i * L + t];
+            if (q < 64) a0 |= 1ull << q; else a1 |= 1ull << (q - 64);
         }
+        s_bits[slot][0] = a0;
+        s_bits[slot][1] = a1;
     }
-    __syncthreads();
+    rd_lds_barrier();
     RD_TR(4);
 
     // ---- F: paddings and masks ---------------------------------------------------------------------------------

@@ -13,6 +13,16 @@ static inline int rd_check_launch()
     return hipGetLastError() == hipSuccess ? RD_OK : RD_ERR_HIP;
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every global
+// load and store the wave has in flight, which turns each barrier after a global store into a
+// round trip to memory.
+__device__ __forceinline__ void rd_lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // Validates the (W, L) pair shared by rd_dedup and rd_accept.
 static inline int rd_check_beam_shape(int B, int W, int L)
 {
