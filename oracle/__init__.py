@@ -153,6 +153,37 @@ def accept(beams, unpack_index, argmax_in, root_token=None) -> dict:
     return out
 
 
+def commit(k_new, v_new, accepted_idx, best_len, ctx_len, k_cache, v_cache, dtype: str,
+           hidden=None) -> dict:
+    """Commit of the accepted tokens: returns updated COPIES of the caches, ctx_len_out,
+    n_committed and (if `hidden` [B,N,Dh] is given) hidden_last [B,Dh] (zeros where best_len == 0)."""
+    np_dt = np.uint16 if dtype == "bf16" else np.float32
+    k_new = np.ascontiguousarray(k_new, dtype=np_dt)
+    v_new = np.ascontiguousarray(v_new, dtype=np_dt)
+    kc = np.array(k_cache, dtype=np_dt, order="C", copy=True)
+    vc = np.array(v_cache, dtype=np_dt, order="C", copy=True)
+    B, H, N, D = k_new.shape
+    Cmax = kc.shape[2]
+    assert v_new.shape == k_new.shape and kc.shape == (B, H, Cmax, D) and vc.shape == kc.shape
+    accepted_idx = _i32(accepted_idx)
+    L = accepted_idx.shape[1]
+    best_len, ctx_len = _i32(best_len), _i32(ctx_len)
+    ctx_out = np.zeros(B, np.int32)
+    n_comm = np.zeros(B, np.int32)
+    hid_last = None
+    Dh = 0
+    if hidden is not None:
+        hidden = np.ascontiguousarray(hidden, dtype=np_dt)
+        Dh = hidden.shape[2]
+        assert hidden.shape == (B, N, Dh)
+        hid_last = np.zeros((B, Dh), np_dt)
+    lib().orc_commit(_p(k_new), _p(v_new), _p(accepted_idx), _p(best_len), _p(ctx_len),
+                     B, H, N, D, Cmax, L, DTYPES[dtype], _p(kc), _p(vc), _p(ctx_out), _p(n_comm),
+                     _p(hidden), Dh, _p(hid_last))
+    return {"k_cache": kc, "v_cache": vc, "ctx_len": ctx_out, "n_committed": n_comm,
+            "hidden_last": hid_last}
+
+
 def verify_step(beams, ctx_len, q, k_cache, v_cache, k_new, v_new, logits, dtype, scale,
                 root_token=None) -> dict:
     """The whole path in order: dedup -> tree attention -> argmax -> accept."""

@@ -2,8 +2,8 @@
  * CPU oracle for the ReDrafter verification step.  TEST INFRASTRUCTURE ONLY.
  *
  * A plain, slow, definition-level implementation of what the verification step
- * computes (dynamic tree attention, Sec. 3.3 and App. A.1; verification and greedy
- * acceptance, Sec. 3.4).  It exists so that the HIP path can be checked against
+ * computes (dynamic tree attention, Sec. 3.3 and App. A.1; verification, greedy
+ * acceptance and the commit of the accepted tokens, Sec. 3.4).  It exists so that the HIP path can be checked against
  * something that is easy to compare with the paper by eye.  It shares no code
  * with the HIP path and must never be called from it; only tests, the smoke
  * check and the benchmark's CPU-baseline leg use it.
@@ -16,7 +16,9 @@
  *
  * Every function in this file is pinned by tests that do not use this file's
  * own arithmetic (the worked example of App. A.1, a literal prefix trie, closed
- * forms, per-beam causal attention in numpy, library argmax, a toy greedy LM).
+ * forms, per-beam causal attention in numpy, library argmax, a toy greedy LM; for the
+ * commit: numpy index arithmetic, attention over the committed cache, and a many-step
+ * speculative loop that must reproduce plain greedy decoding of a toy attention LM).
  *
  * OpenMP (if enabled at compile time) parallelises only over independent
  * (sequence, head) pairs or logit rows; the arithmetic per output is unchanged.
@@ -364,5 +366,56 @@ void orc_accept(const int32_t *beams, const int32_t *unpack_index, const int32_t
         for (int t = 0; t < L; ++t)
             accepted_idx[b * L + t] = (t < bl) ? ui[bw * L + t] : -1;
         next_token[b] = (bl > 0) ? am[ui[bw * L + bl - 1]] : root_token[b];
+    }
+}
+
+/* ---------------------------------------------------------------------------------
+ * Commit of the accepted tokens (Sec. 3.4: the accepted tokens are appended to the
+ * previously generated ones, and the LLM's hidden state at the last accepted token
+ * seeds the next draft call).  For the attention path this means that the key and
+ * value rows of the accepted packed tokens join the context:
+ *     n = min(best_len[b], Cmax - ctx_len[b])            (what still fits)
+ *     cache[b,h,ctx_len[b]+t,:] = new[b,h,accepted_idx[b][t],:]   for t < n, every h
+ *     ctx_len_out[b] = ctx_len[b] + n,   n_committed[b] = n
+ *     hidden_last[b,:] = hidden[b, accepted_idx[b][best_len[b]-1], :]  if best_len[b] > 0
+ * Rows are copied bit for bit (no arithmetic).  best_len is clamped to [0, L], ctx_len
+ * to [0, Cmax] and slots to [0, N-1], as the device code does for out-of-range data.
+ * n_committed, hidden / hidden_last may be NULL.                                   */
+void orc_commit(const void *k_new, const void *v_new, const int32_t *accepted_idx,
+                const int32_t *best_len, const int32_t *ctx_len,
+                int B, int H, int N, int D, int Cmax, int L, int dtype,
+                void *k_cache, void *v_cache, int32_t *ctx_len_out, int32_t *n_committed,
+                const void *hidden, int Dh, void *hidden_last)
+{
+    const size_t es = (dtype == ORC_BF16) ? 2 : 4;
+    const size_t row = (size_t)D * es;
+    for (int b = 0; b < B; ++b) {
+        int bl = best_len[b];
+        if (bl < 0) bl = 0;
+        if (bl > L) bl = L;
+        int ctx = ctx_len[b];
+        if (ctx < 0) ctx = 0;
+        if (ctx > Cmax) ctx = Cmax;
+        const int n = (bl < Cmax - ctx) ? bl : Cmax - ctx;
+        for (int t = 0; t < n; ++t) {
+            int slot = accepted_idx[(size_t)b * L + t];
+            if (slot < 0) slot = 0;
+            if (slot > N - 1) slot = N - 1;
+            for (int h = 0; h < H; ++h) {
+                const size_t src = (((size_t)b * H + h) * N + slot) * row;
+                const size_t dst = (((size_t)b * H + h) * Cmax + (size_t)(ctx + t)) * row;
+                memcpy((unsigned char *)k_cache + dst, (const unsigned char *)k_new + src, row);
+                memcpy((unsigned char *)v_cache + dst, (const unsigned char *)v_new + src, row);
+            }
+        }
+        ctx_len_out[b] = ctx + n;
+        if (n_committed) n_committed[b] = n;
+        if (hidden && hidden_last && bl > 0) {
+            int slot = accepted_idx[(size_t)b * L + bl - 1];
+            if (slot < 0) slot = 0;
+            if (slot > N - 1) slot = N - 1;
+            memcpy((unsigned char *)hidden_last + (size_t)b * Dh * es,
+                   (const unsigned char *)hidden + ((size_t)b * N + slot) * Dh * es, (size_t)Dh * es);
+        }
     }
 }

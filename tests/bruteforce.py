@@ -95,3 +95,44 @@ def greedy_rollout(start_prefix, n_steps, V, salt=0):
         out.append(t)
         seq.append(t)
     return out
+
+
+class ToyAttentionLM:
+    """A one-layer attention "LLM" in numpy float64, for end-to-end checks of the whole step.
+
+    Token t contributes key Ek[t] and value Ev[t] (per head); the model's output at the last token
+    of a sequence is plain softmax attention of Eq[last token] over the keys of ALL tokens of the
+    sequence (itself included), heads concatenated, times a readout matrix.  It is a deterministic
+    function of the sequence, so greedy decoding with it is well defined."""
+
+    def __init__(self, V, H, D, seed):
+        rng = np.random.default_rng(seed)
+        self.V, self.H, self.D = V, H, D
+        self.Eq = rng.standard_normal((V, H, D)).astype(np.float32)
+        self.Ek = rng.standard_normal((V, H, D)).astype(np.float32)
+        self.Ev = rng.standard_normal((V, H, D)).astype(np.float32)
+        self.Wout = rng.standard_normal((H * D, V)).astype(np.float32)
+        self.scale = 1.0 / np.sqrt(D)
+
+    def logits_from_attn(self, out_hd):
+        """out_hd [..., H, D] (attention output at a token) -> logits [..., V]."""
+        o = np.asarray(out_hd, np.float64)
+        return o.reshape(o.shape[:-2] + (self.H * self.D,)) @ self.Wout.astype(np.float64)
+
+    def next_logits(self, seq):
+        seq = np.asarray(seq, np.int64)
+        q = self.Eq[seq[-1]].astype(np.float64)              # [H, D]
+        k = self.Ek[seq].astype(np.float64)                  # [T, H, D]
+        v = self.Ev[seq].astype(np.float64)
+        out = np.empty((self.H, self.D))
+        for h in range(self.H):
+            s = (k[:, h, :] @ q[h]) * self.scale
+            w = np.exp(s - s.max())
+            out[h] = (w / w.sum()) @ v[:, h, :]
+        return self.logits_from_attn(out)
+
+    def greedy(self, prompt, n_new):
+        seq = list(prompt)
+        for _ in range(n_new):
+            seq.append(int(np.argmax(self.next_logits(seq))))
+        return seq
