@@ -203,6 +203,51 @@ def main():
     attn_us = a0.elapsed_time(a1) * 1e3 / args.steps
     achieved = attn_bytes_mean / (attn_us * 1e-6) / 1e9
 
+    # ---- the other kernels one by one (reported beside the headline figures, not part of them) ------
+    # rd_commit (what follows the step, Sec. 3.4) appends the accepted rows behind position
+    # ctx_len - L here, because the synthetic caches are allocated full.
+    for c in copies:
+        c["ctx_commit"] = (c["ctx_len"] - cfg.L).clamp_(min=0)
+        c["ctx_out"] = torch.empty_like(c["ctx_len"])
+        c["n_comm"] = torch.empty_like(c["ctx_len"])
+
+    def k_dedup(c):
+        rd.rd_dedup(c["beams"], c["ctx_len"], out=c["dedup"])
+
+    def k_accept(c):
+        rd.rd_accept(c["logits"], c["beams"], c["dedup"]["unpack_index"], c["dedup"]["n_packed"],
+                     out=c["accept"], workspace=ws_acc)
+
+    def k_commit(c):
+        rd.rd_commit(c["k_new"], c["v_new"], c["accept"]["accepted_idx"], c["accept"]["best_len"], c["ctx_commit"],
+                     c["k_cache"], c["v_cache"], ctx_len_out=c["ctx_out"], n_committed=c["n_comm"])
+
+    def time_kernel(fn):
+        n = max(R, args.steps // 4)
+        with torch.cuda.stream(stream):
+            for c in copies:
+                fn(c)
+            g = None
+            if use_graph:
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=stream):
+                    for c in copies:
+                        fn(c)
+            k0, k1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            k0.record(stream)
+            for i in range(n // R):
+                if g is not None:
+                    g.replay()
+                else:
+                    for c in copies:
+                        fn(c)
+            k1.record(stream)
+        torch.cuda.synchronize()
+        return round(k0.elapsed_time(k1) * 1e3 / (n // R * R), 3)
+
+    kernels_us = {"rd_dedup": time_kernel(k_dedup), "rd_tree_attn": round(attn_us, 3),
+                  "rd_accept": time_kernel(k_accept), "rd_commit": time_kernel(k_commit)}
+
     result = {
         "metric": "verify_steps_per_sec",
         "value": round(steps_per_s, 2),
@@ -227,6 +272,7 @@ def main():
         "packed_tokens_per_sec": round(packed_mean * steps_per_s, 1),
         "packed_tokens_per_step": round(packed_mean, 2),
         "wall_ms_timed_region": round(wall_ms, 3),
+        "kernels_us": kernels_us,
         "roofline": {
             "kernel": "rd_tree_attn",
             "bound": "hbm",

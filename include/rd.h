@@ -12,7 +12,10 @@
  *                 with that mask, against the KV cache (Sec. 3.3, 3.4);
  *   rd_accept     greedy "token match" acceptance (Sec. 3.4, Fig. 2): arg max of the
  *                 LLM's logits per packed token, longest accepted prefix per candidate,
- *                 best candidate, next token.
+ *                 best candidate, next token;
+ *   rd_commit     what follows acceptance (Sec. 3.4): the accepted tokens join the context
+ *                 (their K/V rows are appended to the cache, ctx_len grows) and the LLM's
+ *                 hidden state at the last accepted token is picked out for the next draft.
  *
  * Conventions for every entry point
  *   - All tensor pointers are DEVICE pointers to dense row-major arrays (last index
@@ -149,6 +152,35 @@ int rd_accept(const float *logits, const int32_t *beams, const int32_t *unpack_i
               int32_t *argmax_out, int32_t *n_accept, int32_t *best_beam,
               int32_t *best_len, int32_t *next_token, int32_t *accepted_idx,
               void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * rd_commit — append the accepted tokens to the context (Sec. 3.4: "append accepted tokens to
+ * the end of previously generated tokens"; the LLM's hidden state at the last accepted token
+ * and next_token start the next draft).  Runs after rd_accept, on its outputs.
+ *
+ * For every sequence b, with bl = best_len[b] clamped to [0, L], c = ctx_len[b] clamped to
+ * [0, Cmax] and n = min(bl, Cmax - c) (what still fits in the cache):
+ *   k_cache[b,h,c+t,:] = k_new[b,h,accepted_idx[b][t],:]   for t < n and every head h
+ *   v_cache likewise;  rows are copied bit for bit
+ *   ctx_len_out[b] = c + n;   n_committed[b] = n (a caller sees n < best_len[b] when the
+ *   cache is full)
+ *   hidden_last[b,:] = hidden[b, accepted_idx[b][bl-1], :]  if bl > 0, else left unchanged
+ * Slots in accepted_idx are clamped to [0, N-1].  Nothing else in the caches is touched.
+ *
+ *   k_new, v_new : [B,H,N,D];  k_cache, v_cache : [B,H,Cmax,D] (updated in place), element
+ *   type by `dt` as for rd_tree_attn, all 16-byte aligned.
+ *   accepted_idx : int32 [B,L];  best_len, ctx_len : int32 [B];  ctx_len_out : int32 [B],
+ *   must not overlap ctx_len (workgroups read ctx_len while another writes the new value:
+ *   keep two arrays and alternate).  n_committed : int32 [B] or NULL.
+ *   hidden : [B,N,Dh] and hidden_last : [B,Dh] of the same element type, 16-byte aligned,
+ *   Dh * element size a multiple of 16; both NULL (and Dh = 0) to skip.
+ * No workspace.  D in {64, 128} as for rd_tree_attn; Cmax >= 1.
+ */
+int rd_commit(const void *k_new, const void *v_new, const int32_t *accepted_idx,
+              const int32_t *best_len, const int32_t *ctx_len,
+              int B, int H, int N, int D, int Cmax, int L, rd_dtype dt,
+              void *k_cache, void *v_cache, int32_t *ctx_len_out, int32_t *n_committed,
+              const void *hidden, int Dh, void *hidden_last, void *stream);
 
 #ifdef __cplusplus
 }

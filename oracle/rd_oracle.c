@@ -3,8 +3,9 @@
  *
  * A plain, slow, definition-level implementation of what the verification step
  * computes (dynamic tree attention, Sec. 3.3 and App. A.1; verification, greedy
- * acceptance and the commit of the accepted tokens, Sec. 3.4).  It exists so that the HIP path can be checked against
- * something that is easy to compare with the paper by eye.  It shares no code
+ * acceptance and the commit of the accepted tokens, Sec. 3.4).  It exists so that
+ * the HIP path can be checked against something that is easy to compare with the
+ * paper by eye.  It shares no code
  * with the HIP path and must never be called from it; only tests, the smoke
  * check and the benchmark's CPU-baseline leg use it.
  *

@@ -36,6 +36,7 @@ EXPORTS = {
     "rd_tree_attn": (_i, [_vp] * 8 + [_i, _i, _i, _i, _i, _i, _f, _vp, _vp, _sz, _vp]),
     "rd_accept_workspace": (_sz, [_i, _i, _i, _i]),
     "rd_accept": (_i, [_vp] * 5 + [_i, _i, _i, _i] + [_vp] * 6 + [_vp, _sz, _vp]),
+    "rd_commit": (_i, [_vp] * 5 + [_i] * 7 + [_vp] * 4 + [_vp, _i, _vp, _vp]),
 }
 for _name, (_res, _args) in EXPORTS.items():
     _fn = getattr(_lib, _name)
@@ -197,3 +198,35 @@ def rd_accept(logits, beams, unpack_index, n_packed, root_token: Optional[torch.
         _ptr(workspace, torch.uint8, None, "workspace"), workspace.numel(), _stream())
     _check(code, "rd_accept")
     return out
+
+
+def rd_commit(k_new, v_new, accepted_idx, best_len, ctx_len, k_cache, v_cache,
+              ctx_len_out: Optional[torch.Tensor] = None, n_committed: Optional[torch.Tensor] = None,
+              hidden: Optional[torch.Tensor] = None, hidden_last: Optional[torch.Tensor] = None) -> dict:
+    """Appends the accepted packed tokens' K/V rows to the caches IN PLACE (see include/rd.h,
+    rd_commit); returns dict(ctx_len, n_committed, hidden_last)."""
+    B, H, N, D = k_new.shape
+    Cmax = k_cache.shape[2]
+    L = accepted_idx.shape[1]
+    dev = k_new.device
+    i32 = torch.int32
+    dt = _dt_code(k_new)
+    if ctx_len_out is None:
+        ctx_len_out = torch.empty((B,), dtype=i32, device=dev)
+    if n_committed is None:
+        n_committed = torch.empty((B,), dtype=i32, device=dev)
+    Dh = 0
+    if hidden is not None:
+        Dh = hidden.shape[2]
+        if hidden_last is None:
+            hidden_last = torch.zeros((B, Dh), dtype=hidden.dtype, device=dev)
+    code = _lib.rd_commit(
+        _ptr(k_new, None, (B, H, N, D), "k_new"), _ptr(v_new, k_new.dtype, (B, H, N, D), "v_new"),
+        _ptr(accepted_idx, i32, (B, L), "accepted_idx"), _ptr(best_len, i32, (B,), "best_len"),
+        _ptr(ctx_len, i32, (B,), "ctx_len"), B, H, N, D, Cmax, L, dt,
+        _ptr(k_cache, k_new.dtype, (B, H, Cmax, D), "k_cache"), _ptr(v_cache, k_new.dtype, (B, H, Cmax, D), "v_cache"),
+        _ptr(ctx_len_out, i32, (B,), "ctx_len_out"), _ptr(n_committed, i32, (B,), "n_committed"),
+        _ptr(hidden, k_new.dtype, (B, N, Dh), "hidden") if hidden is not None else None, Dh,
+        _ptr(hidden_last, k_new.dtype, (B, Dh), "hidden_last") if hidden is not None else None, _stream())
+    _check(code, "rd_commit")
+    return dict(ctx_len=ctx_len_out, n_committed=n_committed, hidden_last=hidden_last)

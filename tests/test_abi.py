@@ -31,7 +31,7 @@ def _declared_symbols():
 def test_header_symbols_exported(lib):
     names = _declared_symbols()
     assert names == sorted(["rd_strerror", "rd_version", "rd_dedup", "rd_tree_attn_workspace",
-                            "rd_tree_attn", "rd_accept_workspace", "rd_accept"])
+                            "rd_tree_attn", "rd_accept_workspace", "rd_accept", "rd_commit"])
     raw = ctypes.CDLL(LIB)
     for n in names:
         assert hasattr(raw, n), n
@@ -122,6 +122,28 @@ def test_accept_argument_errors(lib):
     assert _accept(lib, req=None) == INVALID
     assert _accept(lib, ws=None) == WORKSPACE
     assert _accept(lib, ws_bytes=8) == WORKSPACE
+
+
+def _commit(lib, B=1, H=2, N=8, D=64, Cmax=16, L=4, dt=0, src=FAKE, cache=FAKE, ctx=FAKE, ctx_out=FAKE + 64,
+            hidden=None, Dh=0, hid_last=None):
+    return lib.rd_commit(src, src, FAKE, FAKE, ctx, B, H, N, D, Cmax, L, dt, cache, cache, ctx_out, None,
+                         hidden, Dh, hid_last, None)
+
+
+def test_commit_argument_errors(lib):
+    assert _commit(lib, B=0) == INVALID
+    assert _commit(lib, Cmax=0) == INVALID
+    assert _commit(lib, D=96) == UNSUPPORTED
+    assert _commit(lib, N=129) == UNSUPPORTED
+    assert _commit(lib, dt=5) == UNSUPPORTED
+    assert _commit(lib, src=None) == INVALID
+    assert _commit(lib, cache=None) == INVALID
+    assert _commit(lib, cache=FAKE + 8) == INVALID            # 16-byte alignment
+    assert _commit(lib, ctx_out=None) == INVALID
+    assert _commit(lib, ctx_out=FAKE) == INVALID              # must not be ctx_len itself
+    assert _commit(lib, hidden=FAKE, Dh=0, hid_last=FAKE) == INVALID
+    assert _commit(lib, hidden=FAKE, Dh=6, hid_last=FAKE) == INVALID   # 24 bytes: not a multiple of 16
+    assert _commit(lib, hidden=FAKE, Dh=8, hid_last=None) == INVALID
 
 
 def test_binding_rejects_host_tensors():

@@ -1,0 +1,111 @@
+"""GPU parity for rd_commit (bit-exact against the CPU oracle) and the whole step in a loop:
+rd_dedup -> rd_tree_attn -> rd_accept -> rd_commit must reproduce plain greedy decoding of a toy
+attention LM (the guarantee of Sec. 3.4), with no host round trip inside a step."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from bruteforce import ToyAttentionLM
+from gpu_util import announce, dev, host
+from paper_2403_09919_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def rd():
+    assert torch.cuda.is_available(), "GPU tests need a device"
+    from paper_2403_09919_amd import binding
+    return binding
+
+
+def _case(rng, B, H, N, D, Cmax, L, dtype, Dh):
+    def t(shape):
+        x = rng.standard_normal(shape).astype(np.float32)
+        return synth.f32_to_bf16_bits(x) if dtype == "bf16" else x
+    k_new, v_new, kc, vc = t((B, H, N, D)), t((B, H, N, D)), t((B, H, Cmax, D)), t((B, H, Cmax, D))
+    best_len = rng.integers(0, L + 1, B).astype(np.int32)
+    acc = np.full((B, L), -1, np.int32)
+    for b in range(B):
+        acc[b, :best_len[b]] = rng.choice(N, best_len[b], replace=False)
+    ctx = rng.integers(0, Cmax + 1, B).astype(np.int32)
+    ctx[0] = Cmax - 1                      # capacity edge
+    if B > 1:
+        best_len[1] = 0
+        acc[1] = -1
+    hidden = t((B, N, Dh)) if Dh else None
+    return k_new, v_new, acc, best_len, ctx, kc, vc, hidden
+
+
+@pytest.mark.parametrize("dtype,D,B,H,N,L,Cmax,Dh", [
+    ("f32", 64, 3, 4, 16, 4, 40, 8),
+    ("bf16", 128, 4, 8, 40, 5, 64, 256),
+    ("bf16", 128, 16, 52, 80, 5, 96, 0),
+    ("f32", 128, 1, 1, 128, 128, 200, 4),
+    ("bf16", 64, 2, 3, 1, 1, 1, 8),
+])
+def test_commit_matches_oracle(rd, dtype, D, B, H, N, L, Cmax, Dh):
+    announce(f"commit {dtype} D={D} B={B} H={H} N={N} L={L} Cmax={Cmax} Dh={Dh}")
+    rng = np.random.default_rng(5 + D + B)
+    k_new, v_new, acc, best_len, ctx, kc, vc, hidden = _case(rng, B, H, N, D, Cmax, L, dtype, Dh)
+    ref = oracle.commit(k_new, v_new, acc, best_len, ctx, kc, vc, dtype, hidden=hidden)
+    kc_d, vc_d = dev(kc), dev(vc)
+    got = rd.rd_commit(dev(k_new), dev(v_new), dev(acc), dev(best_len), dev(ctx), kc_d, vc_d,
+                       hidden=None if hidden is None else dev(hidden))
+    torch.cuda.synchronize()
+    assert np.array_equal(host(kc_d), ref["k_cache"]) and np.array_equal(host(vc_d), ref["v_cache"])
+    assert np.array_equal(host(got["ctx_len"]), ref["ctx_len"])
+    assert np.array_equal(host(got["n_committed"]), ref["n_committed"])
+    if hidden is not None:
+        assert np.array_equal(host(got["hidden_last"]), ref["hidden_last"])
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_decode_loop_reproduces_greedy_decoding(rd, seed):
+    announce(f"decode loop seed={seed}")
+    lm = ToyAttentionLM(V=64, H=2, D=64, seed=200 + seed)
+    prompt = [3, 17, 5, 9]
+    n_new, W, L, Cmax = 24, 4, 4, 64
+    truth = lm.greedy(prompt, n_new + 2 * L)
+    rng = np.random.default_rng(seed)
+    H, D, N = lm.H, lm.D, W * L
+    Eq, Ek, Ev = (torch.from_numpy(x).cuda() for x in (lm.Eq, lm.Ek, lm.Ev))
+    Wout = torch.from_numpy(lm.Wout).cuda()
+    kc = torch.zeros((1, H, Cmax, D), device="cuda")
+    vc = torch.zeros((1, H, Cmax, D), device="cuda")
+    seq = list(prompt)
+    pre = torch.tensor(seq[:-1], device="cuda")
+    kc[0, :, :len(pre)] = Ek[pre].permute(1, 0, 2)
+    vc[0, :, :len(pre)] = Ev[pre].permute(1, 0, 2)
+    ctx = [torch.tensor([len(pre)], dtype=torch.int32, device="cuda"), torch.zeros(1, dtype=torch.int32, device="cuda")]
+    ws_attn = rd.new_workspace(rd.rd_tree_attn_workspace(1, H, N, D, Cmax, rd.RD_F32), "cuda")
+    ws_acc = rd.new_workspace(rd.rd_accept_workspace(1, W, L, lm.V), "cuda")
+    steps = 0
+    while len(seq) < len(prompt) + n_new:
+        root = seq[-1]
+        beams = np.empty((1, W, L), np.int32)
+        for w in range(W):
+            beams[0, w, 0] = root
+            cont = truth[len(seq):len(seq) + L - 1]
+            good = rng.integers(0, L) if rng.random() < 0.6 else 0
+            for j in range(1, L):
+                beams[0, w, j] = cont[j - 1] if j <= good else rng.integers(0, lm.V)
+        beams_d = dev(beams)
+        d = rd.rd_dedup(beams_d, ctx[0])
+        tok = d["packed_tokens"][0].clamp(min=0).long()       # pad slots read token 0 and are ignored
+        q = Eq[tok].permute(1, 0, 2).contiguous()[None]
+        kn = Ek[tok].permute(1, 0, 2).contiguous()[None]
+        vn = Ev[tok].permute(1, 0, 2).contiguous()[None]
+        out = rd.rd_tree_attn(q, kc, vc, ctx[0], kn, vn, d["n_packed"], d["tree_mask_bits"], lm.scale,
+                              workspace=ws_attn)
+        logits = (out[0].permute(1, 0, 2).reshape(N, H * D) @ Wout)[None].contiguous()
+        acc = rd.rd_accept(logits, beams_d, d["unpack_index"], d["n_packed"], workspace=ws_acc)
+        rd.rd_commit(kn, vn, acc["accepted_idx"], acc["best_len"], ctx[0], kc, vc, ctx_len_out=ctx[1])
+        ctx.reverse()
+        bl, bw, nxt = int(acc["best_len"][0]), int(acc["best_beam"][0]), int(acc["next_token"][0])
+        assert bl >= 1 and int(ctx[0][0]) == len(seq) - 1 + bl
+        seq = seq[:-1] + [int(t) for t in beams[0, bw, :bl]] + [nxt]
+        steps += 1
+    assert seq == truth[:len(seq)]
+    assert steps < n_new
