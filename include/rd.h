@@ -31,7 +31,8 @@
  *     too small) are rejected before anything is launched.  Data preconditions that
  *     live on the device (0 <= ctx_len[b] <= Cmax, n_packed[b] <= N, logits free of
  *     NaN) are not checked; ctx_len and n_packed are clamped into range.
- *   - Limits: 1 <= W <= 64, L >= 1, N = W*L <= 128, D in {64, 128}.
+ *   - Limits: 1 <= W <= 128, L >= 1, N = W*L <= 384, D in {64, 128} (the paper's widest beams,
+ *     Sec. 4.3: 70 candidates of 5 tokens, are N = 350).
  */
 #ifndef RD_H
 #define RD_H
@@ -53,8 +54,8 @@ typedef enum {
     RD_ERR_HIP = -4          /* a kernel launch failed (hipGetLastError) */
 } rd_status;
 
-#define RD_MAX_W 64
-#define RD_MAX_N 128
+#define RD_MAX_W 128
+#define RD_MAX_N 384
 
 /* Static description of a status code; never NULL. */
 const char *rd_strerror(int code);

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "librd.so")
 
 RD_F32, RD_BF16 = 0, 1
 RD_OK = 0
-RD_MAX_W, RD_MAX_N = 64, 128
+RD_MAX_W, RD_MAX_N = 128, 384
 
 if not os.path.exists(LIB_PATH):
     raise ImportError("librd.so is not built: run `python -m paper_2403_09919_amd.build` "

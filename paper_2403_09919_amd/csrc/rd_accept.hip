@@ -93,6 +93,7 @@ __global__ __launch_bounds__(kAccThreads) void rd_accept_kernel(
     __shared__ int s_am[RD_MAX_N];
     __shared__ int s_beam[RD_MAX_N], s_slot[RD_MAX_N];
     __shared__ uint32_t s_seq_last;
+    __shared__ int s_best;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int chunk = blockIdx.x, p = blockIdx.y, b = blockIdx.z;
@@ -106,10 +107,13 @@ __global__ __launch_bounds__(kAccThreads) void rd_accept_kernel(
     // sequence, but nobody knows which one that is: every workgroup fetches them now (a few
     // hundred bytes, overlapped with the logit stream) instead of paying two dependent round
     // trips to memory per accepted token at the very end.
-    int my_beam = 0, my_slot = 0, my_root = 0;
-    if (tid < N) {
-        my_beam = beams[(size_t)b * N + tid];
-        my_slot = unpack_index[(size_t)b * N + tid];
+    constexpr int kPre = (RD_MAX_N + kAccThreads - 1) / kAccThreads;     // tokens per thread
+    int my_beam[kPre], my_slot[kPre], my_root = 0;
+#pragma unroll
+    for (int u = 0; u < kPre; ++u) {
+        const int e = min(u * kAccThreads + tid, N - 1);
+        my_beam[u] = beams[(size_t)b * N + e];
+        my_slot[u] = unpack_index[(size_t)b * N + e];
     }
     if (root_token != nullptr) my_root = root_token[b];
 
@@ -185,21 +189,27 @@ __global__ __launch_bounds__(kAccThreads) void rd_accept_kernel(
         s_am[r] = am;
         argmax_out[(size_t)b * N + r] = am;
     }
-    if (tid < N) {
-        s_beam[tid] = my_beam;
-        s_slot[tid] = min(max(my_slot, 0), N - 1);
+#pragma unroll
+    for (int u = 0; u < kPre; ++u) {
+        const int e = u * kAccThreads + tid;
+        if (e < N) {
+            s_beam[e] = my_beam[u];
+            s_slot[e] = min(max(my_slot[u], 0), N - 1);
+        }
     }
+    if (tid == 0) s_best = -1;
     __syncthreads();                                      // every key has been read
     RD_TR(4);
     for (int r = tid; r < P; r += kAccThreads) row_keys[(size_t)b * N + r] = 0;   // ready for the next call
     if (tid == 0) seq_counters[b] = 0;
-    if (wave != 0) return;
 
-    const int w = lane;
-    int len = 0;
+    // one thread per candidate (W <= RD_MAX_W <= kAccThreads)
+    static_assert(RD_MAX_W <= kAccThreads && RD_MAX_W <= 256, "one thread per candidate, index in 8 bits");
+    const int w = tid;
     if (w < W) {
         const int *bm = s_beam + w * L;
         const int *ui = s_slot + w * L;
+        int len = 0;
         bool ok = (root_token == nullptr) || (bm[0] == my_root);
         while (ok) {
             ++len;
@@ -207,16 +217,16 @@ __global__ __launch_bounds__(kAccThreads) void rd_accept_kernel(
             ok = (s_am[ui[len - 1]] == bm[len]);
         }
         n_accept[(size_t)b * W + w] = len;
+        // best candidate: longest accepted prefix, smallest index among equals
+        atomicMax(&s_best, (len << 8) | (255 - w));
     }
-    // best candidate: longest accepted prefix, smallest index among equals
-    int key = (w < W) ? (len << 8) | (255 - w) : -1;
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) key = max(key, __shfl_xor(key, off, 64));
+    __syncthreads();
+    const int key = s_best;
     const int bl = key >> 8;
     const int bw = 255 - (key & 255);
     const int *bui = s_slot + bw * L;
-    for (int t = lane; t < L; t += 64) accepted_idx[(size_t)b * L + t] = (t < bl) ? bui[t] : -1;
-    if (lane == 0) {
+    for (int t = tid; t < L; t += kAccThreads) accepted_idx[(size_t)b * L + t] = (t < bl) ? bui[t] : -1;
+    if (tid == 0) {
         best_beam[b] = bw;
         best_len[b] = bl;
         next_token[b] = (bl > 0) ? s_am[bui[bl - 1]] : my_root;

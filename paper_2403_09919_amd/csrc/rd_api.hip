@@ -6,7 +6,7 @@ extern "C" const char *rd_strerror(int code)
     switch (code) {
     case RD_OK: return "ok";
     case RD_ERR_INVALID_ARG: return "invalid argument (null pointer, non-positive size or misaligned buffer)";
-    case RD_ERR_UNSUPPORTED: return "unsupported size or dtype (limits: W <= 64, W*L <= 128, D in {64,128})";
+    case RD_ERR_UNSUPPORTED: return "unsupported size or dtype (limits: W <= 128, W*L <= 384, D in {64,128})";
     case RD_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case RD_ERR_HIP: return "HIP kernel launch failed";
     default: return "unknown rd status";

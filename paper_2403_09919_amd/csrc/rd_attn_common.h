@@ -23,7 +23,9 @@ struct AttnPlan {
     int S;             // context splits per (sequence, head)
     int fuse_tree;     // 1: the packed keys are the last block of the last context range, not a range of their own
     int n_part;        // workgroups (and partial results) per head: S, or S + 1 with a separate packed-key range
-    int rows_pad;      // packed rows padded to a multiple of 16
+    int rows_pad;      // packed rows padded to a multiple of 16 (fp32 kernel's partial layout)
+    int rg_tiles;      // bf16 kernel: 16-row tiles of packed rows per workgroup (a row group)
+    int n_rg;          // bf16 kernel: row groups per (sequence, head); 1 unless N is large
     size_t counters_bytes;
     size_t partial_floats;   // floats per partial: m[rows_pad] + l[rows_pad] + O[rows_pad][D]
     size_t total_bytes;
@@ -52,11 +54,20 @@ static inline AttnPlan attn_plan(int B, int H, int N, int D, int Cmax, size_t el
     const double kv_bytes = 2.0 * (double)BH * Cmax * D * (double)elem_bytes;
     const bool small = kv_bytes < 64e6;          // latency-bound: few blocks per range
     static const int waves_env = env_int("RD_ATTN_WAVES", 0);
-    p.waves = (elem_bytes == 2 && D == 128 && N <= 80 && small) ? 8 : 4;
-    if (waves_env == 4 || (waves_env == 8 && elem_bytes == 2 && D == 128 && N <= 80)) p.waves = waves_env;
+    p.waves = (elem_bytes == 2 && D == 128 && small) ? 8 : 4;
+    if (waves_env == 4 || (waves_env == 8 && elem_bytes == 2 && D == 128)) p.waves = waves_env;
     const int block_keys = elem_bytes == 2 ? 32 * p.waves : kBlockKeys;
     const int nblk = (Cmax + block_keys - 1) / block_keys;
-    const int nq = (N + 15) / 16;
+    // Packed rows per workgroup: all of them while they fit the register budget (5 row tiles at
+    // D = 128, 8 at D = 64); wider beams are cut into row groups of 3 (4) tiles, each a workgroup
+    // of its own per key range (K/V are then re-read per group, from L2 mostly).
+    const int nq_all = (N + 15) / 16;
+    static const int tiles_env = env_int("RD_ATTN_ROWTILES", 0);       // tuning: largest single group
+    int nq_max = D == 128 ? 5 : 8;
+    const int nq_grp = D == 128 ? 3 : 4;
+    if (tiles_env >= nq_grp && tiles_env <= nq_max) nq_max = tiles_env;
+    const int nq = elem_bytes == 2 ? (nq_all <= nq_max ? nq_all : nq_grp) : nq_all;
+    const int n_rg = elem_bytes == 2 ? (nq_all + nq - 1) / nq : 1;
     const long long slots = (elem_bytes == 2 && p.waves == 4 && nq <= 5) ? 512 : 256;
     const bool can_fuse = elem_bytes == 2;
     const double blk_bytes = 2.0 * block_keys * D * (double)elem_bytes;      // K and V of one block of one head
@@ -69,11 +80,11 @@ static inline AttnPlan attn_plan(int B, int H, int N, int D, int Cmax, size_t el
         const int per = (nblk + S - 1) / S;
         const bool fuse = can_fuse && per >= 4;
         const int n_part = S + (fuse ? 0 : 1);
-        const long long wg = BH * S;
+        const long long wg = BH * S * n_rg;
         const long long rounds = wg <= slots ? (wg + 255) / 256 : (wg + slots - 1) / slots * (slots / 256);
         double T = (double)rounds * (per + (fuse ? 1 : 0)) * t_blk;
         if (T < t_hbm) T = t_hbm;
-        if (n_part > 1) T += 3e-6 + 2.0 * (double)BH * n_part * part_bytes / 4e12;
+        if (n_part > 1) T += 3e-6 + 2.0 * (double)BH * n_rg * n_part * part_bytes / 4e12;
         if (T < best_T * (1.0 - 1e-9)) { best_T = T; best_S = S; }
     }
     static const int forced = env_int("RD_ATTN_SPLITS", 0);
@@ -84,9 +95,14 @@ static inline AttnPlan attn_plan(int B, int H, int N, int D, int Cmax, size_t el
     if (fuse_env >= 0 && can_fuse && nblk > 0) p.fuse_tree = fuse_env ? 1 : 0;
     p.n_part = p.S + (p.fuse_tree ? 0 : 1);
     p.rows_pad = (N + 15) / 16 * 16;
-    p.counters_bytes = ((size_t)BH * sizeof(uint32_t) + 255) / 256 * 256;
-    p.partial_floats = (size_t)p.rows_pad * (2 + D);
-    p.total_bytes = p.counters_bytes + (p.n_part > 1 ? (size_t)BH * p.n_part * p.partial_floats * sizeof(float) : 0);
+    p.rg_tiles = nq;
+    p.n_rg = n_rg;
+    p.counters_bytes = ((size_t)BH * n_rg * sizeof(uint32_t) + 255) / 256 * 256;
+    // floats per partial: fp32 kernel m[rows_pad] + l[rows_pad] + O[rows_pad][D] per (b,h,part);
+    // bf16 kernel the same for the rows of one group, per (b,h,group,part)
+    p.partial_floats = elem_bytes == 2 ? (size_t)nq * 16 * (2 + D) : (size_t)p.rows_pad * (2 + D);
+    p.total_bytes = p.counters_bytes +
+                    (p.n_part > 1 ? (size_t)BH * n_rg * p.n_part * p.partial_floats * sizeof(float) : 0);
     return p;
 }
 
@@ -98,6 +114,7 @@ struct AttnArgs {
     uint32_t *counters;
     float *partials;
     int B, H, N, Cmax, S, words, rows_pad;
+    int n_rg;      // row groups per (sequence, head) (bf16 kernel; each is NQ*16 rows of the template)
     int fuse_tree; // 1: packed keys walked by the workgroup of the last context range (see AttnPlan)
     int xcd_remap; // 1: workgroup i serves XCD i%8's share of the heads (needs B*H % 8 == 0)
     float scale_log2e;

@@ -21,7 +21,8 @@ RD_TRACE_DEFINE(rd_debug_set_trace_dedup)
 
 namespace {
 
-constexpr int kDedupThreads = 256;
+constexpr int kDedupThreads = 384;
+constexpr int kMaskWords = (RD_MAX_N + 63) / 64;
 
 __global__ __launch_bounds__(kDedupThreads) void rd_dedup_kernel(
     const int32_t *__restrict__ beams, const int32_t *__restrict__ ctx_len, int W, int L,
@@ -34,7 +35,7 @@ __global__ __launch_bounds__(kDedupThreads) void rd_dedup_kernel(
     __shared__ int32_t s_owner[RD_MAX_N];          // prefix_tree of this sequence
     __shared__ int32_t s_slot[RD_MAX_N];           // unpack_index of this sequence
     __shared__ int32_t s_base[RD_MAX_W + 1], s_first[RD_MAX_W + 1];
-    __shared__ uint64_t s_bits[RD_MAX_N][2];       // mask row of each packed slot
+    __shared__ uint64_t s_bits[RD_MAX_N][kMaskWords];   // mask row of each packed slot
     __shared__ int s_P;
 
     const int b = blockIdx.x;
@@ -55,8 +56,8 @@ __global__ __launch_bounds__(kDedupThreads) void rd_dedup_kernel(
     if (tok) {
         s_beam[e] = beams[seq + e];
         s_owner[e] = i;
-        s_bits[e][0] = 0;
-        s_bits[e][1] = 0;
+#pragma unroll
+        for (int w = 0; w < kMaskWords; ++w) s_bits[e][w] = 0;
     }
     if (tid < W) s_first[tid] = L;
     __syncthreads();
@@ -123,13 +124,17 @@ __global__ __launch_bounds__(kDedupThreads) void rd_dedup_kernel(
         packed_tokens[seq + slot] = s_beam[e];
         parent[seq + slot] = j ? s_slot[e - 1] : -1;
         position_ids[seq + slot] = ctx + j;
-        uint64_t a0 = 0, a1 = 0;               // slots on the path from the root to (i, j)
+        uint64_t path[kMaskWords];             // slots on the path from the root to (i, j)
+#pragma unroll
+        for (int w = 0; w < kMaskWords; ++w) path[w] = 0;
         for (int t = 0; t <= j; ++t) {
             const int q = s_slot[i * L + t];
-            if (q < 64) a0 |= 1ull << q; else a1 |= 1ull << (q - 64);
+#pragma unroll
+            for (int w = 0; w < kMaskWords; ++w)
+                if ((q >> 6) == w) path[w] |= 1ull << (q & 63);
         }
-        s_bits[slot][0] = a0;
-        s_bits[slot][1] = a1;
+#pragma unroll
+        for (int w = 0; w < kMaskWords; ++w) s_bits[slot][w] = path[w];
     }
     rd_lds_barrier();
     RD_TR(4);

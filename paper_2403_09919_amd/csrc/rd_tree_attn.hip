@@ -3,7 +3,7 @@
 #include "rd_attn_common.h"
 
 namespace rd {
-int tree_attn_bf16(const AttnArgs &a, int D, int waves, hipStream_t stream);
+int tree_attn_bf16(const AttnArgs &a, int D, int waves, int rg_tiles, hipStream_t stream);
 int tree_attn_f32(const AttnArgs &a, int D, hipStream_t stream);
 }  // namespace rd
 
@@ -48,5 +48,6 @@ extern "C" int rd_tree_attn(const void *q, const void *k_cache, const void *v_ca
     a.scale_log2e = scale * 1.44269504088896340736f;
     a.xcd_remap = (((long long)B * H) % 8 == 0) ? 1 : 0;
     a.fuse_tree = plan.fuse_tree;
-    return dt == RD_BF16 ? rd::tree_attn_bf16(a, D, plan.waves, (hipStream_t)stream) : rd::tree_attn_f32(a, D, (hipStream_t)stream);
+    a.n_rg = plan.n_rg;
+    return dt == RD_BF16 ? rd::tree_attn_bf16(a, D, plan.waves, plan.rg_tiles, (hipStream_t)stream) : rd::tree_attn_f32(a, D, (hipStream_t)stream);
 }

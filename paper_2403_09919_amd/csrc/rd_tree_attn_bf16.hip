@@ -2,7 +2,7 @@
 // cache (Sec. 3.3, 3.4) as a split-key flash kernel on the gfx950 matrix cores.
 //
 // Decoding attention is bound by streaming K and V from HBM (512 bytes per key and head at
-// D = 128) while the packed rows (at most 128) are reused for every key, so the kernel is
+// D = 128) while the packed rows (a few dozen to a few hundred) are reused for every key, so the kernel is
 // organised around the stream:
 //   * a workgroup (4 waves) owns a contiguous key range of one (sequence, head) and walks
 //     it in blocks of 128 keys; wave w loads rows 32w..32w+31 of the block for K and for V
@@ -22,7 +22,10 @@
 //     block; the A operand V^T needs eight keys of one column per lane, which
 //     ds_read_b64_tr_b16 (LDS transpose read) delivers from the row-major V tiles, taken in
 //     the same key order.  The output accumulators therefore need no cross-wave reduction.
-//   * the partial state goes to the workspace and the last workgroup of the head merges.
+//   * the partial state goes to the workspace and the last workgroup of the head merges; a head
+//     whose keys are all walked by one workgroup writes its output directly;
+//   * beams too wide for one workgroup's registers are cut into row groups, each walking the
+//     same keys (a workgroup = one key range x one row group).
 #include "rd_attn_common.h"
 #include <type_traits>
 
@@ -95,7 +98,9 @@ __device__ __forceinline__ float quad_sum(float x)
     return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
-template <int D, int NQ, int NW>
+// TB = packed-key blocks the launch can need: ceil(N / block keys).  1 for all but the widest beams;
+// the mask words of every such block are fetched up front, so the common case should not pay for three.
+template <int D, int NQ, int NW, int TB>
 __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs a)
 {
     using G = Geo<D>;
@@ -110,6 +115,7 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
     unsigned char *sKV = sQ + kRows * G::kRowBytes;             // NW tiles [32][kRowBytes]
     unsigned char *sP = sKV + NW * G::kTileBytes;               // [NW kt][NQ][64 lanes] x 16 B
     float *sM = reinterpret_cast<float *>(sP + NW * NQ * 64 * 16);  // [NW waves][kRows]
+    uint32_t *sVis = reinterpret_cast<uint32_t *>(sM + NW * kRows);   // [NW waves][NQ][64 lanes]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -127,41 +133,50 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
     // when the context ranges are long (a.fuse_tree), one more block at the end of the last context
     // range; with a single context range the head then has one workgroup and needs no merge.
     const int n_part = a.S + (a.fuse_tree ? 0 : 1);
-    int bh, split;
-    if (a.xcd_remap) {
-        const int xcd = blockIdx.x & 7, k = blockIdx.x >> 3;
-        const int heads_here = (a.B * a.H) >> 3;          // heads served by each XCD
-        const int n_ctx = heads_here * a.S;
+    // Work items are (head, key range, row group); the row groups of one key range are neighbours
+    // in launch order so that they stream the same K/V at the same time (one reads HBM, the others L2).
+    const int n_rg = a.n_rg;
+    int bh, split, rg;
+    {
+        const int xcd = a.xcd_remap ? (int)(blockIdx.x & 7) : 0;
+        const int k = a.xcd_remap ? (int)(blockIdx.x >> 3) : (int)blockIdx.x;
+        const int heads_here = a.xcd_remap ? (a.B * a.H) >> 3 : a.B * a.H;    // heads served by this XCD
+        const int per_head = a.S * n_rg;
+        const int n_ctx = heads_here * per_head;
+        int hl;
         if (k < n_ctx) {
-            bh = (k / a.S) * 8 + xcd;
-            split = k % a.S;
+            hl = k / per_head;
+            const int r = k - hl * per_head;
+            split = r / n_rg;
+            rg = r - split * n_rg;
         } else {
-            bh = (k - n_ctx) * 8 + xcd;
+            const int r = k - n_ctx;
+            hl = r / n_rg;
+            rg = r - hl * n_rg;
             split = a.S;
         }
-    } else {
-        const int n_ctx = a.B * a.H * a.S;
-        if ((int)blockIdx.x < n_ctx) {
-            bh = blockIdx.x / a.S;
-            split = blockIdx.x % a.S;
-        } else {
-            bh = blockIdx.x - n_ctx;
-            split = a.S;
-        }
+        bh = a.xcd_remap ? hl * 8 + xcd : hl;
     }
     const int b = bh / a.H;
     const int C = clampi(a.ctx_len[b], 0, a.Cmax);
-    const int P = clampi(a.n_packed[b], 0, a.N);
+    const int P_all = clampi(a.n_packed[b], 0, a.N);
+    // This workgroup's rows are row0 .. row0 + kRows - 1 of the packed rows; P of them are real.
+    // A packed row p sees no packed key beyond itself (the mask is lower triangular), so the group
+    // needs the packed keys [0, tree_end) only.
+    const int row0 = rg * kRows;
+    const int P = clampi(P_all - row0, 0, kRows);
+    const int Ng = min(kRows, a.N - row0);                 // rows of `out` this group owns
+    const int tree_end = min(P_all, row0 + kRows);
 
-    // Blocks this workgroup walks: nA blocks of context keys [k_begin, k_end), then nB (0 or 1)
-    // block of packed keys [0, P).  All of this is wave-uniform.
+    // Blocks this workgroup walks: nA blocks of context keys [k_begin, k_end), then nB blocks of
+    // packed keys [0, tree_end).  All of this is wave-uniform.  A group without real rows walks nothing.
     int k_begin = 0, k_end = 0;
-    if (split < a.S) ctx_range(C, a.S, split, kBlock, &k_begin, &k_end);
+    if (split < a.S && P > 0) ctx_range(C, a.S, split, kBlock, &k_begin, &k_end);
     const bool has_tree = (split == a.S) || (a.fuse_tree && split == a.S - 1);
     const int nA = (k_end - k_begin + kBlock - 1) / kBlock;
-    const int nB = (has_tree && P > 0) ? 1 : 0;
+    const int nB = (has_tree && P > 0) ? (tree_end + kBlock - 1) / kBlock : 0;
     const int nb = nA + nB;
-    const unsigned char *Qb = static_cast<const unsigned char *>(a.q) + (size_t)bh * a.N * G::kRowBytes;
+    const unsigned char *Qb = static_cast<const unsigned char *>(a.q) + ((size_t)bh * a.N + row0) * G::kRowBytes;
     const unsigned char *Kc = static_cast<const unsigned char *>(a.k_cache) + (size_t)bh * a.Cmax * G::kRowBytes;
     const unsigned char *Vc = static_cast<const unsigned char *>(a.v_cache) + (size_t)bh * a.Cmax * G::kRowBytes;
     const unsigned char *Kn = static_cast<const unsigned char *>(a.k_new) + (size_t)bh * a.N * G::kRowBytes;
@@ -176,16 +191,19 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
         const int row = min(i * kQRowsPerPass + tid / G::kChunks, P - 1);    // rows >= P are zeroed below
         qreg[i] = ldg16(Qb + max(row, 0) * G::kRowBytes + (tid % G::kChunks) * 16);
     }
-    // Visibility of this wave's 32 keys for the packed rows this lane scores (row 16*qt + r16).
-    // Context keys are visible to every row; the packed keys (one block, since N <= 128) are
-    // visible per the tree mask: wave w holds keys 32w..32w+31, i.e. half of mask word w/2.
-    // (Loaded by every workgroup; those without a packed-key block ignore it.)
-    uint64_t mword[NQ];
-    {
-        const int word = min(wave >> 1, a.words - 1);
+    // Visibility of this wave's 32 keys, in each packed-key block, for the packed rows this lane
+    // scores (row row0 + 16*qt + r16).  Context keys are visible to every row; packed keys per the
+    // tree mask: in packed-key block t wave w holds keys 32*(t*NW + w) .. +31, i.e. one half of mask
+    // word (t*NW + w)/2.  (Loaded by every workgroup; those without a packed-key block ignore it.)
+    constexpr int kTreeBlocks = TB;
+    static_assert(TB * kBlock < RD_MAX_N + kBlock, "more packed-key blocks than the largest N has");
+    uint64_t mword[kTreeBlocks][NQ];
+#pragma unroll
+    for (int t = 0; t < kTreeBlocks; ++t) {
+        const int word = min((t * NW + wave) >> 1, a.words - 1);
 #pragma unroll
         for (int qt = 0; qt < NQ; ++qt)
-            mword[qt] = a.mask_bits[((size_t)b * a.N + min(qt * 16 + r16, a.N - 1)) * a.words + word];
+            mword[t][qt] = a.mask_bits[((size_t)b * a.N + min(row0 + qt * 16 + r16, a.N - 1)) * a.words + word];
     }
 
     // This wave's slice of a block: coalesced 16-byte loads into registers; a wave-wide load
@@ -206,17 +224,41 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
         const unsigned char *kb = nb == 0 ? Qb : (ctx ? Kc : Kn);
         const unsigned char *vb = nb == 0 ? Qb : (ctx ? Vc : Vn);
         const int key0 = ctx ? k_begin : 0;
-        const int end = nb == 0 ? 1 : (ctx ? k_end : P);
+        const int end = nb == 0 ? 1 : (ctx ? k_end : tree_end);
         load_tile(kb, key0, end, kreg);
         load_tile(vb, key0, end, vreg);
     }
 
-    // visibility of this wave's packed keys (used in the packed-key block only)
+    // Visibility of this wave's packed keys (used in the packed-key blocks only).  Of a tile's 32
+    // keys this lane scores only the eight with index 4g+i and 16+4g+i, so one byte per block is
+    // all it keeps: bit 4*mt+i of byte t (row tile qt) = key 16*mt+4g+i of packed-key block t is
+    // visible to row 16*qt+r16.
+    // With up to three row tiles the bytes stay in registers.  The larger variants are short of
+    // registers: there the bytes are parked in LDS (each lane reads back only what it wrote),
+    // because a register that is first used inside the block loop but refilled from scratch memory
+    // makes the compiler wait for it, and with it for the K/V tiles in flight, in every iteration.
+    constexpr bool kVisInLds = NQ > 3;
     uint32_t vis[NQ];
+    static_assert(kTreeBlocks <= 4, "one byte per packed-key block");
 #pragma unroll
     for (int qt = 0; qt < NQ; ++qt) {
-        const bool real = (qt * 16 + r16 < P) && ((wave >> 1) < a.words);
-        vis[qt] = real ? (uint32_t)(mword[qt] >> ((wave & 1) * 32)) : 0u;
+        uint32_t packed = 0;
+        if (qt * 16 + r16 < P) {
+#pragma unroll
+            for (int t = 0; t < kTreeBlocks; ++t) {
+                if (((t * NW + wave) >> 1) < a.words) {
+                    const uint32_t v32 = (uint32_t)(mword[t][qt] >> ((wave & 1) * 32));
+                    packed |= (((v32 >> (4 * g)) & 0xfu) | (((v32 >> (16 + 4 * g)) & 0xfu) << 4)) << (8 * t);
+                }
+            }
+        }
+        if (kVisInLds) {
+            sVis[(wave * NQ + qt) * 64 + lane] = packed;
+            vis[qt] = 0;
+        } else {
+            asm volatile("" : "+v"(packed));          // computed here, not sunk into the loop's masked path
+            vis[qt] = packed;
+        }
     }
 
 #pragma unroll
@@ -275,14 +317,14 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
             // this block and the one to prefetch: tensors, first key, end of the key range.  After
             // the last block the prefetch repeats it (issued and ignored).
             const bool cur_tree = ib >= nA;
-            const int cur_key0 = cur_tree ? 0 : k_begin + ib * kBlock;
-            const int cur_end = cur_tree ? P : k_end;
+            const int cur_key0 = cur_tree ? (ib - nA) * kBlock : k_begin + ib * kBlock;
+            const int cur_end = cur_tree ? tree_end : k_end;
             const int inext = ib + 1 < nb ? ib + 1 : ib;
             const bool next_tree = inext >= nA;
             const unsigned char *next_kb = next_tree ? Kn : Kc;
             const unsigned char *next_vb = next_tree ? Vn : Vc;
-            const int next_key0 = next_tree ? 0 : k_begin + inext * kBlock;
-            const int next_end = next_tree ? P : k_end;
+            const int next_key0 = next_tree ? (inext - nA) * kBlock : k_begin + inext * kBlock;
+            const int next_end = next_tree ? tree_end : k_end;
             const int tile0 = cur_key0 + wave * G::kTileKeys;
 
             // K registers -> own LDS tile (K swizzle); then fetch the next block's K.  The prefetch
@@ -333,16 +375,20 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
                 }
             } else {
                 const uint32_t tail = rem >= 32 ? 0xffffffffu : (rem <= 0 ? 0u : ((1u << rem) - 1u));
+                const uint32_t tail8 = ((tail >> (4 * g)) & 0xfu) | (((tail >> (16 + 4 * g)) & 0xfu) << 4);
+                const int tsh = cur_tree ? 8 * (ib - nA) : 0;
 #pragma unroll
                 for (int qt = 0; qt < NQA; ++qt) {
                     {
-                        const uint32_t bits = ((cur_tree ? vis[qt] : 0xffffffffu) & tail) >> (4 * g);     // element (mt, i) at bit 16 mt + i
+                        // element (mt, i) at bit 4 mt + i; context keys are all visible
+                        const uint32_t vq = kVisInLds ? sVis[(wave * NQ + qt) * 64 + lane] : vis[qt];
+                        const uint32_t bits = (cur_tree ? (vq >> tsh) : 0xffu) & tail8;
                         float tmax = -INFINITY;
 #pragma unroll
                         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
                             for (int i = 0; i < 4; ++i) {
-                                const float sv = ((bits >> (16 * mt + i)) & 1u) ? sacc[mt][qt][i] * a.scale_log2e : -INFINITY;
+                                const float sv = ((bits >> (4 * mt + i)) & 1u) ? sacc[mt][qt][i] * a.scale_log2e : -INFINITY;
                                 sacc[mt][qt][i] = sv;
                                 tmax = fmaxf(tmax, sv);
                             }
@@ -442,11 +488,11 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
             if (g == 0) sL1[(qt * 16 + r16) * NW + wave] = l;
         }
         lds_barrier();
-        __bf16 *outp = static_cast<__bf16 *>(a.out) + (size_t)bh * a.N * D;
+        __bf16 *outp = static_cast<__bf16 *>(a.out) + ((size_t)bh * a.N + row0) * D;
 #pragma unroll
         for (int qt = 0; qt < NQ; ++qt) {
             const int qrow = qt * 16 + r16;
-            if (qrow < a.N) {
+            if (qrow < Ng) {
                 float lsum = sL1[qrow * NW];
 #pragma unroll
                 for (int w = 1; w < NW; ++w) lsum += sL1[qrow * NW + w];
@@ -468,7 +514,8 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
     // Layout of one partial: (m, l) pairs [kRows][2], then the output accumulators exactly as the
     // lanes hold them, [wave][d-tile j][row tile qt][lane][4 floats], so that every wave store
     // (and the merge's loads) covers 1 KB of contiguous memory.
-    float *part = a.partials + ((size_t)bh * n_part + split) * kPF;
+    const size_t unit = (size_t)bh * n_rg + rg;                    // (head, row group): one merge each
+    float *part = a.partials + (unit * n_part + split) * kPF;
     const int frag_off = 2 * kRows + wave * kDTW * NQ * 256 + lane * 4;    // + (j*NQ + qt)*256
     float *sL = sM;           // reuse: [NW waves][kRows]
 #pragma unroll
@@ -505,7 +552,7 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
     // is off, the merge reads with device-scope loads instead.
     RD_TR(4);
     const uint32_t off_xcd = (!a.xcd_remap || xcc_id() != (blockIdx.x & 7u)) ? 1u : 0u;
-    const int last = arrive_is_last(a.counters + bh, (uint32_t)n_part, off_xcd);
+    const int last = arrive_is_last(a.counters + unit, (uint32_t)n_part, off_xcd);
     RD_TR(5);
     if (last == kNotLast) return;
     const bool cached = (last == kLastClean);
@@ -519,9 +566,9 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
     // read of a head's partials by one compute unit is what this phase costs, so it should be a
     // single round trip whenever the partials are few).
     constexpr int kChunk = 6;
-    const float *hp = a.partials + (size_t)bh * n_part * kPF;
-    __bf16 *outp = static_cast<__bf16 *>(a.out) + (size_t)bh * a.N * D;
-    const int nqt_out = (a.N + 15) >> 4;
+    const float *hp = a.partials + unit * n_part * kPF;
+    __bf16 *outp = static_cast<__bf16 *>(a.out) + ((size_t)bh * a.N + row0) * D;
+    const int nqt_out = (Ng + 15) >> 4;
 #pragma unroll 1
     for (int qt0 = 0; qt0 < nqt_out; qt0 += 2) {
         float M[2], den[2];
@@ -594,7 +641,7 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const int qrow = (qt0 + u) * 16 + r16;
-            if (qrow < a.N) {
+            if (qrow < Ng) {
                 const bool keep = qrow < P;                               // rows beyond the packed count are zero
                 const float inv = keep ? 1.0f / den[u] : 0.f;
 #pragma unroll
@@ -606,7 +653,7 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
             }
         }
     }
-    if (tid == 0) a.counters[bh] = 0;     // leave the workspace ready for the next call
+    if (tid == 0) a.counters[unit] = 0;   // leave the workspace ready for the next call
     RD_TR(6);
 }
 
@@ -614,51 +661,64 @@ template <int D, int NQ, int NW>
 static size_t bf16_smem_bytes()
 {
     return (size_t)NQ * 16 * Geo<D>::kRowBytes + NW * Geo<D>::kTileBytes + (size_t)NW * NQ * 64 * 16 +
-           (size_t)NW * NQ * 16 * sizeof(float);
+           (size_t)NW * NQ * 16 * sizeof(float) + (size_t)NW * NQ * 64 * sizeof(uint32_t);
 }
 
-template <int D, int NQ, int NW>
+template <int D, int NQ, int NW, int TB>
 static int launch_bf16(const AttnArgs &a, hipStream_t stream)
 {
     const size_t smem = bf16_smem_bytes<D, NQ, NW>();
     static bool configured = false;          // raising the dynamic LDS limit is per kernel, once
     if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&rd_tree_attn_bf16_kernel<D, NQ, NW>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&rd_tree_attn_bf16_kernel<D, NQ, NW, TB>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
             return RD_ERR_HIP;
         configured = true;
     }
-    const unsigned grid = (unsigned)((size_t)a.B * a.H * (a.S + (a.fuse_tree ? 0 : 1)));
-    hipLaunchKernelGGL((rd_tree_attn_bf16_kernel<D, NQ, NW>), dim3(grid), dim3(NW * 64), smem, stream, a);
+    const unsigned grid = (unsigned)((size_t)a.B * a.H * (a.S + (a.fuse_tree ? 0 : 1)) * a.n_rg);
+    hipLaunchKernelGGL((rd_tree_attn_bf16_kernel<D, NQ, NW, TB>), dim3(grid), dim3(NW * 64), smem, stream, a);
     return rd_check_launch();
 }
 
+// rg_tiles = 16-row tiles per workgroup (the template's NQ); D = 128 kernels exist for 1..5 tiles,
+// D = 64 kernels for 1..8 (the plan never asks for more).  Beams with more packed keys than one
+// block (N > 32*NW) only occur with row groups, i.e. with kGroupTiles tiles.
 template <int D, int NW>
-static int dispatch_nq(const AttnArgs &a, hipStream_t stream)
+static int dispatch_nq(const AttnArgs &a, int rg_tiles, hipStream_t stream)
 {
-    switch ((a.N + 15) / 16) {
-    case 1: return launch_bf16<D, 1, NW>(a, stream);
-    case 2: return launch_bf16<D, 2, NW>(a, stream);
-    case 3: return launch_bf16<D, 3, NW>(a, stream);
-    case 4: return launch_bf16<D, 4, NW>(a, stream);
-    case 5: return launch_bf16<D, 5, NW>(a, stream);
+    constexpr int kGroupTiles = D == 128 ? 3 : 4;
+    const int tb = (a.N + 32 * NW - 1) / (32 * NW);
+    if (tb > 1) {
+        if (rg_tiles != kGroupTiles) return RD_ERR_UNSUPPORTED;
+        if (tb == 2) return launch_bf16<D, kGroupTiles, NW, 2>(a, stream);
+        if constexpr (NW == 4) {
+            if (tb == 3) return launch_bf16<D, kGroupTiles, 4, 3>(a, stream);
+        }
+        return RD_ERR_UNSUPPORTED;
+    }
+    switch (rg_tiles) {
+    case 1: return launch_bf16<D, 1, NW, 1>(a, stream);
+    case 2: return launch_bf16<D, 2, NW, 1>(a, stream);
+    case 3: return launch_bf16<D, 3, NW, 1>(a, stream);
+    case 4: return launch_bf16<D, 4, NW, 1>(a, stream);
+    case 5: return launch_bf16<D, 5, NW, 1>(a, stream);
     default: break;
     }
-    if constexpr (NW == 4) {
-        switch ((a.N + 15) / 16) {
-        case 6: return launch_bf16<D, 6, 4>(a, stream);
-        case 7: return launch_bf16<D, 7, 4>(a, stream);
-        case 8: return launch_bf16<D, 8, 4>(a, stream);
+    if constexpr (D == 64) {
+        switch (rg_tiles) {
+        case 6: return launch_bf16<64, 6, NW, 1>(a, stream);
+        case 7: return launch_bf16<64, 7, NW, 1>(a, stream);
+        case 8: return launch_bf16<64, 8, NW, 1>(a, stream);
         default: break;
         }
     }
     return RD_ERR_UNSUPPORTED;
 }
 
-int tree_attn_bf16(const AttnArgs &a, int D, int waves, hipStream_t stream)
+int tree_attn_bf16(const AttnArgs &a, int D, int waves, int rg_tiles, hipStream_t stream)
 {
-    if (D == 128) return waves == 8 ? dispatch_nq<128, 8>(a, stream) : dispatch_nq<128, 4>(a, stream);
-    return dispatch_nq<64, 4>(a, stream);
+    if (D == 128) return waves == 8 ? dispatch_nq<128, 8>(a, rg_tiles, stream) : dispatch_nq<128, 4>(a, rg_tiles, stream);
+    return dispatch_nq<64, 4>(a, rg_tiles, stream);
 }
 
 }  // namespace rd

@@ -60,17 +60,9 @@ __global__ __launch_bounds__(kAttnThreads) void rd_tree_attn_f32_kernel(AttnArgs
         }
     }
 
-    uint64_t mlo[4], mhi[4];             // tree-mask words 0 and 1 of this wave's four rows
     float m_run[4], l_run[4], o[4][kCols];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-        const int qrow = row0 + wave * 4 + r;
-        mlo[r] = mhi[r] = 0;
-        if (is_tree && qrow < P) {
-            const uint64_t *mrow = a.mask_bits + ((size_t)b * a.N + qrow) * a.words;
-            mlo[r] = mrow[0];
-            if (a.words > 1) mhi[r] = mrow[1];
-        }
         m_run[r] = -INFINITY;
         l_run[r] = 0.f;
 #pragma unroll
@@ -110,7 +102,11 @@ __global__ __launch_bounds__(kAttnThreads) void rd_tree_attn_f32_kernel(AttnArgs
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             bool ok = key < k_end;
-            if (is_tree) ok = ok && (((t0 ? mhi[r] : mlo[r]) >> lane) & 1ull);   // packed keys: t0 is 0 or 64
+            if (is_tree) {                               // packed keys t0 .. t0+63 are mask word t0/64 of the row
+                const int qrow = row0 + wave * 4 + r;
+                const uint64_t mw = qrow < P ? a.mask_bits[((size_t)b * a.N + qrow) * a.words + (t0 >> 6)] : 0ull;
+                ok = ok && ((mw >> lane) & 1ull);
+            }
             const float sv = ok ? s[r] * a.scale_log2e : -INFINITY;
             float tmax = sv;
 #pragma unroll

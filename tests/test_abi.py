@@ -57,8 +57,8 @@ def test_dedup_argument_errors(lib):
     assert _dedup(lib, 0, 4, 4) == INVALID
     assert _dedup(lib, 1, 0, 4) == INVALID
     assert _dedup(lib, 1, 4, -1) == INVALID
-    assert _dedup(lib, 1, 65, 1) == UNSUPPORTED
-    assert _dedup(lib, 1, 16, 9) == UNSUPPORTED          # N = 144 > 128
+    assert _dedup(lib, 1, 129, 1) == UNSUPPORTED
+    assert _dedup(lib, 1, 77, 5) == UNSUPPORTED          # N = 385 > 384
     assert _dedup(lib, 1, 4, 4, beams=None) == INVALID
     assert _dedup(lib, 1, 4, 4, req=None) == INVALID
     assert _dedup(lib, 1, 4, 4, bits=FAKE + 4) == INVALID   # uint64 rows need 8-byte alignment
@@ -78,7 +78,7 @@ def test_tree_attn_argument_errors(lib):
     assert _attn(lib, B=0) == INVALID
     assert _attn(lib, Cmax=-1) == INVALID
     assert _attn(lib, D=96) == UNSUPPORTED
-    assert _attn(lib, N=129) == UNSUPPORTED
+    assert _attn(lib, N=385) == UNSUPPORTED
     assert _attn(lib, dt=7) == UNSUPPORTED
     assert _attn(lib, q=None) == INVALID
     assert _attn(lib, kc=None) == INVALID
@@ -102,7 +102,7 @@ def test_workspace_sizes(lib):
     assert lib.rd_tree_attn_workspace(1, 4, 16, 64, 128, 0) >= 256 + 4 * 2 * 16 * (2 + 64) * 4
     assert lib.rd_tree_attn_workspace(1, 32, 40, 96, 1024, 1) == 0        # unsupported head size
     assert lib.rd_accept_workspace(1, 8, 5, 32000) < lib.rd_accept_workspace(16, 16, 5, 32000)
-    assert lib.rd_accept_workspace(1, 65, 1, 10) == 0
+    assert lib.rd_accept_workspace(1, 129, 1, 10) == 0
 
 
 def _accept(lib, B=1, W=4, L=4, V=100, logits=FAKE, req=FAKE, ws=FAKE, ws_bytes=None):
@@ -116,7 +116,7 @@ def _accept(lib, B=1, W=4, L=4, V=100, logits=FAKE, req=FAKE, ws=FAKE, ws_bytes=
 def test_accept_argument_errors(lib):
     assert _accept(lib, B=0) == INVALID
     assert _accept(lib, V=0) == INVALID
-    assert _accept(lib, W=65, L=1) == UNSUPPORTED
+    assert _accept(lib, W=129, L=1) == UNSUPPORTED
     assert _accept(lib, logits=None) == INVALID
     assert _accept(lib, logits=FAKE + 4) == INVALID
     assert _accept(lib, req=None) == INVALID
@@ -134,7 +134,7 @@ def test_commit_argument_errors(lib):
     assert _commit(lib, B=0) == INVALID
     assert _commit(lib, Cmax=0) == INVALID
     assert _commit(lib, D=96) == UNSUPPORTED
-    assert _commit(lib, N=129) == UNSUPPORTED
+    assert _commit(lib, N=385) == UNSUPPORTED
     assert _commit(lib, dt=5) == UNSUPPORTED
     assert _commit(lib, src=None) == INVALID
     assert _commit(lib, cache=None) == INVALID

@@ -129,6 +129,24 @@ def test_degenerate_beams_and_scales(rd, dtype):
     full_check(rd, t, dtype, scale=1.0, what="scale1")            # peaked softmax
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("W,L,V", [(70, 5, 6), (64, 6, 3), (1, 384, 5), (128, 3, 2), (29, 5, 50), (20, 7, 4), (50, 5, 1000)])
+def test_wide_beams(rd, dtype, D, W, L, V):
+    """The paper's widest beams (Sec. 4.3: up to 70 candidates of 5 tokens) and beyond: packed rows
+    in several row groups, packed keys in several blocks, mask rows of up to six words."""
+    announce("attn wide beams dtype=%s D=%d W=%d L=%d V=%d" % (dtype, D, W, L, V))
+    ctx = [0, 97, 700]
+    t = make_case(len(ctx), 2, D, W, L, ctx, dtype, seed=W * 7 + L, V=V)
+    full_check(rd, t, dtype, what="wide")
+
+
+def test_wide_beams_config2_shape(rd):
+    announce("attn wide beams, Vicuna-7B-shaped layer with 70 candidates")
+    t = make_case(1, 32, 128, 70, 5, [1024], "bf16", seed=70, V=32000, share="high")
+    full_check(rd, t, "bf16", what="wide-7b")
+
+
 def test_many_splits_long_context(rd):
     announce("attn long ragged context, many splits")
     t = make_case(2, 4, 128, 8, 5, [5000, 2311], "bf16", seed=21, V=3)

@@ -44,6 +44,7 @@ def _case(rng, B, H, N, D, Cmax, L, dtype, Dh):
     ("bf16", 128, 16, 52, 80, 5, 96, 0),
     ("f32", 128, 1, 1, 128, 128, 200, 4),
     ("bf16", 64, 2, 3, 1, 1, 1, 8),
+    ("bf16", 128, 2, 4, 350, 5, 64, 16),
 ])
 def test_commit_matches_oracle(rd, dtype, D, B, H, N, L, Cmax, Dh):
     announce(f"commit {dtype} D={D} B={B} H={H} N={N} L={L} Cmax={Cmax} Dh={Dh}")

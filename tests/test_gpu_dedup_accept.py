@@ -45,7 +45,8 @@ def test_dedup_configs(rd, idx):
 
 
 @pytest.mark.parametrize("W,L", [(1, 1), (1, 7), (1, 128), (2, 64), (3, 5), (7, 9), (16, 8), (25, 5),
-                                 (32, 4), (33, 3), (63, 2), (64, 1), (64, 2), (42, 3), (12, 10)])
+                                 (32, 4), (33, 3), (63, 2), (64, 1), (64, 2), (42, 3), (12, 10),
+                                 (70, 5), (128, 3), (1, 384), (127, 3), (65, 5), (96, 4), (2, 192)])
 def test_dedup_shapes(rd, W, L):
     for seed, V, share in ((1, 3, "uniform"), (2, 1000, "high"), (3, 2, "high"), (4, 50, "uniform")):
         announce("dedup W=%d L=%d seed=%d V=%d" % (W, L, seed, V))
@@ -126,7 +127,8 @@ def test_accept_shapes_and_workspace_reuse(rd):
     announce("accept shapes + one workspace reused by successive calls of the same shape")
     up = lambda x: (x + 255) // 256 * 256
     for (B, W, L, V, seed) in [(1, 1, 1, 10, 0), (2, 1, 9, 300, 1), (4, 64, 2, 5000, 2), (16, 16, 5, 640, 3),
-                               (3, 25, 5, 1200, 4), (2, 2, 64, 100, 5)]:
+                               (3, 25, 5, 1200, 4), (2, 2, 64, 100, 5), (2, 70, 5, 900, 6), (1, 128, 3, 64, 7),
+                               (2, 1, 384, 50, 8), (1, 65, 5, 32000, 9)]:
         ws = rd.new_workspace(rd.rd_accept_workspace(B, W, L, V), "cuda")
         for rep in range(3):
             beams = synth.make_beams(B, W, L, 4, seed + 10 * rep, "high")
