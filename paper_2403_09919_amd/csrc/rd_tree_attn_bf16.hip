@@ -326,6 +326,12 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
             const int next_key0 = next_tree ? (inext - nA) * kBlock : k_begin + inext * kBlock;
             const int next_end = next_tree ? tree_end : k_end;
             const int tile0 = cur_key0 + wave * G::kTileKeys;
+            // Lane ids re-read through an opaque copy: the LDS addresses derived from them are then
+            // recomputed in each iteration (one or two ALU operations) instead of being kept in
+            // registers across the loop, where the larger variants would park them in scratch memory
+            // and wait for ALL loads in flight on every reload.
+            int r16_l = r16, lane_l = lane;
+            asm volatile("" : "+v"(r16_l), "+v"(lane_l));
 
             // K registers -> own LDS tile (K swizzle); then fetch the next block's K.  The prefetch
             // is issued after the last block too (and ignored): a branch around it would make the
@@ -370,7 +376,7 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
                         float tmax = fmaxf(fmaxf(fmaxf(sacc[0][qt][0], sacc[0][qt][1]), fmaxf(sacc[0][qt][2], sacc[0][qt][3])),
                                            fmaxf(fmaxf(sacc[1][qt][0], sacc[1][qt][1]), fmaxf(sacc[1][qt][2], sacc[1][qt][3])));
                         tmax = quad_max(tmax) * c_abs;
-                        if (g == 0) sM[(qt * 16 + r16) * NW + wave] = tmax;
+                        if (g == 0) sM[(qt * 16 + r16_l) * NW + wave] = tmax;
                     }
                 }
             } else {
@@ -381,7 +387,7 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
                 for (int qt = 0; qt < NQA; ++qt) {
                     {
                         // element (mt, i) at bit 4 mt + i; context keys are all visible
-                        const uint32_t vq = kVisInLds ? sVis[(wave * NQ + qt) * 64 + lane] : vis[qt];
+                        const uint32_t vq = kVisInLds ? sVis[(wave * NQ + qt) * 64 + lane_l] : vis[qt];
                         const uint32_t bits = (cur_tree ? (vq >> tsh) : 0xffu) & tail8;
                         float tmax = -INFINITY;
 #pragma unroll
@@ -393,7 +399,7 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
                                 tmax = fmaxf(tmax, sv);
                             }
                         tmax = quad_max(tmax);
-                        if (g == 0) sM[(qt * 16 + r16) * NW + wave] = tmax;
+                        if (g == 0) sM[(qt * 16 + r16_l) * NW + wave] = tmax;
                     }
                 }
             }
@@ -410,7 +416,7 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
 #pragma unroll
             for (int qt = 0; qt < NQA; ++qt) {
                 {
-                    const f32x4 *pm = reinterpret_cast<const f32x4 *>(sM + (qt * 16 + r16) * NW);
+                    const f32x4 *pm = reinterpret_cast<const f32x4 *>(sM + (qt * 16 + r16_l) * NW);
                     f32x4 mv = pm[0];
                     if (NW == 8) {
                         const f32x4 mv2 = pm[1];
@@ -434,7 +440,7 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_bf16_kernel(AttnArgs 
                             pb[4 * mt + i] = (__bf16)pv;
                         }
                     l_run[qt] = l_run[qt] * alpha + psum;
-                    *reinterpret_cast<bf16x8 *>(sP + ((wave * NQ + qt) * 64 + lane) * 16) = pb;
+                    *reinterpret_cast<bf16x8 *>(sP + ((wave * NQ + qt) * 64 + lane_l) * 16) = pb;
                     if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {      // the maximum moved for some row
 #pragma unroll
                         for (int j = 0; j < kDTW; ++j) oacc[j][qt] *= alpha;
