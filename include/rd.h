@@ -44,7 +44,7 @@
 extern "C" {
 #endif
 
-typedef enum { RD_F32 = 0, RD_BF16 = 1 } rd_dtype;
+typedef enum { RD_F32 = 0, RD_BF16 = 1, RD_F16 = 2 } rd_dtype;
 
 typedef enum {
     RD_OK = 0,
@@ -99,8 +99,9 @@ int rd_dedup(const int32_t *beams, const int32_t *ctx_len, int B, int W, int L,
  * >= ctx_len[b] and packed rows >= n_packed[b] are never read.
  *
  *   q, k_new, v_new, out : [B,H,N,D]      k_cache, v_cache : [B,H,Cmax,D]
- *   element type by `dt`: RD_F32 (float) or RD_BF16 (bfloat16 bit patterns); scores and
- *   accumulation are fp32 in both; all tensor pointers 16-byte aligned.
+ *   element type by `dt`: RD_F32 (float), RD_BF16 (bfloat16) or RD_F16 (IEEE half; the paper's
+ *   App. A.2 runs its drafting in float16); scores and accumulation are fp32 in all three; all
+ *   tensor pointers 16-byte aligned.
  *   ctx_len, n_packed : int32 [B];  tree_mask_bits : uint64 [B,N,ceil(N/64)] (rd_dedup's).
  *   Cmax >= 0 (k_cache/v_cache may be NULL when Cmax == 0).
  *

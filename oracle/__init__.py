@@ -2,7 +2,8 @@
 
 Only tests, the smoke check and the benchmark's CPU-baseline leg may import this
 package.  It takes and returns numpy arrays, never touches a GPU, and imports
-nothing from the HIP package.  bf16 tensors travel as uint16 bit patterns.
+nothing from the HIP package.  bf16 tensors travel as uint16 bit patterns, fp16
+tensors as numpy float16.
 """
 from __future__ import annotations
 
@@ -17,7 +18,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "rd_oracle.c")
 _LIB = os.path.join(_HERE, "librd_oracle.so")
 
-DTYPES = {"f32": 0, "bf16": 1}
+DTYPES = {"f32": 0, "bf16": 1, "f16": 2}
+NP_DTYPES = {"f32": np.float32, "bf16": np.uint16, "f16": np.float16}
 
 
 def build(force: bool = False) -> str:
@@ -82,7 +84,7 @@ def dedup(beams: np.ndarray, ctx_len: Optional[np.ndarray] = None) -> dict:
 
 
 def _check_attn(q, k_cache, v_cache, k_new, v_new, dtype):
-    want = np.uint16 if dtype == "bf16" else np.float32
+    want = NP_DTYPES[dtype]
     arrs = []
     for a in (q, k_cache, v_cache, k_new, v_new):
         a = np.ascontiguousarray(a)
@@ -157,7 +159,7 @@ def commit(k_new, v_new, accepted_idx, best_len, ctx_len, k_cache, v_cache, dtyp
            hidden=None) -> dict:
     """Commit of the accepted tokens: returns updated COPIES of the caches, ctx_len_out,
     n_committed and (if `hidden` [B,N,Dh] is given) hidden_last [B,Dh] (zeros where best_len == 0)."""
-    np_dt = np.uint16 if dtype == "bf16" else np.float32
+    np_dt = NP_DTYPES[dtype]
     k_new = np.ascontiguousarray(k_new, dtype=np_dt)
     v_new = np.ascontiguousarray(v_new, dtype=np_dt)
     kc = np.array(k_cache, dtype=np_dt, order="C", copy=True)

@@ -34,6 +34,7 @@
 
 #define ORC_F32 0
 #define ORC_BF16 1
+#define ORC_F16 2
 
 int orc_num_threads(void)
 {
@@ -171,6 +172,16 @@ static double load_elem(const void *base, size_t idx, int dtype)
         memcpy(&f, &u, 4);
         return (double)f;
     }
+    if (dtype == ORC_F16) {
+        /* IEEE binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits */
+        const uint16_t h = ((const uint16_t *)base)[idx];
+        const int sign = h >> 15, e = (h >> 10) & 31, frac = h & 1023;
+        double v;
+        if (e == 31) v = frac ? NAN : INFINITY;
+        else if (e == 0) v = ldexp((double)frac, -24);              /* subnormal or zero */
+        else v = ldexp(1.0 + (double)frac / 1024.0, e - 15);
+        return sign ? -v : v;
+    }
     return (double)((const float *)base)[idx];
 }
 
@@ -194,8 +205,33 @@ static uint16_t double_to_bf16(double x)
     return (uint16_t)(u >> 16);
 }
 
+static uint16_t double_to_f16(double x)
+{
+    /* one rounding, ties to even, from the double straight to 11 significand bits */
+    const uint16_t sign = signbit(x) ? 0x8000 : 0;
+    if (isnan(x)) return 0x7E00;
+    const double ax = fabs(x);
+    if (isinf(ax)) return sign | 0x7C00;
+    if (ax == 0.0) return sign;
+    int e;
+    (void)frexp(ax, &e);                    /* ax = m * 2^e with m in [0.5, 1) */
+    int qexp = e - 11;                      /* exponent of the last kept bit */
+    if (qexp < -24) qexp = -24;             /* subnormal spacing */
+    const double r = nearbyint(ldexp(ax, -qexp));      /* integer in [0, 2048] */
+    const double v = ldexp(r, qexp);
+    if (v >= 65520.0) return sign | 0x7C00; /* rounds past the largest finite half (65504) */
+    if (v == 0.0) return sign;
+    int e2;
+    const double m2 = frexp(v, &e2);        /* v = m2 * 2^e2, exact */
+    if (e2 - 1 < -14)                       /* subnormal: fraction field = v / 2^-24 */
+        return sign | (uint16_t)ldexp(v, 24);
+    const uint16_t frac = (uint16_t)(ldexp(m2, 11) - 1024.0);       /* m2*2 in [1,2): 10 fraction bits */
+    return sign | (uint16_t)((e2 - 1 + 15) << 10) | frac;
+}
+
 static void store_elem(void *base, size_t idx, int dtype, double x)
 {
+    if (dtype == ORC_F16) { ((uint16_t *)base)[idx] = double_to_f16(x); return; }
     if (dtype == ORC_BF16) ((uint16_t *)base)[idx] = double_to_bf16(x);
     else ((float *)base)[idx] = (float)x;
 }
@@ -388,7 +424,7 @@ void orc_commit(const void *k_new, const void *v_new, const int32_t *accepted_id
                 void *k_cache, void *v_cache, int32_t *ctx_len_out, int32_t *n_committed,
                 const void *hidden, int Dh, void *hidden_last)
 {
-    const size_t es = (dtype == ORC_BF16) ? 2 : 4;
+    const size_t es = (dtype == ORC_F32) ? 4 : 2;
     const size_t row = (size_t)D * es;
     for (int b = 0; b < B; ++b) {
         int bl = best_len[b];

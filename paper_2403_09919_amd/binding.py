@@ -16,7 +16,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "librd.so")
 
-RD_F32, RD_BF16 = 0, 1
+RD_F32, RD_BF16, RD_F16 = 0, 1, 2
 RD_OK = 0
 RD_MAX_W, RD_MAX_N = 128, 384
 
@@ -131,7 +131,9 @@ def _dt_code(t: torch.Tensor) -> int:
         return RD_F32
     if t.dtype == torch.bfloat16:
         return RD_BF16
-    raise ValueError("unsupported element type %s (float32 or bfloat16)" % t.dtype)
+    if t.dtype == torch.float16:
+        return RD_F16
+    raise ValueError("unsupported element type %s (float32, bfloat16 or float16)" % t.dtype)
 
 
 def rd_tree_attn_workspace(B: int, H: int, N: int, D: int, Cmax: int, dt: int) -> int:

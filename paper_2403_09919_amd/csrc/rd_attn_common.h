@@ -146,6 +146,14 @@ __device__ __forceinline__ void store_out4(__bf16 *dst, float a, float b, float 
     *reinterpret_cast<bf16x4 *>(dst) = v;
 }
 
+__device__ __forceinline__ void store_out4(_Float16 *dst, float a, float b, float c, float d)
+{
+    typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
+    f16x4 v;
+    v[0] = (_Float16)a; v[1] = (_Float16)b; v[2] = (_Float16)c; v[3] = (_Float16)d;   // round to nearest even
+    *reinterpret_cast<f16x4 *>(dst) = v;
+}
+
 // ---- exchange of partial results between workgroups -------------------------------------------
 // The partials are written by one workgroup and read by another that may sit on a different
 // XCD (each XCD has its own L2).  A device-wide release/acquire fence would write back and

@@ -57,14 +57,14 @@ extern "C" int rd_commit(const void *k_new, const void *v_new, const int32_t *ac
                          const void *hidden, int Dh, void *hidden_last, void *stream)
 {
     if (B <= 0 || H <= 0 || N <= 0 || L <= 0 || Cmax <= 0 || Dh < 0) return RD_ERR_INVALID_ARG;
-    if (dt != RD_F32 && dt != RD_BF16) return RD_ERR_UNSUPPORTED;
+    if (dt != RD_F32 && dt != RD_BF16 && dt != RD_F16) return RD_ERR_UNSUPPORTED;
     if ((D != 64 && D != 128) || N > RD_MAX_N || L > RD_MAX_N || B > 65535) return RD_ERR_UNSUPPORTED;
     if (!k_new || !v_new || !accepted_idx || !best_len || !ctx_len || !k_cache || !v_cache || !ctx_len_out)
         return RD_ERR_INVALID_ARG;
     if (ctx_len_out == ctx_len) return RD_ERR_INVALID_ARG;
     if (!rd_aligned(k_new, 16) || !rd_aligned(v_new, 16) || !rd_aligned(k_cache, 16) || !rd_aligned(v_cache, 16))
         return RD_ERR_INVALID_ARG;
-    const size_t es = dt == RD_BF16 ? 2 : 4;
+    const size_t es = dt == RD_F32 ? 4 : 2;
     int hid_vecs = 0;
     if (hidden || hidden_last || Dh) {
         if (!hidden || !hidden_last || Dh <= 0 || (Dh * es) % 16 != 0) return RD_ERR_INVALID_ARG;

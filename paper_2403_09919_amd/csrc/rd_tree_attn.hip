@@ -1,16 +1,17 @@
-// rd_tree_attn host entry: argument checks, split plan, dispatch to the bf16 (MFMA) or
-// fp32 kernel.  See rd_attn_common.h for the decomposition.
+// rd_tree_attn host entry: argument checks, split plan, dispatch to the MFMA kernel (bf16 or
+// fp16 elements) or the fp32 kernel.  See rd_attn_common.h for the decomposition.
 #include "rd_attn_common.h"
 
 namespace rd {
 int tree_attn_bf16(const AttnArgs &a, int D, int waves, int rg_tiles, hipStream_t stream);
+int tree_attn_f16(const AttnArgs &a, int D, int waves, int rg_tiles, hipStream_t stream);
 int tree_attn_f32(const AttnArgs &a, int D, hipStream_t stream);
 }  // namespace rd
 
 static int attn_check_shape(int B, int H, int N, int D, int Cmax, rd_dtype dt)
 {
     if (B <= 0 || H <= 0 || N <= 0 || D <= 0 || Cmax < 0) return RD_ERR_INVALID_ARG;
-    if (dt != RD_F32 && dt != RD_BF16) return RD_ERR_UNSUPPORTED;
+    if (dt != RD_F32 && dt != RD_BF16 && dt != RD_F16) return RD_ERR_UNSUPPORTED;
     if (N > RD_MAX_N) return RD_ERR_UNSUPPORTED;
     if (D != 64 && D != 128) return RD_ERR_UNSUPPORTED;
     if ((long long)B * H > (1ll << 24)) return RD_ERR_UNSUPPORTED;
@@ -20,7 +21,7 @@ static int attn_check_shape(int B, int H, int N, int D, int Cmax, rd_dtype dt)
 extern "C" size_t rd_tree_attn_workspace(int B, int H, int N, int D, int Cmax, rd_dtype dt)
 {
     if (attn_check_shape(B, H, N, D, Cmax, dt) != RD_OK) return 0;
-    return rd::attn_plan(B, H, N, D, Cmax, dt == RD_BF16 ? 2 : 4).total_bytes;
+    return rd::attn_plan(B, H, N, D, Cmax, dt == RD_F32 ? 4 : 2).total_bytes;
 }
 
 extern "C" int rd_tree_attn(const void *q, const void *k_cache, const void *v_cache,
@@ -36,7 +37,7 @@ extern "C" int rd_tree_attn(const void *q, const void *k_cache, const void *v_ca
     if (!rd_aligned(q, 16) || !rd_aligned(k_cache, 16) || !rd_aligned(v_cache, 16) || !rd_aligned(k_new, 16) ||
         !rd_aligned(v_new, 16) || !rd_aligned(out, 16) || !rd_aligned(tree_mask_bits, 8))
         return RD_ERR_INVALID_ARG;
-    const rd::AttnPlan plan = rd::attn_plan(B, H, N, D, Cmax, dt == RD_BF16 ? 2 : 4);
+    const rd::AttnPlan plan = rd::attn_plan(B, H, N, D, Cmax, dt == RD_F32 ? 4 : 2);
     if (!workspace || !rd_aligned(workspace, 256) || workspace_bytes < plan.total_bytes) return RD_ERR_WORKSPACE;
 
     rd::AttnArgs a;
@@ -49,5 +50,7 @@ extern "C" int rd_tree_attn(const void *q, const void *k_cache, const void *v_ca
     a.xcd_remap = (((long long)B * H) % 8 == 0) ? 1 : 0;
     a.fuse_tree = plan.fuse_tree;
     a.n_rg = plan.n_rg;
-    return dt == RD_BF16 ? rd::tree_attn_bf16(a, D, plan.waves, plan.rg_tiles, (hipStream_t)stream) : rd::tree_attn_f32(a, D, (hipStream_t)stream);
+    if (dt == RD_BF16) return rd::tree_attn_bf16(a, D, plan.waves, plan.rg_tiles, (hipStream_t)stream);
+    if (dt == RD_F16) return rd::tree_attn_f16(a, D, plan.waves, plan.rg_tiles, (hipStream_t)stream);
+    return rd::tree_attn_f32(a, D, (hipStream_t)stream);
 }

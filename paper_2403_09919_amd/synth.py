@@ -34,7 +34,7 @@ class Config:
     ctx_hi: int
     H: int
     D: int
-    dtype: str           # "f32" or "bf16"
+    dtype: str           # "f32", "bf16" (or "f16" in tests)
     W: int
     L: int
     V: int
@@ -84,19 +84,25 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
 
 
 def to_f64(x: np.ndarray, dtype: str) -> np.ndarray:
-    """Exact upcast of a stored tensor (fp32 values or bf16 bit patterns) to float64."""
+    """Exact upcast of a stored tensor (fp32 values, bf16 bit patterns or numpy float16) to float64."""
     if dtype == "bf16":
         return bf16_bits_to_f32(x).astype(np.float64)
+    if dtype == "f16":
+        return np.asarray(x, dtype=np.float16).astype(np.float64)
     return np.asarray(x, dtype=np.float32).astype(np.float64)
 
 
 def _normal(rng: np.random.Generator, shape, dtype: str) -> np.ndarray:
     x = rng.standard_normal(shape, dtype=np.float32)
+    if dtype == "f16":
+        return x.astype(np.float16)          # numpy rounds to nearest even
     return f32_to_bf16_bits(x) if dtype == "bf16" else x
 
 
 def poison_value(dtype: str):
     """A NaN in the storage format, used to fill cache entries that must never be read."""
+    if dtype == "f16":
+        return np.float16(np.nan)
     return np.uint16(0x7FC1) if dtype == "bf16" else np.float32(np.nan)
 
 
@@ -146,7 +152,7 @@ def make_kv_cache(B: int, H: int, Cmax: int, D: int, dtype: str, seed: int,
     out = []
     for stream in (_S_KCACHE, _S_VCACHE):
         rng = _rng(seed, stream)
-        t = np.empty((B, H, Cmax, D), dtype=np.uint16 if dtype == "bf16" else np.float32)
+        t = np.empty((B, H, Cmax, D), dtype={"bf16": np.uint16, "f16": np.float16}.get(dtype, np.float32))
         for b in range(B):               # chunked: the 33B-shaped cache is 436 MB per tensor
             t[b] = _normal(rng, (H, Cmax, D), dtype)
             if poison and ctx_len is not None and int(ctx_len[b]) < Cmax:

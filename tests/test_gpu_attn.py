@@ -14,6 +14,7 @@ pytestmark = pytest.mark.gpu
 
 F32_REL = 1e-5
 BF16_ABS = 2e-2
+F16_ABS = 5e-3       # fp16: probabilities and output carry 11 significand bits (2^-11 relative each)
 
 
 @pytest.fixture(scope="module")
@@ -38,7 +39,7 @@ def compare(got, ref, dtype, what=""):
     if dtype == "f32":
         assert err <= F32_REL * max(np.abs(r).max(), 1e-30), (what, err, np.abs(r).max())
     else:
-        assert err <= BF16_ABS, (what, err)
+        assert err <= (F16_ABS if dtype == "f16" else BF16_ABS), (what, err)
     return err
 
 
@@ -104,7 +105,7 @@ def test_full_size_configs_sampled(rd, idx):
     assert err <= BF16_ABS + 2.0 ** -9     # the sampled reference is unrounded: allow half a bf16 ulp at |x|<1
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f32", "f16"])
 @pytest.mark.parametrize("D", [64, 128])
 @pytest.mark.parametrize("W,L", [(1, 1), (1, 5), (3, 5), (4, 4), (7, 5), (8, 8), (13, 6), (16, 6), (16, 7), (64, 2), (1, 128)])
 def test_shapes(rd, dtype, D, W, L):
@@ -116,7 +117,7 @@ def test_shapes(rd, dtype, D, W, L):
     full_check(rd, t, dtype, what="shapes")
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f32", "f16"])
 def test_degenerate_beams_and_scales(rd, dtype):
     announce("attn degenerate beams dtype=%s" % dtype)
     B, H, D, W, L = 2, 3, 128, 8, 5
@@ -129,7 +130,7 @@ def test_degenerate_beams_and_scales(rd, dtype):
     full_check(rd, t, dtype, scale=1.0, what="scale1")            # peaked softmax
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype", ["bf16", "f32", "f16"])
 @pytest.mark.parametrize("D", [64, 128])
 @pytest.mark.parametrize("W,L,V", [(70, 5, 6), (64, 6, 3), (1, 384, 5), (128, 3, 2), (29, 5, 50), (20, 7, 4), (50, 5, 1000)])
 def test_wide_beams(rd, dtype, D, W, L, V):
@@ -147,10 +148,19 @@ def test_wide_beams_config2_shape(rd):
     full_check(rd, t, "bf16", what="wide-7b")
 
 
-def test_many_splits_long_context(rd):
-    announce("attn long ragged context, many splits")
-    t = make_case(2, 4, 128, 8, 5, [5000, 2311], "bf16", seed=21, V=3)
-    full_check(rd, t, "bf16", what="long")
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_many_splits_long_context(rd, dtype):
+    announce("attn long ragged context, many splits, " + dtype)
+    t = make_case(2, 4, 128, 8, 5, [5000, 2311], dtype, seed=21, V=3)
+    full_check(rd, t, dtype, what="long")
+
+
+def test_config2_shape_fp16(rd):
+    """The Vicuna-7B-shaped layer with half-precision K/V (App. A.2 runs its drafting in float16)."""
+    announce("attn config 2 shape, fp16")
+    cfg = synth.CONFIGS[2]
+    t = make_case(cfg.B, cfg.H, cfg.D, cfg.W, cfg.L, [cfg.ctx_hi], "f16", seed=cfg.seed, V=cfg.V)
+    full_check(rd, t, "f16", what="cfg2-f16")
 
 
 def test_workspace_reuse_and_determinism(rd):

@@ -23,6 +23,8 @@ def rd():
 def _case(rng, B, H, N, D, Cmax, L, dtype, Dh):
     def t(shape):
         x = rng.standard_normal(shape).astype(np.float32)
+        if dtype == "f16":
+            return x.astype(np.float16)
         return synth.f32_to_bf16_bits(x) if dtype == "bf16" else x
     k_new, v_new, kc, vc = t((B, H, N, D)), t((B, H, N, D)), t((B, H, Cmax, D)), t((B, H, Cmax, D))
     best_len = rng.integers(0, L + 1, B).astype(np.int32)
@@ -45,6 +47,7 @@ def _case(rng, B, H, N, D, Cmax, L, dtype, Dh):
     ("f32", 128, 1, 1, 128, 128, 200, 4),
     ("bf16", 64, 2, 3, 1, 1, 1, 8),
     ("bf16", 128, 2, 4, 350, 5, 64, 16),
+    ("f16", 128, 3, 4, 40, 5, 64, 8),
 ])
 def test_commit_matches_oracle(rd, dtype, D, B, H, N, L, Cmax, Dh):
     announce(f"commit {dtype} D={D} B={B} H={H} N={N} L={L} Cmax={Cmax} Dh={Dh}")

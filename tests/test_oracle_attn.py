@@ -22,7 +22,7 @@ def _f64(x, dtype):
     return synth.to_f64(x, dtype)
 
 
-@pytest.mark.parametrize("seed,dtype", [(0, "f32"), (1, "f32"), (2, "bf16"), (3, "bf16")])
+@pytest.mark.parametrize("seed,dtype", [(0, "f32"), (1, "f32"), (2, "bf16"), (3, "bf16"), (4, "f16"), (5, "f16")])
 def test_per_candidate_equivalence(seed, dtype):
     """Output at packed slot unpack_index[i][j] equals ordinary causal attention of the
     unpacked candidate i (context + its own tokens 0..j), for every i, j."""
@@ -93,6 +93,46 @@ def test_bf16_rounding_is_nearest_even():
     # the generator's own fp32 -> bf16 conversion follows the same rule
     b = synth.f32_to_bf16_bits(np.array([1.00390625, 1.01171875, 1.0117188, -1.00390625], np.float32))
     assert b.tolist() == [0x3F80, 0x3F82, 0x3F82, 0xBF80]
+
+
+def test_f16_storage_matches_numpy_float16():
+    """The oracle's half-precision load and store against numpy's float16 (an independent IEEE
+    binary16 implementation): with q = 0 and a single visible key (the token itself, no context)
+    the output is that key's value, so every finite half bit pattern must pass through unchanged
+    (load then store); with one context value a and the own value c the output is the mean
+    (a+c)/2 computed in double and rounded once, which numpy gives as float16(float64 mean)."""
+    D = 8
+    beams = np.array([[[1]]], np.int32)
+    g = oracle.dedup(beams)
+    allbits = np.arange(0x10000, dtype=np.uint32).astype(np.uint16).view(np.float16)
+    finite = allbits[np.isfinite(allbits) & (allbits.view(np.uint16) != 0x8000)]   # -0 + 0 = +0 in the sum
+    finite = finite[: finite.size // D * D].reshape(-1, 1, 1, D)          # batch of single-token sequences
+    B = finite.shape[0]
+    bb = np.ones((B, 1, 1), np.int32)
+    gg = oracle.dedup(bb)
+    z = np.zeros((B, 1, 1, D), np.float16)
+    empty = np.zeros((B, 1, 0, D), np.float16)
+    out = oracle.tree_attn(z, empty, empty, np.zeros(B, np.int32), z, finite, gg["n_packed"], gg["tree_mask"], "f16", 1.0)
+    assert np.array_equal(out.view(np.uint16), finite.view(np.uint16))
+    rng = np.random.default_rng(3)
+    pairs = [(1.0, 1.0009765625), (1.0009765625, 1.001953125), (-1.0, -1.0009765625), (65504.0, 65504.0),
+             (65504.0, 65472.0), (6e-8, 0.0), (6e-8, 1.2e-7), (5.96e-8, 5.96e-8), (1e-5, 3e-5), (-2.5, 7.25)]
+    pairs += [tuple(rng.standard_normal(2) * 10.0 ** rng.integers(-7, 5)) for _ in range(300)]
+    for a, c in pairs:
+        a16, c16 = np.float16(a), np.float16(c)
+        vc = np.full((1, 1, 1, D), a16, np.float16)
+        vn = np.full((1, 1, 1, D), c16, np.float16)
+        z1 = np.zeros((1, 1, 1, D), np.float16)
+        out = oracle.tree_attn(z1, z1, vc, [1], z1, vn, g["n_packed"], g["tree_mask"], "f16", 1.0)
+        want = np.float16((np.float64(a16) + np.float64(c16)) / 2.0)
+        got = out.flat[0]
+        assert got == want and (want == 0 or got.view(np.uint16) == want.view(np.uint16)), (a, c, got, want)   # sign of zero aside
+    # ties go to the even neighbour: (1 + (1 + 2^-10)) / 2 lies exactly between 1 and 1 + 2^-10
+    vc = np.full((1, 1, 1, D), np.float16(1.0), np.float16)
+    vn = np.full((1, 1, 1, D), np.float16(1.0009765625), np.float16)
+    z1 = np.zeros((1, 1, 1, D), np.float16)
+    out = oracle.tree_attn(z1, z1, vc, [1], z1, vn, g["n_packed"], g["tree_mask"], "f16", 1.0)
+    assert out.view(np.uint16).flat[0] == 0x3C00
 
 
 def test_single_candidate_matches_torch_sdpa():
