@@ -12,6 +12,7 @@
 // the whole operation is a single launch.
 #pragma once
 #include "rd_internal.h"
+#include <atomic>
 
 namespace rd {
 
@@ -104,6 +105,20 @@ static inline AttnPlan attn_plan(int B, int H, int N, int D, int Cmax, size_t el
     p.total_bytes = p.counters_bytes +
                     (p.n_part > 1 ? (size_t)BH * n_rg * p.n_part * p.partial_floats * sizeof(float) : 0);
     return p;
+}
+
+// Raising a kernel's dynamic LDS limit is per kernel and per device; `done` (one per kernel) keeps
+// a bit for each device already set up.  Returns RD_OK or RD_ERR_HIP.
+static inline int ensure_dynamic_lds(const void *kernel, size_t bytes, std::atomic<unsigned long long> &done)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return RD_ERR_HIP;
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (dev < 64 && (done.load(std::memory_order_acquire) & bit)) return RD_OK;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess)
+        return RD_ERR_HIP;
+    if (dev < 64) done.fetch_or(bit, std::memory_order_release);
+    return RD_OK;
 }
 
 struct AttnArgs {

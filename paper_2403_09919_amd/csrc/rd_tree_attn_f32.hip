@@ -168,15 +168,13 @@ static int launch_f32(const AttnArgs &a, hipStream_t stream)
 {
     const size_t smem = sizeof(float) * ((size_t)kF32Rows * D + (size_t)kF32TileKeys * (D + 1) +
                                          (size_t)kF32TileKeys * D + (size_t)kF32Rows * kF32TileKeys);
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&rd_tree_attn_f32_kernel<D>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-            return RD_ERR_HIP;
-        configured = true;
-    }
+    static std::atomic<unsigned long long> configured{0};
+    const int st = ensure_dynamic_lds(reinterpret_cast<const void *>(&rd_tree_attn_f32_kernel<D>), smem, configured);
+    if (st != RD_OK) return st;
     const int row_groups = a.rows_pad / kF32Rows;
-    const unsigned grid = (unsigned)((size_t)a.B * a.H * (a.S + 1) * row_groups);
+    const size_t wgs = (size_t)a.B * a.H * (a.S + 1) * row_groups;
+    if (wgs > 0x7fffffffull) return RD_ERR_UNSUPPORTED;
+    const unsigned grid = (unsigned)wgs;
     hipLaunchKernelGGL((rd_tree_attn_f32_kernel<D>), dim3(grid), dim3(kAttnThreads), smem, stream, a, row_groups);
     return rd_check_launch();
 }

@@ -665,14 +665,13 @@ template <typename T, int D, int NQ, int NW, int TB>
 static int launch_mfma(const AttnArgs &a, hipStream_t stream)
 {
     const size_t smem = mfma_smem_bytes<D, NQ, NW>();
-    static bool configured = false;          // raising the dynamic LDS limit is per kernel, once
-    if (!configured) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&rd_tree_attn_mfma_kernel<T, D, NQ, NW, TB>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-            return RD_ERR_HIP;
-        configured = true;
-    }
-    const unsigned grid = (unsigned)((size_t)a.B * a.H * (a.S + (a.fuse_tree ? 0 : 1)) * a.n_rg);
+    static std::atomic<unsigned long long> configured{0};
+    const int st = ensure_dynamic_lds(reinterpret_cast<const void *>(&rd_tree_attn_mfma_kernel<T, D, NQ, NW, TB>), smem,
+                                      configured);
+    if (st != RD_OK) return st;
+    const size_t wgs = (size_t)a.B * a.H * (a.S + (a.fuse_tree ? 0 : 1)) * a.n_rg;
+    if (wgs > 0x7fffffffull) return RD_ERR_UNSUPPORTED;
+    const unsigned grid = (unsigned)wgs;
     hipLaunchKernelGGL((rd_tree_attn_mfma_kernel<T, D, NQ, NW, TB>), dim3(grid), dim3(NW * 64), smem, stream, a);
     return rd_check_launch();
 }
