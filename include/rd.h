@@ -122,6 +122,28 @@ int rd_tree_attn(const void *q, const void *k_cache, const void *v_cache,
                  void *out, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * rd_tree_attn_paged — rd_tree_attn with the context keys and values held in fixed-size pages, the
+ * cache layout of serving systems built on paged attention (the production inference framework
+ * the paper reports on in Sec. 4.1 and its acknowledgements is one).  Same computation and outputs as rd_tree_attn.
+ *
+ *   k_pages, v_pages : [n_pages, H, page_size, D], bf16 or fp16 (dt = RD_BF16 / RD_F16 only)
+ *   block_table      : int32 [B, max_pages]; entry j of row b is the page that holds context keys
+ *                      j*page_size .. (j+1)*page_size-1 of sequence b.  Only entries below
+ *                      ceil(ctx_len[b] / page_size) are read; values are clamped to [0, n_pages-1].
+ *   page_size        : keys per page, a multiple of 32;  ctx_len[b] <= page_size * max_pages.
+ *   q, k_new, v_new, out, ctx_len, n_packed, tree_mask_bits, scale, workspace: as for rd_tree_attn
+ *   (workspace size from rd_tree_attn_paged_workspace; same zero-before-first-use contract).
+ */
+size_t rd_tree_attn_paged_workspace(int B, int H, int N, int D, int page_size, int max_pages, rd_dtype dt);
+
+int rd_tree_attn_paged(const void *q, const void *k_pages, const void *v_pages,
+                       const int32_t *block_table, int page_size, int max_pages, int n_pages,
+                       const int32_t *ctx_len, const void *k_new, const void *v_new,
+                       const int32_t *n_packed, const uint64_t *tree_mask_bits,
+                       int B, int H, int N, int D, rd_dtype dt, float scale,
+                       void *out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * rd_accept — greedy verification (Sec. 3.4, Fig. 2; temperature 0).
  *
  *   argmax_out[b][p] = arg max_v logits[b][p][v] for p < n_packed[b] (smallest v among

@@ -112,6 +112,26 @@ def tree_attn(q, k_cache, v_cache, ctx_len, k_new, v_new, n_packed, tree_mask,
     return out
 
 
+def tree_attn_paged(q, k_pages, v_pages, block_table, ctx_len, k_new, v_new, n_packed, tree_mask,
+                    dtype: str, scale: float) -> np.ndarray:
+    """Tree-masked attention over a paged cache: pages [n_pages,H,page_size,D], block_table [B,max_pages].
+    Context key c of sequence b is row c % page_size of page block_table[b][c // page_size]; the keys
+    are laid out one by one into a dense cache with exactly that rule and the dense routine is run."""
+    k_pages, v_pages = np.ascontiguousarray(k_pages), np.ascontiguousarray(v_pages)
+    block_table, ctx_len = _i32(block_table), _i32(ctx_len)
+    n_pages, H, ps, D = k_pages.shape
+    B = block_table.shape[0]
+    Cmax = max(int(ctx_len.max()), 1)
+    kc = np.zeros((B, H, Cmax, D), k_pages.dtype)
+    vc = np.zeros((B, H, Cmax, D), v_pages.dtype)
+    for b in range(B):
+        for c in range(int(ctx_len[b])):
+            page = block_table[b, c // ps]
+            kc[b, :, c, :] = k_pages[page, :, c % ps, :]
+            vc[b, :, c, :] = v_pages[page, :, c % ps, :]
+    return tree_attn(q, kc, vc, ctx_len, k_new, v_new, n_packed, tree_mask, dtype, scale)
+
+
 def tree_attn_rows(q, k_cache, v_cache, ctx_len, k_new, v_new, n_packed, tree_mask,
                    dtype: str, scale: float, rows) -> np.ndarray:
     """Attention output of selected (b, h, p) rows as unrounded float64 [n_rows, D]."""

@@ -34,6 +34,8 @@ EXPORTS = {
     "rd_dedup": (_i, [_vp, _vp, _i, _i, _i] + [_vp] * 8 + [_vp]),
     "rd_tree_attn_workspace": (_sz, [_i, _i, _i, _i, _i, _i]),
     "rd_tree_attn": (_i, [_vp] * 8 + [_i, _i, _i, _i, _i, _i, _f, _vp, _vp, _sz, _vp]),
+    "rd_tree_attn_paged_workspace": (_sz, [_i, _i, _i, _i, _i, _i, _i]),
+    "rd_tree_attn_paged": (_i, [_vp] * 4 + [_i, _i, _i] + [_vp] * 5 + [_i, _i, _i, _i, _i, _f, _vp, _vp, _sz, _vp]),
     "rd_accept_workspace": (_sz, [_i, _i, _i, _i]),
     "rd_accept": (_i, [_vp] * 5 + [_i, _i, _i, _i] + [_vp] * 6 + [_vp, _sz, _vp]),
     "rd_commit": (_i, [_vp] * 5 + [_i] * 7 + [_vp] * 4 + [_vp, _i, _vp, _vp]),
@@ -163,6 +165,37 @@ def rd_tree_attn(q, k_cache, v_cache, ctx_len, k_new, v_new, n_packed, tree_mask
         _ptr(out, q.dtype, (B, H, N, D), "out"),
         _ptr(workspace, torch.uint8, None, "workspace"), workspace.numel(), _stream())
     _check(code, "rd_tree_attn")
+    return out
+
+
+def rd_tree_attn_paged_workspace(B: int, H: int, N: int, D: int, page_size: int, max_pages: int, dt: int) -> int:
+    return int(_lib.rd_tree_attn_paged_workspace(B, H, N, D, page_size, max_pages, dt))
+
+
+def rd_tree_attn_paged(q, k_pages, v_pages, block_table, ctx_len, k_new, v_new, n_packed, tree_mask_bits,
+                       scale: float, out: Optional[torch.Tensor] = None,
+                       workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """As rd_tree_attn with k_pages/v_pages [n_pages,H,page_size,D] and block_table int32 [B,max_pages]
+    (see include/rd.h, rd_tree_attn_paged)."""
+    B, H, N, D = q.shape
+    n_pages, Hp, page_size, Dp = k_pages.shape
+    max_pages = block_table.shape[1]
+    dt = _dt_code(q)
+    words = (N + 63) // 64
+    if out is None:
+        out = torch.empty_like(q)
+    if workspace is None:
+        workspace = new_workspace(rd_tree_attn_paged_workspace(B, H, N, D, page_size, max_pages, dt), q.device)
+    code = _lib.rd_tree_attn_paged(
+        _ptr(q, q.dtype, (B, H, N, D), "q"), _ptr(k_pages, q.dtype, (n_pages, H, page_size, D), "k_pages"),
+        _ptr(v_pages, q.dtype, (n_pages, H, page_size, D), "v_pages"),
+        _ptr(block_table, torch.int32, (B, max_pages), "block_table"), page_size, max_pages, n_pages,
+        _ptr(ctx_len, torch.int32, (B,), "ctx_len"), _ptr(k_new, q.dtype, (B, H, N, D), "k_new"),
+        _ptr(v_new, q.dtype, (B, H, N, D), "v_new"), _ptr(n_packed, torch.int32, (B,), "n_packed"),
+        _ptr(tree_mask_bits, torch.int64, (B, N, words), "tree_mask_bits"), B, H, N, D, dt, float(scale),
+        _ptr(out, q.dtype, (B, H, N, D), "out"), _ptr(workspace, torch.uint8, None, "workspace"),
+        workspace.numel(), _stream())
+    _check(code, "rd_tree_attn_paged")
     return out
 
 

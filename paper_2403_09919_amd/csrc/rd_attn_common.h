@@ -124,6 +124,8 @@ static inline int ensure_dynamic_lds(const void *kernel, size_t bytes, std::atom
 struct AttnArgs {
     const void *q, *k_cache, *v_cache, *k_new, *v_new;
     const int32_t *ctx_len, *n_packed;
+    const int32_t *block_table;   // paged cache only: [B, max_pages] page of keys [j*page_size, (j+1)*page_size)
+    int page_size, max_pages, n_pages;
     const uint64_t *mask_bits;
     void *out;
     uint32_t *counters;

@@ -5,6 +5,7 @@
 namespace rd {
 int tree_attn_bf16(const AttnArgs &a, int D, int waves, int rg_tiles, hipStream_t stream);
 int tree_attn_f16(const AttnArgs &a, int D, int waves, int rg_tiles, hipStream_t stream);
+int tree_attn_paged(const AttnArgs &a, int D, int waves, int rg_tiles, bool f16, hipStream_t stream);
 int tree_attn_f32(const AttnArgs &a, int D, hipStream_t stream);
 }  // namespace rd
 
@@ -50,7 +51,56 @@ extern "C" int rd_tree_attn(const void *q, const void *k_cache, const void *v_ca
     a.xcd_remap = (((long long)B * H) % 8 == 0) ? 1 : 0;
     a.fuse_tree = plan.fuse_tree;
     a.n_rg = plan.n_rg;
+    a.block_table = nullptr; a.page_size = 0; a.max_pages = 0; a.n_pages = 0;
     if (dt == RD_BF16) return rd::tree_attn_bf16(a, D, plan.waves, plan.rg_tiles, (hipStream_t)stream);
     if (dt == RD_F16) return rd::tree_attn_f16(a, D, plan.waves, plan.rg_tiles, (hipStream_t)stream);
     return rd::tree_attn_f32(a, D, (hipStream_t)stream);
+}
+
+// ---- paged KV cache ---------------------------------------------------------------------------
+static int paged_check_shape(int B, int H, int N, int D, int page_size, int max_pages, int n_pages, rd_dtype dt)
+{
+    if (page_size <= 0 || max_pages <= 0 || n_pages <= 0) return RD_ERR_INVALID_ARG;
+    if (dt != RD_BF16 && dt != RD_F16) return RD_ERR_UNSUPPORTED;            // 16-bit caches only
+    if (page_size % 32 != 0) return RD_ERR_UNSUPPORTED;                      // a 32-key tile must not straddle pages
+    if ((long long)page_size * max_pages > (1ll << 30)) return RD_ERR_UNSUPPORTED;
+    return attn_check_shape(B, H, N, D, page_size * max_pages, dt);
+}
+
+extern "C" size_t rd_tree_attn_paged_workspace(int B, int H, int N, int D, int page_size, int max_pages, rd_dtype dt)
+{
+    if (paged_check_shape(B, H, N, D, page_size, max_pages, 1, dt) != RD_OK) return 0;
+    return rd::attn_plan(B, H, N, D, page_size * max_pages, 2).total_bytes;
+}
+
+extern "C" int rd_tree_attn_paged(const void *q, const void *k_pages, const void *v_pages,
+                                  const int32_t *block_table, int page_size, int max_pages, int n_pages,
+                                  const int32_t *ctx_len, const void *k_new, const void *v_new,
+                                  const int32_t *n_packed, const uint64_t *tree_mask_bits,
+                                  int B, int H, int N, int D, rd_dtype dt, float scale,
+                                  void *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    const int st = paged_check_shape(B, H, N, D, page_size, max_pages, n_pages, dt);
+    if (st != RD_OK) return st;
+    if (!q || !k_pages || !v_pages || !block_table || !k_new || !v_new || !ctx_len || !n_packed || !tree_mask_bits || !out)
+        return RD_ERR_INVALID_ARG;
+    if (!rd_aligned(q, 16) || !rd_aligned(k_pages, 16) || !rd_aligned(v_pages, 16) || !rd_aligned(k_new, 16) ||
+        !rd_aligned(v_new, 16) || !rd_aligned(out, 16) || !rd_aligned(tree_mask_bits, 8) || !rd_aligned(block_table, 4))
+        return RD_ERR_INVALID_ARG;
+    const int Cmax = page_size * max_pages;
+    const rd::AttnPlan plan = rd::attn_plan(B, H, N, D, Cmax, 2);
+    if (!workspace || !rd_aligned(workspace, 256) || workspace_bytes < plan.total_bytes) return RD_ERR_WORKSPACE;
+
+    rd::AttnArgs a;
+    a.q = q; a.k_cache = k_pages; a.v_cache = v_pages; a.k_new = k_new; a.v_new = v_new;
+    a.ctx_len = ctx_len; a.n_packed = n_packed; a.mask_bits = tree_mask_bits; a.out = out;
+    a.block_table = block_table; a.page_size = page_size; a.max_pages = max_pages; a.n_pages = n_pages;
+    a.counters = static_cast<uint32_t *>(workspace);
+    a.partials = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + plan.counters_bytes);
+    a.B = B; a.H = H; a.N = N; a.Cmax = Cmax; a.S = plan.S; a.words = (N + 63) / 64; a.rows_pad = plan.rows_pad;
+    a.scale_log2e = scale * 1.44269504088896340736f;
+    a.xcd_remap = (((long long)B * H) % 8 == 0) ? 1 : 0;
+    a.fuse_tree = plan.fuse_tree;
+    a.n_rg = plan.n_rg;
+    return rd::tree_attn_paged(a, D, plan.waves, plan.rg_tiles, dt == RD_F16, (hipStream_t)stream);
 }

@@ -33,6 +33,6 @@ RD_TRACE_DEFINE(rd_debug_set_trace)
 namespace rd {
 int tree_attn_bf16(const AttnArgs &a, int D, int waves, int rg_tiles, hipStream_t stream)
 {
-    return tree_attn_mfma<__bf16>(a, D, waves, rg_tiles, stream);
+    return tree_attn_mfma<__bf16, false>(a, D, waves, rg_tiles, stream);
 }
 }  // namespace rd

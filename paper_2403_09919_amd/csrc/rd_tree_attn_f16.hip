@@ -8,6 +8,6 @@ RD_TRACE_DEFINE(rd_debug_set_trace_f16)
 namespace rd {
 int tree_attn_f16(const AttnArgs &a, int D, int waves, int rg_tiles, hipStream_t stream)
 {
-    return tree_attn_mfma<_Float16>(a, D, waves, rg_tiles, stream);
+    return tree_attn_mfma<_Float16, false>(a, D, waves, rg_tiles, stream);
 }
 }  // namespace rd

@@ -90,7 +90,9 @@ __device__ __forceinline__ float quad_sum(float x)
 
 // TB = packed-key blocks the launch can need: ceil(N / block keys).  1 for all but the widest beams;
 // the mask words of every such block are fetched up front, so the common case should not pay for three.
-template <typename T, int D, int NQ, int NW, int TB>
+// PAGED: the context keys and values live in fixed-size pages found through a block table
+// (a.block_table, a.page_size, a.max_pages) instead of one dense [B,H,Cmax,D] tensor.
+template <typename T, int D, int NQ, int NW, int TB, bool PAGED>
 __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs a)
 {
     using G = Geo<D>;
@@ -168,8 +170,9 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
     const int nB = (has_tree && P > 0) ? (tree_end + kBlock - 1) / kBlock : 0;
     const int nb = nA + nB;
     const unsigned char *Qb = static_cast<const unsigned char *>(a.q) + ((size_t)bh * a.N + row0) * G::kRowBytes;
-    const unsigned char *Kc = static_cast<const unsigned char *>(a.k_cache) + (size_t)bh * a.Cmax * G::kRowBytes;
-    const unsigned char *Vc = static_cast<const unsigned char *>(a.v_cache) + (size_t)bh * a.Cmax * G::kRowBytes;
+    // dense cache: this head's rows; paged cache: the page pool (the head is picked inside a page)
+    const unsigned char *Kc = static_cast<const unsigned char *>(a.k_cache) + (PAGED ? 0 : (size_t)bh * a.Cmax * G::kRowBytes);
+    const unsigned char *Vc = static_cast<const unsigned char *>(a.v_cache) + (PAGED ? 0 : (size_t)bh * a.Cmax * G::kRowBytes);
     const unsigned char *Kn = static_cast<const unsigned char *>(a.k_new) + (size_t)bh * a.N * G::kRowBytes;
     const unsigned char *Vn = static_cast<const unsigned char *>(a.v_new) + (size_t)bh * a.N * G::kRowBytes;
     // ---- all first loads, without branches so that the waits on them stay exact --------------------
@@ -210,14 +213,43 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
 #pragma unroll
         for (int s = 0; s < G::kLoads; ++s) reg[s] = ldg16(base + min(off0 + s * 1024u, last_off));
     };
+    // Paged cache: a tile (32 keys, never straddling a page because page_size % 32 == 0) is
+    // addressed through the page of its first key.  Tiles beyond the end of the range are
+    // redirected to the last tile that holds a key, rows beyond the end to the tile's last valid
+    // row.  The page id of the tile to prefetch is itself fetched one iteration earlier, so the
+    // scalar load's latency is off the critical path.
+    const int head = bh - b * a.H;
+    auto ctx_tile_first = [&](int key0, int end) __attribute__((always_inline)) {   // first key of this wave's (redirected) tile
+        return min(key0 + wave * G::kTileKeys, ((end - 1) >> 5) << 5);
+    };
+    auto page_of = [&](int t0) __attribute__((always_inline)) {                 // wave-uniform scalar load
+        const int pg = min(t0 / a.page_size, a.max_pages - 1);
+        return clampi(a.block_table[(size_t)b * a.max_pages + pg], 0, a.n_pages - 1);
+    };
+    auto load_tile_paged = [&](const unsigned char *pages, int pid, int t0, int end, uint4 (&reg)[G::kLoads]) __attribute__((always_inline)) {
+        const unsigned char *base = pages + (((size_t)pid * a.H + head) * a.page_size + (t0 % a.page_size)) * G::kRowBytes;
+        const uint32_t off0 = (uint32_t)ld_row * G::kRowBytes + ld_chunk * 16;
+        const uint32_t last_off = (uint32_t)(min(G::kTileKeys, end - t0) - 1) * G::kRowBytes + ld_chunk * 16;
+#pragma unroll
+        for (int s = 0; s < G::kLoads; ++s) reg[s] = ldg16(base + min(off0 + s * 1024u, last_off));
+    };
+    int pid_next = 0;         // page of this wave's tile in the block after the current one (paged context only)
     {   // first block; a workgroup with no block at all reads (and ignores) the first row of Q
         const bool ctx = nA > 0;
-        const unsigned char *kb = nb == 0 ? Qb : (ctx ? Kc : Kn);
-        const unsigned char *vb = nb == 0 ? Qb : (ctx ? Vc : Vn);
-        const int key0 = ctx ? k_begin : 0;
-        const int end = nb == 0 ? 1 : (ctx ? k_end : tree_end);
-        load_tile(kb, key0, end, kreg);
-        load_tile(vb, key0, end, vreg);
+        if (PAGED && ctx) {
+            const int t0 = ctx_tile_first(k_begin, k_end);
+            const int pid = page_of(t0);
+            load_tile_paged(Kc, pid, t0, k_end, kreg);
+            load_tile_paged(Vc, pid, t0, k_end, vreg);
+            if (nA > 1) pid_next = page_of(ctx_tile_first(k_begin + kBlock, k_end));
+        } else {
+            const unsigned char *kb = nb == 0 ? Qb : (ctx ? Kc : Kn);
+            const unsigned char *vb = nb == 0 ? Qb : (ctx ? Vc : Vn);
+            const int key0 = ctx ? k_begin : 0;
+            const int end = nb == 0 ? 1 : (ctx ? k_end : tree_end);
+            load_tile(kb, key0, end, kreg);
+            load_tile(vb, key0, end, vreg);
+        }
     }
 
     // Visibility of this wave's packed keys (used in the packed-key blocks only).  Of a tile's 32
@@ -329,7 +361,17 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
             // compiler wait for all loads in flight wherever it waits for one of them.
 #pragma unroll
             for (int s = 0; s < G::kLoads; ++s) *reinterpret_cast<uint4 *>(my_tile + k_wr(s)) = kreg[s];
-            load_tile(next_kb, next_key0, next_end, kreg);
+            int pid_cur_next = 0, t0_next = 0;
+            if (PAGED && !next_tree) {
+                // page of the tile fetched now (looked up one iteration ago), and the lookup for the
+                // block after it
+                pid_cur_next = pid_next;
+                t0_next = ctx_tile_first(next_key0, next_end);
+                if (inext + 1 < nA) pid_next = page_of(ctx_tile_first(next_key0 + kBlock, next_end));
+                load_tile_paged(Kc, pid_cur_next, t0_next, next_end, kreg);
+            } else {
+                load_tile(next_kb, next_key0, next_end, kreg);
+            }
             wave_lds_sync();
 
             // S^T tile pair: keys (16 mt + r) x packed rows (16 qt + c), raw (unscaled) scores
@@ -401,7 +443,8 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
             // V registers -> own LDS tile (V swizzle), replacing K which this wave has consumed
 #pragma unroll
             for (int s = 0; s < G::kLoads; ++s) *reinterpret_cast<uint4 *>(my_tile + v_wr(s)) = vreg[s];
-            load_tile(next_vb, next_key0, next_end, vreg);
+            if (PAGED && !next_tree) load_tile_paged(Vc, pid_cur_next, t0_next, next_end, vreg);
+            else load_tile(next_vb, next_key0, next_end, vreg);
 
             // online softmax with the block-wide maximum; P^T to LDS in B-operand layout
 #pragma unroll
@@ -661,62 +704,63 @@ static size_t mfma_smem_bytes()
            (size_t)NW * NQ * 16 * sizeof(float) + (size_t)NW * NQ * 64 * sizeof(uint32_t);
 }
 
-template <typename T, int D, int NQ, int NW, int TB>
+template <typename T, int D, int NQ, int NW, int TB, bool PAGED>
 static int launch_mfma(const AttnArgs &a, hipStream_t stream)
 {
     const size_t smem = mfma_smem_bytes<D, NQ, NW>();
     static std::atomic<unsigned long long> configured{0};
-    const int st = ensure_dynamic_lds(reinterpret_cast<const void *>(&rd_tree_attn_mfma_kernel<T, D, NQ, NW, TB>), smem,
+    const int st = ensure_dynamic_lds(reinterpret_cast<const void *>(&rd_tree_attn_mfma_kernel<T, D, NQ, NW, TB, PAGED>), smem,
                                       configured);
     if (st != RD_OK) return st;
     const size_t wgs = (size_t)a.B * a.H * (a.S + (a.fuse_tree ? 0 : 1)) * a.n_rg;
     if (wgs > 0x7fffffffull) return RD_ERR_UNSUPPORTED;
     const unsigned grid = (unsigned)wgs;
-    hipLaunchKernelGGL((rd_tree_attn_mfma_kernel<T, D, NQ, NW, TB>), dim3(grid), dim3(NW * 64), smem, stream, a);
+    hipLaunchKernelGGL((rd_tree_attn_mfma_kernel<T, D, NQ, NW, TB, PAGED>), dim3(grid), dim3(NW * 64), smem, stream, a);
     return rd_check_launch();
 }
 
 // rg_tiles = 16-row tiles per workgroup (the template's NQ); D = 128 kernels exist for 1..5 tiles,
 // D = 64 kernels for 1..8 (the plan never asks for more).  Beams with more packed keys than one
 // block (N > 32*NW) only occur with row groups, i.e. with kGroupTiles tiles.
-template <typename T, int D, int NW>
+template <typename T, int D, int NW, bool PAGED>
 static int dispatch_nq(const AttnArgs &a, int rg_tiles, hipStream_t stream)
 {
     constexpr int kGroupTiles = D == 128 ? 3 : 4;
     const int tb = (a.N + 32 * NW - 1) / (32 * NW);
     if (tb > 1) {
         if (rg_tiles != kGroupTiles) return RD_ERR_UNSUPPORTED;
-        if (tb == 2) return launch_mfma<T, D, kGroupTiles, NW, 2>(a, stream);
+        if (tb == 2) return launch_mfma<T, D, kGroupTiles, NW, 2, PAGED>(a, stream);
         if constexpr (NW == 4) {
-            if (tb == 3) return launch_mfma<T, D, kGroupTiles, 4, 3>(a, stream);
+            if (tb == 3) return launch_mfma<T, D, kGroupTiles, 4, 3, PAGED>(a, stream);
         }
         return RD_ERR_UNSUPPORTED;
     }
     switch (rg_tiles) {
-    case 1: return launch_mfma<T, D, 1, NW, 1>(a, stream);
-    case 2: return launch_mfma<T, D, 2, NW, 1>(a, stream);
-    case 3: return launch_mfma<T, D, 3, NW, 1>(a, stream);
-    case 4: return launch_mfma<T, D, 4, NW, 1>(a, stream);
-    case 5: return launch_mfma<T, D, 5, NW, 1>(a, stream);
+    case 1: return launch_mfma<T, D, 1, NW, 1, PAGED>(a, stream);
+    case 2: return launch_mfma<T, D, 2, NW, 1, PAGED>(a, stream);
+    case 3: return launch_mfma<T, D, 3, NW, 1, PAGED>(a, stream);
+    case 4: return launch_mfma<T, D, 4, NW, 1, PAGED>(a, stream);
+    case 5: return launch_mfma<T, D, 5, NW, 1, PAGED>(a, stream);
     default: break;
     }
     if constexpr (D == 64) {
         switch (rg_tiles) {
-        case 6: return launch_mfma<T, 64, 6, NW, 1>(a, stream);
-        case 7: return launch_mfma<T, 64, 7, NW, 1>(a, stream);
-        case 8: return launch_mfma<T, 64, 8, NW, 1>(a, stream);
+        case 6: return launch_mfma<T, 64, 6, NW, 1, PAGED>(a, stream);
+        case 7: return launch_mfma<T, 64, 7, NW, 1, PAGED>(a, stream);
+        case 8: return launch_mfma<T, 64, 8, NW, 1, PAGED>(a, stream);
         default: break;
         }
     }
     return RD_ERR_UNSUPPORTED;
 }
 
-template <typename T>
+template <typename T, bool PAGED>
 static int tree_attn_mfma(const AttnArgs &a, int D, int waves, int rg_tiles, hipStream_t stream)
 {
     if (D == 128)
-        return waves == 8 ? dispatch_nq<T, 128, 8>(a, rg_tiles, stream) : dispatch_nq<T, 128, 4>(a, rg_tiles, stream);
-    return dispatch_nq<T, 64, 4>(a, rg_tiles, stream);
+        return waves == 8 ? dispatch_nq<T, 128, 8, PAGED>(a, rg_tiles, stream)
+                          : dispatch_nq<T, 128, 4, PAGED>(a, rg_tiles, stream);
+    return dispatch_nq<T, 64, 4, PAGED>(a, rg_tiles, stream);
 }
 
 }  // namespace rd

@@ -31,7 +31,8 @@ def _declared_symbols():
 def test_header_symbols_exported(lib):
     names = _declared_symbols()
     assert names == sorted(["rd_strerror", "rd_version", "rd_dedup", "rd_tree_attn_workspace",
-                            "rd_tree_attn", "rd_accept_workspace", "rd_accept", "rd_commit"])
+                            "rd_tree_attn", "rd_tree_attn_paged_workspace", "rd_tree_attn_paged",
+                            "rd_accept_workspace", "rd_accept", "rd_commit"])
     raw = ctypes.CDLL(LIB)
     for n in names:
         assert hasattr(raw, n), n
@@ -122,6 +123,33 @@ def test_accept_argument_errors(lib):
     assert _accept(lib, req=None) == INVALID
     assert _accept(lib, ws=None) == WORKSPACE
     assert _accept(lib, ws_bytes=8) == WORKSPACE
+
+
+def _paged(lib, B=1, H=2, N=8, D=64, ps=64, mp=4, npg=8, dt=1, q=FAKE, pages=FAKE, table=FAKE, ws=FAKE, ws_bytes=None):
+    import ctypes
+    need = lib.rd_tree_attn_paged_workspace(B, H, N, D, ps, mp, dt)
+    if ws_bytes is None:
+        ws_bytes = need
+    return lib.rd_tree_attn_paged(q, pages, pages, table, ps, mp, npg, FAKE, FAKE, FAKE, FAKE, FAKE,
+                                  B, H, N, D, dt, ctypes.c_float(0.125), FAKE, ws, ws_bytes, None)
+
+
+def test_paged_attention_argument_errors(lib):
+    assert _paged(lib, ps=0) == INVALID
+    assert _paged(lib, mp=0) == INVALID
+    assert _paged(lib, npg=0) == INVALID
+    assert _paged(lib, ps=48) == UNSUPPORTED              # a 32-key tile must not straddle pages
+    assert _paged(lib, dt=0) == UNSUPPORTED               # 16-bit caches only
+    assert _paged(lib, D=96) == UNSUPPORTED
+    assert _paged(lib, N=385) == UNSUPPORTED
+    assert _paged(lib, q=None) == INVALID
+    assert _paged(lib, pages=None) == INVALID
+    assert _paged(lib, table=None) == INVALID
+    assert _paged(lib, pages=FAKE + 8) == INVALID
+    assert _paged(lib, ws=None) == WORKSPACE
+    assert _paged(lib, ws_bytes=16) == WORKSPACE
+    assert lib.rd_tree_attn_paged_workspace(1, 2, 8, 64, 48, 4, 1) == 0
+    assert lib.rd_tree_attn_paged_workspace(1, 2, 8, 64, 64, 4, 1) >= 256
 
 
 def _commit(lib, B=1, H=2, N=8, D=64, Cmax=16, L=4, dt=0, src=FAKE, cache=FAKE, ctx=FAKE, ctx_out=FAKE + 64,

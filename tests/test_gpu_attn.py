@@ -247,3 +247,64 @@ def test_graph_replay_matches_eager(rd):
         got = snapshot()
         for k in eager:
             assert np.array_equal(got[k], eager[k]), (rep, k)
+
+
+def _to_pages(t, ps, rng, extra=5):
+    """Cuts the dense caches of case t into pages of ps keys scattered over a pool in random order."""
+    kc, vc, ctx = t["k_cache"], t["v_cache"], t["ctx_len"]
+    B, H, Cmax, D = kc.shape
+    max_pages = max(1, -(-Cmax // ps))
+    need = int(sum(-(-int(c) // ps) for c in ctx))
+    n_pages = need + extra
+    order = rng.permutation(n_pages)
+    poison = synth.poison_value("bf16" if kc.dtype == np.uint16 else "f16")
+    kp = np.full((n_pages, H, ps, D), poison, kc.dtype)
+    vp = np.full((n_pages, H, ps, D), poison, kc.dtype)
+    table = np.full((B, max_pages), -7, np.int32)
+    nxt = 0
+    for b in range(B):
+        for j in range(-(-int(ctx[b]) // ps)):
+            page = int(order[nxt]); nxt += 1
+            table[b, j] = page
+            n = min(ps, Cmax - j * ps)
+            kp[page, :, :n] = kc[b, :, j * ps:j * ps + n]
+            vp[page, :, :n] = vc[b, :, j * ps:j * ps + n]
+    return kp, vp, table
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("ps", [32, 64, 128, 256])
+@pytest.mark.parametrize("D,W,L,ctx", [(128, 8, 5, [0, 1, 31, 129, 300, 517]), (64, 16, 6, [700, 33]),
+                                       (128, 70, 5, [97, 640]), (128, 16, 5, [5000, 2311])])
+def test_paged_cache(rd, dtype, ps, D, W, L, ctx):
+    """rd_tree_attn_paged against the oracle's paged routine: pages scattered over a pool, every
+    page size, ragged contexts ending inside a page, wide beams, long contexts with several splits;
+    unused rows of the pages and unused table entries hold poison."""
+    announce("attn paged dtype=%s page=%d D=%d W=%d L=%d" % (dtype, ps, D, W, L))
+    rng = np.random.default_rng(ps + D + W)
+    t = make_case(len(ctx), 2, D, W, L, ctx, dtype, seed=ps + W, V=6)
+    kp, vp, table = _to_pages(t, ps, rng)
+    d = oracle.dedup(t["beams"], t["ctx_len"])
+    scale = float(1.0 / np.sqrt(D))
+    ref = oracle.tree_attn_paged(t["q"], kp, vp, np.maximum(table, 0), t["ctx_len"], t["k_new"], t["v_new"],
+                                 d["n_packed"], d["tree_mask"], dtype, scale)
+    got = rd.rd_tree_attn_paged(dev(t["q"]), dev(kp), dev(vp), dev(table), dev(t["ctx_len"]), dev(t["k_new"]),
+                                dev(t["v_new"]), dev(d["n_packed"]), dev(d["tree_mask_bits"]), scale)
+    torch.cuda.synchronize()
+    compare(host(got), ref, dtype, "paged")
+
+
+def test_paged_equals_dense_on_config2(rd):
+    """Same bits as the dense entry point on the Vicuna-7B-shaped layer (the arithmetic is identical;
+    only the addresses of the context tiles differ)."""
+    announce("attn paged vs dense, config 2")
+    cfg = synth.CONFIGS[2]
+    t = synth.make_attn_inputs(cfg, poison=False)
+    d = oracle.dedup(t["beams"], t["ctx_len"])
+    scale = float(1.0 / np.sqrt(cfg.D))
+    dense = gpu_attn(rd, t, d, cfg.dtype, scale)
+    kp, vp, table = _to_pages(t, 128, np.random.default_rng(2))
+    got = rd.rd_tree_attn_paged(dev(t["q"]), dev(kp), dev(vp), dev(table), dev(t["ctx_len"]), dev(t["k_new"]),
+                                dev(t["v_new"]), dev(d["n_packed"]), dev(d["tree_mask_bits"]), scale)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(got), dense)

@@ -258,3 +258,31 @@ def test_duplicate_candidate_changes_nothing():
     o2 = oracle.tree_attn_rows(pad(q), kc, vc, ctx, pad(kn), pad(vn), g2["n_packed"], g2["tree_mask"],
                                "f32", 0.25, rows)
     assert np.array_equal(o, o2)
+
+
+def test_paged_cache_equals_dense_cache():
+    """The paged wrapper against the dense routine: cutting a dense cache into pages, scattering the
+    pages over a larger pool in random order and pointing the block table at them changes nothing;
+    entries of the table beyond a sequence's last page are never looked at."""
+    rng = np.random.default_rng(8)
+    B, H, D, W, L, ps = 3, 2, 16, 4, 3, 32
+    ctx = np.array([70, 0, 96], np.int32)
+    beams = synth.make_beams(B, W, L, 5, 8)
+    q, kn, vn = synth.make_qkv_new(B, H, W * L, D, "f32", 8)
+    kc, vc = synth.make_kv_cache(B, H, 96, D, "f32", 8, ctx, poison=False)
+    g = oracle.dedup(beams, ctx)
+    dense = oracle.tree_attn(q, kc, vc, ctx, kn, vn, g["n_packed"], g["tree_mask"], "f32", 0.25)
+    max_pages, n_pages = 3, 20
+    order = rng.permutation(n_pages)
+    table = np.full((B, max_pages), 10 ** 6, np.int32)          # garbage where no page is needed
+    kp = rng.standard_normal((n_pages, H, ps, D)).astype(np.float32)
+    vp = rng.standard_normal((n_pages, H, ps, D)).astype(np.float32)
+    nxt = 0
+    for b in range(B):
+        for j in range(-(-int(ctx[b]) // ps)):
+            page = int(order[nxt]); nxt += 1
+            table[b, j] = page
+            kp[page] = kc[b, :, j * ps:(j + 1) * ps, :]
+            vp[page] = vc[b, :, j * ps:(j + 1) * ps, :]
+    paged = oracle.tree_attn_paged(q, kp, vp, table, ctx, kn, vn, g["n_packed"], g["tree_mask"], "f32", 0.25)
+    assert np.array_equal(paged, dense)
