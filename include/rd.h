@@ -206,6 +206,22 @@ int rd_commit(const void *k_new, const void *v_new, const int32_t *accepted_idx,
               void *k_cache, void *v_cache, int32_t *ctx_len_out, int32_t *n_committed,
               const void *hidden, int Dh, void *hidden_last, void *stream);
 
+/*
+ * rd_commit_paged — rd_commit for the paged cache of rd_tree_attn_paged: position p of sequence b is
+ * row p % page_size of page block_table[b][p / page_size] (pages [n_pages, H, page_size, D]); the
+ * capacity per sequence is page_size * max_pages.  The caller must have entered pages into the block
+ * table for every position that can be written (ctx_len[b] .. ctx_len[b] + L - 1); entries are
+ * clamped to [0, n_pages-1].  Everything else as for rd_commit (any page_size > 0; fp32 pages are
+ * accepted here although rd_tree_attn_paged reads 16-bit pages only).
+ */
+int rd_commit_paged(const void *k_new, const void *v_new, const int32_t *accepted_idx,
+                    const int32_t *best_len, const int32_t *ctx_len,
+                    int B, int H, int N, int D, int L, rd_dtype dt,
+                    void *k_pages, void *v_pages, const int32_t *block_table,
+                    int page_size, int max_pages, int n_pages,
+                    int32_t *ctx_len_out, int32_t *n_committed,
+                    const void *hidden, int Dh, void *hidden_last, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

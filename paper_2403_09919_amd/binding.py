@@ -39,6 +39,7 @@ EXPORTS = {
     "rd_accept_workspace": (_sz, [_i, _i, _i, _i]),
     "rd_accept": (_i, [_vp] * 5 + [_i, _i, _i, _i] + [_vp] * 6 + [_vp, _sz, _vp]),
     "rd_commit": (_i, [_vp] * 5 + [_i] * 7 + [_vp] * 4 + [_vp, _i, _vp, _vp]),
+    "rd_commit_paged": (_i, [_vp] * 5 + [_i] * 6 + [_vp] * 3 + [_i, _i, _i] + [_vp, _vp] + [_vp, _i, _vp, _vp]),
 }
 for _name, (_res, _args) in EXPORTS.items():
     _fn = getattr(_lib, _name)
@@ -265,3 +266,29 @@ def rd_commit(k_new, v_new, accepted_idx, best_len, ctx_len, k_cache, v_cache,
         _ptr(hidden_last, k_new.dtype, (B, Dh), "hidden_last") if hidden is not None else None, _stream())
     _check(code, "rd_commit")
     return dict(ctx_len=ctx_len_out, n_committed=n_committed, hidden_last=hidden_last)
+
+
+def rd_commit_paged(k_new, v_new, accepted_idx, best_len, ctx_len, k_pages, v_pages, block_table,
+                    ctx_len_out: Optional[torch.Tensor] = None, n_committed: Optional[torch.Tensor] = None) -> dict:
+    """rd_commit into a paged cache IN PLACE (see include/rd.h, rd_commit_paged)."""
+    B, H, N, D = k_new.shape
+    n_pages, _, page_size, _ = k_pages.shape
+    max_pages = block_table.shape[1]
+    L = accepted_idx.shape[1]
+    i32 = torch.int32
+    dev = k_new.device
+    if ctx_len_out is None:
+        ctx_len_out = torch.empty((B,), dtype=i32, device=dev)
+    if n_committed is None:
+        n_committed = torch.empty((B,), dtype=i32, device=dev)
+    code = _lib.rd_commit_paged(
+        _ptr(k_new, None, (B, H, N, D), "k_new"), _ptr(v_new, k_new.dtype, (B, H, N, D), "v_new"),
+        _ptr(accepted_idx, i32, (B, L), "accepted_idx"), _ptr(best_len, i32, (B,), "best_len"),
+        _ptr(ctx_len, i32, (B,), "ctx_len"), B, H, N, D, L, _dt_code(k_new),
+        _ptr(k_pages, k_new.dtype, (n_pages, H, page_size, D), "k_pages"),
+        _ptr(v_pages, k_new.dtype, (n_pages, H, page_size, D), "v_pages"),
+        _ptr(block_table, i32, (B, max_pages), "block_table"), page_size, max_pages, n_pages,
+        _ptr(ctx_len_out, i32, (B,), "ctx_len_out"), _ptr(n_committed, i32, (B,), "n_committed"),
+        None, 0, None, _stream())
+    _check(code, "rd_commit_paged")
+    return dict(ctx_len=ctx_len_out, n_committed=n_committed)

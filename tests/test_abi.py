@@ -32,7 +32,7 @@ def test_header_symbols_exported(lib):
     names = _declared_symbols()
     assert names == sorted(["rd_strerror", "rd_version", "rd_dedup", "rd_tree_attn_workspace",
                             "rd_tree_attn", "rd_tree_attn_paged_workspace", "rd_tree_attn_paged",
-                            "rd_accept_workspace", "rd_accept", "rd_commit"])
+                            "rd_accept_workspace", "rd_accept", "rd_commit", "rd_commit_paged"])
     raw = ctypes.CDLL(LIB)
     for n in names:
         assert hasattr(raw, n), n
@@ -172,6 +172,20 @@ def test_commit_argument_errors(lib):
     assert _commit(lib, hidden=FAKE, Dh=0, hid_last=FAKE) == INVALID
     assert _commit(lib, hidden=FAKE, Dh=6, hid_last=FAKE) == INVALID   # 24 bytes: not a multiple of 16
     assert _commit(lib, hidden=FAKE, Dh=8, hid_last=None) == INVALID
+
+
+def test_commit_paged_argument_errors(lib):
+    def call(B=1, H=2, N=8, D=64, L=4, dt=1, ps=64, mp=2, npg=4, pages=FAKE, table=FAKE, ctx_out=FAKE + 64):
+        return lib.rd_commit_paged(FAKE, FAKE, FAKE, FAKE, FAKE, B, H, N, D, L, dt, pages, pages, table, ps, mp, npg,
+                                   ctx_out, None, None, 0, None, None)
+    assert call(ps=0) == INVALID
+    assert call(npg=0) == INVALID
+    assert call(D=96) == UNSUPPORTED
+    assert call(dt=9) == UNSUPPORTED
+    assert call(pages=None) == INVALID
+    assert call(table=None) == INVALID
+    assert call(ctx_out=FAKE) == INVALID                     # must not be ctx_len itself
+    assert call(pages=FAKE + 8) == INVALID
 
 
 def test_binding_rejects_host_tensors():

@@ -113,3 +113,38 @@ def test_decode_loop_reproduces_greedy_decoding(rd, seed):
         steps += 1
     assert seq == truth[:len(seq)]
     assert steps < n_new
+
+
+@pytest.mark.parametrize("dtype,ps", [("bf16", 32), ("f16", 128), ("f32", 16)])
+def test_commit_paged_matches_dense_oracle(rd, dtype, ps):
+    """Committing into pages and reading the pages back through the block table gives the cache the
+    oracle's (dense) commit gives; pages that belong to nobody are untouched."""
+    announce(f"commit paged {dtype} page={ps}")
+    rng = np.random.default_rng(ps)
+    B, H, N, D, L = 3, 4, 40, 128, 5
+    max_pages = 4
+    Cmax = ps * max_pages
+    k_new, v_new, acc, best_len, ctx, kc, vc, _ = _case(rng, B, H, N, D, Cmax, L, dtype, 0)
+    ref = oracle.commit(k_new, v_new, acc, best_len, ctx, kc, vc, dtype)
+    n_pages = B * max_pages + 3
+    order = rng.permutation(n_pages)
+    table = order[:B * max_pages].reshape(B, max_pages).astype(np.int32)
+    kp = np.zeros((n_pages, H, ps, D), kc.dtype)
+    vp = np.zeros((n_pages, H, ps, D), kc.dtype)
+    for b in range(B):
+        for j in range(max_pages):
+            kp[table[b, j]] = kc[b, :, j * ps:(j + 1) * ps]
+            vp[table[b, j]] = vc[b, :, j * ps:(j + 1) * ps]
+    spare = order[B * max_pages:]
+    kp[spare] = k_new.flat[0]
+    kp_d, vp_d = dev(kp), dev(vp)
+    got = rd.rd_commit_paged(dev(k_new), dev(v_new), dev(acc), dev(best_len), dev(ctx), kp_d, vp_d, dev(table))
+    torch.cuda.synchronize()
+    kp_h, vp_h = host(kp_d), host(vp_d)
+    for b in range(B):
+        for j in range(max_pages):
+            assert np.array_equal(kp_h[table[b, j]], ref["k_cache"][b, :, j * ps:(j + 1) * ps])
+            assert np.array_equal(vp_h[table[b, j]], ref["v_cache"][b, :, j * ps:(j + 1) * ps])
+    assert np.array_equal(kp_h[spare], kp[spare]) and np.array_equal(vp_h[spare], vp[spare])
+    assert np.array_equal(host(got["ctx_len"]), ref["ctx_len"])
+    assert np.array_equal(host(got["n_committed"]), ref["n_committed"])
