@@ -2,8 +2,8 @@
  * rd.h — C ABI of the ReDrafter verification step on AMD MI355X (gfx950).
  *
  * One speculative-decoding step of ReDrafter (arXiv 2403.09919, Sec. 3.4) verifies the
- * drafter's beam with the LLM.  This library implements the three parts of that step
- * that are not the LLM's dense layers:
+ * drafter's beam with the LLM.  This library implements the parts of that step that are
+ * not the LLM's dense layers:
  *
  *   rd_dedup      dynamic tree attention construction (Sec. 3.3, App. A.1): remove the
  *                 duplicated prefixes of W candidates of length L, giving a packed token
