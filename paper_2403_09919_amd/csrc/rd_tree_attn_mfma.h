@@ -565,7 +565,7 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
     }
 #pragma unroll
     for (int qt = 0; qt < NQ; ++qt) {
-        if (qt < nqt) {
+        if (qt * 16 + r16 < P) {                        // lanes whose row is padding neither store nor (in the merge) load
 #pragma unroll
             for (int j = 0; j < kDTW; ++j) {
                 const f32x4 o = oacc[j][qt];
@@ -635,7 +635,7 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
                         ml[u][c] = make_float2(-INFINITY, 0.f);                 // absent: weight 2^-inf = 0
 #pragma unroll
                         for (int j = 0; j < kDTW; ++j) f[u][c][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-                        if (have && (u == 0 || two)) {
+                        if (have && (u == 0 || two) && (qt0 + u) * 16 + r16 < P) {
                             const int qt = qt0 + u;
                             const float *pm = ps + 2 * (qt * 16 + r16);
                             const float *pf = ps + frag_off + qt * 256;
