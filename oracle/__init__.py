@@ -206,6 +206,20 @@ def commit(k_new, v_new, accepted_idx, best_len, ctx_len, k_cache, v_cache, dtyp
             "hidden_last": hid_last}
 
 
+def rope(x, position_ids, n_packed, cos_tab, sin_tab, dtype: str) -> np.ndarray:
+    """Rotary embedding ("rotate half" pairing) of rows p < n_packed[b] of x [B,H,N,D]; returns a copy."""
+    x = np.array(x, dtype=NP_DTYPES[dtype], order="C", copy=True)
+    B, H, N, D = x.shape
+    position_ids, n_packed = _i32(position_ids), _i32(n_packed)
+    cos_tab = np.ascontiguousarray(cos_tab, dtype=np.float32)
+    sin_tab = np.ascontiguousarray(sin_tab, dtype=np.float32)
+    max_pos = cos_tab.shape[0]
+    assert position_ids.shape == (B, N) and cos_tab.shape == (max_pos, D // 2) and sin_tab.shape == cos_tab.shape
+    lib().orc_rope(_p(x), _p(position_ids), _p(n_packed), _p(cos_tab), _p(sin_tab), max_pos,
+                   B, H, N, D, DTYPES[dtype])
+    return x
+
+
 def verify_step(beams, ctx_len, q, k_cache, v_cache, k_new, v_new, logits, dtype, scale,
                 root_token=None) -> dict:
     """The whole path in order: dedup -> tree attention -> argmax -> accept."""

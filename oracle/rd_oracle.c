@@ -456,3 +456,43 @@ void orc_commit(const void *k_new, const void *v_new, const int32_t *accepted_id
         }
     }
 }
+
+/* ---------------------------------------------------------------------------------
+ * Rotary position embedding of the packed candidates.  The paper does not spell out
+ * positions; with Vicuna (LLaMA family) as the LLM of Sec. 4, queries and keys carry
+ * rotary embeddings, and a packed token's position is ctx_len + depth (position_ids
+ * of the tree structure).  Convention: the LLaMA "rotate half" pairing, element i is
+ * paired with element i + D/2 and the pair is rotated by the angle pos * theta_i whose
+ * cosine and sine the caller supplies in tables [max_pos][D/2]:
+ *     y[i]       = x[i] * cos[pos][i] - x[i + D/2] * sin[pos][i]
+ *     y[i + D/2] = x[i + D/2] * cos[pos][i] + x[i] * sin[pos][i]
+ * applied in place to rows p < n_packed[b] of x [B,H,N,D]; the result is rounded once
+ * to the storage type.  pos is clamped to [0, max_pos - 1].                           */
+void orc_rope(void *x, const int32_t *position_ids /*[B,N]*/, const int32_t *n_packed,
+              const float *cos_tab, const float *sin_tab, int max_pos,
+              int B, int H, int N, int D, int dtype)
+{
+    const int half = D / 2;
+    double *y = (double *)malloc(sizeof(double) * (size_t)D);
+    for (int b = 0; b < B; ++b) {
+        int P = n_packed[b];
+        if (P < 0) P = 0;
+        if (P > N) P = N;
+        for (int h = 0; h < H; ++h)
+            for (int p = 0; p < P; ++p) {
+                int pos = position_ids[(size_t)b * N + p];
+                if (pos < 0) pos = 0;
+                if (pos > max_pos - 1) pos = max_pos - 1;
+                const size_t row = (((size_t)b * H + h) * N + p) * (size_t)D;
+                for (int i = 0; i < half; ++i) {
+                    const double c = (double)cos_tab[(size_t)pos * half + i];
+                    const double s = (double)sin_tab[(size_t)pos * half + i];
+                    const double lo = load_elem(x, row + i, dtype), hi = load_elem(x, row + i + half, dtype);
+                    y[i] = lo * c - hi * s;
+                    y[i + half] = hi * c + lo * s;
+                }
+                for (int d = 0; d < D; ++d) store_elem(x, row + d, dtype, y[d]);
+            }
+    }
+    free(y);
+}
