@@ -15,7 +15,10 @@
  *                 best candidate, next token;
  *   rd_commit     what follows acceptance (Sec. 3.4): the accepted tokens join the context
  *                 (their K/V rows are appended to the cache, ctx_len grows) and the LLM's
- *                 hidden state at the last accepted token is picked out for the next draft.
+ *                 hidden state at the last accepted token is picked out for the next draft;
+ *   rd_rope       rotary position embedding of the packed queries and keys at rd_dedup's
+ *                 position ids (for LLaMA-family LLMs such as the paper's Vicuna models).
+ * rd_tree_attn_paged and rd_commit_paged are the same over a paged KV cache.
  *
  * Conventions for every entry point
  *   - All tensor pointers are DEVICE pointers to dense row-major arrays (last index
@@ -205,6 +208,28 @@ int rd_commit(const void *k_new, const void *v_new, const int32_t *accepted_idx,
               int B, int H, int N, int D, int Cmax, int L, rd_dtype dt,
               void *k_cache, void *v_cache, int32_t *ctx_len_out, int32_t *n_committed,
               const void *hidden, int Dh, void *hidden_last, void *stream);
+
+/*
+ * rd_rope — rotary position embedding of the packed candidates, at the positions rd_dedup produced.
+ * The paper leaves positions to the LLM; its LLMs (Vicuna, Sec. 4) are LLaMA-family models whose
+ * attention rotates queries and keys, and a packed token sits at position ctx_len + depth
+ * (rd_dedup's position_ids).  Run it on q and k_new before rd_tree_attn (and rd_commit then stores
+ * rotated keys, as such a model's cache holds them).
+ *
+ * For b, h, packed row p < n_packed[b], pos = position_ids[b][p] clamped to [0, max_pos-1], i < D/2:
+ *     y[i]       = x[i] * cos_tab[pos][i] - x[i + D/2] * sin_tab[pos][i]
+ *     y[i + D/2] = x[i + D/2] * cos_tab[pos][i] + x[i] * sin_tab[pos][i]
+ * ("rotate half" pairing), computed in fp32 with every product rounded before the sum, rounded once
+ * to the storage type, in place.  Rows p >= n_packed[b] are left untouched.
+ *
+ *   q, k_new : [B,H,N,D], element type by `dt` (any of the three), 32-byte aligned; either may be
+ *   NULL (skipped).  position_ids : int32 [B,N];  n_packed : int32 [B].
+ *   cos_tab, sin_tab : float [max_pos, D/2], cos / sin of pos * theta_i for whatever base and
+ *   scaling the model uses (the library does no trigonometry).
+ */
+int rd_rope(void *q, void *k_new, const int32_t *position_ids, const int32_t *n_packed,
+            const float *cos_tab, const float *sin_tab, int max_pos,
+            int B, int H, int N, int D, rd_dtype dt, void *stream);
 
 /*
  * rd_commit_paged — rd_commit for the paged cache of rd_tree_attn_paged: position p of sequence b is

@@ -39,6 +39,7 @@ EXPORTS = {
     "rd_accept_workspace": (_sz, [_i, _i, _i, _i]),
     "rd_accept": (_i, [_vp] * 5 + [_i, _i, _i, _i] + [_vp] * 6 + [_vp, _sz, _vp]),
     "rd_commit": (_i, [_vp] * 5 + [_i] * 7 + [_vp] * 4 + [_vp, _i, _vp, _vp]),
+    "rd_rope": (_i, [_vp] * 6 + [_i] * 6 + [_vp]),
     "rd_commit_paged": (_i, [_vp] * 5 + [_i] * 6 + [_vp] * 3 + [_i, _i, _i] + [_vp, _vp] + [_vp, _i, _vp, _vp]),
 }
 for _name, (_res, _args) in EXPORTS.items():
@@ -292,3 +293,18 @@ def rd_commit_paged(k_new, v_new, accepted_idx, best_len, ctx_len, k_pages, v_pa
         None, 0, None, _stream())
     _check(code, "rd_commit_paged")
     return dict(ctx_len=ctx_len_out, n_committed=n_committed)
+
+
+def rd_rope(q, k_new, position_ids, n_packed, cos_tab, sin_tab) -> None:
+    """Rotates q and k_new [B,H,N,D] IN PLACE at position_ids [B,N] (see include/rd.h, rd_rope);
+    cos_tab/sin_tab float32 [max_pos, D/2]."""
+    ref = q if q is not None else k_new
+    B, H, N, D = ref.shape
+    max_pos = cos_tab.shape[0]
+    code = _lib.rd_rope(
+        _ptr(q, ref.dtype, (B, H, N, D), "q") if q is not None else None,
+        _ptr(k_new, ref.dtype, (B, H, N, D), "k_new") if k_new is not None else None,
+        _ptr(position_ids, torch.int32, (B, N), "position_ids"), _ptr(n_packed, torch.int32, (B,), "n_packed"),
+        _ptr(cos_tab, torch.float32, (max_pos, D // 2), "cos_tab"), _ptr(sin_tab, torch.float32, (max_pos, D // 2), "sin_tab"),
+        max_pos, B, H, N, D, _dt_code(ref), _stream())
+    _check(code, "rd_rope")

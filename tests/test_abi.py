@@ -32,7 +32,7 @@ def test_header_symbols_exported(lib):
     names = _declared_symbols()
     assert names == sorted(["rd_strerror", "rd_version", "rd_dedup", "rd_tree_attn_workspace",
                             "rd_tree_attn", "rd_tree_attn_paged_workspace", "rd_tree_attn_paged",
-                            "rd_accept_workspace", "rd_accept", "rd_commit", "rd_commit_paged"])
+                            "rd_accept_workspace", "rd_accept", "rd_commit", "rd_commit_paged", "rd_rope"])
     raw = ctypes.CDLL(LIB)
     for n in names:
         assert hasattr(raw, n), n
@@ -186,6 +186,20 @@ def test_commit_paged_argument_errors(lib):
     assert call(table=None) == INVALID
     assert call(ctx_out=FAKE) == INVALID                     # must not be ctx_len itself
     assert call(pages=FAKE + 8) == INVALID
+
+
+def test_rope_argument_errors(lib):
+    def call(q=FAKE, k=FAKE, pos=FAKE, tab=FAKE, max_pos=16, B=1, H=2, N=8, D=64, dt=1):
+        return lib.rd_rope(q, k, pos, FAKE, tab, tab, max_pos, B, H, N, D, dt, None)
+    assert call(B=0) == INVALID
+    assert call(max_pos=0) == INVALID
+    assert call(D=96) == UNSUPPORTED
+    assert call(N=385) == UNSUPPORTED
+    assert call(dt=4) == UNSUPPORTED
+    assert call(q=None, k=None) == INVALID
+    assert call(pos=None) == INVALID
+    assert call(tab=None) == INVALID
+    assert call(q=FAKE + 16) == INVALID                      # 32-byte alignment
 
 
 def test_binding_rejects_host_tensors():
