@@ -220,6 +220,49 @@ def rope(x, position_ids, n_packed, cos_tab, sin_tab, dtype: str) -> np.ndarray:
     return x
 
 
+def _draft_args(params, h, Dm):
+    emb = np.ascontiguousarray(params["emb"], np.uint16)
+    V = emb.shape[0]
+    mlp_w = np.ascontiguousarray(params["mlp_w"], np.uint16)
+    n_mlp = mlp_w.shape[0]
+    assert emb.shape == (V, Dm) and params["rnn_u"].shape == (Dm, Dm) and params["rnn_w"].shape == (Dm, Dm)
+    assert mlp_w.shape == (n_mlp, 2 * Dm, 2 * Dm) and params["head_w"].shape == (V, 2 * Dm)
+    arrs = dict(emb=emb, rnn_u=np.ascontiguousarray(params["rnn_u"], np.uint16),
+                rnn_w=np.ascontiguousarray(params["rnn_w"], np.uint16),
+                rnn_b=np.ascontiguousarray(params["rnn_b"], np.float32), mlp_w=mlp_w,
+                mlp_b=np.ascontiguousarray(params["mlp_b"], np.float32),
+                head_w=np.ascontiguousarray(params["head_w"], np.uint16),
+                h=np.ascontiguousarray(h, np.uint16))
+    return arrs, V, n_mlp
+
+
+def draft(params: dict, h, last_token, W: int, L: int) -> dict:
+    """Draft model + beam search (Sec. 3.1, 3.2).  params: bf16 bit patterns emb [V,Dm], rnn_u, rnn_w
+    [Dm,Dm], mlp_w [K,2Dm,2Dm], head_w [V,2Dm]; float32 rnn_b [Dm], mlp_b [K,2Dm].  h bf16 bits [B,Dm],
+    last_token int32 [B].  Returns beams int32 [B,W,L] (position 0 = last_token) and beam_logp [B,W]."""
+    B, Dm = np.asarray(h).shape
+    a, V, n_mlp = _draft_args(params, h, Dm)
+    last_token = _i32(last_token)
+    assert 1 <= W <= V and L >= 1
+    beams = np.empty((B, W, L), np.int32)
+    logp = np.empty((B, W), np.float32)
+    lib().orc_draft(_p(a["emb"]), _p(a["rnn_u"]), _p(a["rnn_w"]), _p(a["rnn_b"]), _p(a["mlp_w"]), _p(a["mlp_b"]),
+                    n_mlp, _p(a["head_w"]), _p(a["h"]), _p(last_token), B, Dm, V, W, L, _p(beams), _p(logp))
+    return {"beams": beams, "beam_logp": logp}
+
+
+def draft_path_logp(params: dict, h, paths) -> np.ndarray:
+    """Cumulative log probability (float64 [B,n]) of candidate paths int32 [B,n,L] under the draft model."""
+    B, Dm = np.asarray(h).shape
+    a, V, n_mlp = _draft_args(params, h, Dm)
+    paths = _i32(paths)
+    n, L = paths.shape[1:]
+    out = np.empty((B, n), np.float64)
+    lib().orc_draft_path_logp(_p(a["emb"]), _p(a["rnn_u"]), _p(a["rnn_w"]), _p(a["rnn_b"]), _p(a["mlp_w"]),
+                              _p(a["mlp_b"]), n_mlp, _p(a["head_w"]), _p(a["h"]), _p(paths), B, n, Dm, V, L, _p(out))
+    return out
+
+
 def verify_step(beams, ctx_len, q, k_cache, v_cache, k_new, v_new, logits, dtype, scale,
                 root_token=None) -> dict:
     """The whole path in order: dedup -> tree attention -> argmax -> accept."""

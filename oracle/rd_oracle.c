@@ -18,6 +18,7 @@
  * Every function in this file is pinned by tests that do not use this file's
  * own arithmetic (the worked example of App. A.1, a literal prefix trie, closed
  * forms, per-beam causal attention in numpy, library argmax, a toy greedy LM; for the
+ * draft model: a numpy/scipy forward pass, greedy decoding, exhaustive search; for the
  * commit: numpy index arithmetic, attention over the committed cache, and a many-step
  * speculative loop that must reproduce plain greedy decoding of a toy attention LM).
  *
@@ -495,4 +496,174 @@ void orc_rope(void *x, const int32_t *position_ids /*[B,N]*/, const int32_t *n_p
             }
     }
     free(y);
+}
+
+/* ---------------------------------------------------------------------------------
+ * The draft model and its beam search (Sec. 3.1, 3.2).  Per sequence:
+ *   s_1 = e(last token)                    the embedding of the LLM's latest token
+ *   g_t = [s_t, h]                         h = the LLM's last hidden state (Sec. 3.1)
+ *   x = g_t;  x <- x + f(A_k x + c_k)      "a few layers of MLPs with skip connections"
+ *   z = O x;  log p = log_softmax(z)       "a standard softmax layer"
+ *   s_{t+1} = f(U s_t + W e(token_t) + b)  the RNN update with the token chosen at step t
+ * The paper names no activation f; SiLU is this build's reading (it is what the public
+ * ReDrafter release uses).  Beam search of width W (Sec. 3.2) over T = L - 1 drafted
+ * tokens, position 0 of every candidate being the LLM's own token: at each step the
+ * candidates (beam w, token v) are ranked by cumulative log probability (ties: smaller w,
+ * then smaller v) and the best W survive; at the first step there is one state, so the W
+ * candidates are its W most probable tokens.
+ *
+ * Numerics (the precision contract shared with the device code): weights, embeddings and h
+ * are bf16; every linear layer reads its input vector rounded to bf16 and accumulates
+ * without further rounding; biases, activation, skip connection, log-softmax and scores
+ * are computed on unrounded values.  Here that arithmetic is double.
+ * Weights are row-major [out][in]: rnn_u, rnn_w [Dm][Dm]; mlp_w [n_mlp][2Dm][2Dm];
+ * head_w [V][2Dm]; emb [V][Dm].  Biases float.                                       */
+static double bf16_to_double(uint16_t b)
+{
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return (double)f;
+}
+static double round_bf16(double x) { return bf16_to_double(double_to_bf16(x)); }
+static double silu(double x) { return x / (1.0 + exp(-x)); }
+
+/* y[n] = sum_k round_bf16(x[k]) * W[n][k] (+ bias[n]) */
+static void linear_bf16(const uint16_t *Wt, const float *bias, int N, int K, const double *x, double *y)
+{
+    double *xr = (double *)malloc(sizeof(double) * (size_t)K);
+    for (int k = 0; k < K; ++k) xr[k] = round_bf16(x[k]);
+#pragma omp parallel for schedule(static)
+    for (int n = 0; n < N; ++n) {
+        const uint16_t *row = Wt + (size_t)n * K;
+        double acc = 0.0;
+        for (int k = 0; k < K; ++k) acc += xr[k] * bf16_to_double(row[k]);
+        y[n] = acc + (bias ? (double)bias[n] : 0.0);
+    }
+    free(xr);
+}
+
+/* log-probabilities of the next token given RNN state s and hidden h; lp has V entries */
+static void draft_logp(const uint16_t *mlp_w, const float *mlp_b, int n_mlp, const uint16_t *head_w,
+                       const double *s, const double *h, int Dm, int V, double *lp)
+{
+    const int G = 2 * Dm;
+    double *x = (double *)malloc(sizeof(double) * (size_t)G);
+    double *y = (double *)malloc(sizeof(double) * (size_t)G);
+    for (int i = 0; i < Dm; ++i) { x[i] = s[i]; x[Dm + i] = h[i]; }
+    for (int k = 0; k < n_mlp; ++k) {
+        linear_bf16(mlp_w + (size_t)k * G * G, mlp_b ? mlp_b + (size_t)k * G : NULL, G, G, x, y);
+        for (int i = 0; i < G; ++i) x[i] += silu(y[i]);
+    }
+    linear_bf16(head_w, NULL, V, G, x, lp);
+    double m = -INFINITY, sum = 0.0;
+    for (int v = 0; v < V; ++v) if (lp[v] > m) m = lp[v];
+    for (int v = 0; v < V; ++v) sum += exp(lp[v] - m);
+    const double lse = m + log(sum);
+    for (int v = 0; v < V; ++v) lp[v] -= lse;
+    free(x);
+    free(y);
+}
+
+/* s_next = f(U s + W e(token) + b) */
+static void draft_rnn(const uint16_t *emb, const uint16_t *rnn_u, const uint16_t *rnn_w, const float *rnn_b,
+                      const double *s, int token, int Dm, double *s_next)
+{
+    double *e = (double *)malloc(sizeof(double) * (size_t)Dm);
+    double *a = (double *)malloc(sizeof(double) * (size_t)Dm);
+    double *c = (double *)malloc(sizeof(double) * (size_t)Dm);
+    for (int i = 0; i < Dm; ++i) e[i] = bf16_to_double(emb[(size_t)token * Dm + i]);
+    linear_bf16(rnn_u, NULL, Dm, Dm, s, a);
+    linear_bf16(rnn_w, rnn_b, Dm, Dm, e, c);
+    for (int i = 0; i < Dm; ++i) s_next[i] = silu(a[i] + c[i]);
+    free(e);
+    free(a);
+    free(c);
+}
+
+void orc_draft(const uint16_t *emb, const uint16_t *rnn_u, const uint16_t *rnn_w, const float *rnn_b,
+               const uint16_t *mlp_w, const float *mlp_b, int n_mlp, const uint16_t *head_w,
+               const uint16_t *h /*[B][Dm] bf16*/, const int32_t *last_token /*[B]*/,
+               int B, int Dm, int V, int W, int L,
+               int32_t *beams /*[B][W][L]*/, float *beam_logp /*[B][W]*/)
+{
+    const int T = L - 1;
+    double *hd = (double *)malloc(sizeof(double) * (size_t)Dm);
+    double *s = (double *)malloc(sizeof(double) * (size_t)W * Dm);        /* state per live beam */
+    double *s2 = (double *)malloc(sizeof(double) * (size_t)W * Dm);
+    double *lp = (double *)malloc(sizeof(double) * (size_t)W * V);
+    double *cum = (double *)malloc(sizeof(double) * (size_t)W), *cum2 = (double *)malloc(sizeof(double) * (size_t)W);
+    int32_t *path = (int32_t *)malloc(sizeof(int32_t) * (size_t)W * L), *path2 = (int32_t *)malloc(sizeof(int32_t) * (size_t)W * L);
+    unsigned char *taken = (unsigned char *)malloc((size_t)W * V);
+    for (int b = 0; b < B; ++b) {
+        for (int i = 0; i < Dm; ++i) {
+            hd[i] = bf16_to_double(h[(size_t)b * Dm + i]);
+            s[i] = bf16_to_double(emb[(size_t)last_token[b] * Dm + i]);
+        }
+        int live = 1;
+        cum[0] = 0.0;
+        path[0] = last_token[b];
+        for (int w = 0; w < W; ++w) { beam_logp[(size_t)b * W + w] = 0.f; for (int j = 0; j < L; ++j) beams[((size_t)b * W + w) * L + j] = last_token[b]; }
+        for (int t = 1; t <= T; ++t) {
+            for (int w = 0; w < live; ++w)
+                draft_logp(mlp_w, mlp_b, n_mlp, head_w, s + (size_t)w * Dm, hd, Dm, V, lp + (size_t)w * V);
+            memset(taken, 0, (size_t)live * V);
+            for (int r = 0; r < W; ++r) {                 /* the r-th best candidate (beam w, token v) */
+                int bw = -1, bv = -1;
+                double best = -INFINITY;
+                for (int w = 0; w < live; ++w)
+                    for (int v = 0; v < V; ++v) {
+                        if (taken[(size_t)w * V + v]) continue;
+                        const double sc = cum[w] + lp[(size_t)w * V + v];
+                        if (bw < 0 || sc > best) { best = sc; bw = w; bv = v; }   /* scan order = (w, v) ascending */
+                    }
+                taken[(size_t)bw * V + bv] = 1;
+                cum2[r] = best;
+                memcpy(path2 + (size_t)r * L, path + (size_t)bw * L, sizeof(int32_t) * (size_t)t);
+                path2[(size_t)r * L + t] = bv;
+                if (t < T) draft_rnn(emb, rnn_u, rnn_w, rnn_b, s + (size_t)bw * Dm, bv, Dm, s2 + (size_t)r * Dm);
+            }
+            live = W;
+            memcpy(cum, cum2, sizeof(double) * (size_t)W);
+            memcpy(path, path2, sizeof(int32_t) * (size_t)W * L);
+            if (t < T) memcpy(s, s2, sizeof(double) * (size_t)W * Dm);
+        }
+        if (T >= 1)
+            for (int w = 0; w < W; ++w) {
+                beam_logp[(size_t)b * W + w] = (float)cum[w];
+                memcpy(beams + ((size_t)b * W + w) * L, path + (size_t)w * L, sizeof(int32_t) * (size_t)L);
+            }
+    }
+    free(hd); free(s); free(s2); free(lp); free(cum); free(cum2); free(path); free(path2); free(taken);
+}
+
+/* Cumulative log probability of given candidates under the draft model (teacher forcing):
+ * paths [B][n_paths][L] with position 0 the LLM's token; out [B][n_paths].               */
+void orc_draft_path_logp(const uint16_t *emb, const uint16_t *rnn_u, const uint16_t *rnn_w, const float *rnn_b,
+                         const uint16_t *mlp_w, const float *mlp_b, int n_mlp, const uint16_t *head_w,
+                         const uint16_t *h, const int32_t *paths, int B, int n_paths, int Dm, int V, int L,
+                         double *out)
+{
+    double *hd = (double *)malloc(sizeof(double) * (size_t)Dm);
+    double *s = (double *)malloc(sizeof(double) * (size_t)Dm), *s2 = (double *)malloc(sizeof(double) * (size_t)Dm);
+    double *lp = (double *)malloc(sizeof(double) * (size_t)V);
+    for (int b = 0; b < B; ++b)
+        for (int r = 0; r < n_paths; ++r) {
+            const int32_t *p = paths + ((size_t)b * n_paths + r) * L;
+            for (int i = 0; i < Dm; ++i) {
+                hd[i] = bf16_to_double(h[(size_t)b * Dm + i]);
+                s[i] = bf16_to_double(emb[(size_t)p[0] * Dm + i]);
+            }
+            double total = 0.0;
+            for (int t = 1; t < L; ++t) {
+                draft_logp(mlp_w, mlp_b, n_mlp, head_w, s, hd, Dm, V, lp);
+                total += lp[p[t]];
+                if (t + 1 < L) {
+                    draft_rnn(emb, rnn_u, rnn_w, rnn_b, s, p[t], Dm, s2);
+                    memcpy(s, s2, sizeof(double) * (size_t)Dm);
+                }
+            }
+            out[(size_t)b * n_paths + r] = total;
+        }
+    free(hd); free(s); free(s2); free(lp);
 }
