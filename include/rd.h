@@ -18,6 +18,8 @@
  *                 hidden state at the last accepted token is picked out for the next draft;
  *   rd_rope       rotary position embedding of the packed queries and keys at rd_dedup's
  *                 position ids (for LLaMA-family LLMs such as the paper's Vicuna models).
+ *   rd_draft      the step before: the draft model and its beam search (Sec. 3.1, 3.2), which
+ *                 produce the candidates.
  * rd_tree_attn_paged and rd_commit_paged are the same over a paged KV cache.
  *
  * Conventions for every entry point
@@ -246,6 +248,47 @@ int rd_commit_paged(const void *k_new, const void *v_new, const int32_t *accepte
                     int page_size, int max_pages, int n_pages,
                     int32_t *ctx_len_out, int32_t *n_committed,
                     const void *hidden, int Dh, void *hidden_last, void *stream);
+
+/*
+ * rd_draft — the draft model and its beam search (Sec. 3.1, 3.2): produces the W candidates of
+ * length L that rd_dedup takes, from the LLM's last hidden state and latest token.
+ *
+ *   s_1 = e(last_token);  at drafted position t = 1 .. L-1, for every live candidate:
+ *     g = [s_t, h];  x = g;  x <- x + f(A_k x + c_k) for k < n_mlp;  log p = log_softmax(O x)
+ *   the best W (candidate, token) pairs by cumulative log probability survive (ties: smaller
+ *   candidate, then smaller token; at t = 1 there is one state, so they are its W most probable
+ *   tokens), and s_{t+1} = f(U s_t[parent] + W e(token) + b).  f = SiLU (the paper names none).
+ *   beams[b][w] = [last_token[b], token_1, ..., token_{L-1}], best candidate first;
+ *   beam_logp[b][w] = its cumulative log probability (0 when L == 1).
+ *
+ * Precision: weights, embeddings and h are bf16; every linear layer reads its input rounded to
+ * bf16 and accumulates in fp32; biases, activation, skip connection, log-softmax, scores fp32.
+ * Two candidates whose scores differ by less than that arithmetic resolves may swap places
+ * against an exact evaluation.
+ *
+ * rd_draft_params (a HOST struct of DEVICE pointers, all weights row-major [out][in], 16-byte
+ * aligned): emb bf16 [V,Dm]; rnn_u, rnn_w bf16 [Dm,Dm]; rnn_b float [Dm]; mlp_w bf16
+ * [n_mlp,2Dm,2Dm]; mlp_b float [n_mlp,2Dm]; head_w bf16 [V,2Dm].
+ * h : bf16 [B,Dm];  last_token : int32 [B] (clamped to [0, V-1]);  beams : int32 [B,W,L];
+ * beam_logp : float [B,W].  workspace: rd_draft_workspace(...) bytes, 256-byte aligned, no
+ * initial contents required, not shared by concurrent calls.
+ * Limits: Dm a multiple of 64; W <= 32, W <= V; B*W <= 128; V <= 32768; L <= 384.
+ * The call enqueues 3 + n_mlp launches per drafted position.
+ */
+typedef struct {
+    const void *emb, *rnn_u, *rnn_w;
+    const float *rnn_b;
+    const void *mlp_w;
+    const float *mlp_b;
+    const void *head_w;
+    int n_mlp, Dm, V;
+} rd_draft_params;
+
+size_t rd_draft_workspace(int B, int W, int L, int Dm, int V);
+
+int rd_draft(const rd_draft_params *p, const void *h, const int32_t *last_token,
+             int B, int W, int L, int32_t *beams, float *beam_logp,
+             void *workspace, size_t workspace_bytes, void *stream);
 
 #ifdef __cplusplus
 }

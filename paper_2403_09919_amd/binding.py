@@ -39,6 +39,8 @@ EXPORTS = {
     "rd_accept_workspace": (_sz, [_i, _i, _i, _i]),
     "rd_accept": (_i, [_vp] * 5 + [_i, _i, _i, _i] + [_vp] * 6 + [_vp, _sz, _vp]),
     "rd_commit": (_i, [_vp] * 5 + [_i] * 7 + [_vp] * 4 + [_vp, _i, _vp, _vp]),
+    "rd_draft_workspace": (_sz, [_i, _i, _i, _i, _i]),
+    "rd_draft": (_i, [_vp, _vp, _vp, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]),
     "rd_rope": (_i, [_vp] * 6 + [_i] * 6 + [_vp]),
     "rd_commit_paged": (_i, [_vp] * 5 + [_i] * 6 + [_vp] * 3 + [_i, _i, _i] + [_vp, _vp] + [_vp, _i, _vp, _vp]),
 }
@@ -308,3 +310,41 @@ def rd_rope(q, k_new, position_ids, n_packed, cos_tab, sin_tab) -> None:
         _ptr(cos_tab, torch.float32, (max_pos, D // 2), "cos_tab"), _ptr(sin_tab, torch.float32, (max_pos, D // 2), "sin_tab"),
         max_pos, B, H, N, D, _dt_code(ref), _stream())
     _check(code, "rd_rope")
+
+
+class _DraftParams(ctypes.Structure):
+    _fields_ = [("emb", _vp), ("rnn_u", _vp), ("rnn_w", _vp), ("rnn_b", _vp), ("mlp_w", _vp), ("mlp_b", _vp),
+                ("head_w", _vp), ("n_mlp", _i), ("Dm", _i), ("V", _i)]
+
+
+def rd_draft_workspace(B: int, W: int, L: int, Dm: int, V: int) -> int:
+    return int(_lib.rd_draft_workspace(B, W, L, Dm, V))
+
+
+def rd_draft(params: dict, h, last_token, W: int, L: int, out: Optional[dict] = None,
+             workspace: Optional[torch.Tensor] = None) -> dict:
+    """Draft model + beam search (see include/rd.h, rd_draft).  params: device tensors emb [V,Dm],
+    rnn_u, rnn_w [Dm,Dm], mlp_w [K,2Dm,2Dm], head_w [V,2Dm] (bfloat16), rnn_b [Dm], mlp_b [K,2Dm]
+    (float32); h bfloat16 [B,Dm]; last_token int32 [B] -> dict(beams int32 [B,W,L], beam_logp [B,W])."""
+    bf = torch.bfloat16
+    V, Dm = params["emb"].shape
+    K = params["mlp_w"].shape[0]
+    B = h.shape[0]
+    dev = h.device
+    p = _DraftParams(
+        _ptr(params["emb"], bf, (V, Dm), "emb"), _ptr(params["rnn_u"], bf, (Dm, Dm), "rnn_u"),
+        _ptr(params["rnn_w"], bf, (Dm, Dm), "rnn_w"), _ptr(params["rnn_b"], torch.float32, (Dm,), "rnn_b"),
+        _ptr(params["mlp_w"], bf, (K, 2 * Dm, 2 * Dm), "mlp_w") if K else None,
+        _ptr(params["mlp_b"], torch.float32, (K, 2 * Dm), "mlp_b") if K else None,
+        _ptr(params["head_w"], bf, (V, 2 * Dm), "head_w"), K, Dm, V)
+    if out is None:
+        out = dict(beams=torch.empty((B, W, L), dtype=torch.int32, device=dev),
+                   beam_logp=torch.empty((B, W), dtype=torch.float32, device=dev))
+    if workspace is None:
+        workspace = torch.empty(max(rd_draft_workspace(B, W, L, Dm, V), 256), dtype=torch.uint8, device=dev)
+    code = _lib.rd_draft(ctypes.byref(p), _ptr(h, bf, (B, Dm), "h"), _ptr(last_token, torch.int32, (B,), "last_token"),
+                         B, W, L, _ptr(out["beams"], torch.int32, (B, W, L), "beams"),
+                         _ptr(out["beam_logp"], torch.float32, (B, W), "beam_logp"),
+                         _ptr(workspace, torch.uint8, None, "workspace"), workspace.numel(), _stream())
+    _check(code, "rd_draft")
+    return out

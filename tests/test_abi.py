@@ -32,7 +32,8 @@ def test_header_symbols_exported(lib):
     names = _declared_symbols()
     assert names == sorted(["rd_strerror", "rd_version", "rd_dedup", "rd_tree_attn_workspace",
                             "rd_tree_attn", "rd_tree_attn_paged_workspace", "rd_tree_attn_paged",
-                            "rd_accept_workspace", "rd_accept", "rd_commit", "rd_commit_paged", "rd_rope"])
+                            "rd_accept_workspace", "rd_accept", "rd_commit", "rd_commit_paged", "rd_rope",
+                            "rd_draft_workspace", "rd_draft"])
     raw = ctypes.CDLL(LIB)
     for n in names:
         assert hasattr(raw, n), n
@@ -200,6 +201,32 @@ def test_rope_argument_errors(lib):
     assert call(pos=None) == INVALID
     assert call(tab=None) == INVALID
     assert call(q=FAKE + 16) == INVALID                      # 32-byte alignment
+
+
+def test_draft_argument_errors(lib):
+    import ctypes
+    from paper_2403_09919_amd.binding import _DraftParams
+
+    def call(Dm=64, V=100, K=1, B=1, W=4, L=5, emb=FAKE, mlp=FAKE, h=FAKE, ws=FAKE, ws_bytes=None, params=True):
+        p = _DraftParams(emb, FAKE, FAKE, FAKE, mlp, mlp, FAKE, K, Dm, V)
+        need = lib.rd_draft_workspace(B, W, L, Dm, V)
+        return lib.rd_draft(ctypes.byref(p) if params else None, h, FAKE, B, W, L, FAKE, FAKE, ws,
+                            need if ws_bytes is None else ws_bytes, None)
+    assert call(params=False) == INVALID
+    assert call(B=0) == INVALID
+    assert call(Dm=0) == INVALID
+    assert call(Dm=96) == UNSUPPORTED                        # multiple of 64
+    assert call(W=33) == UNSUPPORTED
+    assert call(B=40, W=4) == UNSUPPORTED                    # B*W <= 128
+    assert call(V=40000) == UNSUPPORTED
+    assert call(V=3, W=4) == UNSUPPORTED                     # W <= V
+    assert call(emb=None) == INVALID
+    assert call(mlp=None) == INVALID
+    assert call(h=None) == INVALID
+    assert call(emb=FAKE + 8) == INVALID
+    assert call(ws=None) == WORKSPACE
+    assert call(ws_bytes=64) == WORKSPACE
+    assert lib.rd_draft_workspace(1, 4, 5, 96, 100) == 0
 
 
 def test_binding_rejects_host_tensors():
