@@ -273,7 +273,7 @@ int rd_commit_paged(const void *k_new, const void *v_new, const int32_t *accepte
  * beam_logp : float [B,W].  workspace: rd_draft_workspace(...) bytes, 256-byte aligned, no
  * initial contents required, not shared by concurrent calls.
  * Limits: Dm a multiple of 64; W <= 32, W <= V; B*W <= 128; V <= 32768; L <= 384.
- * The call enqueues 3 + n_mlp launches per drafted position.
+ * The call enqueues 3 + n_mlp launches per drafted position (4 + n_mlp after the first).
  */
 typedef struct {
     const void *emb, *rnn_u, *rnn_w;

@@ -8,8 +8,10 @@
 //     column x 8 consecutive k), the activations (a few hundred KB, L2 resident) into the B
 //     operand, and the four partial sums meet in LDS.  Bias, SiLU, skip connection and the bf16
 //     copy that the next layer reads are fused into the epilogue;
-//   * log-softmax over the vocabulary and the W best tokens of every row;
-//   * the beam step: the best W of the (candidate, token) pairs of a sequence by cumulative log
+//   * a first pass over the logits: per chunk of 4096 and row, the pieces of the log-sum-exp and the
+//     W best tokens;
+//   * the beam step, one workgroup per sequence: log-softmax and the W best tokens of every row
+//     from the chunk results, then the best W of the (candidate, token) pairs by cumulative log
 //     probability, ties to the smaller candidate, then the smaller token.
 // The RNN update reads its two inputs in place: the parent's state through a row map and the
 // chosen token's embedding straight from the table, so no gather pass exists.
@@ -25,11 +27,10 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
-constexpr int kLinThreads = 256;       // 4 waves: K is split four ways
 constexpr int kMaxRows = 128;          // B*W
 constexpr int kMaxBeam = 32;           // W
 constexpr int kTopThreads = 1024;
-constexpr int kTopPer = 32;            // logits per thread held in registers: V <= 32768
+constexpr int kTopPer = 32;            // V <= kTopThreads * kTopPer = 32768 (eight chunks of 4096 logits)
 
 enum { EPI_HEAD = 0, EPI_RNN = 1, EPI_MLP = 2 };
 
@@ -51,10 +52,14 @@ struct LinArgs {
 
 __device__ __forceinline__ float silu(float x) { return x / (1.0f + __expf(-x)); }
 
-template <int MT, int EPI>
-__global__ __launch_bounds__(kLinThreads) void rd_linear_kernel(LinArgs a)
+// NWV waves of a workgroup split K; the host picks NWV so that the launch has enough waves to keep
+// the HBM stream busy (a layer with few output columns has few workgroups) and every wave's share
+// is a whole number of 32-wide steps inside one of the two products.
+template <int MT, int NWV, int EPI>
+__global__ __launch_bounds__(NWV * 64) void rd_linear_kernel(LinArgs a)
 {
-    __shared__ f32x4 s_part[3][MT][64];
+    static_assert((NWV - 1) * MT <= 60, "partial sums must fit in LDS");
+    __shared__ f32x4 s_part[NWV - 1][MT][64];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r16 = lane & 15, g = lane >> 4;
@@ -62,7 +67,7 @@ __global__ __launch_bounds__(kLinThreads) void rd_linear_kernel(LinArgs a)
 
     // this wave's share of the k-steps (32 wide); the host guarantees it lies within one product
     const int ks1 = a.K1 >> 5, ks = ks1 + (a.K2 >> 5);
-    const int kb = (int)((long long)ks * wave / 4), ke = (int)((long long)ks * (wave + 1) / 4);
+    const int kb = (int)((long long)ks * wave / NWV), ke = (int)((long long)ks * (wave + 1) / NWV);
     const bool second = kb >= ks1;
     const __bf16 *wbase = second ? a.w2 : a.w1;
     const int K = second ? a.K2 : a.K1;
@@ -84,7 +89,7 @@ __global__ __launch_bounds__(kLinThreads) void rd_linear_kernel(LinArgs a)
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    constexpr int U = 4;                                        // k-steps in flight
+    constexpr int U = MT <= 2 ? 8 : 4;                          // k-steps in flight
     int s = 0;
     for (; s + U <= steps; s += U) {
         bf16x8 wa[U], xb[U][MT];
@@ -108,7 +113,7 @@ __global__ __launch_bounds__(kLinThreads) void rd_linear_kernel(LinArgs a)
         }
     }
 
-    // the four K-quarters meet in LDS; wave 0 finishes
+    // the K shares meet in LDS; wave 0 finishes
     if (wave > 0) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) s_part[wave - 1][mt][lane] = acc[mt];
@@ -118,7 +123,9 @@ __global__ __launch_bounds__(kLinThreads) void rd_linear_kernel(LinArgs a)
     // accumulator layout: element i of lane (r16, g) is output column n0 + 4g + i of row mt*16 + r16
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-        f32x4 v = acc[mt] + s_part[0][mt][lane] + s_part[1][mt][lane] + s_part[2][mt][lane];
+        f32x4 v = acc[mt];
+#pragma unroll
+        for (int w = 0; w < NWV - 1; ++w) v += s_part[w][mt][lane];
         const int m = mt * 16 + r16;
         if (m >= a.M) continue;
 #pragma unroll
@@ -149,13 +156,17 @@ __global__ void rd_draft_init_kernel(const __bf16 *__restrict__ emb, const __bf1
     const int m = blockIdx.x, b = m / W;
     int tok = last_token[b];
     tok = tok < 0 ? 0 : (tok > V - 1 ? V - 1 : tok);
-    for (int i = threadIdx.x; i < Dm; i += blockDim.x) {
-        const __bf16 e = emb[(size_t)tok * Dm + i], hv = h[(size_t)b * Dm + i];
-        x_f32[(size_t)m * 2 * Dm + i] = (float)e;
-        x_bf[(size_t)m * 2 * Dm + i] = e;
-        x_f32[(size_t)m * 2 * Dm + Dm + i] = (float)hv;
-        x_bf[(size_t)m * 2 * Dm + Dm + i] = hv;
-        s_bf[(size_t)m * Dm + i] = e;
+    for (int i = threadIdx.x * 8; i < Dm; i += blockDim.x * 8) {          // Dm is a multiple of 64
+        const bf16x8 e = *reinterpret_cast<const bf16x8 *>(emb + (size_t)tok * Dm + i);
+        const bf16x8 hv = *reinterpret_cast<const bf16x8 *>(h + (size_t)b * Dm + i);
+        *reinterpret_cast<bf16x8 *>(x_bf + (size_t)m * 2 * Dm + i) = e;
+        *reinterpret_cast<bf16x8 *>(x_bf + (size_t)m * 2 * Dm + Dm + i) = hv;
+        *reinterpret_cast<bf16x8 *>(s_bf + (size_t)m * Dm + i) = e;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            x_f32[(size_t)m * 2 * Dm + i + j] = (float)e[j];
+            x_f32[(size_t)m * 2 * Dm + Dm + i + j] = (float)hv[j];
+        }
     }
     for (int j = threadIdx.x; j < L; j += blockDim.x) paths[(size_t)m * L + j] = tok;
     if (threadIdx.x == 0) cum[m] = 0.f;
@@ -163,54 +174,86 @@ __global__ void rd_draft_init_kernel(const __bf16 *__restrict__ emb, const __bf1
 
 __device__ __forceinline__ bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
 
-// One workgroup per row: log-softmax over V logits and the W best tokens (value first, then the
-// smaller index), as cumulative scores cand_score[m][r] = cum[m] + log p and tokens cand_tok[m][r].
-__global__ __launch_bounds__(kTopThreads) void rd_topw_kernel(const float *__restrict__ logits, int V, int W,
-                                                              const float *__restrict__ cum,
-                                                              float *__restrict__ cand_score, int32_t *__restrict__ cand_tok)
+// (value, index) arg max over the 64 lanes of a wave; every lane gets the result.  Lane exchanges
+// use the data-parallel primitives (quad permutes, row mirrors, the gfx950 16/32-lane swaps): the
+// selection loops call this dozens of times in a dependent chain, and a bpermute through the LDS
+// crossbar per step would dominate them.
+template <int kCtrl>
+__device__ __forceinline__ void best_step_dpp(float &bv, int &bi)
 {
-    __shared__ float s_v[kTopThreads / 64];
-    __shared__ int s_i[kTopThreads / 64];
-    __shared__ float s_bcast[2];
-    __shared__ int s_win;
-    const int m = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const float ov = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(bv), kCtrl, 0xf, 0xf, false));
+    const int oi = __builtin_amdgcn_update_dpp(0, bi, kCtrl, 0xf, 0xf, false);
+    if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+}
+__device__ __forceinline__ void wave_best(float &bv, int &bi)
+{
+    best_step_dpp<0xB1>(bv, bi);        // quad_perm [1,0,3,2]: partner lane ^ 1
+    best_step_dpp<0x4E>(bv, bi);        // quad_perm [2,3,0,1]: partner lane ^ 2
+    best_step_dpp<0x141>(bv, bi);       // row_half_mirror: the other quad of the 8
+    best_step_dpp<0x140>(bv, bi);       // row_mirror: the other half of the 16
+    {
+        const auto v = __builtin_amdgcn_permlane16_swap(__float_as_uint(bv), __float_as_uint(bv), false, false);
+        const auto i = __builtin_amdgcn_permlane16_swap((unsigned)bi, (unsigned)bi, false, false);
+        const float v0 = __uint_as_float(v[0]), v1 = __uint_as_float(v[1]);
+        const int i0 = (int)i[0], i1 = (int)i[1];
+        const bool first = better(v0, i0, v1, i1);
+        bv = first ? v0 : v1;
+        bi = first ? i0 : i1;
+    }
+    {
+        const auto v = __builtin_amdgcn_permlane32_swap(__float_as_uint(bv), __float_as_uint(bv), false, false);
+        const auto i = __builtin_amdgcn_permlane32_swap((unsigned)bi, (unsigned)bi, false, false);
+        const float v0 = __uint_as_float(v[0]), v1 = __uint_as_float(v[1]);
+        const int i0 = (int)i[0], i1 = (int)i[1];
+        const bool first = better(v0, i0, v1, i1);
+        bv = first ? v0 : v1;
+        bi = first ? i0 : i1;
+    }
+}
+
+constexpr int kChunk = 4096;            // logits per workgroup of the first top-W pass
+constexpr int kChunkThreads = 256;
+constexpr int kChunkPer = kChunk / kChunkThreads;
+constexpr int kMaxChunks = kTopThreads * kTopPer / kChunk;      // V <= 32768
+
+// First pass over the logits: workgroup (chunk c, row m) reduces 4096 logits to their maximum, the
+// sum of exp(x - maximum) and their W best (value, then smaller index).  Every wave finds the W best
+// of its own 1024 logits with lane shuffles only; wave 0 then picks the W best of the 4 x W survivors.
+__global__ __launch_bounds__(kChunkThreads) void rd_topw_chunk_kernel(const float *__restrict__ logits, int V, int W, int chunks,
+                                                                      float *__restrict__ part_max, float *__restrict__ part_sum,
+                                                                      float *__restrict__ part_cv, int32_t *__restrict__ part_ci)
+{
+    constexpr int kWaves = kChunkThreads / 64;
+    __shared__ float s_v[kWaves];
+    __shared__ float s_mx;
+    __shared__ float s_cv[kWaves * kMaxBeam];
+    __shared__ int s_ci[kWaves * kMaxBeam];
+    const int c = blockIdx.x, m = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float *z = logits + (size_t)m * V;
-    float x[kTopPer];
+    const int v0 = c * kChunk;
+    float x[kChunkPer];
     float mx = -INFINITY;
 #pragma unroll
-    for (int j = 0; j < kTopPer; ++j) {
-        const int v = j * kTopThreads + tid;
+    for (int j = 0; j < kChunkPer; ++j) {
+        const int v = v0 + j * kChunkThreads + tid;
         x[j] = v < V ? z[v] : -INFINITY;
         mx = fmaxf(mx, x[j]);
     }
     for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
     if (lane == 0) s_v[wave] = mx;
     __syncthreads();
-    if (tid == 0) {
-        float t = s_v[0];
-        for (int w = 1; w < kTopThreads / 64; ++w) t = fmaxf(t, s_v[w]);
-        s_bcast[0] = t;
-    }
+    if (tid == 0) s_mx = fmaxf(fmaxf(s_v[0], s_v[1]), fmaxf(s_v[2], s_v[3]));
     __syncthreads();
-    mx = s_bcast[0];
+    mx = s_mx;
     float sum = 0.f;
 #pragma unroll
-    for (int j = 0; j < kTopPer; ++j) sum += (j * kTopThreads + tid < V) ? __expf(x[j] - mx) : 0.f;
+    for (int j = 0; j < kChunkPer; ++j) sum += (v0 + j * kChunkThreads + tid < V) ? __expf(x[j] - mx) : 0.f;
     for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off, 64);
     __syncthreads();
     if (lane == 0) s_v[wave] = sum;
-    __syncthreads();
-    if (tid == 0) {
-        float t = 0.f;
-        for (int w = 0; w < kTopThreads / 64; ++w) t += s_v[w];
-        s_bcast[1] = mx + __logf(t);
-    }
-    __syncthreads();
-    const float lse = s_bcast[1];
-    const float base = cum[m];
 
     uint32_t gone = 0;                          // bit j: x[j] already taken
-    float lv = -INFINITY;                       // this thread's best remaining (value, index)
+    float lv = -INFINITY;                       // this lane's best remaining (value, index)
     int li = 0x7fffffff;
     bool stale = true;
     for (int r = 0; r < W; ++r) {
@@ -218,105 +261,168 @@ __global__ __launch_bounds__(kTopThreads) void rd_topw_kernel(const float *__res
             lv = -INFINITY;
             li = 0x7fffffff;
 #pragma unroll
-            for (int j = 0; j < kTopPer; ++j) {
-                const int v = j * kTopThreads + tid;
+            for (int j = 0; j < kChunkPer; ++j) {
+                const int v = v0 + j * kChunkThreads + tid;
                 if (v < V && !((gone >> j) & 1u) && better(x[j], v, lv, li)) { lv = x[j]; li = v; }
             }
             stale = false;
         }
         float bv = lv;
         int bi = li;
-        for (int off = 32; off > 0; off >>= 1) {
-            const float ov = __shfl_xor(bv, off, 64);
-            const int oi = __shfl_xor(bi, off, 64);
-            if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
-        }
-        __syncthreads();
-        if (lane == 0) { s_v[wave] = bv; s_i[wave] = bi; }
-        __syncthreads();
-        if (tid == 0) {
-            for (int w = 1; w < kTopThreads / 64; ++w)
-                if (better(s_v[w], s_i[w], bv, bi)) { bv = s_v[w]; bi = s_i[w]; }
-            s_win = bi;
-            cand_score[(size_t)m * W + r] = base + (bv - lse);
-            cand_tok[(size_t)m * W + r] = bi;
-        }
-        __syncthreads();
-        const int win = s_win;
-        if (win == li) {                         // mine: retire it
-            gone |= 1u << (win / kTopThreads);
+        wave_best(bv, bi);
+        if (lane == 0) { s_cv[wave * W + r] = bv; s_ci[wave * W + r] = bi; }
+        if (bi == li && li != 0x7fffffff) {      // mine: retire it
+            gone |= 1u << ((bi - v0) / kChunkThreads);
             stale = true;
         }
     }
-}
-
-// One workgroup per sequence: the best W of live*W candidates (live = 1 at the first position).
-// Candidate c = w*W + r (row w's r-th best token); ties in score go to the smaller c, which is
-// the smaller candidate first and, within a row, the smaller token (rows are sorted that way).
-__global__ __launch_bounds__(256) void rd_beam_select_kernel(
-    const float *__restrict__ cand_score, const int32_t *__restrict__ cand_tok, int W, int L, int t, int live,
-    const int32_t *__restrict__ paths_cur, int32_t *__restrict__ paths_next, float *__restrict__ cum_next,
-    int32_t *__restrict__ parent_row, int32_t *__restrict__ tok_row,
-    int32_t *__restrict__ beams_out, float *__restrict__ logp_out /* both NULL except at the last position */)
-{
-    __shared__ float s_v[4];
-    __shared__ int s_i[4];
-    __shared__ int s_win;
-    __shared__ float s_winv;
-    constexpr int kPer = (kMaxBeam * kMaxBeam + 255) / 256;
-    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int n_cand = live * W;
-    float x[kPer];
+    __syncthreads();
+    if (wave != 0) return;
+    const size_t slot = (size_t)m * chunks + c;
+    if (lane == 0) {
+        part_max[slot] = mx;
+        part_sum[slot] = s_v[0] + s_v[1] + s_v[2] + s_v[3];
+    }
+    constexpr int kPer = kWaves * kMaxBeam / 64;
+    float cv[kPer];
+    int ci[kPer];
+    const int n_surv = kWaves * W;
 #pragma unroll
     for (int j = 0; j < kPer; ++j) {
-        const int c = j * 256 + tid;
-        x[j] = c < n_cand ? cand_score[(size_t)b * W * W + c] : -INFINITY;     // rows of sequence b are contiguous
+        const int q = j * 64 + lane;
+        cv[j] = q < n_surv ? s_cv[q] : -INFINITY;
+        ci[j] = q < n_surv ? s_ci[q] : 0x7fffffff;
     }
-    uint32_t gone = 0;
     for (int r = 0; r < W; ++r) {
         float bv = -INFINITY;
         int bi = 0x7fffffff;
 #pragma unroll
+        for (int j = 0; j < kPer; ++j)
+            if (better(cv[j], ci[j], bv, bi)) { bv = cv[j]; bi = ci[j]; }
+        wave_best(bv, bi);
+        if (lane == 0) {
+            part_cv[slot * W + r] = bv;
+            part_ci[slot * W + r] = bi;
+        }
+#pragma unroll
+        for (int j = 0; j < kPer; ++j)
+            if (ci[j] == bi) { cv[j] = -INFINITY; ci[j] = 0x7fffffff; }   // token indices are unique
+    }
+}
+
+// Second pass and beam step, one workgroup per sequence.  A wave per live candidate row: the row's
+// log-sum-exp from the chunk partials and its W best tokens from the chunks' survivors, as cumulative
+// scores in LDS.  Then the best W of the live*W (candidate, token) pairs: pair c = w*W + r (row w's
+// r-th best token); ties in score go to the smaller c, i.e. the smaller candidate first and, within a
+// row, the smaller token (rows are sorted that way).  All rounds touch LDS only; paths, scores and
+// the row maps of the next RNN update are written at the end.
+__global__ __launch_bounds__(256) void rd_beam_step_kernel(
+    const float *__restrict__ part_max, const float *__restrict__ part_sum, const float *__restrict__ part_cv,
+    const int32_t *__restrict__ part_ci, int chunks, const float *__restrict__ cum_cur,
+    int W, int L, int t, int live,
+    const int32_t *__restrict__ paths_cur, int32_t *__restrict__ paths_next, float *__restrict__ cum_next,
+    int32_t *__restrict__ parent_row, int32_t *__restrict__ tok_row,
+    int32_t *__restrict__ beams_out, float *__restrict__ logp_out /* both NULL except at the last position */)
+{
+    __shared__ float s_score[kMaxBeam * kMaxBeam];
+    __shared__ int s_ctok[kMaxBeam * kMaxBeam];
+    __shared__ float s_v[4];
+    __shared__ int s_i[4];
+    __shared__ int s_win[kMaxBeam], s_tok[kMaxBeam];
+    __shared__ float s_winv[kMaxBeam];
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    for (int w = wave; w < live; w += 4) {
+        const size_t row = (size_t)b * W + w;
+        // log-sum-exp of the row: sum_c part_sum[c] * exp(part_max[c] - max)
+        float pm = lane < chunks ? part_max[row * chunks + lane] : -INFINITY;
+        float gm = pm;
+        for (int off = 32; off > 0; off >>= 1) gm = fmaxf(gm, __shfl_xor(gm, off, 64));
+        float ps = lane < chunks ? part_sum[row * chunks + lane] * __expf(pm - gm) : 0.f;
+        for (int off = 32; off > 0; off >>= 1) ps += __shfl_xor(ps, off, 64);
+        const float lse = gm + __logf(ps);
+        const float base = cum_cur[row];
+        constexpr int kPer = kMaxChunks * kMaxBeam / 64;
+        float cv[kPer];
+        int ci[kPer];
+        const int n_surv = chunks * W;
+#pragma unroll
         for (int j = 0; j < kPer; ++j) {
+            const int q = j * 64 + lane;
+            cv[j] = q < n_surv ? part_cv[row * n_surv + q] : -INFINITY;
+            ci[j] = q < n_surv ? part_ci[row * n_surv + q] : 0x7fffffff;
+        }
+        for (int r = 0; r < W; ++r) {
+            float bv = -INFINITY;
+            int bi = 0x7fffffff;
+#pragma unroll
+            for (int j = 0; j < kPer; ++j)
+                if (better(cv[j], ci[j], bv, bi)) { bv = cv[j]; bi = ci[j]; }
+            wave_best(bv, bi);
+            if (lane == 0) {
+                s_score[w * W + r] = base + (bv - lse);
+                s_ctok[w * W + r] = bi;
+            }
+#pragma unroll
+            for (int j = 0; j < kPer; ++j)
+                if (ci[j] == bi) { cv[j] = -INFINITY; ci[j] = 0x7fffffff; }
+        }
+    }
+    __syncthreads();
+
+    constexpr int kPerSel = (kMaxBeam * kMaxBeam + 255) / 256;
+    const int n_cand = live * W;
+    float x[kPerSel];
+#pragma unroll
+    for (int j = 0; j < kPerSel; ++j) {
+        const int c = j * 256 + tid;
+        x[j] = c < n_cand ? s_score[c] : -INFINITY;
+    }
+    for (int r = 0; r < W; ++r) {
+        float bv = -INFINITY;
+        int bi = 0x7fffffff;
+#pragma unroll
+        for (int j = 0; j < kPerSel; ++j) {
             const int c = j * 256 + tid;
-            if (c < n_cand && !((gone >> j) & 1u) && better(x[j], c, bv, bi)) { bv = x[j]; bi = c; }
+            if (c < n_cand && better(x[j], c, bv, bi)) { bv = x[j]; bi = c; }
         }
-        for (int off = 32; off > 0; off >>= 1) {
-            const float ov = __shfl_xor(bv, off, 64);
-            const int oi = __shfl_xor(bi, off, 64);
-            if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
-        }
-        __syncthreads();
+        wave_best(bv, bi);
         if (lane == 0) { s_v[wave] = bv; s_i[wave] = bi; }
         __syncthreads();
-        if (tid == 0) {
-            for (int w = 1; w < 4; ++w)
-                if (better(s_v[w], s_i[w], bv, bi)) { bv = s_v[w]; bi = s_i[w]; }
-            s_win = bi;
-            s_winv = bv;
-        }
+        bv = s_v[0];
+        bi = s_i[0];
+#pragma unroll
+        for (int w = 1; w < 4; ++w)
+            if (better(s_v[w], s_i[w], bv, bi)) { bv = s_v[w]; bi = s_i[w]; }
+#pragma unroll
+        for (int j = 0; j < kPerSel; ++j)
+            if (j * 256 + tid == bi) {                                   // mine: record and retire it
+                s_win[r] = bi;
+                s_winv[r] = x[j];
+                s_tok[r] = s_ctok[bi];
+                x[j] = -INFINITY;
+            }
         __syncthreads();
-        const int win = s_win;
-        if ((win & 255) == tid) gone |= 1u << (win >> 8);
-        const int pw = win / W;                                   // parent candidate
-        const int tok = cand_tok[(size_t)b * W * W + win];
-        const size_t dst = ((size_t)b * W + r) * L, src = ((size_t)b * W + pw) * L;
-        for (int j = tid; j < L; j += 256) {
-            const int v = j < t ? paths_cur[src + j] : (j == t ? tok : paths_cur[src]);
-            paths_next[dst + j] = v;
-            if (beams_out) beams_out[dst + j] = v;
-        }
-        if (tid == 0) {
-            cum_next[(size_t)b * W + r] = s_winv;
-            parent_row[(size_t)b * W + r] = b * W + pw;
-            tok_row[(size_t)b * W + r] = tok;
-            if (logp_out) logp_out[(size_t)b * W + r] = s_winv;
-        }
+    }
+    // candidate r: parent pw = s_win[r] / W, new token s_tok[r]
+    for (int i = tid; i < W * L; i += 256) {
+        const int r = i / L, j = i - r * L;
+        const int pw = s_win[r] / W;
+        const size_t src = ((size_t)b * W + pw) * L;
+        const int v = j < t ? paths_cur[src + j] : (j == t ? s_tok[r] : paths_cur[src]);
+        paths_next[((size_t)b * W + r) * L + j] = v;
+        if (beams_out) beams_out[((size_t)b * W + r) * L + j] = v;
+    }
+    if (tid < W) {
+        cum_next[(size_t)b * W + tid] = s_winv[tid];
+        parent_row[(size_t)b * W + tid] = b * W + s_win[tid] / W;
+        tok_row[(size_t)b * W + tid] = s_tok[tid];
+        if (logp_out) logp_out[(size_t)b * W + tid] = s_winv[tid];
     }
 }
 
 struct Plan {
-    size_t x_f32[3], x_bf[3], s_bf[2], logits, cand_score, cand_tok, paths[2], cum[2], parent, tok, total;
+    size_t x_f32[3], x_bf[3], s_bf[2], logits, part_max, part_sum, part_cv, part_ci, paths[2], cum[2], parent, tok, total;
 };
 
 Plan draft_plan(int B, int W, int L, int Dm, int V)
@@ -328,8 +434,10 @@ Plan draft_plan(int B, int W, int L, int Dm, int V)
     for (int i = 0; i < 3; ++i) { p.x_f32[i] = take(M * G * 4); p.x_bf[i] = take(M * G * 2); }
     for (int i = 0; i < 2; ++i) p.s_bf[i] = take(M * Dm * 2);
     p.logits = take(M * (size_t)V * 4);
-    p.cand_score = take(M * W * 4);
-    p.cand_tok = take(M * W * 4);
+    p.part_max = take(M * kMaxChunks * 4);
+    p.part_sum = take(M * kMaxChunks * 4);
+    p.part_cv = take(M * kMaxChunks * W * 4);
+    p.part_ci = take(M * kMaxChunks * W * 4);
     for (int i = 0; i < 2; ++i) { p.paths[i] = take(M * L * 4); p.cum[i] = take(M * 4); }
     p.parent = take(M * 4);
     p.tok = take(M * 4);
@@ -347,16 +455,40 @@ int draft_check(const rd_draft_params *p, int B, int W, int L)
     return RD_OK;
 }
 
+template <int MT, int NWV, int EPI>
+void launch_linear_one(const LinArgs &a, hipStream_t stream)
+{
+    hipLaunchKernelGGL((rd_linear_kernel<MT, NWV, EPI>), dim3((a.N + 15) / 16), dim3(NWV * 64), 0, stream, a);
+}
+
+// waves per workgroup: as many as give the launch about 16 waves per compute unit, as long as
+// every wave gets whole k-steps inside one product and the partial sums fit in LDS
+template <int MT, int EPI>
+int launch_linear_mt(const LinArgs &a, hipStream_t stream)
+{
+    const int ks1 = a.K1 / 32, ks2 = a.K2 / 32, wgs = (a.N + 15) / 16;
+    auto ok = [&](int nwv) {
+        if ((nwv - 1) * MT > 60) return false;
+        if (ks2 == 0) return ks1 % nwv == 0;
+        return ks1 == ks2 && ks1 % (nwv / 2) == 0;
+    };
+    int nwv = 4;
+    if (wgs * 4 < 4096 && ok(8)) nwv = 8;
+    if (wgs * 8 < 4096 && ok(16)) nwv = 16;
+    if (nwv == 16) { if constexpr (MT <= 4) launch_linear_one<MT, 16, EPI>(a, stream); else launch_linear_one<MT, 8, EPI>(a, stream); }
+    else if (nwv == 8) launch_linear_one<MT, 8, EPI>(a, stream);
+    else launch_linear_one<MT, 4, EPI>(a, stream);
+    return rd_check_launch();
+}
+
 template <int EPI>
 int launch_linear(const LinArgs &a, hipStream_t stream)
 {
-    const dim3 grid((a.N + 15) / 16), block(kLinThreads);
     const int mt = (a.M + 15) / 16;
-    if (mt <= 1) hipLaunchKernelGGL((rd_linear_kernel<1, EPI>), grid, block, 0, stream, a);
-    else if (mt <= 2) hipLaunchKernelGGL((rd_linear_kernel<2, EPI>), grid, block, 0, stream, a);
-    else if (mt <= 4) hipLaunchKernelGGL((rd_linear_kernel<4, EPI>), grid, block, 0, stream, a);
-    else hipLaunchKernelGGL((rd_linear_kernel<8, EPI>), grid, block, 0, stream, a);
-    return rd_check_launch();
+    if (mt <= 1) return launch_linear_mt<1, EPI>(a, stream);
+    if (mt <= 2) return launch_linear_mt<2, EPI>(a, stream);
+    if (mt <= 4) return launch_linear_mt<4, EPI>(a, stream);
+    return launch_linear_mt<8, EPI>(a, stream);
 }
 
 }  // namespace
@@ -391,8 +523,10 @@ extern "C" int rd_draft(const rd_draft_params *p, const void *h, const int32_t *
     for (int i = 0; i < 3; ++i) { x_f32[i] = reinterpret_cast<float *>(ws + plan.x_f32[i]); x_bf[i] = reinterpret_cast<__bf16 *>(ws + plan.x_bf[i]); }
     for (int i = 0; i < 2; ++i) s_bf[i] = reinterpret_cast<__bf16 *>(ws + plan.s_bf[i]);
     float *logits = reinterpret_cast<float *>(ws + plan.logits);
-    float *cand_score = reinterpret_cast<float *>(ws + plan.cand_score);
-    int32_t *cand_tok = reinterpret_cast<int32_t *>(ws + plan.cand_tok);
+    float *part_max = reinterpret_cast<float *>(ws + plan.part_max), *part_sum = reinterpret_cast<float *>(ws + plan.part_sum);
+    float *part_cv = reinterpret_cast<float *>(ws + plan.part_cv);
+    int32_t *part_ci = reinterpret_cast<int32_t *>(ws + plan.part_ci);
+    const int chunks = (V + kChunk - 1) / kChunk;
     int32_t *paths[2] = {reinterpret_cast<int32_t *>(ws + plan.paths[0]), reinterpret_cast<int32_t *>(ws + plan.paths[1])};
     float *cum[2] = {reinterpret_cast<float *>(ws + plan.cum[0]), reinterpret_cast<float *>(ws + plan.cum[1])};
     int32_t *parent = reinterpret_cast<int32_t *>(ws + plan.parent), *tok = reinterpret_cast<int32_t *>(ws + plan.tok);
@@ -435,11 +569,13 @@ extern "C" int rd_draft(const rd_draft_params *p, const void *h, const int32_t *
             a.M = M; a.N = V; a.y_f32 = logits; a.ldy = V;
             if (launch_linear<EPI_HEAD>(a, s) != RD_OK) return RD_ERR_HIP;
         }
-        hipLaunchKernelGGL(rd_topw_kernel, dim3(M), dim3(kTopThreads), 0, s, logits, V, W, cum[cur], cand_score, cand_tok);
+        hipLaunchKernelGGL(rd_topw_chunk_kernel, dim3(chunks, M), dim3(kChunkThreads), 0, s, logits, V, W, chunks,
+                           part_max, part_sum, part_cv, part_ci);
         if (rd_check_launch() != RD_OK) return RD_ERR_HIP;
         const bool last = t == T;
-        hipLaunchKernelGGL(rd_beam_select_kernel, dim3(B), dim3(256), 0, s, cand_score, cand_tok, W, L, t, t == 1 ? 1 : W,
-                           paths[cur], paths[nxt], cum[nxt], parent, tok, last ? beams : nullptr, last ? beam_logp : nullptr);
+        hipLaunchKernelGGL(rd_beam_step_kernel, dim3(B), dim3(256), 0, s, part_max, part_sum, part_cv, part_ci, chunks,
+                           cum[cur], W, L, t, t == 1 ? 1 : W, paths[cur], paths[nxt], cum[nxt], parent, tok,
+                           last ? beams : nullptr, last ? beam_logp : nullptr);
         if (rd_check_launch() != RD_OK) return RD_ERR_HIP;
     }
     return RD_OK;
