@@ -44,6 +44,7 @@ def parse():
     ap.add_argument("--copies", type=int, default=0, help="rotating input copies (0 = enough for > 512 MiB of K/V)")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of graph replays")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-draft", action="store_true", help="skip the separate rd_draft timing")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time budget of the oracle baseline")
     ap.add_argument("--pmc-calib", action="store_true",
                     help="also run plain device copies of 64 MiB (reference dispatches for scaling rocprofv3 "
@@ -248,6 +249,8 @@ def main():
     kernels_us = {"rd_dedup": time_kernel(k_dedup), "rd_tree_attn": round(attn_us, 3),
                   "rd_accept": time_kernel(k_accept), "rd_commit": time_kernel(k_commit)}
 
+    draft = None if args.no_draft else time_draft(rd, cfg, stream, max(4, min(40, args.steps // 10)), torch)
+
     result = {
         "metric": "verify_steps_per_sec",
         "value": round(steps_per_s, 2),
@@ -273,6 +276,7 @@ def main():
         "packed_tokens_per_step": round(packed_mean, 2),
         "wall_ms_timed_region": round(wall_ms, 3),
         "kernels_us": kernels_us,
+        "rd_draft": draft,
         "roofline": {
             "kernel": "rd_tree_attn",
             "bound": "hbm",
@@ -289,6 +293,46 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, synth, args.cpu_seconds)
     print(json.dumps(result), flush=True)
+
+
+def time_draft(rd, cfg, stream, n, torch):
+    """rd_draft (Sec. 3.1, 3.2), the stage that feeds the verification step, timed on its own at the
+    drafter dimensions that go with the workload: hidden size H*D, the workload's vocabulary, two MLP
+    layers, its batch, beam width and length.  Reported beside the headline figures, not part of them.
+    The weights (seeded normals, bf16) rotate over two copies so that no launch finds them in cache;
+    the roofline figure is the weight bytes one call streams over its duration."""
+    Dm, V, K, B, W, L = cfg.H * cfg.D, cfg.V, 2, cfg.B, cfg.W, cfg.L
+    if B * W > 128 or W > 32:
+        return None                                 # beyond rd_draft's present row limit
+    G = 2 * Dm
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(cfg.seed + 1)
+
+    def rn(*shape, s=1.0):
+        return (torch.randn(*shape, device="cuda", generator=gen) * s).to(torch.bfloat16)
+
+    sets = [dict(emb=rn(V, Dm), rnn_u=rn(Dm, Dm, s=Dm ** -0.5), rnn_w=rn(Dm, Dm, s=Dm ** -0.5),
+                 rnn_b=torch.randn(Dm, device="cuda", generator=gen) * 0.1,
+                 mlp_w=rn(K, G, G, s=G ** -0.5), mlp_b=torch.randn(K, G, device="cuda", generator=gen) * 0.1,
+                 head_w=rn(V, G, s=4 * G ** -0.5)) for _ in range(2)]
+    h = rn(B, Dm)
+    last = torch.randint(0, V, (B,), device="cuda", dtype=torch.int32, generator=gen)
+    ws = torch.empty(rd.rd_draft_workspace(B, W, L, Dm, V), dtype=torch.uint8, device="cuda")
+    with torch.cuda.stream(stream):
+        out = rd.rd_draft(sets[0], h, last, W, L, workspace=ws)
+        rd.rd_draft(sets[1], h, last, W, L, out=out, workspace=ws)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for i in range(n):
+            rd.rd_draft(sets[i % 2], h, last, W, L, out=out, workspace=ws)
+        e1.record(stream)
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / n
+    wbytes = (L - 1) * (K * G * G + V * G) * 2 + max(L - 2, 0) * 2 * Dm * Dm * 2
+    gbs = wbytes / us / 1e3
+    return {"us_per_call": round(us, 1), "config": "Dm=%d V=%d K=%d B=%d W=%d L=%d" % (Dm, V, K, B, W, L),
+            "weight_bytes_streamed": wbytes, "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS,
+            "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4)}
 
 
 def cpu_baseline(cfg, synth, budget_s):

@@ -183,9 +183,9 @@ int rd_accept(const float *logits, const int32_t *beams, const int32_t *unpack_i
               void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * rd_commit — append the accepted tokens to the context (Sec. 3.4: "append accepted tokens to
- * the end of previously generated tokens"; the LLM's hidden state at the last accepted token
- * and next_token start the next draft).  Runs after rd_accept, on its outputs.
+ * rd_commit — the accepted tokens join the sequence generated so far (last step of the decoding
+ * loop of Sec. 3.4; the LLM's hidden state at the last accepted token and next_token start the
+ * next draft).  Runs after rd_accept, on its outputs.
  *
  * For every sequence b, with bl = best_len[b] clamped to [0, L], c = ctx_len[b] clamped to
  * [0, Cmax] and n = min(bl, Cmax - c) (what still fits in the cache):

@@ -502,8 +502,8 @@ void orc_rope(void *x, const int32_t *position_ids /*[B,N]*/, const int32_t *n_p
  * The draft model and its beam search (Sec. 3.1, 3.2).  Per sequence:
  *   s_1 = e(last token)                    the embedding of the LLM's latest token
  *   g_t = [s_t, h]                         h = the LLM's last hidden state (Sec. 3.1)
- *   x = g_t;  x <- x + f(A_k x + c_k)      "a few layers of MLPs with skip connections"
- *   z = O x;  log p = log_softmax(z)       "a standard softmax layer"
+ *   x = g_t;  x <- x + f(A_k x + c_k)      n_mlp residual MLP layers (Sec. 3.1)
+ *   z = O x;  log p = log_softmax(z)       softmax output layer over the vocabulary
  *   s_{t+1} = f(U s_t + W e(token_t) + b)  the RNN update with the token chosen at step t
  * The paper names no activation f; SiLU is this build's reading (it is what the public
  * ReDrafter release uses).  Beam search of width W (Sec. 3.2) over T = L - 1 drafted

@@ -102,3 +102,41 @@ def test_draft_feeds_the_verification_step(rd):
     ref = oracle.dedup(host(got["beams"]))
     assert np.array_equal(host(d["n_packed"]), ref["n_packed"])
     assert ((ref["n_packed"] >= L) & (ref["n_packed"] <= W * (L - 1) + 1)).all()
+
+
+TOL_7B = 3e-2     # see test_draft_vicuna7b_dimensions
+
+
+def test_draft_vicuna7b_dimensions(rd):
+    """Drafter dimensions of a 7B LLM (hidden 4096, vocabulary 32000, two MLP layers), the shape the
+    benchmark times.  The oracle scores the GPU's candidates by teacher forcing (a few seconds) and
+    runs its own beam search for the comparison.
+
+    Tolerance: every linear layer's input is rounded to bf16, so an fp32-vs-fp64 difference of 1e-6
+    in a hidden value that sits next to a rounding boundary moves that input by a whole bf16 ulp
+    (2^-7 for values in [1, 2)).  With 8192 inputs a layer sees a few tens of such flips; each moves a
+    logit by ulp * |head weight| ~ 3e-4 here, so a logit carries ~1e-3 per layer, and a score sums three
+    layers over four steps.  A plain numpy fp32 evaluation of the same model differs from the fp64
+    oracle by up to 1.0e-2 on these very paths; the bound is three times that."""
+    announce("draft Dm=4096 V=32000 K=2 B=1 W=8 L=5")
+    Dm, V, K, B, W, L = 4096, 32000, 2, 1, 8, 5
+    p = make_params(V, Dm, K, seed=4096, scale=4.0)
+    rng = np.random.default_rng(11)
+    h = synth.f32_to_bf16_bits(rng.standard_normal((B, Dm)).astype(np.float32))
+    last = rng.integers(0, V, B).astype(np.int32)
+    got = rd.rd_draft(dev_params(p), dev(h), dev(last), W, L)
+    torch.cuda.synchronize()
+    gb, gl = host(got["beams"]), host(got["beam_logp"])
+    assert (gb[:, :, 0] == last[:, None]).all() and (gb >= 0).all() and (gb < V).all()
+    assert (np.diff(gl, axis=1) <= 1e-6).all()
+    assert len({tuple(x) for x in gb[0].tolist()}) == W
+    tf = oracle.draft_path_logp(p, h, gb)
+    assert np.abs(tf - gl).max() <= TOL_7B, np.abs(tf - gl).max()
+    ref = oracle.draft(p, h, last, W, L)
+    rl = ref["beam_logp"][0].astype(np.float64)
+    assert (tf[0] >= rl - TOL_7B).all()
+    # candidates the oracle separates from all others by more than the tolerance must be present
+    got_set = {tuple(x) for x in gb[0].tolist()}
+    for w in range(W - 1):
+        if np.abs(np.delete(rl, w) - rl[w]).min() > 2 * TOL_7B and rl[w] - rl[W - 1] > 2 * TOL_7B:
+            assert tuple(ref["beams"][0, w].tolist()) in got_set, w

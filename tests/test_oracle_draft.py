@@ -14,16 +14,21 @@ from paper_2403_09919_amd import synth
 
 def make_params(V, Dm, K, seed, scale=1.0):
     rng = np.random.default_rng(seed)
-    bf = lambda x: synth.f32_to_bf16_bits(x.astype(np.float32))
     G = 2 * Dm
+
+    def bf(shape, s):
+        x = rng.standard_normal(shape, dtype=np.float32)
+        x *= np.float32(s)
+        return synth.f32_to_bf16_bits(x)
+
     return dict(
-        emb=bf(rng.standard_normal((V, Dm))),
-        rnn_u=bf(rng.standard_normal((Dm, Dm)) / np.sqrt(Dm)),
-        rnn_w=bf(rng.standard_normal((Dm, Dm)) / np.sqrt(Dm)),
+        emb=bf((V, Dm), 1.0),
+        rnn_u=bf((Dm, Dm), Dm ** -0.5),
+        rnn_w=bf((Dm, Dm), Dm ** -0.5),
         rnn_b=(0.1 * rng.standard_normal(Dm)).astype(np.float32),
-        mlp_w=bf(rng.standard_normal((K, G, G)) / np.sqrt(G)),
+        mlp_w=bf((K, G, G), G ** -0.5),
         mlp_b=(0.1 * rng.standard_normal((K, G))).astype(np.float32),
-        head_w=bf(scale * rng.standard_normal((V, G)) / np.sqrt(G)),
+        head_w=bf((V, G), scale * G ** -0.5),
     )
 
 
