@@ -42,6 +42,7 @@ struct LinArgs {
     int ldx1, ldx2, K1, K2;            // K2 = 0: single product
     const float *bias;                 // [N] or NULL
     int M, N;
+    int mstride;                       // logical row m of X (without a map), Y and res is physical row m*mstride
     // epilogue
     float *y_f32;                      // HEAD: logits [M][ldy];  RNN/MLP: activations fp32 [M][ldy]
     __bf16 *y_bf;                      // RNN/MLP: the same rounded to bf16 [M][ldy]
@@ -52,18 +53,49 @@ struct LinArgs {
 
 __device__ __forceinline__ float silu(float x) { return x / (1.0f + __expf(-x)); }
 
-// NWV waves of a workgroup split K; the host picks NWV so that the launch has enough waves to keep
-// the HBM stream busy (a layer with few output columns has few workgroups) and every wave's share
-// is a whole number of 32-wide steps inside one of the two products.
-template <int MT, int NWV, int EPI>
+// One output tile (16 rows x 16 columns) leaves the kernel: bias, activation, skip connection and the
+// bf16 copy that the next layer reads.  Accumulator layout: element i of lane (r16, g) is output
+// column n_tile + 4g + i of logical row m_tile + r16.
+template <int EPI>
+__device__ __forceinline__ void linear_epilogue(const LinArgs &a, f32x4 v, int m_tile, int n_tile, int r16, int g)
+{
+    const int m = m_tile + r16;
+    if (m >= a.M) return;
+    const size_t prow = (size_t)m * a.mstride;                  // physical row of the activation buffers
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int n = n_tile + 4 * g + i;
+        if (n >= a.N) continue;
+        float y = v[i] + (a.bias ? a.bias[n] : 0.f);
+        const size_t o = prow * a.ldy + n;
+        if (EPI == EPI_HEAD) {
+            a.y_f32[o] = y;
+        } else {
+            y = silu(y);
+            if (EPI == EPI_MLP) y += a.res[o];
+            a.y_f32[o] = y;
+            a.y_bf[o] = (__bf16)y;
+            if (EPI == EPI_RNN) a.s_bf[prow * a.N + n] = (__bf16)y;
+        }
+    }
+}
+
+// A workgroup owns NT*16 output columns for all M = MT*16 rows; its NWV waves split K.  The host
+// picks NT so that the activations, which every workgroup re-reads through the caches, do not
+// outweigh the weights it streams (their ratio is MT : NT) while the launch still covers the chip,
+// and NWV so that the launch has enough waves in flight to keep the HBM stream busy; every wave's
+// share of K is a whole number of 32-wide steps inside one of the two products.
+template <int MT, int NT, int NWV, int EPI>
 __global__ __launch_bounds__(NWV * 64) void rd_linear_kernel(LinArgs a)
 {
-    static_assert((NWV - 1) * MT <= 60, "partial sums must fit in LDS");
-    __shared__ f32x4 s_part[NWV - 1][MT][64];
+    constexpr int kTiles = MT * NT;
+    constexpr int kGroup = kTiles < 64 / NWV ? kTiles : 64 / NWV;     // tiles reduced per pass: <= 64 KB of LDS
+    static_assert(kTiles % kGroup == 0, "tile groups must divide the tiles");
+    __shared__ f32x4 s_part[NWV][kGroup][64];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r16 = lane & 15, g = lane >> 4;
-    const int n0 = blockIdx.x * 16;
+    const int n0 = blockIdx.x * (16 * NT);
 
     // this wave's share of the k-steps (32 wide); the host guarantees it lies within one product
     const int ks1 = a.K1 >> 5, ks = ks1 + (a.K2 >> 5);
@@ -76,73 +108,71 @@ __global__ __launch_bounds__(NWV * 64) void rd_linear_kernel(LinArgs a)
     const int32_t *map = second ? a.map2 : a.map1;
     const int ldx = second ? a.ldx2 : a.ldx1;
 
-    const int nrow = min(n0 + r16, a.N - 1);                    // rows past N read the last row; never stored
-    const __bf16 *wp = wbase + (size_t)nrow * K + k_first + 8 * g;
+    const __bf16 *wp[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int nrow = min(n0 + nt * 16 + r16, a.N - 1);      // rows past N read the last row; never stored
+        wp[nt] = wbase + (size_t)nrow * K + k_first + 8 * g;
+    }
     const __bf16 *xp[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int m = min(mt * 16 + r16, a.M - 1);
-        const int row = map ? map[m] : m;
-        xp[mt] = xbase + (size_t)row * ldx + k_first + 8 * g;
+        const size_t row = map ? (size_t)map[m] : (size_t)m * a.mstride;
+        xp[mt] = xbase + row * ldx + k_first + 8 * g;
     }
-    f32x4 acc[MT];
+    f32x4 acc[MT][NT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    constexpr int U = MT <= 2 ? 8 : 4;                          // k-steps in flight
+    constexpr int U = MT + NT <= 3 ? 8 : (MT + NT <= 9 ? 4 : 2);   // k-steps in flight
     int s = 0;
     for (; s + U <= steps; s += U) {
-        bf16x8 wa[U], xb[U][MT];
+        bf16x8 wa[U][NT], xb[U][MT];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            wa[u] = *reinterpret_cast<const bf16x8 *>(wp + (s + u) * 32);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) wa[u][nt] = *reinterpret_cast<const bf16x8 *>(wp[nt] + (s + u) * 32);
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) xb[u][mt] = *reinterpret_cast<const bf16x8 *>(xp[mt] + (s + u) * 32);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[u], xb[u][mt], acc[mt], 0, 0, 0);
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[u][nt], xb[u][mt], acc[mt][nt], 0, 0, 0);
     }
     for (; s < steps; ++s) {
-        const bf16x8 wa = *reinterpret_cast<const bf16x8 *>(wp + s * 32);
+        bf16x8 wa[NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) wa[nt] = *reinterpret_cast<const bf16x8 *>(wp[nt] + s * 32);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
             const bf16x8 xb = *reinterpret_cast<const bf16x8 *>(xp[mt] + s * 32);
-            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, xb, acc[mt], 0, 0, 0);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[nt], xb, acc[mt][nt], 0, 0, 0);
         }
     }
 
-    // the K shares meet in LDS; wave 0 finishes
-    if (wave > 0) {
+    // the K shares meet in LDS, a group of tiles at a time; tile j of a group is summed (in wave
+    // order, so the result does not depend on timing) and finished by wave j mod NWV
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) s_part[wave - 1][mt][lane] = acc[mt];
-    }
-    __syncthreads();
-    if (wave > 0) return;
-    // accumulator layout: element i of lane (r16, g) is output column n0 + 4g + i of row mt*16 + r16
+    for (int p = 0; p < kTiles / kGroup; ++p) {
+        if (p > 0) __syncthreads();
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        f32x4 v = acc[mt];
+        for (int j = 0; j < kGroup; ++j) s_part[wave][j][lane] = acc[(p * kGroup + j) / NT][(p * kGroup + j) % NT];
+        __syncthreads();
+        for (int j = wave; j < kGroup; j += NWV) {
+            f32x4 v = s_part[0][j][lane];
 #pragma unroll
-        for (int w = 0; w < NWV - 1; ++w) v += s_part[w][mt][lane];
-        const int m = mt * 16 + r16;
-        if (m >= a.M) continue;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int n = n0 + 4 * g + i;
-            if (n >= a.N) continue;
-            float y = v[i] + (a.bias ? a.bias[n] : 0.f);
-            const size_t o = (size_t)m * a.ldy + n;
-            if (EPI == EPI_HEAD) {
-                a.y_f32[o] = y;
-            } else {
-                y = silu(y);
-                if (EPI == EPI_MLP) y += a.res[o];
-                a.y_f32[o] = y;
-                a.y_bf[o] = (__bf16)y;
-                if (EPI == EPI_RNN) a.s_bf[(size_t)m * a.N + n] = (__bf16)y;
-            }
+            for (int w = 1; w < NWV; ++w) v += s_part[w][j][lane];
+            const int id = p * kGroup + j;
+            linear_epilogue<EPI>(a, v, (id / NT) * 16, n0 + (id % NT) * 16, r16, g);
         }
     }
 }
@@ -219,7 +249,7 @@ constexpr int kMaxChunks = kTopThreads * kTopPer / kChunk;      // V <= 32768
 // First pass over the logits: workgroup (chunk c, row m) reduces 4096 logits to their maximum, the
 // sum of exp(x - maximum) and their W best (value, then smaller index).  Every wave finds the W best
 // of its own 1024 logits with lane shuffles only; wave 0 then picks the W best of the 4 x W survivors.
-__global__ __launch_bounds__(kChunkThreads) void rd_topw_chunk_kernel(const float *__restrict__ logits, int V, int W, int chunks,
+__global__ __launch_bounds__(kChunkThreads) void rd_topw_chunk_kernel(const float *__restrict__ logits, int V, int W, int chunks, int mstride,
                                                                       float *__restrict__ part_max, float *__restrict__ part_sum,
                                                                       float *__restrict__ part_cv, int32_t *__restrict__ part_ci)
 {
@@ -228,7 +258,7 @@ __global__ __launch_bounds__(kChunkThreads) void rd_topw_chunk_kernel(const floa
     __shared__ float s_mx;
     __shared__ float s_cv[kWaves * kMaxBeam];
     __shared__ int s_ci[kWaves * kMaxBeam];
-    const int c = blockIdx.x, m = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = blockIdx.x, m = blockIdx.y * mstride, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float *z = logits + (size_t)m * V;
     const int v0 = c * kChunk;
     float x[kChunkPer];
@@ -455,30 +485,44 @@ int draft_check(const rd_draft_params *p, int B, int W, int L)
     return RD_OK;
 }
 
-template <int MT, int NWV, int EPI>
+template <int MT, int NT, int NWV, int EPI>
 void launch_linear_one(const LinArgs &a, hipStream_t stream)
 {
-    hipLaunchKernelGGL((rd_linear_kernel<MT, NWV, EPI>), dim3((a.N + 15) / 16), dim3(NWV * 64), 0, stream, a);
+    hipLaunchKernelGGL((rd_linear_kernel<MT, NT, NWV, EPI>), dim3((a.N + 16 * NT - 1) / (16 * NT)), dim3(NWV * 64), 0, stream, a);
 }
 
 // waves per workgroup: as many as give the launch about 16 waves per compute unit, as long as
-// every wave gets whole k-steps inside one product and the partial sums fit in LDS
-template <int MT, int EPI>
-int launch_linear_mt(const LinArgs &a, hipStream_t stream)
+// every wave gets whole k-steps inside one product and its registers allow that many residents
+template <int MT, int NT, int EPI>
+int launch_linear_nt(const LinArgs &a, hipStream_t stream)
 {
-    const int ks1 = a.K1 / 32, ks2 = a.K2 / 32, wgs = (a.N + 15) / 16;
+    const int ks1 = a.K1 / 32, ks2 = a.K2 / 32, wgs = (a.N + 16 * NT - 1) / (16 * NT);
     auto ok = [&](int nwv) {
-        if ((nwv - 1) * MT > 60) return false;
         if (ks2 == 0) return ks1 % nwv == 0;
         return ks1 == ks2 && ks1 % (nwv / 2) == 0;
     };
     int nwv = 4;
     if (wgs * 4 < 4096 && ok(8)) nwv = 8;
     if (wgs * 8 < 4096 && ok(16)) nwv = 16;
-    if (nwv == 16) { if constexpr (MT <= 4) launch_linear_one<MT, 16, EPI>(a, stream); else launch_linear_one<MT, 8, EPI>(a, stream); }
-    else if (nwv == 8) launch_linear_one<MT, 8, EPI>(a, stream);
-    else launch_linear_one<MT, 4, EPI>(a, stream);
+    constexpr bool k16 = MT * NT <= 4 && MT + NT <= 5;          // 16 waves need <= 128 registers per lane
+    if (nwv == 16) { if constexpr (k16) launch_linear_one<MT, NT, 16, EPI>(a, stream); else launch_linear_one<MT, NT, 8, EPI>(a, stream); }
+    else if (nwv == 8) launch_linear_one<MT, NT, 8, EPI>(a, stream);
+    else launch_linear_one<MT, NT, 4, EPI>(a, stream);
     return rd_check_launch();
+}
+
+// column tiles per workgroup: the most (up to the row tiles, at most 4) that still leave one
+// workgroup per compute unit
+template <int MT, int EPI>
+int launch_linear_mt(const LinArgs &a, hipStream_t stream)
+{
+    if constexpr (MT >= 4) {
+        if (a.N >= 256 * 64) return launch_linear_nt<MT, 4, EPI>(a, stream);
+    }
+    if constexpr (MT >= 2) {
+        if (a.N >= 256 * 32) return launch_linear_nt<MT, 2, EPI>(a, stream);
+    }
+    return launch_linear_nt<MT, 1, EPI>(a, stream);
 }
 
 template <int EPI>
@@ -548,17 +592,19 @@ extern "C" int rd_draft(const rd_draft_params *p, const void *h, const int32_t *
             LinArgs a = {};
             a.w1 = static_cast<const __bf16 *>(p->rnn_u); a.x1 = s_bf[si]; a.map1 = parent; a.ldx1 = Dm; a.K1 = Dm;
             a.w2 = static_cast<const __bf16 *>(p->rnn_w); a.x2 = emb; a.map2 = tok; a.ldx2 = Dm; a.K2 = Dm;
-            a.bias = p->rnn_b; a.M = M; a.N = Dm;
+            a.bias = p->rnn_b; a.M = M; a.N = Dm; a.mstride = 1;
             a.y_f32 = x_f32[0]; a.y_bf = x_bf[0]; a.s_bf = s_bf[si ^ 1]; a.ldy = G;
             if (launch_linear<EPI_RNN>(a, s) != RD_OK) return RD_ERR_HIP;
             si ^= 1;
         }
+        // at the first position the W rows of a sequence are one and the same state: compute row b*W only
+        const int rows = t == 1 ? B : M, mstride = t == 1 ? W : 1;
         int in = 0;
         for (int k = 0; k < p->n_mlp; ++k) {        // x <- x + f(A_k x + c_k)
             const int out = in == 1 ? 2 : 1;
             LinArgs a = {};
             a.w1 = static_cast<const __bf16 *>(p->mlp_w) + (size_t)k * G * G; a.x1 = x_bf[in]; a.ldx1 = G; a.K1 = G;
-            a.bias = p->mlp_b + (size_t)k * G; a.M = M; a.N = G;
+            a.bias = p->mlp_b + (size_t)k * G; a.M = rows; a.N = G; a.mstride = mstride;
             a.y_f32 = x_f32[out]; a.y_bf = x_bf[out]; a.res = x_f32[in]; a.ldy = G;
             if (launch_linear<EPI_MLP>(a, s) != RD_OK) return RD_ERR_HIP;
             in = out;
@@ -566,10 +612,10 @@ extern "C" int rd_draft(const rd_draft_params *p, const void *h, const int32_t *
         {                                           // logits
             LinArgs a = {};
             a.w1 = static_cast<const __bf16 *>(p->head_w); a.x1 = x_bf[in]; a.ldx1 = G; a.K1 = G;
-            a.M = M; a.N = V; a.y_f32 = logits; a.ldy = V;
+            a.M = rows; a.N = V; a.mstride = mstride; a.y_f32 = logits; a.ldy = V;
             if (launch_linear<EPI_HEAD>(a, s) != RD_OK) return RD_ERR_HIP;
         }
-        hipLaunchKernelGGL(rd_topw_chunk_kernel, dim3(chunks, M), dim3(kChunkThreads), 0, s, logits, V, W, chunks,
+        hipLaunchKernelGGL(rd_topw_chunk_kernel, dim3(chunks, rows), dim3(kChunkThreads), 0, s, logits, V, W, chunks, mstride,
                            part_max, part_sum, part_cv, part_ci);
         if (rd_check_launch() != RD_OK) return RD_ERR_HIP;
         const bool last = t == T;
