@@ -272,8 +272,9 @@ int rd_commit_paged(const void *k_new, const void *v_new, const int32_t *accepte
  * h : bf16 [B,Dm];  last_token : int32 [B] (clamped to [0, V-1]);  beams : int32 [B,W,L];
  * beam_logp : float [B,W].  workspace: rd_draft_workspace(...) bytes, 256-byte aligned, no
  * initial contents required, not shared by concurrent calls.
- * Limits: Dm a multiple of 64; W <= 32, W <= V; B*W <= 128; V <= 32768; L <= 384.
- * The call enqueues 3 + n_mlp launches per drafted position (4 + n_mlp after the first).
+ * Limits: Dm a multiple of 64; W <= 32, W <= V; B*W <= 512; V <= 32768; L <= 384.
+ * The call enqueues 3 + n_mlp launches per drafted position (4 + n_mlp after the first) while
+ * B*W <= 128; every further 128 rows add one launch per linear layer.
  */
 typedef struct {
     const void *emb, *rnn_u, *rnn_w;

@@ -27,7 +27,8 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
-constexpr int kMaxRows = 128;          // B*W
+constexpr int kMaxRows = 512;          // B*W
+constexpr int kRowsPerLaunch = 128;    // rows of one linear-layer launch (8 MFMA row tiles)
 constexpr int kMaxBeam = 32;           // W
 constexpr int kTopThreads = 1024;
 constexpr int kTopPer = 32;            // V <= kTopThreads * kTopPer = 32768 (eight chunks of 4096 logits)
@@ -42,6 +43,7 @@ struct LinArgs {
     int ldx1, ldx2, K1, K2;            // K2 = 0: single product
     const float *bias;                 // [N] or NULL
     int M, N;
+    int m0;                            // first logical row of this launch (a launch covers rows m0 .. m0+M-1)
     int mstride;                       // logical row m of X (without a map), Y and res is physical row m*mstride
     // epilogue
     float *y_f32;                      // HEAD: logits [M][ldy];  RNN/MLP: activations fp32 [M][ldy]
@@ -61,7 +63,7 @@ __device__ __forceinline__ void linear_epilogue(const LinArgs &a, f32x4 v, int m
 {
     const int m = m_tile + r16;
     if (m >= a.M) return;
-    const size_t prow = (size_t)m * a.mstride;                  // physical row of the activation buffers
+    const size_t prow = (size_t)(a.m0 + m) * a.mstride;         // physical row of the activation buffers
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int n = n_tile + 4 * g + i;
@@ -117,7 +119,7 @@ __global__ __launch_bounds__(NWV * 64) void rd_linear_kernel(LinArgs a)
     const __bf16 *xp[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-        const int m = min(mt * 16 + r16, a.M - 1);
+        const int m = a.m0 + min(mt * 16 + r16, a.M - 1);
         const size_t row = map ? (size_t)map[m] : (size_t)m * a.mstride;
         xp[mt] = xbase + row * ldx + k_first + 8 * g;
     }
@@ -525,14 +527,23 @@ int launch_linear_mt(const LinArgs &a, hipStream_t stream)
     return launch_linear_nt<MT, 1, EPI>(a, stream);
 }
 
+// more than 128 rows: one launch per 128 rows (each streams the weights again)
 template <int EPI>
-int launch_linear(const LinArgs &a, hipStream_t stream)
+int launch_linear(const LinArgs &all, hipStream_t stream)
 {
-    const int mt = (a.M + 15) / 16;
-    if (mt <= 1) return launch_linear_mt<1, EPI>(a, stream);
-    if (mt <= 2) return launch_linear_mt<2, EPI>(a, stream);
-    if (mt <= 4) return launch_linear_mt<4, EPI>(a, stream);
-    return launch_linear_mt<8, EPI>(a, stream);
+    for (int m0 = 0; m0 < all.M; m0 += kRowsPerLaunch) {
+        LinArgs a = all;
+        a.m0 = m0;
+        a.M = all.M - m0 < kRowsPerLaunch ? all.M - m0 : kRowsPerLaunch;
+        const int mt = (a.M + 15) / 16;
+        int st;
+        if (mt <= 1) st = launch_linear_mt<1, EPI>(a, stream);
+        else if (mt <= 2) st = launch_linear_mt<2, EPI>(a, stream);
+        else if (mt <= 4) st = launch_linear_mt<4, EPI>(a, stream);
+        else st = launch_linear_mt<8, EPI>(a, stream);
+        if (st != RD_OK) return st;
+    }
+    return RD_OK;
 }
 
 }  // namespace

@@ -67,7 +67,9 @@ def check(rd, p, h, last, W, L, what):
                                           (192, 2000, 3, 2, 8, 2), (64, 100, 1, 2, 4, 1),
                                           # many rows and a wide vocabulary: workgroups that own 32 and 64 columns
                                           (64, 9000, 1, 3, 8, 3), (64, 17000, 1, 5, 8, 3), (128, 16500, 2, 9, 8, 4),
-                                          (64, 20000, 0, 4, 32, 3)])
+                                          (64, 20000, 0, 4, 32, 3),
+                                          # more rows than one linear-layer launch covers
+                                          (64, 700, 1, 20, 8, 4), (64, 16400, 1, 9, 32, 3)])
 def test_draft_matches_oracle(rd, Dm, V, K, B, W, L):
     announce(f"draft Dm={Dm} V={V} K={K} B={B} W={W} L={L}")
     p = make_params(V, Dm, K, seed=Dm + V, scale=4.0)
