@@ -175,6 +175,41 @@ def accept(beams, unpack_index, argmax_in, root_token=None) -> dict:
     return out
 
 
+def accept_sample(logits, draft_logits, beams, unpack_index, u_accept, u_next, temperature: float,
+                  root_token=None, diagnostics: bool = False) -> dict:
+    """Acceptance by rejection sampling (Sec. 3.4's other selection mode).  logits, draft_logits float32
+    [B,N,V]; u_accept float32 [B,N] (one uniform number per packed slot); u_next float32 [B].  With
+    `diagnostics`, also accept_ratio float64 [B,W,L] and next_weights float64 [B,V]."""
+    logits = np.ascontiguousarray(logits, dtype=np.float32)
+    draft_logits = np.ascontiguousarray(draft_logits, dtype=np.float32)
+    beams, unpack_index = _i32(beams), _i32(unpack_index)
+    B, W, L = beams.shape
+    V = logits.shape[2]
+    assert logits.shape == (B, W * L, V) and draft_logits.shape == logits.shape
+    u_accept = np.ascontiguousarray(u_accept, dtype=np.float32)
+    u_next = np.ascontiguousarray(u_next, dtype=np.float32)
+    assert u_accept.shape == (B, W * L) and u_next.shape == (B,)
+    root = None if root_token is None else _i32(root_token)
+    out = dict(
+        n_accept=np.empty((B, W), np.int32),
+        best_beam=np.empty((B,), np.int32),
+        best_len=np.empty((B,), np.int32),
+        next_token=np.empty((B,), np.int32),
+        accepted_idx=np.empty((B, L), np.int32),
+    )
+    ratio = np.empty((B, W, L), np.float64) if diagnostics else None
+    weights = np.empty((B, V), np.float64) if diagnostics else None
+    fn = lib().orc_accept_sample
+    fn.argtypes = [ctypes.c_void_p] * 7 + [ctypes.c_double] + [ctypes.c_int] * 4 + [ctypes.c_void_p] * 7
+    fn.restype = None
+    fn(_p(logits), _p(draft_logits), _p(beams), _p(unpack_index), _p(root), _p(u_accept), _p(u_next),
+       float(temperature), B, W, L, V, _p(out["n_accept"]), _p(out["best_beam"]), _p(out["best_len"]),
+       _p(out["next_token"]), _p(out["accepted_idx"]), _p(ratio), _p(weights))
+    if diagnostics:
+        out["accept_ratio"], out["next_weights"] = ratio, weights
+    return out
+
+
 def commit(k_new, v_new, accepted_idx, best_len, ctx_len, k_cache, v_cache, dtype: str,
            hidden=None) -> dict:
     """Commit of the accepted tokens: returns updated COPIES of the caches, ctx_len_out,

@@ -2,8 +2,9 @@
  * CPU oracle for the ReDrafter verification step.  TEST INFRASTRUCTURE ONLY.
  *
  * A plain, slow, definition-level implementation of what the verification step
- * computes (dynamic tree attention, Sec. 3.3 and App. A.1; verification, greedy
- * acceptance and the commit of the accepted tokens, Sec. 3.4).  It exists so that
+ * computes (dynamic tree attention, Sec. 3.3 and App. A.1; verification, greedy and
+ * rejection-sampling acceptance and the commit of the accepted tokens, Sec. 3.4) and of the
+ * draft model with its beam search (Sec. 3.1, 3.2).  It exists so that
  * the HIP path can be checked against something that is easy to compare with the
  * paper by eye.  It shares no code
  * with the HIP path and must never be called from it; only tests, the smoke
@@ -20,7 +21,10 @@
  * forms, per-beam causal attention in numpy, library argmax, a toy greedy LM; for the
  * draft model: a numpy/scipy forward pass, greedy decoding, exhaustive search; for the
  * commit: numpy index arithmetic, attention over the committed cache, and a many-step
- * speculative loop that must reproduce plain greedy decoding of a toy attention LM).
+ * speculative loop that must reproduce plain greedy decoding of a toy attention LM; for
+ * the rejection-sampling acceptance: the published guarantee that the emitted token follows
+ * the LLM's distribution with acceptance rate sum min(p, q), the zero-temperature limit,
+ * identical models, library softmax / cumsum / searchsorted, a walk over a literal trie).
  *
  * OpenMP (if enabled at compile time) parallelises only over independent
  * (sequence, head) pairs or logit rows; the arithmetic per output is unchanged.
@@ -666,4 +670,119 @@ void orc_draft_path_logp(const uint16_t *emb, const uint16_t *rnn_u, const uint1
             out[(size_t)b * n_paths + r] = total;
         }
     free(hd); free(s); free(s2); free(lp);
+}
+
+/* ---------------------------------------------------------------------------------
+ * Acceptance by rejection sampling, the selection mode of Sec. 3.4 for sampling at a
+ * temperature (the paper names the mode and gives no procedure; this is speculative
+ * sampling as published by Leviathan et al. and Chen et al., 2023, applied to every
+ * candidate of the beam on the packed tree).  Per sequence:
+ *   p_s = softmax(logits[s] / temperature)   the LLM's distribution after packed token s
+ *   q_s = softmax(draft_logits[s])           the draft model's distribution at the same place
+ *   candidate w's token j >= 1 (x = beams[w][j], hanging under slot s = unpack[w][j-1], stored
+ *   in slot c = unpack[w][j]) is accepted, given all earlier ones were, iff
+ *       u_accept[c] < min(1, p_s(x) / q_s(x));
+ *   the uniform number belongs to the packed slot, so candidates that share a prefix share
+ *   its decisions.  Token 0 as in token matching (given, or compared with root_token).
+ *   The best candidate has the longest accepted prefix (smallest index among equals).
+ *   The token that follows it is drawn by inverting the cumulative distribution with
+ *   u_next[b]: from p_s when the whole candidate was accepted, else from the residual
+ *   max(0, p_s - q_s) (normalised) at the slot s under which its first rejected token hangs;
+ *   it is the smallest v with  sum_{v' <= v} weight(v') > u_next * sum_v weight(v)  (the last
+ *   v of positive weight if rounding leaves none).  A residual that vanishes identically
+ *   (p_s == q_s) falls back to p_s.  With nothing accepted (root mismatch) the next token is
+ *   root_token.
+ * Diagnostics for the tests (each may be NULL): accept_ratio[b][w][j] = min(1, p/q) of every
+ * token that was examined (j >= 1; -1 where the scan had already stopped), next_weights[b][v] =
+ * the normalised distribution the next token was drawn from (zeros when best_len == 0).   */
+static double log_sum_exp(const float *z, int V, double inv_t)
+{
+    double m = -INFINITY;
+    for (int v = 0; v < V; ++v)
+        if ((double)z[v] * inv_t > m) m = (double)z[v] * inv_t;
+    if (m == -INFINITY) return m;
+    double s = 0.0;
+    for (int v = 0; v < V; ++v) s += exp((double)z[v] * inv_t - m);
+    return m + log(s);
+}
+
+void orc_accept_sample(const float *logits, const float *draft_logits, const int32_t *beams,
+                       const int32_t *unpack_index, const int32_t *root_token,
+                       const float *u_accept /*[B,N]*/, const float *u_next /*[B]*/, double temperature,
+                       int B, int W, int L, int V,
+                       int32_t *n_accept, int32_t *best_beam, int32_t *best_len, int32_t *next_token,
+                       int32_t *accepted_idx, double *accept_ratio, double *next_weights)
+{
+    const int N = W * L;
+    const double inv_t = 1.0 / temperature;
+    double *wt = (double *)malloc(sizeof(double) * (size_t)V);
+    for (int b = 0; b < B; ++b) {
+        const int32_t *beam = beams + (size_t)b * N;
+        const int32_t *ui = unpack_index + (size_t)b * N;
+        int bw = 0, bl = -1;
+        for (int w = 0; w < W; ++w) {
+            int len = 0;
+            if (accept_ratio)
+                for (int j = 0; j < L; ++j) accept_ratio[((size_t)b * W + w) * L + j] = -1.0;
+            for (int j = 0; j < L; ++j) {
+                int ok;
+                if (j == 0) {
+                    ok = (root_token == NULL) || (beam[w * L] == root_token[b]);
+                } else {
+                    const int s = ui[w * L + j - 1], c = ui[w * L + j], x = beam[w * L + j];
+                    const float *zp = logits + ((size_t)b * N + s) * V;
+                    const float *zq = draft_logits + ((size_t)b * N + s) * V;
+                    const double lp = (double)zp[x] * inv_t - log_sum_exp(zp, V, inv_t);
+                    const double lq = (double)zq[x] - log_sum_exp(zq, V, 1.0);
+                    double ratio = exp(lp - lq);            /* p(x) / q(x) */
+                    if (ratio > 1.0) ratio = 1.0;
+                    if (accept_ratio) accept_ratio[((size_t)b * W + w) * L + j] = ratio;
+                    ok = (double)u_accept[(size_t)b * N + c] < ratio;
+                }
+                if (!ok) break;
+                ++len;
+            }
+            n_accept[b * W + w] = len;
+            if (len > bl) { bl = len; bw = w; }
+        }
+        best_beam[b] = bw;
+        best_len[b] = bl;
+        for (int t = 0; t < L; ++t) accepted_idx[b * L + t] = (t < bl) ? ui[bw * L + t] : -1;
+        if (next_weights) memset(next_weights + (size_t)b * V, 0, sizeof(double) * (size_t)V);
+        if (bl == 0) {
+            next_token[b] = root_token[b];
+            continue;
+        }
+        const int s = ui[bw * L + bl - 1];
+        const float *zp = logits + ((size_t)b * N + s) * V;
+        const float *zq = draft_logits + ((size_t)b * N + s) * V;
+        const double lse_p = log_sum_exp(zp, V, inv_t), lse_q = log_sum_exp(zq, V, 1.0);
+        double total = 0.0;
+        if (bl < L) {                                       /* a rejection: the residual distribution */
+            for (int v = 0; v < V; ++v) {
+                const double d = exp((double)zp[v] * inv_t - lse_p) - exp((double)zq[v] - lse_q);
+                wt[v] = d > 0.0 ? d : 0.0;
+                total += wt[v];
+            }
+        }
+        if (bl == L || total == 0.0) {
+            total = 0.0;
+            for (int v = 0; v < V; ++v) {
+                wt[v] = exp((double)zp[v] * inv_t - lse_p);
+                total += wt[v];
+            }
+        }
+        const double target = (double)u_next[b] * total;
+        int pick = -1, last_pos = 0;
+        double cum = 0.0;
+        for (int v = 0; v < V; ++v) {
+            cum += wt[v];
+            if (wt[v] > 0.0) last_pos = v;
+            if (pick < 0 && cum > target) pick = v;
+        }
+        next_token[b] = pick >= 0 ? pick : last_pos;
+        if (next_weights)
+            for (int v = 0; v < V; ++v) next_weights[(size_t)b * V + v] = wt[v] / total;
+    }
+    free(wt);
 }

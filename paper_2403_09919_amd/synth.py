@@ -22,7 +22,7 @@ SEED_BASE = 0x5EED0000
 
 # stream ids: every tensor group has its own counter-based child stream so a
 # test can draw only what it needs and still see the same values.
-_S_CTX, _S_BEAM, _S_QNEW, _S_KCACHE, _S_VCACHE, _S_LOGITS = range(6)
+_S_CTX, _S_BEAM, _S_QNEW, _S_KCACHE, _S_VCACHE, _S_LOGITS, _S_DRAFT, _S_UNIFORM = range(8)
 
 
 @dataclass(frozen=True)
@@ -183,6 +183,20 @@ def make_logits(B: int, N: int, V: int, seed: int,
                 if 0 <= tok < V:
                     logits[b, p, tok] += np.float32(bump)
     return logits
+
+
+def make_draft_logits(logits: np.ndarray, seed: int, noise: float = 1.0) -> np.ndarray:
+    """Draft-model stand-in for sampling-mode acceptance: the LLM's logits plus N(0, noise^2), so the
+    two distributions agree roughly, as a distilled drafter's do."""
+    rng = _rng(seed, _S_DRAFT)
+    return (logits + np.float32(noise) * rng.standard_normal(logits.shape, dtype=np.float32)).astype(np.float32)
+
+
+def make_uniforms(shape, seed: int) -> np.ndarray:
+    """Uniform numbers in [0, 1) as float32 (the random draws of sampling-mode acceptance)."""
+    rng = _rng(seed, _S_UNIFORM)
+    u = rng.random(shape, dtype=np.float32)
+    return np.minimum(u, np.float32(1.0 - 2.0 ** -24))
 
 
 def make_attn_inputs(cfg: Config, seed: Optional[int] = None, poison: bool = True) -> dict:
