@@ -692,6 +692,8 @@ void orc_draft_path_logp(const uint16_t *emb, const uint16_t *rnn_u, const uint1
  *   v of positive weight if rounding leaves none).  A residual that vanishes identically
  *   (p_s == q_s) falls back to p_s.  With nothing accepted (root mismatch) the next token is
  *   root_token.
+ * draft_logits rows of slots at the last position (depth L-1) are never read: the draft model
+ * has no distribution there, and after a fully accepted candidate the LLM's own is used.
  * Diagnostics for the tests (each may be NULL): accept_ratio[b][w][j] = min(1, p/q) of every
  * token that was examined (j >= 1; -1 where the scan had already stopped), next_weights[b][v] =
  * the normalised distribution the next token was drawn from (zeros when best_len == 0).   */
@@ -732,10 +734,13 @@ void orc_accept_sample(const float *logits, const float *draft_logits, const int
                     const int s = ui[w * L + j - 1], c = ui[w * L + j], x = beam[w * L + j];
                     const float *zp = logits + ((size_t)b * N + s) * V;
                     const float *zq = draft_logits + ((size_t)b * N + s) * V;
-                    const double lp = (double)zp[x] * inv_t - log_sum_exp(zp, V, inv_t);
-                    const double lq = (double)zq[x] - log_sum_exp(zq, V, 1.0);
-                    double ratio = exp(lp - lq);            /* p(x) / q(x) */
-                    if (ratio > 1.0) ratio = 1.0;
+                    double ratio = 0.0;                     /* a token outside the vocabulary is rejected */
+                    if (x >= 0 && x < V) {
+                        const double lp = (double)zp[x] * inv_t - log_sum_exp(zp, V, inv_t);
+                        const double lq = (double)zq[x] - log_sum_exp(zq, V, 1.0);
+                        ratio = exp(lp - lq);               /* p(x) / q(x) */
+                        if (ratio > 1.0) ratio = 1.0;
+                    }
                     if (accept_ratio) accept_ratio[((size_t)b * W + w) * L + j] = ratio;
                     ok = (double)u_accept[(size_t)b * N + c] < ratio;
                 }
@@ -756,9 +761,10 @@ void orc_accept_sample(const float *logits, const float *draft_logits, const int
         const int s = ui[bw * L + bl - 1];
         const float *zp = logits + ((size_t)b * N + s) * V;
         const float *zq = draft_logits + ((size_t)b * N + s) * V;
-        const double lse_p = log_sum_exp(zp, V, inv_t), lse_q = log_sum_exp(zq, V, 1.0);
+        const double lse_p = log_sum_exp(zp, V, inv_t);
         double total = 0.0;
         if (bl < L) {                                       /* a rejection: the residual distribution */
+            const double lse_q = log_sum_exp(zq, V, 1.0);
             for (int v = 0; v < V; ++v) {
                 const double d = exp((double)zp[v] * inv_t - lse_p) - exp((double)zq[v] - lse_q);
                 wt[v] = d > 0.0 ? d : 0.0;

@@ -168,3 +168,26 @@ def test_refuted_first_token_returns_the_root_token():
     r = oracle.accept_sample(z, z, beams, d["unpack_index"], np.zeros((B, W * L), np.float32), np.zeros(B, np.float32), 1.0, root)
     assert r["best_len"][0] == 0 and r["next_token"][0] == root[0] and (r["accepted_idx"][0] == -1).all()
     assert r["best_len"][1] == L                               # uniform models: ratio 1, everything accepted
+
+
+def test_last_position_draft_rows_are_never_read_and_foreign_tokens_are_rejected():
+    B, W, L, V = 3, 4, 3, 13
+    beams = synth.make_beams(B, W, L, V, 2, "uniform")
+    d = oracle.dedup(beams, np.full(B, 4, np.int32))
+    logits = np.random.default_rng(2).standard_normal((B, W * L, V)).astype(np.float32)
+    draft = synth.make_draft_logits(logits, 2, 0.5)
+    u_acc, u_next = synth.make_uniforms((B, W * L), 6), synth.make_uniforms((B,), 7)
+    want = oracle.accept_sample(logits, draft, beams, d["unpack_index"], u_acc, u_next, 1.0)
+    poisoned = draft.copy()
+    for b in range(B):
+        poisoned[b, d["unpack_index"][b, :, L - 1]] = np.nan       # the draft model has no distribution there
+        poisoned[b, d["n_packed"][b]:] = np.nan                      # nor at padding slots
+    got = oracle.accept_sample(logits, poisoned, beams, d["unpack_index"], u_acc, u_next, 1.0)
+    for k in want:
+        assert np.array_equal(want[k], got[k]), k
+    bad = beams.copy()
+    bad[0, :, 1] = V + 5                                             # not a token of the vocabulary
+    bad[1, :, 1] = -1
+    d2 = oracle.dedup(bad, np.full(B, 4, np.int32))
+    r = oracle.accept_sample(logits, draft, bad, d2["unpack_index"], np.zeros((B, W * L), np.float32), u_next, 1.0)
+    assert (r["n_accept"][:2] == 1).all()
