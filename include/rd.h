@@ -13,6 +13,7 @@
  *   rd_accept     greedy "token match" acceptance (Sec. 3.4, Fig. 2): arg max of the
  *                 LLM's logits per packed token, longest accepted prefix per candidate,
  *                 best candidate, next token;
+ *   rd_accept_sample  the same selection by rejection sampling, for sampling at a temperature;
  *   rd_commit     what follows acceptance (Sec. 3.4): the accepted tokens join the context
  *                 (their K/V rows are appended to the cache, ctx_len grows) and the LLM's
  *                 hidden state at the last accepted token is picked out for the next draft;
@@ -181,6 +182,46 @@ int rd_accept(const float *logits, const int32_t *beams, const int32_t *unpack_i
               int32_t *argmax_out, int32_t *n_accept, int32_t *best_beam,
               int32_t *best_len, int32_t *next_token, int32_t *accepted_idx,
               void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * rd_accept_sample — acceptance by rejection sampling, the selection mode Sec. 3.4 names for
+ * sampling at a temperature.  The paper gives no procedure; this is speculative sampling as
+ * published (Leviathan et al.; Chen et al., 2023), applied to every candidate on the packed tree.
+ *
+ *   p_s = softmax(logits[b][s] / temperature), the LLM's distribution after packed token s;
+ *   q_s = softmax(draft_logits[b][s]), the draft model's distribution at the same place.
+ *   Candidate w's token j >= 1 (x = beams[b][w][j], under slot s = unpack_index[b][w][j-1], stored in
+ *   slot c = unpack_index[b][w][j]) is accepted, given tokens 0..j-1 were, iff
+ *       u_accept[b][c] < min(1, p_s(x) / q_s(x))
+ *   (one uniform number per packed slot: candidates that share a prefix share its decisions; a
+ *   token outside [0, V) is rejected).  Token 0 as in rd_accept (root_token).
+ *   n_accept, best_beam (longest accepted prefix, smallest index among equals), best_len,
+ *   accepted_idx as in rd_accept.
+ *   next_token[b]: drawn by inverting the cumulative distribution with u_next[b] — the smallest v
+ *   with sum_{v' <= v} weight(v') > u_next[b] * sum weight and weight(v) > 0 — where weight = p_s
+ *   at the candidate's last slot when it was accepted whole, else the residual max(0, p_s - q_s) at
+ *   the slot s under which its first rejected token hangs (p_s if the residual vanishes);
+ *   root_token[b] if best_len == 0.
+ *
+ * Arithmetic is fp32: a decision whose u lies within ~1e-5 of its threshold, or of a step of the
+ * cumulative distribution, may differ from an exact evaluation.
+ *
+ * logits, draft_logits : float [B,N,V], 16-byte aligned, free of NaN, at least one finite entry per
+ * row that is read.  Rows p >= n_packed[b] are not read; draft_logits rows of slots at the last
+ * position (depth L-1) are not read either (the draft model has no distribution there).
+ * u_accept : float [B,N] in [0,1);  u_next : float [B] in [0,1);  temperature > 0.
+ * beams, unpack_index, n_packed, root_token and the int32 outputs as for rd_accept (no argmax_out).
+ * workspace: rd_accept_sample_workspace(...) bytes, 256-byte aligned, no initial contents required,
+ * not shared by concurrent calls.  V <= 1048576.  Two launches on `stream`.
+ */
+size_t rd_accept_sample_workspace(int B, int W, int L, int V);
+
+int rd_accept_sample(const float *logits, const float *draft_logits, const int32_t *beams,
+                     const int32_t *unpack_index, const int32_t *n_packed, const int32_t *root_token,
+                     const float *u_accept, const float *u_next, float temperature,
+                     int B, int W, int L, int V,
+                     int32_t *n_accept, int32_t *best_beam, int32_t *best_len, int32_t *next_token,
+                     int32_t *accepted_idx, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * rd_commit — the accepted tokens join the sequence generated so far (last step of the decoding

@@ -38,6 +38,8 @@ EXPORTS = {
     "rd_tree_attn_paged": (_i, [_vp] * 4 + [_i, _i, _i] + [_vp] * 5 + [_i, _i, _i, _i, _i, _f, _vp, _vp, _sz, _vp]),
     "rd_accept_workspace": (_sz, [_i, _i, _i, _i]),
     "rd_accept": (_i, [_vp] * 5 + [_i, _i, _i, _i] + [_vp] * 6 + [_vp, _sz, _vp]),
+    "rd_accept_sample_workspace": (_sz, [_i, _i, _i, _i]),
+    "rd_accept_sample": (_i, [_vp] * 8 + [_f, _i, _i, _i, _i] + [_vp] * 5 + [_vp, _sz, _vp]),
     "rd_commit": (_i, [_vp] * 5 + [_i] * 7 + [_vp] * 4 + [_vp, _i, _vp, _vp]),
     "rd_draft_workspace": (_sz, [_i, _i, _i, _i, _i]),
     "rd_draft": (_i, [_vp, _vp, _vp, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]),
@@ -236,6 +238,44 @@ def rd_accept(logits, beams, unpack_index, n_packed, root_token: Optional[torch.
         _ptr(out["accepted_idx"], i32, (B, L), "accepted_idx"),
         _ptr(workspace, torch.uint8, None, "workspace"), workspace.numel(), _stream())
     _check(code, "rd_accept")
+    return out
+
+
+def rd_accept_sample_workspace(B: int, W: int, L: int, V: int) -> int:
+    return int(_lib.rd_accept_sample_workspace(B, W, L, V))
+
+
+def rd_accept_sample(logits, draft_logits, beams, unpack_index, n_packed, u_accept, u_next, temperature: float,
+                     root_token: Optional[torch.Tensor] = None, out: Optional[dict] = None,
+                     workspace: Optional[torch.Tensor] = None) -> dict:
+    """Rejection-sampling acceptance: logits, draft_logits float32 [B,N,V]; u_accept float32 [B,N];
+    u_next float32 [B] -> dict(n_accept, best_beam, best_len, next_token, accepted_idx)."""
+    B, W, L = beams.shape
+    N = W * L
+    V = logits.shape[2]
+    dev = logits.device
+    i32, f32 = torch.int32, torch.float32
+    if out is None:
+        out = dict(
+            n_accept=torch.empty((B, W), dtype=i32, device=dev),
+            best_beam=torch.empty((B,), dtype=i32, device=dev),
+            best_len=torch.empty((B,), dtype=i32, device=dev),
+            next_token=torch.empty((B,), dtype=i32, device=dev),
+            accepted_idx=torch.empty((B, L), dtype=i32, device=dev),
+        )
+    if workspace is None:
+        workspace = new_workspace(rd_accept_sample_workspace(B, W, L, V), dev)
+    code = _lib.rd_accept_sample(
+        _ptr(logits, f32, (B, N, V), "logits"), _ptr(draft_logits, f32, (B, N, V), "draft_logits"),
+        _ptr(beams, i32, (B, W, L), "beams"), _ptr(unpack_index, i32, (B, W, L), "unpack_index"),
+        _ptr(n_packed, i32, (B,), "n_packed"), _ptr(root_token, i32, (B,), "root_token"),
+        _ptr(u_accept, f32, (B, N), "u_accept"), _ptr(u_next, f32, (B,), "u_next"), float(temperature),
+        B, W, L, V,
+        _ptr(out["n_accept"], i32, (B, W), "n_accept"), _ptr(out["best_beam"], i32, (B,), "best_beam"),
+        _ptr(out["best_len"], i32, (B,), "best_len"), _ptr(out["next_token"], i32, (B,), "next_token"),
+        _ptr(out["accepted_idx"], i32, (B, L), "accepted_idx"),
+        _ptr(workspace, torch.uint8, None, "workspace"), workspace.numel(), _stream())
+    _check(code, "rd_accept_sample")
     return out
 
 

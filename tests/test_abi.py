@@ -32,7 +32,7 @@ def test_header_symbols_exported(lib):
     names = _declared_symbols()
     assert names == sorted(["rd_strerror", "rd_version", "rd_dedup", "rd_tree_attn_workspace",
                             "rd_tree_attn", "rd_tree_attn_paged_workspace", "rd_tree_attn_paged",
-                            "rd_accept_workspace", "rd_accept", "rd_commit", "rd_commit_paged", "rd_rope",
+                            "rd_accept_workspace", "rd_accept", "rd_accept_sample_workspace", "rd_accept_sample", "rd_commit", "rd_commit_paged", "rd_rope",
                             "rd_draft_workspace", "rd_draft"])
     raw = ctypes.CDLL(LIB)
     for n in names:
@@ -124,6 +124,34 @@ def test_accept_argument_errors(lib):
     assert _accept(lib, req=None) == INVALID
     assert _accept(lib, ws=None) == WORKSPACE
     assert _accept(lib, ws_bytes=8) == WORKSPACE
+
+
+def _sample(lib, B=1, W=4, L=4, V=100, logits=FAKE, draft=FAKE, req=FAKE, u=FAKE, t=1.0, ws=FAKE, ws_bytes=None):
+    import ctypes
+    need = lib.rd_accept_sample_workspace(B, W, L, V)
+    if ws_bytes is None:
+        ws_bytes = need
+    return lib.rd_accept_sample(logits, draft, FAKE, FAKE, FAKE, None, u, u, ctypes.c_float(t), B, W, L, V,
+                                req, req, req, req, req, ws, ws_bytes, None)
+
+
+def test_accept_sample_argument_errors(lib):
+    assert lib.rd_accept_sample_workspace(1, 8, 5, 32000) >= 8 * 40 * 16
+    assert lib.rd_accept_sample_workspace(1, 129, 1, 10) == 0
+    assert _sample(lib, B=0) == INVALID
+    assert _sample(lib, V=0) == INVALID
+    assert _sample(lib, t=0.0) == INVALID
+    assert _sample(lib, t=-1.0) == INVALID
+    assert _sample(lib, t=float("nan")) == INVALID
+    assert _sample(lib, t=float("inf")) == INVALID
+    assert _sample(lib, W=129, L=1) == UNSUPPORTED
+    assert _sample(lib, V=(1 << 20) + 4) == UNSUPPORTED
+    assert _sample(lib, logits=None) == INVALID
+    assert _sample(lib, draft=FAKE + 4) == INVALID
+    assert _sample(lib, u=None) == INVALID
+    assert _sample(lib, req=None) == INVALID
+    assert _sample(lib, ws=None) == WORKSPACE
+    assert _sample(lib, ws_bytes=8) == WORKSPACE
 
 
 def _paged(lib, B=1, H=2, N=8, D=64, ps=64, mp=4, npg=8, dt=1, q=FAKE, pages=FAKE, table=FAKE, ws=FAKE, ws_bytes=None):
