@@ -219,6 +219,21 @@ def main():
         rd.rd_accept(c["logits"], c["beams"], c["dedup"]["unpack_index"], c["dedup"]["n_packed"],
                      out=c["accept"], workspace=ws_acc)
 
+    dev = "cuda"
+    ws_samp = rd.new_workspace(rd.rd_accept_sample_workspace(cfg.B, cfg.W, cfg.L, cfg.V), dev)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(cfg.seed + 2)
+    for c in copies:                                  # sampling-mode acceptance: draft logits near the LLM's, uniform draws
+        c["draft_logits"] = c["logits"] + torch.randn(c["logits"].shape, generator=gen, device=dev)
+        c["u_accept"] = torch.rand((cfg.B, cfg.N), generator=gen, device=dev)
+        c["u_next"] = torch.rand((cfg.B,), generator=gen, device=dev)
+        c["sample"] = rd.rd_accept_sample(c["logits"], c["draft_logits"], c["beams"], c["dedup"]["unpack_index"],
+                                          c["dedup"]["n_packed"], c["u_accept"], c["u_next"], 1.0, workspace=ws_samp)
+
+    def k_sample(c):
+        rd.rd_accept_sample(c["logits"], c["draft_logits"], c["beams"], c["dedup"]["unpack_index"], c["dedup"]["n_packed"],
+                            c["u_accept"], c["u_next"], 1.0, out=c["sample"], workspace=ws_samp)
+
     def k_commit(c):
         rd.rd_commit(c["k_new"], c["v_new"], c["accept"]["accepted_idx"], c["accept"]["best_len"], c["ctx_commit"],
                      c["k_cache"], c["v_cache"], ctx_len_out=c["ctx_out"], n_committed=c["n_comm"])
@@ -247,7 +262,8 @@ def main():
         return round(k0.elapsed_time(k1) * 1e3 / (n // R * R), 3)
 
     kernels_us = {"rd_dedup": time_kernel(k_dedup), "rd_tree_attn": round(attn_us, 3),
-                  "rd_accept": time_kernel(k_accept), "rd_commit": time_kernel(k_commit)}
+                  "rd_accept": time_kernel(k_accept), "rd_commit": time_kernel(k_commit),
+                  "rd_accept_sample": time_kernel(k_sample)}
 
     draft = None if args.no_draft else time_draft(rd, cfg, stream, max(4, min(40, args.steps // 10)), torch)
 

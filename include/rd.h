@@ -211,8 +211,9 @@ int rd_accept(const float *logits, const int32_t *beams, const int32_t *unpack_i
  * position (depth L-1) are not read either (the draft model has no distribution there).
  * u_accept : float [B,N] in [0,1);  u_next : float [B] in [0,1);  temperature > 0.
  * beams, unpack_index, n_packed, root_token and the int32 outputs as for rd_accept (no argmax_out).
- * workspace: rd_accept_sample_workspace(...) bytes, 256-byte aligned, no initial contents required,
- * not shared by concurrent calls.  V <= 1048576.  Two launches on `stream`.
+ * workspace: as for rd_accept (at least rd_accept_sample_workspace(...) bytes, 256-byte aligned, all
+ * zero before first use, counters left zero by every call, not shared by concurrent calls).
+ * V <= 1048576.  Two launches on `stream`.
  */
 size_t rd_accept_sample_workspace(int B, int W, int L, int V);
 

@@ -7,36 +7,55 @@
 // stores the two pairs in the workspace.  Rows of slots at the last position carry no draft
 // distribution and their draft half is skipped.  No atomics, no counters: the partials are
 // combined in a fixed order by launch 2, so results do not depend on timing.
-// Launch 2 (one workgroup of 1024 threads per sequence): log-sum-exps of the rows; one thread per
+// Launch 2 (grid: chunks of 4096 vocabulary entries x sequences, 256 threads).  Every workgroup of a
+// sequence repeats the small part: log-sum-exps of the rows from the partials; one thread per
 // candidate token gathers the two logits of its token under its parent slot and decides
 // u < min(1, p/q); one thread per candidate counts its accepted prefix; the best candidate is the
-// longest (smallest index among equals).  The token that follows is drawn by inverting the
-// cumulative distribution of p, or of the residual max(0, p - q) after a rejection, with the
-// caller's uniform number: a first pass over the row computes the total of every chunk of 4096
-// weights with a block-wide scan, the chunk in which the running total crosses the target is
-// scanned again (same arithmetic, same values), and the first token of positive weight whose
-// cumulative weight exceeds the target is taken.
+// longest (smallest index among equals).  The token that follows is drawn by inverting a cumulative
+// distribution with the caller's uniform number.  One compute unit alone needs ~10 us for the 2 x V
+// exponentials of a residual max(0, p - q), so that pass is spread: each workgroup sums the residual
+// weights of its own chunk, stores the total and signals; the last one to arrive adds the totals in
+// chunk order, finds the chunk in which the running total crosses the target, recomputes that
+// chunk's weights and takes, by a block-wide prefix scan, the first token of positive weight whose
+// cumulative weight exceeds the target.  After a fully accepted candidate the weights are p itself,
+// whose chunk totals follow from launch 1's partials: workgroup 0 goes straight to the last step.
 #include "rd_internal.h"
 #include <math.h>
+
+RD_TRACE_DEFINE(rd_debug_set_trace_sample)
 
 namespace {
 
 constexpr int kLseThreads = 256;
 constexpr int kLseChunk = 4096;              // entries per workgroup of launch 1: 4 x 16 bytes per thread and array
-constexpr int kSelThreads = 1024;
-constexpr int kSelChunk = 4 * kSelThreads;   // weights per block-wide scan of launch 2
+constexpr int kSelThreads = 256;
+constexpr int kSelPer = 16;                  // consecutive entries per thread of launch 2
+constexpr int kSelChunk = kSelPer * kSelThreads;
 constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kMaxSelChunks = 256;           // V <= 1 Mi entries
+static_assert(kSelChunk == kLseChunk, "launch 2 takes the chunk totals of p from launch 1's partials");
 
-__device__ __forceinline__ float4 load4(const float *row, int v, int V, bool vec)
+// Entries v .. v+3 of a row, -inf past the end (weight 0, neutral for the maximum).  No branch: a
+// load inside a branch makes the compiler wait for every load in flight at the join, which turns a
+// batch of loads into a chain of round trips.  Addresses past the end are pulled back into the row
+// and the values replaced afterwards.  VEC: V is a multiple of 4 (16-byte loads), else four scalar loads.
+template <bool VEC>
+__device__ __forceinline__ float4 load4(const float *row, int v, int V)
 {
-    // entries v .. v+3 of a row; -inf past the end (weight 0, neutral for the maximum)
-    if (vec && v + 3 < V) return *reinterpret_cast<const float4 *>(row + v);
     float4 r;
-    r.x = v < V ? row[v] : -INFINITY;
-    r.y = v + 1 < V ? row[v + 1] : -INFINITY;
-    r.z = v + 2 < V ? row[v + 2] : -INFINITY;
-    r.w = v + 3 < V ? row[v + 3] : -INFINITY;
+    if constexpr (VEC) {
+        r = *reinterpret_cast<const float4 *>(row + min(v, V - 4));
+        if (v >= V) r = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+    } else {
+        r.x = row[min(v, V - 1)];
+        r.y = row[min(v + 1, V - 1)];
+        r.z = row[min(v + 2, V - 1)];
+        r.w = row[min(v + 3, V - 1)];
+        if (v >= V) r.x = -INFINITY;
+        if (v + 1 >= V) r.y = -INFINITY;
+        if (v + 2 >= V) r.z = -INFINITY;
+        if (v + 3 >= V) r.w = -INFINITY;
+    }
     return r;
 }
 
@@ -66,6 +85,7 @@ __device__ __forceinline__ float2 chunk_max_sum(const float4 (&x)[4], float scal
     return make_float2(m, s);
 }
 
+template <bool VEC>
 __global__ __launch_bounds__(kLseThreads) void rd_lse_chunk_kernel(
     const float *__restrict__ logits, const float *__restrict__ draft_logits, const int32_t *__restrict__ unpack_index,
     const int32_t *__restrict__ n_packed, int W, int L, int V, int chunks, float inv_t, float4 *__restrict__ part)
@@ -81,24 +101,19 @@ __global__ __launch_bounds__(kLseThreads) void rd_lse_chunk_kernel(
     if (tid == 0) s_leaf = 0;
     __syncthreads();
     if (tid < W && unpack_index[(size_t)b * N + tid * L + (L - 1)] == p) s_leaf = 1;   // a slot at the last position
-    const bool vec = (V & 3) == 0;
     const size_t rowid = (size_t)b * N + p;
     const float *zp = logits + rowid * V, *zq = draft_logits + rowid * V;
     const int v0 = chunk * kLseChunk;
     float4 xp[4], xq[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) xp[u] = load4(zp, v0 + (u * kLseThreads + tid) * 4, V, vec);
-    __syncthreads();
-    const bool leaf = s_leaf != 0;
-    if (!leaf) {
+    for (int u = 0; u < 4; ++u) xp[u] = load4<VEC>(zp, v0 + (u * kLseThreads + tid) * 4, V);
+    const float2 a = chunk_max_sum(xp, inv_t, s_red);       // (its barriers also publish s_leaf)
+    float2 c = make_float2(0.f, 1.f);
+    if (s_leaf == 0) {                                      // uniform: the draft half of the row exists
 #pragma unroll
-        for (int u = 0; u < 4; ++u) xq[u] = load4(zq, v0 + (u * kLseThreads + tid) * 4, V, vec);
-    } else {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) xq[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int u = 0; u < 4; ++u) xq[u] = load4<VEC>(zq, v0 + (u * kLseThreads + tid) * 4, V);
+        c = chunk_max_sum(xq, 1.0f, s_red);
     }
-    const float2 a = chunk_max_sum(xp, inv_t, s_red);
-    const float2 c = chunk_max_sum(xq, 1.0f, s_red);
     if (tid == 0) part[rowid * chunks + chunk] = make_float4(a.x, a.y, c.x, c.y);
 }
 
@@ -110,8 +125,8 @@ __device__ __forceinline__ float weight(float zp, float zq, float inv_t, float l
     return fmaxf(p - __expf(zq - lse_q), 0.f);
 }
 
-// Inclusive prefix sums of one value per thread over the workgroup, in thread order; returns the
-// exclusive prefix of this thread and, in `total`, the workgroup's sum (the same bits in every thread).
+// Exclusive prefix sums of one value per thread over the workgroup, in thread order; `total` gets the
+// workgroup's sum (the same bits in every thread).
 __device__ __forceinline__ float block_exclusive_scan(float x, float *s_wave, float &total)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -135,11 +150,40 @@ __device__ __forceinline__ float block_exclusive_scan(float x, float *s_wave, fl
     return before + (incl - x);
 }
 
+// The 16 consecutive weights of this thread in chunk `chunk` of the row; returns their sum.
+template <bool VEC>
+__device__ __forceinline__ float chunk_weights(const float *zp, const float *zq, int chunk, int V, float inv_t,
+                                               float lse_p, float lse_q, bool residual, float (&w)[kSelPer])
+{
+    const int v0 = chunk * kSelChunk + threadIdx.x * kSelPer;
+    const float *zr = residual ? zq : zp;                   // no draft row to read when drawing from p (value unused)
+    float4 a[kSelPer / 4], q[kSelPer / 4];
+#pragma unroll
+    for (int i = 0; i < kSelPer / 4; ++i) a[i] = load4<VEC>(zp, v0 + 4 * i, V);
+#pragma unroll
+    for (int i = 0; i < kSelPer / 4; ++i) q[i] = load4<VEC>(zr, v0 + 4 * i, V);
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < kSelPer / 4; ++i) {
+        w[4 * i + 0] = weight(a[i].x, q[i].x, inv_t, lse_p, lse_q, residual);
+        w[4 * i + 1] = weight(a[i].y, q[i].y, inv_t, lse_p, lse_q, residual);
+        w[4 * i + 2] = weight(a[i].z, q[i].z, inv_t, lse_p, lse_q, residual);
+        w[4 * i + 3] = weight(a[i].w, q[i].w, inv_t, lse_p, lse_q, residual);
+        sum += ((w[4 * i] + w[4 * i + 1]) + w[4 * i + 2]) + w[4 * i + 3];
+    }
+    return sum;
+}
+
+__device__ __forceinline__ void st_dev(float *p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ float ld_dev(const float *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
+template <bool VEC>
 __global__ __launch_bounds__(kSelThreads) void rd_accept_sample_kernel(
     const float *__restrict__ logits, const float *__restrict__ draft_logits, const int32_t *__restrict__ beams,
     const int32_t *__restrict__ unpack_index, const int32_t *__restrict__ n_packed,
     const int32_t *__restrict__ root_token, const float *__restrict__ u_accept, const float *__restrict__ u_next,
     int W, int L, int V, int chunks, float inv_t, const float4 *__restrict__ part,
+    float *chunk_totals /*[B][chunks]*/, uint32_t *counters /*[B]*/,
     int32_t *__restrict__ n_accept, int32_t *__restrict__ best_beam, int32_t *__restrict__ best_len,
     int32_t *__restrict__ next_token, int32_t *__restrict__ accepted_idx)
 {
@@ -147,16 +191,20 @@ __global__ __launch_bounds__(kSelThreads) void rd_accept_sample_kernel(
     __shared__ int s_slot[RD_MAX_N];
     __shared__ unsigned char s_ok[RD_MAX_N];
     __shared__ int s_best, s_pick, s_lastpos;
+    __shared__ uint32_t s_last;
     __shared__ float s_wave[kSelWaves];
-    __shared__ float s_chunk_total[kMaxSelChunks];
+    __shared__ float s_total[kMaxSelChunks];
 
-    const int tid = threadIdx.x, b = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int chunk = blockIdx.x, b = blockIdx.y;
     const int N = W * L;
     int P = n_packed[b];
     P = P < 1 ? 1 : (P > N ? N : P);
     const int my_root = root_token ? root_token[b] : 0;
+    const float u_draw = u_next[b];
+    RD_TR(0);
 
-    // log-sum-exp of every valid row from its chunk partials, in chunk order
+    // ---- every workgroup of the sequence: log-sum-exps, rejection tests, best candidate -------------------
     for (int r = tid; r < N; r += kSelThreads) {
         float lp = 0.f, lq = 0.f;
         if (r < P) {
@@ -164,7 +212,7 @@ __global__ __launch_bounds__(kSelThreads) void rd_accept_sample_kernel(
             float mp = -INFINITY, mq = -INFINITY;
             for (int c = 0; c < chunks; ++c) { mp = fmaxf(mp, pr[c].x); mq = fmaxf(mq, pr[c].z); }
             float sp = 0.f, sq = 0.f;
-            for (int c = 0; c < chunks; ++c) {
+            for (int c = 0; c < chunks; ++c) {              // in chunk order: the same bits in every workgroup
                 const float4 v = pr[c];
                 sp += v.y * __expf(v.x - mp);
                 sq += v.w * __expf(v.z - mq);
@@ -178,6 +226,7 @@ __global__ __launch_bounds__(kSelThreads) void rd_accept_sample_kernel(
     }
     if (tid == 0) { s_best = -1; s_pick = 0x7fffffff; s_lastpos = -1; }
     __syncthreads();
+    RD_TR(1);
 
     // one thread per candidate token: the rejection test of token (w, j), j >= 1
     for (int e = tid; e < N; e += kSelThreads) {
@@ -200,22 +249,26 @@ __global__ __launch_bounds__(kSelThreads) void rd_accept_sample_kernel(
         s_ok[e] = ok ? 1 : 0;
     }
     __syncthreads();
+    RD_TR(2);
 
     // one thread per candidate: length of the accepted prefix; best = longest, then smallest index
-    static_assert(RD_MAX_W <= 256, "candidate index in 8 bits");
+    static_assert(RD_MAX_W <= kSelThreads && RD_MAX_W <= 256, "one thread per candidate, index in 8 bits");
     if (tid < W) {
         int len = 0;
         while (len < L && s_ok[tid * L + len]) ++len;
-        n_accept[(size_t)b * W + tid] = len;
+        if (chunk == 0) n_accept[(size_t)b * W + tid] = len;
         atomicMax(&s_best, (len << 8) | (255 - tid));
     }
     __syncthreads();
+    RD_TR(3);
     const int key = s_best;
     const int bl = key >> 8, bw = 255 - (key & 255);
-    for (int t = tid; t < L; t += kSelThreads) accepted_idx[(size_t)b * L + t] = (t < bl) ? s_slot[bw * L + t] : -1;
-    if (tid == 0) { best_beam[b] = bw; best_len[b] = bl; }
+    if (chunk == 0) {
+        for (int t = tid; t < L; t += kSelThreads) accepted_idx[(size_t)b * L + t] = (t < bl) ? s_slot[bw * L + t] : -1;
+        if (tid == 0) { best_beam[b] = bw; best_len[b] = bl; }
+    }
     if (bl == 0) {                                          // the first token was refuted: nothing to draw
-        if (tid == 0) next_token[b] = my_root;
+        if (chunk == 0 && tid == 0) next_token[b] = my_root;
         return;
     }
 
@@ -224,63 +277,72 @@ __global__ __launch_bounds__(kSelThreads) void rd_accept_sample_kernel(
     const float *zp = logits + ((size_t)b * N + s) * V;
     const float *zq = draft_logits + ((size_t)b * N + s) * V;       // not read when the candidate was accepted whole
     const float lse_p = s_lse_p[s], lse_q = s_lse_q[s];
-    const bool vec = (V & 3) == 0;
-    const int n_chunks = (V + kSelChunk - 1) / kSelChunk;
+    const float4 *prow = part + ((size_t)b * N + s) * chunks;
     bool residual = bl < L;
-    float total = 0.f;
-    for (int attempt = 0; attempt < 2; ++attempt) {
-        int lastpos = -1;
-        for (int i = 0; i < n_chunks; ++i) {
-            const int v = i * kSelChunk + tid * 4;
-            const float4 a = load4(zp, v, V, vec);
-            const float4 q = residual ? load4(zq, v, V, vec) : make_float4(0.f, 0.f, 0.f, 0.f);
-            const float w0 = weight(a.x, q.x, inv_t, lse_p, lse_q, residual), w1 = weight(a.y, q.y, inv_t, lse_p, lse_q, residual);
-            const float w2 = weight(a.z, q.z, inv_t, lse_p, lse_q, residual), w3 = weight(a.w, q.w, inv_t, lse_p, lse_q, residual);
-            if (w3 > 0.f) lastpos = v + 3; else if (w2 > 0.f) lastpos = v + 2; else if (w1 > 0.f) lastpos = v + 1; else if (w0 > 0.f) lastpos = v;
-            float chunk_total;
-            block_exclusive_scan(((w0 + w1) + w2) + w3, s_wave, chunk_total);
-            if (tid == 0) s_chunk_total[i] = chunk_total;
+    float w[kSelPer];
+    if (residual) {
+        // this workgroup's chunk of the residual: total -> workspace, then find out who is last
+        float t = chunk_weights<VEC>(zp, zq, chunk, V, inv_t, lse_p, lse_q, true, w);
+        for (int off = 32; off > 0; off >>= 1) t += __shfl_xor(t, off, 64);
+        if (lane == 0) s_wave[wave] = t;
+        __syncthreads();
+        if (tid == 0) {
+            st_dev(chunk_totals + (size_t)b * chunks + chunk, (s_wave[0] + s_wave[1]) + (s_wave[2] + s_wave[3]));
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");          // the total is visible before the arrival
+            const uint32_t prev = __hip_atomic_fetch_add(counters + b, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_last = (prev + 1u == (uint32_t)chunks) ? 1u : 0u;
         }
-        if (lastpos >= 0) atomicMax(&s_lastpos, lastpos);
         __syncthreads();
-        total = 0.f;
-        for (int i = 0; i < n_chunks; ++i) total += s_chunk_total[i];
-        if (total > 0.f || !residual) break;
-        residual = false;                                   // p == q everywhere: draw from p
+        if (!s_last) return;
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        if (tid == 0) counters[b] = 0;                      // ready for the next call
+        for (int i = tid; i < chunks; i += kSelThreads) s_total[i] = ld_dev(chunk_totals + (size_t)b * chunks + i);
         __syncthreads();
-        if (tid == 0) s_lastpos = -1;
+        float total = 0.f;
+        for (int i = 0; i < chunks; ++i) total += s_total[i];
+        if (!(total > 0.f)) residual = false;               // p == q everywhere: draw from p
         __syncthreads();
+    } else if (chunk != 0) {
+        return;
     }
-    const float target = u_next[b] * total;
-    // the chunk in which the running total crosses the target
-    int ci = -1;
-    float base = 0.f;
-    for (int i = 0; i < n_chunks; ++i) {
-        const float next = base + s_chunk_total[i];
-        if (target < next) { ci = i; break; }
-        base = next;
+    RD_TR(4);
+    if (!residual)                                          // chunk totals of p from launch 1's partials
+        for (int i = tid; i < chunks; i += kSelThreads) s_total[i] = prow[i].y * __expf(prow[i].x - lse_p);
+    __syncthreads();
+    float total = 0.f;
+    for (int i = 0; i < chunks; ++i) total += s_total[i];
+    const float target = u_draw * total;
+    // the chunk in which the running total crosses the target; if rounding leaves none, the last chunk
+    // that holds any weight
+    int ci = -1, lastc = 0;
+    float base = 0.f, run = 0.f;
+    for (int i = 0; i < chunks; ++i) {
+        if (s_total[i] > 0.f) lastc = i;
+        const float next = run + s_total[i];
+        if (ci < 0 && target < next) { ci = i; base = run; }
+        run = next;
     }
-    if (ci >= 0) {
-        const int v = ci * kSelChunk + tid * 4;
-        const float4 a = load4(zp, v, V, vec);
-        const float4 q = residual ? load4(zq, v, V, vec) : make_float4(0.f, 0.f, 0.f, 0.f);
-        const float w0 = weight(a.x, q.x, inv_t, lse_p, lse_q, residual), w1 = weight(a.y, q.y, inv_t, lse_p, lse_q, residual);
-        const float w2 = weight(a.z, q.z, inv_t, lse_p, lse_q, residual), w3 = weight(a.w, q.w, inv_t, lse_p, lse_q, residual);
-        float chunk_total;
-        const float excl = base + block_exclusive_scan(((w0 + w1) + w2) + w3, s_wave, chunk_total);
-        const float c0 = excl + w0, c1 = c0 + w1, c2 = c1 + w2, c3 = c2 + w3;
-        int pick = 0x7fffffff, lastc = -1;
-        if (w3 > 0.f) { lastc = v + 3; if (c3 > target) pick = v + 3; }
-        if (w2 > 0.f) { lastc = max(lastc, v + 2); if (c2 > target) pick = v + 2; }
-        if (w1 > 0.f) { lastc = max(lastc, v + 1); if (c1 > target) pick = v + 1; }
-        if (w0 > 0.f) { lastc = max(lastc, v); if (c0 > target) pick = v; }
-        __syncthreads();
-        if (tid == 0) s_lastpos = -1;                       // now: last positive weight of this chunk
-        __syncthreads();
-        if (pick != 0x7fffffff) atomicMin(&s_pick, pick);
-        if (lastc >= 0) atomicMax(&s_lastpos, lastc);
-        __syncthreads();
+    if (ci < 0) { ci = lastc; base = 0.f; }
+    // cumulative weights inside the chunk, in token order.  The scan sums in another order than the
+    // chunk totals did, so its last value may fall short of the target by rounding: then the chunk's
+    // last token of positive weight is the one.
+    const float tsum = chunk_weights<VEC>(zp, zq, ci, V, inv_t, lse_p, lse_q, residual, w);
+    float chunk_total;
+    float cum = base + block_exclusive_scan(tsum, s_wave, chunk_total);
+    const int v0 = ci * kSelChunk + tid * kSelPer;
+    int pick = 0x7fffffff, lastpos = -1;
+#pragma unroll
+    for (int k = 0; k < kSelPer; ++k) {
+        cum += w[k];
+        if (w[k] > 0.f) {
+            lastpos = v0 + k;
+            if (pick == 0x7fffffff && cum > target) pick = v0 + k;
+        }
     }
+    if (pick != 0x7fffffff) atomicMin(&s_pick, pick);
+    if (lastpos >= 0) atomicMax(&s_lastpos, lastpos);
+    __syncthreads();
+    RD_TR(5);
     if (tid == 0) {
         int tok = s_pick;
         if (tok == 0x7fffffff) tok = s_lastpos;             // rounding left no crossing: the last token of positive weight
@@ -291,14 +353,18 @@ __global__ __launch_bounds__(kSelThreads) void rd_accept_sample_kernel(
 
 struct SamplePlan {
     int chunks;
+    size_t totals_off, part_off;         // byte offsets in the workspace (arrival counters at 0)
     size_t total_bytes;
 };
 
 SamplePlan sample_plan(int B, int N, int V)
 {
     SamplePlan p;
+    auto up = [](size_t x) { return (x + 255) / 256 * 256; };
     p.chunks = (V + kLseChunk - 1) / kLseChunk;
-    p.total_bytes = ((size_t)B * N * p.chunks * sizeof(float4) + 255) / 256 * 256;
+    p.totals_off = up((size_t)B * sizeof(uint32_t));
+    p.part_off = p.totals_off + up((size_t)B * p.chunks * sizeof(float));
+    p.total_bytes = p.part_off + up((size_t)B * N * p.chunks * sizeof(float4));
     return p;
 }
 
@@ -328,14 +394,19 @@ extern "C" int rd_accept_sample(const float *logits, const float *draft_logits, 
     const int N = W * L;
     const SamplePlan plan = sample_plan(B, N, V);
     if (!workspace || !rd_aligned(workspace, 256) || workspace_bytes < plan.total_bytes) return RD_ERR_WORKSPACE;
-    float4 *part = static_cast<float4 *>(workspace);
+    unsigned char *ws = static_cast<unsigned char *>(workspace);
+    uint32_t *counters = reinterpret_cast<uint32_t *>(ws);
+    float *chunk_totals = reinterpret_cast<float *>(ws + plan.totals_off);
+    float4 *part = reinterpret_cast<float4 *>(ws + plan.part_off);
     const float inv_t = 1.0f / temperature;
     hipStream_t s = (hipStream_t)stream;
-    hipLaunchKernelGGL(rd_lse_chunk_kernel, dim3(plan.chunks, N, B), dim3(kLseThreads), 0, s, logits, draft_logits,
-                       unpack_index, n_packed, W, L, V, plan.chunks, inv_t, part);
+    const bool vec = (V & 3) == 0;                          // rows stay 16-byte aligned
+    hipLaunchKernelGGL(vec ? rd_lse_chunk_kernel<true> : rd_lse_chunk_kernel<false>, dim3(plan.chunks, N, B),
+                       dim3(kLseThreads), 0, s, logits, draft_logits, unpack_index, n_packed, W, L, V, plan.chunks, inv_t, part);
     if (rd_check_launch() != RD_OK) return RD_ERR_HIP;
-    hipLaunchKernelGGL(rd_accept_sample_kernel, dim3(B), dim3(kSelThreads), 0, s, logits, draft_logits, beams,
-                       unpack_index, n_packed, root_token, u_accept, u_next, W, L, V, plan.chunks, inv_t, part,
-                       n_accept, best_beam, best_len, next_token, accepted_idx);
+    hipLaunchKernelGGL(vec ? rd_accept_sample_kernel<true> : rd_accept_sample_kernel<false>, dim3(plan.chunks, B),
+                       dim3(kSelThreads), 0, s, logits, draft_logits, beams, unpack_index, n_packed, root_token, u_accept,
+                       u_next, W, L, V, plan.chunks, inv_t, part, chunk_totals, counters, n_accept, best_beam, best_len,
+                       next_token, accepted_idx);
     return rd_check_launch();
 }

@@ -87,7 +87,7 @@ def check(rd, c, temperature, root=None, what=""):
 @pytest.mark.parametrize("B,W,L,V,t", [(1, 4, 4, 1000, 1.0), (3, 8, 5, 4096, 0.7), (2, 8, 5, 1037, 1.3),
                                        (5, 3, 6, 130, 1.0), (4, 16, 5, 9001, 0.9), (2, 1, 5, 5000, 1.0),
                                        (6, 5, 1, 777, 1.0), (2, 70, 5, 3000, 1.1), (1, 128, 3, 2048, 0.8),
-                                       (40, 6, 4, 517, 1.0)])
+                                       (40, 6, 4, 517, 1.0), (2, 4, 3, 40004, 1.0), (1, 3, 3, 70001, 0.8)])
 def test_accept_sample_shapes(rd, B, W, L, V, t):
     announce(f"accept_sample B={B} W={W} L={L} V={V} t={t}")
     c = make_case(B, W, L, V, seed=B + W + V, share="high" if W > 8 else "uniform")
@@ -137,13 +137,15 @@ def test_extreme_uniform_numbers_and_repeat_calls(rd):
     c["u_next"][4:] = np.float32(1.0 - 2.0 ** -24)
     ref, got = check(rd, c, 1.0, what="extremes")
     d = c["d"]
-    ws = torch.empty(rd.rd_accept_sample_workspace(B, W, L, V), dtype=torch.uint8, device="cuda")
+    ws = torch.zeros(rd.rd_accept_sample_workspace(B, W, L, V), dtype=torch.uint8, device="cuda")
     args = (dev(c["logits"]), dev(c["draft"]), dev(c["beams"]), dev(d["unpack_index"]), dev(d["n_packed"]),
             dev(c["u_accept"]), dev(c["u_next"]), 1.0)
     a = {k: host(v) for k, v in rd.rd_accept_sample(*args, workspace=ws).items()}
     b = {k: host(v) for k, v in rd.rd_accept_sample(*args, workspace=ws).items()}
     for k in a:
         assert np.array_equal(a[k], b[k]) and np.array_equal(a[k], got[k]), k
+    torch.cuda.synchronize()
+    assert int(ws[:256].view(torch.int32).abs().sum()) == 0        # the arrival counters are left at zero
 
 
 def test_sampled_tokens_follow_the_llm_distribution(rd):
