@@ -176,16 +176,25 @@ def accept(beams, unpack_index, argmax_in, root_token=None) -> dict:
 
 
 def accept_sample(logits, draft_logits, beams, unpack_index, u_accept, u_next, temperature: float,
-                  root_token=None, diagnostics: bool = False) -> dict:
+                  root_token=None, diagnostics: bool = False, step_row=None) -> dict:
     """Acceptance by rejection sampling (Sec. 3.4's other selection mode).  logits, draft_logits float32
     [B,N,V]; u_accept float32 [B,N] (one uniform number per packed slot); u_next float32 [B].  With
-    `diagnostics`, also accept_ratio float64 [B,W,L] and next_weights float64 [B,V]."""
+    `step_row` int32 [B,W,L-1], draft_logits is [L-1,rows,V] as the beam search recorded it
+    (oracle.draft(..., steps=True)).  With `diagnostics`, also accept_ratio float64 [B,W,L] and
+    next_weights float64 [B,V]."""
     logits = np.ascontiguousarray(logits, dtype=np.float32)
     draft_logits = np.ascontiguousarray(draft_logits, dtype=np.float32)
     beams, unpack_index = _i32(beams), _i32(unpack_index)
     B, W, L = beams.shape
     V = logits.shape[2]
-    assert logits.shape == (B, W * L, V) and draft_logits.shape == logits.shape
+    assert logits.shape == (B, W * L, V)
+    rows_per_step = 0
+    if step_row is None:
+        assert draft_logits.shape == logits.shape
+    else:                                     # draft logits as the beam search recorded them: [L-1, rows, V]
+        step_row = _i32(step_row)
+        rows_per_step = draft_logits.shape[1]
+        assert draft_logits.shape == (L - 1, rows_per_step, V) and step_row.shape == (B, W, L - 1)
     u_accept = np.ascontiguousarray(u_accept, dtype=np.float32)
     u_next = np.ascontiguousarray(u_next, dtype=np.float32)
     assert u_accept.shape == (B, W * L) and u_next.shape == (B,)
@@ -200,9 +209,10 @@ def accept_sample(logits, draft_logits, beams, unpack_index, u_accept, u_next, t
     ratio = np.empty((B, W, L), np.float64) if diagnostics else None
     weights = np.empty((B, V), np.float64) if diagnostics else None
     fn = lib().orc_accept_sample
-    fn.argtypes = [ctypes.c_void_p] * 7 + [ctypes.c_double] + [ctypes.c_int] * 4 + [ctypes.c_void_p] * 7
+    fn.argtypes = ([ctypes.c_void_p] * 3 + [ctypes.c_int] + [ctypes.c_void_p] * 5 + [ctypes.c_double] + [ctypes.c_int] * 4
+                   + [ctypes.c_void_p] * 7)
     fn.restype = None
-    fn(_p(logits), _p(draft_logits), _p(beams), _p(unpack_index), _p(root), _p(u_accept), _p(u_next),
+    fn(_p(logits), _p(draft_logits), _p(step_row), rows_per_step, _p(beams), _p(unpack_index), _p(root), _p(u_accept), _p(u_next),
        float(temperature), B, W, L, V, _p(out["n_accept"]), _p(out["best_beam"]), _p(out["best_len"]),
        _p(out["next_token"]), _p(out["accepted_idx"]), _p(ratio), _p(weights))
     if diagnostics:
@@ -271,19 +281,27 @@ def _draft_args(params, h, Dm):
     return arrs, V, n_mlp
 
 
-def draft(params: dict, h, last_token, W: int, L: int) -> dict:
+def draft(params: dict, h, last_token, W: int, L: int, steps: bool = False) -> dict:
     """Draft model + beam search (Sec. 3.1, 3.2).  params: bf16 bit patterns emb [V,Dm], rnn_u, rnn_w
     [Dm,Dm], mlp_w [K,2Dm,2Dm], head_w [V,2Dm]; float32 rnn_b [Dm], mlp_b [K,2Dm].  h bf16 bits [B,Dm],
-    last_token int32 [B].  Returns beams int32 [B,W,L] (position 0 = last_token) and beam_logp [B,W]."""
+    last_token int32 [B].  Returns beams int32 [B,W,L] (position 0 = last_token) and beam_logp [B,W];
+    with `steps` also step_logp float32 [L-1,B*W,V] (the log-probabilities computed during the search) and
+    step_row int32 [B,W,L-1] (the row of step t-1 behind token t of final candidate w)."""
     B, Dm = np.asarray(h).shape
     a, V, n_mlp = _draft_args(params, h, Dm)
     last_token = _i32(last_token)
     assert 1 <= W <= V and L >= 1
     beams = np.empty((B, W, L), np.int32)
     logp = np.empty((B, W), np.float32)
+    step_logp = np.zeros((max(L - 1, 0), B * W, V), np.float32) if steps else None
+    step_row = np.zeros((B, W, max(L - 1, 0)), np.int32) if steps else None
     lib().orc_draft(_p(a["emb"]), _p(a["rnn_u"]), _p(a["rnn_w"]), _p(a["rnn_b"]), _p(a["mlp_w"]), _p(a["mlp_b"]),
-                    n_mlp, _p(a["head_w"]), _p(a["h"]), _p(last_token), B, Dm, V, W, L, _p(beams), _p(logp))
-    return {"beams": beams, "beam_logp": logp}
+                    n_mlp, _p(a["head_w"]), _p(a["h"]), _p(last_token), B, Dm, V, W, L, _p(beams), _p(logp),
+                    _p(step_logp), _p(step_row))
+    out = {"beams": beams, "beam_logp": logp}
+    if steps:
+        out["step_logp"], out["step_row"] = step_logp, step_row
+    return out
 
 
 def draft_path_logp(params: dict, h, paths) -> np.ndarray:

@@ -589,9 +589,17 @@ void orc_draft(const uint16_t *emb, const uint16_t *rnn_u, const uint16_t *rnn_w
                const uint16_t *mlp_w, const float *mlp_b, int n_mlp, const uint16_t *head_w,
                const uint16_t *h /*[B][Dm] bf16*/, const int32_t *last_token /*[B]*/,
                int B, int Dm, int V, int W, int L,
-               int32_t *beams /*[B][W][L]*/, float *beam_logp /*[B][W]*/)
+               int32_t *beams /*[B][W][L]*/, float *beam_logp /*[B][W]*/,
+               float *step_logp /*[L-1][B*W][V] or NULL*/, int32_t *step_row /*[B][W][L-1] or NULL*/)
 {
+    /* step_logp: the draft model's log-probabilities as they were computed during the search, row
+     * b*W + w of step t-1 = live candidate w of sequence b at drafted position t (rows of candidates
+     * that were not live, i.e. w >= 1 at the first position, are left untouched).  step_row[b][w][t-1]
+     * = the row of step t-1 that produced token t of final candidate w, so that the draft
+     * distribution behind every token of every candidate can be found without recomputation. */
     const int T = L - 1;
+    int32_t *rows = (int32_t *)malloc(sizeof(int32_t) * (size_t)W * (T > 0 ? T : 1));
+    int32_t *rows2 = (int32_t *)malloc(sizeof(int32_t) * (size_t)W * (T > 0 ? T : 1));
     double *hd = (double *)malloc(sizeof(double) * (size_t)Dm);
     double *s = (double *)malloc(sizeof(double) * (size_t)W * Dm);        /* state per live beam */
     double *s2 = (double *)malloc(sizeof(double) * (size_t)W * Dm);
@@ -611,6 +619,10 @@ void orc_draft(const uint16_t *emb, const uint16_t *rnn_u, const uint16_t *rnn_w
         for (int t = 1; t <= T; ++t) {
             for (int w = 0; w < live; ++w)
                 draft_logp(mlp_w, mlp_b, n_mlp, head_w, s + (size_t)w * Dm, hd, Dm, V, lp + (size_t)w * V);
+            if (step_logp)
+                for (int w = 0; w < live; ++w)
+                    for (int v = 0; v < V; ++v)
+                        step_logp[(((size_t)(t - 1) * B + b) * W + w) * V + v] = (float)lp[(size_t)w * V + v];
             memset(taken, 0, (size_t)live * V);
             for (int r = 0; r < W; ++r) {                 /* the r-th best candidate (beam w, token v) */
                 int bw = -1, bv = -1;
@@ -625,19 +637,24 @@ void orc_draft(const uint16_t *emb, const uint16_t *rnn_u, const uint16_t *rnn_w
                 cum2[r] = best;
                 memcpy(path2 + (size_t)r * L, path + (size_t)bw * L, sizeof(int32_t) * (size_t)t);
                 path2[(size_t)r * L + t] = bv;
+                memcpy(rows2 + (size_t)r * T, rows + (size_t)bw * T, sizeof(int32_t) * (size_t)(t - 1));
+                rows2[(size_t)r * T + t - 1] = b * W + bw;
                 if (t < T) draft_rnn(emb, rnn_u, rnn_w, rnn_b, s + (size_t)bw * Dm, bv, Dm, s2 + (size_t)r * Dm);
             }
             live = W;
             memcpy(cum, cum2, sizeof(double) * (size_t)W);
             memcpy(path, path2, sizeof(int32_t) * (size_t)W * L);
+            memcpy(rows, rows2, sizeof(int32_t) * (size_t)W * T);
             if (t < T) memcpy(s, s2, sizeof(double) * (size_t)W * Dm);
         }
         if (T >= 1)
             for (int w = 0; w < W; ++w) {
                 beam_logp[(size_t)b * W + w] = (float)cum[w];
                 memcpy(beams + ((size_t)b * W + w) * L, path + (size_t)w * L, sizeof(int32_t) * (size_t)L);
+                if (step_row) memcpy(step_row + ((size_t)b * W + w) * T, rows + (size_t)w * T, sizeof(int32_t) * (size_t)T);
             }
     }
+    free(rows); free(rows2);
     free(hd); free(s); free(s2); free(lp); free(cum); free(cum2); free(path); free(path2); free(taken);
 }
 
@@ -708,8 +725,20 @@ static double log_sum_exp(const float *z, int V, double inv_t)
     return m + log(s);
 }
 
-void orc_accept_sample(const float *logits, const float *draft_logits, const int32_t *beams,
-                       const int32_t *unpack_index, const int32_t *root_token,
+/* Where the draft model's logits of the distribution after candidate w's token j live: row
+ * unpack_index[w][j] of the packed layout [B][N][V], or, when the rows recorded during the beam
+ * search are handed over as they are (step layout [L-1][rows_per_step][V], step_row [B][W][L-1]),
+ * row step_row[b][w][j] of step j.                                                          */
+static const float *draft_row_of(const float *draft_logits, const int32_t *step_row, int rows_per_step,
+                                 const int32_t *ui, int b, int w, int j, int W, int L, int V)
+{
+    const int N = W * L;
+    if (step_row == NULL) return draft_logits + ((size_t)b * N + ui[w * L + j]) * V;
+    return draft_logits + ((size_t)j * rows_per_step + step_row[((size_t)b * W + w) * (L - 1) + j]) * V;
+}
+
+void orc_accept_sample(const float *logits, const float *draft_logits, const int32_t *step_row, int rows_per_step,
+                       const int32_t *beams, const int32_t *unpack_index, const int32_t *root_token,
                        const float *u_accept /*[B,N]*/, const float *u_next /*[B]*/, double temperature,
                        int B, int W, int L, int V,
                        int32_t *n_accept, int32_t *best_beam, int32_t *best_len, int32_t *next_token,
@@ -733,7 +762,7 @@ void orc_accept_sample(const float *logits, const float *draft_logits, const int
                 } else {
                     const int s = ui[w * L + j - 1], c = ui[w * L + j], x = beam[w * L + j];
                     const float *zp = logits + ((size_t)b * N + s) * V;
-                    const float *zq = draft_logits + ((size_t)b * N + s) * V;
+                    const float *zq = draft_row_of(draft_logits, step_row, rows_per_step, ui, b, w, j - 1, W, L, V);
                     double ratio = 0.0;                     /* a token outside the vocabulary is rejected */
                     if (x >= 0 && x < V) {
                         const double lp = (double)zp[x] * inv_t - log_sum_exp(zp, V, inv_t);
@@ -760,10 +789,10 @@ void orc_accept_sample(const float *logits, const float *draft_logits, const int
         }
         const int s = ui[bw * L + bl - 1];
         const float *zp = logits + ((size_t)b * N + s) * V;
-        const float *zq = draft_logits + ((size_t)b * N + s) * V;
         const double lse_p = log_sum_exp(zp, V, inv_t);
         double total = 0.0;
         if (bl < L) {                                       /* a rejection: the residual distribution */
+            const float *zq = draft_row_of(draft_logits, step_row, rows_per_step, ui, b, bw, bl - 1, W, L, V);
             const double lse_q = log_sum_exp(zq, V, 1.0);
             for (int v = 0; v < V; ++v) {
                 const double d = exp((double)zp[v] * inv_t - lse_p) - exp((double)zq[v] - lse_q);

@@ -191,3 +191,39 @@ def test_last_position_draft_rows_are_never_read_and_foreign_tokens_are_rejected
     d2 = oracle.dedup(bad, np.full(B, 4, np.int32))
     r = oracle.accept_sample(logits, draft, bad, d2["unpack_index"], np.zeros((B, W * L), np.float32), u_next, 1.0)
     assert (r["n_accept"][:2] == 1).all()
+
+
+def test_step_layout_equals_packed_layout():
+    """Draft logits handed over as the beam search recorded them (one matrix per drafted position plus
+    the row behind every candidate token) must give what the packed layout gives; the packed copy is
+    gathered here with numpy."""
+    rng = np.random.default_rng(12)
+    B, W, L, V, t = 3, 5, 4, 9, 1.2
+    rows = B * W
+    beams = rng.integers(0, 3, (B, W, L)).astype(np.int32)          # tiny alphabet: shared prefixes
+    beams[:, :, 0] = 1
+    d = oracle.dedup(beams, np.full(B, 3, np.int32))
+    # rows: candidates with the same prefix must name the same row (as a beam search guarantees)
+    step_row = np.zeros((B, W, L - 1), np.int32)
+    for b in range(B):
+        for j in range(L - 1):
+            ids = {}
+            for w in range(W):
+                key = tuple(beams[b, w, : j + 1].tolist())
+                ids.setdefault(key, b * W + (len(ids) * 2 + j) % W)
+                step_row[b, w, j] = ids[key]
+            assert len(set(ids.values())) == len(ids)
+    step_logits = rng.standard_normal((L - 1, rows, V)).astype(np.float32)
+    packed = np.full((B, W * L, V), np.nan, np.float32)
+    for b in range(B):
+        for w in range(W):
+            for j in range(L - 1):
+                packed[b, d["unpack_index"][b, w, j]] = step_logits[j, step_row[b, w, j]]
+    logits = rng.standard_normal((B, W * L, V)).astype(np.float32)
+    u_acc, u_next = synth.make_uniforms((B, W * L), 3), synth.make_uniforms((B,), 4)
+    want = oracle.accept_sample(logits, packed, beams, d["unpack_index"], u_acc, u_next, t, diagnostics=True)
+    got = oracle.accept_sample(logits, step_logits, beams, d["unpack_index"], u_acc, u_next, t, diagnostics=True,
+                               step_row=step_row)
+    for k in want:
+        assert np.array_equal(want[k], got[k]), k
+    assert (want["best_len"] < L).any() and (want["best_len"] > 1).any()

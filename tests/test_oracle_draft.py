@@ -168,3 +168,35 @@ def test_zero_mlp_is_the_identity_block():
     order = np.argsort(-lp, kind="stable")
     assert r["beams"][0, :, 1].tolist() == order.tolist()
     assert np.allclose(r["beam_logp"][0], lp[order], atol=1e-5)
+
+
+@pytest.mark.parametrize("seed", [0, 3])
+def test_step_rows_hold_the_distribution_behind_every_candidate_token(seed):
+    """step_row/step_logp: for every final candidate and position, the recorded row must be the draft
+    model's log-probabilities given that candidate's prefix (recomputed here with the numpy model), and
+    candidates that share a prefix must point at the same row."""
+    V, Dm, K, L, W, B = 40, 16, 1, 5, 6, 2
+    p = make_params(V, Dm, K, seed, scale=3.0)
+    h = synth.f32_to_bf16_bits(np.random.default_rng(seed + 30).standard_normal((B, Dm)).astype(np.float32))
+    last = np.array([5, 17], np.int32)
+    r = oracle.draft(p, h, last, W, L, steps=True)
+    plain = oracle.draft(p, h, last, W, L)
+    assert np.array_equal(r["beams"], plain["beams"]) and np.array_equal(r["beam_logp"], plain["beam_logp"])
+    assert r["step_logp"].shape == (L - 1, B * W, V) and r["step_row"].shape == (B, W, L - 1)
+    for b in range(B):
+        m = NumpyDrafter(p, h[b])
+        seen = {}
+        for w in range(W):
+            path = r["beams"][b, w].tolist()
+            s, total = m.start(path[0]), 0.0
+            for j in range(L - 1):
+                row = int(r["step_row"][b, w, j])
+                assert b * W <= row < (b + 1) * W
+                want = m.logp(s)
+                got = r["step_logp"][j, row].astype(np.float64)
+                assert np.abs(got - want).max() < 1e-4
+                assert seen.setdefault((j, tuple(path[: j + 1])), row) == row
+                total += got[path[j + 1]]
+                s = m.step(s, path[j + 1])
+            assert _close(total, float(r["beam_logp"][b, w]))
+        assert (r["step_row"][b, :, 0] == b * W).all()            # one live state at the first position
