@@ -209,6 +209,10 @@ int rd_accept(const float *logits, const int32_t *beams, const int32_t *unpack_i
  * logits, draft_logits : float [B,N,V], 16-byte aligned, free of NaN, at least one finite entry per
  * row that is read.  Rows p >= n_packed[b] are not read; draft_logits rows of slots at the last
  * position (depth L-1) are not read either (the draft model has no distribution there).
+ * draft_step_row : NULL, or int32 [B][W][L-1] = rd_draft's step_row: then draft_logits is rd_draft's
+ * step_logits, float [L-1][draft_rows_per_step][V] (draft_rows_per_step = the B*W of that call), and the
+ * draft distribution after candidate w's token j is row draft_step_row[b][w][j] of matrix j; no copy
+ * into the packed layout is needed.  Row numbers are clamped to the matrix.
  * u_accept : float [B,N] in [0,1);  u_next : float [B] in [0,1);  temperature > 0.
  * beams, unpack_index, n_packed, root_token and the int32 outputs as for rd_accept (no argmax_out).
  * workspace: as for rd_accept (at least rd_accept_sample_workspace(...) bytes, 256-byte aligned, all
@@ -217,8 +221,8 @@ int rd_accept(const float *logits, const int32_t *beams, const int32_t *unpack_i
  */
 size_t rd_accept_sample_workspace(int B, int W, int L, int V);
 
-int rd_accept_sample(const float *logits, const float *draft_logits, const int32_t *beams,
-                     const int32_t *unpack_index, const int32_t *n_packed, const int32_t *root_token,
+int rd_accept_sample(const float *logits, const float *draft_logits, const int32_t *draft_step_row,
+                     int draft_rows_per_step, const int32_t *beams, const int32_t *unpack_index, const int32_t *n_packed, const int32_t *root_token,
                      const float *u_accept, const float *u_next, float temperature,
                      int B, int W, int L, int V,
                      int32_t *n_accept, int32_t *best_beam, int32_t *best_len, int32_t *next_token,
@@ -312,7 +316,13 @@ int rd_commit_paged(const void *k_new, const void *v_new, const int32_t *accepte
  * aligned): emb bf16 [V,Dm]; rnn_u, rnn_w bf16 [Dm,Dm]; rnn_b float [Dm]; mlp_w bf16
  * [n_mlp,2Dm,2Dm]; mlp_b float [n_mlp,2Dm]; head_w bf16 [V,2Dm].
  * h : bf16 [B,Dm];  last_token : int32 [B] (clamped to [0, V-1]);  beams : int32 [B,W,L];
- * beam_logp : float [B,W].  workspace: rd_draft_workspace(...) bytes, 256-byte aligned, no
+ * beam_logp : float [B,W].
+ * step_logits, step_row : both NULL, or the record of the search that rd_accept_sample takes:
+ *   step_logits float [L-1][B*W][V], 16-byte aligned: the output layer's values (softmax of a row = the
+ *   draft distribution) of every live candidate at every drafted position, row b*W + w of matrix t-1
+ *   = live candidate w of sequence b at position t (at position 1 only w = 0 is live; other rows
+ *   of that matrix are not written);
+ *   step_row int32 [B][W][L-1]: the row of matrix t-1 that produced token t of final candidate w.  workspace: rd_draft_workspace(...) bytes, 256-byte aligned, no
  * initial contents required, not shared by concurrent calls.
  * Limits: Dm a multiple of 64; W <= 32, W <= V; B*W <= 512; V <= 32768; L <= 384.
  * The call enqueues 3 + n_mlp launches per drafted position (4 + n_mlp after the first) while
@@ -331,6 +341,7 @@ size_t rd_draft_workspace(int B, int W, int L, int Dm, int V);
 
 int rd_draft(const rd_draft_params *p, const void *h, const int32_t *last_token,
              int B, int W, int L, int32_t *beams, float *beam_logp,
+             float *step_logits, int32_t *step_row,
              void *workspace, size_t workspace_bytes, void *stream);
 
 #ifdef __cplusplus

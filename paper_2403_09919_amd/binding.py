@@ -39,10 +39,10 @@ EXPORTS = {
     "rd_accept_workspace": (_sz, [_i, _i, _i, _i]),
     "rd_accept": (_i, [_vp] * 5 + [_i, _i, _i, _i] + [_vp] * 6 + [_vp, _sz, _vp]),
     "rd_accept_sample_workspace": (_sz, [_i, _i, _i, _i]),
-    "rd_accept_sample": (_i, [_vp] * 8 + [_f, _i, _i, _i, _i] + [_vp] * 5 + [_vp, _sz, _vp]),
+    "rd_accept_sample": (_i, [_vp] * 3 + [_i] + [_vp] * 6 + [_f, _i, _i, _i, _i] + [_vp] * 5 + [_vp, _sz, _vp]),
     "rd_commit": (_i, [_vp] * 5 + [_i] * 7 + [_vp] * 4 + [_vp, _i, _vp, _vp]),
     "rd_draft_workspace": (_sz, [_i, _i, _i, _i, _i]),
-    "rd_draft": (_i, [_vp, _vp, _vp, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]),
+    "rd_draft": (_i, [_vp, _vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "rd_rope": (_i, [_vp] * 6 + [_i] * 6 + [_vp]),
     "rd_commit_paged": (_i, [_vp] * 5 + [_i] * 6 + [_vp] * 3 + [_i, _i, _i] + [_vp, _vp] + [_vp, _i, _vp, _vp]),
 }
@@ -247,12 +247,18 @@ def rd_accept_sample_workspace(B: int, W: int, L: int, V: int) -> int:
 
 def rd_accept_sample(logits, draft_logits, beams, unpack_index, n_packed, u_accept, u_next, temperature: float,
                      root_token: Optional[torch.Tensor] = None, out: Optional[dict] = None,
-                     workspace: Optional[torch.Tensor] = None) -> dict:
+                     workspace: Optional[torch.Tensor] = None, step_row: Optional[torch.Tensor] = None) -> dict:
     """Rejection-sampling acceptance: logits, draft_logits float32 [B,N,V]; u_accept float32 [B,N];
-    u_next float32 [B] -> dict(n_accept, best_beam, best_len, next_token, accepted_idx)."""
+    u_next float32 [B] -> dict(n_accept, best_beam, best_len, next_token, accepted_idx).  With
+    `step_row` (rd_draft's), draft_logits is rd_draft's step_logits [L-1, rows, V]."""
     B, W, L = beams.shape
     N = W * L
     V = logits.shape[2]
+    rows = 0
+    draft_shape = (B, N, V)
+    if step_row is not None:
+        rows = draft_logits.shape[1]
+        draft_shape = (L - 1, rows, V)
     dev = logits.device
     i32, f32 = torch.int32, torch.float32
     if out is None:
@@ -266,7 +272,8 @@ def rd_accept_sample(logits, draft_logits, beams, unpack_index, n_packed, u_acce
     if workspace is None:
         workspace = new_workspace(rd_accept_sample_workspace(B, W, L, V), dev)
     code = _lib.rd_accept_sample(
-        _ptr(logits, f32, (B, N, V), "logits"), _ptr(draft_logits, f32, (B, N, V), "draft_logits"),
+        _ptr(logits, f32, (B, N, V), "logits"), _ptr(draft_logits, f32, draft_shape, "draft_logits"),
+        _ptr(step_row, i32, (B, W, L - 1), "step_row"), rows,
         _ptr(beams, i32, (B, W, L), "beams"), _ptr(unpack_index, i32, (B, W, L), "unpack_index"),
         _ptr(n_packed, i32, (B,), "n_packed"), _ptr(root_token, i32, (B,), "root_token"),
         _ptr(u_accept, f32, (B, N), "u_accept"), _ptr(u_next, f32, (B,), "u_next"), float(temperature),
@@ -362,10 +369,12 @@ def rd_draft_workspace(B: int, W: int, L: int, Dm: int, V: int) -> int:
 
 
 def rd_draft(params: dict, h, last_token, W: int, L: int, out: Optional[dict] = None,
-             workspace: Optional[torch.Tensor] = None) -> dict:
+             workspace: Optional[torch.Tensor] = None, steps: bool = False) -> dict:
     """Draft model + beam search (see include/rd.h, rd_draft).  params: device tensors emb [V,Dm],
     rnn_u, rnn_w [Dm,Dm], mlp_w [K,2Dm,2Dm], head_w [V,2Dm] (bfloat16), rnn_b [Dm], mlp_b [K,2Dm]
-    (float32); h bfloat16 [B,Dm]; last_token int32 [B] -> dict(beams int32 [B,W,L], beam_logp [B,W])."""
+    (float32); h bfloat16 [B,Dm]; last_token int32 [B] -> dict(beams int32 [B,W,L], beam_logp [B,W]);
+    with `steps` (or an `out` that holds them) also step_logits float32 [L-1,B*W,V] and step_row int32
+    [B,W,L-1], the record of the search that rd_accept_sample takes."""
     bf = torch.bfloat16
     V, Dm = params["emb"].shape
     K = params["mlp_w"].shape[0]
@@ -380,11 +389,17 @@ def rd_draft(params: dict, h, last_token, W: int, L: int, out: Optional[dict] = 
     if out is None:
         out = dict(beams=torch.empty((B, W, L), dtype=torch.int32, device=dev),
                    beam_logp=torch.empty((B, W), dtype=torch.float32, device=dev))
+        if steps:
+            out["step_logits"] = torch.empty((max(L - 1, 0), B * W, V), dtype=torch.float32, device=dev)
+            out["step_row"] = torch.empty((B, W, max(L - 1, 0)), dtype=torch.int32, device=dev)
     if workspace is None:
         workspace = torch.empty(max(rd_draft_workspace(B, W, L, Dm, V), 256), dtype=torch.uint8, device=dev)
+    sl, sr = out.get("step_logits"), out.get("step_row")
     code = _lib.rd_draft(ctypes.byref(p), _ptr(h, bf, (B, Dm), "h"), _ptr(last_token, torch.int32, (B,), "last_token"),
                          B, W, L, _ptr(out["beams"], torch.int32, (B, W, L), "beams"),
                          _ptr(out["beam_logp"], torch.float32, (B, W), "beam_logp"),
+                         _ptr(sl, torch.float32, (max(L - 1, 0), B * W, V), "step_logits"),
+                         _ptr(sr, torch.int32, (B, W, max(L - 1, 0)), "step_row"),
                          _ptr(workspace, torch.uint8, None, "workspace"), workspace.numel(), _stream())
     _check(code, "rd_draft")
     return out

@@ -85,31 +85,48 @@ __device__ __forceinline__ float2 chunk_max_sum(const float4 (&x)[4], float scal
     return make_float2(m, s);
 }
 
+// The draft model's logits of the distribution after candidate w's token j (which sits in packed
+// slot `slot`): row `slot` of the packed layout [B][N][V], or, in the layout the beam search records
+// ([L-1][rows_per_step][V] plus step_row [B][W][L-1]), row step_row[b][w][j] of step j.
+__device__ __forceinline__ const float *draft_row_ptr(const float *draft_logits, const int32_t *step_row, int rows_per_step,
+                                                      int b, int w, int j, int slot, int W, int L, int V)
+{
+    if (step_row == nullptr) return draft_logits + ((size_t)b * W * L + slot) * V;
+    const int r = min(max(step_row[((size_t)b * W + w) * (L - 1) + j], 0), rows_per_step - 1);
+    return draft_logits + ((size_t)j * rows_per_step + r) * V;
+}
+
 template <bool VEC>
 __global__ __launch_bounds__(kLseThreads) void rd_lse_chunk_kernel(
-    const float *__restrict__ logits, const float *__restrict__ draft_logits, const int32_t *__restrict__ unpack_index,
+    const float *__restrict__ logits, const float *__restrict__ draft_logits, const int32_t *__restrict__ step_row,
+    int rows_per_step, const int32_t *__restrict__ unpack_index,
     const int32_t *__restrict__ n_packed, int W, int L, int V, int chunks, float inv_t, float4 *__restrict__ part)
 {
     __shared__ float s_red[kLseThreads / 64];
-    __shared__ int s_leaf;
+    __shared__ int s_owner;
     const int tid = threadIdx.x;
     const int chunk = blockIdx.x, p = blockIdx.y, b = blockIdx.z;
     const int N = W * L;
     int P = n_packed[b];
     P = P < 1 ? 1 : (P > N ? N : P);
     if (p >= P) return;
-    if (tid == 0) s_leaf = 0;
+    // which (candidate, position) this slot holds: the first entry of unpack_index that names it
+    if (tid == 0) s_owner = 0x7fffffff;
     __syncthreads();
-    if (tid < W && unpack_index[(size_t)b * N + tid * L + (L - 1)] == p) s_leaf = 1;   // a slot at the last position
+    for (int e = tid; e < N; e += kLseThreads)
+        if (unpack_index[(size_t)b * N + e] == p) atomicMin(&s_owner, e);
     const size_t rowid = (size_t)b * N + p;
-    const float *zp = logits + rowid * V, *zq = draft_logits + rowid * V;
+    const float *zp = logits + rowid * V;
     const int v0 = chunk * kLseChunk;
     float4 xp[4], xq[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) xp[u] = load4<VEC>(zp, v0 + (u * kLseThreads + tid) * 4, V);
-    const float2 a = chunk_max_sum(xp, inv_t, s_red);       // (its barriers also publish s_leaf)
+    const float2 a = chunk_max_sum(xp, inv_t, s_red);       // (its barriers also publish s_owner)
     float2 c = make_float2(0.f, 1.f);
-    if (s_leaf == 0) {                                      // uniform: the draft half of the row exists
+    const int owner = s_owner;
+    const int ow = owner / L, oj = owner - ow * L;
+    if (owner != 0x7fffffff && oj < L - 1) {                // uniform: not at the last position, a draft row exists
+        const float *zq = draft_row_ptr(draft_logits, step_row, rows_per_step, b, ow, oj, p, W, L, V);
 #pragma unroll
         for (int u = 0; u < 4; ++u) xq[u] = load4<VEC>(zq, v0 + (u * kLseThreads + tid) * 4, V);
         c = chunk_max_sum(xq, 1.0f, s_red);
@@ -179,7 +196,8 @@ __device__ __forceinline__ float ld_dev(const float *p) { return __hip_atomic_lo
 
 template <bool VEC>
 __global__ __launch_bounds__(kSelThreads) void rd_accept_sample_kernel(
-    const float *__restrict__ logits, const float *__restrict__ draft_logits, const int32_t *__restrict__ beams,
+    const float *__restrict__ logits, const float *__restrict__ draft_logits, const int32_t *__restrict__ step_row,
+    int rows_per_step, const int32_t *__restrict__ beams,
     const int32_t *__restrict__ unpack_index, const int32_t *__restrict__ n_packed,
     const int32_t *__restrict__ root_token, const float *__restrict__ u_accept, const float *__restrict__ u_next,
     int W, int L, int V, int chunks, float inv_t, const float4 *__restrict__ part,
@@ -239,9 +257,9 @@ __global__ __launch_bounds__(kSelThreads) void rd_accept_sample_kernel(
             ok = false;
             if (x >= 0 && x < V) {
                 const int s = s_slot[e - 1], c = s_slot[e];
-                const size_t row = ((size_t)b * N + s) * V;
-                const float lp = logits[row + x] * inv_t - s_lse_p[s];
-                const float lq = draft_logits[row + x] - s_lse_q[s];
+                const float *zq_row = draft_row_ptr(draft_logits, step_row, rows_per_step, b, e / L, j - 1, s, W, L, V);
+                const float lp = logits[((size_t)b * N + s) * V + x] * inv_t - s_lse_p[s];
+                const float lq = zq_row[x] - s_lse_q[s];
                 const float ratio = fminf(__expf(lp - lq), 1.0f);
                 ok = u_accept[(size_t)b * N + c] < ratio;
             }
@@ -275,7 +293,8 @@ __global__ __launch_bounds__(kSelThreads) void rd_accept_sample_kernel(
     // ---- the next token: inverse CDF of p (whole candidate accepted) or of the residual -------------------
     const int s = s_slot[bw * L + bl - 1];
     const float *zp = logits + ((size_t)b * N + s) * V;
-    const float *zq = draft_logits + ((size_t)b * N + s) * V;       // not read when the candidate was accepted whole
+    // (not read when the candidate was accepted whole)
+    const float *zq = bl < L ? draft_row_ptr(draft_logits, step_row, rows_per_step, b, bw, bl - 1, s, W, L, V) : zp;
     const float lse_p = s_lse_p[s], lse_q = s_lse_q[s];
     const float4 *prow = part + ((size_t)b * N + s) * chunks;
     bool residual = bl < L;
@@ -376,8 +395,8 @@ extern "C" size_t rd_accept_sample_workspace(int B, int W, int L, int V)
     return sample_plan(B, W * L, V).total_bytes;
 }
 
-extern "C" int rd_accept_sample(const float *logits, const float *draft_logits, const int32_t *beams,
-                                const int32_t *unpack_index, const int32_t *n_packed, const int32_t *root_token,
+extern "C" int rd_accept_sample(const float *logits, const float *draft_logits, const int32_t *draft_step_row,
+                                int draft_rows_per_step, const int32_t *beams, const int32_t *unpack_index, const int32_t *n_packed, const int32_t *root_token,
                                 const float *u_accept, const float *u_next, float temperature,
                                 int B, int W, int L, int V,
                                 int32_t *n_accept, int32_t *best_beam, int32_t *best_len, int32_t *next_token,
@@ -391,6 +410,7 @@ extern "C" int rd_accept_sample(const float *logits, const float *draft_logits, 
         !best_beam || !best_len || !next_token || !accepted_idx)
         return RD_ERR_INVALID_ARG;
     if (!rd_aligned(logits, 16) || !rd_aligned(draft_logits, 16)) return RD_ERR_INVALID_ARG;
+    if (draft_step_row != nullptr && draft_rows_per_step <= 0) return RD_ERR_INVALID_ARG;
     const int N = W * L;
     const SamplePlan plan = sample_plan(B, N, V);
     if (!workspace || !rd_aligned(workspace, 256) || workspace_bytes < plan.total_bytes) return RD_ERR_WORKSPACE;
@@ -402,10 +422,12 @@ extern "C" int rd_accept_sample(const float *logits, const float *draft_logits, 
     hipStream_t s = (hipStream_t)stream;
     const bool vec = (V & 3) == 0;                          // rows stay 16-byte aligned
     hipLaunchKernelGGL(vec ? rd_lse_chunk_kernel<true> : rd_lse_chunk_kernel<false>, dim3(plan.chunks, N, B),
-                       dim3(kLseThreads), 0, s, logits, draft_logits, unpack_index, n_packed, W, L, V, plan.chunks, inv_t, part);
+                       dim3(kLseThreads), 0, s, logits, draft_logits, draft_step_row, draft_rows_per_step, unpack_index, n_packed, W, L, V,
+                       plan.chunks, inv_t, part);
     if (rd_check_launch() != RD_OK) return RD_ERR_HIP;
     hipLaunchKernelGGL(vec ? rd_accept_sample_kernel<true> : rd_accept_sample_kernel<false>, dim3(plan.chunks, B),
-                       dim3(kSelThreads), 0, s, logits, draft_logits, beams, unpack_index, n_packed, root_token, u_accept,
+                       dim3(kSelThreads), 0, s, logits, draft_logits, draft_step_row, draft_rows_per_step, beams, unpack_index, n_packed,
+                       root_token, u_accept,
                        u_next, W, L, V, plan.chunks, inv_t, part, chunk_totals, counters, n_accept, best_beam, best_len,
                        next_token, accepted_idx);
     return rd_check_launch();

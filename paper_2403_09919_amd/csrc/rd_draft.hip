@@ -453,6 +453,21 @@ __global__ __launch_bounds__(256) void rd_beam_step_kernel(
     }
 }
 
+// For every final candidate, the row of each position's logit matrix that produced its token there:
+// follow the parent rows back from the last position.  One thread per candidate.
+__global__ void rd_draft_rows_kernel(const int32_t *__restrict__ parents /*[T][M]*/, int M, int W, int T,
+                                     int32_t *__restrict__ step_row /*[B][W][T]*/)
+{
+    const int m = blockIdx.x * blockDim.x + threadIdx.x;
+    if (m >= M) return;
+    int r = m;
+    for (int t = T; t >= 1; --t) {
+        r = parents[(size_t)(t - 1) * M + r];
+        r = r < 0 ? 0 : (r > M - 1 ? M - 1 : r);
+        step_row[(size_t)m * T + t - 1] = r;
+    }
+}
+
 struct Plan {
     size_t x_f32[3], x_bf[3], s_bf[2], logits, part_max, part_sum, part_cv, part_ci, paths[2], cum[2], parent, tok, total;
 };
@@ -471,7 +486,7 @@ Plan draft_plan(int B, int W, int L, int Dm, int V)
     p.part_cv = take(M * kMaxChunks * W * 4);
     p.part_ci = take(M * kMaxChunks * W * 4);
     for (int i = 0; i < 2; ++i) { p.paths[i] = take(M * L * 4); p.cum[i] = take(M * 4); }
-    p.parent = take(M * 4);
+    p.parent = take(M * 4 * (size_t)(L > 1 ? L - 1 : 1));       // parent rows of every drafted position
     p.tok = take(M * 4);
     p.total = off;
     return p;
@@ -558,6 +573,7 @@ extern "C" size_t rd_draft_workspace(int B, int W, int L, int Dm, int V)
 
 extern "C" int rd_draft(const rd_draft_params *p, const void *h, const int32_t *last_token,
                         int B, int W, int L, int32_t *beams, float *beam_logp,
+                        float *step_logits, int32_t *step_row,
                         void *workspace, size_t workspace_bytes, void *stream)
 {
     const int st = draft_check(p, B, W, L);
@@ -565,6 +581,7 @@ extern "C" int rd_draft(const rd_draft_params *p, const void *h, const int32_t *
     if (!p->emb || !p->rnn_u || !p->rnn_w || !p->rnn_b || !p->head_w || (p->n_mlp > 0 && (!p->mlp_w || !p->mlp_b)))
         return RD_ERR_INVALID_ARG;
     if (!h || !last_token || !beams || !beam_logp) return RD_ERR_INVALID_ARG;
+    if ((step_logits == nullptr) != (step_row == nullptr) || !rd_aligned(step_logits, 16)) return RD_ERR_INVALID_ARG;
     if (!rd_aligned(p->emb, 16) || !rd_aligned(p->rnn_u, 16) || !rd_aligned(p->rnn_w, 16) || !rd_aligned(p->mlp_w, 16) ||
         !rd_aligned(p->head_w, 16) || !rd_aligned(h, 16))
         return RD_ERR_INVALID_ARG;
@@ -601,7 +618,7 @@ extern "C" int rd_draft(const rd_draft_params *p, const void *h, const int32_t *
         const int cur = (t - 1) & 1, nxt = t & 1;
         if (t > 1) {                                // s_t = f(U s_{t-1}[parent] + W e(token) + b) -> X0[:, :Dm]
             LinArgs a = {};
-            a.w1 = static_cast<const __bf16 *>(p->rnn_u); a.x1 = s_bf[si]; a.map1 = parent; a.ldx1 = Dm; a.K1 = Dm;
+            a.w1 = static_cast<const __bf16 *>(p->rnn_u); a.x1 = s_bf[si]; a.map1 = parent + (size_t)(t - 2) * M; a.ldx1 = Dm; a.K1 = Dm;
             a.w2 = static_cast<const __bf16 *>(p->rnn_w); a.x2 = emb; a.map2 = tok; a.ldx2 = Dm; a.K2 = Dm;
             a.bias = p->rnn_b; a.M = M; a.N = Dm; a.mstride = 1;
             a.y_f32 = x_f32[0]; a.y_bf = x_bf[0]; a.s_bf = s_bf[si ^ 1]; a.ldy = G;
@@ -623,6 +640,7 @@ extern "C" int rd_draft(const rd_draft_params *p, const void *h, const int32_t *
         {                                           // logits
             LinArgs a = {};
             a.w1 = static_cast<const __bf16 *>(p->head_w); a.x1 = x_bf[in]; a.ldx1 = G; a.K1 = G;
+            if (step_logits) logits = step_logits + (size_t)(t - 1) * M * V;   // every position keeps its matrix
             a.M = rows; a.N = V; a.mstride = mstride; a.y_f32 = logits; a.ldy = V;
             if (launch_linear<EPI_HEAD>(a, s) != RD_OK) return RD_ERR_HIP;
         }
@@ -631,8 +649,12 @@ extern "C" int rd_draft(const rd_draft_params *p, const void *h, const int32_t *
         if (rd_check_launch() != RD_OK) return RD_ERR_HIP;
         const bool last = t == T;
         hipLaunchKernelGGL(rd_beam_step_kernel, dim3(B), dim3(256), 0, s, part_max, part_sum, part_cv, part_ci, chunks,
-                           cum[cur], W, L, t, t == 1 ? 1 : W, paths[cur], paths[nxt], cum[nxt], parent, tok,
+                           cum[cur], W, L, t, t == 1 ? 1 : W, paths[cur], paths[nxt], cum[nxt], parent + (size_t)(t - 1) * M, tok,
                            last ? beams : nullptr, last ? beam_logp : nullptr);
+        if (rd_check_launch() != RD_OK) return RD_ERR_HIP;
+    }
+    if (step_row) {
+        hipLaunchKernelGGL(rd_draft_rows_kernel, dim3((M + 255) / 256), dim3(256), 0, s, parent, M, W, T, step_row);
         if (rd_check_launch() != RD_OK) return RD_ERR_HIP;
     }
     return RD_OK;

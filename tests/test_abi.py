@@ -126,12 +126,13 @@ def test_accept_argument_errors(lib):
     assert _accept(lib, ws_bytes=8) == WORKSPACE
 
 
-def _sample(lib, B=1, W=4, L=4, V=100, logits=FAKE, draft=FAKE, req=FAKE, u=FAKE, t=1.0, ws=FAKE, ws_bytes=None):
+def _sample(lib, B=1, W=4, L=4, V=100, logits=FAKE, draft=FAKE, req=FAKE, u=FAKE, t=1.0, ws=FAKE, ws_bytes=None,
+            step_row=None, rows=0):
     import ctypes
     need = lib.rd_accept_sample_workspace(B, W, L, V)
     if ws_bytes is None:
         ws_bytes = need
-    return lib.rd_accept_sample(logits, draft, FAKE, FAKE, FAKE, None, u, u, ctypes.c_float(t), B, W, L, V,
+    return lib.rd_accept_sample(logits, draft, step_row, rows, FAKE, FAKE, FAKE, None, u, u, ctypes.c_float(t), B, W, L, V,
                                 req, req, req, req, req, ws, ws_bytes, None)
 
 
@@ -149,6 +150,7 @@ def test_accept_sample_argument_errors(lib):
     assert _sample(lib, logits=None) == INVALID
     assert _sample(lib, draft=FAKE + 4) == INVALID
     assert _sample(lib, u=None) == INVALID
+    assert _sample(lib, step_row=FAKE, rows=0) == INVALID
     assert _sample(lib, req=None) == INVALID
     assert _sample(lib, ws=None) == WORKSPACE
     assert _sample(lib, ws_bytes=8) == WORKSPACE
@@ -235,11 +237,15 @@ def test_draft_argument_errors(lib):
     import ctypes
     from paper_2403_09919_amd.binding import _DraftParams
 
-    def call(Dm=64, V=100, K=1, B=1, W=4, L=5, emb=FAKE, mlp=FAKE, h=FAKE, ws=FAKE, ws_bytes=None, params=True):
+    def call(Dm=64, V=100, K=1, B=1, W=4, L=5, emb=FAKE, mlp=FAKE, h=FAKE, ws=FAKE, ws_bytes=None, params=True,
+             sl=None, sr=None):
         p = _DraftParams(emb, FAKE, FAKE, FAKE, mlp, mlp, FAKE, K, Dm, V)
         need = lib.rd_draft_workspace(B, W, L, Dm, V)
-        return lib.rd_draft(ctypes.byref(p) if params else None, h, FAKE, B, W, L, FAKE, FAKE, ws,
+        return lib.rd_draft(ctypes.byref(p) if params else None, h, FAKE, B, W, L, FAKE, FAKE, sl, sr, ws,
                             need if ws_bytes is None else ws_bytes, None)
+    assert call(sl=FAKE) == INVALID                          # the record of the search: both outputs or neither
+    assert call(sr=FAKE) == INVALID
+    assert call(sl=FAKE + 4, sr=FAKE) == INVALID
     assert call(params=False) == INVALID
     assert call(B=0) == INVALID
     assert call(Dm=0) == INVALID

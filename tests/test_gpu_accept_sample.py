@@ -171,3 +171,79 @@ def test_sampled_tokens_follow_the_llm_distribution(rd):
     freq = np.bincount(emitted, minlength=V) / B
     assert np.abs(freq - p).max() < 4.5 * np.sqrt(0.25 / B)
     assert abs(acc.mean() - np.minimum(p, q).sum()) < 4.5 * np.sqrt(0.25 / B)
+
+
+def test_step_layout_against_the_oracle(rd):
+    """Draft logits in the layout the beam search records (one matrix per position + the row behind
+    every candidate token), synthetic rows that respect shared prefixes."""
+    announce("accept_sample step layout")
+    rng = np.random.default_rng(52)
+    B, W, L, V, t = 5, 6, 5, 1500, 1.0
+    rows = B * W
+    c = make_case(B, W, L, V, seed=52, share="high", poison=False)
+    beams, d = c["beams"], c["d"]
+    step_row = np.zeros((B, W, L - 1), np.int32)
+    for b in range(B):
+        for j in range(L - 1):
+            ids = {}
+            for w in range(W):
+                step_row[b, w, j] = ids.setdefault(tuple(beams[b, w, : j + 1].tolist()), b * W + (len(ids) * 5 + j) % W)
+    step_logits = np.full((L - 1, rows, V), np.nan, np.float32)       # rows nobody names stay poisoned
+    for b in range(B):
+        for w in range(W):
+            for j in range(L - 1):
+                step_logits[j, step_row[b, w, j]] = c["draft"][b, d["unpack_index"][b, w, j]]
+    ref = oracle.accept_sample(c["logits"], step_logits, beams, d["unpack_index"], c["u_accept"], c["u_next"], t,
+                               step_row=step_row)
+    packed = oracle.accept_sample(c["logits"], c["draft"], beams, d["unpack_index"], c["u_accept"], c["u_next"], t)
+    got_step = rd.rd_accept_sample(dev(c["logits"]), dev(step_logits), dev(beams), dev(d["unpack_index"]), dev(d["n_packed"]),
+                                   dev(c["u_accept"]), dev(c["u_next"]), t, step_row=dev(step_row))
+    got_packed = run_gpu(rd, c, t)
+    torch.cuda.synchronize()
+    for k in packed:
+        assert np.array_equal(ref[k], packed[k]), k                  # same data, two layouts
+        assert np.array_equal(host(got_step[k]), got_packed[k]), k   # and the device agrees with itself bit for bit
+    check(rd, c, t, what="step layout (packed twin)")                # ... and with the oracle
+
+
+def test_draft_then_accept_sample(rd):
+    """rd_draft -> rd_dedup -> rd_accept_sample with the draft's own record, no copy in between; the
+    oracle runs on the same record (the device's logits are its input data)."""
+    announce("draft -> dedup -> accept_sample")
+    from test_oracle_draft import make_params
+    Dm, V, K, B, W, L, t = 64, 1200, 1, 4, 6, 5, 1.0
+    p = make_params(V, Dm, K, seed=77, scale=4.0)
+    rng = np.random.default_rng(77)
+    h = synth.f32_to_bf16_bits(rng.standard_normal((B, Dm)).astype(np.float32))
+    last = rng.integers(0, V, B).astype(np.int32)
+    dr = rd.rd_draft({k: dev(v) for k, v in p.items()}, dev(h), dev(last), W, L, steps=True)
+    dd = rd.rd_dedup(dr["beams"], dev(np.full(B, 9, np.int32)))
+    torch.cuda.synchronize()
+    beams, ui, npk = host(dr["beams"]), host(dd["unpack_index"]), host(dd["n_packed"])
+    step_logits, step_row = host(dr["step_logits"]), host(dr["step_row"])
+    N = W * L
+    # the LLM agrees with its drafter up to noise: logits of slot s = draft logits of s + N(0,1) (leaves: noise only)
+    logits = rng.standard_normal((B, N, V)).astype(np.float32)
+    for b in range(B):
+        for w in range(W):
+            for j in range(L - 1):
+                s = ui[b, w, j]
+                logits[b, s] = step_logits[j, step_row[b, w, j]] + rng.standard_normal(V).astype(np.float32) * 0.7
+    u_acc, u_next = synth.make_uniforms((B, N), 78), synth.make_uniforms((B,), 79)
+    ref = oracle.accept_sample(logits, step_logits, beams, ui, u_acc, u_next, t, diagnostics=True, step_row=step_row)
+    got = rd.rd_accept_sample(dev(logits), dr["step_logits"], dr["beams"], dd["unpack_index"], dd["n_packed"],
+                              dev(u_acc), dev(u_next), t, step_row=dr["step_row"])
+    torch.cuda.synchronize()
+    compared = 0
+    for b in range(B):
+        ratio = ref["accept_ratio"][b]
+        margin = np.abs(u_acc[b][ui[b]].astype(np.float64) - ratio)
+        if ((ratio >= 0) & (margin <= TOL) & (ratio < 1.0)).any():
+            continue
+        compared += 1
+        for k in ("n_accept", "best_beam", "best_len", "accepted_idx"):
+            assert np.array_equal(host(got[k])[b], ref[k][b]), (b, k)
+        v = int(host(got["next_token"])[b])
+        cdf = np.cumsum(ref["next_weights"][b])
+        assert ref["next_weights"][b][v] > 0 and (cdf[v - 1] if v else 0.0) - TOL <= float(u_next[b]) < cdf[v] + TOL
+    assert compared >= B - 1 and ref["best_len"].max() > 1

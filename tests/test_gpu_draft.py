@@ -145,3 +145,51 @@ def test_draft_vicuna7b_dimensions(rd):
     for w in range(W - 1):
         if np.abs(np.delete(rl, w) - rl[w]).min() > 2 * TOL_7B and rl[w] - rl[W - 1] > 2 * TOL_7B:
             assert tuple(ref["beams"][0, w].tolist()) in got_set, w
+
+
+@pytest.mark.parametrize("Dm,V,K,B,W,L", [(64, 500, 2, 2, 4, 5), (128, 4000, 1, 3, 8, 4), (64, 9000, 1, 3, 8, 3),
+                                          (64, 300, 1, 2, 1, 4), (64, 200, 1, 2, 4, 1)])
+def test_draft_records_the_search(rd, Dm, V, K, B, W, L):
+    """step_logits / step_row: the row recorded behind every candidate token must hold the draft
+    distribution given that candidate's prefix (the oracle's record, where the beams agree), rows of
+    candidates with a common prefix coincide, and the recorded distributions reproduce the scores."""
+    announce(f"draft record Dm={Dm} V={V} K={K} B={B} W={W} L={L}")
+    p = make_params(V, Dm, K, seed=Dm + V + 1, scale=4.0)
+    rng = np.random.default_rng(V + W + 1)
+    h = synth.f32_to_bf16_bits(rng.standard_normal((B, Dm)).astype(np.float32))
+    last = rng.integers(0, V, B).astype(np.int32)
+    ref = oracle.draft(p, h, last, W, L, steps=True)
+    got = rd.rd_draft(dev_params(p), dev(h), dev(last), W, L, steps=True)
+    plain = rd.rd_draft(dev_params(p), dev(h), dev(last), W, L)
+    torch.cuda.synchronize()
+    gb, gl, sr = host(got["beams"]), host(got["beam_logp"]), host(got["step_row"])
+    assert np.array_equal(gb, host(plain["beams"])) and np.array_equal(gl, host(plain["beam_logp"]))
+    if L == 1:
+        assert sr.shape == (B, W, 0)
+        return
+    sl = host(got["step_logits"]).astype(np.float64)
+    M = B * W
+    agree = 0
+    for b in range(B):
+        seen = {}
+        for w in range(W):
+            total = 0.0
+            for j in range(L - 1):
+                row = int(sr[b, w, j])
+                assert b * W <= row < (b + 1) * W and (j > 0 or row == b * W)
+                assert seen.setdefault((j, tuple(gb[b, w, : j + 1].tolist())), row) == row
+                z = sl[j, row]
+                lp = z - (z.max() + np.log(np.exp(z - z.max()).sum()))
+                total += lp[gb[b, w, j + 1]]
+            assert abs(total - gl[b, w]) <= 1e-4 * max(1.0, abs(total))       # the record reproduces the score
+        if np.array_equal(gb[b], ref["beams"][b]):
+            agree += 1
+            assert np.array_equal(sr[b], ref["step_row"][b])
+            for w in range(W):
+                for j in range(L - 1):
+                    z = sl[j, sr[b, w, j]]
+                    lp = z - (z.max() + np.log(np.exp(z - z.max()).sum()))
+                    # all V entries of a row, not just the few best: the maximum over thousands of entries of
+                    # the same bf16 re-rounding effect that TOL bounds for a handful of path scores
+                    assert np.abs(lp - ref["step_logp"][j, ref["step_row"][b, w, j]]).max() <= 10 * TOL
+    assert agree >= (B + 1) // 2
