@@ -29,7 +29,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 constexpr int kMaxRows = 512;          // B*W
 constexpr int kRowsPerLaunch = 128;    // rows of one linear-layer launch (8 MFMA row tiles)
-constexpr int kMaxBeam = 32;           // W
+constexpr int kMaxBeam = 64;           // W
 constexpr int kTopThreads = 1024;
 constexpr int kTopPer = 32;            // V <= kTopThreads * kTopPer = 32768 (eight chunks of 4096 logits)
 
@@ -342,15 +342,58 @@ __global__ __launch_bounds__(kChunkThreads) void rd_topw_chunk_kernel(const floa
     }
 }
 
-// Second pass and beam step, one workgroup per sequence.  A wave per live candidate row: the row's
-// log-sum-exp from the chunk partials and its W best tokens from the chunks' survivors, as cumulative
-// scores in LDS.  Then the best W of the live*W (candidate, token) pairs: pair c = w*W + r (row w's
-// r-th best token); ties in score go to the smaller c, i.e. the smaller candidate first and, within a
-// row, the smaller token (rows are sorted that way).  All rounds touch LDS only; paths, scores and
-// the row maps of the next RNN update are written at the end.
-__global__ __launch_bounds__(256) void rd_beam_step_kernel(
+// Second pass, one wave per live candidate row: the row's log-sum-exp from the chunk partials and its
+// W best tokens from the chunks' survivors (value, then smaller token), written as cumulative scores
+// row_score[row][r] = cum[row] + log p(token r), best first, with the tokens beside them.
+__global__ __launch_bounds__(64) void rd_topw_row_kernel(
     const float *__restrict__ part_max, const float *__restrict__ part_sum, const float *__restrict__ part_cv,
-    const int32_t *__restrict__ part_ci, int chunks, const float *__restrict__ cum_cur,
+    const int32_t *__restrict__ part_ci, int chunks, const float *__restrict__ cum_cur, int W, int mstride,
+    float *__restrict__ row_score, int32_t *__restrict__ row_tok)
+{
+    const int lane = threadIdx.x;
+    const size_t row = (size_t)blockIdx.x * mstride;
+    // log-sum-exp of the row: sum_c part_sum[c] * exp(part_max[c] - max)
+    const float pm = lane < chunks ? part_max[row * chunks + lane] : -INFINITY;
+    float gm = pm;
+    for (int off = 32; off > 0; off >>= 1) gm = fmaxf(gm, __shfl_xor(gm, off, 64));
+    float ps = lane < chunks ? part_sum[row * chunks + lane] * __expf(pm - gm) : 0.f;
+    for (int off = 32; off > 0; off >>= 1) ps += __shfl_xor(ps, off, 64);
+    const float lse = gm + __logf(ps);
+    const float base = cum_cur[row];
+    constexpr int kPer = kMaxChunks * kMaxBeam / 64;
+    float cv[kPer];
+    int ci[kPer];
+    const int n_surv = chunks * W;
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+        const int q = j * 64 + lane;
+        cv[j] = q < n_surv ? part_cv[row * n_surv + q] : -INFINITY;
+        ci[j] = q < n_surv ? part_ci[row * n_surv + q] : 0x7fffffff;
+    }
+    for (int r = 0; r < W; ++r) {
+        float bv = -INFINITY;
+        int bi = 0x7fffffff;
+#pragma unroll
+        for (int j = 0; j < kPer; ++j)
+            if (better(cv[j], ci[j], bv, bi)) { bv = cv[j]; bi = ci[j]; }
+        wave_best(bv, bi);
+        if (lane == 0) {
+            row_score[row * W + r] = base + (bv - lse);
+            row_tok[row * W + r] = bi;
+        }
+#pragma unroll
+        for (int j = 0; j < kPer; ++j)
+            if (ci[j] == bi) { cv[j] = -INFINITY; ci[j] = 0x7fffffff; }   // token indices are unique
+    }
+}
+
+// Beam step, one wave per sequence: the best W of the live*W (candidate, token) pairs by cumulative
+// score.  Every live row's list is sorted (best first; equal scores by smaller token), so this is a
+// merge: lane w holds a pointer into row w's list, each round takes the best of the heads -- ties to
+// the smaller candidate, and within a row the list order, i.e. the smaller token -- and advances
+// that lane.  Then the paths, the scores and the row maps of the next RNN update are written.
+__global__ __launch_bounds__(64) void rd_beam_step_kernel(
+    const float *__restrict__ row_score, const int32_t *__restrict__ row_tok, const float *__restrict__ cum_cur,
     int W, int L, int t, int live,
     const int32_t *__restrict__ paths_cur, int32_t *__restrict__ paths_next, float *__restrict__ cum_next,
     int32_t *__restrict__ parent_row, int32_t *__restrict__ tok_row,
@@ -358,98 +401,45 @@ __global__ __launch_bounds__(256) void rd_beam_step_kernel(
 {
     __shared__ float s_score[kMaxBeam * kMaxBeam];
     __shared__ int s_ctok[kMaxBeam * kMaxBeam];
-    __shared__ float s_v[4];
-    __shared__ int s_i[4];
     __shared__ int s_win[kMaxBeam], s_tok[kMaxBeam];
     __shared__ float s_winv[kMaxBeam];
-    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-
-    for (int w = wave; w < live; w += 4) {
-        const size_t row = (size_t)b * W + w;
-        // log-sum-exp of the row: sum_c part_sum[c] * exp(part_max[c] - max)
-        float pm = lane < chunks ? part_max[row * chunks + lane] : -INFINITY;
-        float gm = pm;
-        for (int off = 32; off > 0; off >>= 1) gm = fmaxf(gm, __shfl_xor(gm, off, 64));
-        float ps = lane < chunks ? part_sum[row * chunks + lane] * __expf(pm - gm) : 0.f;
-        for (int off = 32; off > 0; off >>= 1) ps += __shfl_xor(ps, off, 64);
-        const float lse = gm + __logf(ps);
-        const float base = cum_cur[row];
-        constexpr int kPer = kMaxChunks * kMaxBeam / 64;
-        float cv[kPer];
-        int ci[kPer];
-        const int n_surv = chunks * W;
-#pragma unroll
-        for (int j = 0; j < kPer; ++j) {
-            const int q = j * 64 + lane;
-            cv[j] = q < n_surv ? part_cv[row * n_surv + q] : -INFINITY;
-            ci[j] = q < n_surv ? part_ci[row * n_surv + q] : 0x7fffffff;
-        }
-        for (int r = 0; r < W; ++r) {
-            float bv = -INFINITY;
-            int bi = 0x7fffffff;
-#pragma unroll
-            for (int j = 0; j < kPer; ++j)
-                if (better(cv[j], ci[j], bv, bi)) { bv = cv[j]; bi = ci[j]; }
-            wave_best(bv, bi);
-            if (lane == 0) {
-                s_score[w * W + r] = base + (bv - lse);
-                s_ctok[w * W + r] = bi;
-            }
-#pragma unroll
-            for (int j = 0; j < kPer; ++j)
-                if (ci[j] == bi) { cv[j] = -INFINITY; ci[j] = 0x7fffffff; }
-        }
+    const int b = blockIdx.x, lane = threadIdx.x;
+    static_assert(kMaxBeam <= 64, "one lane per live candidate");
+    const int n_cand = live * W;
+    for (int i = lane; i < n_cand; i += 64) {                     // rows b*W .. b*W+live-1 are contiguous
+        s_score[i] = row_score[(size_t)b * W * W + i];
+        s_ctok[i] = row_tok[(size_t)b * W * W + i];
     }
     __syncthreads();
-
-    constexpr int kPerSel = (kMaxBeam * kMaxBeam + 255) / 256;
-    const int n_cand = live * W;
-    float x[kPerSel];
-#pragma unroll
-    for (int j = 0; j < kPerSel; ++j) {
-        const int c = j * 256 + tid;
-        x[j] = c < n_cand ? s_score[c] : -INFINITY;
-    }
+    int ptr = 0;
     for (int r = 0; r < W; ++r) {
-        float bv = -INFINITY;
-        int bi = 0x7fffffff;
-#pragma unroll
-        for (int j = 0; j < kPerSel; ++j) {
-            const int c = j * 256 + tid;
-            if (c < n_cand && better(x[j], c, bv, bi)) { bv = x[j]; bi = c; }
+        float bv = (lane < live && ptr < W) ? s_score[lane * W + ptr] : -INFINITY;
+        int bi = lane < live ? lane : 0x7fffffff;
+        if (!(lane < live && ptr < W)) bi = 0x7fffffff;
+        wave_best(bv, bi);                                        // bi = the winning candidate row
+        const int wptr = __shfl(ptr, bi, 64);
+        if (lane == 0) {
+            s_win[r] = bi;
+            s_winv[r] = bv;
+            s_tok[r] = s_ctok[bi * W + wptr];
         }
-        wave_best(bv, bi);
-        if (lane == 0) { s_v[wave] = bv; s_i[wave] = bi; }
-        __syncthreads();
-        bv = s_v[0];
-        bi = s_i[0];
-#pragma unroll
-        for (int w = 1; w < 4; ++w)
-            if (better(s_v[w], s_i[w], bv, bi)) { bv = s_v[w]; bi = s_i[w]; }
-#pragma unroll
-        for (int j = 0; j < kPerSel; ++j)
-            if (j * 256 + tid == bi) {                                   // mine: record and retire it
-                s_win[r] = bi;
-                s_winv[r] = x[j];
-                s_tok[r] = s_ctok[bi];
-                x[j] = -INFINITY;
-            }
-        __syncthreads();
+        if (lane == bi) ++ptr;
     }
-    // candidate r: parent pw = s_win[r] / W, new token s_tok[r]
-    for (int i = tid; i < W * L; i += 256) {
+    __syncthreads();
+    // candidate r: parent pw = s_win[r], new token s_tok[r]
+    for (int i = lane; i < W * L; i += 64) {
         const int r = i / L, j = i - r * L;
-        const int pw = s_win[r] / W;
+        const int pw = s_win[r];
         const size_t src = ((size_t)b * W + pw) * L;
         const int v = j < t ? paths_cur[src + j] : (j == t ? s_tok[r] : paths_cur[src]);
         paths_next[((size_t)b * W + r) * L + j] = v;
         if (beams_out) beams_out[((size_t)b * W + r) * L + j] = v;
     }
-    if (tid < W) {
-        cum_next[(size_t)b * W + tid] = s_winv[tid];
-        parent_row[(size_t)b * W + tid] = b * W + s_win[tid] / W;
-        tok_row[(size_t)b * W + tid] = s_tok[tid];
-        if (logp_out) logp_out[(size_t)b * W + tid] = s_winv[tid];
+    if (lane < W) {
+        cum_next[(size_t)b * W + lane] = s_winv[lane];
+        parent_row[(size_t)b * W + lane] = b * W + s_win[lane];
+        tok_row[(size_t)b * W + lane] = s_tok[lane];
+        if (logp_out) logp_out[(size_t)b * W + lane] = s_winv[lane];
     }
 }
 
@@ -469,7 +459,7 @@ __global__ void rd_draft_rows_kernel(const int32_t *__restrict__ parents /*[T][M
 }
 
 struct Plan {
-    size_t x_f32[3], x_bf[3], s_bf[2], logits, part_max, part_sum, part_cv, part_ci, paths[2], cum[2], parent, tok, total;
+    size_t x_f32[3], x_bf[3], s_bf[2], logits, part_max, part_sum, part_cv, part_ci, row_score, row_tok, paths[2], cum[2], parent, tok, total;
 };
 
 Plan draft_plan(int B, int W, int L, int Dm, int V)
@@ -485,6 +475,8 @@ Plan draft_plan(int B, int W, int L, int Dm, int V)
     p.part_sum = take(M * kMaxChunks * 4);
     p.part_cv = take(M * kMaxChunks * W * 4);
     p.part_ci = take(M * kMaxChunks * W * 4);
+    p.row_score = take(M * W * 4);
+    p.row_tok = take(M * W * 4);
     for (int i = 0; i < 2; ++i) { p.paths[i] = take(M * L * 4); p.cum[i] = take(M * 4); }
     p.parent = take(M * 4 * (size_t)(L > 1 ? L - 1 : 1));       // parent rows of every drafted position
     p.tok = take(M * 4);
@@ -598,6 +590,8 @@ extern "C" int rd_draft(const rd_draft_params *p, const void *h, const int32_t *
     float *part_max = reinterpret_cast<float *>(ws + plan.part_max), *part_sum = reinterpret_cast<float *>(ws + plan.part_sum);
     float *part_cv = reinterpret_cast<float *>(ws + plan.part_cv);
     int32_t *part_ci = reinterpret_cast<int32_t *>(ws + plan.part_ci);
+    float *row_score = reinterpret_cast<float *>(ws + plan.row_score);
+    int32_t *row_tok = reinterpret_cast<int32_t *>(ws + plan.row_tok);
     const int chunks = (V + kChunk - 1) / kChunk;
     int32_t *paths[2] = {reinterpret_cast<int32_t *>(ws + plan.paths[0]), reinterpret_cast<int32_t *>(ws + plan.paths[1])};
     float *cum[2] = {reinterpret_cast<float *>(ws + plan.cum[0]), reinterpret_cast<float *>(ws + plan.cum[1])};
@@ -648,8 +642,11 @@ extern "C" int rd_draft(const rd_draft_params *p, const void *h, const int32_t *
                            part_max, part_sum, part_cv, part_ci);
         if (rd_check_launch() != RD_OK) return RD_ERR_HIP;
         const bool last = t == T;
-        hipLaunchKernelGGL(rd_beam_step_kernel, dim3(B), dim3(256), 0, s, part_max, part_sum, part_cv, part_ci, chunks,
-                           cum[cur], W, L, t, t == 1 ? 1 : W, paths[cur], paths[nxt], cum[nxt], parent + (size_t)(t - 1) * M, tok,
+        hipLaunchKernelGGL(rd_topw_row_kernel, dim3(rows), dim3(64), 0, s, part_max, part_sum, part_cv, part_ci, chunks,
+                           cum[cur], W, mstride, row_score, row_tok);
+        if (rd_check_launch() != RD_OK) return RD_ERR_HIP;
+        hipLaunchKernelGGL(rd_beam_step_kernel, dim3(B), dim3(64), 0, s, row_score, row_tok, cum[cur], W, L, t,
+                           t == 1 ? 1 : W, paths[cur], paths[nxt], cum[nxt], parent + (size_t)(t - 1) * M, tok,
                            last ? beams : nullptr, last ? beam_logp : nullptr);
         if (rd_check_launch() != RD_OK) return RD_ERR_HIP;
     }

@@ -17,7 +17,12 @@ from test_oracle_draft import make_params
 
 pytestmark = pytest.mark.gpu
 
-TOL = 2e-3        # log-probability units; fp32 sums over 2*Dm terms of bf16 products, a few layers deep
+# Log-probability units.  The two sides round every layer input to bf16, so a 1e-7 difference between
+# fp32 and fp64 sums that straddles a rounding boundary moves that input by one bf16 ulp (2^-7 for
+# values in [1, 2)); through an output-layer weight of these tests (sigma = 4/sqrt(2 Dm) = 0.35 at
+# Dm = 64) one such flip shifts a logit by ~3e-3.  Flips are rare (a few per call) but with dozens of
+# candidates some path meets one: the bound is about three of them.
+TOL = 1e-2
 
 
 @pytest.fixture(scope="module")
@@ -69,7 +74,10 @@ def check(rd, p, h, last, W, L, what):
                                           (64, 9000, 1, 3, 8, 3), (64, 17000, 1, 5, 8, 3), (128, 16500, 2, 9, 8, 4),
                                           (64, 20000, 0, 4, 32, 3),
                                           # more rows than one linear-layer launch covers
-                                          (64, 700, 1, 20, 8, 4), (64, 16400, 1, 9, 32, 3)])
+                                          (64, 700, 1, 20, 8, 4), (64, 16400, 1, 9, 32, 3),
+                                          # the widest beams (the paper's best GPU settings use 50 and more)
+                                          (64, 3000, 1, 1, 64, 3), (64, 500, 1, 2, 48, 4), (128, 9000, 1, 2, 64, 3),
+                                          (64, 70, 1, 1, 64, 3)])
 def test_draft_matches_oracle(rd, Dm, V, K, B, W, L):
     announce(f"draft Dm={Dm} V={V} K={K} B={B} W={W} L={L}")
     p = make_params(V, Dm, K, seed=Dm + V, scale=4.0)
@@ -191,5 +199,5 @@ def test_draft_records_the_search(rd, Dm, V, K, B, W, L):
                     lp = z - (z.max() + np.log(np.exp(z - z.max()).sum()))
                     # all V entries of a row, not just the few best: the maximum over thousands of entries of
                     # the same bf16 re-rounding effect that TOL bounds for a handful of path scores
-                    assert np.abs(lp - ref["step_logp"][j, ref["step_row"][b, w, j]]).max() <= 10 * TOL
+                    assert np.abs(lp - ref["step_logp"][j, ref["step_row"][b, w, j]]).max() <= 3 * TOL
     assert agree >= (B + 1) // 2
