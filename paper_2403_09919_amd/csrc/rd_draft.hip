@@ -206,41 +206,38 @@ __global__ void rd_draft_init_kernel(const __bf16 *__restrict__ emb, const __bf1
 
 __device__ __forceinline__ bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
 
-// (value, index) arg max over the 64 lanes of a wave; every lane gets the result.  Lane exchanges
-// use the data-parallel primitives (quad permutes, row mirrors, the gfx950 16/32-lane swaps): the
-// selection loops call this dozens of times in a dependent chain, and a bpermute through the LDS
-// crossbar per step would dominate them.
+// Selection here is always a merge of sorted lists, one list per lane: every round the lanes offer
+// the heads of their lists, the largest value wins and, among equal values, the lowest lane (lists are
+// laid out so that a lower lane means a smaller candidate or smaller tokens, which is the tie rule).
+// A round is a maximum over lanes by data-parallel primitives, a ballot and a find-first-set; only the
+// winning lane fetches a new head.
 template <int kCtrl>
-__device__ __forceinline__ void best_step_dpp(float &bv, int &bi)
+__device__ __forceinline__ float max_step_dpp(float x)
 {
-    const float ov = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(bv), kCtrl, 0xf, 0xf, false));
-    const int oi = __builtin_amdgcn_update_dpp(0, bi, kCtrl, 0xf, 0xf, false);
-    if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+    return fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), kCtrl, 0xf, 0xf, false)));
 }
-__device__ __forceinline__ void wave_best(float &bv, int &bi)
+// maximum over each group of 8 consecutive lanes
+__device__ __forceinline__ float group8_max(float x)
 {
-    best_step_dpp<0xB1>(bv, bi);        // quad_perm [1,0,3,2]: partner lane ^ 1
-    best_step_dpp<0x4E>(bv, bi);        // quad_perm [2,3,0,1]: partner lane ^ 2
-    best_step_dpp<0x141>(bv, bi);       // row_half_mirror: the other quad of the 8
-    best_step_dpp<0x140>(bv, bi);       // row_mirror: the other half of the 16
-    {
-        const auto v = __builtin_amdgcn_permlane16_swap(__float_as_uint(bv), __float_as_uint(bv), false, false);
-        const auto i = __builtin_amdgcn_permlane16_swap((unsigned)bi, (unsigned)bi, false, false);
-        const float v0 = __uint_as_float(v[0]), v1 = __uint_as_float(v[1]);
-        const int i0 = (int)i[0], i1 = (int)i[1];
-        const bool first = better(v0, i0, v1, i1);
-        bv = first ? v0 : v1;
-        bi = first ? i0 : i1;
-    }
-    {
-        const auto v = __builtin_amdgcn_permlane32_swap(__float_as_uint(bv), __float_as_uint(bv), false, false);
-        const auto i = __builtin_amdgcn_permlane32_swap((unsigned)bi, (unsigned)bi, false, false);
-        const float v0 = __uint_as_float(v[0]), v1 = __uint_as_float(v[1]);
-        const int i0 = (int)i[0], i1 = (int)i[1];
-        const bool first = better(v0, i0, v1, i1);
-        bv = first ? v0 : v1;
-        bi = first ? i0 : i1;
-    }
+    x = max_step_dpp<0xB1>(x);          // quad_perm [1,0,3,2]: partner lane ^ 1
+    x = max_step_dpp<0x4E>(x);          // quad_perm [2,3,0,1]: partner lane ^ 2
+    return max_step_dpp<0x141>(x);      // row_half_mirror: the other quad of the 8
+}
+// maximum over the 64 lanes, the same value in every lane
+__device__ __forceinline__ float wave_max(float x)
+{
+    x = max_step_dpp<0x140>(group8_max(x));                 // row_mirror: the other half of the 16
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 0));
+    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 16));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 32));
+    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 48));
+    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
+}
+// lowest lane of the wave whose `offer` is set, -1 if none (uniform)
+__device__ __forceinline__ int first_lane(bool offer)
+{
+    const unsigned long long m = __ballot(offer);
+    return m ? __ffsll((long long)m) - 1 : -1;
 }
 
 constexpr int kChunk = 4096;            // logits per workgroup of the first top-W pass
@@ -248,9 +245,19 @@ constexpr int kChunkThreads = 256;
 constexpr int kChunkPer = kChunk / kChunkThreads;
 constexpr int kMaxChunks = kTopThreads * kTopPer / kChunk;      // V <= 32768
 
+// Compare-exchange of a sorting network on (value, position) pairs: the better pair goes to a.
+__device__ __forceinline__ void order_pair(float &va, int &ka, float &vb, int &kb)
+{
+    const bool swap = better(vb, kb, va, ka);
+    const float tv = swap ? vb : va, uv = swap ? va : vb;
+    const int tk = swap ? kb : ka, uk = swap ? ka : kb;
+    va = tv; vb = uv; ka = tk; kb = uk;
+}
+
 // First pass over the logits: workgroup (chunk c, row m) reduces 4096 logits to their maximum, the
-// sum of exp(x - maximum) and their W best (value, then smaller index).  Every wave finds the W best
-// of its own 1024 logits with lane shuffles only; wave 0 then picks the W best of the 4 x W survivors.
+// sum of exp(x - maximum) and their W best (value, then smaller token).  A lane owns 16 consecutive
+// tokens and sorts them in registers (odd-even merge sort network); the sorted lists go to LDS.  Each
+// wave merges its 64 lists into its W best, wave 0 then merges the four waves' lists.
 __global__ __launch_bounds__(kChunkThreads) void rd_topw_chunk_kernel(const float *__restrict__ logits, int V, int W, int chunks, int mstride,
                                                                       float *__restrict__ part_max, float *__restrict__ part_sum,
                                                                       float *__restrict__ part_cv, int32_t *__restrict__ part_ci)
@@ -258,20 +265,31 @@ __global__ __launch_bounds__(kChunkThreads) void rd_topw_chunk_kernel(const floa
     constexpr int kWaves = kChunkThreads / 64;
     __shared__ float s_v[kWaves];
     __shared__ float s_mx;
-    __shared__ float s_cv[kWaves * kMaxBeam];
-    __shared__ int s_ci[kWaves * kMaxBeam];
+    __shared__ float s_lv[kChunkPer][kChunkThreads];        // sorted lists, position-major (a lane's column)
+    __shared__ unsigned char s_lk[kChunkPer][kChunkThreads];
+    __shared__ float s_cv[kWaves][kMaxBeam];
+    __shared__ int s_ci[kWaves][kMaxBeam];
     const int c = blockIdx.x, m = blockIdx.y * mstride, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float *z = logits + (size_t)m * V;
-    const int v0 = c * kChunk;
+    const int t0 = c * kChunk + tid * kChunkPer;            // this lane's first token
     float x[kChunkPer];
+    int k[kChunkPer];
+    if ((V & 3) == 0 && t0 + kChunkPer <= V) {
+#pragma unroll
+        for (int j = 0; j < kChunkPer; j += 4) {
+            const float4 q = *reinterpret_cast<const float4 *>(z + t0 + j);
+            x[j] = q.x; x[j + 1] = q.y; x[j + 2] = q.z; x[j + 3] = q.w;
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < kChunkPer; ++j) x[j] = t0 + j < V ? z[t0 + j] : -INFINITY;
+    }
+    int n_valid = V - t0;
+    n_valid = n_valid < 0 ? 0 : (n_valid > kChunkPer ? kChunkPer : n_valid);
     float mx = -INFINITY;
 #pragma unroll
-    for (int j = 0; j < kChunkPer; ++j) {
-        const int v = v0 + j * kChunkThreads + tid;
-        x[j] = v < V ? z[v] : -INFINITY;
-        mx = fmaxf(mx, x[j]);
-    }
-    for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+    for (int j = 0; j < kChunkPer; ++j) { k[j] = j; mx = fmaxf(mx, x[j]); }
+    mx = wave_max(mx);
     if (lane == 0) s_v[wave] = mx;
     __syncthreads();
     if (tid == 0) s_mx = fmaxf(fmaxf(s_v[0], s_v[1]), fmaxf(s_v[2], s_v[3]));
@@ -279,33 +297,51 @@ __global__ __launch_bounds__(kChunkThreads) void rd_topw_chunk_kernel(const floa
     mx = s_mx;
     float sum = 0.f;
 #pragma unroll
-    for (int j = 0; j < kChunkPer; ++j) sum += (v0 + j * kChunkThreads + tid < V) ? __expf(x[j] - mx) : 0.f;
+    for (int j = 0; j < kChunkPer; ++j) sum += j < n_valid ? __expf(x[j] - mx) : 0.f;
     for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off, 64);
     __syncthreads();
     if (lane == 0) s_v[wave] = sum;
 
-    uint32_t gone = 0;                          // bit j: x[j] already taken
-    float lv = -INFINITY;                       // this lane's best remaining (value, index)
-    int li = 0x7fffffff;
-    bool stale = true;
-    for (int r = 0; r < W; ++r) {
-        if (stale) {
-            lv = -INFINITY;
-            li = 0x7fffffff;
+    // sort the lane's 16 (value, position) pairs, best first (Batcher's odd-even merge sort);
+    // positions past the end of the vocabulary hold -inf and, being later positions, sort behind
+    // real tokens of the same value
 #pragma unroll
-            for (int j = 0; j < kChunkPer; ++j) {
-                const int v = v0 + j * kChunkThreads + tid;
-                if (v < V && !((gone >> j) & 1u) && better(x[j], v, lv, li)) { lv = x[j]; li = v; }
-            }
-            stale = false;
+    for (int pp = 1; pp < kChunkPer; pp <<= 1)
+#pragma unroll
+        for (int kk = pp; kk >= 1; kk >>= 1)
+#pragma unroll
+            for (int jj = kk % pp; jj + kk < kChunkPer; jj += 2 * kk)
+#pragma unroll
+                for (int ii = 0; ii < kk; ++ii)
+                    if (ii + jj + kk < kChunkPer && (ii + jj) / (2 * pp) == (ii + jj + kk) / (2 * pp))
+                        order_pair(x[ii + jj], k[ii + jj], x[ii + jj + kk], k[ii + jj + kk]);
+#pragma unroll
+    for (int j = 0; j < kChunkPer; ++j) {
+        s_lv[j][tid] = x[j];
+        s_lk[j][tid] = (unsigned char)k[j];
+    }
+    // (a lane reads back only its own column: no barrier needed before the merge)
+
+    // merge of the wave's 64 lists
+    float hv = n_valid > 0 ? x[0] : -INFINITY;
+    int hk = k[0], ptr = 0;
+    bool live = n_valid > 0;
+    for (int r = 0; r < W; ++r) {
+        const float best = wave_max(live ? hv : -INFINITY);
+        const int win = first_lane(live && hv == best);
+        if (win < 0) {                                      // fewer than W tokens in this wave's range
+            if (lane == 0) { s_cv[wave][r] = -INFINITY; s_ci[wave][r] = 0x7fffffff; }
+            continue;
         }
-        float bv = lv;
-        int bi = li;
-        wave_best(bv, bi);
-        if (lane == 0) { s_cv[wave * W + r] = bv; s_ci[wave * W + r] = bi; }
-        if (bi == li && li != 0x7fffffff) {      // mine: retire it
-            gone |= 1u << ((bi - v0) / kChunkThreads);
-            stale = true;
+        const int wk = __builtin_amdgcn_readlane(hk, win);
+        if (lane == 0) {
+            s_cv[wave][r] = best;
+            s_ci[wave][r] = c * kChunk + (wave * 64 + win) * kChunkPer + wk;
+        }
+        if (lane == win) {
+            ++ptr;
+            live = ptr < n_valid;
+            if (live) { hv = s_lv[ptr][tid]; hk = s_lk[ptr][tid]; }
         }
     }
     __syncthreads();
@@ -315,85 +351,98 @@ __global__ __launch_bounds__(kChunkThreads) void rd_topw_chunk_kernel(const floa
         part_max[slot] = mx;
         part_sum[slot] = s_v[0] + s_v[1] + s_v[2] + s_v[3];
     }
-    constexpr int kPer = kWaves * kMaxBeam / 64;
-    float cv[kPer];
-    int ci[kPer];
-    const int n_surv = kWaves * W;
-#pragma unroll
-    for (int j = 0; j < kPer; ++j) {
-        const int q = j * 64 + lane;
-        cv[j] = q < n_surv ? s_cv[q] : -INFINITY;
-        ci[j] = q < n_surv ? s_ci[q] : 0x7fffffff;
-    }
+    // merge of the four waves' lists (a lower wave holds smaller tokens): lanes 0..3
+    int p4 = 0;
+    float h4 = lane < kWaves ? s_cv[lane][0] : -INFINITY;
+    bool live4 = lane < kWaves && s_ci[lane & (kWaves - 1)][0] != 0x7fffffff;
     for (int r = 0; r < W; ++r) {
-        float bv = -INFINITY;
-        int bi = 0x7fffffff;
-#pragma unroll
-        for (int j = 0; j < kPer; ++j)
-            if (better(cv[j], ci[j], bv, bi)) { bv = cv[j]; bi = ci[j]; }
-        wave_best(bv, bi);
-        if (lane == 0) {
-            part_cv[slot * W + r] = bv;
-            part_ci[slot * W + r] = bi;
+        const float best = wave_max(live4 ? h4 : -INFINITY);
+        const int win = first_lane(live4 && h4 == best);
+        if (win < 0) {
+            if (lane == 0) { part_cv[slot * W + r] = -INFINITY; part_ci[slot * W + r] = 0x7fffffff; }
+            continue;
         }
-#pragma unroll
-        for (int j = 0; j < kPer; ++j)
-            if (ci[j] == bi) { cv[j] = -INFINITY; ci[j] = 0x7fffffff; }   // token indices are unique
+        if (lane == win) {
+            part_cv[slot * W + r] = best;
+            part_ci[slot * W + r] = s_ci[lane][p4];
+            ++p4;
+            live4 = p4 < W && s_ci[lane][p4 < W ? p4 : 0] != 0x7fffffff;
+            if (live4) h4 = s_cv[lane][p4];
+        }
     }
 }
 
-// Second pass, one wave per live candidate row: the row's log-sum-exp from the chunk partials and its
-// W best tokens from the chunks' survivors (value, then smaller token), written as cumulative scores
+// Second pass, eight live candidate rows per wave (lane = row-in-wave * 8 + chunk): the row's
+// log-sum-exp from the chunk partials and its W best tokens as a merge of the chunks' sorted lists
+// (a lower chunk holds smaller tokens), written as cumulative scores
 // row_score[row][r] = cum[row] + log p(token r), best first, with the tokens beside them.
+constexpr int kRowsPerWave = 8;
+static_assert(kMaxChunks == 8, "one lane per chunk in groups of eight lanes");
 __global__ __launch_bounds__(64) void rd_topw_row_kernel(
     const float *__restrict__ part_max, const float *__restrict__ part_sum, const float *__restrict__ part_cv,
-    const int32_t *__restrict__ part_ci, int chunks, const float *__restrict__ cum_cur, int W, int mstride,
+    const int32_t *__restrict__ part_ci, int chunks, const float *__restrict__ cum_cur, int W, int n_rows, int mstride,
     float *__restrict__ row_score, int32_t *__restrict__ row_tok)
 {
-    const int lane = threadIdx.x;
-    const size_t row = (size_t)blockIdx.x * mstride;
-    // log-sum-exp of the row: sum_c part_sum[c] * exp(part_max[c] - max)
-    const float pm = lane < chunks ? part_max[row * chunks + lane] : -INFINITY;
-    float gm = pm;
-    for (int off = 32; off > 0; off >>= 1) gm = fmaxf(gm, __shfl_xor(gm, off, 64));
-    float ps = lane < chunks ? part_sum[row * chunks + lane] * __expf(pm - gm) : 0.f;
-    for (int off = 32; off > 0; off >>= 1) ps += __shfl_xor(ps, off, 64);
-    const float lse = gm + __logf(ps);
-    const float base = cum_cur[row];
-    constexpr int kPer = kMaxChunks * kMaxBeam / 64;
-    float cv[kPer];
-    int ci[kPer];
+    __shared__ float s_cv[kRowsPerWave * kMaxChunks * kMaxBeam];
+    __shared__ int s_ci[kRowsPerWave * kMaxChunks * kMaxBeam];
+    const int lane = threadIdx.x, g = lane >> 3, c = lane & 7;
+    const int row_l = blockIdx.x * kRowsPerWave + g;                  // logical row of this lane's group
+    const bool row_ok = row_l < n_rows;
+    const size_t row = (size_t)(row_ok ? row_l : n_rows - 1) * mstride;
     const int n_surv = chunks * W;
-#pragma unroll
-    for (int j = 0; j < kPer; ++j) {
-        const int q = j * 64 + lane;
-        cv[j] = q < n_surv ? part_cv[row * n_surv + q] : -INFINITY;
-        ci[j] = q < n_surv ? part_ci[row * n_surv + q] : 0x7fffffff;
-    }
-    for (int r = 0; r < W; ++r) {
-        float bv = -INFINITY;
-        int bi = 0x7fffffff;
-#pragma unroll
-        for (int j = 0; j < kPer; ++j)
-            if (better(cv[j], ci[j], bv, bi)) { bv = cv[j]; bi = ci[j]; }
-        wave_best(bv, bi);
-        if (lane == 0) {
-            row_score[row * W + r] = base + (bv - lse);
-            row_tok[row * W + r] = bi;
+    // the survivors of the wave's rows -> LDS, [group][chunk][W]
+    for (int gg = 0; gg < kRowsPerWave; ++gg) {
+        const int rl = blockIdx.x * kRowsPerWave + gg;
+        if (rl >= n_rows) break;
+        const size_t rr = (size_t)rl * mstride;
+        for (int q = lane; q < n_surv; q += 64) {
+            s_cv[gg * kMaxChunks * kMaxBeam + q] = part_cv[rr * n_surv + q];
+            s_ci[gg * kMaxChunks * kMaxBeam + q] = part_ci[rr * n_surv + q];
         }
-#pragma unroll
-        for (int j = 0; j < kPer; ++j)
-            if (ci[j] == bi) { cv[j] = -INFINITY; ci[j] = 0x7fffffff; }   // token indices are unique
+    }
+    // log-sum-exp of the row: sum_c part_sum[c] * exp(part_max[c] - max)
+    const bool lane_ok = row_ok && c < chunks;
+    const float pm = lane_ok ? part_max[row * chunks + c] : -INFINITY;
+    const float gm = group8_max(pm);
+    float ps = lane_ok ? part_sum[row * chunks + c] * __expf(pm - gm) : 0.f;
+    ps += __shfl_xor(ps, 1, 64);
+    ps += __shfl_xor(ps, 2, 64);
+    ps += __shfl_xor(ps, 4, 64);
+    const float lse = gm + __logf(ps);
+    const float base = row_ok ? cum_cur[row] : 0.f;
+    __syncthreads();
+
+    const float *lv = s_cv + g * kMaxChunks * kMaxBeam + c * W;      // this lane's list: chunk c of its row
+    const int *li = s_ci + g * kMaxChunks * kMaxBeam + c * W;
+    int ptr = 0;
+    bool live = lane_ok && li[0] != 0x7fffffff;
+    float hv = live ? lv[0] : -INFINITY;
+    for (int r = 0; r < W; ++r) {
+        const float best = group8_max(live ? hv : -INFINITY);
+        const unsigned long long offers = __ballot(live && hv == best);
+        const unsigned mine = (unsigned)(offers >> (g * 8)) & 0xffu;   // offers of this lane's group
+        const int win = mine ? __ffs((int)mine) - 1 : -1;             // chunk that wins in this group
+        if (c == 0 && row_ok) {
+            row_score[row * W + r] = win >= 0 ? base + (best - lse) : -INFINITY;
+        }
+        if (c == win) {
+            row_tok[row * W + r] = li[ptr];
+            ++ptr;
+            live = ptr < W && li[ptr < W ? ptr : 0] != 0x7fffffff;
+            if (live) hv = lv[ptr];
+        } else if (c == 0 && win < 0 && row_ok) {
+            row_tok[row * W + r] = 0;
+        }
     }
 }
 
 // Beam step, one wave per sequence: the best W of the live*W (candidate, token) pairs by cumulative
 // score.  Every live row's list is sorted (best first; equal scores by smaller token), so this is a
-// merge: lane w holds a pointer into row w's list, each round takes the best of the heads -- ties to
-// the smaller candidate, and within a row the list order, i.e. the smaller token -- and advances
-// that lane.  Then the paths, the scores and the row maps of the next RNN update are written.
+// merge with lane w holding row w's list: ties go to the smaller candidate, and within a row to the
+// list order, i.e. the smaller token.  Then the paths, the scores and the row maps of the next RNN
+// update are written.
 __global__ __launch_bounds__(64) void rd_beam_step_kernel(
-    const float *__restrict__ row_score, const int32_t *__restrict__ row_tok, const float *__restrict__ cum_cur,
+    const float *__restrict__ row_score, const int32_t *__restrict__ row_tok, int V,
     int W, int L, int t, int live,
     const int32_t *__restrict__ paths_cur, int32_t *__restrict__ paths_next, float *__restrict__ cum_next,
     int32_t *__restrict__ parent_row, int32_t *__restrict__ tok_row,
@@ -412,18 +461,22 @@ __global__ __launch_bounds__(64) void rd_beam_step_kernel(
     }
     __syncthreads();
     int ptr = 0;
+    bool on = lane < live;
+    float hv = on ? s_score[lane * W] : -INFINITY;
     for (int r = 0; r < W; ++r) {
-        float bv = (lane < live && ptr < W) ? s_score[lane * W + ptr] : -INFINITY;
-        int bi = lane < live ? lane : 0x7fffffff;
-        if (!(lane < live && ptr < W)) bi = 0x7fffffff;
-        wave_best(bv, bi);                                        // bi = the winning candidate row
-        const int wptr = __shfl(ptr, bi, 64);
-        if (lane == 0) {
-            s_win[r] = bi;
-            s_winv[r] = bv;
-            s_tok[r] = s_ctok[bi * W + wptr];
+        const float best = wave_max(on ? hv : -INFINITY);
+        int win = first_lane(on && hv == best);
+        if (win < 0) win = first_lane(on);                        // NaN scores: keep indices in range
+        if (win < 0) win = 0;
+        if (lane == win) {
+            s_win[r] = lane;
+            s_winv[r] = best;
+            const int tk = s_ctok[lane * W + (ptr < W ? ptr : W - 1)];
+            s_tok[r] = tk < 0 ? 0 : (tk > V - 1 ? V - 1 : tk);
+            ++ptr;
+            on = ptr < W;
+            if (on) hv = s_score[lane * W + ptr];
         }
-        if (lane == bi) ++ptr;
     }
     __syncthreads();
     // candidate r: parent pw = s_win[r], new token s_tok[r]
@@ -642,10 +695,10 @@ extern "C" int rd_draft(const rd_draft_params *p, const void *h, const int32_t *
                            part_max, part_sum, part_cv, part_ci);
         if (rd_check_launch() != RD_OK) return RD_ERR_HIP;
         const bool last = t == T;
-        hipLaunchKernelGGL(rd_topw_row_kernel, dim3(rows), dim3(64), 0, s, part_max, part_sum, part_cv, part_ci, chunks,
-                           cum[cur], W, mstride, row_score, row_tok);
+        hipLaunchKernelGGL(rd_topw_row_kernel, dim3((rows + kRowsPerWave - 1) / kRowsPerWave), dim3(64), 0, s, part_max, part_sum,
+                           part_cv, part_ci, chunks, cum[cur], W, rows, mstride, row_score, row_tok);
         if (rd_check_launch() != RD_OK) return RD_ERR_HIP;
-        hipLaunchKernelGGL(rd_beam_step_kernel, dim3(B), dim3(64), 0, s, row_score, row_tok, cum[cur], W, L, t,
+        hipLaunchKernelGGL(rd_beam_step_kernel, dim3(B), dim3(64), 0, s, row_score, row_tok, V, W, L, t,
                            t == 1 ? 1 : W, paths[cur], paths[nxt], cum[nxt], parent + (size_t)(t - 1) * M, tok,
                            last ? beams : nullptr, last ? beam_logp : nullptr);
         if (rd_check_launch() != RD_OK) return RD_ERR_HIP;
