@@ -390,14 +390,31 @@ __global__ __launch_bounds__(64) void rd_topw_row_kernel(
     const bool row_ok = row_l < n_rows;
     const size_t row = (size_t)(row_ok ? row_l : n_rows - 1) * mstride;
     const int n_surv = chunks * W;
-    // the survivors of the wave's rows -> LDS, [group][chunk][W]
-    for (int gg = 0; gg < kRowsPerWave; ++gg) {
-        const int rl = blockIdx.x * kRowsPerWave + gg;
-        if (rl >= n_rows) break;
-        const size_t rr = (size_t)rl * mstride;
-        for (int q = lane; q < n_surv; q += 64) {
-            s_cv[gg * kMaxChunks * kMaxBeam + q] = part_cv[rr * n_surv + q];
-            s_ci[gg * kMaxChunks * kMaxBeam + q] = part_ci[rr * n_surv + q];
+    // the survivors of the wave's rows -> LDS, [group][chunk][W]; eight loads per lane in flight
+    // together, addresses past the end pulled back (no load sits behind a branch)
+    {
+        const int rows_here = min(kRowsPerWave, n_rows - blockIdx.x * kRowsPerWave);
+        const int total = rows_here * n_surv;
+        for (int i0 = 0; i0 < total; i0 += 64 * 8) {
+            float v[8];
+            int ti[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = min(i0 + u * 64 + lane, total - 1);
+                const int gg = idx / n_surv, q = idx - gg * n_surv;
+                const size_t src = (size_t)(blockIdx.x * kRowsPerWave + gg) * mstride * n_surv + q;
+                v[u] = part_cv[src];
+                ti[u] = part_ci[src];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = i0 + u * 64 + lane;
+                if (idx < total) {
+                    const int gg = idx / n_surv, q = idx - gg * n_surv;
+                    s_cv[gg * kMaxChunks * kMaxBeam + q] = v[u];
+                    s_ci[gg * kMaxChunks * kMaxBeam + q] = ti[u];
+                }
+            }
         }
     }
     // log-sum-exp of the row: sum_c part_sum[c] * exp(part_max[c] - max)
@@ -455,9 +472,20 @@ __global__ __launch_bounds__(64) void rd_beam_step_kernel(
     const int b = blockIdx.x, lane = threadIdx.x;
     static_assert(kMaxBeam <= 64, "one lane per live candidate");
     const int n_cand = live * W;
-    for (int i = lane; i < n_cand; i += 64) {                     // rows b*W .. b*W+live-1 are contiguous
-        s_score[i] = row_score[(size_t)b * W * W + i];
-        s_ctok[i] = row_tok[(size_t)b * W * W + i];
+    for (int i0 = 0; i0 < n_cand; i0 += 64 * 8) {                 // rows b*W .. b*W+live-1 are contiguous
+        float v[8];                                               // eight loads per lane in flight together
+        int ti[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int idx = min(i0 + u * 64 + lane, n_cand - 1);
+            v[u] = row_score[(size_t)b * W * W + idx];
+            ti[u] = row_tok[(size_t)b * W * W + idx];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int idx = i0 + u * 64 + lane;
+            if (idx < n_cand) { s_score[idx] = v[u]; s_ctok[idx] = ti[u]; }
+        }
     }
     __syncthreads();
     int ptr = 0;
