@@ -1,18 +1,17 @@
 // rd_draft: the draft model and its beam search (Sec. 3.1, 3.2) for gfx950.
 //
-// Per drafted position the work is three kinds of launches on the caller's stream:
+// Per drafted position the work is two kinds of launches on the caller's stream:
 //   * skinny linear layers  Y[M,N] = X[M,K] W[N,K]^T  with M = B*W rows (one per live candidate)
 //     and bf16 weights streamed once from HBM: the layers are bound by that stream (the LM-head
-//     alone is V x 2Dm), so a workgroup owns 16 output columns, its four waves split K, weights
+//     alone is V x 2Dm), so a workgroup owns 16 to 64 output columns, its waves split K, weights
 //     go from memory straight into the A operand of v_mfma_f32_16x16x32_bf16 (lane = one output
 //     column x 8 consecutive k), the activations (a few hundred KB, L2 resident) into the B
-//     operand, and the four partial sums meet in LDS.  Bias, SiLU, skip connection and the bf16
+//     operand, and the partial sums meet in LDS.  Bias, SiLU, skip connection and the bf16
 //     copy that the next layer reads are fused into the epilogue;
-//   * a first pass over the logits: per chunk of 4096 and row, the pieces of the log-sum-exp and the
-//     W best tokens;
-//   * the beam step, one workgroup per sequence: log-softmax and the W best tokens of every row
-//     from the chunk results, then the best W of the (candidate, token) pairs by cumulative log
-//     probability, ties to the smaller candidate, then the smaller token.
+//   * three selection launches, all merges of sorted lists: per chunk of 4096 logits and row, the
+//     pieces of the log-sum-exp and the W best tokens; per row, its log-sum-exp and the W best
+//     tokens of its chunks as cumulative scores; per sequence, the best W of the (candidate, token)
+//     pairs by cumulative log probability, ties to the smaller candidate, then the smaller token.
 // The RNN update reads its two inputs in place: the parent's state through a row map and the
 // chosen token's embedding straight from the table, so no gather pass exists.
 //
@@ -30,8 +29,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 constexpr int kMaxRows = 512;          // B*W
 constexpr int kRowsPerLaunch = 128;    // rows of one linear-layer launch (8 MFMA row tiles)
 constexpr int kMaxBeam = 64;           // W
-constexpr int kTopThreads = 1024;
-constexpr int kTopPer = 32;            // V <= kTopThreads * kTopPer = 32768 (eight chunks of 4096 logits)
+constexpr int kMaxVocab = 32768;       // eight chunks of 4096 logits: one lane per chunk in the row pass
 
 enum { EPI_HEAD = 0, EPI_RNN = 1, EPI_MLP = 2 };
 
@@ -243,7 +241,7 @@ __device__ __forceinline__ int first_lane(bool offer)
 constexpr int kChunk = 4096;            // logits per workgroup of the first top-W pass
 constexpr int kChunkThreads = 256;
 constexpr int kChunkPer = kChunk / kChunkThreads;
-constexpr int kMaxChunks = kTopThreads * kTopPer / kChunk;      // V <= 32768
+constexpr int kMaxChunks = kMaxVocab / kChunk;
 
 // Compare-exchange of a sorting network on (value, position) pairs: the better pair goes to a.
 __device__ __forceinline__ void order_pair(float &va, int &ka, float &vb, int &kb)
@@ -571,7 +569,7 @@ int draft_check(const rd_draft_params *p, int B, int W, int L)
     if (p->Dm <= 0 || p->V <= 0 || p->n_mlp < 0) return RD_ERR_INVALID_ARG;
     if (p->Dm % 64 != 0) return RD_ERR_UNSUPPORTED;              // every wave's K share is whole 32-wide steps
     if (W > kMaxBeam || (long long)B * W > kMaxRows || W > p->V) return RD_ERR_UNSUPPORTED;
-    if (p->V > kTopThreads * kTopPer || L > RD_MAX_N) return RD_ERR_UNSUPPORTED;
+    if (p->V > kMaxVocab || L > RD_MAX_N) return RD_ERR_UNSUPPORTED;
     return RD_OK;
 }
 
