@@ -32,7 +32,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per rd_tree_attn launch from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, each scaled
 # by what the same counter reads for a 64 MiB copy); see profiles/bench_vicuna7b_layer_rocprofv3.md.
 # Keyed by workload; None where no counter run has been made.
-MEASURED_TRAFFIC_BYTES = {2: 22717491}
+MEASURED_TRAFFIC_BYTES = {2: 21900746}
 
 
 def parse():
