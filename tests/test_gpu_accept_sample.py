@@ -97,7 +97,7 @@ def test_accept_sample_shapes(rd, B, W, L, V, t):
     check(rd, c, t, root, what="shapes+root")
 
 
-@pytest.mark.parametrize("idx", [2, 3])
+@pytest.mark.parametrize("idx", [2, 3, 4, 5])
 def test_accept_sample_configs(rd, idx):
     cfg = synth.CONFIGS[idx]
     announce("accept_sample config %d" % idx)
