@@ -389,9 +389,9 @@ def rd_draft(params: dict, h, last_token, W: int, L: int, out: Optional[dict] = 
     if out is None:
         out = dict(beams=torch.empty((B, W, L), dtype=torch.int32, device=dev),
                    beam_logp=torch.empty((B, W), dtype=torch.float32, device=dev))
-        if steps:
-            out["step_logits"] = torch.empty((max(L - 1, 0), B * W, V), dtype=torch.float32, device=dev)
-            out["step_row"] = torch.empty((B, W, max(L - 1, 0)), dtype=torch.int32, device=dev)
+    if steps and out.get("step_logits") is None:
+        out["step_logits"] = torch.empty((max(L - 1, 0), B * W, V), dtype=torch.float32, device=dev)
+        out["step_row"] = torch.empty((B, W, max(L - 1, 0)), dtype=torch.int32, device=dev)
     if workspace is None:
         workspace = torch.empty(max(rd_draft_workspace(B, W, L, Dm, V), 256), dtype=torch.uint8, device=dev)
     sl, sr = out.get("step_logits"), out.get("step_row")
