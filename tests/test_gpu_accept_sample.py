@@ -247,3 +247,31 @@ def test_draft_then_accept_sample(rd):
         cdf = np.cumsum(ref["next_weights"][b])
         assert ref["next_weights"][b][v] > 0 and (cdf[v - 1] if v else 0.0) - TOL <= float(u_next[b]) < cdf[v] + TOL
     assert compared >= B - 1 and ref["best_len"].max() > 1
+
+
+@pytest.mark.parametrize("B,W,L,V", [(3, 4, 3, 1), (2, 5, 4, 3), (4, 6, 1, 50), (2, 128, 3, 300), (1, 1, 384, 64),
+                                     (2, 2, 2, 5)])
+def test_accept_sample_degenerate_shapes(rd, B, W, L, V):
+    """One-token vocabularies, vocabularies below the vector width, no drafted tokens (L = 1), the widest
+    beam and the longest candidate the library takes."""
+    announce(f"accept_sample degenerate B={B} W={W} L={L} V={V}")
+    c = make_case(B, W, L, V, seed=3 * B + W + L + V, share="high")
+    check(rd, c, 1.0, what="degenerate")
+
+
+def test_masked_vocabulary_entries(rd):
+    """-inf logits (a masked vocabulary) carry no probability: never drawn, and a candidate token the LLM
+    masks is rejected whatever the uniform number."""
+    announce("accept_sample with -inf logits")
+    B, W, L, V = 4, 6, 4, 1000
+    c = make_case(B, W, L, V, seed=91, poison=False)
+    rng = np.random.default_rng(91)
+    masked = rng.random((B, 1, V)) < 0.5
+    c["logits"] = np.where(masked, -np.inf, c["logits"]).astype(np.float32)
+    c["u_accept"][:] = 1e-3                                  # small: nearly everything with p > 0 is accepted
+    ref, got = check(rd, c, 1.0, what="masked")
+    assert (got["n_accept"] < L).any() and (got["n_accept"] > 1).any()
+    for b in range(B):
+        assert not masked[b, 0, got["next_token"][b]]
+        for w in range(W):
+            assert not masked[b, 0, c["beams"][b, w, 1:got["n_accept"][b, w]]].any()

@@ -77,7 +77,9 @@ def check(rd, p, h, last, W, L, what):
                                           (64, 700, 1, 20, 8, 4), (64, 16400, 1, 9, 32, 3),
                                           # the widest beams (the paper's best GPU settings use 50 and more)
                                           (64, 3000, 1, 1, 64, 3), (64, 500, 1, 2, 48, 4), (128, 9000, 1, 2, 64, 3),
-                                          (64, 70, 1, 1, 64, 3)])
+                                          (64, 70, 1, 1, 64, 3),
+                                          # every token of the vocabulary is a candidate; the most rows; the shortest draft
+                                          (64, 16, 1, 2, 16, 3), (64, 200, 0, 16, 32, 2), (64, 40, 1, 3, 5, 2)])
 def test_draft_matches_oracle(rd, Dm, V, K, B, W, L):
     announce(f"draft Dm={Dm} V={V} K={K} B={B} W={W} L={L}")
     p = make_params(V, Dm, K, seed=Dm + V, scale=4.0)
