@@ -599,11 +599,15 @@ int launch_linear_nt(const LinArgs &a, hipStream_t stream)
     return rd_check_launch();
 }
 
-// column tiles per workgroup: the most (up to the row tiles, at most 4) that still leave one
-// workgroup per compute unit
+// column tiles per workgroup: the most that still leave about one workgroup per compute unit (the
+// activation re-reads are MT : NT of the weight bytes, and measured they cost as much as the
+// weights' own stream; halving the workgroups below the number of compute units costs more)
 template <int MT, int EPI>
 int launch_linear_mt(const LinArgs &a, hipStream_t stream)
 {
+    if constexpr (MT == 2 || MT == 4) {
+        if (a.N >= 240 * 128) return launch_linear_nt<MT, 8, EPI>(a, stream);
+    }
     if constexpr (MT >= 4) {
         if (a.N >= 256 * 64) return launch_linear_nt<MT, 4, EPI>(a, stream);
     }

@@ -79,7 +79,9 @@ def check(rd, p, h, last, W, L, what):
                                           (64, 3000, 1, 1, 64, 3), (64, 500, 1, 2, 48, 4), (128, 9000, 1, 2, 64, 3),
                                           (64, 70, 1, 1, 64, 3),
                                           # every token of the vocabulary is a candidate; the most rows; the shortest draft
-                                          (64, 16, 1, 2, 16, 3), (64, 200, 0, 16, 32, 2), (64, 40, 1, 3, 5, 2)])
+                                          (64, 16, 1, 2, 16, 3), (64, 200, 0, 16, 32, 2), (64, 40, 1, 3, 5, 2),
+                                          # output layers wide enough for workgroups of 128 columns
+                                          (64, 31000, 1, 3, 8, 3), (64, 32768, 0, 5, 8, 2)])
 def test_draft_matches_oracle(rd, Dm, V, K, B, W, L):
     announce(f"draft Dm={Dm} V={V} K={K} B={B} W={W} L={L}")
     p = make_params(V, Dm, K, seed=Dm + V, scale=4.0)
