@@ -573,7 +573,7 @@ static void draft_logp(const uint16_t *mlp_w, const float *mlp_b, int n_mlp, con
 static void draft_rnn(const uint16_t *emb, const uint16_t *rnn_u, const uint16_t *rnn_w, const float *rnn_b,
                       const double *s, int token, int Dm, double *s_next)
 {
-    double *e = (double *)malloc(sizeof(double) * (size_t)Dm);
+    double *e = (double *)calloc((size_t)Dm, sizeof(double));
     double *a = (double *)malloc(sizeof(double) * (size_t)Dm);
     double *c = (double *)malloc(sizeof(double) * (size_t)Dm);
     for (int i = 0; i < Dm; ++i) e[i] = bf16_to_double(emb[(size_t)token * Dm + i]);
