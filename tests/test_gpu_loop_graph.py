@@ -57,6 +57,9 @@ def test_sampling_loop_eager_and_graph():
         for name in ("dr", "d", "a", "c"):
             s.update({name + "_" + k: host(v) for k, v in st[name].items() if v is not None})
         s["o"], s["k_cache"], s["v_cache"] = host(st["o"]), host(g["k_cache"]), host(g["v_cache"])
+        dead = np.ones(B * W, bool)                              # rows of the first position that rd_draft does not write
+        dead[::W] = False
+        s["dr_step_logits"][0, dead] = 0
         return s
 
     step()
