@@ -265,6 +265,16 @@ def main():
                   "rd_accept": time_kernel(k_accept), "rd_commit": time_kernel(k_commit),
                   "rd_accept_sample": time_kernel(k_sample)}
 
+    # algorithmic bytes of the other streaming kernels (means over the copies): rd_accept reads the valid logit
+    # rows; rd_accept_sample reads them and the draft rows of slots that are not at the last position
+    valid_rows = float(np.mean([c["n_packed_np"].sum() for c in copies]))
+    leaf_rows = float(np.mean([sum(len(set(u[:, -1].tolist())) for u in c["dedup"]["unpack_index"].cpu().numpy())
+                               for c in copies]))
+    kernels_gbs = {
+        "rd_accept": round(valid_rows * cfg.V * 4 / kernels_us["rd_accept"] / 1e3, 1),
+        "rd_accept_sample": round((2 * valid_rows - leaf_rows) * cfg.V * 4 / kernels_us["rd_accept_sample"] / 1e3, 1),
+    }
+
     draft = None if args.no_draft else time_draft(rd, cfg, stream, max(4, min(40, args.steps // 10)), torch)
 
     result = {
@@ -292,6 +302,7 @@ def main():
         "packed_tokens_per_step": round(packed_mean, 2),
         "wall_ms_timed_region": round(wall_ms, 3),
         "kernels_us": kernels_us,
+        "kernels_algorithmic_gbs": kernels_gbs,
         "rd_draft": draft,
         "roofline": {
             "kernel": "rd_tree_attn",
@@ -334,8 +345,8 @@ def time_draft(rd, cfg, stream, n, torch):
     h = rn(B, Dm)
     last = torch.randint(0, V, (B,), device="cuda", dtype=torch.int32, generator=gen)
     ws = torch.empty(rd.rd_draft_workspace(B, W, L, Dm, V), dtype=torch.uint8, device="cuda")
-    with torch.cuda.stream(stream):
-        out = rd.rd_draft(sets[0], h, last, W, L, workspace=ws)
+    with torch.cuda.stream(stream):                 # eager launches: replaying the call from a HIP graph was slower
+        out = rd.rd_draft(sets[0], h, last, W, L, workspace=ws)     # (885 against 835 us at config 2)
         rd.rd_draft(sets[1], h, last, W, L, out=out, workspace=ws)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(stream)
