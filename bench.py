@@ -45,6 +45,7 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of graph replays")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-draft", action="store_true", help="skip the separate rd_draft timing")
+    ap.add_argument("--no-floor", action="store_true", help="skip the plain streaming-read floor measurement")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time budget of the oracle baseline")
     ap.add_argument("--pmc-calib", action="store_true",
                     help="also run plain device copies of 64 MiB (reference dispatches for scaling rocprofv3 "
@@ -275,6 +276,42 @@ def main():
         "rd_accept_sample": round((2 * valid_rows - leaf_rows) * cfg.V * 4 / kernels_us["rd_accept_sample"] / 1e3, 1),
     }
 
+    # ---- the machine's floor for the dominant kernel: a plain streaming read of the same number of bytes,
+    # launched back to back over rotating buffers, best of a few workgroup counts
+    floor = None
+    if not args.no_floor:
+        nbytes = int(attn_bytes_mean) // 16 * 16
+        slab = torch.empty((R, nbytes), dtype=torch.uint8, device="cuda").fill_(1)
+        best = None
+        for wgs in (256, 512, 1024, 2048):
+            with torch.cuda.stream(stream):
+                for r in range(R):
+                    rd.rd_debug_stream_read(slab[r], wgs)
+                gf = None
+                if use_graph:                           # like the attention launches: R of them per replay
+                    gf = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(gf, stream=stream):
+                        for r in range(R):
+                            rd.rd_debug_stream_read(slab[r], wgs)
+                    gf.replay()
+                f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                reps = max(1, 660 // R)
+                f0.record(stream)
+                for _ in range(reps):
+                    if gf is not None:
+                        gf.replay()
+                    else:
+                        for r in range(R):
+                            rd.rd_debug_stream_read(slab[r], wgs)
+                f1.record(stream)
+            torch.cuda.synchronize()
+            us = f0.elapsed_time(f1) * 1e3 / (reps * R)
+            if best is None or us < best[0]:
+                best = (us, wgs)
+        del slab
+        floor = {"us_per_launch": round(best[0], 3), "workgroups": best[1], "bytes": nbytes,
+                 "GB/s": round(nbytes / best[0] / 1e3, 1), "launch": "hip_graph_replay" if use_graph else "eager"}
+
     draft = None if args.no_draft else time_draft(rd, cfg, stream, max(4, min(40, args.steps // 10)), torch)
 
     result = {
@@ -314,6 +351,7 @@ def main():
             "traffic": MEASURED_TRAFFIC_BYTES.get(args.config),
             "algorithmic_bytes_per_launch": round(attn_bytes_mean, 1),
             "us_per_launch": round(attn_us, 3),
+            "stream_read_floor": floor,
         },
     }
 

@@ -31,6 +31,7 @@ _vp, _i, _sz, _f = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t, ctypes.c_floa
 EXPORTS = {
     "rd_strerror": (ctypes.c_char_p, [_i]),
     "rd_version": (_i, []),
+    "rd_debug_stream_read": (_i, [_vp, _sz, _i, _vp, _vp]),
     "rd_dedup": (_i, [_vp, _vp, _i, _i, _i] + [_vp] * 8 + [_vp]),
     "rd_tree_attn_workspace": (_sz, [_i, _i, _i, _i, _i, _i]),
     "rd_tree_attn": (_i, [_vp] * 8 + [_i, _i, _i, _i, _i, _i, _f, _vp, _vp, _sz, _vp]),
@@ -203,6 +204,13 @@ def rd_tree_attn_paged(q, k_pages, v_pages, block_table, ctx_len, k_new, v_new, 
         workspace.numel(), _stream())
     _check(code, "rd_tree_attn_paged")
     return out
+
+
+def rd_debug_stream_read(src: torch.Tensor, workgroups: int, nbytes: Optional[int] = None) -> None:
+    """One launch that reads `src` (or its first nbytes) once and discards it: the streaming floor."""
+    n = src.numel() * src.element_size() if nbytes is None else int(nbytes)
+    _check(_lib.rd_debug_stream_read(_ptr(src, None, None, "src"), n, int(workgroups), None, _stream()),
+           "rd_debug_stream_read")
 
 
 def rd_accept_workspace(B: int, W: int, L: int, V: int) -> int:

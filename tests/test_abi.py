@@ -30,7 +30,7 @@ def _declared_symbols():
 
 def test_header_symbols_exported(lib):
     names = _declared_symbols()
-    assert names == sorted(["rd_strerror", "rd_version", "rd_dedup", "rd_tree_attn_workspace",
+    assert names == sorted(["rd_strerror", "rd_version", "rd_debug_stream_read", "rd_dedup", "rd_tree_attn_workspace",
                             "rd_tree_attn", "rd_tree_attn_paged_workspace", "rd_tree_attn_paged",
                             "rd_accept_workspace", "rd_accept", "rd_accept_sample_workspace", "rd_accept_sample", "rd_commit", "rd_commit_paged", "rd_rope",
                             "rd_draft_workspace", "rd_draft"])
@@ -113,6 +113,13 @@ def _accept(lib, B=1, W=4, L=4, V=100, logits=FAKE, req=FAKE, ws=FAKE, ws_bytes=
         ws_bytes = need
     return lib.rd_accept(logits, FAKE, FAKE, FAKE, None, B, W, L, V, req, req, req, req, req, req,
                          ws, ws_bytes, None)
+
+
+def test_stream_read_argument_errors(lib):
+    assert lib.rd_debug_stream_read(None, 1024, 4, None, None) == INVALID
+    assert lib.rd_debug_stream_read(FAKE, 8, 4, None, None) == INVALID
+    assert lib.rd_debug_stream_read(FAKE, 1024, 0, None, None) == INVALID
+    assert lib.rd_debug_stream_read(FAKE + 4, 1024, 4, None, None) == INVALID
 
 
 def test_accept_argument_errors(lib):
