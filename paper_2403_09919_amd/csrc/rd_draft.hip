@@ -29,7 +29,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 constexpr int kMaxRows = 512;          // B*W
 constexpr int kRowsPerLaunch = 128;    // rows of one linear-layer launch (8 MFMA row tiles)
 constexpr int kMaxBeam = 64;           // W
-constexpr int kMaxVocab = 32768;       // eight chunks of 4096 logits: one lane per chunk in the row pass
+constexpr int kMaxVocab = 262144;      // 64 chunks of 4096 logits: one lane per chunk in the row pass
 
 enum { EPI_HEAD = 0, EPI_RNN = 1, EPI_MLP = 2 };
 
@@ -241,7 +241,7 @@ __device__ __forceinline__ int first_lane(bool offer)
 constexpr int kChunk = 4096;            // logits per workgroup of the first top-W pass
 constexpr int kChunkThreads = 256;
 constexpr int kChunkPer = kChunk / kChunkThreads;
-constexpr int kMaxChunks = kMaxVocab / kChunk;
+static_assert(kMaxVocab / kChunk <= 64, "one lane per chunk in the row pass");
 
 // Compare-exchange of a sorting network on (value, position) pairs: the better pair goes to a.
 __device__ __forceinline__ void order_pair(float &va, int &ka, float &vb, int &kb)
@@ -370,28 +370,29 @@ __global__ __launch_bounds__(kChunkThreads) void rd_topw_chunk_kernel(const floa
     }
 }
 
-// Second pass, eight live candidate rows per wave (lane = row-in-wave * 8 + chunk): the row's
-// log-sum-exp from the chunk partials and its W best tokens as a merge of the chunks' sorted lists
-// (a lower chunk holds smaller tokens), written as cumulative scores
-// row_score[row][r] = cum[row] + log p(token r), best first, with the tokens beside them.
-constexpr int kRowsPerWave = 8;
-static_assert(kMaxChunks == 8, "one lane per chunk in groups of eight lanes");
+// Second pass, one lane per (row, chunk): the row's log-sum-exp from the chunk partials and its W best
+// tokens as a merge of the chunks' sorted lists (a lower chunk holds smaller tokens), written as
+// cumulative scores row_score[row][r] = cum[row] + log p(token r), best first, with the tokens beside
+// them.  LPR lanes serve a row: 8 (eight rows per wave) while the vocabulary has at most eight chunks,
+// else 64 (one row per wave).
+template <int LPR>
 __global__ __launch_bounds__(64) void rd_topw_row_kernel(
     const float *__restrict__ part_max, const float *__restrict__ part_sum, const float *__restrict__ part_cv,
     const int32_t *__restrict__ part_ci, int chunks, const float *__restrict__ cum_cur, int W, int n_rows, int mstride,
     float *__restrict__ row_score, int32_t *__restrict__ row_tok)
 {
-    __shared__ float s_cv[kRowsPerWave * kMaxChunks * kMaxBeam];
-    __shared__ int s_ci[kRowsPerWave * kMaxChunks * kMaxBeam];
-    const int lane = threadIdx.x, g = lane >> 3, c = lane & 7;
-    const int row_l = blockIdx.x * kRowsPerWave + g;                  // logical row of this lane's group
+    constexpr int kRows = 64 / LPR;                                   // rows per wave
+    __shared__ float s_cv[64 * kMaxBeam];                             // [row in wave][chunk][W], LPR * kMaxBeam per row
+    __shared__ int s_ci[64 * kMaxBeam];
+    const int lane = threadIdx.x, g = lane / LPR, c = lane % LPR;
+    const int row_l = blockIdx.x * kRows + g;                         // logical row of this lane's group
     const bool row_ok = row_l < n_rows;
     const size_t row = (size_t)(row_ok ? row_l : n_rows - 1) * mstride;
     const int n_surv = chunks * W;
-    // the survivors of the wave's rows -> LDS, [group][chunk][W]; eight loads per lane in flight
-    // together, addresses past the end pulled back (no load sits behind a branch)
+    // the survivors of the wave's rows -> LDS; eight loads per lane in flight together, addresses
+    // past the end pulled back (no load sits behind a branch)
     {
-        const int rows_here = min(kRowsPerWave, n_rows - blockIdx.x * kRowsPerWave);
+        const int rows_here = min(kRows, n_rows - blockIdx.x * kRows);
         const int total = rows_here * n_surv;
         for (int i0 = 0; i0 < total; i0 += 64 * 8) {
             float v[8];
@@ -400,7 +401,7 @@ __global__ __launch_bounds__(64) void rd_topw_row_kernel(
             for (int u = 0; u < 8; ++u) {
                 const int idx = min(i0 + u * 64 + lane, total - 1);
                 const int gg = idx / n_surv, q = idx - gg * n_surv;
-                const size_t src = (size_t)(blockIdx.x * kRowsPerWave + gg) * mstride * n_surv + q;
+                const size_t src = (size_t)(blockIdx.x * kRows + gg) * mstride * n_surv + q;
                 v[u] = part_cv[src];
                 ti[u] = part_ci[src];
             }
@@ -409,34 +410,39 @@ __global__ __launch_bounds__(64) void rd_topw_row_kernel(
                 const int idx = i0 + u * 64 + lane;
                 if (idx < total) {
                     const int gg = idx / n_surv, q = idx - gg * n_surv;
-                    s_cv[gg * kMaxChunks * kMaxBeam + q] = v[u];
-                    s_ci[gg * kMaxChunks * kMaxBeam + q] = ti[u];
+                    s_cv[gg * LPR * kMaxBeam + q] = v[u];
+                    s_ci[gg * LPR * kMaxBeam + q] = ti[u];
                 }
             }
         }
     }
+    auto group_max = [](float x) { return LPR == 8 ? group8_max(x) : wave_max(x); };
     // log-sum-exp of the row: sum_c part_sum[c] * exp(part_max[c] - max)
     const bool lane_ok = row_ok && c < chunks;
     const float pm = lane_ok ? part_max[row * chunks + c] : -INFINITY;
-    const float gm = group8_max(pm);
+    const float gm = group_max(pm);
     float ps = lane_ok ? part_sum[row * chunks + c] * __expf(pm - gm) : 0.f;
-    ps += __shfl_xor(ps, 1, 64);
-    ps += __shfl_xor(ps, 2, 64);
-    ps += __shfl_xor(ps, 4, 64);
+#pragma unroll
+    for (int off = 1; off < LPR; off <<= 1) ps += __shfl_xor(ps, off, 64);
     const float lse = gm + __logf(ps);
     const float base = row_ok ? cum_cur[row] : 0.f;
     __syncthreads();
 
-    const float *lv = s_cv + g * kMaxChunks * kMaxBeam + c * W;      // this lane's list: chunk c of its row
-    const int *li = s_ci + g * kMaxChunks * kMaxBeam + c * W;
+    const float *lv = s_cv + g * LPR * kMaxBeam + c * W;              // this lane's list: chunk c of its row
+    const int *li = s_ci + g * LPR * kMaxBeam + c * W;
     int ptr = 0;
     bool live = lane_ok && li[0] != 0x7fffffff;
     float hv = live ? lv[0] : -INFINITY;
     for (int r = 0; r < W; ++r) {
-        const float best = group8_max(live ? hv : -INFINITY);
+        const float best = group_max(live ? hv : -INFINITY);
         const unsigned long long offers = __ballot(live && hv == best);
-        const unsigned mine = (unsigned)(offers >> (g * 8)) & 0xffu;   // offers of this lane's group
-        const int win = mine ? __ffs((int)mine) - 1 : -1;             // chunk that wins in this group
+        int win;                                                      // chunk that wins in this lane's group
+        if (LPR == 8) {
+            const unsigned mine = (unsigned)(offers >> (g * 8)) & 0xffu;
+            win = mine ? __ffs((int)mine) - 1 : -1;
+        } else {
+            win = offers ? __ffsll((long long)offers) - 1 : -1;
+        }
         if (c == 0 && row_ok) {
             row_score[row * W + r] = win >= 0 ? base + (best - lse) : -INFINITY;
         }
@@ -550,10 +556,11 @@ Plan draft_plan(int B, int W, int L, int Dm, int V)
     for (int i = 0; i < 3; ++i) { p.x_f32[i] = take(M * G * 4); p.x_bf[i] = take(M * G * 2); }
     for (int i = 0; i < 2; ++i) p.s_bf[i] = take(M * Dm * 2);
     p.logits = take(M * (size_t)V * 4);
-    p.part_max = take(M * kMaxChunks * 4);
-    p.part_sum = take(M * kMaxChunks * 4);
-    p.part_cv = take(M * kMaxChunks * W * 4);
-    p.part_ci = take(M * kMaxChunks * W * 4);
+    const size_t chunks = ((size_t)V + kChunk - 1) / kChunk;
+    p.part_max = take(M * chunks * 4);
+    p.part_sum = take(M * chunks * 4);
+    p.part_cv = take(M * chunks * W * 4);
+    p.part_ci = take(M * chunks * W * 4);
     p.row_score = take(M * W * 4);
     p.row_tok = take(M * W * 4);
     for (int i = 0; i < 2; ++i) { p.paths[i] = take(M * L * 4); p.cum[i] = take(M * 4); }
@@ -725,8 +732,12 @@ extern "C" int rd_draft(const rd_draft_params *p, const void *h, const int32_t *
                            part_max, part_sum, part_cv, part_ci);
         if (rd_check_launch() != RD_OK) return RD_ERR_HIP;
         const bool last = t == T;
-        hipLaunchKernelGGL(rd_topw_row_kernel, dim3((rows + kRowsPerWave - 1) / kRowsPerWave), dim3(64), 0, s, part_max, part_sum,
-                           part_cv, part_ci, chunks, cum[cur], W, rows, mstride, row_score, row_tok);
+        if (chunks <= 8)
+            hipLaunchKernelGGL(rd_topw_row_kernel<8>, dim3((rows + 7) / 8), dim3(64), 0, s, part_max, part_sum, part_cv, part_ci,
+                               chunks, cum[cur], W, rows, mstride, row_score, row_tok);
+        else
+            hipLaunchKernelGGL(rd_topw_row_kernel<64>, dim3(rows), dim3(64), 0, s, part_max, part_sum, part_cv, part_ci,
+                               chunks, cum[cur], W, rows, mstride, row_score, row_tok);
         if (rd_check_launch() != RD_OK) return RD_ERR_HIP;
         hipLaunchKernelGGL(rd_beam_step_kernel, dim3(B), dim3(64), 0, s, row_score, row_tok, V, W, L, t,
                            t == 1 ? 1 : W, paths[cur], paths[nxt], cum[nxt], parent + (size_t)(t - 1) * M, tok,

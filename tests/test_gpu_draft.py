@@ -81,7 +81,10 @@ def check(rd, p, h, last, W, L, what):
                                           # every token of the vocabulary is a candidate; the most rows; the shortest draft
                                           (64, 16, 1, 2, 16, 3), (64, 200, 0, 16, 32, 2), (64, 40, 1, 3, 5, 2),
                                           # output layers wide enough for workgroups of 128 columns
-                                          (64, 31000, 1, 3, 8, 3), (64, 32768, 0, 5, 8, 2)])
+                                          (64, 31000, 1, 3, 8, 3), (64, 32768, 0, 5, 8, 2),
+                                          # vocabularies of more than eight chunks of 4096 (one row per wave in the row pass)
+                                          (64, 40000, 1, 2, 8, 3), (64, 70001, 0, 1, 4, 3), (64, 151936, 0, 2, 16, 2),
+                                          (64, 262144, 0, 1, 2, 2)])
 def test_draft_matches_oracle(rd, Dm, V, K, B, W, L):
     announce(f"draft Dm={Dm} V={V} K={K} B={B} W={W} L={L}")
     p = make_params(V, Dm, K, seed=Dm + V, scale=4.0)
