@@ -227,3 +227,49 @@ def test_step_layout_equals_packed_layout():
     for k in want:
         assert np.array_equal(want[k], got[k]), k
     assert (want["best_len"] < L).any() and (want["best_len"] > 1).any()
+
+
+def test_two_generated_tokens_follow_the_llm_joint_distribution():
+    """Multi-token guarantee of speculative sampling: with the drafted tokens drawn autoregressively from
+    q, the tokens a decoding loop emits are distributed as the LLM's own autoregressive process.  A toy
+    first-order LM (logits = a table row of the previous token) drafts two tokens per step; the joint
+    distribution of the first two generated tokens must be p(a | x0) p(b | a)."""
+    rng = np.random.default_rng(21)
+    V, B, t, x0 = 4, 400_000, 0.8, 2
+    Tp = (rng.standard_normal((V, V)) * 1.2).astype(np.float32)
+    Tq = (Tp + rng.standard_normal((V, V)) * 0.9).astype(np.float32)
+    P = softmax(Tp.astype(np.float64) / t, axis=1)
+    Q = softmax(Tq.astype(np.float64), axis=1)
+
+    def draw(prob_rows):                                         # one sample per row of probabilities
+        c = np.cumsum(prob_rows, axis=1)
+        return (rng.random((len(prob_rows), 1)) * c[:, -1:] >= c).sum(axis=1).clip(0, V - 1).astype(np.int32)
+
+    def step(prev):
+        """One decoding step for every sequence: returns (number of tokens emitted, [n,3] tokens)."""
+        x1 = draw(Q[prev])
+        x2 = draw(Q[x1])
+        beams = np.stack([prev, x1, x2], axis=1)[:, None, :].astype(np.int32)
+        ui = np.tile(np.array([[0, 1, 2]], np.int32), (len(prev), 1, 1))
+        logits = np.stack([Tp[prev], Tp[x1], Tp[x2]], axis=1)
+        draft = np.stack([Tq[prev], Tq[x1], np.full((len(prev), V), np.nan, np.float32)], axis=1)
+        r = oracle.accept_sample(logits, draft, beams, ui, rng.random((len(prev), 3), dtype=np.float32),
+                                 rng.random(len(prev), dtype=np.float32), t)
+        bl = r["best_len"]
+        out = np.stack([np.where(bl >= 2, x1, r["next_token"]),
+                        np.where(bl >= 3, x2, r["next_token"]), r["next_token"]], axis=1)
+        return bl, out                                           # bl tokens emitted: out[:, :bl]
+
+    prev = np.full(B, x0, np.int32)
+    n1, e = step(prev)
+    a = e[:, 0]
+    b = e[:, 1].copy()
+    short = n1 == 1                                              # only one token came out: run another step from it
+    _, e2 = step(a[short])
+    b[short] = e2[:, 0]
+    joint = np.zeros((V, V))
+    np.add.at(joint, (a, b), 1.0)
+    joint /= B
+    want = P[x0][:, None] * P
+    assert np.abs(joint - want).max() < 4.5 * np.sqrt(0.25 / B)
+    assert 0.15 < short.mean() < 0.85                            # both outcomes of the first test are exercised
