@@ -98,7 +98,7 @@ static inline AttnPlan attn_plan(int B, int H, int N, int D, int Cmax, size_t el
     p.rows_pad = (N + 15) / 16 * 16;
     p.rg_tiles = nq;
     p.n_rg = n_rg;
-    p.counters_bytes = ((size_t)BH * n_rg * sizeof(uint32_t) + 255) / 256 * 256;
+    p.counters_bytes = ((size_t)BH * n_rg * sizeof(unsigned long long) + 255) / 256 * 256;
     // floats per partial: fp32 kernel m[rows_pad] + l[rows_pad] + O[rows_pad][D] per (b,h,part);
     // bf16 kernel the same for the rows of one group, per (b,h,group,part)
     p.partial_floats = elem_bytes == 2 ? (size_t)nq * 16 * (2 + D) : (size_t)p.rows_pad * (2 + D);
@@ -128,7 +128,7 @@ struct AttnArgs {
     int page_size, max_pages, n_pages;
     const uint64_t *mask_bits;
     void *out;
-    uint32_t *counters;
+    unsigned long long *counters;
     float *partials;
     int B, H, N, Cmax, S, words, rows_pad;
     int n_rg;      // row groups per (sequence, head) (bf16 kernel; each is NQ*16 rows of the template)
@@ -215,20 +215,26 @@ __device__ __forceinline__ uint32_t xcc_id() { return __builtin_amdgcn_s_getreg(
 enum { kNotLast = 0, kLastClean = 1, kLastMixed = 2 };
 
 // Signals that this workgroup's partial is stored (with st_dev*); tells every thread of the
-// workgroup whether it arrived last among `expected` for this (sequence, head).  `off_xcd` is
-// nonzero if this workgroup found itself on another XCD than the work mapping assumes; the last
-// arriver learns (kLastMixed) if that happened to any of them, and must then read the partials
-// with ld_dev* rather than through its own L2.
-__device__ __forceinline__ int arrive_is_last(uint32_t *counter, uint32_t expected, uint32_t off_xcd = 0)
+// workgroup whether it arrived last among `expected` for this (sequence, head).  The last arriver
+// also learns whether every contributor ran on its own XCD (kLastClean: the partials are then
+// current in its L2, which is coherent within an XCD) or not (kLastMixed: it must read them with
+// ld_dev*, past its L2, which may still hold an older call's lines).  No assumption is made about
+// which XCD a workgroup lands on: the 64-bit word collects, beside the count (bits 0-15), the sum
+// (bits 16-31) and the sum of squares (bits 32-63) of the contributors' XCD numbers, and n values
+// are all equal to x exactly if their sum is n*x and their sum of squares n*x*x.
+__device__ __forceinline__ int arrive_is_last(unsigned long long *counter, uint32_t expected)
 {
     __shared__ uint32_t s_last;
     wait_dev_stores();
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // waits until this thread's stores are acknowledged
     __syncthreads();
     if (threadIdx.x == 0) {
-        const uint32_t add = 1u + (off_xcd ? 0x10000u : 0u);
-        const uint32_t now = __hip_atomic_fetch_add(counter, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + add;
-        s_last = ((now & 0xffffu) == expected) ? ((now >> 16) ? kLastMixed : kLastClean) : kNotLast;
+        const unsigned long long x = xcc_id();
+        const unsigned long long add = 1ull | (x << 16) | ((x * x) << 32);
+        const unsigned long long now = __hip_atomic_fetch_add(counter, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + add;
+        const unsigned long long n = now & 0xffffull;
+        const bool same = ((now >> 16) & 0xffffull) == n * x && (now >> 32) == n * x * x;
+        s_last = (n == expected) ? (same ? kLastClean : kLastMixed) : kNotLast;
     }
     __syncthreads();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");   // later loads stay after the counter update

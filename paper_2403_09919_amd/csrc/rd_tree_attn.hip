@@ -44,7 +44,7 @@ extern "C" int rd_tree_attn(const void *q, const void *k_cache, const void *v_ca
     rd::AttnArgs a;
     a.q = q; a.k_cache = k_cache; a.v_cache = v_cache; a.k_new = k_new; a.v_new = v_new;
     a.ctx_len = ctx_len; a.n_packed = n_packed; a.mask_bits = tree_mask_bits; a.out = out;
-    a.counters = static_cast<uint32_t *>(workspace);
+    a.counters = static_cast<unsigned long long *>(workspace);
     a.partials = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + plan.counters_bytes);
     a.B = B; a.H = H; a.N = N; a.Cmax = Cmax; a.S = plan.S; a.words = (N + 63) / 64; a.rows_pad = plan.rows_pad;
     a.scale_log2e = scale * 1.44269504088896340736f;
@@ -95,7 +95,7 @@ extern "C" int rd_tree_attn_paged(const void *q, const void *k_pages, const void
     a.q = q; a.k_cache = k_pages; a.v_cache = v_pages; a.k_new = k_new; a.v_new = v_new;
     a.ctx_len = ctx_len; a.n_packed = n_packed; a.mask_bits = tree_mask_bits; a.out = out;
     a.block_table = block_table; a.page_size = page_size; a.max_pages = max_pages; a.n_pages = n_pages;
-    a.counters = static_cast<uint32_t *>(workspace);
+    a.counters = static_cast<unsigned long long *>(workspace);
     a.partials = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + plan.counters_bytes);
     a.B = B; a.H = H; a.N = N; a.Cmax = Cmax; a.S = plan.S; a.words = (N + 63) / 64; a.rows_pad = plan.rows_pad;
     a.scale_log2e = scale * 1.44269504088896340736f;

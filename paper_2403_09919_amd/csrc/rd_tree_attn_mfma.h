@@ -588,11 +588,8 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
     // ---- last workgroup of this (sequence, head) merges and writes the output ---------------------
     // With the XCD-aligned mapping every producer of this head ran on this XCD, so their
     // write-through stores also updated this XCD's L2 and plain (cached, 16-byte) loads see them.
-    // Each workgroup checks the XCD it really runs on; if any of them was elsewhere, or the mapping
-    // is off, the merge reads with device-scope loads instead.
     RD_TR(4);
-    const uint32_t off_xcd = (!a.xcd_remap || xcc_id() != (blockIdx.x & 7u)) ? 1u : 0u;
-    const int last = arrive_is_last(a.counters + unit, (uint32_t)n_part, off_xcd);
+    const int last = arrive_is_last(a.counters + unit, (uint32_t)n_part);
     RD_TR(5);
     if (last == kNotLast) return;
     const bool cached = (last == kLastClean);
