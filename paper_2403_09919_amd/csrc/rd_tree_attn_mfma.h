@@ -593,6 +593,7 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
     RD_TR(5);
     if (last == kNotLast) return;
     const bool cached = (last == kLastClean);
+    RD_TR(11);
 #ifdef RD_TRACE
     if (tid == 0 && rd_trace_buf) rd_trace_buf[(size_t)blockIdx.x * 16 + 13] = 1000 + last * 10 + xcc_id();
 #endif
@@ -653,6 +654,7 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
                         }
                     }
                 }
+                if (qt0 == 0 && s0 == 0) RD_TR(12);
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
                     float Mn = M[u];
