@@ -265,30 +265,36 @@ def rope(x, position_ids, n_packed, cos_tab, sin_tab, dtype: str) -> np.ndarray:
     return x
 
 
-def _draft_args(params, h, Dm):
-    emb = np.ascontiguousarray(params["emb"], np.uint16)
+def _bits16(x, dtype: str) -> np.ndarray:
+    """16-bit storage as bit patterns: bf16 arrives as uint16 bit patterns, float16 as numpy float16."""
+    if dtype == "f16":
+        return np.ascontiguousarray(x, np.float16).view(np.uint16)
+    return np.ascontiguousarray(x, np.uint16)
+
+
+def _draft_args(params, h, Dm, dtype):
+    emb = _bits16(params["emb"], dtype)
     V = emb.shape[0]
-    mlp_w = np.ascontiguousarray(params["mlp_w"], np.uint16)
+    mlp_w = _bits16(params["mlp_w"], dtype)
     n_mlp = mlp_w.shape[0]
     assert emb.shape == (V, Dm) and params["rnn_u"].shape == (Dm, Dm) and params["rnn_w"].shape == (Dm, Dm)
     assert mlp_w.shape == (n_mlp, 2 * Dm, 2 * Dm) and params["head_w"].shape == (V, 2 * Dm)
-    arrs = dict(emb=emb, rnn_u=np.ascontiguousarray(params["rnn_u"], np.uint16),
-                rnn_w=np.ascontiguousarray(params["rnn_w"], np.uint16),
+    arrs = dict(emb=emb, rnn_u=_bits16(params["rnn_u"], dtype), rnn_w=_bits16(params["rnn_w"], dtype),
                 rnn_b=np.ascontiguousarray(params["rnn_b"], np.float32), mlp_w=mlp_w,
                 mlp_b=np.ascontiguousarray(params["mlp_b"], np.float32),
-                head_w=np.ascontiguousarray(params["head_w"], np.uint16),
-                h=np.ascontiguousarray(h, np.uint16))
+                head_w=_bits16(params["head_w"], dtype), h=_bits16(h, dtype))
     return arrs, V, n_mlp
 
 
-def draft(params: dict, h, last_token, W: int, L: int, steps: bool = False) -> dict:
-    """Draft model + beam search (Sec. 3.1, 3.2).  params: bf16 bit patterns emb [V,Dm], rnn_u, rnn_w
-    [Dm,Dm], mlp_w [K,2Dm,2Dm], head_w [V,2Dm]; float32 rnn_b [Dm], mlp_b [K,2Dm].  h bf16 bits [B,Dm],
+def draft(params: dict, h, last_token, W: int, L: int, steps: bool = False, dtype: str = "bf16") -> dict:
+    """Draft model + beam search (Sec. 3.1, 3.2).  params: bf16 bit patterns (dtype "f16": numpy float16)
+    emb [V,Dm], rnn_u, rnn_w [Dm,Dm], mlp_w [K,2Dm,2Dm], head_w [V,2Dm]; float32 rnn_b [Dm], mlp_b
+    [K,2Dm].  h of the same 16-bit type [B,Dm],
     last_token int32 [B].  Returns beams int32 [B,W,L] (position 0 = last_token) and beam_logp [B,W];
     with `steps` also step_logp float32 [L-1,B*W,V] (the log-probabilities computed during the search) and
     step_row int32 [B,W,L-1] (the row of step t-1 behind token t of final candidate w)."""
     B, Dm = np.asarray(h).shape
-    a, V, n_mlp = _draft_args(params, h, Dm)
+    a, V, n_mlp = _draft_args(params, h, Dm, dtype)
     last_token = _i32(last_token)
     assert 1 <= W <= V and L >= 1
     beams = np.empty((B, W, L), np.int32)
@@ -296,7 +302,7 @@ def draft(params: dict, h, last_token, W: int, L: int, steps: bool = False) -> d
     step_logp = np.zeros((max(L - 1, 0), B * W, V), np.float32) if steps else None
     step_row = np.zeros((B, W, max(L - 1, 0)), np.int32) if steps else None
     lib().orc_draft(_p(a["emb"]), _p(a["rnn_u"]), _p(a["rnn_w"]), _p(a["rnn_b"]), _p(a["mlp_w"]), _p(a["mlp_b"]),
-                    n_mlp, _p(a["head_w"]), _p(a["h"]), _p(last_token), B, Dm, V, W, L, _p(beams), _p(logp),
+                    n_mlp, _p(a["head_w"]), _p(a["h"]), _p(last_token), B, Dm, V, W, L, DTYPES[dtype], _p(beams), _p(logp),
                     _p(step_logp), _p(step_row))
     out = {"beams": beams, "beam_logp": logp}
     if steps:
@@ -304,15 +310,15 @@ def draft(params: dict, h, last_token, W: int, L: int, steps: bool = False) -> d
     return out
 
 
-def draft_path_logp(params: dict, h, paths) -> np.ndarray:
+def draft_path_logp(params: dict, h, paths, dtype: str = "bf16") -> np.ndarray:
     """Cumulative log probability (float64 [B,n]) of candidate paths int32 [B,n,L] under the draft model."""
     B, Dm = np.asarray(h).shape
-    a, V, n_mlp = _draft_args(params, h, Dm)
+    a, V, n_mlp = _draft_args(params, h, Dm, dtype)
     paths = _i32(paths)
     n, L = paths.shape[1:]
     out = np.empty((B, n), np.float64)
     lib().orc_draft_path_logp(_p(a["emb"]), _p(a["rnn_u"]), _p(a["rnn_w"]), _p(a["rnn_b"]), _p(a["mlp_w"]),
-                              _p(a["mlp_b"]), n_mlp, _p(a["head_w"]), _p(a["h"]), _p(paths), B, n, Dm, V, L, _p(out))
+                              _p(a["mlp_b"]), n_mlp, _p(a["head_w"]), _p(a["h"]), _p(paths), B, n, Dm, V, L, DTYPES[dtype], _p(out))
     return out
 
 

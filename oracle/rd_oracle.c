@@ -517,7 +517,8 @@ void orc_rope(void *x, const int32_t *position_ids /*[B,N]*/, const int32_t *n_p
  * candidates are its W most probable tokens.
  *
  * Numerics (the precision contract shared with the device code): weights, embeddings and h
- * are bf16; every linear layer reads its input vector rounded to bf16 and accumulates
+ * are bf16 (or float16, the type of the paper's MLX runs, App. A.2); every linear layer reads its
+ * input vector rounded to that type and accumulates
  * without further rounding; biases, activation, skip connection, log-softmax and scores
  * are computed on unrounded values.  Here that arithmetic is double.
  * Weights are row-major [out][in]: rnn_u, rnn_w [Dm][Dm]; mlp_w [n_mlp][2Dm][2Dm];
@@ -529,19 +530,27 @@ static double bf16_to_double(uint16_t b)
     memcpy(&f, &u, 4);
     return (double)f;
 }
-static double round_bf16(double x) { return bf16_to_double(double_to_bf16(x)); }
 static double silu(double x) { return x / (1.0 + exp(-x)); }
+/* the 16-bit storage type of the draft model: bf16 or, as in the paper's MLX runs (App. A.2), float16 */
+static double w16_to_double(uint16_t v, int dtype)
+{
+    return dtype == ORC_F16 ? load_elem(&v, 0, ORC_F16) : bf16_to_double(v);
+}
+static double round16(double x, int dtype)
+{
+    return dtype == ORC_F16 ? w16_to_double(double_to_f16(x), ORC_F16) : bf16_to_double(double_to_bf16(x));
+}
 
-/* y[n] = sum_k round_bf16(x[k]) * W[n][k] (+ bias[n]) */
-static void linear_bf16(const uint16_t *Wt, const float *bias, int N, int K, const double *x, double *y)
+/* y[n] = sum_k round16(x[k]) * W[n][k] (+ bias[n]) */
+static void linear16(const uint16_t *Wt, const float *bias, int N, int K, const double *x, double *y, int dtype)
 {
     double *xr = (double *)malloc(sizeof(double) * (size_t)K);
-    for (int k = 0; k < K; ++k) xr[k] = round_bf16(x[k]);
+    for (int k = 0; k < K; ++k) xr[k] = round16(x[k], dtype);
 #pragma omp parallel for schedule(static)
     for (int n = 0; n < N; ++n) {
         const uint16_t *row = Wt + (size_t)n * K;
         double acc = 0.0;
-        for (int k = 0; k < K; ++k) acc += xr[k] * bf16_to_double(row[k]);
+        for (int k = 0; k < K; ++k) acc += xr[k] * w16_to_double(row[k], dtype);
         y[n] = acc + (bias ? (double)bias[n] : 0.0);
     }
     free(xr);
@@ -549,17 +558,17 @@ static void linear_bf16(const uint16_t *Wt, const float *bias, int N, int K, con
 
 /* log-probabilities of the next token given RNN state s and hidden h; lp has V entries */
 static void draft_logp(const uint16_t *mlp_w, const float *mlp_b, int n_mlp, const uint16_t *head_w,
-                       const double *s, const double *h, int Dm, int V, double *lp)
+                       const double *s, const double *h, int Dm, int V, double *lp, int dtype)
 {
     const int G = 2 * Dm;
     double *x = (double *)malloc(sizeof(double) * (size_t)G);
     double *y = (double *)malloc(sizeof(double) * (size_t)G);
     for (int i = 0; i < Dm; ++i) { x[i] = s[i]; x[Dm + i] = h[i]; }
     for (int k = 0; k < n_mlp; ++k) {
-        linear_bf16(mlp_w + (size_t)k * G * G, mlp_b ? mlp_b + (size_t)k * G : NULL, G, G, x, y);
+        linear16(mlp_w + (size_t)k * G * G, mlp_b ? mlp_b + (size_t)k * G : NULL, G, G, x, y, dtype);
         for (int i = 0; i < G; ++i) x[i] += silu(y[i]);
     }
-    linear_bf16(head_w, NULL, V, G, x, lp);
+    linear16(head_w, NULL, V, G, x, lp, dtype);
     double m = -INFINITY, sum = 0.0;
     for (int v = 0; v < V; ++v) if (lp[v] > m) m = lp[v];
     for (int v = 0; v < V; ++v) sum += exp(lp[v] - m);
@@ -571,14 +580,14 @@ static void draft_logp(const uint16_t *mlp_w, const float *mlp_b, int n_mlp, con
 
 /* s_next = f(U s + W e(token) + b) */
 static void draft_rnn(const uint16_t *emb, const uint16_t *rnn_u, const uint16_t *rnn_w, const float *rnn_b,
-                      const double *s, int token, int Dm, double *s_next)
+                      const double *s, int token, int Dm, double *s_next, int dtype)
 {
     double *e = (double *)calloc((size_t)Dm, sizeof(double));
     double *a = (double *)malloc(sizeof(double) * (size_t)Dm);
     double *c = (double *)malloc(sizeof(double) * (size_t)Dm);
-    for (int i = 0; i < Dm; ++i) e[i] = bf16_to_double(emb[(size_t)token * Dm + i]);
-    linear_bf16(rnn_u, NULL, Dm, Dm, s, a);
-    linear_bf16(rnn_w, rnn_b, Dm, Dm, e, c);
+    for (int i = 0; i < Dm; ++i) e[i] = w16_to_double(emb[(size_t)token * Dm + i], dtype);
+    linear16(rnn_u, NULL, Dm, Dm, s, a, dtype);
+    linear16(rnn_w, rnn_b, Dm, Dm, e, c, dtype);
     for (int i = 0; i < Dm; ++i) s_next[i] = silu(a[i] + c[i]);
     free(e);
     free(a);
@@ -587,8 +596,8 @@ static void draft_rnn(const uint16_t *emb, const uint16_t *rnn_u, const uint16_t
 
 void orc_draft(const uint16_t *emb, const uint16_t *rnn_u, const uint16_t *rnn_w, const float *rnn_b,
                const uint16_t *mlp_w, const float *mlp_b, int n_mlp, const uint16_t *head_w,
-               const uint16_t *h /*[B][Dm] bf16*/, const int32_t *last_token /*[B]*/,
-               int B, int Dm, int V, int W, int L,
+               const uint16_t *h /*[B][Dm]*/, const int32_t *last_token /*[B]*/,
+               int B, int Dm, int V, int W, int L, int dtype /* ORC_BF16 or ORC_F16: weights, embeddings, h */,
                int32_t *beams /*[B][W][L]*/, float *beam_logp /*[B][W]*/,
                float *step_logp /*[L-1][B*W][V] or NULL*/, int32_t *step_row /*[B][W][L-1] or NULL*/)
 {
@@ -609,8 +618,8 @@ void orc_draft(const uint16_t *emb, const uint16_t *rnn_u, const uint16_t *rnn_w
     unsigned char *taken = (unsigned char *)malloc((size_t)W * V);
     for (int b = 0; b < B; ++b) {
         for (int i = 0; i < Dm; ++i) {
-            hd[i] = bf16_to_double(h[(size_t)b * Dm + i]);
-            s[i] = bf16_to_double(emb[(size_t)last_token[b] * Dm + i]);
+            hd[i] = w16_to_double(h[(size_t)b * Dm + i], dtype);
+            s[i] = w16_to_double(emb[(size_t)last_token[b] * Dm + i], dtype);
         }
         int live = 1;
         cum[0] = 0.0;
@@ -618,7 +627,7 @@ void orc_draft(const uint16_t *emb, const uint16_t *rnn_u, const uint16_t *rnn_w
         for (int w = 0; w < W; ++w) { beam_logp[(size_t)b * W + w] = 0.f; for (int j = 0; j < L; ++j) beams[((size_t)b * W + w) * L + j] = last_token[b]; }
         for (int t = 1; t <= T; ++t) {
             for (int w = 0; w < live; ++w)
-                draft_logp(mlp_w, mlp_b, n_mlp, head_w, s + (size_t)w * Dm, hd, Dm, V, lp + (size_t)w * V);
+                draft_logp(mlp_w, mlp_b, n_mlp, head_w, s + (size_t)w * Dm, hd, Dm, V, lp + (size_t)w * V, dtype);
             if (step_logp)
                 for (int w = 0; w < live; ++w)
                     for (int v = 0; v < V; ++v)
@@ -639,7 +648,7 @@ void orc_draft(const uint16_t *emb, const uint16_t *rnn_u, const uint16_t *rnn_w
                 path2[(size_t)r * L + t] = bv;
                 memcpy(rows2 + (size_t)r * T, rows + (size_t)bw * T, sizeof(int32_t) * (size_t)(t - 1));
                 rows2[(size_t)r * T + t - 1] = b * W + bw;
-                if (t < T) draft_rnn(emb, rnn_u, rnn_w, rnn_b, s + (size_t)bw * Dm, bv, Dm, s2 + (size_t)r * Dm);
+                if (t < T) draft_rnn(emb, rnn_u, rnn_w, rnn_b, s + (size_t)bw * Dm, bv, Dm, s2 + (size_t)r * Dm, dtype);
             }
             live = W;
             memcpy(cum, cum2, sizeof(double) * (size_t)W);
@@ -662,7 +671,7 @@ void orc_draft(const uint16_t *emb, const uint16_t *rnn_u, const uint16_t *rnn_w
  * paths [B][n_paths][L] with position 0 the LLM's token; out [B][n_paths].               */
 void orc_draft_path_logp(const uint16_t *emb, const uint16_t *rnn_u, const uint16_t *rnn_w, const float *rnn_b,
                          const uint16_t *mlp_w, const float *mlp_b, int n_mlp, const uint16_t *head_w,
-                         const uint16_t *h, const int32_t *paths, int B, int n_paths, int Dm, int V, int L,
+                         const uint16_t *h, const int32_t *paths, int B, int n_paths, int Dm, int V, int L, int dtype,
                          double *out)
 {
     double *hd = (double *)malloc(sizeof(double) * (size_t)Dm);
@@ -672,15 +681,15 @@ void orc_draft_path_logp(const uint16_t *emb, const uint16_t *rnn_u, const uint1
         for (int r = 0; r < n_paths; ++r) {
             const int32_t *p = paths + ((size_t)b * n_paths + r) * L;
             for (int i = 0; i < Dm; ++i) {
-                hd[i] = bf16_to_double(h[(size_t)b * Dm + i]);
-                s[i] = bf16_to_double(emb[(size_t)p[0] * Dm + i]);
+                hd[i] = w16_to_double(h[(size_t)b * Dm + i], dtype);
+                s[i] = w16_to_double(emb[(size_t)p[0] * Dm + i], dtype);
             }
             double total = 0.0;
             for (int t = 1; t < L; ++t) {
-                draft_logp(mlp_w, mlp_b, n_mlp, head_w, s, hd, Dm, V, lp);
+                draft_logp(mlp_w, mlp_b, n_mlp, head_w, s, hd, Dm, V, lp, dtype);
                 total += lp[p[t]];
                 if (t + 1 < L) {
-                    draft_rnn(emb, rnn_u, rnn_w, rnn_b, s, p[t], Dm, s2);
+                    draft_rnn(emb, rnn_u, rnn_w, rnn_b, s, p[t], Dm, s2, dtype);
                     memcpy(s, s2, sizeof(double) * (size_t)Dm);
                 }
             }

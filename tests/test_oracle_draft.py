@@ -12,33 +12,45 @@ import oracle
 from paper_2403_09919_amd import synth
 
 
-def make_params(V, Dm, K, seed, scale=1.0):
+def make_params(V, Dm, K, seed, scale=1.0, dtype="bf16"):
+    """Seeded draft-model weights in their 16-bit storage type: bf16 bit patterns or numpy float16."""
     rng = np.random.default_rng(seed)
     G = 2 * Dm
 
-    def bf(shape, s):
+    def w16(shape, s):
         x = rng.standard_normal(shape, dtype=np.float32)
         x *= np.float32(s)
-        return synth.f32_to_bf16_bits(x)
+        return x.astype(np.float16) if dtype == "f16" else synth.f32_to_bf16_bits(x)
 
     return dict(
-        emb=bf((V, Dm), 1.0),
-        rnn_u=bf((Dm, Dm), Dm ** -0.5),
-        rnn_w=bf((Dm, Dm), Dm ** -0.5),
+        emb=w16((V, Dm), 1.0),
+        rnn_u=w16((Dm, Dm), Dm ** -0.5),
+        rnn_w=w16((Dm, Dm), Dm ** -0.5),
         rnn_b=(0.1 * rng.standard_normal(Dm)).astype(np.float32),
-        mlp_w=bf((K, G, G), G ** -0.5),
+        mlp_w=w16((K, G, G), G ** -0.5),
         mlp_b=(0.1 * rng.standard_normal((K, G))).astype(np.float32),
-        head_w=bf((V, G), scale * G ** -0.5),
+        head_w=w16((V, G), scale * G ** -0.5),
     )
 
 
-def f64(bits):
-    return synth.bf16_bits_to_f32(bits).astype(np.float64)
+def make_h(B, Dm, seed, dtype="bf16"):
+    x = np.random.default_rng(seed).standard_normal((B, Dm)).astype(np.float32)
+    return x.astype(np.float16) if dtype == "f16" else synth.f32_to_bf16_bits(x)
 
 
-def rb(x):
-    """Round float64 values to bf16 (through float32, exact for these magnitudes' purposes)."""
-    return f64(synth.f32_to_bf16_bits(np.asarray(x, np.float64).astype(np.float32)))
+def f64(v):
+    """Exact upcast of 16-bit storage (bf16 bit patterns or numpy float16) to float64."""
+    if v.dtype == np.float16:
+        return v.astype(np.float64)
+    return synth.bf16_bits_to_f32(v).astype(np.float64)
+
+
+def rb(x, dtype="bf16"):
+    """Round float64 values to the 16-bit storage type (through float32, exact for these magnitudes' purposes)."""
+    x32 = np.asarray(x, np.float64).astype(np.float32)
+    if dtype == "f16":
+        return x32.astype(np.float16).astype(np.float64)
+    return f64(synth.f32_to_bf16_bits(x32))
 
 
 def silu(x):
@@ -48,9 +60,10 @@ def silu(x):
 class NumpyDrafter:
     """The draft model with library matrix products; operands of every product rounded to bf16."""
 
-    def __init__(self, p, h_bits):
-        self.p = {k: (f64(v) if v.dtype == np.uint16 else v.astype(np.float64)) for k, v in p.items()}
+    def __init__(self, p, h_bits, dtype="bf16"):
+        self.p = {k: (f64(v) if v.dtype in (np.uint16, np.float16) else v.astype(np.float64)) for k, v in p.items()}
         self.h = f64(h_bits)
+        self.dtype = dtype
 
     def start(self, token):
         return self.p["emb"][token]
@@ -58,11 +71,11 @@ class NumpyDrafter:
     def logp(self, s):
         x = np.concatenate([s, self.h])
         for k in range(self.p["mlp_w"].shape[0]):
-            x = x + silu(self.p["mlp_w"][k] @ rb(x) + self.p["mlp_b"][k])
-        return log_softmax(self.p["head_w"] @ rb(x))
+            x = x + silu(self.p["mlp_w"][k] @ rb(x, self.dtype) + self.p["mlp_b"][k])
+        return log_softmax(self.p["head_w"] @ rb(x, self.dtype))
 
     def step(self, s, token):
-        return silu(self.p["rnn_u"] @ rb(s) + self.p["rnn_w"] @ self.p["emb"][token] + self.p["rnn_b"])
+        return silu(self.p["rnn_u"] @ rb(s, self.dtype) + self.p["rnn_w"] @ self.p["emb"][token] + self.p["rnn_b"])
 
     def path_logp(self, path):
         s, total = self.start(path[0]), 0.0
@@ -200,3 +213,33 @@ def test_step_rows_hold_the_distribution_behind_every_candidate_token(seed):
                 s = m.step(s, path[j + 1])
             assert _close(total, float(r["beam_logp"][b, w]))
         assert (r["step_row"][b, :, 0] == b * W).all()            # one live state at the first position
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_float16_model_greedy_and_teacher_forcing(seed):
+    """The float16 storage type (App. A.2 runs its drafting in float16): width 1 = greedy decoding of
+    the numpy model whose products read float16 operands, and candidates of a wider beam carry their
+    teacher-forced scores."""
+    V, Dm, K, L = 60, 16, 2, 5
+    p = make_params(V, Dm, K, seed + 40, scale=3.0, dtype="f16")
+    h = make_h(2, Dm, seed + 50, "f16")
+    last = np.array([7, 33], np.int32)
+    r = oracle.draft(p, h, last, W=1, L=L, dtype="f16")
+    wide = oracle.draft(p, h, last, W=4, L=L, dtype="f16")
+    tf = oracle.draft_path_logp(p, h, wide["beams"], dtype="f16")
+    for b in range(2):
+        m = NumpyDrafter(p, h[b], "f16")
+        s, path, total = m.start(last[b]), [int(last[b])], 0.0
+        for t in range(1, L):
+            lp = m.logp(s)
+            v = int(np.argmax(lp))
+            total += lp[v]
+            path.append(v)
+            s = m.step(s, v)
+        assert r["beams"][b, 0].tolist() == path
+        assert _close(float(r["beam_logp"][b, 0]), total)
+        for w in range(4):
+            assert _close(m.path_logp(wide["beams"][b, w].tolist()), float(wide["beam_logp"][b, w]))
+            assert _close(float(tf[b, w]), float(wide["beam_logp"][b, w]))
+    bf = oracle.draft(make_params(V, Dm, K, seed + 40, scale=3.0), make_h(2, Dm, seed + 50), last, W=4, L=L)
+    assert not np.array_equal(bf["beam_logp"], wide["beam_logp"])      # the storage type does matter
