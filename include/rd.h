@@ -317,15 +317,15 @@ int rd_commit_paged(const void *k_new, const void *v_new, const int32_t *accepte
  *   beams[b][w] = [last_token[b], token_1, ..., token_{L-1}], best candidate first;
  *   beam_logp[b][w] = its cumulative log probability (0 when L == 1).
  *
- * Precision: weights, embeddings and h are bf16; every linear layer reads its input rounded to
- * bf16 and accumulates in fp32; biases, activation, skip connection, log-softmax, scores fp32.
+ * Precision: weights, embeddings and h are bf16 (or fp16, params.dtype; the paper's MLX runs draft in
+ * float16, App. A.2); every linear layer reads its input rounded to that type and accumulates in fp32; biases, activation, skip connection, log-softmax, scores fp32.
  * Two candidates whose scores differ by less than that arithmetic resolves may swap places
  * against an exact evaluation.
  *
  * rd_draft_params (a HOST struct of DEVICE pointers, all weights row-major [out][in], 16-byte
- * aligned): emb bf16 [V,Dm]; rnn_u, rnn_w bf16 [Dm,Dm]; rnn_b float [Dm]; mlp_w bf16
- * [n_mlp,2Dm,2Dm]; mlp_b float [n_mlp,2Dm]; head_w bf16 [V,2Dm].
- * h : bf16 [B,Dm];  last_token : int32 [B] (clamped to [0, V-1]);  beams : int32 [B,W,L];
+ * aligned): emb [V,Dm]; rnn_u, rnn_w [Dm,Dm]; rnn_b float [Dm]; mlp_w [n_mlp,2Dm,2Dm]; mlp_b float
+ * [n_mlp,2Dm]; head_w [V,2Dm]; the matrices and emb in the 16-bit type `dtype`.
+ * h : that type, [B,Dm];  last_token : int32 [B] (clamped to [0, V-1]);  beams : int32 [B,W,L];
  * beam_logp : float [B,W].
  * step_logits, step_row : both NULL, or the record of the search that rd_accept_sample takes:
  *   step_logits float [L-1][B*W][V], 16-byte aligned: the output layer's values (softmax of a row = the
@@ -345,6 +345,7 @@ typedef struct {
     const float *mlp_b;
     const void *head_w;
     int n_mlp, Dm, V;
+    rd_dtype dtype;          /* RD_BF16 or RD_F16: type of emb, rnn_u, rnn_w, mlp_w, head_w and of h */
 } rd_draft_params;
 
 size_t rd_draft_workspace(int B, int W, int L, int Dm, int V);

@@ -369,7 +369,7 @@ def rd_rope(q, k_new, position_ids, n_packed, cos_tab, sin_tab) -> None:
 
 class _DraftParams(ctypes.Structure):
     _fields_ = [("emb", _vp), ("rnn_u", _vp), ("rnn_w", _vp), ("rnn_b", _vp), ("mlp_w", _vp), ("mlp_b", _vp),
-                ("head_w", _vp), ("n_mlp", _i), ("Dm", _i), ("V", _i)]
+                ("head_w", _vp), ("n_mlp", _i), ("Dm", _i), ("V", _i), ("dtype", _i)]
 
 
 def rd_draft_workspace(B: int, W: int, L: int, Dm: int, V: int) -> int:
@@ -379,11 +379,13 @@ def rd_draft_workspace(B: int, W: int, L: int, Dm: int, V: int) -> int:
 def rd_draft(params: dict, h, last_token, W: int, L: int, out: Optional[dict] = None,
              workspace: Optional[torch.Tensor] = None, steps: bool = False) -> dict:
     """Draft model + beam search (see include/rd.h, rd_draft).  params: device tensors emb [V,Dm],
-    rnn_u, rnn_w [Dm,Dm], mlp_w [K,2Dm,2Dm], head_w [V,2Dm] (bfloat16), rnn_b [Dm], mlp_b [K,2Dm]
+    rnn_u, rnn_w [Dm,Dm], mlp_w [K,2Dm,2Dm], head_w [V,2Dm] (all bfloat16 or all float16), rnn_b [Dm], mlp_b [K,2Dm]
     (float32); h bfloat16 [B,Dm]; last_token int32 [B] -> dict(beams int32 [B,W,L], beam_logp [B,W]);
     with `steps` (or an `out` that holds them) also step_logits float32 [L-1,B*W,V] and step_row int32
     [B,W,L-1], the record of the search that rd_accept_sample takes."""
-    bf = torch.bfloat16
+    bf = params["emb"].dtype                  # bfloat16 or float16: the model's 16-bit storage type
+    if bf not in (torch.bfloat16, torch.float16):
+        raise ValueError("draft model weights must be bfloat16 or float16, got %s" % bf)
     V, Dm = params["emb"].shape
     K = params["mlp_w"].shape[0]
     B = h.shape[0]
@@ -393,7 +395,7 @@ def rd_draft(params: dict, h, last_token, W: int, L: int, out: Optional[dict] = 
         _ptr(params["rnn_w"], bf, (Dm, Dm), "rnn_w"), _ptr(params["rnn_b"], torch.float32, (Dm,), "rnn_b"),
         _ptr(params["mlp_w"], bf, (K, 2 * Dm, 2 * Dm), "mlp_w") if K else None,
         _ptr(params["mlp_b"], torch.float32, (K, 2 * Dm), "mlp_b") if K else None,
-        _ptr(params["head_w"], bf, (V, 2 * Dm), "head_w"), K, Dm, V)
+        _ptr(params["head_w"], bf, (V, 2 * Dm), "head_w"), K, Dm, V, RD_BF16 if bf == torch.bfloat16 else RD_F16)
     if out is None:
         out = dict(beams=torch.empty((B, W, L), dtype=torch.int32, device=dev),
                    beam_logp=torch.empty((B, W), dtype=torch.float32, device=dev))

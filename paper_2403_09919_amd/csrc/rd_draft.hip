@@ -25,6 +25,18 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+
+// The 16-bit storage type of the model (bf16 or fp16): eight-element vector and its MFMA.
+template <typename T> struct Elem16;
+template <> struct Elem16<__bf16> {
+    typedef bf16x8 vec8;
+    static __device__ __forceinline__ f32x4 mfma(vec8 a, vec8 b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0); }
+};
+template <> struct Elem16<_Float16> {
+    typedef f16x8 vec8;
+    static __device__ __forceinline__ f32x4 mfma(vec8 a, vec8 b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0); }
+};
 
 constexpr int kMaxRows = 512;          // B*W
 constexpr int kRowsPerLaunch = 128;    // rows of one linear-layer launch (8 MFMA row tiles)
@@ -33,10 +45,11 @@ constexpr int kMaxVocab = 262144;      // 64 chunks of 4096 logits: one lane per
 
 enum { EPI_HEAD = 0, EPI_RNN = 1, EPI_MLP = 2 };
 
+template <typename T>
 struct LinArgs {
     // Y = X1 W1^T (+ X2 W2^T) + bias;  W row-major [N][K]; X rows found through row maps
-    const __bf16 *w1, *w2;
-    const __bf16 *x1, *x2;             // row r of X1 is x1 + map1[r]*ldx1 (map NULL: r itself)
+    const T *w1, *w2;
+    const T *x1, *x2;             // row r of X1 is x1 + map1[r]*ldx1 (map NULL: r itself)
     const int32_t *map1, *map2;
     int ldx1, ldx2, K1, K2;            // K2 = 0: single product
     const float *bias;                 // [N] or NULL
@@ -45,8 +58,8 @@ struct LinArgs {
     int mstride;                       // logical row m of X (without a map), Y and res is physical row m*mstride
     // epilogue
     float *y_f32;                      // HEAD: logits [M][ldy];  RNN/MLP: activations fp32 [M][ldy]
-    __bf16 *y_bf;                      // RNN/MLP: the same rounded to bf16 [M][ldy]
-    __bf16 *s_bf;                      // RNN: next state [M][N]
+    T *y_bf;                           // RNN/MLP: the same rounded to the storage type [M][ldy]
+    T *s_bf;                           // RNN: next state [M][N]
     const float *res;                  // MLP: skip input fp32 [M][ldy]
     int ldy;
 };
@@ -56,8 +69,8 @@ __device__ __forceinline__ float silu(float x) { return x / (1.0f + __expf(-x));
 // One output tile (16 rows x 16 columns) leaves the kernel: bias, activation, skip connection and the
 // bf16 copy that the next layer reads.  Accumulator layout: element i of lane (r16, g) is output
 // column n_tile + 4g + i of logical row m_tile + r16.
-template <int EPI>
-__device__ __forceinline__ void linear_epilogue(const LinArgs &a, f32x4 v, int m_tile, int n_tile, int r16, int g)
+template <typename T, int EPI>
+__device__ __forceinline__ void linear_epilogue(const LinArgs<T> &a, f32x4 v, int m_tile, int n_tile, int r16, int g)
 {
     const int m = m_tile + r16;
     if (m >= a.M) return;
@@ -74,8 +87,8 @@ __device__ __forceinline__ void linear_epilogue(const LinArgs &a, f32x4 v, int m
             y = silu(y);
             if (EPI == EPI_MLP) y += a.res[o];
             a.y_f32[o] = y;
-            a.y_bf[o] = (__bf16)y;
-            if (EPI == EPI_RNN) a.s_bf[prow * a.N + n] = (__bf16)y;
+            a.y_bf[o] = (T)y;
+            if (EPI == EPI_RNN) a.s_bf[prow * a.N + n] = (T)y;
         }
     }
 }
@@ -85,9 +98,10 @@ __device__ __forceinline__ void linear_epilogue(const LinArgs &a, f32x4 v, int m
 // outweigh the weights it streams (their ratio is MT : NT) while the launch still covers the chip,
 // and NWV so that the launch has enough waves in flight to keep the HBM stream busy; every wave's
 // share of K is a whole number of 32-wide steps inside one of the two products.
-template <int MT, int NT, int NWV, int EPI>
-__global__ __launch_bounds__(NWV * 64) void rd_linear_kernel(LinArgs a)
+template <typename T, int MT, int NT, int NWV, int EPI>
+__global__ __launch_bounds__(NWV * 64) void rd_linear_kernel(LinArgs<T> a)
 {
+    typedef typename Elem16<T>::vec8 vec8;
     constexpr int kTiles = MT * NT;
     constexpr int kGroup = kTiles < 64 / NWV ? kTiles : 64 / NWV;     // tiles reduced per pass: <= 64 KB of LDS
     static_assert(kTiles % kGroup == 0, "tile groups must divide the tiles");
@@ -101,20 +115,20 @@ __global__ __launch_bounds__(NWV * 64) void rd_linear_kernel(LinArgs a)
     const int ks1 = a.K1 >> 5, ks = ks1 + (a.K2 >> 5);
     const int kb = (int)((long long)ks * wave / NWV), ke = (int)((long long)ks * (wave + 1) / NWV);
     const bool second = kb >= ks1;
-    const __bf16 *wbase = second ? a.w2 : a.w1;
+    const T *wbase = second ? a.w2 : a.w1;
     const int K = second ? a.K2 : a.K1;
     const int k_first = (second ? kb - ks1 : kb) * 32, steps = ke - kb;
-    const __bf16 *xbase = second ? a.x2 : a.x1;
+    const T *xbase = second ? a.x2 : a.x1;
     const int32_t *map = second ? a.map2 : a.map1;
     const int ldx = second ? a.ldx2 : a.ldx1;
 
-    const __bf16 *wp[NT];
+    const T *wp[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         const int nrow = min(n0 + nt * 16 + r16, a.N - 1);      // rows past N read the last row; never stored
         wp[nt] = wbase + (size_t)nrow * K + k_first + 8 * g;
     }
-    const __bf16 *xp[MT];
+    const T *xp[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int m = a.m0 + min(mt * 16 + r16, a.M - 1);
@@ -130,13 +144,13 @@ __global__ __launch_bounds__(NWV * 64) void rd_linear_kernel(LinArgs a)
     constexpr int U = MT + NT <= 3 ? 8 : (MT + NT <= 9 ? 4 : 2);   // k-steps in flight
     int s = 0;
     for (; s + U <= steps; s += U) {
-        bf16x8 wa[U][NT], xb[U][MT];
+        vec8 wa[U][NT], xb[U][MT];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) wa[u][nt] = *reinterpret_cast<const bf16x8 *>(wp[nt] + (s + u) * 32);
+            for (int nt = 0; nt < NT; ++nt) wa[u][nt] = *reinterpret_cast<const vec8 *>(wp[nt] + (s + u) * 32);
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) xb[u][mt] = *reinterpret_cast<const bf16x8 *>(xp[mt] + (s + u) * 32);
+            for (int mt = 0; mt < MT; ++mt) xb[u][mt] = *reinterpret_cast<const vec8 *>(xp[mt] + (s + u) * 32);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u)
@@ -144,18 +158,18 @@ __global__ __launch_bounds__(NWV * 64) void rd_linear_kernel(LinArgs a)
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt)
-                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[u][nt], xb[u][mt], acc[mt][nt], 0, 0, 0);
+                    acc[mt][nt] = Elem16<T>::mfma(wa[u][nt], xb[u][mt], acc[mt][nt]);
     }
     for (; s < steps; ++s) {
-        bf16x8 wa[NT];
+        vec8 wa[NT];
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) wa[nt] = *reinterpret_cast<const bf16x8 *>(wp[nt] + s * 32);
+        for (int nt = 0; nt < NT; ++nt) wa[nt] = *reinterpret_cast<const vec8 *>(wp[nt] + s * 32);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-            const bf16x8 xb = *reinterpret_cast<const bf16x8 *>(xp[mt] + s * 32);
+            const vec8 xb = *reinterpret_cast<const vec8 *>(xp[mt] + s * 32);
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
-                acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[nt], xb, acc[mt][nt], 0, 0, 0);
+                acc[mt][nt] = Elem16<T>::mfma(wa[nt], xb, acc[mt][nt]);
         }
     }
 
@@ -172,26 +186,28 @@ __global__ __launch_bounds__(NWV * 64) void rd_linear_kernel(LinArgs a)
 #pragma unroll
             for (int w = 1; w < NWV; ++w) v += s_part[w][j][lane];
             const int id = p * kGroup + j;
-            linear_epilogue<EPI>(a, v, (id / NT) * 16, n0 + (id % NT) * 16, r16, g);
+            linear_epilogue<T, EPI>(a, v, (id / NT) * 16, n0 + (id % NT) * 16, r16, g);
         }
     }
 }
 
 // rows m = b*W + w: X0 = [e(last token), h] (fp32 and bf16), state = e(last token), path = [last token]
-__global__ void rd_draft_init_kernel(const __bf16 *__restrict__ emb, const __bf16 *__restrict__ h,
+template <typename T>
+__global__ void rd_draft_init_kernel(const T *__restrict__ emb, const T *__restrict__ h,
                                      const int32_t *__restrict__ last_token, int W, int L, int Dm, int V,
-                                     float *__restrict__ x_f32, __bf16 *__restrict__ x_bf, __bf16 *__restrict__ s_bf,
+                                     float *__restrict__ x_f32, T *__restrict__ x_bf, T *__restrict__ s_bf,
                                      int32_t *__restrict__ paths, float *__restrict__ cum)
 {
     const int m = blockIdx.x, b = m / W;
     int tok = last_token[b];
     tok = tok < 0 ? 0 : (tok > V - 1 ? V - 1 : tok);
     for (int i = threadIdx.x * 8; i < Dm; i += blockDim.x * 8) {          // Dm is a multiple of 64
-        const bf16x8 e = *reinterpret_cast<const bf16x8 *>(emb + (size_t)tok * Dm + i);
-        const bf16x8 hv = *reinterpret_cast<const bf16x8 *>(h + (size_t)b * Dm + i);
-        *reinterpret_cast<bf16x8 *>(x_bf + (size_t)m * 2 * Dm + i) = e;
-        *reinterpret_cast<bf16x8 *>(x_bf + (size_t)m * 2 * Dm + Dm + i) = hv;
-        *reinterpret_cast<bf16x8 *>(s_bf + (size_t)m * Dm + i) = e;
+        typedef typename Elem16<T>::vec8 vec8;
+        const vec8 e = *reinterpret_cast<const vec8 *>(emb + (size_t)tok * Dm + i);
+        const vec8 hv = *reinterpret_cast<const vec8 *>(h + (size_t)b * Dm + i);
+        *reinterpret_cast<vec8 *>(x_bf + (size_t)m * 2 * Dm + i) = e;
+        *reinterpret_cast<vec8 *>(x_bf + (size_t)m * 2 * Dm + Dm + i) = hv;
+        *reinterpret_cast<vec8 *>(s_bf + (size_t)m * Dm + i) = e;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             x_f32[(size_t)m * 2 * Dm + i + j] = (float)e[j];
@@ -575,21 +591,22 @@ int draft_check(const rd_draft_params *p, int B, int W, int L)
     if (!p || B <= 0 || W <= 0 || L <= 0) return RD_ERR_INVALID_ARG;
     if (p->Dm <= 0 || p->V <= 0 || p->n_mlp < 0) return RD_ERR_INVALID_ARG;
     if (p->Dm % 64 != 0) return RD_ERR_UNSUPPORTED;              // every wave's K share is whole 32-wide steps
+    if (p->dtype != RD_BF16 && p->dtype != RD_F16) return RD_ERR_UNSUPPORTED;
     if (W > kMaxBeam || (long long)B * W > kMaxRows || W > p->V) return RD_ERR_UNSUPPORTED;
     if (p->V > kMaxVocab || L > RD_MAX_N) return RD_ERR_UNSUPPORTED;
     return RD_OK;
 }
 
-template <int MT, int NT, int NWV, int EPI>
-void launch_linear_one(const LinArgs &a, hipStream_t stream)
+template <typename T, int MT, int NT, int NWV, int EPI>
+void launch_linear_one(const LinArgs<T> &a, hipStream_t stream)
 {
-    hipLaunchKernelGGL((rd_linear_kernel<MT, NT, NWV, EPI>), dim3((a.N + 16 * NT - 1) / (16 * NT)), dim3(NWV * 64), 0, stream, a);
+    hipLaunchKernelGGL((rd_linear_kernel<T, MT, NT, NWV, EPI>), dim3((a.N + 16 * NT - 1) / (16 * NT)), dim3(NWV * 64), 0, stream, a);
 }
 
 // waves per workgroup: as many as give the launch about 16 waves per compute unit, as long as
 // every wave gets whole k-steps inside one product and its registers allow that many residents
-template <int MT, int NT, int EPI>
-int launch_linear_nt(const LinArgs &a, hipStream_t stream)
+template <typename T, int MT, int NT, int EPI>
+int launch_linear_nt(const LinArgs<T> &a, hipStream_t stream)
 {
     const int ks1 = a.K1 / 32, ks2 = a.K2 / 32, wgs = (a.N + 16 * NT - 1) / (16 * NT);
     auto ok = [&](int nwv) {
@@ -600,82 +617,64 @@ int launch_linear_nt(const LinArgs &a, hipStream_t stream)
     if (wgs * 4 < 4096 && ok(8)) nwv = 8;
     if (wgs * 8 < 4096 && ok(16)) nwv = 16;
     constexpr bool k16 = MT * NT <= 4 && MT + NT <= 5;          // 16 waves need <= 128 registers per lane
-    if (nwv == 16) { if constexpr (k16) launch_linear_one<MT, NT, 16, EPI>(a, stream); else launch_linear_one<MT, NT, 8, EPI>(a, stream); }
-    else if (nwv == 8) launch_linear_one<MT, NT, 8, EPI>(a, stream);
-    else launch_linear_one<MT, NT, 4, EPI>(a, stream);
+    if (nwv == 16) { if constexpr (k16) launch_linear_one<T, MT, NT, 16, EPI>(a, stream); else launch_linear_one<T, MT, NT, 8, EPI>(a, stream); }
+    else if (nwv == 8) launch_linear_one<T, MT, NT, 8, EPI>(a, stream);
+    else launch_linear_one<T, MT, NT, 4, EPI>(a, stream);
     return rd_check_launch();
 }
 
 // column tiles per workgroup: the most that still leave about one workgroup per compute unit (the
 // activation re-reads are MT : NT of the weight bytes, and measured they cost as much as the
 // weights' own stream; halving the workgroups below the number of compute units costs more)
-template <int MT, int EPI>
-int launch_linear_mt(const LinArgs &a, hipStream_t stream)
+template <typename T, int MT, int EPI>
+int launch_linear_mt(const LinArgs<T> &a, hipStream_t stream)
 {
     if constexpr (MT == 2 || MT == 4) {
-        if (a.N >= 240 * 128) return launch_linear_nt<MT, 8, EPI>(a, stream);
+        if (a.N >= 240 * 128) return launch_linear_nt<T, MT, 8, EPI>(a, stream);
     }
     if constexpr (MT >= 4) {
-        if (a.N >= 256 * 64) return launch_linear_nt<MT, 4, EPI>(a, stream);
+        if (a.N >= 256 * 64) return launch_linear_nt<T, MT, 4, EPI>(a, stream);
     }
     if constexpr (MT >= 2) {
-        if (a.N >= 256 * 32) return launch_linear_nt<MT, 2, EPI>(a, stream);
+        if (a.N >= 256 * 32) return launch_linear_nt<T, MT, 2, EPI>(a, stream);
     }
-    return launch_linear_nt<MT, 1, EPI>(a, stream);
+    return launch_linear_nt<T, MT, 1, EPI>(a, stream);
 }
 
 // more than 128 rows: one launch per 128 rows (each streams the weights again)
-template <int EPI>
-int launch_linear(const LinArgs &all, hipStream_t stream)
+template <typename T, int EPI>
+int launch_linear(const LinArgs<T> &all, hipStream_t stream)
 {
     for (int m0 = 0; m0 < all.M; m0 += kRowsPerLaunch) {
-        LinArgs a = all;
+        LinArgs<T> a = all;
         a.m0 = m0;
         a.M = all.M - m0 < kRowsPerLaunch ? all.M - m0 : kRowsPerLaunch;
         const int mt = (a.M + 15) / 16;
         int st;
-        if (mt <= 1) st = launch_linear_mt<1, EPI>(a, stream);
-        else if (mt <= 2) st = launch_linear_mt<2, EPI>(a, stream);
-        else if (mt <= 4) st = launch_linear_mt<4, EPI>(a, stream);
-        else st = launch_linear_mt<8, EPI>(a, stream);
+        if (mt <= 1) st = launch_linear_mt<T, 1, EPI>(a, stream);
+        else if (mt <= 2) st = launch_linear_mt<T, 2, EPI>(a, stream);
+        else if (mt <= 4) st = launch_linear_mt<T, 4, EPI>(a, stream);
+        else st = launch_linear_mt<T, 8, EPI>(a, stream);
         if (st != RD_OK) return st;
     }
     return RD_OK;
 }
 
-}  // namespace
-
-extern "C" size_t rd_draft_workspace(int B, int W, int L, int Dm, int V)
+// The whole call for one storage type (launches only; arguments already checked).
+template <typename E>
+int draft_run(const rd_draft_params *p, const void *h, const int32_t *last_token, int B, int W, int L,
+              int32_t *beams, float *beam_logp, float *step_logits, int32_t *step_row,
+              void *workspace, size_t workspace_bytes, void *stream)
 {
-    rd_draft_params p = {};
-    p.Dm = Dm; p.V = V;
-    if (draft_check(&p, B, W, L) != RD_OK) return 0;
-    return draft_plan(B, W, L, Dm, V).total;
-}
-
-extern "C" int rd_draft(const rd_draft_params *p, const void *h, const int32_t *last_token,
-                        int B, int W, int L, int32_t *beams, float *beam_logp,
-                        float *step_logits, int32_t *step_row,
-                        void *workspace, size_t workspace_bytes, void *stream)
-{
-    const int st = draft_check(p, B, W, L);
-    if (st != RD_OK) return st;
-    if (!p->emb || !p->rnn_u || !p->rnn_w || !p->rnn_b || !p->head_w || (p->n_mlp > 0 && (!p->mlp_w || !p->mlp_b)))
-        return RD_ERR_INVALID_ARG;
-    if (!h || !last_token || !beams || !beam_logp) return RD_ERR_INVALID_ARG;
-    if ((step_logits == nullptr) != (step_row == nullptr) || !rd_aligned(step_logits, 16)) return RD_ERR_INVALID_ARG;
-    if (!rd_aligned(p->emb, 16) || !rd_aligned(p->rnn_u, 16) || !rd_aligned(p->rnn_w, 16) || !rd_aligned(p->mlp_w, 16) ||
-        !rd_aligned(p->head_w, 16) || !rd_aligned(h, 16))
-        return RD_ERR_INVALID_ARG;
     const Plan plan = draft_plan(B, W, L, p->Dm, p->V);
     if (!workspace || !rd_aligned(workspace, 256) || workspace_bytes < plan.total) return RD_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     unsigned char *ws = static_cast<unsigned char *>(workspace);
     const int Dm = p->Dm, G = 2 * Dm, V = p->V, M = B * W, T = L - 1;
     float *x_f32[3];
-    __bf16 *x_bf[3], *s_bf[2];
-    for (int i = 0; i < 3; ++i) { x_f32[i] = reinterpret_cast<float *>(ws + plan.x_f32[i]); x_bf[i] = reinterpret_cast<__bf16 *>(ws + plan.x_bf[i]); }
-    for (int i = 0; i < 2; ++i) s_bf[i] = reinterpret_cast<__bf16 *>(ws + plan.s_bf[i]);
+    E *x_bf[3], *s_bf[2];
+    for (int i = 0; i < 3; ++i) { x_f32[i] = reinterpret_cast<float *>(ws + plan.x_f32[i]); x_bf[i] = reinterpret_cast<E *>(ws + plan.x_bf[i]); }
+    for (int i = 0; i < 2; ++i) s_bf[i] = reinterpret_cast<E *>(ws + plan.s_bf[i]);
     float *logits = reinterpret_cast<float *>(ws + plan.logits);
     float *part_max = reinterpret_cast<float *>(ws + plan.part_max), *part_sum = reinterpret_cast<float *>(ws + plan.part_sum);
     float *part_cv = reinterpret_cast<float *>(ws + plan.part_cv);
@@ -686,13 +685,13 @@ extern "C" int rd_draft(const rd_draft_params *p, const void *h, const int32_t *
     int32_t *paths[2] = {reinterpret_cast<int32_t *>(ws + plan.paths[0]), reinterpret_cast<int32_t *>(ws + plan.paths[1])};
     float *cum[2] = {reinterpret_cast<float *>(ws + plan.cum[0]), reinterpret_cast<float *>(ws + plan.cum[1])};
     int32_t *parent = reinterpret_cast<int32_t *>(ws + plan.parent), *tok = reinterpret_cast<int32_t *>(ws + plan.tok);
-    const __bf16 *emb = static_cast<const __bf16 *>(p->emb);
+    const E *emb = static_cast<const E *>(p->emb);
 
-    hipLaunchKernelGGL(rd_draft_init_kernel, dim3(M), dim3(256), 0, s, emb, static_cast<const __bf16 *>(h), last_token,
+    hipLaunchKernelGGL(rd_draft_init_kernel<E>, dim3(M), dim3(256), 0, s, emb, static_cast<const E *>(h), last_token,
                        W, L, Dm, V, x_f32[0], x_bf[0], s_bf[0], paths[0], cum[0]);
     if (rd_check_launch() != RD_OK) return RD_ERR_HIP;
     if (T == 0) {                                   // nothing to draft: the candidates are the LLM's token alone
-        hipLaunchKernelGGL(rd_draft_init_kernel, dim3(M), dim3(256), 0, s, emb, static_cast<const __bf16 *>(h), last_token,
+        hipLaunchKernelGGL(rd_draft_init_kernel<E>, dim3(M), dim3(256), 0, s, emb, static_cast<const E *>(h), last_token,
                            W, L, Dm, V, x_f32[0], x_bf[0], s_bf[0], beams, beam_logp);
         return rd_check_launch();
     }
@@ -701,12 +700,12 @@ extern "C" int rd_draft(const rd_draft_params *p, const void *h, const int32_t *
     for (int t = 1; t <= T; ++t) {
         const int cur = (t - 1) & 1, nxt = t & 1;
         if (t > 1) {                                // s_t = f(U s_{t-1}[parent] + W e(token) + b) -> X0[:, :Dm]
-            LinArgs a = {};
-            a.w1 = static_cast<const __bf16 *>(p->rnn_u); a.x1 = s_bf[si]; a.map1 = parent + (size_t)(t - 2) * M; a.ldx1 = Dm; a.K1 = Dm;
-            a.w2 = static_cast<const __bf16 *>(p->rnn_w); a.x2 = emb; a.map2 = tok; a.ldx2 = Dm; a.K2 = Dm;
+            LinArgs<E> a = {};
+            a.w1 = static_cast<const E *>(p->rnn_u); a.x1 = s_bf[si]; a.map1 = parent + (size_t)(t - 2) * M; a.ldx1 = Dm; a.K1 = Dm;
+            a.w2 = static_cast<const E *>(p->rnn_w); a.x2 = emb; a.map2 = tok; a.ldx2 = Dm; a.K2 = Dm;
             a.bias = p->rnn_b; a.M = M; a.N = Dm; a.mstride = 1;
             a.y_f32 = x_f32[0]; a.y_bf = x_bf[0]; a.s_bf = s_bf[si ^ 1]; a.ldy = G;
-            if (launch_linear<EPI_RNN>(a, s) != RD_OK) return RD_ERR_HIP;
+            if (launch_linear<E, EPI_RNN>(a, s) != RD_OK) return RD_ERR_HIP;
             si ^= 1;
         }
         // at the first position the W rows of a sequence are one and the same state: compute row b*W only
@@ -714,19 +713,19 @@ extern "C" int rd_draft(const rd_draft_params *p, const void *h, const int32_t *
         int in = 0;
         for (int k = 0; k < p->n_mlp; ++k) {        // x <- x + f(A_k x + c_k)
             const int out = in == 1 ? 2 : 1;
-            LinArgs a = {};
-            a.w1 = static_cast<const __bf16 *>(p->mlp_w) + (size_t)k * G * G; a.x1 = x_bf[in]; a.ldx1 = G; a.K1 = G;
+            LinArgs<E> a = {};
+            a.w1 = static_cast<const E *>(p->mlp_w) + (size_t)k * G * G; a.x1 = x_bf[in]; a.ldx1 = G; a.K1 = G;
             a.bias = p->mlp_b + (size_t)k * G; a.M = rows; a.N = G; a.mstride = mstride;
             a.y_f32 = x_f32[out]; a.y_bf = x_bf[out]; a.res = x_f32[in]; a.ldy = G;
-            if (launch_linear<EPI_MLP>(a, s) != RD_OK) return RD_ERR_HIP;
+            if (launch_linear<E, EPI_MLP>(a, s) != RD_OK) return RD_ERR_HIP;
             in = out;
         }
         {                                           // logits
-            LinArgs a = {};
-            a.w1 = static_cast<const __bf16 *>(p->head_w); a.x1 = x_bf[in]; a.ldx1 = G; a.K1 = G;
+            LinArgs<E> a = {};
+            a.w1 = static_cast<const E *>(p->head_w); a.x1 = x_bf[in]; a.ldx1 = G; a.K1 = G;
             if (step_logits) logits = step_logits + (size_t)(t - 1) * M * V;   // every position keeps its matrix
             a.M = rows; a.N = V; a.mstride = mstride; a.y_f32 = logits; a.ldy = V;
-            if (launch_linear<EPI_HEAD>(a, s) != RD_OK) return RD_ERR_HIP;
+            if (launch_linear<E, EPI_HEAD>(a, s) != RD_OK) return RD_ERR_HIP;
         }
         hipLaunchKernelGGL(rd_topw_chunk_kernel, dim3(chunks, rows), dim3(kChunkThreads), 0, s, logits, V, W, chunks, mstride,
                            part_max, part_sum, part_cv, part_ci);
@@ -749,4 +748,33 @@ extern "C" int rd_draft(const rd_draft_params *p, const void *h, const int32_t *
         if (rd_check_launch() != RD_OK) return RD_ERR_HIP;
     }
     return RD_OK;
+}
+
+}  // namespace
+
+extern "C" size_t rd_draft_workspace(int B, int W, int L, int Dm, int V)
+{
+    rd_draft_params p = {};
+    p.Dm = Dm; p.V = V; p.dtype = RD_BF16;
+    if (draft_check(&p, B, W, L) != RD_OK) return 0;
+    return draft_plan(B, W, L, Dm, V).total;
+}
+
+extern "C" int rd_draft(const rd_draft_params *p, const void *h, const int32_t *last_token,
+                        int B, int W, int L, int32_t *beams, float *beam_logp,
+                        float *step_logits, int32_t *step_row,
+                        void *workspace, size_t workspace_bytes, void *stream)
+{
+    const int st = draft_check(p, B, W, L);
+    if (st != RD_OK) return st;
+    if (!p->emb || !p->rnn_u || !p->rnn_w || !p->rnn_b || !p->head_w || (p->n_mlp > 0 && (!p->mlp_w || !p->mlp_b)))
+        return RD_ERR_INVALID_ARG;
+    if (!h || !last_token || !beams || !beam_logp) return RD_ERR_INVALID_ARG;
+    if ((step_logits == nullptr) != (step_row == nullptr) || !rd_aligned(step_logits, 16)) return RD_ERR_INVALID_ARG;
+    if (!rd_aligned(p->emb, 16) || !rd_aligned(p->rnn_u, 16) || !rd_aligned(p->rnn_w, 16) || !rd_aligned(p->mlp_w, 16) ||
+        !rd_aligned(p->head_w, 16) || !rd_aligned(h, 16))
+        return RD_ERR_INVALID_ARG;
+    if (p->dtype == RD_F16)
+        return draft_run<_Float16>(p, h, last_token, B, W, L, beams, beam_logp, step_logits, step_row, workspace, workspace_bytes, stream);
+    return draft_run<__bf16>(p, h, last_token, B, W, L, beams, beam_logp, step_logits, step_row, workspace, workspace_bytes, stream);
 }

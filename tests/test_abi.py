@@ -245,11 +245,13 @@ def test_draft_argument_errors(lib):
     from paper_2403_09919_amd.binding import _DraftParams
 
     def call(Dm=64, V=100, K=1, B=1, W=4, L=5, emb=FAKE, mlp=FAKE, h=FAKE, ws=FAKE, ws_bytes=None, params=True,
-             sl=None, sr=None):
-        p = _DraftParams(emb, FAKE, FAKE, FAKE, mlp, mlp, FAKE, K, Dm, V)
+             sl=None, sr=None, dt=1):
+        p = _DraftParams(emb, FAKE, FAKE, FAKE, mlp, mlp, FAKE, K, Dm, V, dt)
         need = lib.rd_draft_workspace(B, W, L, Dm, V)
         return lib.rd_draft(ctypes.byref(p) if params else None, h, FAKE, B, W, L, FAKE, FAKE, sl, sr, ws,
                             need if ws_bytes is None else ws_bytes, None)
+    assert call(dt=0) == UNSUPPORTED                         # weights are bf16 (1) or fp16 (2)
+    assert call(dt=3) == UNSUPPORTED
     assert call(sl=FAKE) == INVALID                          # the record of the search: both outputs or neither
     assert call(sr=FAKE) == INVALID
     assert call(sl=FAKE + 4, sr=FAKE) == INVALID

@@ -13,7 +13,7 @@ import torch
 import oracle
 from gpu_util import announce, dev, host
 from paper_2403_09919_amd import synth
-from test_oracle_draft import make_params
+from test_oracle_draft import make_h, make_params
 
 pytestmark = pytest.mark.gpu
 
@@ -208,3 +208,33 @@ def test_draft_records_the_search(rd, Dm, V, K, B, W, L):
                     # the same bf16 re-rounding effect that TOL bounds for a handful of path scores
                     assert np.abs(lp - ref["step_logp"][j, ref["step_row"][b, w, j]]).max() <= 3 * TOL
     assert agree >= (B + 1) // 2
+
+
+@pytest.mark.parametrize("Dm,V,K,B,W,L", [(64, 500, 2, 2, 4, 5), (128, 4000, 1, 3, 8, 4), (64, 17000, 1, 5, 8, 3),
+                                          (256, 1000, 2, 1, 16, 4), (64, 300, 0, 20, 8, 3)])
+def test_draft_float16_model(rd, Dm, V, K, B, W, L):
+    """The float16 storage type: same checks as for bf16 (fp16 carries three more significand bits, so a
+    re-rounding flip is eight times smaller and the tolerance is kept)."""
+    announce(f"draft fp16 Dm={Dm} V={V} K={K} B={B} W={W} L={L}")
+    p = make_params(V, Dm, K, seed=Dm + V + 3, scale=4.0, dtype="f16")
+    h = make_h(B, Dm, V + W + 3, "f16")
+    last = np.random.default_rng(V + W + 3).integers(0, V, B).astype(np.int32)
+    ref = oracle.draft(p, h, last, W, L, dtype="f16")
+    got = rd.rd_draft(dev_params(p), dev(h), dev(last), W, L)
+    torch.cuda.synchronize()
+    gb, gl = host(got["beams"]), host(got["beam_logp"])
+    assert (gb[:, :, 0] == last[:, None]).all() and (gb >= 0).all() and (gb < V).all()
+    tf = oracle.draft_path_logp(p, h, gb, dtype="f16")
+    assert np.abs(tf - gl).max() <= TOL
+    assert (np.diff(gl, axis=1) <= 1e-6).all()
+    exact = 0
+    for b in range(B):
+        assert len({tuple(x) for x in gb[b].tolist()}) == W
+        assert (tf[b] >= ref["beam_logp"][b].astype(np.float64) - TOL).all()
+        exact += int(np.array_equal(gb[b], ref["beams"][b]))
+    assert exact >= (B + 1) // 2
+    # not the bf16 model by accident: the same numbers stored as bf16 give other scores
+    pb = make_params(V, Dm, K, seed=Dm + V + 3, scale=4.0)
+    gbf = rd.rd_draft(dev_params(pb), dev(make_h(B, Dm, V + W + 3)), dev(last), W, L)
+    torch.cuda.synchronize()
+    assert not np.array_equal(host(gbf["beam_logp"]), gl)
