@@ -346,7 +346,22 @@ typedef struct {
     const void *head_w;
     int n_mlp, Dm, V;
     rd_dtype dtype;          /* RD_BF16 or RD_F16: type of emb, rnn_u, rnn_w, mlp_w, head_w and of h */
+    int tiled;               /* 0: the matrices are row-major; 1: rnn_u, rnn_w, every mlp_w[k] and head_w are in
+                                the layout rd_draft_pack_weights writes (emb stays row-major) */
 } rd_draft_params;
+
+/*
+ * rd_draft_pack_weights — one-time layout change of a weight matrix for rd_draft (at model load).
+ * src: [N][K] row-major, 16-bit elements (bf16 or fp16, copied bit for bit), K a multiple of 32.
+ * dst: rd_draft_packed_elems(N, K) elements = ceil(N/16)*16 * K: tiles of 16 rows x 32 columns, tile
+ * (n/16, k/32) stored as the 1 KB a wave loads for one matrix-core operand (element (n, k) at
+ * ((n/16 * K/32 + k/32) * 64 + ((k%32)/8) * 16 + n%16) * 8 + k%8), rows past N zero.  With this layout
+ * every wave load of the linear layers reads 1 KB of consecutive memory; results are bit-identical to
+ * the row-major layout.  Each of the n_mlp matrices of mlp_w is packed on its own, back to back.
+ * Both pointers 16-byte aligned, src and dst must not overlap.
+ */
+size_t rd_draft_packed_elems(int N, int K);
+int rd_draft_pack_weights(const void *src, int N, int K, void *dst, void *stream);
 
 size_t rd_draft_workspace(int B, int W, int L, int Dm, int V);
 

@@ -43,6 +43,8 @@ EXPORTS = {
     "rd_accept_sample": (_i, [_vp] * 3 + [_i] + [_vp] * 6 + [_f, _i, _i, _i, _i] + [_vp] * 5 + [_vp, _sz, _vp]),
     "rd_commit": (_i, [_vp] * 5 + [_i] * 7 + [_vp] * 4 + [_vp, _i, _vp, _vp]),
     "rd_draft_workspace": (_sz, [_i, _i, _i, _i, _i]),
+    "rd_draft_packed_elems": (_sz, [_i, _i]),
+    "rd_draft_pack_weights": (_i, [_vp, _i, _i, _vp, _vp]),
     "rd_draft": (_i, [_vp, _vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "rd_rope": (_i, [_vp] * 6 + [_i] * 6 + [_vp]),
     "rd_commit_paged": (_i, [_vp] * 5 + [_i] * 6 + [_vp] * 3 + [_i, _i, _i] + [_vp, _vp] + [_vp, _i, _vp, _vp]),
@@ -369,11 +371,37 @@ def rd_rope(q, k_new, position_ids, n_packed, cos_tab, sin_tab) -> None:
 
 class _DraftParams(ctypes.Structure):
     _fields_ = [("emb", _vp), ("rnn_u", _vp), ("rnn_w", _vp), ("rnn_b", _vp), ("mlp_w", _vp), ("mlp_b", _vp),
-                ("head_w", _vp), ("n_mlp", _i), ("Dm", _i), ("V", _i), ("dtype", _i)]
+                ("head_w", _vp), ("n_mlp", _i), ("Dm", _i), ("V", _i), ("dtype", _i), ("tiled", _i)]
 
 
 def rd_draft_workspace(B: int, W: int, L: int, Dm: int, V: int) -> int:
     return int(_lib.rd_draft_workspace(B, W, L, Dm, V))
+
+
+def rd_draft_pack(params: dict) -> dict:
+    """One-time layout change at model load: returns a copy of `params` whose matrices rnn_u, rnn_w,
+    mlp_w and head_w are in rd_draft's operand-tiled layout (see include/rd.h, rd_draft_pack_weights),
+    marked with "tiled": True.  emb and the biases are shared with the input dict."""
+    def pack(w, n_mats, N, K):
+        w = w.contiguous()
+        per = int(_lib.rd_draft_packed_elems(N, K))
+        dst = torch.empty((n_mats * per,), dtype=w.dtype, device=w.device)
+        for k in range(n_mats):
+            _check(_lib.rd_draft_pack_weights(w.data_ptr() + k * N * K * 2, N, K, dst.data_ptr() + k * per * 2, _stream()),
+                   "rd_draft_pack_weights")
+        return dst
+
+    V, Dm = params["emb"].shape
+    K = params["mlp_w"].shape[0]
+    G = 2 * Dm
+    out = dict(params)
+    out["rnn_u"] = pack(params["rnn_u"], 1, Dm, Dm)
+    out["rnn_w"] = pack(params["rnn_w"], 1, Dm, Dm)
+    out["mlp_w"] = pack(params["mlp_w"], K, G, G) if K else params["mlp_w"]
+    out["head_w"] = pack(params["head_w"], 1, V, G)
+    out["tiled"] = True
+    out["n_mlp"] = K
+    return out
 
 
 def rd_draft(params: dict, h, last_token, W: int, L: int, out: Optional[dict] = None,
@@ -387,15 +415,22 @@ def rd_draft(params: dict, h, last_token, W: int, L: int, out: Optional[dict] = 
     if bf not in (torch.bfloat16, torch.float16):
         raise ValueError("draft model weights must be bfloat16 or float16, got %s" % bf)
     V, Dm = params["emb"].shape
-    K = params["mlp_w"].shape[0]
+    tiled = bool(params.get("tiled", False))      # matrices packed by rd_draft_pack: flat tensors
+    K = params["n_mlp"] if tiled else params["mlp_w"].shape[0]
+    G = 2 * Dm
     B = h.shape[0]
     dev = h.device
+
+    def mat(name, n_mats, N, Kc):
+        shape = (n_mats * int(_lib.rd_draft_packed_elems(N, Kc)),) if tiled else ((N, Kc) if n_mats == 1 and name != "mlp_w" else (n_mats, N, Kc))
+        return _ptr(params[name], bf, shape, name)
+
     p = _DraftParams(
-        _ptr(params["emb"], bf, (V, Dm), "emb"), _ptr(params["rnn_u"], bf, (Dm, Dm), "rnn_u"),
-        _ptr(params["rnn_w"], bf, (Dm, Dm), "rnn_w"), _ptr(params["rnn_b"], torch.float32, (Dm,), "rnn_b"),
-        _ptr(params["mlp_w"], bf, (K, 2 * Dm, 2 * Dm), "mlp_w") if K else None,
-        _ptr(params["mlp_b"], torch.float32, (K, 2 * Dm), "mlp_b") if K else None,
-        _ptr(params["head_w"], bf, (V, 2 * Dm), "head_w"), K, Dm, V, RD_BF16 if bf == torch.bfloat16 else RD_F16)
+        _ptr(params["emb"], bf, (V, Dm), "emb"), mat("rnn_u", 1, Dm, Dm), mat("rnn_w", 1, Dm, Dm),
+        _ptr(params["rnn_b"], torch.float32, (Dm,), "rnn_b"),
+        mat("mlp_w", K, G, G) if K else None,
+        _ptr(params["mlp_b"], torch.float32, (K, G), "mlp_b") if K else None,
+        mat("head_w", 1, V, G), K, Dm, V, RD_BF16 if bf == torch.bfloat16 else RD_F16, 1 if tiled else 0)
     if out is None:
         out = dict(beams=torch.empty((B, W, L), dtype=torch.int32, device=dev),
                    beam_logp=torch.empty((B, W), dtype=torch.float32, device=dev))

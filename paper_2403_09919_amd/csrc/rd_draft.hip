@@ -52,6 +52,7 @@ struct LinArgs {
     const T *x1, *x2;             // row r of X1 is x1 + map1[r]*ldx1 (map NULL: r itself)
     const int32_t *map1, *map2;
     int ldx1, ldx2, K1, K2;            // K2 = 0: single product
+    int tiled;                         // weights in the operand-tiled layout of rd_draft_pack_weights
     const float *bias;                 // [N] or NULL
     int M, N;
     int m0;                            // first logical row of this launch (a launch covers rows m0 .. m0+M-1)
@@ -98,7 +99,7 @@ __device__ __forceinline__ void linear_epilogue(const LinArgs<T> &a, f32x4 v, in
 // outweigh the weights it streams (their ratio is MT : NT) while the launch still covers the chip,
 // and NWV so that the launch has enough waves in flight to keep the HBM stream busy; every wave's
 // share of K is a whole number of 32-wide steps inside one of the two products.
-template <typename T, int MT, int NT, int NWV, int EPI>
+template <typename T, int MT, int NT, int NWV, int EPI, bool TILED>
 __global__ __launch_bounds__(NWV * 64) void rd_linear_kernel(LinArgs<T> a)
 {
     typedef typename Elem16<T>::vec8 vec8;
@@ -125,8 +126,13 @@ __global__ __launch_bounds__(NWV * 64) void rd_linear_kernel(LinArgs<T> a)
     const T *wp[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        const int nrow = min(n0 + nt * 16 + r16, a.N - 1);      // rows past N read the last row; never stored
-        wp[nt] = wbase + (size_t)nrow * K + k_first + 8 * g;
+        if (TILED) {                                            // tile (n/16, k/32): 64 lanes x 8 elements, contiguous
+            const int ntile = min(n0 / 16 + nt, (a.N + 15) / 16 - 1);
+            wp[nt] = wbase + ((size_t)ntile * (K >> 5) + (k_first >> 5)) * 512 + lane * 8;
+        } else {
+            const int nrow = min(n0 + nt * 16 + r16, a.N - 1);  // rows past N read the last row; never stored
+            wp[nt] = wbase + (size_t)nrow * K + k_first + 8 * g;
+        }
     }
     const T *xp[MT];
 #pragma unroll
@@ -135,6 +141,7 @@ __global__ __launch_bounds__(NWV * 64) void rd_linear_kernel(LinArgs<T> a)
         const size_t row = map ? (size_t)map[m] : (size_t)m * a.mstride;
         xp[mt] = xbase + row * ldx + k_first + 8 * g;
     }
+    constexpr int wstep = TILED ? 512 : 32;                     // elements between a lane's vectors of consecutive k-steps
     f32x4 acc[MT][NT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
@@ -148,7 +155,7 @@ __global__ __launch_bounds__(NWV * 64) void rd_linear_kernel(LinArgs<T> a)
 #pragma unroll
         for (int u = 0; u < U; ++u) {
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) wa[u][nt] = *reinterpret_cast<const vec8 *>(wp[nt] + (s + u) * 32);
+            for (int nt = 0; nt < NT; ++nt) wa[u][nt] = *reinterpret_cast<const vec8 *>(wp[nt] + (s + u) * wstep);
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) xb[u][mt] = *reinterpret_cast<const vec8 *>(xp[mt] + (s + u) * 32);
         }
@@ -163,7 +170,7 @@ __global__ __launch_bounds__(NWV * 64) void rd_linear_kernel(LinArgs<T> a)
     for (; s < steps; ++s) {
         vec8 wa[NT];
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) wa[nt] = *reinterpret_cast<const vec8 *>(wp[nt] + s * 32);
+        for (int nt = 0; nt < NT; ++nt) wa[nt] = *reinterpret_cast<const vec8 *>(wp[nt] + s * wstep);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
             const vec8 xb = *reinterpret_cast<const vec8 *>(xp[mt] + s * 32);
@@ -559,6 +566,23 @@ __global__ void rd_draft_rows_kernel(const int32_t *__restrict__ parents /*[T][M
     }
 }
 
+// Operand-tiled weight layout: the matrix [N][K] (row-major, 16-bit elements) cut into tiles of 16
+// rows x 32 columns, tile (n/16, k/32) stored as the 1 KB a wave loads for one MFMA A operand -- lane
+// (row n%16, column group g = (k%32)/8) holds its eight consecutive elements at offset lane*8 with
+// lane = g*16 + n%16 -- tiles of one row band consecutive in k.  Rows past N are zero.  A wave
+// instruction of the linear kernel then reads 1 KB of consecutive memory instead of 64 B from each
+// of 16 rows that lie K elements apart.
+__global__ void rd_pack_weights_kernel(const uint16_t *__restrict__ src, int N, int K, uint16_t *__restrict__ dst)
+{
+    const size_t tile = blockIdx.x;                              // (n/16) * (K/32) + k/32
+    const int ks = (int)(tile % (size_t)(K >> 5)), nt = (int)(tile / (size_t)(K >> 5));
+    const int lane = threadIdx.x, r16 = lane & 15, g = lane >> 4;
+    const int n = nt * 16 + r16;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (n < N) v = *reinterpret_cast<const uint4 *>(src + (size_t)n * K + ks * 32 + g * 8);
+    *reinterpret_cast<uint4 *>(dst + (tile * 64 + lane) * 8) = v;
+}
+
 struct Plan {
     size_t x_f32[3], x_bf[3], s_bf[2], logits, part_max, part_sum, part_cv, part_ci, row_score, row_tok, paths[2], cum[2], parent, tok, total;
 };
@@ -592,6 +616,7 @@ int draft_check(const rd_draft_params *p, int B, int W, int L)
     if (p->Dm <= 0 || p->V <= 0 || p->n_mlp < 0) return RD_ERR_INVALID_ARG;
     if (p->Dm % 64 != 0) return RD_ERR_UNSUPPORTED;              // every wave's K share is whole 32-wide steps
     if (p->dtype != RD_BF16 && p->dtype != RD_F16) return RD_ERR_UNSUPPORTED;
+    if (p->tiled != 0 && p->tiled != 1) return RD_ERR_INVALID_ARG;
     if (W > kMaxBeam || (long long)B * W > kMaxRows || W > p->V) return RD_ERR_UNSUPPORTED;
     if (p->V > kMaxVocab || L > RD_MAX_N) return RD_ERR_UNSUPPORTED;
     return RD_OK;
@@ -600,7 +625,10 @@ int draft_check(const rd_draft_params *p, int B, int W, int L)
 template <typename T, int MT, int NT, int NWV, int EPI>
 void launch_linear_one(const LinArgs<T> &a, hipStream_t stream)
 {
-    hipLaunchKernelGGL((rd_linear_kernel<T, MT, NT, NWV, EPI>), dim3((a.N + 16 * NT - 1) / (16 * NT)), dim3(NWV * 64), 0, stream, a);
+    if (a.tiled)
+        hipLaunchKernelGGL((rd_linear_kernel<T, MT, NT, NWV, EPI, true>), dim3((a.N + 16 * NT - 1) / (16 * NT)), dim3(NWV * 64), 0, stream, a);
+    else
+        hipLaunchKernelGGL((rd_linear_kernel<T, MT, NT, NWV, EPI, false>), dim3((a.N + 16 * NT - 1) / (16 * NT)), dim3(NWV * 64), 0, stream, a);
 }
 
 // waves per workgroup: as many as give the launch about 16 waves per compute unit, as long as
@@ -703,7 +731,7 @@ int draft_run(const rd_draft_params *p, const void *h, const int32_t *last_token
             LinArgs<E> a = {};
             a.w1 = static_cast<const E *>(p->rnn_u); a.x1 = s_bf[si]; a.map1 = parent + (size_t)(t - 2) * M; a.ldx1 = Dm; a.K1 = Dm;
             a.w2 = static_cast<const E *>(p->rnn_w); a.x2 = emb; a.map2 = tok; a.ldx2 = Dm; a.K2 = Dm;
-            a.bias = p->rnn_b; a.M = M; a.N = Dm; a.mstride = 1;
+            a.bias = p->rnn_b; a.M = M; a.N = Dm; a.mstride = 1; a.tiled = p->tiled;
             a.y_f32 = x_f32[0]; a.y_bf = x_bf[0]; a.s_bf = s_bf[si ^ 1]; a.ldy = G;
             if (launch_linear<E, EPI_RNN>(a, s) != RD_OK) return RD_ERR_HIP;
             si ^= 1;
@@ -715,7 +743,7 @@ int draft_run(const rd_draft_params *p, const void *h, const int32_t *last_token
             const int out = in == 1 ? 2 : 1;
             LinArgs<E> a = {};
             a.w1 = static_cast<const E *>(p->mlp_w) + (size_t)k * G * G; a.x1 = x_bf[in]; a.ldx1 = G; a.K1 = G;
-            a.bias = p->mlp_b + (size_t)k * G; a.M = rows; a.N = G; a.mstride = mstride;
+            a.bias = p->mlp_b + (size_t)k * G; a.M = rows; a.N = G; a.mstride = mstride; a.tiled = p->tiled;
             a.y_f32 = x_f32[out]; a.y_bf = x_bf[out]; a.res = x_f32[in]; a.ldy = G;
             if (launch_linear<E, EPI_MLP>(a, s) != RD_OK) return RD_ERR_HIP;
             in = out;
@@ -724,7 +752,7 @@ int draft_run(const rd_draft_params *p, const void *h, const int32_t *last_token
             LinArgs<E> a = {};
             a.w1 = static_cast<const E *>(p->head_w); a.x1 = x_bf[in]; a.ldx1 = G; a.K1 = G;
             if (step_logits) logits = step_logits + (size_t)(t - 1) * M * V;   // every position keeps its matrix
-            a.M = rows; a.N = V; a.mstride = mstride; a.y_f32 = logits; a.ldy = V;
+            a.M = rows; a.N = V; a.mstride = mstride; a.tiled = p->tiled; a.y_f32 = logits; a.ldy = V;
             if (launch_linear<E, EPI_HEAD>(a, s) != RD_OK) return RD_ERR_HIP;
         }
         hipLaunchKernelGGL(rd_topw_chunk_kernel, dim3(chunks, rows), dim3(kChunkThreads), 0, s, logits, V, W, chunks, mstride,
@@ -777,4 +805,22 @@ extern "C" int rd_draft(const rd_draft_params *p, const void *h, const int32_t *
     if (p->dtype == RD_F16)
         return draft_run<_Float16>(p, h, last_token, B, W, L, beams, beam_logp, step_logits, step_row, workspace, workspace_bytes, stream);
     return draft_run<__bf16>(p, h, last_token, B, W, L, beams, beam_logp, step_logits, step_row, workspace, workspace_bytes, stream);
+}
+
+extern "C" size_t rd_draft_packed_elems(int N, int K)
+{
+    if (N <= 0 || K <= 0 || K % 32 != 0) return 0;
+    return (size_t)((N + 15) / 16 * 16) * (size_t)K;
+}
+
+extern "C" int rd_draft_pack_weights(const void *src, int N, int K, void *dst, void *stream)
+{
+    if (!src || !dst || N <= 0 || K <= 0) return RD_ERR_INVALID_ARG;
+    if (K % 32 != 0) return RD_ERR_UNSUPPORTED;
+    if (!rd_aligned(src, 16) || !rd_aligned(dst, 16)) return RD_ERR_INVALID_ARG;
+    const size_t tiles = (size_t)((N + 15) / 16) * (size_t)(K / 32);
+    if (tiles > 0x7fffffffull) return RD_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(rd_pack_weights_kernel, dim3((unsigned)tiles), dim3(64), 0, (hipStream_t)stream,
+                       static_cast<const uint16_t *>(src), N, K, static_cast<uint16_t *>(dst));
+    return rd_check_launch();
 }

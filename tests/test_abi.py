@@ -33,7 +33,7 @@ def test_header_symbols_exported(lib):
     assert names == sorted(["rd_strerror", "rd_version", "rd_debug_stream_read", "rd_dedup", "rd_tree_attn_workspace",
                             "rd_tree_attn", "rd_tree_attn_paged_workspace", "rd_tree_attn_paged",
                             "rd_accept_workspace", "rd_accept", "rd_accept_sample_workspace", "rd_accept_sample", "rd_commit", "rd_commit_paged", "rd_rope",
-                            "rd_draft_workspace", "rd_draft"])
+                            "rd_draft_workspace", "rd_draft", "rd_draft_packed_elems", "rd_draft_pack_weights"])
     raw = ctypes.CDLL(LIB)
     for n in names:
         assert hasattr(raw, n), n
@@ -246,7 +246,7 @@ def test_draft_argument_errors(lib):
 
     def call(Dm=64, V=100, K=1, B=1, W=4, L=5, emb=FAKE, mlp=FAKE, h=FAKE, ws=FAKE, ws_bytes=None, params=True,
              sl=None, sr=None, dt=1):
-        p = _DraftParams(emb, FAKE, FAKE, FAKE, mlp, mlp, FAKE, K, Dm, V, dt)
+        p = _DraftParams(emb, FAKE, FAKE, FAKE, mlp, mlp, FAKE, K, Dm, V, dt, 0)
         need = lib.rd_draft_workspace(B, W, L, Dm, V)
         return lib.rd_draft(ctypes.byref(p) if params else None, h, FAKE, B, W, L, FAKE, FAKE, sl, sr, ws,
                             need if ws_bytes is None else ws_bytes, None)
@@ -270,6 +270,16 @@ def test_draft_argument_errors(lib):
     assert call(ws=None) == WORKSPACE
     assert call(ws_bytes=64) == WORKSPACE
     assert lib.rd_draft_workspace(1, 4, 5, 96, 100) == 0
+
+
+def test_pack_weights_argument_errors(lib):
+    assert lib.rd_draft_packed_elems(100, 64) == 112 * 64
+    assert lib.rd_draft_packed_elems(100, 40) == 0            # K a multiple of 32
+    assert lib.rd_draft_pack_weights(None, 16, 32, FAKE, None) == INVALID
+    assert lib.rd_draft_pack_weights(FAKE, 16, 32, None, None) == INVALID
+    assert lib.rd_draft_pack_weights(FAKE, 0, 32, FAKE, None) == INVALID
+    assert lib.rd_draft_pack_weights(FAKE, 16, 40, FAKE, None) == UNSUPPORTED
+    assert lib.rd_draft_pack_weights(FAKE + 2, 16, 32, FAKE, None) == INVALID
 
 
 def test_binding_rejects_host_tensors():

@@ -144,9 +144,12 @@ def test_draft_vicuna7b_dimensions(rd):
     rng = np.random.default_rng(11)
     h = synth.f32_to_bf16_bits(rng.standard_normal((B, Dm)).astype(np.float32))
     last = rng.integers(0, V, B).astype(np.int32)
-    got = rd.rd_draft(dev_params(p), dev(h), dev(last), W, L)
+    pd = dev_params(p)
+    got = rd.rd_draft(pd, dev(h), dev(last), W, L)
+    packed = rd.rd_draft(rd.rd_draft_pack(pd), dev(h), dev(last), W, L)       # the layout bench.py times
     torch.cuda.synchronize()
     gb, gl = host(got["beams"]), host(got["beam_logp"])
+    assert np.array_equal(host(packed["beams"]), gb) and np.array_equal(host(packed["beam_logp"]), gl)
     assert (gb[:, :, 0] == last[:, None]).all() and (gb >= 0).all() and (gb < V).all()
     assert (np.diff(gl, axis=1) <= 1e-6).all()
     assert len({tuple(x) for x in gb[0].tolist()}) == W
@@ -238,3 +241,48 @@ def test_draft_float16_model(rd, Dm, V, K, B, W, L):
     gbf = rd.rd_draft(dev_params(pb), dev(make_h(B, Dm, V + W + 3)), dev(last), W, L)
     torch.cuda.synchronize()
     assert not np.array_equal(host(gbf["beam_logp"]), gl)
+
+
+def numpy_pack(w):
+    """The operand-tiled layout written out with numpy: [N,K] -> tiles (n/16, k/32) of 64 lanes x 8
+    elements, lane = ((k%32)/8)*16 + n%16, rows past N zero."""
+    N, K = w.shape
+    N16 = (N + 15) // 16 * 16
+    wp = np.zeros((N16, K), w.dtype)
+    wp[:N] = w
+    t = wp.reshape(N16 // 16, 16, K // 32, 4, 8)              # nt, r16, ks, g, j
+    return np.ascontiguousarray(t.transpose(0, 2, 3, 1, 4)).reshape(-1)
+
+
+@pytest.mark.parametrize("N,K", [(16, 32), (100, 64), (1037, 128), (3, 256), (512, 8192)])
+def test_pack_weights_layout(rd, N, K):
+    announce(f"pack weights N={N} K={K}")
+    w = np.random.default_rng(N + K).integers(0, 65536, (N, K)).astype(np.uint16)
+    src = dev(w)                                               # bf16 bit patterns; the copy is bit for bit
+    n = rd.raw().rd_draft_packed_elems(N, K)
+    dst = torch.full((n,), -1.0, dtype=torch.bfloat16, device="cuda")
+    code = rd.raw().rd_draft_pack_weights(src.data_ptr(), N, K, dst.data_ptr(), None)
+    torch.cuda.synchronize()
+    assert code == 0
+    assert np.array_equal(host(dst), numpy_pack(w))
+
+
+@pytest.mark.parametrize("Dm,V,K,B,W,L,dtype", [(64, 500, 2, 2, 4, 5, "bf16"), (128, 1037, 1, 3, 8, 4, "bf16"),
+                                                (64, 17000, 1, 5, 8, 3, "bf16"), (64, 31000, 1, 3, 8, 3, "f16"),
+                                                (64, 700, 1, 20, 8, 4, "bf16"), (256, 1000, 0, 1, 64, 3, "f16")])
+def test_packed_weights_give_identical_results(rd, Dm, V, K, B, W, L, dtype):
+    """The operand-tiled layout changes where the weights lie, not the arithmetic: beams, scores and the
+    recorded logits must be bit-identical to the row-major run (which is checked against the oracle)."""
+    announce(f"draft packed Dm={Dm} V={V} K={K} B={B} W={W} L={L} {dtype}")
+    p = make_params(V, Dm, K, seed=Dm + V + 5, scale=4.0, dtype=dtype)
+    h = make_h(B, Dm, V + 5, dtype)
+    last = np.random.default_rng(V + 5).integers(0, V, B).astype(np.int32)
+    pd = dev_params(p)
+    a = rd.rd_draft(pd, dev(h), dev(last), W, L, steps=True)
+    b = rd.rd_draft(rd.rd_draft_pack(pd), dev(h), dev(last), W, L, steps=True)
+    torch.cuda.synchronize()
+    for k in ("beams", "beam_logp", "step_row"):
+        assert np.array_equal(host(a[k]), host(b[k])), k
+    sa, sb = host(a["step_logits"]), host(b["step_logits"])
+    live = np.ones(B * W, bool)
+    assert np.array_equal(sa[1:], sb[1:]) and np.array_equal(sa[0, ::W], sb[0, ::W])
