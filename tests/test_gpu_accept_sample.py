@@ -275,3 +275,40 @@ def test_masked_vocabulary_entries(rd):
         assert not masked[b, 0, got["next_token"][b]]
         for w in range(W):
             assert not masked[b, 0, c["beams"][b, w, 1:got["n_accept"][b, w]]].any()
+
+
+def test_many_random_small_shapes(rd):
+    """Forty seeded shape draws (beam width, length, vocabulary, batch, temperature, with and without a
+    root token, both draft layouts' common path): a sweep for shape-dependent mistakes."""
+    rng = np.random.default_rng(2024)
+    for case in range(40):
+        W = int(rng.integers(1, 20))
+        L = int(rng.integers(1, 8))
+        V = int(rng.choice([2, 3, 5, 17, 64, 257, 1000, 4099, 9000]))
+        B = int(rng.integers(1, 7))
+        t = float(rng.choice([0.5, 1.0, 1.7]))
+        announce(f"accept_sample random case {case}: B={B} W={W} L={L} V={V} t={t}")
+        c = make_case(B, W, L, V, seed=1000 + case, share="high" if case % 2 else "uniform", noise=float(rng.choice([0.3, 1.0, 2.0])))
+        root = None
+        if case % 3 == 0:
+            root = c["beams"][:, 0, 0].copy()
+            root[::2] += 1
+        d = c["d"]
+        ref = oracle.accept_sample(c["logits"], c["draft"], c["beams"], d["unpack_index"], c["u_accept"], c["u_next"], t, root,
+                                   diagnostics=True)
+        got = run_gpu(rd, c, t, root)
+        for b in range(B):
+            ratio = ref["accept_ratio"][b]
+            margin = np.abs(c["u_accept"][b][d["unpack_index"][b]].astype(np.float64) - ratio)
+            if ((ratio >= 0) & (ratio < 1.0) & (margin <= TOL)).any():
+                continue
+            for k in ("n_accept", "best_beam", "best_len", "accepted_idx"):
+                assert np.array_equal(got[k][b], ref[k][b]), (case, b, k)
+            v = int(got["next_token"][b])
+            if ref["best_len"][b] == 0:
+                assert v == root[b], (case, b)
+                continue
+            wts = ref["next_weights"][b]
+            cdf = np.cumsum(wts)
+            assert 0 <= v < V and wts[v] > 0, (case, b, v)
+            assert (cdf[v - 1] if v else 0.0) - TOL <= float(c["u_next"][b]) < cdf[v] + TOL, (case, b, v)

@@ -286,3 +286,36 @@ def test_packed_weights_give_identical_results(rd, Dm, V, K, B, W, L, dtype):
     sa, sb = host(a["step_logits"]), host(b["step_logits"])
     live = np.ones(B * W, bool)
     assert np.array_equal(sa[1:], sb[1:]) and np.array_equal(sa[0, ::W], sb[0, ::W])
+
+
+def test_many_random_small_models(rd):
+    """Thirty seeded draws of model and beam sizes (both storage types, both weight layouts): a sweep for
+    shape-dependent mistakes; every result is checked like the fixed cases."""
+    rng = np.random.default_rng(77)
+    for case in range(30):
+        Dm = int(rng.choice([64, 128, 192]))
+        V = int(rng.choice([40, 333, 1000, 4100, 8200, 16500]))
+        K = int(rng.integers(0, 3))
+        W = int(rng.choice([1, 2, 3, 5, 8, 13, 16, 33, 64]))
+        W = min(W, V)
+        B = int(rng.integers(1, max(2, min(8, 512 // W))))
+        L = int(rng.integers(2, 6))
+        dtype = "f16" if case % 3 == 0 else "bf16"
+        announce(f"draft random case {case}: Dm={Dm} V={V} K={K} B={B} W={W} L={L} {dtype}")
+        p = make_params(V, Dm, K, seed=500 + case, scale=4.0, dtype=dtype)
+        h = make_h(B, Dm, 600 + case, dtype)
+        last = rng.integers(0, V, B).astype(np.int32)
+        ref = oracle.draft(p, h, last, W, L, dtype=dtype)
+        pd = dev_params(p)
+        if case % 2:
+            pd = rd.rd_draft_pack(pd)
+        got = rd.rd_draft(pd, dev(h), dev(last), W, L)
+        torch.cuda.synchronize()
+        gb, gl = host(got["beams"]), host(got["beam_logp"])
+        assert (gb[:, :, 0] == last[:, None]).all() and (gb >= 0).all() and (gb < V).all(), case
+        tf = oracle.draft_path_logp(p, h, gb, dtype=dtype)
+        assert np.abs(tf - gl).max() <= TOL, (case, np.abs(tf - gl).max())
+        assert (np.diff(gl, axis=1) <= 1e-6).all(), case
+        for b in range(B):
+            assert len({tuple(x) for x in gb[b].tolist()}) == W, (case, b)
+            assert (tf[b] >= ref["beam_logp"][b].astype(np.float64) - TOL).all(), (case, b)
