@@ -18,8 +18,9 @@
 // Precision contract: weights, embeddings and h are bf16; every linear layer reads its input
 // rounded to bf16 and accumulates in fp32; bias, activation, skip connection, log-softmax and
 // scores are fp32.
-#include "rd_internal.h"
+#include "rd_attn_common.h"           // device-scope stores/loads for results that cross workgroups
 #include <math.h>
+#include <stdlib.h>
 
 namespace {
 
@@ -42,6 +43,9 @@ constexpr int kMaxRows = 512;          // B*W
 constexpr int kRowsPerLaunch = 128;    // rows of one linear-layer launch (8 MFMA row tiles)
 constexpr int kMaxBeam = 64;           // W
 constexpr int kMaxVocab = 262144;      // 64 chunks of 4096 logits: one lane per chunk in the row pass
+constexpr int kSplitMaxWgs = 256;      // workgroups of a launch whose K is split over workgroups
+constexpr int kSplitMaxGroups = 128;   // ... and its column groups (one arrival counter each)
+constexpr int kSplitTiles = 32;        // ... and the 16x16 output tiles a workgroup holds
 
 enum { EPI_HEAD = 0, EPI_RNN = 1, EPI_MLP = 2 };
 
@@ -63,6 +67,10 @@ struct LinArgs {
     T *s_bf;                           // RNN: next state [M][N]
     const float *res;                  // MLP: skip input fp32 [M][ldy]
     int ldy;
+    // K split over workgroups (kernels instantiated with KSP): workgroup = (column group, split)
+    int ksplit;                        // splits per column group
+    float *kpart;                      // partial tiles [group][split][tile][64 lanes] x 4 floats
+    uint32_t *kcount;                  // arrivals per column group, zero between launches
 };
 
 __device__ __forceinline__ float silu(float x) { return x / (1.0f + __expf(-x)); }
@@ -94,12 +102,44 @@ __device__ __forceinline__ void linear_epilogue(const LinArgs<T> &a, f32x4 v, in
     }
 }
 
+// The last workgroup of a column group adds the KS partial tiles of each output tile in split order
+// and finishes them.  All of a wave's loads are issued before the first sum.
+template <typename T, int MT, int NT, int NWV, int EPI, int KS>
+__device__ __forceinline__ void linear_finish_split(const LinArgs<T> &a, int group, int n0, int wave, int lane)
+{
+    constexpr int kTiles = MT * NT, kMine = kTiles / NWV;       // tiles per wave
+    static_assert(kTiles % NWV == 0, "every wave finishes the same number of tiles");
+    const int r16 = lane & 15, g = lane >> 4;
+    float2 lo[kMine][KS], hi[kMine][KS];
+#pragma unroll
+    for (int i = 0; i < kMine; ++i)
+#pragma unroll
+        for (int sp = 0; sp < KS; ++sp) {
+            const float *src = a.kpart + ((((size_t)group * KS + sp) * kTiles + wave + i * NWV) * 64 + lane) * 4;
+            lo[i][sp] = rd::ld_dev2(src);
+            hi[i][sp] = rd::ld_dev2(src + 2);
+        }
+#pragma unroll
+    for (int i = 0; i < kMine; ++i) {
+        const int id = wave + i * NWV;
+        f32x4 v = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int sp = 0; sp < KS; ++sp) v += f32x4{lo[i][sp].x, lo[i][sp].y, hi[i][sp].x, hi[i][sp].y};
+        linear_epilogue<T, EPI>(a, v, (id / NT) * 16, n0 + (id % NT) * 16, r16, g);
+    }
+}
+
 // A workgroup owns NT*16 output columns for all M = MT*16 rows; its NWV waves split K.  The host
 // picks NT so that the activations, which every workgroup re-reads through the caches, do not
 // outweigh the weights it streams (their ratio is MT : NT) while the launch still covers the chip,
 // and NWV so that the launch has enough waves in flight to keep the HBM stream busy; every wave's
 // share of K is a whole number of 32-wide steps inside one of the two products.
-template <typename T, int MT, int NT, int NWV, int EPI, bool TILED>
+//
+// KSP: K is also split over a.ksplit workgroups per column group, for layers with so few columns that
+// NT-wide workgroups alone would leave most of the chip idle.  Every workgroup stores its partial
+// tiles (write-through) and signals; the last to arrive for its column group adds the partials in
+// split order (so the sum does not depend on who was last) and runs the epilogue.
+template <typename T, int MT, int NT, int NWV, int EPI, bool TILED, bool KSP = false>
 __global__ __launch_bounds__(NWV * 64) void rd_linear_kernel(LinArgs<T> a)
 {
     typedef typename Elem16<T>::vec8 vec8;
@@ -110,11 +150,15 @@ __global__ __launch_bounds__(NWV * 64) void rd_linear_kernel(LinArgs<T> a)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r16 = lane & 15, g = lane >> 4;
-    const int n0 = blockIdx.x * (16 * NT);
+    const int groups = KSP ? (int)gridDim.x / a.ksplit : (int)gridDim.x;
+    const int group = KSP ? (int)blockIdx.x % groups : (int)blockIdx.x;
+    const int split = KSP ? (int)blockIdx.x / groups : 0;
+    const int n0 = group * (16 * NT);
 
     // this wave's share of the k-steps (32 wide); the host guarantees it lies within one product
     const int ks1 = a.K1 >> 5, ks = ks1 + (a.K2 >> 5);
-    const int kb = (int)((long long)ks * wave / NWV), ke = (int)((long long)ks * (wave + 1) / NWV);
+    const int parts = KSP ? a.ksplit * NWV : NWV, part = split * NWV + wave;
+    const int kb = (int)((long long)ks * part / parts), ke = (int)((long long)ks * (part + 1) / parts);
     const bool second = kb >= ks1;
     const T *wbase = second ? a.w2 : a.w1;
     const int K = second ? a.K2 : a.K1;
@@ -193,8 +237,28 @@ __global__ __launch_bounds__(NWV * 64) void rd_linear_kernel(LinArgs<T> a)
 #pragma unroll
             for (int w = 1; w < NWV; ++w) v += s_part[w][j][lane];
             const int id = p * kGroup + j;
-            linear_epilogue<T, EPI>(a, v, (id / NT) * 16, n0 + (id % NT) * 16, r16, g);
+            if constexpr (KSP)
+                rd::st_dev4(a.kpart + ((((size_t)group * a.ksplit + split) * kTiles + id) * 64 + lane) * 4, v[0], v[1], v[2], v[3]);
+            else
+                linear_epilogue<T, EPI>(a, v, (id / NT) * 16, n0 + (id % NT) * 16, r16, g);
         }
+    }
+    if constexpr (KSP) {
+        __shared__ uint32_t s_last;
+        rd::wait_dev_stores();
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");      // this workgroup's partial tiles are acknowledged
+        __syncthreads();
+        if (tid == 0) {
+            const uint32_t prev = __hip_atomic_fetch_add(a.kcount + group, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_last = (prev + 1u == (uint32_t)a.ksplit) ? 1u : 0u;
+            if (s_last) a.kcount[group] = 0;                        // ready for the next launch
+        }
+        __syncthreads();
+        if (!s_last) return;
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        if (a.ksplit == 8) linear_finish_split<T, MT, NT, NWV, EPI, 8>(a, group, n0, wave, lane);
+        else if (a.ksplit == 4) linear_finish_split<T, MT, NT, NWV, EPI, 4>(a, group, n0, wave, lane);
+        else linear_finish_split<T, MT, NT, NWV, EPI, 2>(a, group, n0, wave, lane);
     }
 }
 
@@ -203,9 +267,11 @@ template <typename T>
 __global__ void rd_draft_init_kernel(const T *__restrict__ emb, const T *__restrict__ h,
                                      const int32_t *__restrict__ last_token, int W, int L, int Dm, int V,
                                      float *__restrict__ x_f32, T *__restrict__ x_bf, T *__restrict__ s_bf,
-                                     int32_t *__restrict__ paths, float *__restrict__ cum)
+                                     int32_t *__restrict__ paths, float *__restrict__ cum, uint32_t *__restrict__ kcount)
 {
     const int m = blockIdx.x, b = m / W;
+    if (m == 0 && kcount)                                      // arrival counters of the split linear layers
+        for (int i = threadIdx.x; i < kSplitMaxGroups; i += blockDim.x) kcount[i] = 0;
     int tok = last_token[b];
     tok = tok < 0 ? 0 : (tok > V - 1 ? V - 1 : tok);
     for (int i = threadIdx.x * 8; i < Dm; i += blockDim.x * 8) {          // Dm is a multiple of 64
@@ -584,7 +650,7 @@ __global__ void rd_pack_weights_kernel(const uint16_t *__restrict__ src, int N, 
 }
 
 struct Plan {
-    size_t x_f32[3], x_bf[3], s_bf[2], logits, part_max, part_sum, part_cv, part_ci, row_score, row_tok, paths[2], cum[2], parent, tok, total;
+    size_t x_f32[3], x_bf[3], s_bf[2], logits, part_max, part_sum, part_cv, part_ci, row_score, row_tok, paths[2], cum[2], parent, tok, kcount, kpart, total;
 };
 
 Plan draft_plan(int B, int W, int L, int Dm, int V)
@@ -606,6 +672,8 @@ Plan draft_plan(int B, int W, int L, int Dm, int V)
     for (int i = 0; i < 2; ++i) { p.paths[i] = take(M * L * 4); p.cum[i] = take(M * 4); }
     p.parent = take(M * 4 * (size_t)(L > 1 ? L - 1 : 1));       // parent rows of every drafted position
     p.tok = take(M * 4);
+    p.kcount = take(kSplitMaxGroups * sizeof(uint32_t));
+    p.kpart = take(M > 32 ? (size_t)kSplitMaxWgs * kSplitTiles * 1024 : 0);   // 33 rows and more: layers may split K over workgroups
     p.total = off;
     return p;
 }
@@ -651,17 +719,55 @@ int launch_linear_nt(const LinArgs<T> &a, hipStream_t stream)
     return rd_check_launch();
 }
 
+// Layers with few columns at 17 rows and more: the widest workgroups the registers allow, and K
+// split over as many workgroups per column group as bring the launch to about one workgroup per
+// compute unit.  False if the shape does not fit (the caller then takes the unsplit kernels).
+template <typename T, int MT, int EPI>
+bool launch_linear_split(const LinArgs<T> &a, hipStream_t stream, int *status)
+{
+    if constexpr (MT >= 4 && EPI != EPI_HEAD) {
+        constexpr int NT = MT == 8 ? 4 : 8;
+        static_assert(MT * NT <= kSplitTiles, "partial tiles per workgroup");
+        constexpr int NWV = 8;                                  // 512 threads: <= 256 registers per lane, no accumulation registers
+        static const int ks_env = rd::env_int("RD_DRAFT_KSPLIT", 0);       // 1: never split; 2, 4, 8: only that split
+        constexpr int max_wgs = kSplitMaxWgs;                   // one workgroup of 8 waves per compute unit at this register count
+        if (a.kpart == nullptr || ks_env == 1) return false;
+        const int groups = (a.N + 16 * NT - 1) / (16 * NT);
+        if (groups > kSplitMaxGroups) return false;
+        const int ks1 = a.K1 / 32, ks = ks1 + a.K2 / 32;
+        auto ok = [&](int split) {                              // whole k-steps per wave, inside one product
+            if (groups * split > max_wgs || ks % (split * NWV) != 0) return false;
+            return a.K2 == 0 || ks1 % (ks / (split * NWV)) == 0;
+        };
+        int split = 0;
+        for (int c = 8; c >= 2 && split == 0; c >>= 1)
+            if ((ks_env == 0 || ks_env == c) && ok(c)) split = c;
+        if (split == 0) return false;
+        LinArgs<T> b = a;
+        b.ksplit = split;
+        const dim3 grid(groups * split);
+        if (a.tiled) hipLaunchKernelGGL((rd_linear_kernel<T, MT, NT, NWV, EPI, true, true>), grid, dim3(NWV * 64), 0, stream, b);
+        else hipLaunchKernelGGL((rd_linear_kernel<T, MT, NT, NWV, EPI, false, true>), grid, dim3(NWV * 64), 0, stream, b);
+        *status = rd_check_launch();
+        return true;
+    } else {
+        return false;
+    }
+}
+
 // column tiles per workgroup: the most that still leave about one workgroup per compute unit (the
 // activation re-reads are MT : NT of the weight bytes, and measured they cost as much as the
 // weights' own stream; halving the workgroups below the number of compute units costs more)
 template <typename T, int MT, int EPI>
 int launch_linear_mt(const LinArgs<T> &a, hipStream_t stream)
 {
+    int status = RD_OK;
+    if (launch_linear_split<T, MT, EPI>(a, stream, &status)) return status;
     if constexpr (MT == 2 || MT == 4) {
         if (a.N >= 240 * 128) return launch_linear_nt<T, MT, 8, EPI>(a, stream);
     }
-    if constexpr (MT >= 4) {
-        if (a.N >= 256 * 64) return launch_linear_nt<T, MT, 4, EPI>(a, stream);
+    if constexpr (MT >= 4) {                                    // (at 113 rows and more even half a chip of these beats narrower ones)
+        if (a.N >= (MT == 8 ? 128 : 256) * 64) return launch_linear_nt<T, MT, 4, EPI>(a, stream);
     }
     if constexpr (MT >= 2) {
         if (a.N >= 256 * 32) return launch_linear_nt<T, MT, 2, EPI>(a, stream);
@@ -713,14 +819,16 @@ int draft_run(const rd_draft_params *p, const void *h, const int32_t *last_token
     int32_t *paths[2] = {reinterpret_cast<int32_t *>(ws + plan.paths[0]), reinterpret_cast<int32_t *>(ws + plan.paths[1])};
     float *cum[2] = {reinterpret_cast<float *>(ws + plan.cum[0]), reinterpret_cast<float *>(ws + plan.cum[1])};
     int32_t *parent = reinterpret_cast<int32_t *>(ws + plan.parent), *tok = reinterpret_cast<int32_t *>(ws + plan.tok);
+    uint32_t *kcount = reinterpret_cast<uint32_t *>(ws + plan.kcount);
+    float *kpart = M > 32 ? reinterpret_cast<float *>(ws + plan.kpart) : nullptr;
     const E *emb = static_cast<const E *>(p->emb);
 
     hipLaunchKernelGGL(rd_draft_init_kernel<E>, dim3(M), dim3(256), 0, s, emb, static_cast<const E *>(h), last_token,
-                       W, L, Dm, V, x_f32[0], x_bf[0], s_bf[0], paths[0], cum[0]);
+                       W, L, Dm, V, x_f32[0], x_bf[0], s_bf[0], paths[0], cum[0], kcount);
     if (rd_check_launch() != RD_OK) return RD_ERR_HIP;
     if (T == 0) {                                   // nothing to draft: the candidates are the LLM's token alone
         hipLaunchKernelGGL(rd_draft_init_kernel<E>, dim3(M), dim3(256), 0, s, emb, static_cast<const E *>(h), last_token,
-                           W, L, Dm, V, x_f32[0], x_bf[0], s_bf[0], beams, beam_logp);
+                           W, L, Dm, V, x_f32[0], x_bf[0], s_bf[0], beams, beam_logp, kcount);
         return rd_check_launch();
     }
     // the h half of X0 must survive the MLP ping-pong: layers write X1 and X2 only
@@ -732,7 +840,7 @@ int draft_run(const rd_draft_params *p, const void *h, const int32_t *last_token
             a.w1 = static_cast<const E *>(p->rnn_u); a.x1 = s_bf[si]; a.map1 = parent + (size_t)(t - 2) * M; a.ldx1 = Dm; a.K1 = Dm;
             a.w2 = static_cast<const E *>(p->rnn_w); a.x2 = emb; a.map2 = tok; a.ldx2 = Dm; a.K2 = Dm;
             a.bias = p->rnn_b; a.M = M; a.N = Dm; a.mstride = 1; a.tiled = p->tiled;
-            a.y_f32 = x_f32[0]; a.y_bf = x_bf[0]; a.s_bf = s_bf[si ^ 1]; a.ldy = G;
+            a.y_f32 = x_f32[0]; a.y_bf = x_bf[0]; a.s_bf = s_bf[si ^ 1]; a.ldy = G; a.kpart = kpart; a.kcount = kcount;
             if (launch_linear<E, EPI_RNN>(a, s) != RD_OK) return RD_ERR_HIP;
             si ^= 1;
         }
@@ -744,7 +852,7 @@ int draft_run(const rd_draft_params *p, const void *h, const int32_t *last_token
             LinArgs<E> a = {};
             a.w1 = static_cast<const E *>(p->mlp_w) + (size_t)k * G * G; a.x1 = x_bf[in]; a.ldx1 = G; a.K1 = G;
             a.bias = p->mlp_b + (size_t)k * G; a.M = rows; a.N = G; a.mstride = mstride; a.tiled = p->tiled;
-            a.y_f32 = x_f32[out]; a.y_bf = x_bf[out]; a.res = x_f32[in]; a.ldy = G;
+            a.y_f32 = x_f32[out]; a.y_bf = x_bf[out]; a.res = x_f32[in]; a.ldy = G; a.kpart = kpart; a.kcount = kcount;
             if (launch_linear<E, EPI_MLP>(a, s) != RD_OK) return RD_ERR_HIP;
             in = out;
         }

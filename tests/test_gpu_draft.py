@@ -84,7 +84,13 @@ def check(rd, p, h, last, W, L, what):
                                           (64, 31000, 1, 3, 8, 3), (64, 32768, 0, 5, 8, 2),
                                           # vocabularies of more than eight chunks of 4096 (one row per wave in the row pass)
                                           (64, 40000, 1, 2, 8, 3), (64, 70001, 0, 1, 4, 3), (64, 151936, 0, 2, 16, 2),
-                                          (64, 262144, 0, 1, 2, 2)])
+                                          (64, 262144, 0, 1, 2, 2),
+                                          # layers whose K is split over 2, 4 and 8 workgroups per column group (hidden
+                                          # sizes of 256, 512, 1024 at more than 32 rows), 16-row tiles x 4 and x 8, and
+                                          # a second launch for the rows past 128 that does not split
+                                          (256, 1000, 2, 5, 8, 4), (512, 1200, 1, 3, 16, 3), (1024, 900, 1, 5, 8, 3),
+                                          (256, 1000, 1, 9, 8, 3), (256, 700, 1, 20, 8, 3), (512, 800, 1, 1, 64, 3),
+                                          (1024, 600, 2, 10, 8, 3)])
 def test_draft_matches_oracle(rd, Dm, V, K, B, W, L):
     announce(f"draft Dm={Dm} V={V} K={K} B={B} W={W} L={L}")
     p = make_params(V, Dm, K, seed=Dm + V, scale=4.0)
@@ -269,7 +275,9 @@ def test_pack_weights_layout(rd, N, K):
 
 @pytest.mark.parametrize("Dm,V,K,B,W,L,dtype", [(64, 500, 2, 2, 4, 5, "bf16"), (128, 1037, 1, 3, 8, 4, "bf16"),
                                                 (64, 17000, 1, 5, 8, 3, "bf16"), (64, 31000, 1, 3, 8, 3, "f16"),
-                                                (64, 700, 1, 20, 8, 4, "bf16"), (256, 1000, 0, 1, 64, 3, "f16")])
+                                                (64, 700, 1, 20, 8, 4, "bf16"), (256, 1000, 0, 1, 64, 3, "f16"),
+                                                # K split over workgroups (more than 32 rows, hidden size a multiple of 256)
+                                                (512, 1200, 1, 5, 8, 3, "bf16"), (256, 900, 1, 9, 8, 3, "f16")])
 def test_packed_weights_give_identical_results(rd, Dm, V, K, B, W, L, dtype):
     """The operand-tiled layout changes where the weights lie, not the arithmetic: beams, scores and the
     recorded logits must be bit-identical to the row-major run (which is checked against the oracle)."""
