@@ -33,6 +33,7 @@ HBM_PEAK_GBS = 8000.0
 # by what the same counter reads for a 64 MiB copy); see profiles/bench_vicuna7b_layer_rocprofv3.md.
 # Keyed by workload; None where no counter run has been made.
 MEASURED_TRAFFIC_BYTES = {2: 21900746}
+LAYERS_BY_HEADS = {32: 32, 40: 40, 52: 60}      # decoder layers of the 7B / 13B / 33B models the shapes come from
 
 
 def parse():
@@ -46,6 +47,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-draft", action="store_true", help="skip the separate rd_draft timing")
     ap.add_argument("--no-floor", action="store_true", help="skip the plain streaming-read floor measurement")
+    ap.add_argument("--no-warm-cache", action="store_true",
+                    help="skip the warm-cache attention figure (so that a kernel trace holds rotating launches only)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time budget of the oracle baseline")
     ap.add_argument("--pmc-calib", action="store_true",
                     help="also run plain device copies of 64 MiB (reference dispatches for scaling rocprofv3 "
@@ -205,6 +208,37 @@ def main():
     attn_us = a0.elapsed_time(a1) * 1e3 / args.steps
     achieved = attn_bytes_mean / (attn_us * 1e-6) / 1e9
 
+    # spread of the attention launch: every replay of the R-launch graph timed on its own (median, 10th and
+    # 90th percentile of the per-launch mean), and the same launch on one copy over and over (K/V then sit in
+    # the caches: reported beside the rotating figure, never instead of it)
+    attn_spread = attn_warm_us = None
+    if use_graph:
+        reps = max(10, min(200, args.steps // R))
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+        with torch.cuda.stream(stream):
+            evs[0].record(stream)
+            for i in range(reps):
+                g_attn.replay()
+                evs[i + 1].record(stream)
+        torch.cuda.synchronize()
+        per = np.array([evs[i].elapsed_time(evs[i + 1]) * 1e3 / R for i in range(reps)])
+        attn_spread = {"p10": round(float(np.percentile(per, 10)), 3), "median": round(float(np.median(per)), 3),
+                       "p90": round(float(np.percentile(per, 90)), 3), "replays": reps, "launches_per_replay": R}
+    if use_graph and not args.no_warm_cache:
+        with torch.cuda.stream(stream):
+            g_warm = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g_warm, stream=stream):
+                for _ in range(R):
+                    attn(copies[0])
+            g_warm.replay()
+            w0, w1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            w0.record(stream)
+            for _ in range(reps):
+                g_warm.replay()
+            w1.record(stream)
+        torch.cuda.synchronize()
+        attn_warm_us = round(w0.elapsed_time(w1) * 1e3 / (reps * R), 3)
+
     # ---- the other kernels one by one (reported beside the headline figures, not part of them) ------
     # rd_commit (what follows the step, Sec. 3.4) appends the accepted rows behind position
     # ctx_len - L here, because the synthetic caches are allocated full.
@@ -339,6 +373,12 @@ def main():
         "packed_tokens_per_step": round(packed_mean, 2),
         "wall_ms_timed_region": round(wall_ms, 3),
         "kernels_us": kernels_us,
+        "rd_tree_attn_us_spread": attn_spread,
+        "rd_tree_attn_us_warm_cache": attn_warm_us,
+        # not measured: one decoder layer's attention core times the layer count of the LLaMA-family model of this
+        # shape (32 / 40 / 60 layers for 32 / 40 / 52 heads), plus the per-step calls; no projections, no MLP
+        "derived_attention_us_per_model_step": None if cfg.H not in LAYERS_BY_HEADS else round(
+            LAYERS_BY_HEADS[cfg.H] * attn_us + kernels_us["rd_dedup"] + kernels_us["rd_accept"], 1),
         "kernels_algorithmic_gbs": kernels_gbs,
         "rd_draft": draft,
         "roofline": {
