@@ -408,7 +408,7 @@ def time_draft(rd, cfg, stream, n, torch):
     load) rotate over two copies so that no launch finds them in cache;
     the roofline figure is the weight bytes one call streams over its duration."""
     Dm, V, K, B, W, L = cfg.H * cfg.D, cfg.V, 2, cfg.B, cfg.W, cfg.L
-    if B * W > 512 or W > 64:
+    if B * W > 512 or W > 128:
         return None                                 # beyond rd_draft's present row limit
     G = 2 * Dm
     gen = torch.Generator(device="cuda")

@@ -41,7 +41,8 @@ template <> struct Elem16<_Float16> {
 
 constexpr int kMaxRows = 512;          // B*W
 constexpr int kRowsPerLaunch = 128;    // rows of one linear-layer launch (8 MFMA row tiles)
-constexpr int kMaxBeam = 64;           // W
+constexpr int kMaxBeam = 128;          // W
+constexpr int kNarrowBeam = 64;        // up to here the selection kernels keep their lists in static LDS, one candidate per lane
 constexpr int kMaxVocab = 262144;      // 64 chunks of 4096 logits: one lane per chunk in the row pass
 constexpr int kSplitMaxWgs = 256;      // workgroups of a launch whose K is split over workgroups
 constexpr int kSplitMaxGroups = 128;   // ... and its column groups (one arrival counter each)
@@ -464,15 +465,15 @@ __global__ __launch_bounds__(kChunkThreads) void rd_topw_chunk_kernel(const floa
 // cumulative scores row_score[row][r] = cum[row] + log p(token r), best first, with the tokens beside
 // them.  LPR lanes serve a row: 8 (eight rows per wave) while the vocabulary has at most eight chunks,
 // else 64 (one row per wave).
-template <int LPR>
+template <int LPR, int WMAX>
 __global__ __launch_bounds__(64) void rd_topw_row_kernel(
     const float *__restrict__ part_max, const float *__restrict__ part_sum, const float *__restrict__ part_cv,
     const int32_t *__restrict__ part_ci, int chunks, const float *__restrict__ cum_cur, int W, int n_rows, int mstride,
     float *__restrict__ row_score, int32_t *__restrict__ row_tok)
 {
     constexpr int kRows = 64 / LPR;                                   // rows per wave
-    __shared__ float s_cv[64 * kMaxBeam];                             // [row in wave][chunk][W], LPR * kMaxBeam per row
-    __shared__ int s_ci[64 * kMaxBeam];
+    __shared__ float s_cv[64 * WMAX];                                 // [row in wave][chunk][W], LPR * WMAX per row
+    __shared__ int s_ci[64 * WMAX];
     const int lane = threadIdx.x, g = lane / LPR, c = lane % LPR;
     const int row_l = blockIdx.x * kRows + g;                         // logical row of this lane's group
     const bool row_ok = row_l < n_rows;
@@ -499,8 +500,8 @@ __global__ __launch_bounds__(64) void rd_topw_row_kernel(
                 const int idx = i0 + u * 64 + lane;
                 if (idx < total) {
                     const int gg = idx / n_surv, q = idx - gg * n_surv;
-                    s_cv[gg * LPR * kMaxBeam + q] = v[u];
-                    s_ci[gg * LPR * kMaxBeam + q] = ti[u];
+                    s_cv[gg * LPR * WMAX + q] = v[u];
+                    s_ci[gg * LPR * WMAX + q] = ti[u];
                 }
             }
         }
@@ -517,8 +518,8 @@ __global__ __launch_bounds__(64) void rd_topw_row_kernel(
     const float base = row_ok ? cum_cur[row] : 0.f;
     __syncthreads();
 
-    const float *lv = s_cv + g * LPR * kMaxBeam + c * W;              // this lane's list: chunk c of its row
-    const int *li = s_ci + g * LPR * kMaxBeam + c * W;
+    const float *lv = s_cv + g * LPR * WMAX + c * W;                  // this lane's list: chunk c of its row
+    const int *li = s_ci + g * LPR * WMAX + c * W;
     int ptr = 0;
     bool live = lane_ok && li[0] != 0x7fffffff;
     float hv = live ? lv[0] : -INFINITY;
@@ -550,7 +551,9 @@ __global__ __launch_bounds__(64) void rd_topw_row_kernel(
 // score.  Every live row's list is sorted (best first; equal scores by smaller token), so this is a
 // merge with lane w holding row w's list: ties go to the smaller candidate, and within a row to the
 // list order, i.e. the smaller token.  Then the paths, the scores and the row maps of the next RNN
-// update are written.
+// update are written.  WIDE (more than 64 candidates): lane w also holds row 64 + w's list, which
+// loses ties against every first list, and the lists live in dynamic LDS (2 * live * W words).
+template <bool WIDE>
 __global__ __launch_bounds__(64) void rd_beam_step_kernel(
     const float *__restrict__ row_score, const int32_t *__restrict__ row_tok, int V,
     int W, int L, int t, int live,
@@ -558,13 +561,16 @@ __global__ __launch_bounds__(64) void rd_beam_step_kernel(
     int32_t *__restrict__ parent_row, int32_t *__restrict__ tok_row,
     int32_t *__restrict__ beams_out, float *__restrict__ logp_out /* both NULL except at the last position */)
 {
-    __shared__ float s_score[kMaxBeam * kMaxBeam];
-    __shared__ int s_ctok[kMaxBeam * kMaxBeam];
-    __shared__ int s_win[kMaxBeam], s_tok[kMaxBeam];
-    __shared__ float s_winv[kMaxBeam];
+    constexpr int kCap = WIDE ? kMaxBeam : kNarrowBeam;
+    __shared__ float s_score_static[WIDE ? 1 : kNarrowBeam * kNarrowBeam];
+    __shared__ int s_ctok_static[WIDE ? 1 : kNarrowBeam * kNarrowBeam];
+    extern __shared__ __align__(16) unsigned char s_dyn[];
+    __shared__ int s_win[kCap], s_tok[kCap];
+    __shared__ float s_winv[kCap];
     const int b = blockIdx.x, lane = threadIdx.x;
-    static_assert(kMaxBeam <= 64, "one lane per live candidate");
     const int n_cand = live * W;
+    float *s_score = WIDE ? reinterpret_cast<float *>(s_dyn) : s_score_static;
+    int *s_ctok = WIDE ? reinterpret_cast<int *>(s_dyn) + n_cand : s_ctok_static;
     for (int i0 = 0; i0 < n_cand; i0 += 64 * 8) {                 // rows b*W .. b*W+live-1 are contiguous
         float v[8];                                               // eight loads per lane in flight together
         int ti[8];
@@ -581,22 +587,42 @@ __global__ __launch_bounds__(64) void rd_beam_step_kernel(
         }
     }
     __syncthreads();
-    int ptr = 0;
-    bool on = lane < live;
+    int ptr = 0, ptr2 = 0;
+    bool on = lane < live, on2 = WIDE && lane + 64 < live;
     float hv = on ? s_score[lane * W] : -INFINITY;
+    float hv2 = on2 ? s_score[(lane + 64) * W] : -INFINITY;
     for (int r = 0; r < W; ++r) {
-        const float best = wave_max(on ? hv : -INFINITY);
+        float offer = on ? hv : -INFINITY;
+        if (WIDE) offer = fmaxf(offer, on2 ? hv2 : -INFINITY);
+        const float best = wave_max(offer);
         int win = first_lane(on && hv == best);
+        bool second = false;                                      // the winner is a second list (candidate 64 + lane)
+        if (WIDE && win < 0) {
+            win = first_lane(on2 && hv2 == best);
+            second = win >= 0;
+        }
         if (win < 0) win = first_lane(on);                        // NaN scores: keep indices in range
+        if (WIDE && win < 0) {
+            win = first_lane(on2);
+            second = win >= 0;
+        }
         if (win < 0) win = 0;
         if (lane == win) {
-            s_win[r] = lane;
+            const int cand = second ? lane + 64 : lane;
+            const int pp = second ? ptr2 : ptr;
+            s_win[r] = cand;
             s_winv[r] = best;
-            const int tk = s_ctok[lane * W + (ptr < W ? ptr : W - 1)];
+            const int tk = s_ctok[cand * W + (pp < W ? pp : W - 1)];
             s_tok[r] = tk < 0 ? 0 : (tk > V - 1 ? V - 1 : tk);
-            ++ptr;
-            on = ptr < W;
-            if (on) hv = s_score[lane * W + ptr];
+            if (second) {
+                ++ptr2;
+                on2 = ptr2 < W;
+                if (on2) hv2 = s_score[cand * W + ptr2];
+            } else {
+                ++ptr;
+                on = ptr < W;
+                if (on) hv = s_score[cand * W + ptr];
+            }
         }
     }
     __syncthreads();
@@ -609,11 +635,11 @@ __global__ __launch_bounds__(64) void rd_beam_step_kernel(
         paths_next[((size_t)b * W + r) * L + j] = v;
         if (beams_out) beams_out[((size_t)b * W + r) * L + j] = v;
     }
-    if (lane < W) {
-        cum_next[(size_t)b * W + lane] = s_winv[lane];
-        parent_row[(size_t)b * W + lane] = b * W + s_win[lane];
-        tok_row[(size_t)b * W + lane] = s_tok[lane];
-        if (logp_out) logp_out[(size_t)b * W + lane] = s_winv[lane];
+    for (int w = lane; w < W; w += 64) {
+        cum_next[(size_t)b * W + w] = s_winv[w];
+        parent_row[(size_t)b * W + w] = b * W + s_win[w];
+        tok_row[(size_t)b * W + w] = s_tok[w];
+        if (logp_out) logp_out[(size_t)b * W + w] = s_winv[w];
     }
 }
 
@@ -867,16 +893,31 @@ int draft_run(const rd_draft_params *p, const void *h, const int32_t *last_token
                            part_max, part_sum, part_cv, part_ci);
         if (rd_check_launch() != RD_OK) return RD_ERR_HIP;
         const bool last = t == T;
-        if (chunks <= 8)
-            hipLaunchKernelGGL(rd_topw_row_kernel<8>, dim3((rows + 7) / 8), dim3(64), 0, s, part_max, part_sum, part_cv, part_ci,
-                               chunks, cum[cur], W, rows, mstride, row_score, row_tok);
-        else
-            hipLaunchKernelGGL(rd_topw_row_kernel<64>, dim3(rows), dim3(64), 0, s, part_max, part_sum, part_cv, part_ci,
-                               chunks, cum[cur], W, rows, mstride, row_score, row_tok);
+        const bool wide = W > kNarrowBeam;
+        const int live = t == 1 ? 1 : W;
+#define RD_ROW_LAUNCH(LPR, WMAX, grid)                                                                                   \
+        hipLaunchKernelGGL((rd_topw_row_kernel<LPR, WMAX>), dim3(grid), dim3(64), 0, s, part_max, part_sum, part_cv, part_ci, \
+                           chunks, cum[cur], W, rows, mstride, row_score, row_tok)
+        if (chunks <= 8) {
+            if (wide) RD_ROW_LAUNCH(8, kMaxBeam, (rows + 7) / 8); else RD_ROW_LAUNCH(8, kNarrowBeam, (rows + 7) / 8);
+        } else {
+            if (wide) RD_ROW_LAUNCH(64, kMaxBeam, rows); else RD_ROW_LAUNCH(64, kNarrowBeam, rows);
+        }
+#undef RD_ROW_LAUNCH
         if (rd_check_launch() != RD_OK) return RD_ERR_HIP;
-        hipLaunchKernelGGL(rd_beam_step_kernel, dim3(B), dim3(64), 0, s, row_score, row_tok, V, W, L, t,
-                           t == 1 ? 1 : W, paths[cur], paths[nxt], cum[nxt], parent + (size_t)(t - 1) * M, tok,
-                           last ? beams : nullptr, last ? beam_logp : nullptr);
+        if (wide) {
+            static std::atomic<unsigned long long> configured{0};
+            if (rd::ensure_dynamic_lds(reinterpret_cast<const void *>(&rd_beam_step_kernel<true>), (size_t)kMaxBeam * kMaxBeam * 8,
+                                       configured) != RD_OK)
+                return RD_ERR_HIP;
+            hipLaunchKernelGGL(rd_beam_step_kernel<true>, dim3(B), dim3(64), (size_t)live * W * 8, s, row_score, row_tok, V, W, L, t,
+                               live, paths[cur], paths[nxt], cum[nxt], parent + (size_t)(t - 1) * M, tok,
+                               last ? beams : nullptr, last ? beam_logp : nullptr);
+        } else {
+            hipLaunchKernelGGL(rd_beam_step_kernel<false>, dim3(B), dim3(64), 0, s, row_score, row_tok, V, W, L, t,
+                               live, paths[cur], paths[nxt], cum[nxt], parent + (size_t)(t - 1) * M, tok,
+                               last ? beams : nullptr, last ? beam_logp : nullptr);
+        }
         if (rd_check_launch() != RD_OK) return RD_ERR_HIP;
     }
     if (step_row) {

@@ -259,7 +259,7 @@ def test_draft_argument_errors(lib):
     assert call(B=0) == INVALID
     assert call(Dm=0) == INVALID
     assert call(Dm=96) == UNSUPPORTED                        # multiple of 64
-    assert call(W=65, V=100) == UNSUPPORTED
+    assert call(W=129, V=1000) == UNSUPPORTED
     assert call(B=200, W=4) == UNSUPPORTED                   # B*W <= 512
     assert call(V=300000) == UNSUPPORTED
     assert call(V=3, W=4) == UNSUPPORTED                     # W <= V

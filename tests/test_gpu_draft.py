@@ -90,7 +90,12 @@ def check(rd, p, h, last, W, L, what):
                                           # a second launch for the rows past 128 that does not split
                                           (256, 1000, 2, 5, 8, 4), (512, 1200, 1, 3, 16, 3), (1024, 900, 1, 5, 8, 3),
                                           (256, 1000, 1, 9, 8, 3), (256, 700, 1, 20, 8, 3), (512, 800, 1, 1, 64, 3),
-                                          (1024, 600, 2, 10, 8, 3)])
+                                          (1024, 600, 2, 10, 8, 3),
+                                          # more than 64 candidates (two lists per lane in the beam step): the paper's widest
+                                          # sweep (70), the limit (128), several sequences, a vocabulary of more than 8 chunks
+                                          (64, 3000, 1, 1, 70, 3), (64, 2000, 1, 1, 128, 3), (128, 1500, 1, 3, 70, 4),
+                                          (64, 500, 0, 4, 128, 2), (64, 40000, 0, 1, 70, 3), (64, 129, 1, 2, 128, 3),
+                                          (256, 5000, 2, 1, 96, 5), (64, 4200, 1, 2, 65, 3)])
 def test_draft_matches_oracle(rd, Dm, V, K, B, W, L):
     announce(f"draft Dm={Dm} V={V} K={K} B={B} W={W} L={L}")
     p = make_params(V, Dm, K, seed=Dm + V, scale=4.0)
@@ -172,7 +177,7 @@ def test_draft_vicuna7b_dimensions(rd):
 
 
 @pytest.mark.parametrize("Dm,V,K,B,W,L", [(64, 500, 2, 2, 4, 5), (128, 4000, 1, 3, 8, 4), (64, 9000, 1, 3, 8, 3),
-                                          (64, 300, 1, 2, 1, 4), (64, 200, 1, 2, 4, 1)])
+                                          (64, 300, 1, 2, 1, 4), (64, 200, 1, 2, 4, 1), (64, 3000, 1, 2, 70, 3)])
 def test_draft_records_the_search(rd, Dm, V, K, B, W, L):
     """step_logits / step_row: the row recorded behind every candidate token must hold the draft
     distribution given that candidate's prefix (the oracle's record, where the beams agree), rows of
