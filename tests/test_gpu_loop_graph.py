@@ -101,3 +101,48 @@ def test_sampling_loop_eager_and_graph():
         got = snapshot()
         for k in eager:
             assert np.array_equal(got[k], eager[k]), (rep, k)
+
+
+def test_greedy_loop_at_the_widest_beams():
+    """The token-matching loop at the widest beams of the paper's sweep (Sec. 4.3: 70 candidates of 5
+    tokens, 350 packed slots): rd_draft -> rd_dedup -> rd_tree_attn -> rd_accept -> rd_commit on the
+    device, every link checked against the oracle on the device's own inputs."""
+    assert torch.cuda.is_available(), "GPU tests need a device"
+    from paper_2403_09919_amd import binding as rd
+    announce("draft -> dedup -> attention -> accept -> commit at W=70, L=5")
+    Dm, V, K, B, W, L, H, D, Cmax = 64, 2000, 1, 2, 70, 5, 2, 128, 512
+    N = W * L
+    p = make_params(V, Dm, K, seed=70, scale=4.0)
+    rng = np.random.default_rng(70)
+    h = synth.f32_to_bf16_bits(rng.standard_normal((B, Dm)).astype(np.float32))
+    last = rng.integers(0, V, B).astype(np.int32)
+    ctx = np.array([300, 41], np.int32)
+    q, k_new, v_new = synth.make_qkv_new(B, H, N, D, "bf16", 70)
+    k_cache, v_cache = synth.make_kv_cache(B, H, Cmax, D, "bf16", 70, ctx, False)
+
+    dr = rd.rd_draft({k: dev(v) for k, v in p.items()}, dev(h), dev(last), W, L)
+    d = rd.rd_dedup(dr["beams"], dev(ctx))
+    torch.cuda.synchronize()
+    beams = host(dr["beams"])
+    assert (beams[:, :, 0] == last[:, None]).all()
+    assert all(len({tuple(x) for x in beams[b].tolist()}) == W for b in range(B))
+    dref = oracle.dedup(beams, ctx)
+    for k in ("packed_tokens", "n_packed", "unpack_index", "parent", "position_ids"):
+        assert np.array_equal(host(d[k]), dref[k]), k
+    assert (dref["n_packed"] < N).all()                           # the candidates share their first token at least
+
+    # logits that follow one candidate for a while: the planted path of synth.make_logits
+    logits = synth.make_logits(B, N, V, 70, dref["packed_tokens"], dref["parent"], dref["n_packed"], 0.7)
+    kd, vd = dev(k_cache), dev(v_cache)
+    o = rd.rd_tree_attn(dev(q), kd, vd, dev(ctx), dev(k_new), dev(v_new), d["n_packed"], d["tree_mask_bits"], 0.0884)
+    a = rd.rd_accept(dev(logits), dr["beams"], d["unpack_index"], d["n_packed"])
+    c = rd.rd_commit(dev(k_new), dev(v_new), a["accepted_idx"], a["best_len"], dev(ctx), kd, vd)
+    torch.cuda.synchronize()
+    aref = oracle.tree_attn(q, k_cache, v_cache, ctx, k_new, v_new, dref["n_packed"], dref["tree_mask"], "bf16", 0.0884)
+    assert np.abs(synth.to_f64(host(o), "bf16") - synth.to_f64(aref, "bf16")).max() <= 2e-2
+    acc = oracle.accept(beams, dref["unpack_index"], oracle.argmax(logits, dref["n_packed"]))
+    for k in ("n_accept", "best_beam", "best_len", "next_token", "accepted_idx"):
+        assert np.array_equal(host(a[k]), acc[k]), k
+    cref = oracle.commit(k_new, v_new, acc["accepted_idx"], acc["best_len"], ctx, k_cache, v_cache, "bf16")
+    assert np.array_equal(host(kd), cref["k_cache"]) and np.array_equal(host(vd), cref["v_cache"])
+    assert np.array_equal(host(c["ctx_len"]), cref["ctx_len"])
