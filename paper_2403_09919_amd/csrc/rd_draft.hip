@@ -43,6 +43,7 @@ constexpr int kMaxRows = 512;          // B*W
 constexpr int kRowsPerLaunch = 128;    // rows of one linear-layer launch (8 MFMA row tiles)
 constexpr int kMaxBeam = 128;          // W
 constexpr int kNarrowBeam = 64;        // up to here the selection kernels keep their lists in static LDS, one candidate per lane
+constexpr int kSelThreads = 256;       // row pass and beam step: four waves bring the lists into LDS, the first one merges
 constexpr int kMaxVocab = 262144;      // 64 chunks of 4096 logits: one lane per chunk in the row pass
 constexpr int kSplitMaxWgs = 256;      // workgroups of a launch whose K is split over workgroups
 constexpr int kSplitMaxGroups = 128;   // ... and its column groups (one arrival counter each)
@@ -410,9 +411,11 @@ __global__ __launch_bounds__(kChunkThreads) void rd_topw_chunk_kernel(const floa
     }
     // (a lane reads back only its own column: no barrier needed before the merge)
 
-    // merge of the wave's 64 lists
-    float hv = n_valid > 0 ? x[0] : -INFINITY;
-    int hk = k[0], ptr = 0;
+    // merge of the wave's 64 lists.  Every lane keeps its head and the entry behind it in registers, so
+    // a winner moves on without waiting for LDS; the read that refills the second register is only
+    // waited for when the same lane wins again.
+    float hv = n_valid > 0 ? x[0] : -INFINITY, nv = x[1];
+    int hk = k[0], nk = k[1], ptr = 0;
     bool live = n_valid > 0;
     for (int r = 0; r < W; ++r) {
         const float best = wave_max(live ? hv : -INFINITY);
@@ -429,7 +432,9 @@ __global__ __launch_bounds__(kChunkThreads) void rd_topw_chunk_kernel(const floa
         if (lane == win) {
             ++ptr;
             live = ptr < n_valid;
-            if (live) { hv = s_lv[ptr][tid]; hk = s_lk[ptr][tid]; }
+            hv = nv; hk = nk;
+            const int nx = ptr + 1 < kChunkPer ? ptr + 1 : kChunkPer - 1;
+            nv = s_lv[nx][tid]; nk = s_lk[nx][tid];
         }
     }
     __syncthreads();
@@ -441,8 +446,10 @@ __global__ __launch_bounds__(kChunkThreads) void rd_topw_chunk_kernel(const floa
     }
     // merge of the four waves' lists (a lower wave holds smaller tokens): lanes 0..3
     int p4 = 0;
-    float h4 = lane < kWaves ? s_cv[lane][0] : -INFINITY;
-    bool live4 = lane < kWaves && s_ci[lane & (kWaves - 1)][0] != 0x7fffffff;
+    const int l4 = lane & (kWaves - 1);
+    float h4 = s_cv[l4][0], n4 = s_cv[l4][W > 1 ? 1 : 0];
+    int i4 = s_ci[l4][0], j4 = s_ci[l4][W > 1 ? 1 : 0];
+    bool live4 = lane < kWaves && i4 != 0x7fffffff;
     for (int r = 0; r < W; ++r) {
         const float best = wave_max(live4 ? h4 : -INFINITY);
         const int win = first_lane(live4 && h4 == best);
@@ -452,10 +459,12 @@ __global__ __launch_bounds__(kChunkThreads) void rd_topw_chunk_kernel(const floa
         }
         if (lane == win) {
             part_cv[slot * W + r] = best;
-            part_ci[slot * W + r] = s_ci[lane][p4];
+            part_ci[slot * W + r] = i4;
             ++p4;
-            live4 = p4 < W && s_ci[lane][p4 < W ? p4 : 0] != 0x7fffffff;
-            if (live4) h4 = s_cv[lane][p4];
+            h4 = n4; i4 = j4;
+            live4 = p4 < W && i4 != 0x7fffffff;
+            const int nx = p4 + 1 < W ? p4 + 1 : W - 1;
+            n4 = s_cv[l4][nx]; j4 = s_ci[l4][nx];
         }
     }
 }
@@ -466,7 +475,7 @@ __global__ __launch_bounds__(kChunkThreads) void rd_topw_chunk_kernel(const floa
 // them.  LPR lanes serve a row: 8 (eight rows per wave) while the vocabulary has at most eight chunks,
 // else 64 (one row per wave).
 template <int LPR, int WMAX>
-__global__ __launch_bounds__(64) void rd_topw_row_kernel(
+__global__ __launch_bounds__(kSelThreads) void rd_topw_row_kernel(
     const float *__restrict__ part_max, const float *__restrict__ part_sum, const float *__restrict__ part_cv,
     const int32_t *__restrict__ part_ci, int chunks, const float *__restrict__ cum_cur, int W, int n_rows, int mstride,
     float *__restrict__ row_score, int32_t *__restrict__ row_tok)
@@ -474,40 +483,13 @@ __global__ __launch_bounds__(64) void rd_topw_row_kernel(
     constexpr int kRows = 64 / LPR;                                   // rows per wave
     __shared__ float s_cv[64 * WMAX];                                 // [row in wave][chunk][W], LPR * WMAX per row
     __shared__ int s_ci[64 * WMAX];
-    const int lane = threadIdx.x, g = lane / LPR, c = lane % LPR;
+    const int tid = threadIdx.x, lane = tid & 63, g = lane / LPR, c = lane % LPR;
     const int row_l = blockIdx.x * kRows + g;                         // logical row of this lane's group
     const bool row_ok = row_l < n_rows;
     const size_t row = (size_t)(row_ok ? row_l : n_rows - 1) * mstride;
     const int n_surv = chunks * W;
-    // the survivors of the wave's rows -> LDS; eight loads per lane in flight together, addresses
-    // past the end pulled back (no load sits behind a branch)
-    {
-        const int rows_here = min(kRows, n_rows - blockIdx.x * kRows);
-        const int total = rows_here * n_surv;
-        for (int i0 = 0; i0 < total; i0 += 64 * 8) {
-            float v[8];
-            int ti[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int idx = min(i0 + u * 64 + lane, total - 1);
-                const int gg = idx / n_surv, q = idx - gg * n_surv;
-                const size_t src = (size_t)(blockIdx.x * kRows + gg) * mstride * n_surv + q;
-                v[u] = part_cv[src];
-                ti[u] = part_ci[src];
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int idx = i0 + u * 64 + lane;
-                if (idx < total) {
-                    const int gg = idx / n_surv, q = idx - gg * n_surv;
-                    s_cv[gg * LPR * WMAX + q] = v[u];
-                    s_ci[gg * LPR * WMAX + q] = ti[u];
-                }
-            }
-        }
-    }
     auto group_max = [](float x) { return LPR == 8 ? group8_max(x) : wave_max(x); };
-    // log-sum-exp of the row: sum_c part_sum[c] * exp(part_max[c] - max)
+    // log-sum-exp of the row: sum_c part_sum[c] * exp(part_max[c] - max) (loads issued before the staging below)
     const bool lane_ok = row_ok && c < chunks;
     const float pm = lane_ok ? part_max[row * chunks + c] : -INFINITY;
     const float gm = group_max(pm);
@@ -516,13 +498,43 @@ __global__ __launch_bounds__(64) void rd_topw_row_kernel(
     for (int off = 1; off < LPR; off <<= 1) ps += __shfl_xor(ps, off, 64);
     const float lse = gm + __logf(ps);
     const float base = row_ok ? cum_cur[row] : 0.f;
+    // the survivors of the workgroup's rows -> LDS, by all four waves (one wave alone would spend most of
+    // the kernel here at wide beams); eight loads per lane in flight together, addresses past the end
+    // pulled back (no load sits behind a branch)
+    {
+        const int rows_here = min(kRows, n_rows - blockIdx.x * kRows);
+        const int total = rows_here * n_surv;
+        for (int i0 = 0; i0 < total; i0 += kSelThreads * 8) {
+            float v[8];
+            int ti[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = min(i0 + u * kSelThreads + tid, total - 1);
+                const int gg = idx / n_surv, q = idx - gg * n_surv;
+                const size_t src = (size_t)(blockIdx.x * kRows + gg) * mstride * n_surv + q;
+                v[u] = part_cv[src];
+                ti[u] = part_ci[src];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = i0 + u * kSelThreads + tid;
+                if (idx < total) {
+                    const int gg = idx / n_surv, q = idx - gg * n_surv;
+                    s_cv[gg * LPR * WMAX + q] = v[u];
+                    s_ci[gg * LPR * WMAX + q] = ti[u];
+                }
+            }
+        }
+    }
     __syncthreads();
+    if (tid >= 64) return;                                            // the merge is one wave's work
 
     const float *lv = s_cv + g * LPR * WMAX + c * W;                  // this lane's list: chunk c of its row
     const int *li = s_ci + g * LPR * WMAX + c * W;
     int ptr = 0;
-    bool live = lane_ok && li[0] != 0x7fffffff;
-    float hv = live ? lv[0] : -INFINITY;
+    int ht = li[0], nt = li[W > 1 ? 1 : 0];                           // head and the entry behind it, in registers
+    float hv = lv[0], nv = lv[W > 1 ? 1 : 0];
+    bool live = lane_ok && ht != 0x7fffffff;
     for (int r = 0; r < W; ++r) {
         const float best = group_max(live ? hv : -INFINITY);
         const unsigned long long offers = __ballot(live && hv == best);
@@ -537,10 +549,12 @@ __global__ __launch_bounds__(64) void rd_topw_row_kernel(
             row_score[row * W + r] = win >= 0 ? base + (best - lse) : -INFINITY;
         }
         if (c == win) {
-            row_tok[row * W + r] = li[ptr];
+            row_tok[row * W + r] = ht;
             ++ptr;
-            live = ptr < W && li[ptr < W ? ptr : 0] != 0x7fffffff;
-            if (live) hv = lv[ptr];
+            hv = nv; ht = nt;
+            live = ptr < W && ht != 0x7fffffff;
+            const int nx = ptr + 1 < W ? ptr + 1 : W - 1;
+            nv = lv[nx]; nt = li[nx];
         } else if (c == 0 && win < 0 && row_ok) {
             row_tok[row * W + r] = 0;
         }
@@ -554,7 +568,7 @@ __global__ __launch_bounds__(64) void rd_topw_row_kernel(
 // update are written.  WIDE (more than 64 candidates): lane w also holds row 64 + w's list, which
 // loses ties against every first list, and the lists live in dynamic LDS (2 * live * W words).
 template <bool WIDE>
-__global__ __launch_bounds__(64) void rd_beam_step_kernel(
+__global__ __launch_bounds__(kSelThreads) void rd_beam_step_kernel(
     const float *__restrict__ row_score, const int32_t *__restrict__ row_tok, int V,
     int W, int L, int t, int live,
     const int32_t *__restrict__ paths_cur, int32_t *__restrict__ paths_next, float *__restrict__ cum_next,
@@ -565,32 +579,37 @@ __global__ __launch_bounds__(64) void rd_beam_step_kernel(
     __shared__ float s_score_static[WIDE ? 1 : kNarrowBeam * kNarrowBeam];
     __shared__ int s_ctok_static[WIDE ? 1 : kNarrowBeam * kNarrowBeam];
     extern __shared__ __align__(16) unsigned char s_dyn[];
-    __shared__ int s_win[kCap], s_tok[kCap];
+    __shared__ int s_win[kCap], s_tok[kCap], s_ptr[kCap];
     __shared__ float s_winv[kCap];
-    const int b = blockIdx.x, lane = threadIdx.x;
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
     const int n_cand = live * W;
     float *s_score = WIDE ? reinterpret_cast<float *>(s_dyn) : s_score_static;
     int *s_ctok = WIDE ? reinterpret_cast<int *>(s_dyn) + n_cand : s_ctok_static;
-    for (int i0 = 0; i0 < n_cand; i0 += 64 * 8) {                 // rows b*W .. b*W+live-1 are contiguous
+    for (int i0 = 0; i0 < n_cand; i0 += kSelThreads * 8) {        // rows b*W .. b*W+live-1 are contiguous
         float v[8];                                               // eight loads per lane in flight together
         int ti[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            const int idx = min(i0 + u * 64 + lane, n_cand - 1);
+            const int idx = min(i0 + u * kSelThreads + tid, n_cand - 1);
             v[u] = row_score[(size_t)b * W * W + idx];
             ti[u] = row_tok[(size_t)b * W * W + idx];
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            const int idx = i0 + u * 64 + lane;
+            const int idx = i0 + u * kSelThreads + tid;
             if (idx < n_cand) { s_score[idx] = v[u]; s_ctok[idx] = ti[u]; }
         }
     }
     __syncthreads();
+    if (tid < 64) {                                               // the merge is one wave's work
+    // Every lane keeps the head of its list and the entry behind it in registers, so the winner moves
+    // on without waiting for LDS; the rounds only record (candidate, position in its list) and the
+    // tokens are looked up afterwards, W at a time.
     int ptr = 0, ptr2 = 0;
     bool on = lane < live, on2 = WIDE && lane + 64 < live;
-    float hv = on ? s_score[lane * W] : -INFINITY;
-    float hv2 = on2 ? s_score[(lane + 64) * W] : -INFINITY;
+    const int la = (on ? lane : 0) * W, lb = (on2 ? lane + 64 : 0) * W;
+    float hv = s_score[la], nv = s_score[la + (W > 1 ? 1 : 0)];
+    float hv2 = s_score[lb], nv2 = s_score[lb + (W > 1 ? 1 : 0)];
     for (int r = 0; r < W; ++r) {
         float offer = on ? hv : -INFINITY;
         if (WIDE) offer = fmaxf(offer, on2 ? hv2 : -INFINITY);
@@ -608,26 +627,36 @@ __global__ __launch_bounds__(64) void rd_beam_step_kernel(
         }
         if (win < 0) win = 0;
         if (lane == win) {
-            const int cand = second ? lane + 64 : lane;
-            const int pp = second ? ptr2 : ptr;
-            s_win[r] = cand;
+            s_win[r] = second ? lane + 64 : lane;
             s_winv[r] = best;
-            const int tk = s_ctok[cand * W + (pp < W ? pp : W - 1)];
-            s_tok[r] = tk < 0 ? 0 : (tk > V - 1 ? V - 1 : tk);
-            if (second) {
-                ++ptr2;
-                on2 = ptr2 < W;
-                if (on2) hv2 = s_score[cand * W + ptr2];
+            if (WIDE && second) {
+                s_ptr[r] = ptr2 < W ? ptr2 : W - 1;
+                if (on2) {
+                    ++ptr2;
+                    on2 = ptr2 < W;
+                    hv2 = nv2;
+                    nv2 = s_score[lb + (ptr2 + 1 < W ? ptr2 + 1 : W - 1)];
+                }
             } else {
-                ++ptr;
-                on = ptr < W;
-                if (on) hv = s_score[cand * W + ptr];
+                s_ptr[r] = ptr < W ? ptr : W - 1;
+                if (on) {                                         // (not so only when no list had anything left to offer)
+                    ++ptr;
+                    on = ptr < W;
+                    hv = nv;
+                    nv = s_score[la + (ptr + 1 < W ? ptr + 1 : W - 1)];
+                }
             }
         }
     }
+    }
+    __syncthreads();
+    for (int r = tid; r < W; r += kSelThreads) {
+        const int tk = s_ctok[s_win[r] * W + s_ptr[r]];
+        s_tok[r] = tk < 0 ? 0 : (tk > V - 1 ? V - 1 : tk);
+    }
     __syncthreads();
     // candidate r: parent pw = s_win[r], new token s_tok[r]
-    for (int i = lane; i < W * L; i += 64) {
+    for (int i = tid; i < W * L; i += kSelThreads) {
         const int r = i / L, j = i - r * L;
         const int pw = s_win[r];
         const size_t src = ((size_t)b * W + pw) * L;
@@ -635,7 +664,7 @@ __global__ __launch_bounds__(64) void rd_beam_step_kernel(
         paths_next[((size_t)b * W + r) * L + j] = v;
         if (beams_out) beams_out[((size_t)b * W + r) * L + j] = v;
     }
-    for (int w = lane; w < W; w += 64) {
+    for (int w = tid; w < W; w += kSelThreads) {
         cum_next[(size_t)b * W + w] = s_winv[w];
         parent_row[(size_t)b * W + w] = b * W + s_win[w];
         tok_row[(size_t)b * W + w] = s_tok[w];
@@ -896,7 +925,7 @@ int draft_run(const rd_draft_params *p, const void *h, const int32_t *last_token
         const bool wide = W > kNarrowBeam;
         const int live = t == 1 ? 1 : W;
 #define RD_ROW_LAUNCH(LPR, WMAX, grid)                                                                                   \
-        hipLaunchKernelGGL((rd_topw_row_kernel<LPR, WMAX>), dim3(grid), dim3(64), 0, s, part_max, part_sum, part_cv, part_ci, \
+        hipLaunchKernelGGL((rd_topw_row_kernel<LPR, WMAX>), dim3(grid), dim3(kSelThreads), 0, s, part_max, part_sum, part_cv, part_ci, \
                            chunks, cum[cur], W, rows, mstride, row_score, row_tok)
         if (chunks <= 8) {
             if (wide) RD_ROW_LAUNCH(8, kMaxBeam, (rows + 7) / 8); else RD_ROW_LAUNCH(8, kNarrowBeam, (rows + 7) / 8);
@@ -910,11 +939,11 @@ int draft_run(const rd_draft_params *p, const void *h, const int32_t *last_token
             if (rd::ensure_dynamic_lds(reinterpret_cast<const void *>(&rd_beam_step_kernel<true>), (size_t)kMaxBeam * kMaxBeam * 8,
                                        configured) != RD_OK)
                 return RD_ERR_HIP;
-            hipLaunchKernelGGL(rd_beam_step_kernel<true>, dim3(B), dim3(64), (size_t)live * W * 8, s, row_score, row_tok, V, W, L, t,
+            hipLaunchKernelGGL(rd_beam_step_kernel<true>, dim3(B), dim3(kSelThreads), (size_t)live * W * 8, s, row_score, row_tok, V, W, L, t,
                                live, paths[cur], paths[nxt], cum[nxt], parent + (size_t)(t - 1) * M, tok,
                                last ? beams : nullptr, last ? beam_logp : nullptr);
         } else {
-            hipLaunchKernelGGL(rd_beam_step_kernel<false>, dim3(B), dim3(64), 0, s, row_score, row_tok, V, W, L, t,
+            hipLaunchKernelGGL(rd_beam_step_kernel<false>, dim3(B), dim3(kSelThreads), 0, s, row_score, row_tok, V, W, L, t,
                                live, paths[cur], paths[nxt], cum[nxt], parent + (size_t)(t - 1) * M, tok,
                                last ? beams : nullptr, last ? beam_logp : nullptr);
         }
