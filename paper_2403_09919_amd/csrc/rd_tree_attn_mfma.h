@@ -333,7 +333,8 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
 
     // The block loop is instantiated twice: for all row tiles, and for the lower half when the
     // packed rows fit there (a padded tile costs as much as a real one, and branches around it
-    // would stop the compiler from overlapping LDS reads with the matrix instructions).
+    // would stop the compiler from overlapping LDS reads with the matrix instructions); the
+    // five-tile kernel, whose full loop is short of registers, has a third for four tiles.
     auto block_loop = [&](auto nqa_tag) __attribute__((always_inline)) {
         constexpr int NQA = decltype(nqa_tag)::value;
         for (int ib = 0; ib < nb; ++ib) {
@@ -516,6 +517,7 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
     };
     constexpr int kHalf = (NQ + 1) / 2;
     if (NQ > 1 && nqt <= kHalf) block_loop(std::integral_constant<int, kHalf>{});
+    else if (NQ == 5 && nqt == 4) block_loop(std::integral_constant<int, NQ == 5 ? 4 : NQ>{});   // five tiles spill; four do not
     else block_loop(std::integral_constant<int, NQ>{});
     RD_TR(3);
 
