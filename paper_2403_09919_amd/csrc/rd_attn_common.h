@@ -12,7 +12,6 @@
 // the whole operation is a single launch.
 #pragma once
 #include "rd_internal.h"
-#include <atomic>
 
 namespace rd {
 
@@ -31,12 +30,6 @@ struct AttnPlan {
     size_t partial_floats;   // floats per partial: m[rows_pad] + l[rows_pad] + O[rows_pad][D]
     size_t total_bytes;
 };
-
-static inline int env_int(const char *name, int dflt)
-{
-    const char *v = getenv(name);
-    return (v && *v) ? atoi(v) : dflt;
-}
 
 // How many context splits per (sequence, head), and whether the packed keys ride on the last
 // context range.  Measured behaviour of the kernel on MI355X that the estimate encodes:
@@ -107,20 +100,6 @@ static inline AttnPlan attn_plan(int B, int H, int N, int D, int Cmax, size_t el
     return p;
 }
 
-// Raising a kernel's dynamic LDS limit is per kernel and per device; `done` (one per kernel) keeps
-// a bit for each device already set up.  Returns RD_OK or RD_ERR_HIP.
-static inline int ensure_dynamic_lds(const void *kernel, size_t bytes, std::atomic<unsigned long long> &done)
-{
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return RD_ERR_HIP;
-    const unsigned long long bit = 1ull << (dev & 63);
-    if (dev < 64 && (done.load(std::memory_order_acquire) & bit)) return RD_OK;
-    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess)
-        return RD_ERR_HIP;
-    if (dev < 64) done.fetch_or(bit, std::memory_order_release);
-    return RD_OK;
-}
-
 struct AttnArgs {
     const void *q, *k_cache, *v_cache, *k_new, *v_new;
     const int32_t *ctx_len, *n_packed;
@@ -170,44 +149,6 @@ __device__ __forceinline__ void store_out4(_Float16 *dst, float a, float b, floa
     v[0] = (_Float16)a; v[1] = (_Float16)b; v[2] = (_Float16)c; v[3] = (_Float16)d;   // round to nearest even
     *reinterpret_cast<f16x4 *>(dst) = v;
 }
-
-// ---- exchange of partial results between workgroups -------------------------------------------
-// The partials are written by one workgroup and read by another that may sit on a different
-// XCD (each XCD has its own L2).  A device-wide release/acquire fence would write back and
-// invalidate whole L2s on every workgroup, which costs far more than the kernel itself, so the
-// exchange uses device-scope (write-through / cache-bypassing) relaxed atomic accesses for the
-// data itself, made complete with a wait for outstanding memory operations before the counter
-// is bumped.  Only these few KB per workgroup travel that way; the K/V stream uses plain loads.
-__device__ __forceinline__ void st_dev(float *p, float v)
-{
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void st_dev2(float *p, float a, float b)
-{
-    unsigned long long u = (unsigned long long)__float_as_uint(a) | ((unsigned long long)__float_as_uint(b) << 32);
-    __hip_atomic_store(reinterpret_cast<unsigned long long *>(p), u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float ld_dev(const float *p)
-{
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float2 ld_dev2(const float *p)
-{
-    const unsigned long long u =
-        __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return make_float2(__uint_as_float((unsigned)u), __uint_as_float((unsigned)(u >> 32)));
-}
-
-// 16-byte device-scope store (write-through); the caller must call wait_dev_stores() before it
-// signals completion, because the compiler does not count this store as outstanding.
-__device__ __forceinline__ void st_dev4(float *p, float a, float b, float c, float d)
-{
-    typedef __attribute__((ext_vector_type(4))) float f32x4_t;
-    const f32x4_t v = {a, b, c, d};
-    // the leading s_nop covers register-write hazards the compiler cannot see into the asm for
-    asm volatile("s_nop 4\n\tglobal_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
-}
-__device__ __forceinline__ void wait_dev_stores() { asm volatile("s_waitcnt vmcnt(0)" : : : "memory"); }
 
 // XCD this workgroup runs on (hardware register XCC_ID).
 __device__ __forceinline__ uint32_t xcc_id() { return __builtin_amdgcn_s_getreg((31 << 11) | 20) & 0xfu; }

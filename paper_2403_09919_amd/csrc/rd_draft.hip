@@ -18,9 +18,8 @@
 // Precision contract: weights, embeddings and h are bf16; every linear layer reads its input
 // rounded to bf16 and accumulates in fp32; bias, activation, skip connection, log-softmax and
 // scores are fp32.
-#include "rd_attn_common.h"           // device-scope stores/loads for results that cross workgroups
+#include "rd_internal.h"
 #include <math.h>
-#include <stdlib.h>
 
 namespace {
 

@@ -1,7 +1,10 @@
-// Shared host-side helpers of the rd library (argument checks, launch checks).
+// Shared helpers of the rd library: argument and launch checks, tuning overrides, and the
+// device-scope accesses with which workgroups hand partial results to one another.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
+#include <atomic>
 #include "rd.h"
 
 #define RD_WAVE 64
@@ -31,6 +34,70 @@ static inline int rd_check_beam_shape(int B, int W, int L)
     if ((long long)W * (long long)L > RD_MAX_N) return RD_ERR_UNSUPPORTED;
     return RD_OK;
 }
+
+namespace rd {
+
+// Integer environment override for tuning sweeps (unset or empty: the default).
+static inline int env_int(const char *name, int dflt)
+{
+    const char *v = getenv(name);
+    return (v && *v) ? atoi(v) : dflt;
+}
+
+// Raising a kernel's dynamic LDS limit is per kernel and per device; `done` (one per kernel) keeps
+// a bit for each device already set up.  Returns RD_OK or RD_ERR_HIP.
+static inline int ensure_dynamic_lds(const void *kernel, size_t bytes, std::atomic<unsigned long long> &done)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return RD_ERR_HIP;
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (dev < 64 && (done.load(std::memory_order_acquire) & bit)) return RD_OK;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess)
+        return RD_ERR_HIP;
+    if (dev < 64) done.fetch_or(bit, std::memory_order_release);
+    return RD_OK;
+}
+
+// ---- exchange of partial results between workgroups -------------------------------------------
+// Partial results (attention states, K-split sums of the drafter's layers) are written by one
+// workgroup and read by another that may sit on a different XCD (each XCD has its own L2).  A
+// device-wide release/acquire fence would write back and invalidate whole L2s on every
+// workgroup, which costs far more than the kernel itself, so the
+// exchange uses device-scope (write-through / cache-bypassing) relaxed atomic accesses for the
+// data itself, made complete with a wait for outstanding memory operations before the counter
+// is bumped.  Only these few KB per workgroup travel that way; the bulk streams use plain loads.
+__device__ __forceinline__ void st_dev(float *p, float v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_dev2(float *p, float a, float b)
+{
+    unsigned long long u = (unsigned long long)__float_as_uint(a) | ((unsigned long long)__float_as_uint(b) << 32);
+    __hip_atomic_store(reinterpret_cast<unsigned long long *>(p), u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_dev(const float *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float2 ld_dev2(const float *p)
+{
+    const unsigned long long u =
+        __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return make_float2(__uint_as_float((unsigned)u), __uint_as_float((unsigned)(u >> 32)));
+}
+
+// 16-byte device-scope store (write-through); the caller must call wait_dev_stores() before it
+// signals completion, because the compiler does not count this store as outstanding.
+__device__ __forceinline__ void st_dev4(float *p, float a, float b, float c, float d)
+{
+    typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+    const f32x4_t v = {a, b, c, d};
+    // the leading s_nop covers register-write hazards the compiler cannot see into the asm for
+    asm volatile("s_nop 4\n\tglobal_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void wait_dev_stores() { asm volatile("s_waitcnt vmcnt(0)" : : : "memory"); }
+
+}  // namespace rd
 
 // Optional phase timestamps for tuning builds (-DRD_TRACE): thread 0 of every workgroup stores
 // the constant-rate wall clock at a few points into a caller-supplied buffer (one per source file).
