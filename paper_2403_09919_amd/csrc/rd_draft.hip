@@ -7,11 +7,14 @@
 //     go from memory straight into the A operand of v_mfma_f32_16x16x32_bf16 (lane = one output
 //     column x 8 consecutive k), the activations (a few hundred KB, L2 resident) into the B
 //     operand, and the partial sums meet in LDS.  Bias, SiLU, skip connection and the bf16
-//     copy that the next layer reads are fused into the epilogue;
+//     copy that the next layer reads are fused into the epilogue.  At more than 32 rows the
+//     layers with few columns use 128- or 64-column workgroups and split K over 2 to 8
+//     workgroups per column group as well; the last of them to finish adds the partial tiles;
 //   * three selection launches, all merges of sorted lists: per chunk of 4096 logits and row, the
 //     pieces of the log-sum-exp and the W best tokens; per row, its log-sum-exp and the W best
 //     tokens of its chunks as cumulative scores; per sequence, the best W of the (candidate, token)
-//     pairs by cumulative log probability, ties to the smaller candidate, then the smaller token.
+//     pairs by cumulative log probability, ties to the smaller candidate, then the smaller token
+//     (W <= 128; beyond 64 candidates a lane of the last merge holds two lists).
 // The RNN update reads its two inputs in place: the parent's state through a row map and the
 // chosen token's embedding straight from the table, so no gather pass exists.
 //
