@@ -365,3 +365,45 @@ def test_many_random_small_models(rd):
         for b in range(B):
             assert len({tuple(x) for x in gb[b].tolist()}) == W, (case, b)
             assert (tf[b] >= ref["beam_logp"][b].astype(np.float64) - TOL).all(), (case, b)
+
+
+def test_split_layers_repeat_and_graph_replay(rd):
+    """The layers that split K over workgroups keep arrival counters in the workspace: back-to-back calls
+    on one workspace, and replays of a captured call with eager work in between, must all give the bits
+    of the first call (which test_draft_matches_oracle checks against the oracle for this shape)."""
+    announce("draft split layers: repeated calls and graph replays, Dm=512 B=5 W=8 L=4")
+    Dm, V, K, B, W, L = 512, 1200, 2, 5, 8, 4
+    p = make_params(V, Dm, K, seed=Dm + V + 9, scale=4.0)
+    h = make_h(B, Dm, V + 9, "bf16")
+    last = np.random.default_rng(V + 9).integers(0, V, B).astype(np.int32)
+    pd = rd.rd_draft_pack(dev_params(p))
+    hd, ld = dev(h), dev(last)
+    ws = torch.zeros(rd.rd_draft_workspace(B, W, L, Dm, V), dtype=torch.uint8, device="cuda")
+    out = rd.rd_draft(pd, hd, ld, W, L, workspace=ws, steps=True)
+    torch.cuda.synchronize()
+    first = {k: host(v).copy() for k, v in out.items()}
+    ref = oracle.draft(p, h, last, W, L)
+    tf = oracle.draft_path_logp(p, h, first["beams"])
+    assert np.abs(tf - first["beam_logp"]).max() <= TOL
+    assert (tf >= ref["beam_logp"].astype(np.float64) - TOL).all()
+
+    def same(tag):
+        torch.cuda.synchronize()
+        for k in ("beams", "beam_logp", "step_row"):
+            assert np.array_equal(host(out[k]), first[k]), (tag, k)
+        assert np.array_equal(host(out["step_logits"])[1:], first["step_logits"][1:]), tag
+
+    for rep in range(3):                                         # eager, same workspace
+        rd.rd_draft(pd, hd, ld, W, L, out=out, workspace=ws, steps=True)
+        same(("eager", rep))
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        with torch.cuda.graph(graph, stream=stream):
+            rd.rd_draft(pd, hd, ld, W, L, out=out, workspace=ws, steps=True)
+    for rep in range(3):
+        for v in out.values():
+            v.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        same(("replay", rep))
