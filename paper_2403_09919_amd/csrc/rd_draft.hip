@@ -266,6 +266,96 @@ __global__ __launch_bounds__(NWV * 64) void rd_linear_kernel(LinArgs<T> a)
     }
 }
 
+// The output layer at many rows (65 and more per launch): with K split over the waves, the accumulators of
+// 128 rows leave a workgroup room for only 64 columns, and every workgroup then pulls two activation bytes
+// through the caches per weight byte.  Here the waves split the columns instead: wave w owns 16 columns for
+// all rows (8 accumulator tiles), so a workgroup of 8 waves covers 128 columns with a quarter of the
+// registers, all waves walk K together in chunks of 256, and the activations of a chunk are staged once per
+// workgroup in LDS (row stride 528 bytes: the 16 rows a B-operand read touches fall in distinct banks),
+// double-buffered, one barrier per chunk.  Weights still go from memory straight into the A operand, one
+// chunk (8 k-steps) ahead.  Sums run over k in order in a single accumulator per output, for either weight
+// layout.
+constexpr int kRowsKC = 256;                       // k per chunk
+constexpr int kRowsStride = kRowsKC * 2 + 16;      // bytes per staged activation row
+
+template <typename T, int MT, bool TILED>
+__global__ __launch_bounds__(512) void rd_head_rows_kernel(LinArgs<T> a)
+{
+    typedef typename Elem16<T>::vec8 vec8;
+    constexpr int kSteps = kRowsKC / 32;                               // k-steps per chunk
+    constexpr int kBuf = MT * 16 * kRowsStride;                        // bytes per buffer
+    constexpr int kPieces = MT * 16 * (kRowsKC * 2 / 16) / 512;        // 16-byte pieces per thread and chunk
+    extern __shared__ __align__(16) unsigned char s_x[];               // two buffers
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r16 = lane & 15, g = lane >> 4;
+    const int n_tile = ((int)blockIdx.x * 8 + wave) * 16;              // this wave's 16 columns
+    const int nchunks = a.K1 / kRowsKC;
+
+    const T *wp;                                                       // this lane's first weight vector
+    if (TILED) {
+        const int ntile = min(n_tile / 16, (a.N + 15) / 16 - 1);       // tiles past N read the last one; never stored
+        wp = a.w1 + (size_t)ntile * (a.K1 >> 5) * 512 + lane * 8;
+    } else {
+        wp = a.w1 + (size_t)min(n_tile + r16, a.N - 1) * a.K1 + 8 * g;
+    }
+    constexpr int wstep = TILED ? 512 : 32;
+    const T *xsrc[kPieces];
+    int xdst[kPieces];
+#pragma unroll
+    for (int i = 0; i < kPieces; ++i) {
+        const int p = tid + 512 * i, row = p >> 5, ch = p & 31;
+        const size_t prow = (size_t)(a.m0 + min(row, a.M - 1)) * a.mstride;
+        xsrc[i] = a.x1 + prow * a.ldx1 + ch * 8;
+        xdst[i] = row * kRowsStride + ch * 16;
+    }
+    f32x4 acc[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // (staged values are kept as native vectors: arrays of those stay in registers)
+    vec8 wa0[kSteps], wa1[kSteps];
+    {   // chunk 0: activations -> buffer 0, weights -> wa0
+        vec8 x0[kPieces];
+#pragma unroll
+        for (int i = 0; i < kPieces; ++i) x0[i] = *reinterpret_cast<const vec8 *>(xsrc[i]);
+#pragma unroll
+        for (int s = 0; s < kSteps; ++s) wa0[s] = *reinterpret_cast<const vec8 *>(wp + s * wstep);
+#pragma unroll
+        for (int i = 0; i < kPieces; ++i) *reinterpret_cast<vec8 *>(s_x + xdst[i]) = x0[i];
+    }
+
+    const int b_off = r16 * kRowsStride + g * 16;                      // B operand: row r16 of a tile, k group g
+    auto chunk = [&](int c, vec8 (&cur)[kSteps], vec8 (&nxt)[kSteps]) __attribute__((always_inline)) {
+        // the next chunk's activations and weights (after the last chunk: the last chunk again, ignored)
+        const int cn = min(c + 1, nchunks - 1);
+        vec8 xs[kPieces];
+#pragma unroll
+        for (int i = 0; i < kPieces; ++i) xs[i] = *reinterpret_cast<const vec8 *>(xsrc[i] + cn * kRowsKC);
+#pragma unroll
+        for (int s = 0; s < kSteps; ++s) nxt[s] = *reinterpret_cast<const vec8 *>(wp + (cn * kSteps + s) * wstep);
+        rd_lds_barrier();                                              // buffer c&1 is complete, buffer (c+1)&1 is free
+        const unsigned char *buf = s_x + (c & 1) * kBuf + b_off;
+#pragma unroll
+        for (int s = 0; s < kSteps; ++s) {
+            vec8 xb[MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) xb[mt] = *reinterpret_cast<const vec8 *>(buf + mt * 16 * kRowsStride + s * 64);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) acc[mt] = Elem16<T>::mfma(cur[s], xb[mt], acc[mt]);
+        }
+        unsigned char *dst = s_x + ((c + 1) & 1) * kBuf;
+#pragma unroll
+        for (int i = 0; i < kPieces; ++i) *reinterpret_cast<vec8 *>(dst + xdst[i]) = xs[i];
+    };
+    for (int c = 0; c < nchunks; c += 2) {
+        chunk(c, wa0, wa1);
+        if (c + 1 < nchunks) chunk(c + 1, wa1, wa0);
+    }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) linear_epilogue<T, EPI_HEAD>(a, acc[mt], mt * 16, n_tile, r16, g);
+}
+
 // rows m = b*W + w: X0 = [e(last token), h] (fp32 and bf16), state = e(last token), path = [last token]
 template <typename T>
 __global__ void rd_draft_init_kernel(const T *__restrict__ emb, const T *__restrict__ h,
@@ -812,6 +902,29 @@ bool launch_linear_split(const LinArgs<T> &a, hipStream_t stream, int *status)
     }
 }
 
+// The output layer at 65 rows and more per launch, wide enough to cover half the chip with 128-column
+// workgroups: waves split the columns, activations staged in LDS (rd_head_rows_kernel).
+template <typename T, int MT, int EPI>
+bool launch_head_rows(const LinArgs<T> &a, hipStream_t stream, int *status)
+{
+    if constexpr (MT == 8 && EPI == EPI_HEAD) {
+        static const int on = rd::env_int("RD_DRAFT_HEAD_ROWS", 1);    // 0: the K-split kernel (for comparisons)
+        if (!on || a.K2 != 0 || a.map1 != nullptr || a.K1 % kRowsKC != 0 || a.N < 128 * 128) return false;
+        constexpr size_t smem = 2 * (size_t)MT * 16 * kRowsStride;
+        static std::atomic<unsigned long long> conf_t{0}, conf_r{0};
+        const void *fn = a.tiled ? reinterpret_cast<const void *>(&rd_head_rows_kernel<T, MT, true>)
+                                 : reinterpret_cast<const void *>(&rd_head_rows_kernel<T, MT, false>);
+        if (rd::ensure_dynamic_lds(fn, smem, a.tiled ? conf_t : conf_r) != RD_OK) { *status = RD_ERR_HIP; return true; }
+        const dim3 grid((a.N + 127) / 128);
+        if (a.tiled) hipLaunchKernelGGL((rd_head_rows_kernel<T, MT, true>), grid, dim3(512), smem, stream, a);
+        else hipLaunchKernelGGL((rd_head_rows_kernel<T, MT, false>), grid, dim3(512), smem, stream, a);
+        *status = rd_check_launch();
+        return true;
+    } else {
+        return false;
+    }
+}
+
 // column tiles per workgroup: the most that still leave about one workgroup per compute unit (the
 // activation re-reads are MT : NT of the weight bytes, and measured they cost as much as the
 // weights' own stream; halving the workgroups below the number of compute units costs more)
@@ -820,6 +933,7 @@ int launch_linear_mt(const LinArgs<T> &a, hipStream_t stream)
 {
     int status = RD_OK;
     if (launch_linear_split<T, MT, EPI>(a, stream, &status)) return status;
+    if (launch_head_rows<T, MT, EPI>(a, stream, &status)) return status;
     if constexpr (MT == 2 || MT == 4) {
         if (a.N >= 240 * 128) return launch_linear_nt<T, MT, 8, EPI>(a, stream);
     }

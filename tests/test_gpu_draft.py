@@ -95,7 +95,12 @@ def check(rd, p, h, last, W, L, what):
                                           # sweep (70), the limit (128), several sequences, a vocabulary of more than 8 chunks
                                           (64, 3000, 1, 1, 70, 3), (64, 2000, 1, 1, 128, 3), (128, 1500, 1, 3, 70, 4),
                                           (64, 500, 0, 4, 128, 2), (64, 40000, 0, 1, 70, 3), (64, 129, 1, 2, 128, 3),
-                                          (256, 5000, 2, 1, 96, 5), (64, 4200, 1, 2, 65, 3)])
+                                          (256, 5000, 2, 1, 96, 5), (64, 4200, 1, 2, 65, 3),
+                                          # 65 rows and more with a wide output layer: waves split the columns and the
+                                          # activations pass through LDS in chunks of 256 (1, 2 and 3 chunks; a second
+                                          # launch for the rows past 128)
+                                          (128, 17000, 1, 9, 8, 3), (256, 16400, 1, 16, 8, 3), (384, 20000, 0, 10, 8, 3),
+                                          (128, 16500, 2, 20, 8, 3)])
 def test_draft_matches_oracle(rd, Dm, V, K, B, W, L):
     announce(f"draft Dm={Dm} V={V} K={K} B={B} W={W} L={L}")
     p = make_params(V, Dm, K, seed=Dm + V, scale=4.0)
@@ -315,7 +320,9 @@ def test_pack_weights_layout(rd, N, K):
                                                 (64, 17000, 1, 5, 8, 3, "bf16"), (64, 31000, 1, 3, 8, 3, "f16"),
                                                 (64, 700, 1, 20, 8, 4, "bf16"), (256, 1000, 0, 1, 64, 3, "f16"),
                                                 # K split over workgroups (more than 32 rows, hidden size a multiple of 256)
-                                                (512, 1200, 1, 5, 8, 3, "bf16"), (256, 900, 1, 9, 8, 3, "f16")])
+                                                (512, 1200, 1, 5, 8, 3, "bf16"), (256, 900, 1, 9, 8, 3, "f16"),
+                                                # the many-row output layer (columns split over the waves)
+                                                (256, 16400, 1, 10, 8, 3, "bf16"), (128, 17000, 1, 9, 8, 3, "f16")])
 def test_packed_weights_give_identical_results(rd, Dm, V, K, B, W, L, dtype):
     """The operand-tiled layout changes where the weights lie, not the arithmetic: beams, scores and the
     recorded logits must be bit-identical to the row-major run (which is checked against the oracle)."""
