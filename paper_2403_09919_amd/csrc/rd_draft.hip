@@ -268,13 +268,14 @@ __global__ __launch_bounds__(NWV * 64) void rd_linear_kernel(LinArgs<T> a)
 
 // The output layer at many rows (65 and more per launch): with K split over the waves, the accumulators of
 // 128 rows leave a workgroup room for only 64 columns, and every workgroup then pulls two activation bytes
-// through the caches per weight byte.  Here the waves split the columns instead: wave w owns 16 columns for
-// all rows (8 accumulator tiles), so a workgroup of 8 waves covers 128 columns with a quarter of the
-// registers, all waves walk K together in chunks of 256, and the activations of a chunk are staged once per
+// through the caches per weight byte.  Here the waves split the columns instead: a wave owns 32 columns for
+// all rows (16 accumulator tiles) and half of every chunk's k-steps, so a workgroup of 8 waves covers 128
+// columns with half of the registers (every B operand read from LDS feeds two matrix instructions), all
+// waves walk K together in chunks of 256, and the activations of a chunk are staged once per
 // workgroup in LDS (row stride 528 bytes: the 16 rows a B-operand read touches fall in distinct banks),
 // double-buffered, one barrier per chunk.  Weights still go from memory straight into the A operand, one
-// chunk (8 k-steps) ahead.  Sums run over k in order in a single accumulator per output, for either weight
-// layout.
+// chunk ahead.  An output is the sum of two accumulators, each over its k-steps in order, for either
+// weight layout.
 constexpr int kRowsKC = 256;                       // k per chunk
 constexpr int kRowsStride = kRowsKC * 2 + 16;      // bytes per staged activation row
 
@@ -283,23 +284,28 @@ __global__ __launch_bounds__(512) void rd_head_rows_kernel(LinArgs<T> a)
 {
     typedef typename Elem16<T>::vec8 vec8;
     constexpr int kSteps = kRowsKC / 32;                               // k-steps per chunk
+    constexpr int kMine = kSteps / 2;                                  // ... of which a wave takes half
     constexpr int kBuf = MT * 16 * kRowsStride;                        // bytes per buffer
     constexpr int kPieces = MT * 16 * (kRowsKC * 2 / 16) / 512;        // 16-byte pieces per thread and chunk
     extern __shared__ __align__(16) unsigned char s_x[];               // two buffers
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int cp = wave & 3, kh = wave >> 2;                           // column pair, half of every chunk's k-steps
     const int r16 = lane & 15, g = lane >> 4;
-    const int n_tile = ((int)blockIdx.x * 8 + wave) * 16;              // this wave's 16 columns
+    const int n_tile = ((int)blockIdx.x * 8 + cp * 2) * 16;            // this wave's 32 columns: tiles n_tile, n_tile + 16
     const int nchunks = a.K1 / kRowsKC;
 
-    const T *wp;                                                       // this lane's first weight vector
-    if (TILED) {
-        const int ntile = min(n_tile / 16, (a.N + 15) / 16 - 1);       // tiles past N read the last one; never stored
-        wp = a.w1 + (size_t)ntile * (a.K1 >> 5) * 512 + lane * 8;
-    } else {
-        wp = a.w1 + (size_t)min(n_tile + r16, a.N - 1) * a.K1 + 8 * g;
-    }
+    const T *wp[2];                                                    // this lane's first weight vector of either tile
     constexpr int wstep = TILED ? 512 : 32;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        if (TILED) {
+            const int ntile = min(n_tile / 16 + t, (a.N + 15) / 16 - 1);   // tiles past N read the last one; never stored
+            wp[t] = a.w1 + (size_t)ntile * (a.K1 >> 5) * 512 + lane * 8 + kh * kMine * wstep;
+        } else {
+            wp[t] = a.w1 + (size_t)min(n_tile + t * 16 + r16, a.N - 1) * a.K1 + 8 * g + kh * kMine * wstep;
+        }
+    }
     const T *xsrc[kPieces];
     int xdst[kPieces];
 #pragma unroll
@@ -309,40 +315,47 @@ __global__ __launch_bounds__(512) void rd_head_rows_kernel(LinArgs<T> a)
         xsrc[i] = a.x1 + prow * a.ldx1 + ch * 8;
         xdst[i] = row * kRowsStride + ch * 16;
     }
-    f32x4 acc[MT];
+    f32x4 acc[MT][2];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int mt = 0; mt < MT; ++mt) acc[mt][0] = acc[mt][1] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     // (staged values are kept as native vectors: arrays of those stay in registers)
-    vec8 wa0[kSteps], wa1[kSteps];
+    vec8 wa0[2][kMine], wa1[2][kMine];
     {   // chunk 0: activations -> buffer 0, weights -> wa0
         vec8 x0[kPieces];
 #pragma unroll
         for (int i = 0; i < kPieces; ++i) x0[i] = *reinterpret_cast<const vec8 *>(xsrc[i]);
 #pragma unroll
-        for (int s = 0; s < kSteps; ++s) wa0[s] = *reinterpret_cast<const vec8 *>(wp + s * wstep);
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int s = 0; s < kMine; ++s) wa0[t][s] = *reinterpret_cast<const vec8 *>(wp[t] + s * wstep);
 #pragma unroll
         for (int i = 0; i < kPieces; ++i) *reinterpret_cast<vec8 *>(s_x + xdst[i]) = x0[i];
     }
 
-    const int b_off = r16 * kRowsStride + g * 16;                      // B operand: row r16 of a tile, k group g
-    auto chunk = [&](int c, vec8 (&cur)[kSteps], vec8 (&nxt)[kSteps]) __attribute__((always_inline)) {
+    const int b_off = r16 * kRowsStride + g * 16 + kh * kMine * 64;    // B operand: row r16 of a tile, k group g, own k-steps
+    auto chunk = [&](int c, vec8 (&cur)[2][kMine], vec8 (&nxt)[2][kMine]) __attribute__((always_inline)) {
         // the next chunk's activations and weights (after the last chunk: the last chunk again, ignored)
         const int cn = min(c + 1, nchunks - 1);
         vec8 xs[kPieces];
 #pragma unroll
         for (int i = 0; i < kPieces; ++i) xs[i] = *reinterpret_cast<const vec8 *>(xsrc[i] + cn * kRowsKC);
 #pragma unroll
-        for (int s = 0; s < kSteps; ++s) nxt[s] = *reinterpret_cast<const vec8 *>(wp + (cn * kSteps + s) * wstep);
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int s = 0; s < kMine; ++s) nxt[t][s] = *reinterpret_cast<const vec8 *>(wp[t] + (cn * kSteps + s) * wstep);
         rd_lds_barrier();                                              // buffer c&1 is complete, buffer (c+1)&1 is free
         const unsigned char *buf = s_x + (c & 1) * kBuf + b_off;
 #pragma unroll
-        for (int s = 0; s < kSteps; ++s) {
+        for (int s = 0; s < kMine; ++s) {
             vec8 xb[MT];
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) xb[mt] = *reinterpret_cast<const vec8 *>(buf + mt * 16 * kRowsStride + s * 64);
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) acc[mt] = Elem16<T>::mfma(cur[s], xb[mt], acc[mt]);
+            for (int mt = 0; mt < MT; ++mt) {
+                acc[mt][0] = Elem16<T>::mfma(cur[0][s], xb[mt], acc[mt][0]);
+                acc[mt][1] = Elem16<T>::mfma(cur[1][s], xb[mt], acc[mt][1]);
+            }
         }
         unsigned char *dst = s_x + ((c + 1) & 1) * kBuf;
 #pragma unroll
@@ -352,8 +365,23 @@ __global__ __launch_bounds__(512) void rd_head_rows_kernel(LinArgs<T> a)
         chunk(c, wa0, wa1);
         if (c + 1 < nchunks) chunk(c + 1, wa1, wa0);
     }
+    // the two halves of k meet in LDS (the staging buffers are free after one more barrier)
+    rd_lds_barrier();
+    f32x4 *s_acc = reinterpret_cast<f32x4 *>(s_x) + (size_t)cp * MT * 2 * 64 + lane;
+    if (kh == 1) {
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) linear_epilogue<T, EPI_HEAD>(a, acc[mt], mt * 16, n_tile, r16, g);
+        for (int mt = 0; mt < MT; ++mt) {
+            s_acc[(mt * 2 + 0) * 64] = acc[mt][0];
+            s_acc[(mt * 2 + 1) * 64] = acc[mt][1];
+        }
+    }
+    rd_lds_barrier();
+    if (kh == 1) return;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        linear_epilogue<T, EPI_HEAD>(a, acc[mt][0] + s_acc[(mt * 2 + 0) * 64], mt * 16, n_tile, r16, g);
+        linear_epilogue<T, EPI_HEAD>(a, acc[mt][1] + s_acc[(mt * 2 + 1) * 64], mt * 16, n_tile + 16, r16, g);
+    }
 }
 
 // rows m = b*W + w: X0 = [e(last token), h] (fp32 and bf16), state = e(last token), path = [last token]
