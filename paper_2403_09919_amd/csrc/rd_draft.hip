@@ -935,7 +935,7 @@ bool launch_linear_split(const LinArgs<T> &a, hipStream_t stream, int *status)
 template <typename T, int MT, int EPI>
 bool launch_head_rows(const LinArgs<T> &a, hipStream_t stream, int *status)
 {
-    if constexpr (MT >= 4 && EPI == EPI_HEAD) {
+    if constexpr (MT >= 2 && EPI == EPI_HEAD) {
         static const int on = rd::env_int("RD_DRAFT_HEAD_ROWS", 1);    // 0: the K-split kernel (for comparisons)
         if (!on || a.K2 != 0 || a.map1 != nullptr || a.K1 % kRowsKC != 0 || a.N < 128 * 128) return false;
         constexpr size_t smem = 2 * (size_t)MT * 16 * kRowsStride;
