@@ -266,9 +266,9 @@ __global__ __launch_bounds__(NWV * 64) void rd_linear_kernel(LinArgs<T> a)
     }
 }
 
-// The output layer at many rows (65 and more per launch): with K split over the waves, the accumulators of
-// 128 rows leave a workgroup room for only 64 columns, and every workgroup then pulls two activation bytes
-// through the caches per weight byte.  Here the waves split the columns instead: a wave owns 32 columns for
+// The output layer at more than a few rows: with K split over the waves, the accumulators of 128 rows leave
+// a workgroup room for only 64 columns, and every workgroup then pulls two activation bytes through the
+// caches per weight byte (one per weight byte already at 16 rows, with 16-column workgroups).  Here the waves split the columns instead: a wave owns 32 columns for
 // all rows (16 accumulator tiles) and half of every chunk's k-steps, so a workgroup of 8 waves covers 128
 // columns with half of the registers (every B operand read from LDS feeds two matrix instructions), all
 // waves walk K together in chunks of 256, and the activations of a chunk are staged once per
@@ -930,14 +930,17 @@ bool launch_linear_split(const LinArgs<T> &a, hipStream_t stream, int *status)
     }
 }
 
-// The output layer at 65 rows and more per launch, wide enough to cover half the chip with 128-column
-// workgroups: waves split the columns, activations staged in LDS (rd_head_rows_kernel).
+// The output layer at 9 rows and more per launch, wide enough to cover half the chip with 128-column
+// workgroups: waves split the columns, activations staged in LDS (rd_head_rows_kernel).  Measured per call
+// at a hidden size of 4096 and 32000 tokens against the K-split kernels: 16 rows 832 -> 766 us, 32 rows
+// 919 -> 835, 64 rows 1007 -> 965, 128 rows 1400 -> 1173; 8 rows 725 -> 730 (not used there).
 template <typename T, int MT, int EPI>
 bool launch_head_rows(const LinArgs<T> &a, hipStream_t stream, int *status)
 {
-    if constexpr (MT >= 2 && EPI == EPI_HEAD) {
+    if constexpr (MT >= 1 && EPI == EPI_HEAD) {
         static const int on = rd::env_int("RD_DRAFT_HEAD_ROWS", 1);    // 0: the K-split kernel (for comparisons)
         if (!on || a.K2 != 0 || a.map1 != nullptr || a.K1 % kRowsKC != 0 || a.N < 128 * 128) return false;
+        if (a.M <= 8) return false;                                    // up to 8 rows the K-split kernel is as fast or faster
         constexpr size_t smem = 2 * (size_t)MT * 16 * kRowsStride;
         static std::atomic<unsigned long long> conf_t{0}, conf_r{0};
         const void *fn = a.tiled ? reinterpret_cast<const void *>(&rd_head_rows_kernel<T, MT, true>)

@@ -100,7 +100,10 @@ def check(rd, p, h, last, W, L, what):
                                           # activations pass through LDS in chunks of 256 (1, 2 and 3 chunks; a second
                                           # launch for the rows past 128)
                                           (128, 17000, 1, 9, 8, 3), (256, 16400, 1, 16, 8, 3), (384, 20000, 0, 10, 8, 3),
-                                          (128, 16500, 2, 20, 8, 3)])
+                                          (128, 16500, 2, 20, 8, 3),
+                                          # the same kernel with 1, 2 and 4 row tiles (12, 16, 24 and 40 rows)
+                                          (128, 16400, 1, 3, 4, 3), (128, 17000, 1, 2, 8, 3), (256, 16500, 1, 3, 8, 3),
+                                          (128, 20000, 1, 5, 8, 3)])
 def test_draft_matches_oracle(rd, Dm, V, K, B, W, L):
     announce(f"draft Dm={Dm} V={V} K={K} B={B} W={W} L={L}")
     p = make_params(V, Dm, K, seed=Dm + V, scale=4.0)
@@ -322,7 +325,8 @@ def test_pack_weights_layout(rd, N, K):
                                                 # K split over workgroups (more than 32 rows, hidden size a multiple of 256)
                                                 (512, 1200, 1, 5, 8, 3, "bf16"), (256, 900, 1, 9, 8, 3, "f16"),
                                                 # the many-row output layer (columns split over the waves)
-                                                (256, 16400, 1, 10, 8, 3, "bf16"), (128, 17000, 1, 9, 8, 3, "f16")])
+                                                (256, 16400, 1, 10, 8, 3, "bf16"), (128, 17000, 1, 9, 8, 3, "f16"),
+                                                (128, 17000, 1, 2, 8, 3, "bf16"), (256, 16500, 1, 3, 8, 3, "f16")])
 def test_packed_weights_give_identical_results(rd, Dm, V, K, B, W, L, dtype):
     """The operand-tiled layout changes where the weights lie, not the arithmetic: beams, scores and the
     recorded logits must be bit-identical to the row-major run (which is checked against the oracle)."""
