@@ -49,7 +49,7 @@ constexpr int kSelThreads = 256;       // row pass and beam step: four waves bri
 constexpr int kMaxVocab = 262144;      // 64 chunks of 4096 logits: one lane per chunk in the row pass
 constexpr int kSplitMaxWgs = 256;      // workgroups of a launch whose K is split over workgroups
 constexpr int kSplitMaxGroups = 128;   // ... and its column groups (one arrival counter each)
-constexpr int kSplitTiles = 32;        // ... and the 16x16 output tiles a workgroup holds
+constexpr int kSplitTiles = 64;        // ... and the 16x16 output tiles a workgroup holds
 
 enum { EPI_HEAD = 0, EPI_RNN = 1, EPI_MLP = 2 };
 
@@ -279,7 +279,9 @@ __global__ __launch_bounds__(NWV * 64) void rd_linear_kernel(LinArgs<T> a)
 constexpr int kRowsKC = 256;                       // k per chunk
 constexpr int kRowsStride = kRowsKC * 2 + 16;      // bytes per staged activation row
 
-template <typename T, int MT, bool TILED>
+// KSP (layers with few columns): K is also split over a.ksplit workgroups per column group, exchanged as in
+// rd_linear_kernel (partial tiles stored write-through, last arriver sums in split order).
+template <typename T, int MT, bool TILED, int EPI = EPI_HEAD, bool KSP = false>
 __global__ __launch_bounds__(512) void rd_head_rows_kernel(LinArgs<T> a)
 {
     typedef typename Elem16<T>::vec8 vec8;
@@ -292,8 +294,14 @@ __global__ __launch_bounds__(512) void rd_head_rows_kernel(LinArgs<T> a)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int cp = wave & 3, kh = wave >> 2;                           // column pair, half of every chunk's k-steps
     const int r16 = lane & 15, g = lane >> 4;
-    const int n_tile = ((int)blockIdx.x * 8 + cp * 2) * 16;            // this wave's 32 columns: tiles n_tile, n_tile + 16
-    const int nchunks = a.K1 / kRowsKC;
+    const int groups = KSP ? (int)gridDim.x / a.ksplit : (int)gridDim.x;
+    const int group = KSP ? (int)blockIdx.x % groups : (int)blockIdx.x;
+    const int split = KSP ? (int)blockIdx.x / groups : 0;
+    const int n_tile = (group * 8 + cp * 2) * 16;                      // this wave's 32 columns: tiles n_tile, n_tile + 16
+    // this workgroup's chunks of K: [c_first, c_first + nchunks)
+    const int all_chunks = a.K1 / kRowsKC;
+    const int c_first = KSP ? all_chunks * split / a.ksplit : 0;
+    const int nchunks = KSP ? all_chunks * (split + 1) / a.ksplit - c_first : all_chunks;
 
     const T *wp[2];                                                    // this lane's first weight vector of either tile
     constexpr int wstep = TILED ? 512 : 32;
@@ -301,9 +309,9 @@ __global__ __launch_bounds__(512) void rd_head_rows_kernel(LinArgs<T> a)
     for (int t = 0; t < 2; ++t) {
         if (TILED) {
             const int ntile = min(n_tile / 16 + t, (a.N + 15) / 16 - 1);   // tiles past N read the last one; never stored
-            wp[t] = a.w1 + (size_t)ntile * (a.K1 >> 5) * 512 + lane * 8 + kh * kMine * wstep;
+            wp[t] = a.w1 + (size_t)ntile * (a.K1 >> 5) * 512 + lane * 8 + (c_first * kSteps + kh * kMine) * wstep;
         } else {
-            wp[t] = a.w1 + (size_t)min(n_tile + t * 16 + r16, a.N - 1) * a.K1 + 8 * g + kh * kMine * wstep;
+            wp[t] = a.w1 + (size_t)min(n_tile + t * 16 + r16, a.N - 1) * a.K1 + 8 * g + (c_first * kSteps + kh * kMine) * wstep;
         }
     }
     const T *xsrc[kPieces];
@@ -312,7 +320,7 @@ __global__ __launch_bounds__(512) void rd_head_rows_kernel(LinArgs<T> a)
     for (int i = 0; i < kPieces; ++i) {
         const int p = tid + 512 * i, row = p >> 5, ch = p & 31;
         const size_t prow = (size_t)(a.m0 + min(row, a.M - 1)) * a.mstride;
-        xsrc[i] = a.x1 + prow * a.ldx1 + ch * 8;
+        xsrc[i] = a.x1 + prow * a.ldx1 + ch * 8 + c_first * kRowsKC;
         xdst[i] = row * kRowsStride + ch * 16;
     }
     f32x4 acc[MT][2];
@@ -376,11 +384,42 @@ __global__ __launch_bounds__(512) void rd_head_rows_kernel(LinArgs<T> a)
         }
     }
     rd_lds_barrier();
-    if (kh == 1) return;
+    if constexpr (!KSP) {
+        if (kh == 1) return;
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        linear_epilogue<T, EPI_HEAD>(a, acc[mt][0] + s_acc[(mt * 2 + 0) * 64], mt * 16, n_tile, r16, g);
-        linear_epilogue<T, EPI_HEAD>(a, acc[mt][1] + s_acc[(mt * 2 + 1) * 64], mt * 16, n_tile + 16, r16, g);
+        for (int mt = 0; mt < MT; ++mt) {
+            linear_epilogue<T, EPI>(a, acc[mt][0] + s_acc[(mt * 2 + 0) * 64], mt * 16, n_tile, r16, g);
+            linear_epilogue<T, EPI>(a, acc[mt][1] + s_acc[(mt * 2 + 1) * 64], mt * 16, n_tile + 16, r16, g);
+        }
+    } else {
+        // this workgroup's tiles, numbered as an MT x 8 grid (row tile, column tile), -> workspace
+        constexpr int kTiles = MT * 8;
+        if (kh == 0) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const f32x4 v = acc[mt][t] + s_acc[(mt * 2 + t) * 64];
+                    const int id = mt * 8 + cp * 2 + t;
+                    rd::st_dev4(a.kpart + ((((size_t)group * a.ksplit + split) * kTiles + id) * 64 + lane) * 4, v[0], v[1], v[2], v[3]);
+                }
+        }
+        __shared__ uint32_t s_last;
+        rd::wait_dev_stores();
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");      // this workgroup's partial tiles are acknowledged
+        __syncthreads();
+        if (tid == 0) {
+            const uint32_t prev = __hip_atomic_fetch_add(a.kcount + group, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_last = (prev + 1u == (uint32_t)a.ksplit) ? 1u : 0u;
+            if (s_last) a.kcount[group] = 0;                        // ready for the next launch
+        }
+        __syncthreads();
+        if (!s_last) return;
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        const int n0 = group * 128;
+        if (a.ksplit == 8) linear_finish_split<T, MT, 8, 8, EPI, 8>(a, group, n0, wave, lane);
+        else if (a.ksplit == 4) linear_finish_split<T, MT, 8, 8, EPI, 4>(a, group, n0, wave, lane);
+        else linear_finish_split<T, MT, 8, 8, EPI, 2>(a, group, n0, wave, lane);
     }
 }
 
@@ -907,6 +946,27 @@ bool launch_linear_split(const LinArgs<T> &a, hipStream_t stream, int *status)
         static const int ks_env = rd::env_int("RD_DRAFT_KSPLIT", 0);       // 1: never split; 2, 4, 8: only that split
         constexpr int max_wgs = kSplitMaxWgs;                   // one workgroup of 8 waves per compute unit at this register count
         if (a.kpart == nullptr || ks_env == 1) return false;
+        if constexpr (EPI == EPI_MLP) {                         // column-split waves, activations through LDS
+            static const int rows_on = rd::env_int("RD_DRAFT_MLP_ROWS", 1);
+            const int g128 = (a.N + 127) / 128, chunks = a.K1 / kRowsKC;
+            int sp = 0;
+            for (int c = 8; c >= 2 && sp == 0; c >>= 1)
+                if ((ks_env == 0 || ks_env == c) && g128 * c <= kSplitMaxWgs && chunks >= c) sp = c;
+            if (rows_on && a.K2 == 0 && a.map1 == nullptr && a.K1 % kRowsKC == 0 && g128 <= kSplitMaxGroups && sp) {
+                constexpr size_t smem = 2 * (size_t)MT * 16 * kRowsStride;
+                static std::atomic<unsigned long long> conf_t{0}, conf_r{0};
+                const void *fn = a.tiled ? reinterpret_cast<const void *>(&rd_head_rows_kernel<T, MT, true, EPI_MLP, true>)
+                                         : reinterpret_cast<const void *>(&rd_head_rows_kernel<T, MT, false, EPI_MLP, true>);
+                if (rd::ensure_dynamic_lds(fn, smem, a.tiled ? conf_t : conf_r) != RD_OK) { *status = RD_ERR_HIP; return true; }
+                LinArgs<T> b = a;
+                b.ksplit = sp;
+                const dim3 grid(g128 * sp);
+                if (a.tiled) hipLaunchKernelGGL((rd_head_rows_kernel<T, MT, true, EPI_MLP, true>), grid, dim3(512), smem, stream, b);
+                else hipLaunchKernelGGL((rd_head_rows_kernel<T, MT, false, EPI_MLP, true>), grid, dim3(512), smem, stream, b);
+                *status = rd_check_launch();
+                return true;
+            }
+        }
         const int groups = (a.N + 16 * NT - 1) / (16 * NT);
         if (groups > kSplitMaxGroups) return false;
         const int ks1 = a.K1 / 32, ks = ks1 + a.K2 / 32;
