@@ -506,7 +506,7 @@ __device__ __forceinline__ void order_pair(float &va, int &ka, float &vb, int &k
 // sum of exp(x - maximum) and their W best (value, then smaller token).  A lane owns 16 consecutive
 // tokens and sorts them in registers (odd-even merge sort network); the sorted lists go to LDS.  Each
 // wave merges its 64 lists into its W best, wave 0 then merges the four waves' lists.
-__global__ __launch_bounds__(kChunkThreads) void rd_topw_chunk_kernel(const float *__restrict__ logits, int V, int W, int chunks, int mstride,
+__global__ __launch_bounds__(kChunkThreads) void rd_topw_chunk_kernel(const float *__restrict__ logits, int V, int W, int chunks, int mstride, int lpc,
                                                                       float *__restrict__ part_max, float *__restrict__ part_sum,
                                                                       float *__restrict__ part_cv, int32_t *__restrict__ part_ci)
 {
@@ -597,8 +597,21 @@ __global__ __launch_bounds__(kChunkThreads) void rd_topw_chunk_kernel(const floa
         }
     }
     __syncthreads();
-    if (wave != 0) return;
     const size_t slot = (size_t)m * chunks + c;
+    if (lpc == kChunkThreads / 64) {
+        // wide beams: the four waves' lists leave as they are (the row pass merges four times as many
+        // lists in the same number of rounds, and the W rounds of the merge below are saved)
+        if (tid == 0) {
+            part_max[slot] = mx;
+            part_sum[slot] = s_v[0] + s_v[1] + s_v[2] + s_v[3];
+        }
+        for (int r = lane; r < W; r += 64) {
+            part_cv[(slot * lpc + wave) * W + r] = s_cv[wave][r];
+            part_ci[(slot * lpc + wave) * W + r] = s_ci[wave][r];
+        }
+        return;
+    }
+    if (wave != 0) return;
     if (lane == 0) {
         part_max[slot] = mx;
         part_sum[slot] = s_v[0] + s_v[1] + s_v[2] + s_v[3];
@@ -636,7 +649,7 @@ __global__ __launch_bounds__(kChunkThreads) void rd_topw_chunk_kernel(const floa
 template <int LPR, int WMAX>
 __global__ __launch_bounds__(kSelThreads) void rd_topw_row_kernel(
     const float *__restrict__ part_max, const float *__restrict__ part_sum, const float *__restrict__ part_cv,
-    const int32_t *__restrict__ part_ci, int chunks, const float *__restrict__ cum_cur, int W, int n_rows, int mstride,
+    const int32_t *__restrict__ part_ci, int chunks, int lpc, const float *__restrict__ cum_cur, int W, int n_rows, int mstride,
     float *__restrict__ row_score, int32_t *__restrict__ row_tok)
 {
     constexpr int kRows = 64 / LPR;                                   // rows per wave
@@ -646,7 +659,8 @@ __global__ __launch_bounds__(kSelThreads) void rd_topw_row_kernel(
     const int row_l = blockIdx.x * kRows + g;                         // logical row of this lane's group
     const bool row_ok = row_l < n_rows;
     const size_t row = (size_t)(row_ok ? row_l : n_rows - 1) * mstride;
-    const int n_surv = chunks * W;
+    const int n_lists = chunks * lpc;                                 // sorted lists per row (lpc per chunk), lane c holds list c
+    const int n_surv = n_lists * W;
     auto group_max = [](float x) { return LPR == 8 ? group8_max(x) : wave_max(x); };
     // log-sum-exp of the row: sum_c part_sum[c] * exp(part_max[c] - max) (loads issued before the staging below)
     const bool lane_ok = row_ok && c < chunks;
@@ -693,7 +707,7 @@ __global__ __launch_bounds__(kSelThreads) void rd_topw_row_kernel(
     int ptr = 0;
     int ht = li[0], nt = li[W > 1 ? 1 : 0];                           // head and the entry behind it, in registers
     float hv = lv[0], nv = lv[W > 1 ? 1 : 0];
-    bool live = lane_ok && ht != 0x7fffffff;
+    bool live = row_ok && c < n_lists && ht != 0x7fffffff;
     for (int r = 0; r < W; ++r) {
         const float best = group_max(live ? hv : -INFINITY);
         const unsigned long long offers = __ballot(live && hv == best);
@@ -879,8 +893,9 @@ Plan draft_plan(int B, int W, int L, int Dm, int V)
     const size_t chunks = ((size_t)V + kChunk - 1) / kChunk;
     p.part_max = take(M * chunks * 4);
     p.part_sum = take(M * chunks * 4);
-    p.part_cv = take(M * chunks * W * 4);
-    p.part_ci = take(M * chunks * W * 4);
+    const size_t lists = chunks * 4 <= 64 ? chunks * 4 : chunks;   // wide beams keep four lists per chunk
+    p.part_cv = take(M * lists * W * 4);
+    p.part_ci = take(M * lists * W * 4);
     p.row_score = take(M * W * 4);
     p.row_tok = take(M * W * 4);
     for (int i = 0; i < 2; ++i) { p.paths[i] = take(M * L * 4); p.cum[i] = take(M * 4); }
@@ -1125,7 +1140,10 @@ int draft_run(const rd_draft_params *p, const void *h, const int32_t *last_token
             a.M = rows; a.N = V; a.mstride = mstride; a.tiled = p->tiled; a.y_f32 = logits; a.ldy = V;
             if (launch_linear<E, EPI_HEAD>(a, s) != RD_OK) return RD_ERR_HIP;
         }
-        hipLaunchKernelGGL(rd_topw_chunk_kernel, dim3(chunks, rows), dim3(kChunkThreads), 0, s, logits, V, W, chunks, mstride,
+        // from 32 candidates on (and while four lists per chunk fit the row pass's 64 lanes) the chunk pass
+        // leaves its four waves' lists unmerged
+        const int lpc = (W >= 32 && chunks * 4 <= 64) ? 4 : 1;
+        hipLaunchKernelGGL(rd_topw_chunk_kernel, dim3(chunks, rows), dim3(kChunkThreads), 0, s, logits, V, W, chunks, mstride, lpc,
                            part_max, part_sum, part_cv, part_ci);
         if (rd_check_launch() != RD_OK) return RD_ERR_HIP;
         const bool last = t == T;
@@ -1133,8 +1151,8 @@ int draft_run(const rd_draft_params *p, const void *h, const int32_t *last_token
         const int live = t == 1 ? 1 : W;
 #define RD_ROW_LAUNCH(LPR, WMAX, grid)                                                                                   \
         hipLaunchKernelGGL((rd_topw_row_kernel<LPR, WMAX>), dim3(grid), dim3(kSelThreads), 0, s, part_max, part_sum, part_cv, part_ci, \
-                           chunks, cum[cur], W, rows, mstride, row_score, row_tok)
-        if (chunks <= 8) {
+                           chunks, lpc, cum[cur], W, rows, mstride, row_score, row_tok)
+        if (chunks * lpc <= 8) {
             if (wide) RD_ROW_LAUNCH(8, kMaxBeam, (rows + 7) / 8); else RD_ROW_LAUNCH(8, kNarrowBeam, (rows + 7) / 8);
         } else {
             if (wide) RD_ROW_LAUNCH(64, kMaxBeam, rows); else RD_ROW_LAUNCH(64, kNarrowBeam, rows);
