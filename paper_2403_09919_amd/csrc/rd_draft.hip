@@ -1140,9 +1140,9 @@ int draft_run(const rd_draft_params *p, const void *h, const int32_t *last_token
             a.M = rows; a.N = V; a.mstride = mstride; a.tiled = p->tiled; a.y_f32 = logits; a.ldy = V;
             if (launch_linear<E, EPI_HEAD>(a, s) != RD_OK) return RD_ERR_HIP;
         }
-        // from 32 candidates on (and while four lists per chunk fit the row pass's 64 lanes) the chunk pass
+        // from 16 candidates on (and while four lists per chunk fit the row pass's 64 lanes) the chunk pass
         // leaves its four waves' lists unmerged
-        const int lpc = (W >= 32 && chunks * 4 <= 64) ? 4 : 1;
+        const int lpc = (W >= 16 && chunks * 4 <= 64) ? 4 : 1;
         hipLaunchKernelGGL(rd_topw_chunk_kernel, dim3(chunks, rows), dim3(kChunkThreads), 0, s, logits, V, W, chunks, mstride, lpc,
                            part_max, part_sum, part_cv, part_ci);
         if (rd_check_launch() != RD_OK) return RD_ERR_HIP;
