@@ -335,8 +335,8 @@ int rd_commit_paged(const void *k_new, const void *v_new, const int32_t *accepte
  *   step_row int32 [B][W][L-1]: the row of matrix t-1 that produced token t of final candidate w.  workspace: rd_draft_workspace(...) bytes, 256-byte aligned, no
  * initial contents required, not shared by concurrent calls.
  * Limits: Dm a multiple of 64; W <= 128, W <= V; B*W <= 512; V <= 262144; L <= 384.
- * The call enqueues 4 + n_mlp launches per drafted position (5 + n_mlp after the first) while
- * B*W <= 128; every further 128 rows add one launch per linear layer.
+ * The call enqueues at most 4 + n_mlp launches per drafted position (5 + n_mlp after the first; one
+ * fewer for W <= 8 and V <= 32768) while B*W <= 128; every further 128 rows add one launch per linear layer.
  */
 typedef struct {
     const void *emb, *rnn_u, *rnn_w;

@@ -845,6 +845,131 @@ __global__ __launch_bounds__(kSelThreads) void rd_beam_step_kernel(
     }
 }
 
+// Row pass and beam step in one launch, for beams of at most 8 candidates over at most 8 chunks (one wave
+// holds a whole sequence: lane = candidate row * 8 + chunk): the rows' sorted lists never leave LDS.  Same
+// merges, same tie rules and the same arithmetic as the two kernels above; one workgroup per sequence.
+__global__ __launch_bounds__(kSelThreads) void rd_row_beam_kernel(
+    const float *__restrict__ part_max, const float *__restrict__ part_sum, const float *__restrict__ part_cv,
+    const int32_t *__restrict__ part_ci, int chunks, const float *__restrict__ cum_cur, int V, int W, int L, int t, int live,
+    const int32_t *__restrict__ paths_cur, int32_t *__restrict__ paths_next, float *__restrict__ cum_next,
+    int32_t *__restrict__ parent_row, int32_t *__restrict__ tok_row,
+    int32_t *__restrict__ beams_out, float *__restrict__ logp_out /* both NULL except at the last position */)
+{
+    constexpr int kW = 8;                                             // candidates, chunks and list length at most
+    __shared__ float s_cv[kW * kW * kW];                              // [row][chunk][W]: the chunk pass's lists
+    __shared__ int s_ci[kW * kW * kW];
+    __shared__ float s_score[kW * kW];                                // [row][W]: the rows' lists, cumulative scores
+    __shared__ int s_ctok[kW * kW];
+    __shared__ int s_win[kW], s_tok[kW], s_ptr[kW];
+    __shared__ float s_winv[kW];
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, g = lane >> 3, c = lane & 7;
+    const bool row_ok = g < live;
+    const size_t row = (size_t)b * W + (row_ok ? g : 0);              // rows b*W .. b*W+live-1 (at the first position: b*W)
+    const int n_surv = chunks * W;
+    const bool lane_ok = row_ok && c < chunks;
+    const float pm = lane_ok ? part_max[row * chunks + c] : -INFINITY;
+    const float gm = group8_max(pm);
+    float ps = lane_ok ? part_sum[row * chunks + c] * __expf(pm - gm) : 0.f;
+#pragma unroll
+    for (int off = 1; off < 8; off <<= 1) ps += __shfl_xor(ps, off, 64);
+    const float lse = gm + __logf(ps);
+    const float base = row_ok ? cum_cur[row] : 0.f;
+    {   // the sequence's survivors -> LDS (two loads per thread in flight, addresses past the end pulled back)
+        const int total = live * n_surv;                              // <= 512
+        float v[2];
+        int ti[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int idx = min(u * kSelThreads + tid, total - 1);
+            const int gg = idx / n_surv, q = idx - gg * n_surv;
+            const size_t src = ((size_t)b * W + gg) * n_surv + q;
+            v[u] = part_cv[src];
+            ti[u] = part_ci[src];
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int idx = u * kSelThreads + tid;
+            if (idx < total) {
+                const int gg = idx / n_surv, q = idx - gg * n_surv;
+                s_cv[gg * kW * kW + q] = v[u];
+                s_ci[gg * kW * kW + q] = ti[u];
+            }
+        }
+    }
+    __syncthreads();
+    if (tid < 64) {
+        // rows: merge of each row's chunk lists into its W best tokens, as cumulative scores
+        const float *lv = s_cv + g * kW * kW + c * W;
+        const int *li = s_ci + g * kW * kW + c * W;
+        int ptr = 0;
+        int ht = li[0], nt = li[W > 1 ? 1 : 0];
+        float hv = lv[0], nv = lv[W > 1 ? 1 : 0];
+        bool on = lane_ok && ht != 0x7fffffff;
+        for (int r = 0; r < W; ++r) {
+            const float best = group8_max(on ? hv : -INFINITY);
+            const unsigned long long offers = __ballot(on && hv == best);
+            const unsigned mine = (unsigned)(offers >> (g * 8)) & 0xffu;
+            const int win = mine ? __ffs((int)mine) - 1 : -1;
+            if (c == 0 && row_ok) s_score[g * W + r] = win >= 0 ? base + (best - lse) : -INFINITY;
+            if (c == win) {
+                s_ctok[g * W + r] = ht;
+                ++ptr;
+                hv = nv; ht = nt;
+                on = ptr < W && ht != 0x7fffffff;
+                const int nx = ptr + 1 < W ? ptr + 1 : W - 1;
+                nv = lv[nx]; nt = li[nx];
+            } else if (c == 0 && win < 0 && row_ok) {
+                s_ctok[g * W + r] = 0;
+            }
+        }
+    }
+    __syncthreads();
+    if (tid < 64) {
+        // sequence: merge of the live rows' lists, lane w = row w
+        int ptr = 0;
+        bool on = lane < live;
+        const int la = (on ? lane : 0) * W;
+        float hv = s_score[la], nv = s_score[la + (W > 1 ? 1 : 0)];
+        for (int r = 0; r < W; ++r) {
+            const float best = wave_max(on ? hv : -INFINITY);
+            int win = first_lane(on && hv == best);
+            if (win < 0) win = first_lane(on);                        // NaN scores: keep indices in range
+            if (win < 0) win = 0;
+            if (lane == win) {
+                s_win[r] = lane;
+                s_winv[r] = best;
+                s_ptr[r] = ptr < W ? ptr : W - 1;
+                if (on) {
+                    ++ptr;
+                    on = ptr < W;
+                    hv = nv;
+                    nv = s_score[la + (ptr + 1 < W ? ptr + 1 : W - 1)];
+                }
+            }
+        }
+    }
+    __syncthreads();
+    for (int r = tid; r < W; r += kSelThreads) {
+        const int tk = s_ctok[s_win[r] * W + s_ptr[r]];
+        s_tok[r] = tk < 0 ? 0 : (tk > V - 1 ? V - 1 : tk);
+    }
+    __syncthreads();
+    for (int i = tid; i < W * L; i += kSelThreads) {
+        const int r = i / L, j = i - r * L;
+        const int pw = s_win[r];
+        const size_t src = ((size_t)b * W + pw) * L;
+        const int v = j < t ? paths_cur[src + j] : (j == t ? s_tok[r] : paths_cur[src]);
+        paths_next[((size_t)b * W + r) * L + j] = v;
+        if (beams_out) beams_out[((size_t)b * W + r) * L + j] = v;
+    }
+    for (int w = tid; w < W; w += kSelThreads) {
+        cum_next[(size_t)b * W + w] = s_winv[w];
+        parent_row[(size_t)b * W + w] = b * W + s_win[w];
+        tok_row[(size_t)b * W + w] = s_tok[w];
+        if (logp_out) logp_out[(size_t)b * W + w] = s_winv[w];
+    }
+}
+
 // For every final candidate, the row of each position's logit matrix that produced its token there:
 // follow the parent rows back from the last position.  One thread per candidate.
 __global__ void rd_draft_rows_kernel(const int32_t *__restrict__ parents /*[T][M]*/, int M, int W, int T,
@@ -1149,6 +1274,14 @@ int draft_run(const rd_draft_params *p, const void *h, const int32_t *last_token
         const bool last = t == T;
         const bool wide = W > kNarrowBeam;
         const int live = t == 1 ? 1 : W;
+        static const int fuse_on = rd::env_int("RD_DRAFT_FUSE_ROW_BEAM", 1);   // 0: the two kernels (for comparisons)
+        if (fuse_on && W <= 8 && chunks <= 8 && lpc == 1) {
+            hipLaunchKernelGGL(rd_row_beam_kernel, dim3(B), dim3(kSelThreads), 0, s, part_max, part_sum, part_cv, part_ci, chunks,
+                               cum[cur], V, W, L, t, live, paths[cur], paths[nxt], cum[nxt], parent + (size_t)(t - 1) * M, tok,
+                               last ? beams : nullptr, last ? beam_logp : nullptr);
+            if (rd_check_launch() != RD_OK) return RD_ERR_HIP;
+            continue;
+        }
 #define RD_ROW_LAUNCH(LPR, WMAX, grid)                                                                                   \
         hipLaunchKernelGGL((rd_topw_row_kernel<LPR, WMAX>), dim3(grid), dim3(kSelThreads), 0, s, part_max, part_sum, part_cv, part_ci, \
                            chunks, lpc, cum[cur], W, rows, mstride, row_score, row_tok)
