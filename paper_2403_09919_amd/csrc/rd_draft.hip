@@ -107,29 +107,34 @@ __device__ __forceinline__ void linear_epilogue(const LinArgs<T> &a, f32x4 v, in
 }
 
 // The last workgroup of a column group adds the KS partial tiles of each output tile in split order
-// and finishes them.  All of a wave's loads are issued before the first sum.
+// and finishes them.  A wave's loads are issued together (in batches of at most 32 partial tiles) before
+// the sums.
 template <typename T, int MT, int NT, int NWV, int EPI, int KS>
 __device__ __forceinline__ void linear_finish_split(const LinArgs<T> &a, int group, int n0, int wave, int lane)
 {
     constexpr int kTiles = MT * NT, kMine = kTiles / NWV;       // tiles per wave
-    static_assert(kTiles % NWV == 0, "every wave finishes the same number of tiles");
+    constexpr int kBatch = kMine * KS > 32 ? 32 / KS : kMine;   // tiles whose loads are in flight together (<= 128 registers)
+    static_assert(kTiles % NWV == 0 && kMine % kBatch == 0, "every wave finishes the same number of tiles, in whole batches");
     const int r16 = lane & 15, g = lane >> 4;
-    float2 lo[kMine][KS], hi[kMine][KS];
 #pragma unroll
-    for (int i = 0; i < kMine; ++i)
+    for (int i0 = 0; i0 < kMine; i0 += kBatch) {
+        float2 lo[kBatch][KS], hi[kBatch][KS];
 #pragma unroll
-        for (int sp = 0; sp < KS; ++sp) {
-            const float *src = a.kpart + ((((size_t)group * KS + sp) * kTiles + wave + i * NWV) * 64 + lane) * 4;
-            lo[i][sp] = rd::ld_dev2(src);
-            hi[i][sp] = rd::ld_dev2(src + 2);
+        for (int i = 0; i < kBatch; ++i)
+#pragma unroll
+            for (int sp = 0; sp < KS; ++sp) {
+                const float *src = a.kpart + ((((size_t)group * KS + sp) * kTiles + wave + (i0 + i) * NWV) * 64 + lane) * 4;
+                lo[i][sp] = rd::ld_dev2(src);
+                hi[i][sp] = rd::ld_dev2(src + 2);
+            }
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) {
+            const int id = wave + (i0 + i) * NWV;
+            f32x4 v = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int sp = 0; sp < KS; ++sp) v += f32x4{lo[i][sp].x, lo[i][sp].y, hi[i][sp].x, hi[i][sp].y};
+            linear_epilogue<T, EPI>(a, v, (id / NT) * 16, n0 + (id % NT) * 16, r16, g);
         }
-#pragma unroll
-    for (int i = 0; i < kMine; ++i) {
-        const int id = wave + i * NWV;
-        f32x4 v = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int sp = 0; sp < KS; ++sp) v += f32x4{lo[i][sp].x, lo[i][sp].y, hi[i][sp].x, hi[i][sp].y};
-        linear_epilogue<T, EPI>(a, v, (id / NT) * 16, n0 + (id % NT) * 16, r16, g);
     }
 }
 
