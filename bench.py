@@ -3,20 +3,28 @@
 
 A step is one pass of the whole hot path over one synthetic batch:
 rd_dedup -> rd_tree_attn (one layer's attention core) -> rd_accept, back to back on one
-stream with all inputs resident in HBM.  The default workload is the Vicuna-7B-shaped
+stream with all inputs resident in HBM.  The headline workload is the Vicuna-7B-shaped
 configuration (B=1, context 1024, H=32, D=128, bf16 KV, W=8, L=5, vocab 32000).
 
-To keep the infinity cache from serving the KV stream, the step rotates over R
-independent copies of the inputs whose K/V total exceeds 512 MiB.  The R steps are
-captured once into a HIP graph (the library only enqueues kernels, so a caller can do
-that) and the graph is replayed, which removes the Python/ctypes launch cost from the
-timed region; --no-graph times eager launches instead.
+To keep the infinity cache from serving the KV stream, step i works on copy i mod R of R
+independent input copies whose K/V total exceeds 512 MiB, and a buffer larger than every cache is
+overwritten before each timed region.  The timed region consists of HIP-graph replays only,
+whatever --steps is: the library only enqueues kernels, so a caller can capture them; the steps
+W .. W+K-1 of the rotation are cut into graphs of at most R consecutive steps, captured before the
+clock starts, and replayed so that EXACTLY K steps run between the two events (--no-graph times
+eager launches instead and says so in config.launch).
+
+Beside the headline figures the JSON line carries a `configs` block with the attention launch time
+(median and 10th / 90th percentile over graph replays), algorithmic bytes, fraction of the 8 TB/s
+HBM peak, the plain streaming-read floor of the same bytes, the step time and the CPU oracle's rate
+for each of the five synthetic configurations.
 
 Prints one JSON line (see README for the fields).
 """
 from __future__ import annotations
 
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -29,11 +37,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per rd_tree_attn launch from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, each scaled
-# by what the same counter reads for a 64 MiB copy); see profiles/bench_vicuna7b_layer_rocprofv3.md.
-# Keyed by workload; None where no counter run has been made.
-MEASURED_TRAFFIC_BYTES = {2: 21900746}
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "rd_tree_attn_hbm_traffic.md")
 LAYERS_BY_HEADS = {32: 32, 40: 40, 52: 60}      # decoder layers of the 7B / 13B / 33B models the shapes come from
+FLUSH_BYTES = 1 << 30                           # larger than the 256 MB infinity cache plus every L2
 
 
 def parse():
@@ -41,47 +47,280 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=6400)
     ap.add_argument("--warmup", type=int, default=640)
-    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2: Vicuna-7B-shaped layer)")
+    ap.add_argument("--config", type=int, default=2, help="headline workload 1..5 (default 2: Vicuna-7B-shaped layer)")
     ap.add_argument("--copies", type=int, default=0, help="rotating input copies (0 = enough for > 512 MiB of K/V)")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of graph replays")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-draft", action="store_true", help="skip the separate rd_draft timing")
     ap.add_argument("--no-floor", action="store_true", help="skip the plain streaming-read floor measurement")
-    ap.add_argument("--no-warm-cache", action="store_true",
-                    help="skip the warm-cache attention figure (so that a kernel trace holds rotating launches only)")
-    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time budget of the oracle baseline")
+    ap.add_argument("--no-configs", action="store_true", help="skip the per-configuration block (configs 1..5)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="headline kernels only: no warm-cache figure, no rd_commit / rd_accept_sample / live-context "
+                         "timings (so that a kernel trace or counter run holds the step's launches only)")
+    ap.add_argument("--cpu-seconds", type=float, default=8.0, help="CPU time budget of the oracle baseline")
     ap.add_argument("--pmc-calib", action="store_true",
                     help="also run plain device copies of 64 MiB (reference dispatches for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
-def build_copies(cfg, R, rd, synth, torch):
-    """R independent synthetic batches on the device, plus their dedup results (from the HIP path)."""
-    dev = torch.device("cuda:0")
-    tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(cfg.seed)
-    copies = []
-    for r in range(R):
-        seed = cfg.seed + 7919 * r
-        beams = torch.from_numpy(synth.make_beams(cfg.B, cfg.W, cfg.L, cfg.V, seed, cfg.share)).to(dev)
-        ctx_np = synth.make_ctx_len(cfg.B, cfg.ctx_lo, cfg.ctx_hi, seed)
-        ctx = torch.from_numpy(ctx_np).to(dev)
-        c = dict(beams=beams, ctx_len=ctx, ctx_np=ctx_np)
-        for name, n in (("q", cfg.N), ("k_new", cfg.N), ("v_new", cfg.N), ("k_cache", cfg.Cmax), ("v_cache", cfg.Cmax)):
-            c[name] = torch.randn((cfg.B, cfg.H, n, cfg.D), generator=gen, device=dev, dtype=torch.float32).to(tdt)
-        c["dedup"] = rd.rd_dedup(beams, ctx)
+def read_traffic_table():
+    """HBM bytes per rd_tree_attn launch by configuration, from the committed counter summary
+    (rows `| config | FETCH_SIZE | WRITE_SIZE | fetch scale | write scale | bytes |`)."""
+    out = {}
+    try:
+        with open(TRAFFIC_TABLE) as f:
+            for line in f:
+                cells = [c.strip() for c in line.strip().strip("|").split("|")]
+                if len(cells) >= 6 and cells[0].isdigit():
+                    out[int(cells[0])] = int(float(cells[5]))
+    except OSError:
+        pass
+    return out
+
+
+class Workload:
+    """R independent synthetic batches of one configuration on the device, with the closures that
+    enqueue the library's calls on them."""
+
+    def __init__(self, cfg, R, rd, synth, torch, ctx_override=None):
+        self.cfg, self.R, self.rd, self.torch = cfg, R, rd, torch
+        dev = torch.device("cuda:0")
+        self.esz = 4 if cfg.dtype == "f32" else 2
+        tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+        self.dt_code = rd.RD_F32 if cfg.dtype == "f32" else rd.RD_BF16
+        self.scale = float(1.0 / np.sqrt(cfg.D))
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(cfg.seed)
+        self.copies = []
+        for r in range(R):
+            seed = cfg.seed + 7919 * r
+            beams = torch.from_numpy(synth.make_beams(cfg.B, cfg.W, cfg.L, cfg.V, seed, cfg.share)).to(dev)
+            ctx_np = synth.make_ctx_len(cfg.B, cfg.ctx_lo, cfg.ctx_hi, seed)
+            if ctx_override is not None:
+                ctx_np = np.full_like(ctx_np, ctx_override)
+            c = dict(beams=beams, ctx_len=torch.from_numpy(ctx_np).to(dev), ctx_np=ctx_np)
+            for name, n in (("q", cfg.N), ("k_new", cfg.N), ("v_new", cfg.N), ("k_cache", cfg.Cmax), ("v_cache", cfg.Cmax)):
+                c[name] = torch.randn((cfg.B, cfg.H, n, cfg.D), generator=gen, device=dev, dtype=torch.float32).to(tdt)
+            c["dedup"] = rd.rd_dedup(beams, c["ctx_len"])
+            torch.cuda.synchronize()
+            d = c["dedup"]
+            c["n_packed_np"] = d["n_packed"].cpu().numpy()
+            logits = synth.make_logits(cfg.B, cfg.N, cfg.V, seed, d["packed_tokens"].cpu().numpy(),
+                                       d["parent"].cpu().numpy(), c["n_packed_np"], cfg.p_plant)
+            c["logits"] = torch.from_numpy(logits).to(dev)
+            c["attn_out"] = torch.empty_like(c["q"])
+            c["accept"] = None
+            self.copies.append(c)
+        self.ws_attn = rd.new_workspace(rd.rd_tree_attn_workspace(cfg.B, cfg.H, cfg.N, cfg.D, cfg.Cmax, self.dt_code), "cuda")
+        self.ws_acc = rd.new_workspace(rd.rd_accept_workspace(cfg.B, cfg.W, cfg.L, cfg.V), "cuda")
+        # algorithmic bytes of one rd_tree_attn launch: every visible K/V element once, packed q/k/v/out once, mask bits
+        words = (cfg.N + 63) // 64
+        ab, pt = [], []
+        for c in self.copies:
+            P = c["n_packed_np"].astype(np.int64)
+            C = c["ctx_np"].astype(np.int64)
+            ab.append(self.esz * cfg.H * cfg.D * int((2 * C + 4 * P).sum()) + int(P.sum()) * words * 8)
+            pt.append(int(P.sum()))
+        self.attn_bytes = float(np.mean(ab))
+        self.packed = float(np.mean(pt))
+        for c in self.copies:                 # eager pass: allocates outputs, sets kernel attributes
+            self.step(c)
         torch.cuda.synchronize()
+
+    def attn(self, c):
         d = c["dedup"]
-        c["n_packed_np"] = d["n_packed"].cpu().numpy()
-        logits = synth.make_logits(cfg.B, cfg.N, cfg.V, seed, d["packed_tokens"].cpu().numpy(),
-                                   d["parent"].cpu().numpy(), c["n_packed_np"], cfg.p_plant)
-        c["logits"] = torch.from_numpy(logits).to(dev)
-        c["attn_out"] = torch.empty_like(c["q"])
-        c["accept"] = None
-        copies.append(c)
-    return copies
+        self.rd.rd_tree_attn(c["q"], c["k_cache"], c["v_cache"], c["ctx_len"], c["k_new"], c["v_new"],
+                             d["n_packed"], d["tree_mask_bits"], self.scale, out=c["attn_out"], workspace=self.ws_attn)
+
+    def dedup(self, c):
+        self.rd.rd_dedup(c["beams"], c["ctx_len"], out=c["dedup"])
+
+    def accept(self, c):
+        d = c["dedup"]
+        c["accept"] = self.rd.rd_accept(c["logits"], c["beams"], d["unpack_index"], d["n_packed"],
+                                        out=c["accept"], workspace=self.ws_acc)
+
+    def step(self, c):
+        self.dedup(c)
+        self.attn(c)
+        self.accept(c)
+
+    def describe(self):
+        cfg = self.cfg
+        return "%s: B=%d ctx=%s H=%d D=%d %s KV, W=%d L=%d V=%d" % (
+            cfg.name, cfg.B, cfg.ctx_lo if cfg.ctx_lo == cfg.ctx_hi else "U{%d..%d}" % (cfg.ctx_lo, cfg.ctx_hi),
+            cfg.H, cfg.D, cfg.dtype, cfg.W, cfg.L, cfg.V)
+
+
+class Rotation:
+    """Enqueues `fn` on consecutive copies of a workload: as replays of HIP graphs that each hold at
+    most R consecutive calls (captured on first use, i.e. outside any timed region when `plan` is
+    called beforehand), or eagerly."""
+
+    def __init__(self, wl, fn, stream, use_graph):
+        self.wl, self.fn, self.stream, self.use_graph = wl, fn, stream, use_graph
+        self.graphs = {}
+
+    def _graph(self, start, count):
+        torch = self.wl.torch
+        key = (start, count)
+        if key not in self.graphs:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=self.stream):
+                for j in range(count):
+                    self.fn(self.wl.copies[(start + j) % self.wl.R])
+            self.graphs[key] = g
+        return self.graphs[key]
+
+    def plan(self, first, n):
+        """Calls number first .. first+n-1 of the rotation as a list of things to run."""
+        R = self.wl.R
+        segs, pos, left = [], first % R, n
+        while left > 0:
+            cnt = min(left, R)
+            segs.append((pos, cnt, self._graph(pos, cnt) if self.use_graph else None))
+            pos = (pos + cnt) % R
+            left -= cnt
+        return segs
+
+    def run(self, segs):
+        for pos, cnt, g in segs:
+            if g is not None:
+                g.replay()
+            else:
+                for j in range(cnt):
+                    self.fn(self.wl.copies[(pos + j) % self.wl.R])
+
+    def timed(self, warmup, steps, flush):
+        """(microseconds per call over exactly `steps` calls, wall ms) after `warmup` untimed calls."""
+        torch = self.wl.torch
+        with torch.cuda.stream(self.stream):
+            w = self.plan(0, warmup)
+            t = self.plan(warmup, steps)
+            torch.cuda.synchronize()
+            if flush is not None:
+                flush.add_(1)
+            self.run(w)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            t0 = time.perf_counter()
+            e0.record(self.stream)
+            self.run(t)
+            e1.record(self.stream)
+            torch.cuda.synchronize()
+            wall_ms = (time.perf_counter() - t0) * 1e3
+        return e0.elapsed_time(e1) * 1e3 / steps, wall_ms
+
+    def spread(self, target_ms=20.0, est_us=None):
+        """Per-call time with every graph replay timed on its own: median and 10th / 90th percentile of
+        the per-call mean of a replay.  A replay holds at least six calls and whole rotations."""
+        torch = self.wl.torch
+        R = self.wl.R
+        rot = max(1, -(-6 // R))
+        with torch.cuda.stream(self.stream):
+            segs = self.plan(0, R) * rot
+            self.run(segs)
+            if est_us is None:
+                torch.cuda.synchronize()
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record(self.stream)
+                self.run(segs)
+                b.record(self.stream)
+                torch.cuda.synchronize()
+                est_us = a.elapsed_time(b) * 1e3 / (R * rot)
+            reps = int(min(200, max(10, target_ms * 1e3 / max(est_us * R * rot, 1.0))))
+            evs = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+            evs[0].record(self.stream)
+            for i in range(reps):
+                self.run(segs)
+                evs[i + 1].record(self.stream)
+            torch.cuda.synchronize()
+        per = np.array([evs[i].elapsed_time(evs[i + 1]) * 1e3 / (R * rot) for i in range(reps)])
+        return {"p10": round(float(np.percentile(per, 10)), 3), "median": round(float(np.median(per)), 3),
+                "p90": round(float(np.percentile(per, 90)), 3), "replays": reps, "launches_per_replay": R * rot,
+                "launch": "hip_graph_replay" if self.use_graph else "eager"}
+
+
+def stream_read_floor(wl, stream, use_graph):
+    """The machine's floor for the dominant kernel: a plain streaming read of the same number of bytes,
+    launched back to back over rotating buffers, best of a few workgroup counts."""
+    torch, rd, R = wl.torch, wl.rd, wl.R
+    nbytes = max(int(wl.attn_bytes) // 16 * 16, 16)
+    slab = torch.empty((R, nbytes), dtype=torch.uint8, device="cuda").fill_(1)
+    best = None
+    for wgs in (256, 512, 1024, 2048):
+        def fn(c, wgs=wgs):
+            rd.rd_debug_stream_read(slab[c["slab"]], wgs)
+        for r, c in enumerate(wl.copies):
+            c["slab"] = r
+        sp = Rotation(wl, fn, stream, use_graph).spread(target_ms=6.0)
+        if best is None or sp["median"] < best[0]:
+            best = (sp["median"], wgs)
+    del slab
+    return {"us_per_launch": round(best[0], 3), "workgroups": best[1], "bytes": nbytes,
+            "GB/s": round(nbytes / best[0] / 1e3, 1), "launch": "hip_graph_replay" if use_graph else "eager"}
+
+
+def cpu_baseline(cfg, synth, budget_s, max_seqs=None):
+    """The CPU oracle as it stands, timed on this host on whole steps.  With max_seqs the sample is the
+    first max_seqs sequences' worth of the batch (same generator, batch size reduced) and the rate is
+    scaled by the fraction of the batch it covers."""
+    import oracle                               # baseline leg only; the timed GPU path never touches it
+    nb = cfg.B if max_seqs is None else min(cfg.B, max_seqs)
+    cpu_cfg = cfg if nb == cfg.B else dataclasses.replace(cfg, B=nb)
+    t = synth.make_attn_inputs(cpu_cfg, seed=cfg.seed, poison=False)
+    scale = float(1.0 / np.sqrt(cpu_cfg.D))
+    d = oracle.dedup(t["beams"], t["ctx_len"])
+    logits = synth.make_logits(cpu_cfg.B, cpu_cfg.N, cpu_cfg.V, cfg.seed, d["packed_tokens"], d["parent"],
+                               d["n_packed"], cpu_cfg.p_plant)
+    reps, t0 = 0, time.perf_counter()
+    while True:
+        oracle.verify_step(t["beams"], t["ctx_len"], t["q"], t["k_cache"], t["v_cache"], t["k_new"], t["v_new"],
+                           logits, cpu_cfg.dtype, scale)
+        reps += 1
+        el = time.perf_counter() - t0
+        if el >= budget_s or (reps >= 3 and el >= 0.5 * budget_s):
+            break
+    rate = reps / el * nb / cfg.B
+    what = "%d whole steps of the same workload (%s), %.1f s" % (reps, cfg.name, el)
+    if nb != cfg.B:
+        what = "%d steps over %d of the %d sequences (%s), %.1f s, rate scaled by %d/%d" % (
+            reps, nb, cfg.B, cfg.name, el, nb, cfg.B)
+    return {"value": round(rate, 4), "unit": "steps/s", "cores": oracle.num_threads(), "kind": "oracle", "sample": what}
+
+
+def copies_for(cfg, want):
+    esz = 4 if cfg.dtype == "f32" else 2
+    kv_bytes = 2 * cfg.B * cfg.H * cfg.Cmax * cfg.D * esz
+    return want if want > 0 else min(33, max(2, -(-(512 << 20) // kv_bytes) + 1))
+
+
+def config_entry(wl, stream, use_graph, flush, traffic, want_floor, cpu_s, synth):
+    """One row of the `configs` block."""
+    cfg = wl.cfg
+    attn = Rotation(wl, wl.attn, stream, use_graph)
+    with wl.torch.cuda.stream(stream):
+        flush.add_(1)
+    sp = attn.spread()
+    step_us, _ = Rotation(wl, wl.step, stream, use_graph).timed(wl.R, max(2 * wl.R, 12), flush)
+    gbs = wl.attn_bytes / sp["median"] / 1e3
+    e = {"workload": wl.describe(), "rotating_copies": wl.R,
+         "rd_tree_attn_us": sp, "algorithmic_bytes_per_launch": round(wl.attn_bytes, 1),
+         "GB/s": round(gbs, 1), "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": traffic.get(cfg.idx),
+         "step_us": round(step_us, 3), "steps_per_sec": round(1e6 / step_us, 1),
+         "packed_tokens_per_step": round(wl.packed, 2),
+         "rd_dedup_us": Rotation(wl, wl.dedup, stream, use_graph).spread(target_ms=3.0)["median"],
+         "rd_accept_us": Rotation(wl, wl.accept, stream, use_graph).spread(target_ms=3.0)["median"]}
+    if want_floor:
+        fl = stream_read_floor(wl, stream, use_graph)
+        e["stream_read_floor_us"] = fl["us_per_launch"]
+        e["stream_read_floor_GB/s"] = fl["GB/s"]
+    if cpu_s > 0:
+        o = cpu_baseline(cfg, synth, cpu_s, max_seqs=2)
+        e["oracle_steps_per_sec"] = o["value"]
+        e["oracle_sample"] = o["sample"]
+    return e
 
 
 def main():
@@ -98,42 +337,14 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     cfg = synth.CONFIGS[args.config]
-    esz = 4 if cfg.dtype == "f32" else 2
-    kv_bytes = 2 * cfg.B * cfg.H * cfg.Cmax * cfg.D * esz
-    R = args.copies if args.copies > 0 else max(2, -(-(512 << 20) // kv_bytes) + 1)
-    scale = float(1.0 / np.sqrt(cfg.D))
-    dt_code = rd.RD_F32 if cfg.dtype == "f32" else rd.RD_BF16
+    use_graph = not args.no_graph
+    launch = "hip_graph_replay" if use_graph else "eager"
+    traffic = read_traffic_table()
+    stream = torch.cuda.Stream()          # default priority; capture needs a non-default stream
+    flush = torch.zeros(FLUSH_BYTES, dtype=torch.uint8, device="cuda")
 
-    copies = build_copies(cfg, R, rd, synth, torch)
-    ws_attn = rd.new_workspace(rd.rd_tree_attn_workspace(cfg.B, cfg.H, cfg.N, cfg.D, cfg.Cmax, dt_code), "cuda")
-    ws_acc = rd.new_workspace(rd.rd_accept_workspace(cfg.B, cfg.W, cfg.L, cfg.V), "cuda")
-
-    def attn(c):
-        d = c["dedup"]
-        rd.rd_tree_attn(c["q"], c["k_cache"], c["v_cache"], c["ctx_len"], c["k_new"], c["v_new"],
-                        d["n_packed"], d["tree_mask_bits"], scale, out=c["attn_out"], workspace=ws_attn)
-
-    def step(c):
-        d = rd.rd_dedup(c["beams"], c["ctx_len"], out=c["dedup"])
-        attn(c)
-        c["accept"] = rd.rd_accept(c["logits"], c["beams"], d["unpack_index"], d["n_packed"],
-                                   out=c["accept"], workspace=ws_acc)
-
-    # algorithmic bytes of one rd_tree_attn launch: every visible K/V element once, packed q/k/v/out once, mask bits
-    words = (cfg.N + 63) // 64
-    attn_bytes = []
-    packed_total = []
-    for c in copies:
-        P = c["n_packed_np"].astype(np.int64)
-        C = c["ctx_np"].astype(np.int64)
-        attn_bytes.append(esz * cfg.H * cfg.D * int((2 * C + 4 * P).sum()) + int(P.sum()) * words * 8)
-        packed_total.append(int(P.sum()))
-    attn_bytes_mean = float(np.mean(attn_bytes))
-    packed_mean = float(np.mean(packed_total))
-
-    for c in copies:                      # eager pass: allocates outputs, sets kernel attributes
-        step(c)
-    torch.cuda.synchronize()
+    wl = Workload(cfg, copies_for(cfg, args.copies), rd, synth, torch)
+    R = wl.R
 
     if args.pmc_calib:                    # known traffic: each copy reads 64 MiB and writes 64 MiB
         src = torch.empty(32 << 20, dtype=torch.bfloat16, device="cuda").normal_()
@@ -142,210 +353,36 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
 
-    use_graph = not args.no_graph
-    stream = torch.cuda.Stream()          # default priority; capture needs a non-default stream
-    if use_graph:
-        with torch.cuda.stream(stream):
-            g_step = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g_step, stream=stream):
-                for c in copies:
-                    step(c)
-            g_attn = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g_attn, stream=stream):
-                for c in copies:
-                    attn(c)
-        torch.cuda.synchronize()
+    # ---- timed region 1: whole steps (exactly --steps of them, graph replays only) ------------------
+    steps_rot = Rotation(wl, wl.step, stream, use_graph)
+    step_us, wall_ms = steps_rot.timed(args.warmup, args.steps, flush)
+    ms_per_step = step_us / 1e3
+    steps_per_s = 1e6 / step_us
 
-    def run_steps(n):
-        """n steps on `stream` (graph replays of R steps each, remainder eagerly rotated)."""
-        with torch.cuda.stream(stream):
-            if use_graph:
-                for _ in range(n // R):
-                    g_step.replay()
-                for i in range(n % R):
-                    step(copies[i])
-            else:
-                for i in range(n):
-                    step(copies[i % R])
+    # ---- timed region 2: the dominant kernel alone (rd_tree_attn), events on its own stream ----------
+    attn_rot = Rotation(wl, wl.attn, stream, use_graph)
+    attn_us, _ = attn_rot.timed(args.warmup, args.steps, flush)
+    achieved = wl.attn_bytes / (attn_us * 1e-6) / 1e9
+    attn_spread = attn_rot.spread(est_us=attn_us)
 
-    def run_attn(n):
-        with torch.cuda.stream(stream):
-            if use_graph:
-                for _ in range(n // R):
-                    g_attn.replay()
-                for i in range(n % R):
-                    attn(copies[i])
-            else:
-                for i in range(n):
-                    attn(copies[i % R])
+    # the other kernels of the step one by one
+    kernels_us = {"rd_dedup": Rotation(wl, wl.dedup, stream, use_graph).spread(target_ms=5.0)["median"],
+                  "rd_tree_attn": round(attn_us, 3),
+                  "rd_accept": Rotation(wl, wl.accept, stream, use_graph).spread(target_ms=5.0)["median"]}
+    valid_rows = float(np.mean([c["n_packed_np"].sum() for c in wl.copies]))
+    kernels_gbs = {"rd_accept": round(valid_rows * cfg.V * 4 / kernels_us["rd_accept"] / 1e3, 1)}
 
-    # ---- timed region 1: whole steps -------------------------------------------------------------
-    run_steps(args.warmup)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    with torch.cuda.stream(stream):
-        e0.record(stream)
-    run_steps(args.steps)
-    with torch.cuda.stream(stream):
-        e1.record(stream)
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
-    step_ms = e0.elapsed_time(e1) / args.steps
-    ms_per_step = max(step_ms, 0.0)
-    steps_per_s = 1e3 / ms_per_step
+    attn_warm_us = None
+    if not args.no_extras:
+        extras(wl, stream, use_graph, kernels_us, kernels_gbs, valid_rows, torch)
+        # the same launch on one copy over and over (K/V then sit in the caches: reported beside the rotating
+        # figure, never instead of it)
+        one = Workload.__new__(Workload)
+        one.__dict__.update(wl.__dict__)
+        one.copies, one.R = [wl.copies[0]] * R, R
+        attn_warm_us = Rotation(one, wl.attn, stream, use_graph).spread(target_ms=8.0)["median"]
 
-    # ---- timed region 2: the dominant kernel alone (rd_tree_attn), events on its own stream --------
-    run_attn(args.warmup)
-    torch.cuda.synchronize()
-    a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    with torch.cuda.stream(stream):
-        a0.record(stream)
-    run_attn(args.steps)
-    with torch.cuda.stream(stream):
-        a1.record(stream)
-    torch.cuda.synchronize()
-    attn_us = a0.elapsed_time(a1) * 1e3 / args.steps
-    achieved = attn_bytes_mean / (attn_us * 1e-6) / 1e9
-
-    # spread of the attention launch: every replay of the R-launch graph timed on its own (median, 10th and
-    # 90th percentile of the per-launch mean), and the same launch on one copy over and over (K/V then sit in
-    # the caches: reported beside the rotating figure, never instead of it)
-    attn_spread = attn_warm_us = None
-    if use_graph:
-        reps = max(10, min(200, args.steps // R))
-        evs = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
-        with torch.cuda.stream(stream):
-            evs[0].record(stream)
-            for i in range(reps):
-                g_attn.replay()
-                evs[i + 1].record(stream)
-        torch.cuda.synchronize()
-        per = np.array([evs[i].elapsed_time(evs[i + 1]) * 1e3 / R for i in range(reps)])
-        attn_spread = {"p10": round(float(np.percentile(per, 10)), 3), "median": round(float(np.median(per)), 3),
-                       "p90": round(float(np.percentile(per, 90)), 3), "replays": reps, "launches_per_replay": R}
-    if use_graph and not args.no_warm_cache:
-        with torch.cuda.stream(stream):
-            g_warm = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g_warm, stream=stream):
-                for _ in range(R):
-                    attn(copies[0])
-            g_warm.replay()
-            w0, w1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            w0.record(stream)
-            for _ in range(reps):
-                g_warm.replay()
-            w1.record(stream)
-        torch.cuda.synchronize()
-        attn_warm_us = round(w0.elapsed_time(w1) * 1e3 / (reps * R), 3)
-
-    # ---- the other kernels one by one (reported beside the headline figures, not part of them) ------
-    # rd_commit (what follows the step, Sec. 3.4) appends the accepted rows behind position
-    # ctx_len - L here, because the synthetic caches are allocated full.
-    for c in copies:
-        c["ctx_commit"] = (c["ctx_len"] - cfg.L).clamp_(min=0)
-        c["ctx_out"] = torch.empty_like(c["ctx_len"])
-        c["n_comm"] = torch.empty_like(c["ctx_len"])
-
-    def k_dedup(c):
-        rd.rd_dedup(c["beams"], c["ctx_len"], out=c["dedup"])
-
-    def k_accept(c):
-        rd.rd_accept(c["logits"], c["beams"], c["dedup"]["unpack_index"], c["dedup"]["n_packed"],
-                     out=c["accept"], workspace=ws_acc)
-
-    dev = "cuda"
-    ws_samp = rd.new_workspace(rd.rd_accept_sample_workspace(cfg.B, cfg.W, cfg.L, cfg.V), dev)
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(cfg.seed + 2)
-    for c in copies:                                  # sampling-mode acceptance: draft logits near the LLM's, uniform draws
-        c["draft_logits"] = c["logits"] + torch.randn(c["logits"].shape, generator=gen, device=dev)
-        c["u_accept"] = torch.rand((cfg.B, cfg.N), generator=gen, device=dev)
-        c["u_next"] = torch.rand((cfg.B,), generator=gen, device=dev)
-        c["sample"] = rd.rd_accept_sample(c["logits"], c["draft_logits"], c["beams"], c["dedup"]["unpack_index"],
-                                          c["dedup"]["n_packed"], c["u_accept"], c["u_next"], 1.0, workspace=ws_samp)
-
-    def k_sample(c):
-        rd.rd_accept_sample(c["logits"], c["draft_logits"], c["beams"], c["dedup"]["unpack_index"], c["dedup"]["n_packed"],
-                            c["u_accept"], c["u_next"], 1.0, out=c["sample"], workspace=ws_samp)
-
-    def k_commit(c):
-        rd.rd_commit(c["k_new"], c["v_new"], c["accept"]["accepted_idx"], c["accept"]["best_len"], c["ctx_commit"],
-                     c["k_cache"], c["v_cache"], ctx_len_out=c["ctx_out"], n_committed=c["n_comm"])
-
-    def time_kernel(fn):
-        n = max(R, args.steps // 4)
-        with torch.cuda.stream(stream):
-            for c in copies:
-                fn(c)
-            g = None
-            if use_graph:
-                g = torch.cuda.CUDAGraph()
-                with torch.cuda.graph(g, stream=stream):
-                    for c in copies:
-                        fn(c)
-            k0, k1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            k0.record(stream)
-            for i in range(n // R):
-                if g is not None:
-                    g.replay()
-                else:
-                    for c in copies:
-                        fn(c)
-            k1.record(stream)
-        torch.cuda.synchronize()
-        return round(k0.elapsed_time(k1) * 1e3 / (n // R * R), 3)
-
-    kernels_us = {"rd_dedup": time_kernel(k_dedup), "rd_tree_attn": round(attn_us, 3),
-                  "rd_accept": time_kernel(k_accept), "rd_commit": time_kernel(k_commit),
-                  "rd_accept_sample": time_kernel(k_sample)}
-
-    # algorithmic bytes of the other streaming kernels (means over the copies): rd_accept reads the valid logit
-    # rows; rd_accept_sample reads them and the draft rows of slots that are not at the last position
-    valid_rows = float(np.mean([c["n_packed_np"].sum() for c in copies]))
-    leaf_rows = float(np.mean([sum(len(set(u[:, -1].tolist())) for u in c["dedup"]["unpack_index"].cpu().numpy())
-                               for c in copies]))
-    kernels_gbs = {
-        "rd_accept": round(valid_rows * cfg.V * 4 / kernels_us["rd_accept"] / 1e3, 1),
-        "rd_accept_sample": round((2 * valid_rows - leaf_rows) * cfg.V * 4 / kernels_us["rd_accept_sample"] / 1e3, 1),
-    }
-
-    # ---- the machine's floor for the dominant kernel: a plain streaming read of the same number of bytes,
-    # launched back to back over rotating buffers, best of a few workgroup counts
-    floor = None
-    if not args.no_floor:
-        nbytes = int(attn_bytes_mean) // 16 * 16
-        slab = torch.empty((R, nbytes), dtype=torch.uint8, device="cuda").fill_(1)
-        best = None
-        for wgs in (256, 512, 1024, 2048):
-            with torch.cuda.stream(stream):
-                for r in range(R):
-                    rd.rd_debug_stream_read(slab[r], wgs)
-                gf = None
-                if use_graph:                           # like the attention launches: R of them per replay
-                    gf = torch.cuda.CUDAGraph()
-                    with torch.cuda.graph(gf, stream=stream):
-                        for r in range(R):
-                            rd.rd_debug_stream_read(slab[r], wgs)
-                    gf.replay()
-                f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                reps = max(1, 660 // R)
-                f0.record(stream)
-                for _ in range(reps):
-                    if gf is not None:
-                        gf.replay()
-                    else:
-                        for r in range(R):
-                            rd.rd_debug_stream_read(slab[r], wgs)
-                f1.record(stream)
-            torch.cuda.synchronize()
-            us = f0.elapsed_time(f1) * 1e3 / (reps * R)
-            if best is None or us < best[0]:
-                best = (us, wgs)
-        del slab
-        floor = {"us_per_launch": round(best[0], 3), "workgroups": best[1], "bytes": nbytes,
-                 "GB/s": round(nbytes / best[0] / 1e3, 1), "launch": "hip_graph_replay" if use_graph else "eager"}
-
+    floor = None if args.no_floor else stream_read_floor(wl, stream, use_graph)
     draft = None if args.no_draft else time_draft(rd, cfg, stream, max(4, min(40, args.steps // 10)), torch)
 
     result = {
@@ -362,15 +399,14 @@ def main():
         "dtype": cfg.dtype,
         "data": "synthetic",
         "config": {
-            "workload": "%s: B=%d ctx=%s H=%d D=%d %s KV, W=%d L=%d V=%d" % (
-                cfg.name, cfg.B, cfg.ctx_lo if cfg.ctx_lo == cfg.ctx_hi else "U{%d..%d}" % (cfg.ctx_lo, cfg.ctx_hi),
-                cfg.H, cfg.D, cfg.dtype, cfg.W, cfg.L, cfg.V),
+            "workload": wl.describe(),
             "rotating_copies": R,
-            "launch": "hip_graph_replay" if use_graph else "eager",
+            "launch": launch,
+            "graph_segments": [[p, c] for p, c, _ in steps_rot.plan(args.warmup, args.steps)][-2:],
             "step": "rd_dedup + rd_tree_attn + rd_accept",
         },
-        "packed_tokens_per_sec": round(packed_mean * steps_per_s, 1),
-        "packed_tokens_per_step": round(packed_mean, 2),
+        "packed_tokens_per_sec": round(wl.packed * steps_per_s, 1),
+        "packed_tokens_per_step": round(wl.packed, 2),
         "wall_ms_timed_region": round(wall_ms, 3),
         "kernels_us": kernels_us,
         "rd_tree_attn_us_spread": attn_spread,
@@ -388,16 +424,78 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
-            "traffic": MEASURED_TRAFFIC_BYTES.get(args.config),
-            "algorithmic_bytes_per_launch": round(attn_bytes_mean, 1),
+            "traffic": traffic.get(args.config),
+            "algorithmic_bytes_per_launch": round(wl.attn_bytes, 1),
             "us_per_launch": round(attn_us, 3),
+            "launch": launch,
             "stream_read_floor": floor,
         },
     }
 
+    if not args.no_configs:
+        block = {}
+        for idx in sorted(synth.CONFIGS):
+            if idx == args.config:
+                e = {"workload": wl.describe(), "rotating_copies": R, "rd_tree_attn_us": attn_spread,
+                     "algorithmic_bytes_per_launch": round(wl.attn_bytes, 1),
+                     "GB/s": round(wl.attn_bytes / attn_spread["median"] / 1e3, 1),
+                     "frac": round(wl.attn_bytes / attn_spread["median"] / 1e3 / HBM_PEAK_GBS, 4),
+                     "traffic": traffic.get(idx), "step_us": round(step_us, 3), "steps_per_sec": round(steps_per_s, 1),
+                     "packed_tokens_per_step": round(wl.packed, 2),
+                     "rd_dedup_us": kernels_us["rd_dedup"], "rd_accept_us": kernels_us["rd_accept"]}
+                if floor:
+                    e["stream_read_floor_us"], e["stream_read_floor_GB/s"] = floor["us_per_launch"], floor["GB/s"]
+                block[str(idx)] = e
+                continue
+            c2 = synth.CONFIGS[idx]
+            w2 = Workload(c2, copies_for(c2, 0), rd, synth, torch)
+            block[str(idx)] = config_entry(w2, stream, use_graph, flush, traffic, not args.no_floor,
+                                           0.0 if args.no_cpu_baseline else min(3.0, args.cpu_seconds / 2), synth)
+            del w2
+            torch.cuda.empty_cache()
+        result["configs"] = block
+
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, synth, args.cpu_seconds)
+        if "configs" in result:
+            result["configs"][str(args.config)]["oracle_steps_per_sec"] = result["cpu_baseline"]["value"]
+            result["configs"][str(args.config)]["oracle_sample"] = result["cpu_baseline"]["sample"]
     print(json.dumps(result), flush=True)
+
+
+def extras(wl, stream, use_graph, kernels_us, kernels_gbs, valid_rows, torch):
+    """Kernels beside the step, one by one (reported beside the headline figures, not part of them)."""
+    cfg, rd = wl.cfg, wl.rd
+    # rd_commit (what follows the step, Sec. 3.4) appends the accepted rows behind position
+    # ctx_len - L here, because the synthetic caches are allocated full.
+    for c in wl.copies:
+        c["ctx_commit"] = (c["ctx_len"] - cfg.L).clamp_(min=0)
+        c["ctx_out"] = torch.empty_like(c["ctx_len"])
+        c["n_comm"] = torch.empty_like(c["ctx_len"])
+    ws_samp = rd.new_workspace(rd.rd_accept_sample_workspace(cfg.B, cfg.W, cfg.L, cfg.V), "cuda")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(cfg.seed + 2)
+    for c in wl.copies:                                  # sampling-mode acceptance: draft logits near the LLM's, uniform draws
+        c["draft_logits"] = c["logits"] + torch.randn(c["logits"].shape, generator=gen, device="cuda")
+        c["u_accept"] = torch.rand((cfg.B, cfg.N), generator=gen, device="cuda")
+        c["u_next"] = torch.rand((cfg.B,), generator=gen, device="cuda")
+        c["sample"] = rd.rd_accept_sample(c["logits"], c["draft_logits"], c["beams"], c["dedup"]["unpack_index"],
+                                          c["dedup"]["n_packed"], c["u_accept"], c["u_next"], 1.0, workspace=ws_samp)
+
+    def k_sample(c):
+        rd.rd_accept_sample(c["logits"], c["draft_logits"], c["beams"], c["dedup"]["unpack_index"], c["dedup"]["n_packed"],
+                            c["u_accept"], c["u_next"], 1.0, out=c["sample"], workspace=ws_samp)
+
+    def k_commit(c):
+        rd.rd_commit(c["k_new"], c["v_new"], c["accept"]["accepted_idx"], c["accept"]["best_len"], c["ctx_commit"],
+                     c["k_cache"], c["v_cache"], ctx_len_out=c["ctx_out"], n_committed=c["n_comm"])
+
+    kernels_us["rd_commit"] = Rotation(wl, k_commit, stream, use_graph).spread(target_ms=4.0)["median"]
+    kernels_us["rd_accept_sample"] = Rotation(wl, k_sample, stream, use_graph).spread(target_ms=5.0)["median"]
+    # rd_accept_sample reads the valid logit rows and the draft rows of slots that are not at the last position
+    leaf_rows = float(np.mean([sum(len(set(u[:, -1].tolist())) for u in c["dedup"]["unpack_index"].cpu().numpy())
+                               for c in wl.copies]))
+    kernels_gbs["rd_accept_sample"] = round((2 * valid_rows - leaf_rows) * cfg.V * 4 / kernels_us["rd_accept_sample"] / 1e3, 1)
 
 
 def time_draft(rd, cfg, stream, n, torch):
@@ -438,30 +536,9 @@ def time_draft(rd, cfg, stream, n, torch):
     wbytes = (L - 1) * (K * G * G + V * G) * 2 + max(L - 2, 0) * 2 * Dm * Dm * 2
     gbs = wbytes / us / 1e3
     return {"us_per_call": round(us, 1), "config": "Dm=%d V=%d K=%d B=%d W=%d L=%d" % (Dm, V, K, B, W, L),
-            "weights": "bf16, operand-tiled by rd_draft_pack_weights",
+            "weights": "bf16, operand-tiled by rd_draft_pack_weights", "launch": "eager",
             "weight_bytes_streamed": wbytes, "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS,
             "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4)}
-
-
-def cpu_baseline(cfg, synth, budget_s):
-    """The CPU oracle as it stands, timed on this host on whole steps of the same workload."""
-    import oracle                               # baseline leg only; the timed GPU path never touches it
-    cpu_cfg = cfg
-    t = synth.make_attn_inputs(cpu_cfg, poison=False)
-    scale = float(1.0 / np.sqrt(cpu_cfg.D))
-    d = oracle.dedup(t["beams"], t["ctx_len"])
-    logits = synth.make_logits(cpu_cfg.B, cpu_cfg.N, cpu_cfg.V, cpu_cfg.seed, d["packed_tokens"], d["parent"],
-                               d["n_packed"], cpu_cfg.p_plant)
-    reps, t0 = 0, time.perf_counter()
-    while True:
-        oracle.verify_step(t["beams"], t["ctx_len"], t["q"], t["k_cache"], t["v_cache"], t["k_new"], t["v_new"],
-                           logits, cpu_cfg.dtype, scale)
-        reps += 1
-        el = time.perf_counter() - t0
-        if el >= budget_s or (reps >= 3 and el >= 0.5 * budget_s):
-            break
-    return {"value": round(reps / el, 4), "unit": "steps/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": "%d whole steps of the same workload (%s), %.1f s" % (reps, cpu_cfg.name, el)}
 
 
 if __name__ == "__main__":

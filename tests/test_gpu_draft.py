@@ -37,9 +37,14 @@ def dev_params(p):
 
 
 def check(rd, p, h, last, W, L, what):
-    ref = oracle.draft(p, h, last, W, L)
     got = rd.rd_draft(dev_params(p), dev(h), dev(last), W, L)
     torch.cuda.synchronize()
+    return validate(p, h, last, W, L, got, what)
+
+
+def validate(p, h, last, W, L, got, what):
+    """Checks one rd_draft result (device tensors, already complete) against the oracle."""
+    ref = oracle.draft(p, h, last, W, L)
     gb, gl = host(got["beams"]), host(got["beam_logp"])
     B = h.shape[0]
     V = p["emb"].shape[0]
@@ -112,6 +117,29 @@ def test_draft_matches_oracle(rd, Dm, V, K, B, W, L):
     last = rng.integers(0, V, B).astype(np.int32)
     frac = check(rd, p, h, last, W, L, "draft")
     assert frac >= 0.5                                   # random models: swaps are the exception
+
+
+def test_draft_workspace_reused_by_different_inputs_back_to_back(rd):
+    """Four different inputs through ONE workspace back to back with no synchronisation in between, at
+    a shape whose layers split K over several workgroups per column group (partial tiles and arrival
+    counters in the workspace); a partial or counter left by the previous call would show."""
+    Dm, V, K, B, W, L = 512, 1200, 1, 5, 8, 4
+    announce(f"draft stale-workspace check Dm={Dm} V={V} K={K} B={B} W={W} L={L}")
+    p = make_params(V, Dm, K, seed=Dm + V, scale=4.0)
+    pd = dev_params(p)
+    ws = torch.empty(rd.rd_draft_workspace(B, W, L, Dm, V), dtype=torch.uint8, device="cuda")
+    ins, outs = [], []
+    for i in range(4):
+        rng = np.random.default_rng(900 + i)
+        h = synth.f32_to_bf16_bits(rng.standard_normal((B, Dm)).astype(np.float32))
+        last = rng.integers(0, V, B).astype(np.int32)
+        ins.append((h, last, dev(h), dev(last)))
+    torch.cuda.synchronize()
+    for h, last, hd, ld in ins:
+        outs.append(rd.rd_draft(pd, hd, ld, W, L, workspace=ws))
+    torch.cuda.synchronize()
+    for i, ((h, last, hd, ld), got) in enumerate(zip(ins, outs)):
+        validate(p, h, last, W, L, got, "draft reuse #%d" % i)
 
 
 def test_draft_uniform_model_tie_rule(rd):
