@@ -70,16 +70,6 @@ const char *rd_strerror(int code);
 int rd_version(void);
 
 /*
- * rd_debug_stream_read — calibration aid, not part of the method: one launch in which `workgroups`
- * workgroups of 256 threads read `bytes` bytes at `src` (device memory, 16-byte aligned; a trailing
- * part of less than 16 bytes is ignored) once, as contiguous slabs with 16-byte loads, and discard
- * them.  Timing it over the bytes an rd_tree_attn launch has to read gives the machine's floor for
- * that launch, which the benchmark reports beside the kernel's own time.  `sink`: device word that
- * is written only if the folded data happens to equal one magic value, or NULL.
- */
-int rd_debug_stream_read(const void *src, size_t bytes, int workgroups, uint32_t *sink, void *stream);
-
-/*
  * rd_dedup — dedup_prefix + pack_beam + tree structure (Sec. 3.3, App. A.1).
  *
  *   prefix_tree[b][i][j]  smallest candidate index k whose first j+1 tokens equal

@@ -421,7 +421,7 @@ void orc_accept(const int32_t *beams, const int32_t *unpack_index, const int32_t
  *     ctx_len_out[b] = ctx_len[b] + n,   n_committed[b] = n
  *     hidden_last[b,:] = hidden[b, accepted_idx[b][best_len[b]-1], :]  if best_len[b] > 0
  * Rows are copied bit for bit (no arithmetic).  best_len is clamped to [0, L], ctx_len
- * to [0, Cmax] and slots to [0, N-1], as the device code does for out-of-range data.
+ * to [0, Cmax] and slots to [0, N-1]: the interface defines the step for out-of-range data this way.
  * n_committed, hidden / hidden_last may be NULL.                                   */
 void orc_commit(const void *k_new, const void *v_new, const int32_t *accepted_idx,
                 const int32_t *best_len, const int32_t *ctx_len,

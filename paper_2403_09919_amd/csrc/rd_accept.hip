@@ -39,7 +39,7 @@ struct AccPlan {
 AccPlan acc_plan(int B, int N, int V)
 {
     AccPlan p;
-    static const int loads_env = [] { const char *v = getenv("RD_ACCEPT_LOADS"); return (v && *v) ? atoi(v) : 0; }();
+    static const int loads_env = rd::env_int("RD_ACCEPT_LOADS", 0);      // tuning builds only
     int loads = ((long long)B * N >= 512) ? 8 : 4;
     if (loads_env == 1 || loads_env == 2 || loads_env == 4 || loads_env == 8 || loads_env == 16 || loads_env == 32) loads = loads_env;
     while ((V + 1024 * loads - 1) / (1024 * loads) > kMaxChunks) loads *= 2;     // huge vocabularies: the kernel loops
@@ -62,18 +62,24 @@ __device__ __forceinline__ bool better(float v, int i, float bv, int bi)
 
 // Order-preserving 64-bit key of (value, index): larger value first, then smaller index.
 // Every key of a real element is greater than 0, the cleared state of the workspace.
+// -0.0 and +0.0 are one value to the comparison that defines the arg max, so both get +0.0's key.
 __device__ __forceinline__ unsigned long long encode_key(float v, int i)
 {
-    const uint32_t u = __float_as_uint(v);
+    const uint32_t u = (v == 0.0f) ? 0u : __float_as_uint(v);
     const uint32_t mono = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
     return ((unsigned long long)mono << 32) | (uint32_t)~(uint32_t)i;
 }
 __device__ __forceinline__ int key_index(unsigned long long k) { return (int)~(uint32_t)k; }
 
 // Device-scope arrival: true for the thread whose increment brought the counter to `expected`.
+// The thread's earlier device-scope atomics (the row key's max, a lower-level counter) and stores must
+// have been performed before the counter moves: they go to other addresses and could otherwise
+// complete after it, and the workgroup that sees the full count would read a key that lacks this
+// workgroup's chunk.  wait_dev_stores() waits for their acknowledgement.
 __device__ __forceinline__ bool arrive(uint32_t *counter, uint32_t expected)
 {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");          // own atomics and stores acknowledged
+    rd::wait_dev_stores();
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     const uint32_t prev = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
     return prev + 1u == expected;

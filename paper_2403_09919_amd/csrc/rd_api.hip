@@ -1,5 +1,6 @@
 // Status strings and version of the rd library, and a plain streaming read for calibration.
 #include "rd_internal.h"
+#include "rd_debug.h"
 
 extern "C" const char *rd_strerror(int code)
 {

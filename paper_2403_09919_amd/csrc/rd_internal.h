@@ -37,11 +37,17 @@ static inline int rd_check_beam_shape(int B, int W, int L)
 
 namespace rd {
 
-// Integer environment override for tuning sweeps (unset or empty: the default).
+// Integer environment override for tuning sweeps (unset or empty: the default).  Only builds made
+// with -DRD_TUNING read the environment; in the product library every plan is fixed by its arguments.
 static inline int env_int(const char *name, int dflt)
 {
+#ifdef RD_TUNING
     const char *v = getenv(name);
     return (v && *v) ? atoi(v) : dflt;
+#else
+    (void)name;
+    return dflt;
+#endif
 }
 
 // Raising a kernel's dynamic LDS limit is per kernel and per device; `done` (one per kernel) keeps
@@ -86,15 +92,18 @@ __device__ __forceinline__ float2 ld_dev2(const float *p)
     return make_float2(__uint_as_float((unsigned)u), __uint_as_float((unsigned)(u >> 32)));
 }
 
-// 16-byte device-scope store (write-through); the caller must call wait_dev_stores() before it
-// signals completion, because the compiler does not count this store as outstanding.
+// 16 bytes as two 8-byte device-scope stores (write-through).  Both are ordinary atomic stores the
+// compiler sees, so it inserts whatever wait states the data registers need before they are reused.
 __device__ __forceinline__ void st_dev4(float *p, float a, float b, float c, float d)
 {
-    typedef __attribute__((ext_vector_type(4))) float f32x4_t;
-    const f32x4_t v = {a, b, c, d};
-    // the leading s_nop covers register-write hazards the compiler cannot see into the asm for
-    asm volatile("s_nop 4\n\tglobal_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
+    st_dev2(p, a, b);
+    st_dev2(p + 2, c, d);
 }
+// Returns once every vector memory operation this wave has issued -- loads, stores and atomics without
+// a return value alike, they share one counter -- has been acknowledged.  A device-scope store or atomic
+// is acknowledged when it has been performed past the XCD's L2, where every other XCD can see it.  This
+// is the release half of the exchange; a release FENCE at device scope would also write back the whole
+// L2, which is what the exchange avoids.
 __device__ __forceinline__ void wait_dev_stores() { asm volatile("s_waitcnt vmcnt(0)" : : : "memory"); }
 
 }  // namespace rd

@@ -30,7 +30,7 @@ def _declared_symbols():
 
 def test_header_symbols_exported(lib):
     names = _declared_symbols()
-    assert names == sorted(["rd_strerror", "rd_version", "rd_debug_stream_read", "rd_dedup", "rd_tree_attn_workspace",
+    assert names == sorted(["rd_strerror", "rd_version", "rd_dedup", "rd_tree_attn_workspace",
                             "rd_tree_attn", "rd_tree_attn_paged_workspace", "rd_tree_attn_paged",
                             "rd_accept_workspace", "rd_accept", "rd_accept_sample_workspace", "rd_accept_sample", "rd_commit", "rd_commit_paged", "rd_rope",
                             "rd_draft_workspace", "rd_draft", "rd_draft_packed_elems", "rd_draft_pack_weights"])
@@ -38,7 +38,10 @@ def test_header_symbols_exported(lib):
     for n in names:
         assert hasattr(raw, n), n
     from paper_2403_09919_amd import binding
-    assert sorted(binding.EXPORTS) == names
+    # the binding also reaches the calibration entry point, which is declared in the library's own
+    # csrc/rd_debug.h, not in the public header
+    assert sorted(set(binding.EXPORTS) - {"rd_debug_stream_read"}) == names
+    assert hasattr(raw, "rd_debug_stream_read")
 
 
 def test_version_and_strerror(lib):

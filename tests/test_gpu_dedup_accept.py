@@ -123,6 +123,23 @@ def test_accept_vocab_sizes_and_ties(rd, V):
     check_accept(rd, logits, beams, np.array([beams[0, 0, 0], -5, beams[2, 1, 0]], np.int32))
 
 
+def test_accept_signed_zeros_across_chunks(rd):
+    """-0.0 and +0.0 are equal to the comparison that defines the arg max, so the smallest index
+    among them wins even when the -0.0 sits in an earlier chunk of the row than the +0.0."""
+    announce("accept signed zeros across chunks")
+    B, W, L, V = 2, 4, 3, 32000
+    beams = synth.make_beams(B, W, L, 5, 11)
+    rng = np.random.default_rng(11)
+    logits = -np.abs(rng.standard_normal((B, W * L, V)).astype(np.float32)) - 0.5     # everything below zero
+    logits[0, 0, 100] = -0.0;  logits[0, 0, 20000] = 0.0        # -0.0 first, +0.0 in a later chunk -> 100
+    logits[0, 1, 100] = 0.0;   logits[0, 1, 20000] = -0.0       # the other way round -> 100
+    logits[1, 0, 31999] = -0.0; logits[1, 0, 5000] = -0.0; logits[1, 0, 9000] = 0.0    # -> 5000
+    logits[1, 1, 3] = -0.0                                      # a lone -0.0 is the maximum -> 3
+    check_accept(rd, logits, beams, None)                       # GPU == oracle, bit for bit
+    am = oracle.argmax(logits, oracle.dedup(beams)["n_packed"])
+    assert am[0, 0] == 100 and am[0, 1] == 100 and am[1, 0] == 5000 and am[1, 1] == 3
+
+
 def test_accept_shapes_and_workspace_reuse(rd):
     announce("accept shapes + one workspace reused by successive calls of the same shape")
     up = lambda x: (x + 255) // 256 * 256
