@@ -57,7 +57,8 @@ typedef enum {
     RD_ERR_INVALID_ARG = -1, /* NULL required pointer, size <= 0, bad alignment */
     RD_ERR_UNSUPPORTED = -2, /* size or dtype outside the limits above */
     RD_ERR_WORKSPACE = -3,   /* workspace NULL or smaller than rd_*_workspace() */
-    RD_ERR_HIP = -4          /* a kernel launch failed (hipGetLastError) */
+    RD_ERR_HIP = -4,         /* a kernel launch failed (hipGetLastError) */
+    RD_ERR_SCRATCH_LIMIT = -5 /* rd_accept_static: the sizes need more than the library's static scratch array */
 } rd_status;
 
 #define RD_MAX_W 128
@@ -182,6 +183,29 @@ int rd_accept(const float *logits, const int32_t *beams, const int32_t *unpack_i
               int32_t *argmax_out, int32_t *n_accept, int32_t *best_beam,
               int32_t *best_len, int32_t *next_token, int32_t *accepted_idx,
               void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * rd_accept_static — rd_accept for callers that cannot allocate device memory or pass a workspace:
+ * code running under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, outputs and kernel as rd_accept, minus the workspace: the counters and row keys live in
+ * a device array inside the library, RD_ACCEPT_STATIC_BYTES (1 MiB) per GPU, held by every GPU the
+ * library runs on until the process ends.  The call allocates nothing and frees nothing (on a GPU's
+ * first call it looks up the array's address once) and enqueues two kernels on `stream`: one that
+ * clears the part of the array the call uses, then rd_accept's.
+ *
+ * Sizes with rd_accept_workspace(B, W, L, V) > RD_ACCEPT_STATIC_BYTES (about B*W*L > 87000 packed rows)
+ * are rejected with RD_ERR_SCRATCH_LIMIT before anything is launched; the other argument errors are
+ * rd_accept's.  All calls on one GPU share that GPU's array: calls that may overlap on one GPU (two
+ * streams, two threads) race and must be serialised by the caller, or use rd_accept with separate
+ * workspaces.
+ */
+#define RD_ACCEPT_STATIC_BYTES (1 << 20)
+
+int rd_accept_static(const float *logits, const int32_t *beams, const int32_t *unpack_index,
+                     const int32_t *n_packed, const int32_t *root_token,
+                     int B, int W, int L, int V,
+                     int32_t *argmax_out, int32_t *n_accept, int32_t *best_beam,
+                     int32_t *best_len, int32_t *next_token, int32_t *accepted_idx, void *stream);
 
 /*
  * rd_accept_sample — acceptance by rejection sampling, the selection mode Sec. 3.4 names for

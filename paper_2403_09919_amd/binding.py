@@ -39,6 +39,7 @@ EXPORTS = {
     "rd_tree_attn_paged": (_i, [_vp] * 4 + [_i, _i, _i] + [_vp] * 5 + [_i, _i, _i, _i, _i, _f, _vp, _vp, _sz, _vp]),
     "rd_accept_workspace": (_sz, [_i, _i, _i, _i]),
     "rd_accept": (_i, [_vp] * 5 + [_i, _i, _i, _i] + [_vp] * 6 + [_vp, _sz, _vp]),
+    "rd_accept_static": (_i, [_vp] * 5 + [_i, _i, _i, _i] + [_vp] * 6 + [_vp]),
     "rd_accept_sample_workspace": (_sz, [_i, _i, _i, _i]),
     "rd_accept_sample": (_i, [_vp] * 3 + [_i] + [_vp] * 6 + [_f, _i, _i, _i, _i] + [_vp] * 5 + [_vp, _sz, _vp]),
     "rd_commit": (_i, [_vp] * 5 + [_i] * 7 + [_vp] * 4 + [_vp, _i, _vp, _vp]),
@@ -248,6 +249,25 @@ def rd_accept(logits, beams, unpack_index, n_packed, root_token: Optional[torch.
         _ptr(out["accepted_idx"], i32, (B, L), "accepted_idx"),
         _ptr(workspace, torch.uint8, None, "workspace"), workspace.numel(), _stream())
     _check(code, "rd_accept")
+    return out
+
+
+def rd_accept_static(logits, beams, unpack_index, n_packed, out: dict, root_token: Optional[torch.Tensor] = None) -> dict:
+    """rd_accept without a workspace and without any allocation (see include/rd.h, rd_accept_static):
+    the caller passes every output tensor in `out`."""
+    B, W, L = beams.shape
+    N = W * L
+    V = logits.shape[2]
+    i32 = torch.int32
+    code = _lib.rd_accept_static(
+        _ptr(logits, torch.float32, (B, N, V), "logits"), _ptr(beams, i32, (B, W, L), "beams"),
+        _ptr(unpack_index, i32, (B, W, L), "unpack_index"), _ptr(n_packed, i32, (B,), "n_packed"),
+        _ptr(root_token, i32, (B,), "root_token"), B, W, L, V,
+        _ptr(out["argmax"], i32, (B, N), "argmax"), _ptr(out["n_accept"], i32, (B, W), "n_accept"),
+        _ptr(out["best_beam"], i32, (B,), "best_beam"), _ptr(out["best_len"], i32, (B,), "best_len"),
+        _ptr(out["next_token"], i32, (B,), "next_token"),
+        _ptr(out["accepted_idx"], i32, (B, L), "accepted_idx"), _stream())
+    _check(code, "rd_accept_static")
     return out
 
 

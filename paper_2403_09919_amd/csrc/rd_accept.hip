@@ -248,12 +248,11 @@ extern "C" size_t rd_accept_workspace(int B, int W, int L, int V)
     return acc_plan(B, W * L, V).total_bytes;
 }
 
-extern "C" int rd_accept(const float *logits, const int32_t *beams, const int32_t *unpack_index,
-                         const int32_t *n_packed, const int32_t *root_token,
-                         int B, int W, int L, int V,
-                         int32_t *argmax_out, int32_t *n_accept, int32_t *best_beam,
-                         int32_t *best_len, int32_t *next_token, int32_t *accepted_idx,
-                         void *workspace, size_t workspace_bytes, void *stream)
+// Argument checks shared by the two entry points; *plan is filled on success.
+static int accept_check(const float *logits, const int32_t *beams, const int32_t *unpack_index,
+                        const int32_t *n_packed, int B, int W, int L, int V,
+                        const int32_t *argmax_out, const int32_t *n_accept, const int32_t *best_beam,
+                        const int32_t *best_len, const int32_t *next_token, const int32_t *accepted_idx, AccPlan *plan)
 {
     const int st = rd_check_beam_shape(B, W, L);
     if (st != RD_OK) return st;
@@ -263,16 +262,23 @@ extern "C" int rd_accept(const float *logits, const int32_t *beams, const int32_
         !best_len || !next_token || !accepted_idx)
         return RD_ERR_INVALID_ARG;
     if (!rd_aligned(logits, 16)) return RD_ERR_INVALID_ARG;
+    *plan = acc_plan(B, W * L, V);
+    return RD_OK;
+}
+
+// Enqueues the kernel on a zeroed workspace of plan.total_bytes at `ws`.
+static int accept_launch(const AccPlan &plan, const float *logits, const int32_t *beams, const int32_t *unpack_index,
+                         const int32_t *n_packed, const int32_t *root_token, int B, int W, int L, int V,
+                         int32_t *argmax_out, int32_t *n_accept, int32_t *best_beam, int32_t *best_len,
+                         int32_t *next_token, int32_t *accepted_idx, unsigned char *ws, hipStream_t stream)
+{
     const int N = W * L;
-    const AccPlan plan = acc_plan(B, N, V);
-    if (!workspace || !rd_aligned(workspace, 256) || workspace_bytes < plan.total_bytes) return RD_ERR_WORKSPACE;
-    unsigned char *ws = static_cast<unsigned char *>(workspace);
     const dim3 grid(plan.chunks, N, B), block(kAccThreads);
     uint32_t *seq_counters = reinterpret_cast<uint32_t *>(ws);
     uint32_t *row_counters = reinterpret_cast<uint32_t *>(ws + plan.row_counters_off);
     unsigned long long *row_keys = reinterpret_cast<unsigned long long *>(ws + plan.keys_off);
 #define RD_ACCEPT_LAUNCH(U)                                                                                   \
-    hipLaunchKernelGGL(rd_accept_kernel<U>, grid, block, 0, (hipStream_t)stream, logits, beams, unpack_index,   \
+    hipLaunchKernelGGL(rd_accept_kernel<U>, grid, block, 0, stream, logits, beams, unpack_index,               \
                        n_packed, root_token, W, L, V, plan.chunks, plan.chunk_len, argmax_out, n_accept,       \
                        best_beam, best_len, next_token, accepted_idx, seq_counters, row_counters, row_keys)
     switch (plan.loads) {
@@ -285,4 +291,85 @@ extern "C" int rd_accept(const float *logits, const int32_t *beams, const int32_
     }
 #undef RD_ACCEPT_LAUNCH
     return rd_check_launch();
+}
+
+extern "C" int rd_accept(const float *logits, const int32_t *beams, const int32_t *unpack_index,
+                         const int32_t *n_packed, const int32_t *root_token,
+                         int B, int W, int L, int V,
+                         int32_t *argmax_out, int32_t *n_accept, int32_t *best_beam,
+                         int32_t *best_len, int32_t *next_token, int32_t *accepted_idx,
+                         void *workspace, size_t workspace_bytes, void *stream)
+{
+    AccPlan plan;
+    const int st = accept_check(logits, beams, unpack_index, n_packed, B, W, L, V, argmax_out, n_accept, best_beam,
+                                best_len, next_token, accepted_idx, &plan);
+    if (st != RD_OK) return st;
+    if (!workspace || !rd_aligned(workspace, 256) || workspace_bytes < plan.total_bytes) return RD_ERR_WORKSPACE;
+    return accept_launch(plan, logits, beams, unpack_index, n_packed, root_token, B, W, L, V, argmax_out, n_accept,
+                         best_beam, best_len, next_token, accepted_idx, static_cast<unsigned char *>(workspace),
+                         (hipStream_t)stream);
+}
+
+// ---- rd_accept_static: the same call for callers that cannot allocate ---------------------------
+// The counters and row keys live in a file-scope device array instead of a caller-provided
+// workspace.  Every device that loads the library holds its own copy of the array at its own
+// address until the process ends; the address is looked up once per device, with that device
+// current, and only that address (never the array's name, which in host code is a stand-in and
+// not a device address) is handed to kernels.
+static __device__ __align__(256) unsigned char scratch[RD_ACCEPT_STATIC_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::atomic<unsigned char *> g_scratch_ptr[kMaxDevices];     // device address of `scratch`, per device, once known
+
+int static_scratch(unsigned char **out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return RD_ERR_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return RD_ERR_UNSUPPORTED;
+    unsigned char *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        void *sym = nullptr;
+        if (hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)) != hipSuccess || sym == nullptr) return RD_ERR_HIP;
+        p = static_cast<unsigned char *>(sym);
+        g_scratch_ptr[dev].store(p, std::memory_order_release);     // two threads racing here store the same address
+    }
+    *out = p;
+    return RD_OK;
+}
+
+// Zeroes n_vec 16-byte vectors.  A kernel rather than a memset so that the call stays safe to
+// capture into a HIP graph.
+__global__ __launch_bounds__(256) void rd_clear_kernel(uint4 *p, size_t n_vec)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n_vec) p[i] = make_uint4(0, 0, 0, 0);
+}
+
+}  // namespace
+
+extern "C" int rd_accept_static(const float *logits, const int32_t *beams, const int32_t *unpack_index,
+                                const int32_t *n_packed, const int32_t *root_token,
+                                int B, int W, int L, int V,
+                                int32_t *argmax_out, int32_t *n_accept, int32_t *best_beam,
+                                int32_t *best_len, int32_t *next_token, int32_t *accepted_idx, void *stream)
+{
+    AccPlan plan;
+    const int st = accept_check(logits, beams, unpack_index, n_packed, B, W, L, V, argmax_out, n_accept, best_beam,
+                                best_len, next_token, accepted_idx, &plan);
+    if (st != RD_OK) return st;
+    if (plan.total_bytes > (size_t)RD_ACCEPT_STATIC_BYTES) return RD_ERR_SCRATCH_LIMIT;
+    unsigned char *ws = nullptr;
+    const int sp = static_scratch(&ws);
+    if (sp != RD_OK) return sp;
+    // The array keeps whatever the last call on this device left (normally zeros, but a call that was
+    // aborted, or one of another shape that failed, may leave anything): clear the part this call uses.
+    const size_t n_vec = plan.total_bytes / 16;                     // every section is a multiple of 256 bytes
+    hipLaunchKernelGGL(rd_clear_kernel, dim3((unsigned)((n_vec + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                       reinterpret_cast<uint4 *>(ws), n_vec);
+    const int cl = rd_check_launch();
+    if (cl != RD_OK) return cl;
+    return accept_launch(plan, logits, beams, unpack_index, n_packed, root_token, B, W, L, V, argmax_out, n_accept,
+                         best_beam, best_len, next_token, accepted_idx, ws, (hipStream_t)stream);
 }

@@ -10,6 +10,7 @@ extern "C" const char *rd_strerror(int code)
     case RD_ERR_UNSUPPORTED: return "unsupported size or dtype (limits: W <= 128, W*L <= 384, D in {64,128})";
     case RD_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case RD_ERR_HIP: return "HIP kernel launch failed";
+    case RD_ERR_SCRATCH_LIMIT: return "sizes need more than the library's static scratch array (use the entry point that takes a workspace)";
     default: return "unknown rd status";
     }
 }

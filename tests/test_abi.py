@@ -32,7 +32,7 @@ def test_header_symbols_exported(lib):
     names = _declared_symbols()
     assert names == sorted(["rd_strerror", "rd_version", "rd_dedup", "rd_tree_attn_workspace",
                             "rd_tree_attn", "rd_tree_attn_paged_workspace", "rd_tree_attn_paged",
-                            "rd_accept_workspace", "rd_accept", "rd_accept_sample_workspace", "rd_accept_sample", "rd_commit", "rd_commit_paged", "rd_rope",
+                            "rd_accept_workspace", "rd_accept", "rd_accept_static", "rd_accept_sample_workspace", "rd_accept_sample", "rd_commit", "rd_commit_paged", "rd_rope",
                             "rd_draft_workspace", "rd_draft", "rd_draft_packed_elems", "rd_draft_pack_weights"])
     raw = ctypes.CDLL(LIB)
     for n in names:
@@ -47,11 +47,11 @@ def test_header_symbols_exported(lib):
 def test_version_and_strerror(lib):
     assert lib.rd_version() >= 100
     seen = set()
-    for code in (0, -1, -2, -3, -4, -99):
+    for code in (0, -1, -2, -3, -4, -5, -99):
         s = lib.rd_strerror(code)
         assert s and len(s) > 1
         seen.add(s)
-    assert len(seen) == 6
+    assert len(seen) == 7
 
 
 def _dedup(lib, B, W, L, beams=FAKE, req=FAKE, mask=FAKE, bits=FAKE):
@@ -123,6 +123,23 @@ def test_stream_read_argument_errors(lib):
     assert lib.rd_debug_stream_read(FAKE, 8, 4, None, None) == INVALID
     assert lib.rd_debug_stream_read(FAKE, 1024, 0, None, None) == INVALID
     assert lib.rd_debug_stream_read(FAKE + 4, 1024, 4, None, None) == INVALID
+
+
+def test_accept_static_argument_errors(lib):
+    """The entry point without a workspace rejects what rd_accept rejects, and sizes beyond its static
+    scratch array, all before anything is launched (the pointers here are not device memory)."""
+    def call(B=1, W=4, L=4, V=100, logits=FAKE, req=FAKE):
+        return lib.rd_accept_static(logits, FAKE, FAKE, FAKE, None, B, W, L, V, req, req, req, req, req, req, None)
+    assert call(B=0) == INVALID
+    assert call(V=0) == INVALID
+    assert call(W=129, L=1) == UNSUPPORTED
+    assert call(logits=None) == INVALID
+    assert call(logits=FAKE + 4) == INVALID
+    assert call(req=None) == INVALID
+    SCRATCH_LIMIT = -5
+    assert lib.rd_accept_workspace(300, 128, 3, 1000) > (1 << 20)
+    assert call(B=300, W=128, L=3, V=1000) == SCRATCH_LIMIT
+    assert b"static scratch" in lib.rd_strerror(SCRATCH_LIMIT)
 
 
 def test_accept_argument_errors(lib):
