@@ -249,9 +249,33 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
         const int k = a.xcd_remap ? (int)(blockIdx.x >> 3) : (int)blockIdx.x;
         const int heads_here = a.xcd_remap ? (a.B * a.H) >> 3 : a.B * a.H;    // heads served by this XCD
         const int per_head = a.S * n_rg;
-        const int n_ctx = heads_here * per_head;
         const int n_tree = heads_here * n_rg * tree_wgs;
         int hl;
+        if (a.rg_major) {
+            // Two row groups: the second one (rows past the first group's) has no real rows for most
+            // beams, and the dispatcher does not refill promptly the slots that such short workgroups
+            // free, so everything of group 0 comes first: [ctx rg0][tree rg0][ctx rg1][tree rg1][mergers].
+            const int half_ctx = heads_here * a.S, half_tree = heads_here * tree_wgs, half = half_ctx + half_tree;
+            if (k < 2 * half) {
+                rg = k >= half ? 1 : 0;
+                const int r = k - rg * half;
+                if (r < half_ctx) {
+                    hl = r / a.S;
+                    split = r - hl * a.S;
+                } else {
+                    hl = r - half_ctx;
+                    split = a.S;
+                }
+            } else {
+                const int r = k - 2 * half;
+                hl = r / (2 * pure);
+                const int rr = r - hl * (2 * pure);
+                rg = rr / pure;
+                merger = tree_wgs + (rr - rg * pure);
+                split = -1;
+            }
+        } else {
+        const int n_ctx = heads_here * per_head;
         if (k < n_ctx) {
             hl = k / per_head;
             const int r = k - hl * per_head;
@@ -270,6 +294,7 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
             merger = tree_wgs + (rr - rg * pure);
             split = -1;
         }
+        }
         bh = a.xcd_remap ? hl * 8 + xcd : hl;
     }
     const int b = bh / a.H;
@@ -283,6 +308,10 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
     const unsigned char *Vc = static_cast<const unsigned char *>(a.v_cache) + (PAGED ? 0 : (size_t)bh * a.Cmax * G::kRowBytes);
     const unsigned char *Kn = static_cast<const unsigned char *>(a.k_new) + (size_t)bh * a.N * G::kRowBytes;
     const unsigned char *Vn = static_cast<const unsigned char *>(a.v_new) + (size_t)bh * a.N * G::kRowBytes;
+
+    // A row group beyond the first whose rows are all padding has nothing to do -- no loads, no
+    // partial, no arrival, no merge: the first group's workgroup zeroes its rows of the output (below).
+    if (rg > 0 && clampi(a.n_packed[b], 0, a.N) <= row0) return;
 
     constexpr size_t kPF = (size_t)(D / 16) * NQ * kFragFloats;     // floats per partial
     const size_t unit = (size_t)bh * n_rg + rg;                    // (head, row group): one merge each
@@ -387,14 +416,19 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
     };
     // Dense cache: the first block is fetched on the assumption that context block `split` exists
     // (true whenever this workgroup has a context block at all); the others fetch packed-key block 0.
-    const bool spec_ctx = !PAGED && split < a.S && (long long)split * kBlock < (long long)a.Cmax;
-    if (!PAGED) {
+    // Only the first row group does this: a later group often has no real rows at all and must not
+    // pull a block of K and V through the chip for nothing, so it looks at n_packed first.
+    const bool spec = !PAGED && rg == 0;
+    const bool spec_ctx = spec && split < a.S && (long long)split * kBlock < (long long)a.Cmax;
+    if (spec) {
         load_tile(spec_ctx ? Kc : Kn, spec_ctx ? split * kBlock : 0, spec_ctx ? a.Cmax : a.N, kreg);
         load_tile(spec_ctx ? Vc : Vn, spec_ctx ? split * kBlock : 0, spec_ctx ? a.Cmax : a.N, vreg);
     }
 
+    RD_TR(13);
     const int C = clampi(a.ctx_len[b], 0, a.Cmax);
     const int P_all = clampi(a.n_packed[b], 0, a.N);
+    if (C + P_all >= 0) RD_TR(14);
     // P of this group's rows are real.  A packed row p sees no packed key beyond itself (the mask is
     // lower triangular), so the group needs the packed keys [0, tree_end) only.
     const int P = clampi(P_all - row0, 0, kRows);
@@ -412,17 +446,19 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
     const int k_first = split * kBlock;
 
     int pid_next = 0;         // page of this wave's tile in the block after the current one (paged context only)
-    if (PAGED) {              // first block; a workgroup with no block at all reads (and ignores) the first row of Q
+    if (!spec) {              // first block; a workgroup with no block at all reads (and ignores) the first row of Q
         const bool ctx = nA > 0;
-        if (ctx) {
+        if (PAGED && ctx) {
             const int t0 = ctx_tile_first(k_first, C);
             const int pid = page_of(t0);
             load_tile_paged(Kc, pid, t0, C, kreg);
             load_tile_paged(Vc, pid, t0, C, vreg);
             if (nA > 1) pid_next = page_of(ctx_tile_first(k_first + k_stride, C));
         } else {
-            load_tile(nb == 0 ? Qb : Kn, 0, nb == 0 ? 1 : tree_end, kreg);
-            load_tile(nb == 0 ? Qb : Vn, 0, nb == 0 ? 1 : tree_end, vreg);
+            const unsigned char *kb = nb == 0 ? Qb : (ctx ? Kc : Kn);
+            const unsigned char *vb = nb == 0 ? Qb : (ctx ? Vc : Vn);
+            load_tile(kb, ctx ? k_first : 0, nb == 0 ? 1 : (ctx ? C : tree_end), kreg);
+            load_tile(vb, ctx ? k_first : 0, nb == 0 ? 1 : (ctx ? C : tree_end), vreg);
         }
     } else if (nb > 0 && nA == 0 && spec_ctx) {
         // the assumed context block does not exist (a short context): the packed keys come first after all
@@ -431,11 +467,18 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
     }
 
     // Rows of the output beyond the packed count are zero; with several workgroups per head the one
-    // of the first key range writes them now, off everybody's critical path.
-    if (n_part > 1 && split == 0) {
+    // of the first key range writes them now, off everybody's critical path.  The first group's also
+    // zeroes the rows of every later group that has no real row (those groups' workgroups have left).
+    if (split == 0) {
         unsigned char *ob = static_cast<unsigned char *>(a.out) + ((size_t)bh * a.N + row0) * G::kRowBytes;
-        for (int idx = P * G::kChunks + tid; idx < Ng * G::kChunks; idx += kThreads)
-            *reinterpret_cast<uint4 *>(ob + (size_t)idx * 16) = make_uint4(0, 0, 0, 0);
+        if (n_part > 1)
+            for (int idx = P * G::kChunks + tid; idx < Ng * G::kChunks; idx += kThreads)
+                *reinterpret_cast<uint4 *>(ob + (size_t)idx * 16) = make_uint4(0, 0, 0, 0);
+        if (n_rg > 1 && rg == 0) {
+            const int first_empty = max(kRows, (P_all + kRows - 1) / kRows * kRows);     // first row of the first empty group
+            for (int idx = first_empty * G::kChunks + tid; idx < a.N * G::kChunks; idx += kThreads)
+                *reinterpret_cast<uint4 *>(ob + (size_t)idx * 16) = make_uint4(0, 0, 0, 0);
+        }
     }
 
     // Visibility of this wave's packed keys (used in the packed-key blocks only).  Of a tile's 32
@@ -520,7 +563,7 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
     // The block loop is instantiated twice: for all row tiles, and for the lower half when the
     // packed rows fit there (a padded tile costs as much as a real one, and branches around it
     // would stop the compiler from overlapping LDS reads with the matrix instructions); the
-    // five-tile kernel, whose full loop is short of registers, has a third for four tiles.
+    // four-tile kernel has a third for three tiles.
     auto block_loop = [&](auto nqa_tag) __attribute__((always_inline)) {
         constexpr int NQA = decltype(nqa_tag)::value;
         for (int ib = 0; ib < nb; ++ib) {
@@ -711,7 +754,7 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
     };
     constexpr int kHalf = (NQ + 1) / 2;
     if (NQ > 1 && nqt <= kHalf) block_loop(std::integral_constant<int, kHalf>{});
-    else if (NQ == 5 && nqt == 4) block_loop(std::integral_constant<int, NQ == 5 ? 4 : NQ>{});   // five tiles spill; four do not
+    else if (NQ == 4 && nqt == 3) block_loop(std::integral_constant<int, NQ == 4 ? 3 : NQ>{});
     else block_loop(std::integral_constant<int, NQ>{});
     RD_TR(3);
 
@@ -776,6 +819,27 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
     RD_TR(4);
     wait_dev_stores();                                             // this wave's partial stores are acknowledged
     __syncthreads();                                               // ... and so are every wave's
+    if (n_merge == 0) {
+        // Large launches (many units merging at the same time anyway): no merge workgroups; the
+        // workgroup whose arrival completes the count merges the unit by itself.
+        if (tid == 0) {
+            const unsigned long long x = xcc_id();
+            const unsigned long long add = 1ull | (x << 16) | ((x * x) << 32);
+            const unsigned long long v = __hip_atomic_fetch_add(words, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + add;
+            const unsigned long long n = v & 0xffffull;
+            const bool same = ((v >> 16) & 0xffffull) == n * x && (v >> 32) == n * x * x;
+            s_state = n == (unsigned long long)n_part ? (same ? 1u : 2u) : 0u;
+        }
+        __syncthreads();                                           // the partial loads stay behind the arrival
+        RD_TR(5);
+        if (s_state == 0) return;
+        RD_TR(11);
+        T *outp = static_cast<T *>(a.out) + ((size_t)bh * a.N + row0) * D;
+        merge_fragments<T, D, NQ>(hp, n_part, kPF, P, nqt, wave, NW, lane, s_state == 1, outp);
+        if (tid == 0) __hip_atomic_store(words, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);    // ready for the next call
+        RD_TR(6);
+        return;
+    }
     if (tid == 0) {
         const unsigned long long x = xcc_id();
         __hip_atomic_fetch_add(words, 1ull | (x << 16) | ((x * x) << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -801,8 +865,8 @@ static int launch_mfma(const AttnArgs &a, hipStream_t stream)
                                       configured);
     if (st != RD_OK) return st;
     const int n_part = a.S + (a.fuse_tree ? 0 : 1);
-    const int pure = n_part > 1 ? a.mergers - (a.fuse_tree ? 0 : 1) : 0;      // merge workgroups that do nothing else
-    if (n_part > 1 && (a.mergers < 1 || a.mergers > kMaxMergers || pure < 0 || (a.fuse_tree && pure < 1))) return RD_ERR_INVALID_ARG;
+    const int pure = (n_part > 1 && a.mergers > 0) ? a.mergers - (a.fuse_tree ? 0 : 1) : 0;      // merge workgroups that do nothing else
+    if (a.mergers < 0 || a.mergers > kMaxMergers) return RD_ERR_INVALID_ARG;
     const size_t wgs = (size_t)a.B * a.H * a.n_rg * (size_t)(n_part + pure);
     if (wgs > 0x7fffffffull) return RD_ERR_UNSUPPORTED;
     const unsigned grid = (unsigned)wgs;
@@ -810,7 +874,7 @@ static int launch_mfma(const AttnArgs &a, hipStream_t stream)
     return rd_check_launch();
 }
 
-// rg_tiles = 16-row tiles per workgroup (the template's NQ); D = 128 kernels exist for 1..5 tiles,
+// rg_tiles = 16-row tiles per workgroup (the template's NQ); D = 128 kernels exist for 1..4 tiles,
 // D = 64 kernels for 1..8 (the plan never asks for more).  Beams with more packed keys than one
 // block (N > 32*NW) only occur with row groups, i.e. with kGroupTiles tiles.
 template <typename T, int D, int NW, bool PAGED>
@@ -831,11 +895,11 @@ static int dispatch_nq(const AttnArgs &a, int rg_tiles, hipStream_t stream)
     case 2: return launch_mfma<T, D, 2, NW, 1, PAGED>(a, stream);
     case 3: return launch_mfma<T, D, 3, NW, 1, PAGED>(a, stream);
     case 4: return launch_mfma<T, D, 4, NW, 1, PAGED>(a, stream);
-    case 5: return launch_mfma<T, D, 5, NW, 1, PAGED>(a, stream);
     default: break;
     }
     if constexpr (D == 64) {
         switch (rg_tiles) {
+        case 5: return launch_mfma<T, 64, 5, NW, 1, PAGED>(a, stream);
         case 6: return launch_mfma<T, 64, 6, NW, 1, PAGED>(a, stream);
         case 7: return launch_mfma<T, 64, 7, NW, 1, PAGED>(a, stream);
         case 8: return launch_mfma<T, 64, 8, NW, 1, PAGED>(a, stream);
