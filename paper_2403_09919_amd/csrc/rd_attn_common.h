@@ -26,7 +26,6 @@ struct AttnPlan {
     int rows_pad;      // packed rows padded to a multiple of 16 (fp32 kernel's partial layout)
     int rg_tiles;      // bf16 kernel: 16-row tiles of packed rows per workgroup (a row group)
     int n_rg;          // bf16 kernel: row groups per (sequence, head); 1 unless N is large
-    int mergers;       // bf16 kernel: workgroups per (head, row group) that merge the partials (0: one workgroup per head, nothing to merge)
     size_t counters_bytes;
     size_t partial_floats;   // floats per partial: m[rows_pad] + l[rows_pad] + O[rows_pad][D]
     size_t total_bytes;
@@ -53,12 +52,12 @@ static inline AttnPlan attn_plan(int B, int H, int N, int D, int Cmax, size_t el
     if (waves_env == 4 || (waves_env == 8 && elem_bytes == 2 && D == 128)) p.waves = waves_env;
     const int block_keys = elem_bytes == 2 ? 32 * p.waves : kBlockKeys;
     const int nblk = (Cmax + block_keys - 1) / block_keys;
-    // Packed rows per workgroup: all of them while they fit the register budget without scratch
-    // memory (4 row tiles at D = 128, 8 at D = 64); wider beams are cut into row groups of 3 (4) tiles,
-    // each a workgroup of its own per key range (K/V are then re-read per group, from L2 mostly).
+    // Packed rows per workgroup: all of them while they fit the register budget (5 row tiles at
+    // D = 128, 8 at D = 64); wider beams are cut into row groups of 3 (4) tiles, each a workgroup
+    // of its own per key range (K/V are then re-read per group, from L2 mostly).
     const int nq_all = (N + 15) / 16;
     static const int tiles_env = env_int("RD_ATTN_ROWTILES", 0);       // tuning: largest single group
-    int nq_max = D == 128 ? 4 : 8;
+    int nq_max = D == 128 ? 5 : 8;
     const int nq_grp = D == 128 ? 3 : 4;
     if (tiles_env >= nq_grp && tiles_env <= nq_max) nq_max = tiles_env;
     const int nq = elem_bytes == 2 ? (nq_all <= nq_max ? nq_all : nq_grp) : nq_all;
@@ -92,27 +91,10 @@ static inline AttnPlan attn_plan(int B, int H, int N, int D, int Cmax, size_t el
     p.rows_pad = (N + 15) / 16 * 16;
     p.rg_tiles = nq;
     p.n_rg = n_rg;
-    // 16-bit kernels: the packed-key workgroup (if the head has one) and enough further merge workgroups
-    // that a wave merges about two of the (d-tile, row tile) fragments
-    // Small launches: the packed-key workgroup (if the head has one) and enough further merge workgroups
-    // that a wave merges about two of the (d-tile, row tile) fragments.  Large launches: none (the last
-    // workgroup of a unit to arrive merges it; hundreds of units do so at the same time anyway, and extra
-    // short workgroups at the end of a large grid cost more than they save).
-    p.mergers = 0;
-    if (elem_bytes == 2 && p.n_part > 1) {
-        const int nfrag = (D / 16) * nq;
-        static const int mergers_env = env_int("RD_ATTN_MERGERS", -1);
-        int m = BH >= 512 ? 0 : (nfrag + 2 * p.waves - 1) / (2 * p.waves);
-        if (mergers_env >= 0) m = mergers_env;
-        p.mergers = m > 4 ? 4 : m;
-        if (p.mergers > 0 && p.fuse_tree == 0 && p.mergers < 1) p.mergers = 1;
-    }
-    // two 64-bit words per (head, row group): arrivals, mergers done
-    p.counters_bytes = ((size_t)BH * n_rg * 2 * sizeof(unsigned long long) + 255) / 256 * 256;
+    p.counters_bytes = ((size_t)BH * n_rg * sizeof(unsigned long long) + 255) / 256 * 256;
     // floats per partial: fp32 kernel m[rows_pad] + l[rows_pad] + O[rows_pad][D] per (b,h,part);
-    // 16-bit kernels one fragment of 288 floats (a 16 x 16 accumulator tile and 16 (m, l) pairs) per
-    // d-tile and row tile of one group, per (b,h,group,part)
-    p.partial_floats = elem_bytes == 2 ? (size_t)nq * (D / 16) * 288 : (size_t)p.rows_pad * (2 + D);
+    // bf16 kernel the same for the rows of one group, per (b,h,group,part)
+    p.partial_floats = elem_bytes == 2 ? (size_t)nq * 16 * (2 + D) : (size_t)p.rows_pad * (2 + D);
     p.total_bytes = p.counters_bytes +
                     (p.n_part > 1 ? (size_t)BH * n_rg * p.n_part * p.partial_floats * sizeof(float) : 0);
     return p;
@@ -129,8 +111,6 @@ struct AttnArgs {
     float *partials;
     int B, H, N, Cmax, S, words, rows_pad;
     int n_rg;      // row groups per (sequence, head) (bf16 kernel; each is NQ*16 rows of the template)
-    int mergers;   // merge workgroups per (head, row group), the packed-key workgroup included (16-bit kernels)
-    int rg_major;  // 1: two row groups, launched one after the other instead of side by side
     int fuse_tree; // 1: packed keys walked by the workgroup of the last context range (see AttnPlan)
     int xcd_remap; // 1: workgroup i serves XCD i%8's share of the heads (needs B*H % 8 == 0)
     float scale_log2e;

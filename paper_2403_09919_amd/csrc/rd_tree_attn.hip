@@ -51,8 +51,6 @@ extern "C" int rd_tree_attn(const void *q, const void *k_cache, const void *v_ca
     a.xcd_remap = (((long long)B * H) % 8 == 0) ? 1 : 0;
     a.fuse_tree = plan.fuse_tree;
     a.n_rg = plan.n_rg;
-    a.mergers = plan.mergers;
-    a.rg_major = (plan.n_rg == 2 && rd::env_int("RD_ATTN_RGMAJOR", 1)) ? 1 : 0;
     a.block_table = nullptr; a.page_size = 0; a.max_pages = 0; a.n_pages = 0;
     if (dt == RD_BF16) return rd::tree_attn_bf16(a, D, plan.waves, plan.rg_tiles, (hipStream_t)stream);
     if (dt == RD_F16) return rd::tree_attn_f16(a, D, plan.waves, plan.rg_tiles, (hipStream_t)stream);
@@ -104,7 +102,5 @@ extern "C" int rd_tree_attn_paged(const void *q, const void *k_pages, const void
     a.xcd_remap = (((long long)B * H) % 8 == 0) ? 1 : 0;
     a.fuse_tree = plan.fuse_tree;
     a.n_rg = plan.n_rg;
-    a.mergers = plan.mergers;
-    a.rg_major = (plan.n_rg == 2 && rd::env_int("RD_ATTN_RGMAJOR", 1)) ? 1 : 0;
     return rd::tree_attn_paged(a, D, plan.waves, plan.rg_tiles, dt == RD_F16, (hipStream_t)stream);
 }

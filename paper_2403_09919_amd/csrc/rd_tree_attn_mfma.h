@@ -88,117 +88,6 @@ __device__ __forceinline__ float quad_sum(float x)
     return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
-// ---- exchange of partial softmax states between the workgroups of one (head, row group) -----------
-// A partial is a sequence of fragments, one per (output d-tile dt, row tile qt), each kFragFloats
-// floats: the 16 x 16 accumulator tile exactly as the 64 lanes of a wave hold it (lane * 4 floats,
-// 1 KB), followed by the (running maximum, sum) pairs of the tile's 16 rows (128 B).  A fragment is
-// written by one wave and merged by one wave with 1 KB wave-wide accesses.
-//
-// Who merges: the workgroups of a unit that come LAST in launch order -- the packed-key workgroup,
-// if the unit has one, and a few more that do nothing else ("merge workgroups").  Each takes a share
-// of the unit's fragments, so the read of the partials is spread over several compute units instead
-// of one.  They wait for the unit's arrival word to show that every key range has stored its partial.
-// That wait cannot deadlock: workgroups are handed to an XCD's compute units in index order, so by
-// the time a merge workgroup runs, every workgroup before it in the grid -- all key-range
-// workgroups included -- has been started and finishes without waiting for anyone.  The wait is
-// bounded all the same (kSpinLimit polls), so that every wave exits whatever happens.
-//
-// Ordering (release / acquire through the arrival word):
-//   writer:  partial stores (device scope, write-through) -> s_waitcnt vmcnt(0): all of them
-//            acknowledged -> workgroup barrier -> one thread adds to the arrival word (device-scope atomic);
-//   merger:  one thread polls the arrival word with device-scope loads until the count is complete ->
-//            workgroup barrier -> loads of the partials.  These loads are plain (cached) ones if every
-//            writer ran on the merger's own XCD -- their write-through stores updated this XCD's L2 on
-//            the way, a compute unit's L1 is invalid at kernel start and nothing has touched these lines
-//            since -- and device-scope loads, which go past the L2, otherwise.
-// The arrival word collects, beside the count (bits 0-15), the sum (bits 16-31) and the sum of squares
-// (bits 32-63) of the writers' XCD numbers: n values all equal x exactly if their sum is n*x and their
-// sum of squares n*x*x.  A second word counts the mergers that are done; the last one clears both.
-constexpr int kFragFloats = 256 + 32;
-constexpr int kSpinLimit = 1 << 17;       // polls of the arrival word before a merge workgroup gives up
-constexpr int kMaxMergers = 4;            // merge workgroups per unit, the packed-key workgroup included
-
-// Merges fragments f = first, first + step, ... (f = dt * nqt + qt) of the n_part partials at `hp`
-// (stride pf floats) and writes rows < P of `outp` ([N][D] of this head, row 0 = the row group's
-// first).  Run by whole waves, two fragments at a time so that all their loads are in flight together.
-template <typename T, int D, int NQ>
-__device__ __forceinline__ void merge_fragments(const float *hp, int n_part, size_t pf, int P, int nqt, int first, int step,
-                                                int lane, bool cached, T *outp)
-{
-    constexpr int kChunk = 9;                 // partials loaded together (one round trip when they are few)
-    const int r16 = lane & 15, g = lane >> 4;
-    const int nfrag = (D / 16) * nqt;
-#pragma unroll 1
-    for (int f0 = first; f0 < nfrag; f0 += 2 * step) {
-        float M[2], den[2];
-        f32x4 acc[2];
-        bool valid[2];
-        const float *fp[2];
-        int dt[2], qt[2];
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int f = f0 + u * step;
-            const int ff = f < nfrag ? f : f0;
-            dt[u] = ff / nqt;
-            qt[u] = ff - dt[u] * nqt;
-            valid[u] = f < nfrag && qt[u] * 16 + r16 < P;             // lanes whose row is padding neither load nor store
-            fp[u] = hp + (size_t)(dt[u] * NQ + qt[u]) * kFragFloats;
-            M[u] = -INFINITY;
-            den[u] = 0.f;
-            acc[u] = f32x4{0.f, 0.f, 0.f, 0.f};
-        }
-#pragma unroll 1
-        for (int s0 = 0; s0 < n_part; s0 += kChunk) {
-            float2 ml[2][kChunk];
-            f32x4 fr[2][kChunk];
-#pragma unroll
-            for (int u = 0; u < 2; ++u)
-#pragma unroll
-                for (int c = 0; c < kChunk; ++c) {
-                    ml[u][c] = make_float2(-INFINITY, 0.f);           // absent: weight 2^-inf = 0
-                    fr[u][c] = f32x4{0.f, 0.f, 0.f, 0.f};
-                    if (s0 + c < n_part && valid[u]) {
-                        const float *ps = fp[u] + (size_t)(s0 + c) * pf;
-                        if (cached) {
-                            fr[u][c] = *reinterpret_cast<const f32x4 *>(ps + lane * 4);
-                            ml[u][c] = *reinterpret_cast<const float2 *>(ps + 256 + 2 * r16);
-                        } else {
-                            const float2 lo = ld_dev2(ps + lane * 4), hi = ld_dev2(ps + lane * 4 + 2);
-                            fr[u][c] = f32x4{lo.x, lo.y, hi.x, hi.y};
-                            ml[u][c] = ld_dev2(ps + 256 + 2 * r16);
-                        }
-                    }
-                }
-            if (f0 == first && s0 == 0) RD_TR(12);
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                float Mn = M[u];
-#pragma unroll
-                for (int c = 0; c < kChunk; ++c) Mn = fmaxf(Mn, ml[u][c].x);
-                const float Ms = (Mn == -INFINITY) ? 0.f : Mn;
-                const float resc = __builtin_amdgcn_exp2f(M[u] - Ms);
-                den[u] *= resc;
-                acc[u] *= resc;
-#pragma unroll
-                for (int c = 0; c < kChunk; ++c) {
-                    const float w = __builtin_amdgcn_exp2f(ml[u][c].x - Ms);     // 0 for an empty or absent range
-                    den[u] += w * ml[u][c].y;
-                    acc[u] += w * fr[u][c];
-                }
-                M[u] = Mn;
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-            if (valid[u]) {
-                const float inv = 1.0f / den[u];
-                store_out4(outp + (size_t)(qt[u] * 16 + r16) * D + dt[u] * 16 + 4 * g, acc[u][0] * inv, acc[u][1] * inv,
-                           acc[u][2] * inv, acc[u][3] * inv);
-            }
-        if (f0 == first) RD_TR(7);
-    }
-}
-
 // TB = packed-key blocks the launch can need: ceil(N / block keys).  1 for all but the widest beams;
 // the mask words of every such block are fetched up front, so the common case should not pay for three.
 // PAGED: the context keys and values live in fixed-size pages found through a block table
@@ -213,6 +102,7 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
     constexpr int kRows = NQ * 16;
     constexpr int kDTW = G::kDTiles / NW;                       // d-tiles of the output owned by a wave
     static_assert(kDTW >= 1, "more waves than output d-tiles");
+    constexpr int kPF = kRows * (2 + D);                        // floats per partial
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     unsigned char *sQ = smem;                                   // [kRows][kRowBytes]
     unsigned char *sKV = sQ + kRows * G::kRowBytes;             // NW tiles [32][kRowBytes]
@@ -238,135 +128,62 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
     const int n_part = a.S + (a.fuse_tree ? 0 : 1);
     // Work items are (head, key range, row group); the row groups of one key range are neighbours
     // in launch order so that they stream the same K/V at the same time (one reads HBM, the others L2).
-    // Behind them, per XCD: the packed-key workgroups, then the pure merge workgroups (split = -1).
     const int n_rg = a.n_rg;
-    const int tree_wgs = a.fuse_tree ? 0 : 1;
-    const int n_merge = n_part > 1 ? a.mergers : 0;              // mergers per unit, the packed-key workgroup included
-    const int pure = n_merge - (n_merge > 0 ? tree_wgs : 0);     // merge workgroups that do nothing else
-    int bh, split, rg, merger = 0;
+    int bh, split, rg;
     {
         const int xcd = a.xcd_remap ? (int)(blockIdx.x & 7) : 0;
         const int k = a.xcd_remap ? (int)(blockIdx.x >> 3) : (int)blockIdx.x;
         const int heads_here = a.xcd_remap ? (a.B * a.H) >> 3 : a.B * a.H;    // heads served by this XCD
         const int per_head = a.S * n_rg;
-        const int n_tree = heads_here * n_rg * tree_wgs;
-        int hl;
-        if (a.rg_major) {
-            // Two row groups: the second one (rows past the first group's) has no real rows for most
-            // beams, and the dispatcher does not refill promptly the slots that such short workgroups
-            // free, so everything of group 0 comes first: [ctx rg0][tree rg0][ctx rg1][tree rg1][mergers].
-            const int half_ctx = heads_here * a.S, half_tree = heads_here * tree_wgs, half = half_ctx + half_tree;
-            if (k < 2 * half) {
-                rg = k >= half ? 1 : 0;
-                const int r = k - rg * half;
-                if (r < half_ctx) {
-                    hl = r / a.S;
-                    split = r - hl * a.S;
-                } else {
-                    hl = r - half_ctx;
-                    split = a.S;
-                }
-            } else {
-                const int r = k - 2 * half;
-                hl = r / (2 * pure);
-                const int rr = r - hl * (2 * pure);
-                rg = rr / pure;
-                merger = tree_wgs + (rr - rg * pure);
-                split = -1;
-            }
-        } else {
         const int n_ctx = heads_here * per_head;
+        int hl;
         if (k < n_ctx) {
             hl = k / per_head;
             const int r = k - hl * per_head;
             split = r / n_rg;
             rg = r - split * n_rg;
-        } else if (k < n_ctx + n_tree) {
+        } else {
             const int r = k - n_ctx;
             hl = r / n_rg;
             rg = r - hl * n_rg;
             split = a.S;
-        } else {
-            const int r = k - n_ctx - n_tree;
-            hl = r / (n_rg * pure);
-            const int rr = r - hl * (n_rg * pure);
-            rg = rr / pure;
-            merger = tree_wgs + (rr - rg * pure);
-            split = -1;
-        }
         }
         bh = a.xcd_remap ? hl * 8 + xcd : hl;
     }
     const int b = bh / a.H;
-    const int head = bh - b * a.H;
-    // This workgroup's rows are row0 .. row0 + kRows - 1 of the packed rows.
+    const int C = clampi(a.ctx_len[b], 0, a.Cmax);
+    const int P_all = clampi(a.n_packed[b], 0, a.N);
+    // This workgroup's rows are row0 .. row0 + kRows - 1 of the packed rows; P of them are real.
+    // A packed row p sees no packed key beyond itself (the mask is lower triangular), so the group
+    // needs the packed keys [0, tree_end) only.
     const int row0 = rg * kRows;
-    const int Ng = min(kRows, a.N - row0);                 // rows of `out` this group owns (>= 1)
+    const int P = clampi(P_all - row0, 0, kRows);
+    const int Ng = min(kRows, a.N - row0);                 // rows of `out` this group owns
+    const int tree_end = min(P_all, row0 + kRows);
+
+    // Blocks this workgroup walks: nA blocks of context keys [k_begin, k_end), then nB blocks of
+    // packed keys [0, tree_end).  All of this is wave-uniform.  A group without real rows walks nothing.
+    int k_begin = 0, k_end = 0;
+    if (split < a.S && P > 0) ctx_range(C, a.S, split, kBlock, &k_begin, &k_end);
+    const bool has_tree = (split == a.S) || (a.fuse_tree && split == a.S - 1);
+    const int nA = (k_end - k_begin + kBlock - 1) / kBlock;
+    const int nB = (has_tree && P > 0) ? (tree_end + kBlock - 1) / kBlock : 0;
+    const int nb = nA + nB;
     const unsigned char *Qb = static_cast<const unsigned char *>(a.q) + ((size_t)bh * a.N + row0) * G::kRowBytes;
     // dense cache: this head's rows; paged cache: the page pool (the head is picked inside a page)
     const unsigned char *Kc = static_cast<const unsigned char *>(a.k_cache) + (PAGED ? 0 : (size_t)bh * a.Cmax * G::kRowBytes);
     const unsigned char *Vc = static_cast<const unsigned char *>(a.v_cache) + (PAGED ? 0 : (size_t)bh * a.Cmax * G::kRowBytes);
     const unsigned char *Kn = static_cast<const unsigned char *>(a.k_new) + (size_t)bh * a.N * G::kRowBytes;
     const unsigned char *Vn = static_cast<const unsigned char *>(a.v_new) + (size_t)bh * a.N * G::kRowBytes;
-
-    // A row group beyond the first whose rows are all padding has nothing to do -- no loads, no
-    // partial, no arrival, no merge: the first group's workgroup zeroes its rows of the output (below).
-    if (rg > 0 && clampi(a.n_packed[b], 0, a.N) <= row0) return;
-
-    constexpr size_t kPF = (size_t)(D / 16) * NQ * kFragFloats;     // floats per partial
-    const size_t unit = (size_t)bh * n_rg + rg;                    // (head, row group): one merge each
-    float *hp = a.partials + unit * n_part * kPF;
-    unsigned long long *words = a.counters + 2 * unit;             // arrival word, mergers-done word
-    __shared__ uint32_t s_state;
-    // Waits until every key range of the unit has arrived, merges this workgroup's share of the
-    // fragments, and clears the unit's words if it is the last merger to finish.
-    auto wait_and_merge = [&](int P_, int nqt_) __attribute__((always_inline)) {
-        if (tid == 0) {
-            const unsigned long long x = xcc_id();
-            unsigned long long v = 0;
-            for (int spins = 0; spins < kSpinLimit; ++spins) {
-                v = __hip_atomic_load(words, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if ((v & 0xffffull) >= (unsigned long long)n_part) break;
-                __builtin_amdgcn_s_sleep(8);
-            }
-            const unsigned long long n = v & 0xffffull;
-            s_state = (((v >> 16) & 0xffffull) == n * x && (v >> 32) == n * x * x) ? 1u : 0u;
-        }
-        __syncthreads();                                           // the partial loads stay behind the poll
-        const bool cached = s_state != 0;
-        RD_TR(11);
-        T *outp = static_cast<T *>(a.out) + ((size_t)bh * a.N + row0) * D;
-        merge_fragments<T, D, NQ>(hp, n_part, kPF, P_, nqt_, merger * NW + wave, n_merge * NW, lane, cached, outp);
-        __syncthreads();                                           // every wave has its values in registers
-        if (tid == 0) {
-            const unsigned long long prev = __hip_atomic_fetch_add(words + 1, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (prev + 1ull == (unsigned long long)n_merge) {      // last merger: leave the workspace ready for the next call
-                __hip_atomic_store(words, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(words + 1, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-        }
-        RD_TR(6);
-    };
-    if (split < 0) {                                               // a pure merge workgroup
-        const int P_m = clampi(clampi(a.n_packed[b], 0, a.N) - row0, 0, kRows);
-        wait_and_merge(P_m, (P_m + 15) >> 4);
-        return;
-    }
-
-    // ---- all first loads, issued before ctx_len[b] and n_packed[b] are known ----------------------
-    // The context blocks of a head are dealt to its S workgroups round-robin (workgroup `split` walks
-    // blocks split, split + S, ...), so the first block's address depends on nothing that has to be
-    // fetched first: Q, the mask words, K and V of the first block all leave at once, together with
-    // the two scalars that say how much of them counts.  Rows past the live context are real memory
-    // inside the tensors (their contents are excluded below: scores by the mask, values by zeroing).
+    // ---- all first loads, without branches so that the waits on them stay exact --------------------
     // Order: Q and the tree-mask words (they gate the first score tile), then K, then V.
     constexpr int kQRowsPerPass = kThreads / G::kChunks;
     constexpr int kQPasses = (kRows + kQRowsPerPass - 1) / kQRowsPerPass;
     uint4 qreg[kQPasses];
 #pragma unroll
     for (int i = 0; i < kQPasses; ++i) {
-        const int row = min(i * kQRowsPerPass + tid / G::kChunks, Ng - 1);    // rows >= P are zeroed below
-        qreg[i] = ldg16(Qb + row * G::kRowBytes + (tid % G::kChunks) * 16);
+        const int row = min(i * kQRowsPerPass + tid / G::kChunks, P - 1);    // rows >= P are zeroed below
+        qreg[i] = ldg16(Qb + max(row, 0) * G::kRowBytes + (tid % G::kChunks) * 16);
     }
     // Visibility of this wave's 32 keys, in each packed-key block, for the packed rows this lane
     // scores (row row0 + 16*qt + r16).  Context keys are visible to every row; packed keys per the
@@ -384,8 +201,9 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
     }
 
     // This wave's slice of a block: coalesced 16-byte loads into registers; a wave-wide load
-    // covers 1 KB of consecutive rows.  Rows past `end` are redirected to row end - 1, so the loads
-    // carry no predicate.
+    // covers 1 KB of consecutive rows.  Rows past the end of the range are redirected to the last
+    // valid row (their scores are masked and their probabilities are zero), so the loads carry no
+    // predicate.
     uint4 kreg[G::kLoads], vreg[G::kLoads];
     const int ld_row = lane / G::kChunks;
     const int ld_chunk = lane % G::kChunks;
@@ -400,6 +218,7 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
     // redirected to the last tile that holds a key, rows beyond the end to the tile's last valid
     // row.  The page id of the tile to prefetch is itself fetched one iteration earlier, so the
     // scalar load's latency is off the critical path.
+    const int head = bh - b * a.H;
     auto ctx_tile_first = [&](int key0, int end) __attribute__((always_inline)) {   // first key of this wave's (redirected) tile
         return min(key0 + wave * G::kTileKeys, ((end - 1) >> 5) << 5);
     };
@@ -414,70 +233,22 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
 #pragma unroll
         for (int s = 0; s < G::kLoads; ++s) reg[s] = ldg16(base + min(off0 + s * 1024u, last_off));
     };
-    // Dense cache: the first block is fetched on the assumption that context block `split` exists
-    // (true whenever this workgroup has a context block at all); the others fetch packed-key block 0.
-    // Only the first row group does this: a later group often has no real rows at all and must not
-    // pull a block of K and V through the chip for nothing, so it looks at n_packed first.
-    const bool spec = !PAGED && rg == 0;
-    const bool spec_ctx = spec && split < a.S && (long long)split * kBlock < (long long)a.Cmax;
-    if (spec) {
-        load_tile(spec_ctx ? Kc : Kn, spec_ctx ? split * kBlock : 0, spec_ctx ? a.Cmax : a.N, kreg);
-        load_tile(spec_ctx ? Vc : Vn, spec_ctx ? split * kBlock : 0, spec_ctx ? a.Cmax : a.N, vreg);
-    }
-
-    RD_TR(13);
-    const int C = clampi(a.ctx_len[b], 0, a.Cmax);
-    const int P_all = clampi(a.n_packed[b], 0, a.N);
-    if (C + P_all >= 0) RD_TR(14);
-    // P of this group's rows are real.  A packed row p sees no packed key beyond itself (the mask is
-    // lower triangular), so the group needs the packed keys [0, tree_end) only.
-    const int P = clampi(P_all - row0, 0, kRows);
-    const int tree_end = min(P_all, row0 + kRows);
-
-    // Blocks this workgroup walks: nA blocks of context keys (blocks split, split + S, ... of the
-    // live context), then nB blocks of packed keys [0, tree_end).  All of this is wave-uniform.  A
-    // group without real rows walks nothing.
-    const int nblkC = (C + kBlock - 1) / kBlock;
-    const int nA = (split < a.S && P > 0 && split < nblkC) ? (nblkC - split + a.S - 1) / a.S : 0;
-    const bool has_tree = (split == a.S) || (a.fuse_tree && split == a.S - 1);
-    const int nB = (has_tree && P > 0) ? (tree_end + kBlock - 1) / kBlock : 0;
-    const int nb = nA + nB;
-    const int k_stride = a.S * kBlock;                     // from one context block of this workgroup to its next
-    const int k_first = split * kBlock;
-
     int pid_next = 0;         // page of this wave's tile in the block after the current one (paged context only)
-    if (!spec) {              // first block; a workgroup with no block at all reads (and ignores) the first row of Q
+    {   // first block; a workgroup with no block at all reads (and ignores) the first row of Q
         const bool ctx = nA > 0;
         if (PAGED && ctx) {
-            const int t0 = ctx_tile_first(k_first, C);
+            const int t0 = ctx_tile_first(k_begin, k_end);
             const int pid = page_of(t0);
-            load_tile_paged(Kc, pid, t0, C, kreg);
-            load_tile_paged(Vc, pid, t0, C, vreg);
-            if (nA > 1) pid_next = page_of(ctx_tile_first(k_first + k_stride, C));
+            load_tile_paged(Kc, pid, t0, k_end, kreg);
+            load_tile_paged(Vc, pid, t0, k_end, vreg);
+            if (nA > 1) pid_next = page_of(ctx_tile_first(k_begin + kBlock, k_end));
         } else {
             const unsigned char *kb = nb == 0 ? Qb : (ctx ? Kc : Kn);
             const unsigned char *vb = nb == 0 ? Qb : (ctx ? Vc : Vn);
-            load_tile(kb, ctx ? k_first : 0, nb == 0 ? 1 : (ctx ? C : tree_end), kreg);
-            load_tile(vb, ctx ? k_first : 0, nb == 0 ? 1 : (ctx ? C : tree_end), vreg);
-        }
-    } else if (nb > 0 && nA == 0 && spec_ctx) {
-        // the assumed context block does not exist (a short context): the packed keys come first after all
-        load_tile(Kn, 0, tree_end, kreg);
-        load_tile(Vn, 0, tree_end, vreg);
-    }
-
-    // Rows of the output beyond the packed count are zero; with several workgroups per head the one
-    // of the first key range writes them now, off everybody's critical path.  The first group's also
-    // zeroes the rows of every later group that has no real row (those groups' workgroups have left).
-    if (split == 0) {
-        unsigned char *ob = static_cast<unsigned char *>(a.out) + ((size_t)bh * a.N + row0) * G::kRowBytes;
-        if (n_part > 1)
-            for (int idx = P * G::kChunks + tid; idx < Ng * G::kChunks; idx += kThreads)
-                *reinterpret_cast<uint4 *>(ob + (size_t)idx * 16) = make_uint4(0, 0, 0, 0);
-        if (n_rg > 1 && rg == 0) {
-            const int first_empty = max(kRows, (P_all + kRows - 1) / kRows * kRows);     // first row of the first empty group
-            for (int idx = first_empty * G::kChunks + tid; idx < a.N * G::kChunks; idx += kThreads)
-                *reinterpret_cast<uint4 *>(ob + (size_t)idx * 16) = make_uint4(0, 0, 0, 0);
+            const int key0 = ctx ? k_begin : 0;
+            const int end = nb == 0 ? 1 : (ctx ? k_end : tree_end);
+            load_tile(kb, key0, end, kreg);
+            load_tile(vb, key0, end, vreg);
         }
     }
 
@@ -563,21 +334,21 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
     // The block loop is instantiated twice: for all row tiles, and for the lower half when the
     // packed rows fit there (a padded tile costs as much as a real one, and branches around it
     // would stop the compiler from overlapping LDS reads with the matrix instructions); the
-    // four-tile kernel has a third for three tiles.
+    // five-tile kernel, whose full loop is short of registers, has a third for four tiles.
     auto block_loop = [&](auto nqa_tag) __attribute__((always_inline)) {
         constexpr int NQA = decltype(nqa_tag)::value;
         for (int ib = 0; ib < nb; ++ib) {
             // this block and the one to prefetch: tensors, first key, end of the key range.  After
             // the last block the prefetch repeats it (issued and ignored).
             const bool cur_tree = ib >= nA;
-            const int cur_key0 = cur_tree ? (ib - nA) * kBlock : k_first + ib * k_stride;
-            const int cur_end = cur_tree ? tree_end : C;
+            const int cur_key0 = cur_tree ? (ib - nA) * kBlock : k_begin + ib * kBlock;
+            const int cur_end = cur_tree ? tree_end : k_end;
             const int inext = ib + 1 < nb ? ib + 1 : ib;
             const bool next_tree = inext >= nA;
             const unsigned char *next_kb = next_tree ? Kn : Kc;
             const unsigned char *next_vb = next_tree ? Vn : Vc;
-            const int next_key0 = next_tree ? (inext - nA) * kBlock : k_first + inext * k_stride;
-            const int next_end = next_tree ? tree_end : C;
+            const int next_key0 = next_tree ? (inext - nA) * kBlock : k_begin + inext * kBlock;
+            const int next_end = next_tree ? tree_end : k_end;
             const int tile0 = cur_key0 + wave * G::kTileKeys;
             // Lane ids re-read through an opaque copy: the LDS addresses derived from them are then
             // recomputed in each iteration (one or two ALU operations) instead of being kept in
@@ -597,7 +368,7 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
                 // block after it
                 pid_cur_next = pid_next;
                 t0_next = ctx_tile_first(next_key0, next_end);
-                if (inext + 1 < nA) pid_next = page_of(ctx_tile_first(next_key0 + k_stride, next_end));
+                if (inext + 1 < nA) pid_next = page_of(ctx_tile_first(next_key0 + kBlock, next_end));
                 load_tile_paged(Kc, pid_cur_next, t0_next, next_end, kreg);
             } else {
                 load_tile(next_kb, next_key0, next_end, kreg);
@@ -670,15 +441,7 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
             lds_barrier();        // (A) tile maxima of all waves visible
             if (ib == 0) RD_TR(9);
 
-            // V registers -> own LDS tile (V swizzle), replacing K which this wave has consumed; the next
-            // block's V is requested right behind, so that it is in flight during the softmax.
-            // Rows past the end of the range may hold anything (the first block is fetched before the
-            // live context length is known): their probabilities are zero, and so must their values be.
-            if (rem < G::kTileKeys) {
-#pragma unroll
-                for (int s = 0; s < G::kLoads; ++s)
-                    if (ld_row + s * G::kRowsPerLoad >= rem) vreg[s] = make_uint4(0, 0, 0, 0);
-            }
+            // V registers -> own LDS tile (V swizzle), replacing K which this wave has consumed
 #pragma unroll
             for (int s = 0; s < G::kLoads; ++s) *reinterpret_cast<uint4 *>(my_tile + v_wr(s)) = vreg[s];
             if (PAGED && !next_tree) load_tile_paged(Vc, pid_cur_next, t0_next, next_end, vreg);
@@ -754,7 +517,7 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
     };
     constexpr int kHalf = (NQ + 1) / 2;
     if (NQ > 1 && nqt <= kHalf) block_loop(std::integral_constant<int, kHalf>{});
-    else if (NQ == 4 && nqt == 3) block_loop(std::integral_constant<int, NQ == 4 ? 3 : NQ>{});
+    else if (NQ == 5 && nqt == 4) block_loop(std::integral_constant<int, NQ == 5 ? 4 : NQ>{});   // five tiles spill; four do not
     else block_loop(std::integral_constant<int, NQ>{});
     RD_TR(3);
 
@@ -790,63 +553,149 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
     }
 
     // ---- partial state of this key range -> workspace ------------------------------------------
-    // One fragment per (d-tile, row tile): the accumulator tile as the lanes hold it, then the (m, l)
-    // pairs of its rows (see merge_fragments).  Only lanes whose row is real store.
-    float *part = hp + (size_t)split * kPF;
-    float *sL = sM;           // reuse: [kRows][NW]
+    // Layout of one partial: (m, l) pairs [kRows][2], then the output accumulators exactly as the
+    // lanes hold them, [wave][d-tile j][row tile qt][lane][4 floats], so that every wave store
+    // (and the merge's loads) covers 1 KB of contiguous memory.
+    const size_t unit = (size_t)bh * n_rg + rg;                    // (head, row group): one merge each
+    float *part = a.partials + (unit * n_part + split) * kPF;
+    const int frag_off = 2 * kRows + wave * kDTW * NQ * 256 + lane * 4;    // + (j*NQ + qt)*256
+    float *sL = sM;           // reuse: [NW waves][kRows]
 #pragma unroll
     for (int qt = 0; qt < NQ; ++qt) {
         const float l = quad_sum(l_run[qt]);
         if (g == 0) sL[(qt * 16 + r16) * NW + wave] = l;
     }
-    lds_barrier();
 #pragma unroll
     for (int qt = 0; qt < NQ; ++qt) {
-        const int qrow = qt * 16 + r16;
-        if (qrow < P) {
-            float lsum = sL[qrow * NW];
-#pragma unroll
-            for (int w = 1; w < NW; ++w) lsum += sL[qrow * NW + w];
+        if (qt * 16 + r16 < P) {                        // lanes whose row is padding neither store nor (in the merge) load
 #pragma unroll
             for (int j = 0; j < kDTW; ++j) {
                 const f32x4 o = oacc[j][qt];
-                float *fp = part + (size_t)((wave * kDTW + j) * NQ + qt) * kFragFloats;
-                st_dev4(fp + lane * 4, o[0], o[1], o[2], o[3]);
-                if (g == 0) st_dev2(fp + 256 + 2 * r16, m_run[qt], lsum);
+                st_dev4(part + frag_off + (j * NQ + qt) * 256, o[0], o[1], o[2], o[3]);
             }
         }
     }
-    RD_TR(4);
-    wait_dev_stores();                                             // this wave's partial stores are acknowledged
-    __syncthreads();                                               // ... and so are every wave's
-    if (n_merge == 0) {
-        // Large launches (many units merging at the same time anyway): no merge workgroups; the
-        // workgroup whose arrival completes the count merges the unit by itself.
-        if (tid == 0) {
-            const unsigned long long x = xcc_id();
-            const unsigned long long add = 1ull | (x << 16) | ((x * x) << 32);
-            const unsigned long long v = __hip_atomic_fetch_add(words, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + add;
-            const unsigned long long n = v & 0xffffull;
-            const bool same = ((v >> 16) & 0xffffull) == n * x && (v >> 32) == n * x * x;
-            s_state = n == (unsigned long long)n_part ? (same ? 1u : 2u) : 0u;
+    lds_barrier();
+    if (wave == 0 && g == 0) {
+#pragma unroll
+        for (int qt = 0; qt < NQ; ++qt) {
+            const int qrow = qt * 16 + r16;
+            float lsum = sL[qrow * NW];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) lsum += sL[qrow * NW + w];
+            st_dev2(part + 2 * qrow, m_run[qt], lsum);
         }
-        __syncthreads();                                           // the partial loads stay behind the arrival
-        RD_TR(5);
-        if (s_state == 0) return;
-        RD_TR(11);
-        T *outp = static_cast<T *>(a.out) + ((size_t)bh * a.N + row0) * D;
-        merge_fragments<T, D, NQ>(hp, n_part, kPF, P, nqt, wave, NW, lane, s_state == 1, outp);
-        if (tid == 0) __hip_atomic_store(words, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);    // ready for the next call
-        RD_TR(6);
-        return;
     }
-    if (tid == 0) {
-        const unsigned long long x = xcc_id();
-        __hip_atomic_fetch_add(words, 1ull | (x << 16) | ((x * x) << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
+
+    // ---- last workgroup of this (sequence, head) merges and writes the output ---------------------
+    // With the XCD-aligned mapping every producer of this head ran on this XCD, so their
+    // write-through stores also updated this XCD's L2 and plain (cached, 16-byte) loads see them.
+    RD_TR(4);
+    const int last = arrive_is_last(a.counters + unit, (uint32_t)n_part);
     RD_TR(5);
-    if (split < a.S) return;                                       // a context range: done
-    wait_and_merge(P, nqt);                                        // the packed-key workgroup is the unit's first merger
+    if (last == kNotLast) return;
+    const bool cached = (last == kLastClean);
+    RD_TR(11);
+#ifdef RD_TRACE
+    if (tid == 0 && rd_trace_buf) rd_trace_buf[(size_t)blockIdx.x * 16 + 13] = 1000 + last * 10 + xcc_id();
+#endif
+
+    // Merge: out[q] = sum_s 2^(m_s - M) O_s[q] / sum_s 2^(m_s - M) l_s[q], M = max_s m_s (log2
+    // units).  Each thread merges the accumulator fragments it would own itself, two row tiles at
+    // a time; the loads of up to kChunk partials for both are issued together, then consumed (the
+    // read of a head's partials by one compute unit is what this phase costs, so it should be a
+    // single round trip whenever the partials are few).
+    constexpr int kChunk = 6;
+    const float *hp = a.partials + unit * n_part * kPF;
+    T *outp = static_cast<T *>(a.out) + ((size_t)bh * a.N + row0) * D;
+    const int nqt_out = (Ng + 15) >> 4;
+#pragma unroll 1
+    for (int qt0 = 0; qt0 < nqt_out; qt0 += 2) {
+        float M[2], den[2];
+        f32x4 acc[2][kDTW];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            M[u] = -INFINITY;
+            den[u] = 0.f;
+#pragma unroll
+            for (int j = 0; j < kDTW; ++j) acc[u][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+        if (qt0 < nqt) {
+            const bool two = qt0 + 1 < nqt;                                     // uniform
+#pragma unroll 1
+            for (int s0 = 0; s0 < n_part; s0 += kChunk) {
+                float2 ml[2][kChunk];
+                f32x4 f[2][kChunk][kDTW];
+#pragma unroll
+                for (int c = 0; c < kChunk; ++c) {
+                    const bool have = s0 + c < n_part;                          // uniform
+                    const float *ps = hp + (size_t)(s0 + c) * kPF;
+#pragma unroll
+                    for (int u = 0; u < 2; ++u) {
+                        ml[u][c] = make_float2(-INFINITY, 0.f);                 // absent: weight 2^-inf = 0
+#pragma unroll
+                        for (int j = 0; j < kDTW; ++j) f[u][c][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+                        if (have && (u == 0 || two) && (qt0 + u) * 16 + r16 < P) {
+                            const int qt = qt0 + u;
+                            const float *pm = ps + 2 * (qt * 16 + r16);
+                            const float *pf = ps + frag_off + qt * 256;
+                            if (cached) {
+                                ml[u][c] = *reinterpret_cast<const float2 *>(pm);
+#pragma unroll
+                                for (int j = 0; j < kDTW; ++j)
+                                    f[u][c][j] = *reinterpret_cast<const f32x4 *>(pf + j * NQ * 256);
+                            } else {
+                                ml[u][c] = ld_dev2(pm);
+#pragma unroll
+                                for (int j = 0; j < kDTW; ++j) {
+                                    const float2 lo = ld_dev2(pf + j * NQ * 256);
+                                    const float2 hi = ld_dev2(pf + j * NQ * 256 + 2);
+                                    f[u][c][j] = f32x4{lo.x, lo.y, hi.x, hi.y};
+                                }
+                            }
+                        }
+                    }
+                }
+                if (qt0 == 0 && s0 == 0) RD_TR(12);
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    float Mn = M[u];
+#pragma unroll
+                    for (int c = 0; c < kChunk; ++c) Mn = fmaxf(Mn, ml[u][c].x);
+                    const float Ms = (Mn == -INFINITY) ? 0.f : Mn;
+                    const float resc = __builtin_amdgcn_exp2f(M[u] - Ms);
+                    den[u] *= resc;
+#pragma unroll
+                    for (int j = 0; j < kDTW; ++j) acc[u][j] *= resc;
+#pragma unroll
+                    for (int c = 0; c < kChunk; ++c) {
+                        const float w = __builtin_amdgcn_exp2f(ml[u][c].x - Ms);     // 0 for an empty or absent range
+                        den[u] += w * ml[u][c].y;
+#pragma unroll
+                        for (int j = 0; j < kDTW; ++j) acc[u][j] += w * f[u][c][j];
+                    }
+                    M[u] = Mn;
+                }
+            }
+        }
+        if (qt0 == 0) RD_TR(7);
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int qrow = (qt0 + u) * 16 + r16;
+            if (qrow < Ng) {
+                const bool keep = qrow < P;                               // rows beyond the packed count are zero
+                const float inv = keep ? 1.0f / den[u] : 0.f;
+#pragma unroll
+                for (int j = 0; j < kDTW; ++j) {
+                    const int d0 = (wave * kDTW + j) * 16 + 4 * g;
+                    store_out4(outp + (size_t)qrow * D + d0, keep ? acc[u][j][0] * inv : 0.f, keep ? acc[u][j][1] * inv : 0.f,
+                               keep ? acc[u][j][2] * inv : 0.f, keep ? acc[u][j][3] * inv : 0.f);
+                }
+            }
+        }
+    }
+    if (tid == 0) a.counters[unit] = 0;   // leave the workspace ready for the next call
+    RD_TR(6);
 }
 
 template <int D, int NQ, int NW>
@@ -864,17 +713,14 @@ static int launch_mfma(const AttnArgs &a, hipStream_t stream)
     const int st = ensure_dynamic_lds(reinterpret_cast<const void *>(&rd_tree_attn_mfma_kernel<T, D, NQ, NW, TB, PAGED>), smem,
                                       configured);
     if (st != RD_OK) return st;
-    const int n_part = a.S + (a.fuse_tree ? 0 : 1);
-    const int pure = (n_part > 1 && a.mergers > 0) ? a.mergers - (a.fuse_tree ? 0 : 1) : 0;      // merge workgroups that do nothing else
-    if (a.mergers < 0 || a.mergers > kMaxMergers) return RD_ERR_INVALID_ARG;
-    const size_t wgs = (size_t)a.B * a.H * a.n_rg * (size_t)(n_part + pure);
+    const size_t wgs = (size_t)a.B * a.H * (a.S + (a.fuse_tree ? 0 : 1)) * a.n_rg;
     if (wgs > 0x7fffffffull) return RD_ERR_UNSUPPORTED;
     const unsigned grid = (unsigned)wgs;
     hipLaunchKernelGGL((rd_tree_attn_mfma_kernel<T, D, NQ, NW, TB, PAGED>), dim3(grid), dim3(NW * 64), smem, stream, a);
     return rd_check_launch();
 }
 
-// rg_tiles = 16-row tiles per workgroup (the template's NQ); D = 128 kernels exist for 1..4 tiles,
+// rg_tiles = 16-row tiles per workgroup (the template's NQ); D = 128 kernels exist for 1..5 tiles,
 // D = 64 kernels for 1..8 (the plan never asks for more).  Beams with more packed keys than one
 // block (N > 32*NW) only occur with row groups, i.e. with kGroupTiles tiles.
 template <typename T, int D, int NW, bool PAGED>
@@ -895,11 +741,11 @@ static int dispatch_nq(const AttnArgs &a, int rg_tiles, hipStream_t stream)
     case 2: return launch_mfma<T, D, 2, NW, 1, PAGED>(a, stream);
     case 3: return launch_mfma<T, D, 3, NW, 1, PAGED>(a, stream);
     case 4: return launch_mfma<T, D, 4, NW, 1, PAGED>(a, stream);
+    case 5: return launch_mfma<T, D, 5, NW, 1, PAGED>(a, stream);
     default: break;
     }
     if constexpr (D == 64) {
         switch (rg_tiles) {
-        case 5: return launch_mfma<T, 64, 5, NW, 1, PAGED>(a, stream);
         case 6: return launch_mfma<T, 64, 6, NW, 1, PAGED>(a, stream);
         case 7: return launch_mfma<T, 64, 7, NW, 1, PAGED>(a, stream);
         case 8: return launch_mfma<T, 64, 8, NW, 1, PAGED>(a, stream);
