@@ -490,6 +490,31 @@ def extras(wl, stream, use_graph, kernels_us, kernels_gbs, valid_rows, torch):
         rd.rd_commit(c["k_new"], c["v_new"], c["accept"]["accepted_idx"], c["accept"]["best_len"], c["ctx_commit"],
                      c["k_cache"], c["v_cache"], ctx_len_out=c["ctx_out"], n_committed=c["n_comm"])
 
+    # rotary embedding (LLaMA-family LLMs): as a launch of its own in front of the attention, and inside it
+    max_pos = cfg.Cmax + cfg.L + 1
+    inv = 1.0 / (10000.0 ** (torch.arange(0, cfg.D // 2, device="cuda", dtype=torch.float64) / (cfg.D // 2)))
+    ang = torch.arange(max_pos, device="cuda", dtype=torch.float64)[:, None] * inv[None, :]
+    cos_t, sin_t = torch.cos(ang).float().contiguous(), torch.sin(ang).float().contiguous()
+    if cfg.dtype != "f32":
+        for c in wl.copies:
+            c["k_rot"] = torch.zeros_like(c["k_new"])
+
+        def k_rope(c):
+            rd.rd_rope(c["q"], c["k_new"], c["dedup"]["position_ids"], c["dedup"]["n_packed"], cos_t, sin_t)
+
+        def k_rope_then_attn(c):
+            k_rope(c)
+            wl.attn(c)
+
+        def k_attn_rope(c):
+            d = c["dedup"]
+            rd.rd_tree_attn_rope(c["q"], c["k_cache"], c["v_cache"], c["ctx_len"], c["k_new"], c["v_new"], d["n_packed"],
+                                 d["tree_mask_bits"], d["position_ids"], cos_t, sin_t, wl.scale, out=c["attn_out"],
+                                 k_new_rot=c["k_rot"], workspace=wl.ws_attn)
+
+        kernels_us["rd_rope"] = Rotation(wl, k_rope, stream, use_graph).spread(target_ms=4.0)["median"]
+        kernels_us["rd_rope_then_rd_tree_attn"] = Rotation(wl, k_rope_then_attn, stream, use_graph).spread(target_ms=8.0)["median"]
+        kernels_us["rd_tree_attn_rope"] = Rotation(wl, k_attn_rope, stream, use_graph).spread(target_ms=8.0)["median"]
     kernels_us["rd_commit"] = Rotation(wl, k_commit, stream, use_graph).spread(target_ms=4.0)["median"]
     kernels_us["rd_accept_sample"] = Rotation(wl, k_sample, stream, use_graph).spread(target_ms=5.0)["median"]
     # rd_accept_sample reads the valid logit rows and the draft rows of slots that are not at the last position

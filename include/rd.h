@@ -129,6 +129,30 @@ int rd_tree_attn(const void *q, const void *k_cache, const void *v_cache,
                  void *out, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * rd_tree_attn_rope — rd_tree_attn with the rotary position embedding of the packed candidates applied
+ * inside the call instead of by a separate rd_rope launch (the paper's LLMs, Vicuna, Sec. 4, are
+ * LLaMA-family models whose attention rotates queries and keys; a packed token sits at position
+ * ctx_len + depth, rd_dedup's position_ids).  q and k_new arrive UNROTATED; the context keys in k_cache
+ * are rotated already, as such a model's cache holds them.  The result equals rd_rope on (q, k_new)
+ * followed by rd_tree_attn, bit for bit: the rotation uses rd_rope's arithmetic and rounds to the
+ * storage type before the scores.
+ *
+ *   position_ids : int32 [B,N];  cos_tab, sin_tab : float [max_pos, D/2];  positions are clamped to
+ *   [0, max_pos-1] (all as for rd_rope).
+ *   k_new_rot : [B,H,N,D] of the element type, or NULL: receives the rotated rows p < n_packed[b] of
+ *   k_new (what rd_commit has to append to the cache); rows beyond are left untouched.  Must not be
+ *   k_new or q themselves (workgroups still read the unrotated rows while others write).
+ *   dt = RD_BF16 or RD_F16.  Everything else, the workspace included (rd_tree_attn_workspace), as for
+ *   rd_tree_attn.
+ */
+int rd_tree_attn_rope(const void *q, const void *k_cache, const void *v_cache,
+                      const int32_t *ctx_len, const void *k_new, const void *v_new,
+                      const int32_t *n_packed, const uint64_t *tree_mask_bits,
+                      const int32_t *position_ids, const float *cos_tab, const float *sin_tab, int max_pos,
+                      int B, int H, int N, int D, int Cmax, rd_dtype dt, float scale,
+                      void *out, void *k_new_rot, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * rd_tree_attn_paged — rd_tree_attn with the context keys and values held in fixed-size pages, the
  * cache layout of serving systems built on paged attention (the production inference framework
  * the paper reports on in Sec. 4.1 and its acknowledgements is one).  Same computation and outputs as rd_tree_attn.

@@ -35,6 +35,7 @@ EXPORTS = {
     "rd_dedup": (_i, [_vp, _vp, _i, _i, _i] + [_vp] * 8 + [_vp]),
     "rd_tree_attn_workspace": (_sz, [_i, _i, _i, _i, _i, _i]),
     "rd_tree_attn": (_i, [_vp] * 8 + [_i, _i, _i, _i, _i, _i, _f, _vp, _vp, _sz, _vp]),
+    "rd_tree_attn_rope": (_i, [_vp] * 8 + [_vp, _vp, _vp, _i] + [_i, _i, _i, _i, _i, _i, _f, _vp, _vp, _vp, _sz, _vp]),
     "rd_tree_attn_paged_workspace": (_sz, [_i, _i, _i, _i, _i, _i, _i]),
     "rd_tree_attn_paged": (_i, [_vp] * 4 + [_i, _i, _i] + [_vp] * 5 + [_i, _i, _i, _i, _i, _f, _vp, _vp, _sz, _vp]),
     "rd_accept_workspace": (_sz, [_i, _i, _i, _i]),
@@ -176,6 +177,41 @@ def rd_tree_attn(q, k_cache, v_cache, ctx_len, k_new, v_new, n_packed, tree_mask
         _ptr(workspace, torch.uint8, None, "workspace"), workspace.numel(), _stream())
     _check(code, "rd_tree_attn")
     return out
+
+
+def rd_tree_attn_rope(q, k_cache, v_cache, ctx_len, k_new, v_new, n_packed, tree_mask_bits, position_ids,
+                      cos_tab, sin_tab, scale: float, out: Optional[torch.Tensor] = None,
+                      k_new_rot: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                      want_k_rot: bool = True):
+    """rd_tree_attn with the rotary embedding of q and k_new applied inside the call (see include/rd.h,
+    rd_tree_attn_rope); returns (out, k_new_rot)."""
+    B, H, N, D = q.shape
+    Cmax = k_cache.shape[2]
+    dt = _dt_code(q)
+    words = (N + 63) // 64
+    max_pos = cos_tab.shape[0]
+    if out is None:
+        out = torch.empty_like(q)
+    if k_new_rot is None and want_k_rot:
+        k_new_rot = torch.zeros_like(k_new)
+    if workspace is None:
+        workspace = new_workspace(rd_tree_attn_workspace(B, H, N, D, Cmax, dt), q.device)
+    code = _lib.rd_tree_attn_rope(
+        _ptr(q, q.dtype, (B, H, N, D), "q"),
+        _ptr(k_cache, q.dtype, (B, H, Cmax, D), "k_cache") if Cmax > 0 else None,
+        _ptr(v_cache, q.dtype, (B, H, Cmax, D), "v_cache") if Cmax > 0 else None,
+        _ptr(ctx_len, torch.int32, (B,), "ctx_len"),
+        _ptr(k_new, q.dtype, (B, H, N, D), "k_new"), _ptr(v_new, q.dtype, (B, H, N, D), "v_new"),
+        _ptr(n_packed, torch.int32, (B,), "n_packed"),
+        _ptr(tree_mask_bits, torch.int64, (B, N, words), "tree_mask_bits"),
+        _ptr(position_ids, torch.int32, (B, N), "position_ids"),
+        _ptr(cos_tab, torch.float32, (max_pos, D // 2), "cos_tab"), _ptr(sin_tab, torch.float32, (max_pos, D // 2), "sin_tab"),
+        max_pos, B, H, N, D, Cmax, dt, float(scale),
+        _ptr(out, q.dtype, (B, H, N, D), "out"),
+        _ptr(k_new_rot, q.dtype, (B, H, N, D), "k_new_rot") if k_new_rot is not None else None,
+        _ptr(workspace, torch.uint8, None, "workspace"), workspace.numel(), _stream())
+    _check(code, "rd_tree_attn_rope")
+    return out, k_new_rot
 
 
 def rd_tree_attn_paged_workspace(B: int, H: int, N: int, D: int, page_size: int, max_pages: int, dt: int) -> int:

@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "librd.so")
 SOURCES = ["rd_api.hip", "rd_dedup.hip", "rd_tree_attn.hip", "rd_tree_attn_bf16.hip",
-           "rd_tree_attn_f16.hip", "rd_tree_attn_paged.hip", "rd_tree_attn_f32.hip", "rd_accept.hip", "rd_accept_sample.hip", "rd_commit.hip", "rd_rope.hip", "rd_draft.hip"]
+           "rd_tree_attn_f16.hip", "rd_tree_attn_paged.hip", "rd_tree_attn_rope_bf16.hip", "rd_tree_attn_rope_f16.hip", "rd_tree_attn_f32.hip", "rd_accept.hip", "rd_accept_sample.hip", "rd_commit.hip", "rd_rope.hip", "rd_draft.hip"]
 # -packed-fp32-ops is switched off for device code on purpose (hipcc's host pass does not
 # know the feature and says so; that message is filtered below).
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

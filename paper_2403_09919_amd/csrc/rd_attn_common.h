@@ -114,6 +114,11 @@ struct AttnArgs {
     int fuse_tree; // 1: packed keys walked by the workgroup of the last context range (see AttnPlan)
     int xcd_remap; // 1: workgroup i serves XCD i%8's share of the heads (needs B*H % 8 == 0)
     float scale_log2e;
+    // rotary embedding fused into the call (rd_tree_attn_rope); unused (null) otherwise
+    const int32_t *position_ids;   // [B, N]
+    const float *cos_tab, *sin_tab;   // [max_pos, D/2]
+    int max_pos;
+    void *k_rot;                   // [B,H,N,D] rotated packed keys (output), or null
 };
 
 __device__ __forceinline__ int clampi(int x, int lo, int hi) { return x < lo ? lo : (x > hi ? hi : x); }

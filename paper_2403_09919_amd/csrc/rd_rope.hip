@@ -51,10 +51,15 @@ __global__ __launch_bounds__(kRopeThreads) void rd_rope_kernel(
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const float a = (float)lo[i], bb = (float)hi[i];
-            // each product is rounded to fp32 before the sum (no fused multiply-add), so the result
-            // is the same whatever the compiler contracts
-            ylo[i] = (T)__fsub_rn(__fmul_rn(a, cs[i]), __fmul_rn(bb, sn[i]));
-            yhi[i] = (T)__fadd_rn(__fmul_rn(bb, cs[i]), __fmul_rn(a, sn[i]));
+            // each product is rounded to fp32 before the sum (no fused multiply-add), and the sum is
+            // an fp32 value before it is rounded to the storage type: the empty asm keeps the compiler
+            // from folding the sum into a mixed-precision instruction that rounds it to fp16 directly
+            // (v_fma_mixlo_f16), which differs from this definition in rare double-rounding cases
+            float rlo = __fsub_rn(__fmul_rn(a, cs[i]), __fmul_rn(bb, sn[i]));
+            float rhi = __fadd_rn(__fmul_rn(bb, cs[i]), __fmul_rn(a, sn[i]));
+            asm volatile("" : "+v"(rlo), "+v"(rhi));
+            ylo[i] = (T)rlo;
+            yhi[i] = (T)rhi;
         }
         *reinterpret_cast<vec8 *>(x + off) = ylo;
         *reinterpret_cast<vec8 *>(x + off + kHalf) = yhi;

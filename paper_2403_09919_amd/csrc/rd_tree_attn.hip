@@ -7,6 +7,8 @@ int tree_attn_bf16(const AttnArgs &a, int D, int waves, int rg_tiles, hipStream_
 int tree_attn_f16(const AttnArgs &a, int D, int waves, int rg_tiles, hipStream_t stream);
 int tree_attn_paged(const AttnArgs &a, int D, int waves, int rg_tiles, bool f16, hipStream_t stream);
 int tree_attn_f32(const AttnArgs &a, int D, hipStream_t stream);
+int tree_attn_rope_bf16(const AttnArgs &a, int D, int waves, int rg_tiles, hipStream_t stream);
+int tree_attn_rope_f16(const AttnArgs &a, int D, int waves, int rg_tiles, hipStream_t stream);
 }  // namespace rd
 
 static int attn_check_shape(int B, int H, int N, int D, int Cmax, rd_dtype dt)
@@ -52,6 +54,7 @@ extern "C" int rd_tree_attn(const void *q, const void *k_cache, const void *v_ca
     a.fuse_tree = plan.fuse_tree;
     a.n_rg = plan.n_rg;
     a.block_table = nullptr; a.page_size = 0; a.max_pages = 0; a.n_pages = 0;
+    a.position_ids = nullptr; a.cos_tab = nullptr; a.sin_tab = nullptr; a.max_pos = 0; a.k_rot = nullptr;
     if (dt == RD_BF16) return rd::tree_attn_bf16(a, D, plan.waves, plan.rg_tiles, (hipStream_t)stream);
     if (dt == RD_F16) return rd::tree_attn_f16(a, D, plan.waves, plan.rg_tiles, (hipStream_t)stream);
     return rd::tree_attn_f32(a, D, (hipStream_t)stream);
@@ -102,5 +105,45 @@ extern "C" int rd_tree_attn_paged(const void *q, const void *k_pages, const void
     a.xcd_remap = (((long long)B * H) % 8 == 0) ? 1 : 0;
     a.fuse_tree = plan.fuse_tree;
     a.n_rg = plan.n_rg;
+    a.position_ids = nullptr; a.cos_tab = nullptr; a.sin_tab = nullptr; a.max_pos = 0; a.k_rot = nullptr;
     return rd::tree_attn_paged(a, D, plan.waves, plan.rg_tiles, dt == RD_F16, (hipStream_t)stream);
+}
+
+// ---- rotary embedding fused into the call -------------------------------------------------------
+extern "C" int rd_tree_attn_rope(const void *q, const void *k_cache, const void *v_cache,
+                                 const int32_t *ctx_len, const void *k_new, const void *v_new,
+                                 const int32_t *n_packed, const uint64_t *tree_mask_bits,
+                                 const int32_t *position_ids, const float *cos_tab, const float *sin_tab, int max_pos,
+                                 int B, int H, int N, int D, int Cmax, rd_dtype dt, float scale,
+                                 void *out, void *k_new_rot, void *workspace, size_t workspace_bytes, void *stream)
+{
+    const int st = attn_check_shape(B, H, N, D, Cmax, dt);
+    if (st != RD_OK) return st;
+    if (dt != RD_BF16 && dt != RD_F16) return RD_ERR_UNSUPPORTED;            // the matrix-core kernels only
+    if (max_pos <= 0) return RD_ERR_INVALID_ARG;
+    if (!q || !k_new || !v_new || !ctx_len || !n_packed || !tree_mask_bits || !out || !position_ids || !cos_tab || !sin_tab)
+        return RD_ERR_INVALID_ARG;
+    if (Cmax > 0 && (!k_cache || !v_cache)) return RD_ERR_INVALID_ARG;
+    if (!rd_aligned(q, 16) || !rd_aligned(k_cache, 16) || !rd_aligned(v_cache, 16) || !rd_aligned(k_new, 16) ||
+        !rd_aligned(v_new, 16) || !rd_aligned(out, 16) || !rd_aligned(k_new_rot, 16) || !rd_aligned(tree_mask_bits, 8) ||
+        !rd_aligned(cos_tab, 4) || !rd_aligned(sin_tab, 4) || !rd_aligned(position_ids, 4))
+        return RD_ERR_INVALID_ARG;
+    if (k_new_rot == k_new || k_new_rot == q) return RD_ERR_INVALID_ARG;    // other workgroups still read the unrotated rows
+    const rd::AttnPlan plan = rd::attn_plan(B, H, N, D, Cmax, 2);
+    if (!workspace || !rd_aligned(workspace, 256) || workspace_bytes < plan.total_bytes) return RD_ERR_WORKSPACE;
+
+    rd::AttnArgs a;
+    a.q = q; a.k_cache = k_cache; a.v_cache = v_cache; a.k_new = k_new; a.v_new = v_new;
+    a.ctx_len = ctx_len; a.n_packed = n_packed; a.mask_bits = tree_mask_bits; a.out = out;
+    a.counters = static_cast<unsigned long long *>(workspace);
+    a.partials = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + plan.counters_bytes);
+    a.B = B; a.H = H; a.N = N; a.Cmax = Cmax; a.S = plan.S; a.words = (N + 63) / 64; a.rows_pad = plan.rows_pad;
+    a.scale_log2e = scale * 1.44269504088896340736f;
+    a.xcd_remap = (((long long)B * H) % 8 == 0) ? 1 : 0;
+    a.fuse_tree = plan.fuse_tree;
+    a.n_rg = plan.n_rg;
+    a.block_table = nullptr; a.page_size = 0; a.max_pages = 0; a.n_pages = 0;
+    a.position_ids = position_ids; a.cos_tab = cos_tab; a.sin_tab = sin_tab; a.max_pos = max_pos; a.k_rot = k_new_rot;
+    if (dt == RD_BF16) return rd::tree_attn_rope_bf16(a, D, plan.waves, plan.rg_tiles, (hipStream_t)stream);
+    return rd::tree_attn_rope_f16(a, D, plan.waves, plan.rg_tiles, (hipStream_t)stream);
 }

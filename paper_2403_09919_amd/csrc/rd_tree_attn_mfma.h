@@ -88,11 +88,34 @@ __device__ __forceinline__ float quad_sum(float x)
     return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
+// Rotary embedding of eight elements ("rotate half": element i pairs with element i + D/2), in the
+// arithmetic of rd_rope: fp32, every product rounded before the sum, one rounding to the storage
+// type.  `x` is this lane's 16-byte chunk, `partner` the chunk D/2 elements away in the same row,
+// cs / sn the cosines and sines of the eight pairs; `low`: x is the lower half of the pairs.
+template <typename T>
+__device__ __forceinline__ uint4 rope8(uint4 x, uint4 partner, const float (&cs)[8], const float (&sn)[8], bool low)
+{
+    typedef typename Elem<T>::vec8 vec8;
+    const vec8 xv = __builtin_bit_cast(vec8, x), pv = __builtin_bit_cast(vec8, partner);
+    vec8 y;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const float a = (float)xv[i], b = (float)pv[i];
+        const float xc = __fmul_rn(a, cs[i]), ps = __fmul_rn(b, sn[i]);
+        float r = low ? __fsub_rn(xc, ps) : __fadd_rn(xc, ps);
+        asm volatile("" : "+v"(r));               // an fp32 sum, then one rounding (as rd_rope does)
+        y[i] = (T)r;
+    }
+    return __builtin_bit_cast(uint4, y);
+}
+
 // TB = packed-key blocks the launch can need: ceil(N / block keys).  1 for all but the widest beams;
 // the mask words of every such block are fetched up front, so the common case should not pay for three.
 // PAGED: the context keys and values live in fixed-size pages found through a block table
 // (a.block_table, a.page_size, a.max_pages) instead of one dense [B,H,Cmax,D] tensor.
-template <typename T, int D, int NQ, int NW, int TB, bool PAGED>
+// ROPE: q and k_new arrive unrotated; the kernel applies the rotary embedding at a.position_ids
+// to the query rows as it brings them into LDS and to the packed-key tiles as it walks them.
+template <typename T, int D, int NQ, int NW, int TB, bool PAGED, bool ROPE = false>
 __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs a)
 {
     using G = Geo<D>;
@@ -184,6 +207,23 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
     for (int i = 0; i < kQPasses; ++i) {
         const int row = min(i * kQRowsPerPass + tid / G::kChunks, P - 1);    // rows >= P are zeroed below
         qreg[i] = ldg16(Qb + max(row, 0) * G::kRowBytes + (tid % G::kChunks) * 16);
+    }
+    // rotary embedding of the query rows: the partner chunk, and the cosines / sines of the row's position
+    constexpr int kHalfChunks = G::kChunks / 2;
+    uint4 qpart[ROPE ? kQPasses : 1];
+    float qcs[ROPE ? kQPasses : 1][8], qsn[ROPE ? kQPasses : 1][8];
+    if constexpr (ROPE) {
+#pragma unroll
+        for (int i = 0; i < kQPasses; ++i) {
+            const int row = max(min(i * kQRowsPerPass + tid / G::kChunks, P - 1), 0);
+            const int chunk = tid % G::kChunks;
+            qpart[i] = ldg16(Qb + row * G::kRowBytes + (chunk ^ kHalfChunks) * 16);
+            const int pos = clampi(a.position_ids[(size_t)b * a.N + row0 + row], 0, a.max_pos - 1);
+            const float *ct = a.cos_tab + (size_t)pos * (D / 2) + (chunk & (kHalfChunks - 1)) * 8;
+            const float *st = a.sin_tab + (size_t)pos * (D / 2) + (chunk & (kHalfChunks - 1)) * 8;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { qcs[i][e] = ct[e]; qsn[i][e] = st[e]; }
+        }
     }
     // Visibility of this wave's 32 keys, in each packed-key block, for the packed rows this lane
     // scores (row row0 + 16*qt + r16).  Context keys are visible to every row; packed keys per the
@@ -289,7 +329,8 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
         const int row = i * kQRowsPerPass + tid / G::kChunks;
         if (row < kRows)
             *reinterpret_cast<uint4 *>(sQ + row * G::kRowBytes + kswz<D>(row, tid % G::kChunks) * 16) =
-                (row < P) ? qreg[i] : make_uint4(0, 0, 0, 0);
+                (row < P) ? (ROPE ? rope8<T>(qreg[i], qpart[i], qcs[i], qsn[i], (tid % G::kChunks) < kHalfChunks) : qreg[i])
+                          : make_uint4(0, 0, 0, 0);
     }
 
     float m_run[NQ], l_run[NQ];
@@ -360,6 +401,31 @@ __global__ __launch_bounds__(NW * 64, 2) void rd_tree_attn_mfma_kernel(AttnArgs 
             // K registers -> own LDS tile (K swizzle); then fetch the next block's K.  The prefetch
             // is issued after the last block too (and ignored): a branch around it would make the
             // compiler wait for all loads in flight wherever it waits for one of them.
+            if constexpr (ROPE) {
+                if (cur_tree) {
+                    // packed keys: rotate at the key's position.  The partner chunk of the same row sits
+                    // kHalfChunks lanes away; rows past the end were redirected to the last packed key and
+                    // take its position.  The rotated rows also go to a.k_rot (what a cache stores).
+                    const int chunk = lane_l % G::kChunks;
+#pragma unroll
+                    for (int s = 0; s < G::kLoads; ++s) {
+                        const int key = tile0 + lane_l / G::kChunks + s * G::kRowsPerLoad;
+                        const int key_eff = min(key, tree_end - 1);
+                        uint4 pr;
+                        pr.x = __shfl_xor(kreg[s].x, kHalfChunks, 64); pr.y = __shfl_xor(kreg[s].y, kHalfChunks, 64);
+                        pr.z = __shfl_xor(kreg[s].z, kHalfChunks, 64); pr.w = __shfl_xor(kreg[s].w, kHalfChunks, 64);
+                        const int pos = clampi(a.position_ids[(size_t)b * a.N + key_eff], 0, a.max_pos - 1);
+                        const float *ct = a.cos_tab + (size_t)pos * (D / 2) + (chunk & (kHalfChunks - 1)) * 8;
+                        const float *st = a.sin_tab + (size_t)pos * (D / 2) + (chunk & (kHalfChunks - 1)) * 8;
+                        float cs[8], sn[8];
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) { cs[e] = ct[e]; sn[e] = st[e]; }
+                        kreg[s] = rope8<T>(kreg[s], pr, cs, sn, chunk < kHalfChunks);
+                        if (a.k_rot != nullptr && key < tree_end)
+                            *reinterpret_cast<uint4 *>(static_cast<unsigned char *>(a.k_rot) + ((size_t)bh * a.N + key) * G::kRowBytes + chunk * 16) = kreg[s];
+                    }
+                }
+            }
 #pragma unroll
             for (int s = 0; s < G::kLoads; ++s) *reinterpret_cast<uint4 *>(my_tile + k_wr(s)) = kreg[s];
             int pid_cur_next = 0, t0_next = 0;
@@ -705,63 +771,63 @@ static size_t mfma_smem_bytes()
            (size_t)NW * NQ * 16 * sizeof(float) + (size_t)NW * NQ * 64 * sizeof(uint32_t);
 }
 
-template <typename T, int D, int NQ, int NW, int TB, bool PAGED>
+template <typename T, int D, int NQ, int NW, int TB, bool PAGED, bool ROPE = false>
 static int launch_mfma(const AttnArgs &a, hipStream_t stream)
 {
     const size_t smem = mfma_smem_bytes<D, NQ, NW>();
     static std::atomic<unsigned long long> configured{0};
-    const int st = ensure_dynamic_lds(reinterpret_cast<const void *>(&rd_tree_attn_mfma_kernel<T, D, NQ, NW, TB, PAGED>), smem,
+    const int st = ensure_dynamic_lds(reinterpret_cast<const void *>(&rd_tree_attn_mfma_kernel<T, D, NQ, NW, TB, PAGED, ROPE>), smem,
                                       configured);
     if (st != RD_OK) return st;
     const size_t wgs = (size_t)a.B * a.H * (a.S + (a.fuse_tree ? 0 : 1)) * a.n_rg;
     if (wgs > 0x7fffffffull) return RD_ERR_UNSUPPORTED;
     const unsigned grid = (unsigned)wgs;
-    hipLaunchKernelGGL((rd_tree_attn_mfma_kernel<T, D, NQ, NW, TB, PAGED>), dim3(grid), dim3(NW * 64), smem, stream, a);
+    hipLaunchKernelGGL((rd_tree_attn_mfma_kernel<T, D, NQ, NW, TB, PAGED, ROPE>), dim3(grid), dim3(NW * 64), smem, stream, a);
     return rd_check_launch();
 }
 
 // rg_tiles = 16-row tiles per workgroup (the template's NQ); D = 128 kernels exist for 1..5 tiles,
 // D = 64 kernels for 1..8 (the plan never asks for more).  Beams with more packed keys than one
 // block (N > 32*NW) only occur with row groups, i.e. with kGroupTiles tiles.
-template <typename T, int D, int NW, bool PAGED>
+template <typename T, int D, int NW, bool PAGED, bool ROPE = false>
 static int dispatch_nq(const AttnArgs &a, int rg_tiles, hipStream_t stream)
 {
     constexpr int kGroupTiles = D == 128 ? 3 : 4;
     const int tb = (a.N + 32 * NW - 1) / (32 * NW);
     if (tb > 1) {
         if (rg_tiles != kGroupTiles) return RD_ERR_UNSUPPORTED;
-        if (tb == 2) return launch_mfma<T, D, kGroupTiles, NW, 2, PAGED>(a, stream);
+        if (tb == 2) return launch_mfma<T, D, kGroupTiles, NW, 2, PAGED, ROPE>(a, stream);
         if constexpr (NW == 4) {
-            if (tb == 3) return launch_mfma<T, D, kGroupTiles, 4, 3, PAGED>(a, stream);
+            if (tb == 3) return launch_mfma<T, D, kGroupTiles, 4, 3, PAGED, ROPE>(a, stream);
         }
         return RD_ERR_UNSUPPORTED;
     }
     switch (rg_tiles) {
-    case 1: return launch_mfma<T, D, 1, NW, 1, PAGED>(a, stream);
-    case 2: return launch_mfma<T, D, 2, NW, 1, PAGED>(a, stream);
-    case 3: return launch_mfma<T, D, 3, NW, 1, PAGED>(a, stream);
-    case 4: return launch_mfma<T, D, 4, NW, 1, PAGED>(a, stream);
-    case 5: return launch_mfma<T, D, 5, NW, 1, PAGED>(a, stream);
+    case 1: return launch_mfma<T, D, 1, NW, 1, PAGED, ROPE>(a, stream);
+    case 2: return launch_mfma<T, D, 2, NW, 1, PAGED, ROPE>(a, stream);
+    case 3: return launch_mfma<T, D, 3, NW, 1, PAGED, ROPE>(a, stream);
+    case 4: return launch_mfma<T, D, 4, NW, 1, PAGED, ROPE>(a, stream);
+    case 5: return launch_mfma<T, D, 5, NW, 1, PAGED, ROPE>(a, stream);
     default: break;
     }
     if constexpr (D == 64) {
         switch (rg_tiles) {
-        case 6: return launch_mfma<T, 64, 6, NW, 1, PAGED>(a, stream);
-        case 7: return launch_mfma<T, 64, 7, NW, 1, PAGED>(a, stream);
-        case 8: return launch_mfma<T, 64, 8, NW, 1, PAGED>(a, stream);
+        case 6: return launch_mfma<T, 64, 6, NW, 1, PAGED, ROPE>(a, stream);
+        case 7: return launch_mfma<T, 64, 7, NW, 1, PAGED, ROPE>(a, stream);
+        case 8: return launch_mfma<T, 64, 8, NW, 1, PAGED, ROPE>(a, stream);
         default: break;
         }
     }
     return RD_ERR_UNSUPPORTED;
 }
 
-template <typename T, bool PAGED>
+template <typename T, bool PAGED, bool ROPE = false>
 static int tree_attn_mfma(const AttnArgs &a, int D, int waves, int rg_tiles, hipStream_t stream)
 {
     if (D == 128)
-        return waves == 8 ? dispatch_nq<T, 128, 8, PAGED>(a, rg_tiles, stream)
-                          : dispatch_nq<T, 128, 4, PAGED>(a, rg_tiles, stream);
-    return dispatch_nq<T, 64, 4, PAGED>(a, rg_tiles, stream);
+        return waves == 8 ? dispatch_nq<T, 128, 8, PAGED, ROPE>(a, rg_tiles, stream)
+                          : dispatch_nq<T, 128, 4, PAGED, ROPE>(a, rg_tiles, stream);
+    return dispatch_nq<T, 64, 4, PAGED, ROPE>(a, rg_tiles, stream);
 }
 
 }  // namespace rd

@@ -31,7 +31,7 @@ def _declared_symbols():
 def test_header_symbols_exported(lib):
     names = _declared_symbols()
     assert names == sorted(["rd_strerror", "rd_version", "rd_dedup", "rd_tree_attn_workspace",
-                            "rd_tree_attn", "rd_tree_attn_paged_workspace", "rd_tree_attn_paged",
+                            "rd_tree_attn", "rd_tree_attn_rope", "rd_tree_attn_paged_workspace", "rd_tree_attn_paged",
                             "rd_accept_workspace", "rd_accept", "rd_accept_static", "rd_accept_sample_workspace", "rd_accept_sample", "rd_commit", "rd_commit_paged", "rd_rope",
                             "rd_draft_workspace", "rd_draft", "rd_draft_packed_elems", "rd_draft_pack_weights"])
     raw = ctypes.CDLL(LIB)
@@ -92,6 +92,25 @@ def test_tree_attn_argument_errors(lib):
     assert _attn(lib, ws=None) == WORKSPACE
     assert _attn(lib, ws=FAKE + 16) == WORKSPACE          # 256-byte alignment
     assert _attn(lib, ws_bytes=16) == WORKSPACE
+
+
+def test_tree_attn_rope_argument_errors(lib):
+    def call(B=1, H=2, N=16, D=64, Cmax=32, dt=1, q=FAKE, pos=FAKE, cos=FAKE, max_pos=64, krot=FAKE + 4096, ws=FAKE, ws_bytes=None):
+        need = lib.rd_tree_attn_workspace(B, H, N, D, Cmax, dt if dt in (0, 1, 2) else 1)
+        return lib.rd_tree_attn_rope(q, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, pos, cos, cos, max_pos,
+                                     B, H, N, D, Cmax, dt, 0.125, FAKE, krot, ws, need if ws_bytes is None else ws_bytes, None)
+    assert call(B=0) == INVALID
+    assert call(D=96) == UNSUPPORTED
+    assert call(dt=0) == UNSUPPORTED                      # 16-bit element types only
+    assert call(dt=7) == UNSUPPORTED
+    assert call(q=None) == INVALID
+    assert call(pos=None) == INVALID
+    assert call(cos=None) == INVALID
+    assert call(max_pos=0) == INVALID
+    assert call(krot=FAKE) == INVALID                     # the rotated keys must not overwrite q / k_new
+    assert call(krot=FAKE + 8) == INVALID                 # 16-byte alignment
+    assert call(ws=None) == WORKSPACE
+    assert call(ws_bytes=16) == WORKSPACE
 
 
 def test_workspace_sizes(lib):

@@ -88,3 +88,57 @@ def test_rotated_step_matches_oracle(rd):
     torch.cuda.synchronize()
     err = np.abs(synth.to_f64(host(out), cfg.dtype) - synth.to_f64(ref, cfg.dtype)).max()
     assert err <= 2e-2, err
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("D,B,H,W,L,ctx", [(128, 1, 32, 8, 5, [1024]),            # the Vicuna-7B-shaped layer
+                                           (128, 3, 2, 8, 5, [0, 517, 129]),      # ragged, an empty context
+                                           (64, 2, 3, 16, 6, [700, 33]),          # D = 64, six row tiles
+                                           (128, 2, 4, 16, 5, [5000, 2311]),      # long contexts: packed keys fused into the last range
+                                           (128, 2, 2, 70, 5, [97, 640]),         # the widest beams: row groups, three packed-key blocks
+                                           (128, 2, 8, 16, 5, [4096, 4096])])
+def test_fused_rope_equals_rope_then_attention(rd, dtype, D, B, H, W, L, ctx):
+    """rd_tree_attn_rope (q and k_new unrotated, rotation inside the attention call) against rd_rope
+    followed by rd_tree_attn -- bit for bit, the rotation arithmetic is the same -- and against the
+    oracle's rope -> tree attention chain within the attention tolerance; the rotated keys it hands back
+    equal rd_rope's."""
+    announce(f"fused rope {dtype} D={D} B={B} H={H} W={W} L={L}")
+    N = W * L
+    ctx = np.asarray(ctx, np.int32)
+    Cmax = int(ctx.max())
+    seed = D + W + B
+    beams = synth.make_beams(B, W, L, 6 if W > 16 else 32000, seed, "high" if W > 16 else "uniform")
+    q, kn, vn = synth.make_qkv_new(B, H, N, D, dtype, seed)
+    kc, vc = synth.make_kv_cache(B, H, Cmax, D, dtype, seed, ctx, True)
+    max_pos = 8192
+    cos, sin = tables(max_pos, D)
+    d = oracle.dedup(beams, ctx)
+    pos = np.maximum(d["position_ids"], 0)
+    scale = float(1.0 / np.sqrt(D))
+    q_r = oracle.rope(q, pos, d["n_packed"], cos, sin, dtype)
+    k_r = oracle.rope(kn, pos, d["n_packed"], cos, sin, dtype)
+    ref = oracle.tree_attn(q_r, kc, vc, ctx, k_r, vn, d["n_packed"], d["tree_mask"], dtype, scale)
+
+    ctx_d = dev(ctx)
+    dd = rd.rd_dedup(dev(beams), ctx_d)
+    cos_d, sin_d = dev(cos), dev(sin)
+    kc_d, vc_d, vn_d = dev(kc), dev(vc), dev(vn)
+    fused, k_rot = rd.rd_tree_attn_rope(dev(q), kc_d, vc_d, ctx_d, dev(kn), vn_d, dd["n_packed"], dd["tree_mask_bits"],
+                                        dd["position_ids"], cos_d, sin_d, scale)
+    q2, k2 = dev(q), dev(kn)
+    rd.rd_rope(q2, k2, dd["position_ids"], dd["n_packed"], cos_d, sin_d)
+    sep = rd.rd_tree_attn(q2, kc_d, vc_d, ctx_d, k2, vn_d, dd["n_packed"], dd["tree_mask_bits"], scale)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(fused), host(sep))
+    kr, k2h = host(k_rot), host(k2)
+    for b in range(B):
+        P = int(d["n_packed"][b])
+        assert np.array_equal(kr[b, :, :P], k2h[b, :, :P])
+        assert not kr[b, :, P:].any()                              # rows beyond the packed count untouched (allocated as zeros)
+    err = np.abs(synth.to_f64(host(fused), dtype) - synth.to_f64(ref, dtype)).max()
+    assert err <= (5e-3 if dtype == "f16" else 2e-2), err
+    # without the rotated-keys output
+    fused2, none = rd.rd_tree_attn_rope(dev(q), kc_d, vc_d, ctx_d, dev(kn), vn_d, dd["n_packed"], dd["tree_mask_bits"],
+                                        dd["position_ids"], cos_d, sin_d, scale, want_k_rot=False)
+    torch.cuda.synchronize()
+    assert none is None and np.array_equal(host(fused2), host(fused))
