@@ -50,7 +50,12 @@
 extern "C" {
 #endif
 
-typedef enum { RD_F32 = 0, RD_BF16 = 1, RD_F16 = 2 } rd_dtype;
+typedef enum {
+    RD_F32 = 0, RD_BF16 = 1, RD_F16 = 2,
+    /* not element types: the two bounds make every int a valid value of the type, so that a wrong code
+       passed by a caller is an RD_ERR_UNSUPPORTED return and never undefined behaviour */
+    RD_DTYPE_RANGE_LO = -2147483647 - 1, RD_DTYPE_RANGE_HI = 2147483647
+} rd_dtype;
 
 typedef enum {
     RD_OK = 0,

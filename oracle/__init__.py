@@ -32,13 +32,24 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def build_sanitized(out_dir: str) -> str:
+    """The same source with gcc's address and undefined-behaviour sanitizers (-O1, no recovery from
+    undefined behaviour), for the tests that run the oracle's pins under them.  The process that loads
+    it must have gcc's libasan preloaded."""
+    out = os.path.join(out_dir, "librd_oracle_san.so")
+    subprocess.check_call(["gcc", "-O1", "-g", "-fopenmp", "-shared", "-fPIC", "-Wall", "-fsanitize=address,undefined",
+                           "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer", "-o", out, _SRC, "-lm"])
+    return out
+
+
 _lib = None
 
 
 def lib() -> ctypes.CDLL:
     global _lib
     if _lib is None:
-        _lib = ctypes.CDLL(build())
+        # RD_ORACLE_LIB: a sanitizer build of this same source (tests/test_sanitizers.py)
+        _lib = ctypes.CDLL(os.environ.get("RD_ORACLE_LIB") or build())
         _lib.orc_num_threads.restype = ctypes.c_int
     return _lib
 

@@ -19,6 +19,13 @@ def lib():
     if not os.path.exists(LIB):
         pytest.fail("librd.so missing: run `python -m paper_2403_09919_amd.build`")
     from paper_2403_09919_amd import binding
+    other = os.environ.get("RD_TEST_LIB")           # a sanitizer build of the host code (tests/test_sanitizers.py)
+    if other:
+        san = ctypes.CDLL(other)
+        for name, (res, args) in binding.EXPORTS.items():
+            fn = getattr(san, name)
+            fn.restype, fn.argtypes = res, args
+        return san
     return binding.raw()
 
 
