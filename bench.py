@@ -128,10 +128,11 @@ class Workload:
             self.step(c)
         torch.cuda.synchronize()
 
-    def attn(self, c):
+    def attn(self, c, ctx_bound=None):
         d = c["dedup"]
         self.rd.rd_tree_attn(c["q"], c["k_cache"], c["v_cache"], c["ctx_len"], c["k_new"], c["v_new"],
-                             d["n_packed"], d["tree_mask_bits"], self.scale, out=c["attn_out"], workspace=self.ws_attn)
+                             d["n_packed"], d["tree_mask_bits"], self.scale, out=c["attn_out"], workspace=self.ws_attn,
+                             ctx_bound=ctx_bound)
 
     def dedup(self, c):
         self.rd.rd_dedup(c["beams"], c["ctx_len"], out=c["dedup"])
@@ -382,6 +383,7 @@ def main():
         one.copies, one.R = [wl.copies[0]] * R, R
         attn_warm_us = Rotation(one, wl.attn, stream, use_graph).spread(target_ms=8.0)["median"]
 
+    live_ctx = None if (args.no_extras or cfg.dtype == "f32") else live_context_point(cfg, rd, synth, torch, stream, use_graph)
     floor = None if args.no_floor else stream_read_floor(wl, stream, use_graph)
     draft = None if args.no_draft else time_draft(rd, cfg, stream, max(4, min(40, args.steps // 10)), torch)
 
@@ -411,6 +413,7 @@ def main():
         "kernels_us": kernels_us,
         "rd_tree_attn_us_spread": attn_spread,
         "rd_tree_attn_us_warm_cache": attn_warm_us,
+        "rd_tree_attn_live_context": live_ctx,
         # not measured: one decoder layer's attention core times the layer count of the LLaMA-family model of this
         # shape (32 / 40 / 60 layers for 32 / 40 / 52 heads), plus the per-step calls; no projections, no MLP
         "derived_attention_us_per_model_step": None if cfg.H not in LAYERS_BY_HEADS else round(
@@ -461,6 +464,22 @@ def main():
             result["configs"][str(args.config)]["oracle_steps_per_sec"] = result["cpu_baseline"]["value"]
             result["configs"][str(args.config)]["oracle_sample"] = result["cpu_baseline"]["sample"]
     print(json.dumps(result), flush=True)
+
+
+def live_context_point(cfg, rd, synth, torch, stream, use_graph, capacity=4096, live=600):
+    """The headline shape with a cache allocated for `capacity` keys that holds `live` of them: rd_tree_attn plans
+    from the capacity (all it knows), rd_tree_attn_bounded from the bound the caller passes."""
+    c2 = dataclasses.replace(cfg, ctx_lo=capacity, ctx_hi=capacity)
+    esz = 2
+    per_launch = 2 * c2.B * c2.H * live * c2.D * esz
+    R = min(64, max(2, -(-(512 << 20) // per_launch) + 1))           # > 512 MiB of K/V actually read per rotation
+    wl = Workload(c2, R, rd, synth, torch, ctx_override=live)
+    a = Rotation(wl, wl.attn, stream, use_graph).spread(target_ms=10.0)
+    b = Rotation(wl, lambda c: wl.attn(c, ctx_bound=live), stream, use_graph).spread(target_ms=10.0)
+    return {"workload": "%s with Cmax=%d, ctx_len=%d" % (cfg.name, capacity, live), "rotating_copies": R,
+            "algorithmic_bytes_per_launch": round(wl.attn_bytes, 1),
+            "rd_tree_attn_us": a["median"], "rd_tree_attn_bounded_us": b["median"],
+            "frac_of_peak_bounded": round(wl.attn_bytes / b["median"] / 1e3 / HBM_PEAK_GBS, 4)}
 
 
 def extras(wl, stream, use_graph, kernels_us, kernels_gbs, valid_rows, torch):

@@ -134,6 +134,25 @@ int rd_tree_attn(const void *q, const void *k_cache, const void *v_cache,
                  void *out, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * rd_tree_attn_bounded — rd_tree_attn for a cache whose capacity is far above the live contexts (a
+ * serving system allocates Cmax for the longest sequence it admits; Sec. 4.1's batches hold much shorter
+ * ones).  rd_tree_attn chooses how many workgroups share a head from Cmax, the only length the host
+ * knows; here the caller, who tracks sequence lengths, supplies ctx_bound, an upper bound of
+ * ctx_len[b] over the batch for this call, and the plan is made for that.  The bound only steers the
+ * plan: a sequence longer than ctx_bound is still computed in full, just with a plan that suits it
+ * less; values above Cmax mean Cmax.  Results are those of rd_tree_attn.
+ * workspace: at least rd_tree_attn_workspace(B, H, N, D, min(ctx_bound, Cmax), dt) bytes -- for a
+ * workspace shared by calls with different bounds, the largest of these -- otherwise as for
+ * rd_tree_attn (the zero-before-first-use contract does not depend on the bound: every call leaves the
+ * counters zero and they sit at the same place for every bound).
+ */
+int rd_tree_attn_bounded(const void *q, const void *k_cache, const void *v_cache,
+                         const int32_t *ctx_len, const void *k_new, const void *v_new,
+                         const int32_t *n_packed, const uint64_t *tree_mask_bits,
+                         int B, int H, int N, int D, int Cmax, int ctx_bound, rd_dtype dt, float scale,
+                         void *out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * rd_tree_attn_rope — rd_tree_attn with the rotary position embedding of the packed candidates applied
  * inside the call instead of by a separate rd_rope launch (the paper's LLMs, Vicuna, Sec. 4, are
  * LLaMA-family models whose attention rotates queries and keys; a packed token sits at position

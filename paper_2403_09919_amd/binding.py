@@ -35,6 +35,7 @@ EXPORTS = {
     "rd_dedup": (_i, [_vp, _vp, _i, _i, _i] + [_vp] * 8 + [_vp]),
     "rd_tree_attn_workspace": (_sz, [_i, _i, _i, _i, _i, _i]),
     "rd_tree_attn": (_i, [_vp] * 8 + [_i, _i, _i, _i, _i, _i, _f, _vp, _vp, _sz, _vp]),
+    "rd_tree_attn_bounded": (_i, [_vp] * 8 + [_i, _i, _i, _i, _i, _i, _i, _f, _vp, _vp, _sz, _vp]),
     "rd_tree_attn_rope": (_i, [_vp] * 8 + [_vp, _vp, _vp, _i] + [_i, _i, _i, _i, _i, _i, _f, _vp, _vp, _vp, _sz, _vp]),
     "rd_tree_attn_paged_workspace": (_sz, [_i, _i, _i, _i, _i, _i, _i]),
     "rd_tree_attn_paged": (_i, [_vp] * 4 + [_i, _i, _i] + [_vp] * 5 + [_i, _i, _i, _i, _i, _f, _vp, _vp, _sz, _vp]),
@@ -154,8 +155,10 @@ def rd_tree_attn_workspace(B: int, H: int, N: int, D: int, Cmax: int, dt: int) -
 
 
 def rd_tree_attn(q, k_cache, v_cache, ctx_len, k_new, v_new, n_packed, tree_mask_bits, scale: float,
-                 out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """q/k_new/v_new [B,H,N,D], k_cache/v_cache [B,H,Cmax,D] -> out [B,H,N,D] (see include/rd.h)."""
+                 out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                 ctx_bound: Optional[int] = None) -> torch.Tensor:
+    """q/k_new/v_new [B,H,N,D], k_cache/v_cache [B,H,Cmax,D] -> out [B,H,N,D] (see include/rd.h).  With
+    ctx_bound (an upper bound of ctx_len known to the caller) the call is rd_tree_attn_bounded."""
     B, H, N, D = q.shape
     Cmax = k_cache.shape[2]
     dt = _dt_code(q)
@@ -163,7 +166,21 @@ def rd_tree_attn(q, k_cache, v_cache, ctx_len, k_new, v_new, n_packed, tree_mask
     if out is None:
         out = torch.empty_like(q)
     if workspace is None:
-        workspace = new_workspace(rd_tree_attn_workspace(B, H, N, D, Cmax, dt), q.device)
+        workspace = new_workspace(rd_tree_attn_workspace(B, H, N, D, Cmax if ctx_bound is None else min(ctx_bound, Cmax), dt), q.device)
+    if ctx_bound is not None:
+        code = _lib.rd_tree_attn_bounded(
+            _ptr(q, q.dtype, (B, H, N, D), "q"),
+            _ptr(k_cache, q.dtype, (B, H, Cmax, D), "k_cache") if Cmax > 0 else None,
+            _ptr(v_cache, q.dtype, (B, H, Cmax, D), "v_cache") if Cmax > 0 else None,
+            _ptr(ctx_len, torch.int32, (B,), "ctx_len"),
+            _ptr(k_new, q.dtype, (B, H, N, D), "k_new"), _ptr(v_new, q.dtype, (B, H, N, D), "v_new"),
+            _ptr(n_packed, torch.int32, (B,), "n_packed"),
+            _ptr(tree_mask_bits, torch.int64, (B, N, words), "tree_mask_bits"),
+            B, H, N, D, Cmax, int(ctx_bound), dt, float(scale),
+            _ptr(out, q.dtype, (B, H, N, D), "out"),
+            _ptr(workspace, torch.uint8, None, "workspace"), workspace.numel(), _stream())
+        _check(code, "rd_tree_attn_bounded")
+        return out
     code = _lib.rd_tree_attn(
         _ptr(q, q.dtype, (B, H, N, D), "q"),
         _ptr(k_cache, q.dtype, (B, H, Cmax, D), "k_cache") if Cmax > 0 else None,

@@ -27,11 +27,14 @@ extern "C" size_t rd_tree_attn_workspace(int B, int H, int N, int D, int Cmax, r
     return rd::attn_plan(B, H, N, D, Cmax, dt == RD_F32 ? 4 : 2).total_bytes;
 }
 
-extern "C" int rd_tree_attn(const void *q, const void *k_cache, const void *v_cache,
-                            const int32_t *ctx_len, const void *k_new, const void *v_new,
-                            const int32_t *n_packed, const uint64_t *tree_mask_bits,
-                            int B, int H, int N, int D, int Cmax, rd_dtype dt, float scale,
-                            void *out, void *workspace, size_t workspace_bytes, void *stream)
+// Dense entry points: `plan_ctx` is the context length the launch plan is made for (the cache's
+// capacity Cmax, or a caller-supplied bound on the live contexts); the kernels themselves take every
+// sequence's range from its own ctx_len, whatever the plan assumed.
+static int tree_attn_dense(const void *q, const void *k_cache, const void *v_cache,
+                           const int32_t *ctx_len, const void *k_new, const void *v_new,
+                           const int32_t *n_packed, const uint64_t *tree_mask_bits,
+                           int B, int H, int N, int D, int Cmax, int plan_ctx, rd_dtype dt, float scale,
+                           void *out, void *workspace, size_t workspace_bytes, void *stream)
 {
     const int st = attn_check_shape(B, H, N, D, Cmax, dt);
     if (st != RD_OK) return st;
@@ -40,7 +43,7 @@ extern "C" int rd_tree_attn(const void *q, const void *k_cache, const void *v_ca
     if (!rd_aligned(q, 16) || !rd_aligned(k_cache, 16) || !rd_aligned(v_cache, 16) || !rd_aligned(k_new, 16) ||
         !rd_aligned(v_new, 16) || !rd_aligned(out, 16) || !rd_aligned(tree_mask_bits, 8))
         return RD_ERR_INVALID_ARG;
-    const rd::AttnPlan plan = rd::attn_plan(B, H, N, D, Cmax, dt == RD_F32 ? 4 : 2);
+    const rd::AttnPlan plan = rd::attn_plan(B, H, N, D, plan_ctx, dt == RD_F32 ? 4 : 2);
     if (!workspace || !rd_aligned(workspace, 256) || workspace_bytes < plan.total_bytes) return RD_ERR_WORKSPACE;
 
     rd::AttnArgs a;
@@ -58,6 +61,27 @@ extern "C" int rd_tree_attn(const void *q, const void *k_cache, const void *v_ca
     if (dt == RD_BF16) return rd::tree_attn_bf16(a, D, plan.waves, plan.rg_tiles, (hipStream_t)stream);
     if (dt == RD_F16) return rd::tree_attn_f16(a, D, plan.waves, plan.rg_tiles, (hipStream_t)stream);
     return rd::tree_attn_f32(a, D, (hipStream_t)stream);
+}
+
+extern "C" int rd_tree_attn(const void *q, const void *k_cache, const void *v_cache,
+                            const int32_t *ctx_len, const void *k_new, const void *v_new,
+                            const int32_t *n_packed, const uint64_t *tree_mask_bits,
+                            int B, int H, int N, int D, int Cmax, rd_dtype dt, float scale,
+                            void *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return tree_attn_dense(q, k_cache, v_cache, ctx_len, k_new, v_new, n_packed, tree_mask_bits, B, H, N, D, Cmax, Cmax, dt,
+                           scale, out, workspace, workspace_bytes, stream);
+}
+
+extern "C" int rd_tree_attn_bounded(const void *q, const void *k_cache, const void *v_cache,
+                                    const int32_t *ctx_len, const void *k_new, const void *v_new,
+                                    const int32_t *n_packed, const uint64_t *tree_mask_bits,
+                                    int B, int H, int N, int D, int Cmax, int ctx_bound, rd_dtype dt, float scale,
+                                    void *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (ctx_bound < 0) return RD_ERR_INVALID_ARG;
+    return tree_attn_dense(q, k_cache, v_cache, ctx_len, k_new, v_new, n_packed, tree_mask_bits, B, H, N, D, Cmax,
+                           ctx_bound < Cmax ? ctx_bound : Cmax, dt, scale, out, workspace, workspace_bytes, stream);
 }
 
 // ---- paged KV cache ---------------------------------------------------------------------------

@@ -38,7 +38,7 @@ def _declared_symbols():
 def test_header_symbols_exported(lib):
     names = _declared_symbols()
     assert names == sorted(["rd_strerror", "rd_version", "rd_dedup", "rd_tree_attn_workspace",
-                            "rd_tree_attn", "rd_tree_attn_rope", "rd_tree_attn_paged_workspace", "rd_tree_attn_paged",
+                            "rd_tree_attn", "rd_tree_attn_bounded", "rd_tree_attn_rope", "rd_tree_attn_paged_workspace", "rd_tree_attn_paged",
                             "rd_accept_workspace", "rd_accept", "rd_accept_static", "rd_accept_sample_workspace", "rd_accept_sample", "rd_commit", "rd_commit_paged", "rd_rope",
                             "rd_draft_workspace", "rd_draft", "rd_draft_packed_elems", "rd_draft_pack_weights"])
     raw = ctypes.CDLL(LIB)
@@ -99,6 +99,19 @@ def test_tree_attn_argument_errors(lib):
     assert _attn(lib, ws=None) == WORKSPACE
     assert _attn(lib, ws=FAKE + 16) == WORKSPACE          # 256-byte alignment
     assert _attn(lib, ws_bytes=16) == WORKSPACE
+
+
+def test_tree_attn_bounded_argument_errors(lib):
+    def call(B=1, H=2, N=16, D=64, Cmax=4096, bound=600, dt=1, q=FAKE, ws=FAKE, ws_bytes=None):
+        need = lib.rd_tree_attn_workspace(B, H, N, D, min(max(bound, 0), Cmax), dt)
+        return lib.rd_tree_attn_bounded(q, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, B, H, N, D, Cmax, bound, dt, 0.125,
+                                        FAKE, ws, need if ws_bytes is None else ws_bytes, None)
+    assert call(B=0) == INVALID
+    assert call(bound=-1) == INVALID
+    assert call(D=96) == UNSUPPORTED
+    assert call(q=None) == INVALID
+    assert call(ws=None) == WORKSPACE
+    assert call(ws_bytes=16) == WORKSPACE
 
 
 def test_tree_attn_rope_argument_errors(lib):

@@ -365,3 +365,35 @@ def test_paged_equals_dense_on_config2(rd):
                                 dev(t["v_new"]), dev(d["n_packed"]), dev(d["tree_mask_bits"]), scale)
     torch.cuda.synchronize()
     assert np.array_equal(host(got), dense)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_plan_from_a_context_bound(rd, dtype):
+    """A cache allocated for 4096 keys holding contexts of a few hundred: rd_tree_attn_bounded plans for the
+    bound the caller passes (exact, generous, or too small -- the bound steers the plan, never the result)
+    and must give what rd_tree_attn gives; one workspace serves all the bounds."""
+    announce("attn planned from a context bound, " + dtype)
+    B, H, D, W, L, Cmax = 2, 8, 128, 8, 5, 4096
+    ctx = np.array([600, 411], np.int32)
+    t = make_case(B, H, D, W, L, ctx, dtype, seed=9, V=32000)
+    for name in ("k_cache", "v_cache"):                      # the live rows at the front of a Cmax-row cache, poison behind
+        full = np.full((B, H, Cmax, D), synth.poison_value(dtype), t[name].dtype)
+        full[:, :, : t[name].shape[2]] = t[name]
+        t[name] = full
+    d = oracle.dedup(t["beams"], t["ctx_len"])
+    scale = float(1.0 / np.sqrt(D))
+    ref = oracle.tree_attn(t["q"], t["k_cache"], t["v_cache"], t["ctx_len"], t["k_new"], t["v_new"],
+                           d["n_packed"], d["tree_mask"], dtype, scale)
+    td = {k: dev(v) for k, v in t.items()}
+    npk, mask = dev(d["n_packed"]), dev(d["tree_mask_bits"])
+    dt_code = rd.RD_BF16 if dtype == "bf16" else rd.RD_F32
+    nbytes = max(rd.rd_tree_attn_workspace(B, H, W * L, D, c, dt_code) for c in (600, 1024, 300, 4096))
+    ws = rd.new_workspace(nbytes, "cuda")
+    base = rd.rd_tree_attn(td["q"], td["k_cache"], td["v_cache"], td["ctx_len"], td["k_new"], td["v_new"], npk, mask, scale)
+    torch.cuda.synchronize()
+    compare(host(base), ref, dtype, "capacity plan")
+    for bound in (600, 1024, 300, 4096, 100000):
+        got = rd.rd_tree_attn(td["q"], td["k_cache"], td["v_cache"], td["ctx_len"], td["k_new"], td["v_new"], npk, mask, scale,
+                              workspace=ws, ctx_bound=bound)
+        torch.cuda.synchronize()
+        compare(host(got), ref, dtype, "bound %d" % bound)
