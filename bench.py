@@ -361,8 +361,11 @@ def main():
     steps_per_s = 1e6 / step_us
 
     # ---- timed region 2: the dominant kernel alone (rd_tree_attn), events on its own stream ----------
+    # At least ten rotations of launches, so that a short --steps (the step region above times exactly
+    # --steps steps, however few) does not leave this figure to the first cold launches after the flush.
     attn_rot = Rotation(wl, wl.attn, stream, use_graph)
-    attn_us, _ = attn_rot.timed(args.warmup, args.steps, flush)
+    attn_launches = max(args.steps, 10 * R)
+    attn_us, _ = attn_rot.timed(max(args.warmup, R), attn_launches, flush)
     achieved = wl.attn_bytes / (attn_us * 1e-6) / 1e9
     attn_spread = attn_rot.spread(est_us=attn_us)
 
@@ -430,6 +433,7 @@ def main():
             "traffic": traffic.get(args.config),
             "algorithmic_bytes_per_launch": round(wl.attn_bytes, 1),
             "us_per_launch": round(attn_us, 3),
+            "launches_timed": attn_launches,
             "launch": launch,
             "stream_read_floor": floor,
         },
