@@ -48,7 +48,12 @@ static inline AttnPlan attn_plan(int B, int H, int N, int D, int Cmax, size_t el
     const double kv_bytes = 2.0 * (double)BH * Cmax * D * (double)elem_bytes;
     const bool small = kv_bytes < 64e6;          // latency-bound: few blocks per range
     static const int waves_env = env_int("RD_ATTN_WAVES", 0);
-    p.waves = (elem_bytes == 2 && D == 128 && small) ? 8 : 4;
+    // Eight waves also when the heads alone come to one workgroup per compute unit (129..256 of them): such a
+    // launch has no second workgroup per compute unit to overlap with, and eight waves keep 128 KB of loads in
+    // flight per compute unit instead of 64 KB.
+    const long long units_est = BH * (((N + 15) / 16 <= (D == 128 ? 5 : 8)) ? 1 : ((N + 15) / 16 + (D == 128 ? 3 : 4) - 1) / (D == 128 ? 3 : 4));
+    const bool one_per_cu = units_est > 128 && units_est <= 256 && (Cmax + 255) / 256 >= 4;   // long enough to take the packed keys along
+    p.waves = (elem_bytes == 2 && D == 128 && (small || one_per_cu)) ? 8 : 4;
     if (waves_env == 4 || (waves_env == 8 && elem_bytes == 2 && D == 128)) p.waves = waves_env;
     const int block_keys = elem_bytes == 2 ? 32 * p.waves : kBlockKeys;
     const int nblk = (Cmax + block_keys - 1) / block_keys;
@@ -81,6 +86,7 @@ static inline AttnPlan attn_plan(int B, int H, int N, int D, int Cmax, size_t el
         if (n_part > 1) T += 3e-6 + 2.0 * (double)BH * n_rg * n_part * part_bytes / 4e12;
         if (T < best_T * (1.0 - 1e-9)) { best_T = T; best_S = S; }
     }
+    if (p.waves == 8 && one_per_cu && !small) best_S = 1;     // the heads fill the compute units by themselves
     static const int forced = env_int("RD_ATTN_SPLITS", 0);
     if (forced > 0) best_S = forced < nblk ? forced : (nblk > 0 ? nblk : 1);
     p.S = best_S;

@@ -81,14 +81,25 @@ def test_config2_vicuna7b_full(rd):
 
 @pytest.mark.parametrize("idx", [3, 4, 5])
 def test_full_size_configs_whole_tensor(rd, idx):
-    """Full-size tensors in the launch configuration the benchmark uses (four-wave workgroups, three,
-    four and five row tiles, one key range per head or three), every head and every row against the
-    oracle."""
+    """Full-size tensors in the launch configuration the benchmark uses (configs 3 and 4: eight-wave
+    workgroups with three and five row tiles, one key range per head; config 5: four-wave workgroups
+    with five row tiles), every head and every row against the oracle."""
     cfg = synth.CONFIGS[idx]
     announce("attn config %d (bf16, full size, whole tensor)" % idx)
     t = synth.make_attn_inputs(cfg)
     err = full_check(rd, t, cfg.dtype, what="cfg%d" % idx)
     print("cfg%d whole-tensor max abs err %.3e" % (idx, err))
+
+
+def test_four_wave_three_tiles_whole_tensor(rd):
+    """More heads than compute units and more than 64 MB of K/V: four-wave workgroups with three row
+    tiles, one fused key range per head, ragged contexts; every head and row against the oracle."""
+    announce("attn bf16, 320 heads, 4-wave workgroups, whole tensor")
+    B, H, D, W, L = 10, 32, 128, 8, 5
+    ctx = [704, 641, 577, 700, 513, 690, 1, 333, 704, 129]
+    assert 2 * B * H * max(ctx) * D * 2 >= 64e6 and B * H > 256
+    t = make_case(B, H, D, W, L, ctx, "bf16", seed=320, V=32000)
+    full_check(rd, t, "bf16", what="4-wave-3-tiles")
 
 
 def test_fp16_large_cache_whole_tensor(rd):
