@@ -238,7 +238,8 @@ int rd_accept(const float *logits, const int32_t *beams, const int32_t *unpack_i
  * arguments, outputs and kernel as rd_accept, minus the workspace: the counters and row keys live in
  * a device array inside the library, RD_ACCEPT_STATIC_BYTES (1 MiB) per GPU, held by every GPU the
  * library runs on until the process ends.  The call allocates nothing and frees nothing (on a GPU's
- * first call it looks up the array's address once) and enqueues two kernels on `stream`: one that
+ * first call it looks up the array's address once; a caller that captures graphs makes one call on
+ * that GPU before the capture begins) and enqueues two kernels on `stream`: one that
  * clears the part of the array the call uses, then rd_accept's.
  *
  * Sizes with rd_accept_workspace(B, W, L, V) > RD_ACCEPT_STATIC_BYTES (about B*W*L > 87000 packed rows)
