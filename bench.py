@@ -57,7 +57,7 @@ def parse():
     ap.add_argument("--no-extras", action="store_true",
                     help="headline kernels only: no warm-cache figure, no rd_commit / rd_accept_sample / live-context "
                          "timings (so that a kernel trace or counter run holds the step's launches only)")
-    ap.add_argument("--cpu-seconds", type=float, default=8.0, help="CPU time budget of the oracle baseline")
+    ap.add_argument("--cpu-seconds", type=float, default=20.0, help="CPU time budget of the oracle baseline")
     ap.add_argument("--pmc-calib", action="store_true",
                     help="also run plain device copies of 64 MiB (reference dispatches for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters)")
