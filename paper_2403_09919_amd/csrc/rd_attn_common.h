@@ -47,16 +47,6 @@ static inline AttnPlan attn_plan(int B, int H, int N, int D, int Cmax, size_t el
     const long long BH = (long long)B * H;
     const double kv_bytes = 2.0 * (double)BH * Cmax * D * (double)elem_bytes;
     const bool small = kv_bytes < 64e6;          // latency-bound: few blocks per range
-    static const int waves_env = env_int("RD_ATTN_WAVES", 0);
-    // Eight waves also when the heads alone come to one workgroup per compute unit (129..256 of them): such a
-    // launch has no second workgroup per compute unit to overlap with, and eight waves keep 128 KB of loads in
-    // flight per compute unit instead of 64 KB.
-    const long long units_est = BH * (((N + 15) / 16 <= (D == 128 ? 5 : 8)) ? 1 : ((N + 15) / 16 + (D == 128 ? 3 : 4) - 1) / (D == 128 ? 3 : 4));
-    const bool one_per_cu = units_est > 128 && units_est <= 256 && (Cmax + 255) / 256 >= 4;   // long enough to take the packed keys along
-    p.waves = (elem_bytes == 2 && D == 128 && (small || one_per_cu)) ? 8 : 4;
-    if (waves_env == 4 || (waves_env == 8 && elem_bytes == 2 && D == 128)) p.waves = waves_env;
-    const int block_keys = elem_bytes == 2 ? 32 * p.waves : kBlockKeys;
-    const int nblk = (Cmax + block_keys - 1) / block_keys;
     // Packed rows per workgroup: all of them while they fit the register budget (5 row tiles at
     // D = 128, 8 at D = 64); wider beams are cut into row groups of 3 (4) tiles, each a workgroup
     // of its own per key range (K/V are then re-read per group, from L2 mostly).
@@ -67,6 +57,17 @@ static inline AttnPlan attn_plan(int B, int H, int N, int D, int Cmax, size_t el
     if (tiles_env >= nq_grp && tiles_env <= nq_max) nq_max = tiles_env;
     const int nq = elem_bytes == 2 ? (nq_all <= nq_max ? nq_all : nq_grp) : nq_all;
     const int n_rg = elem_bytes == 2 ? (nq_all + nq - 1) / nq : 1;
+    // Waves per workgroup: eight for small working sets, and also when the heads (and row groups) alone come
+    // to one workgroup per compute unit (129..256 of them) over contexts long enough to take the packed keys
+    // along: such a launch has no second workgroup per compute unit to overlap with, and eight waves keep
+    // 128 KB of loads in flight per compute unit instead of 64 KB.
+    static const int waves_env = env_int("RD_ATTN_WAVES", 0);
+    const long long units = BH * n_rg;
+    const bool one_per_cu = units > 128 && units <= 256 && (Cmax + 255) / 256 >= 4;
+    p.waves = (elem_bytes == 2 && D == 128 && (small || one_per_cu)) ? 8 : 4;
+    if (waves_env == 4 || (waves_env == 8 && elem_bytes == 2 && D == 128)) p.waves = waves_env;
+    const int block_keys = elem_bytes == 2 ? 32 * p.waves : kBlockKeys;
+    const int nblk = (Cmax + block_keys - 1) / block_keys;
     const long long slots = (elem_bytes == 2 && p.waves == 4 && nq <= 5) ? 512 : 256;
     const bool can_fuse = elem_bytes == 2;
     const double blk_bytes = 2.0 * block_keys * D * (double)elem_bytes;      // K and V of one block of one head
