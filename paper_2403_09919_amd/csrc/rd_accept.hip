@@ -27,6 +27,7 @@ struct AccPlan {
     int chunks;       // chunks per logit row
     int chunk_len;    // floats per chunk (multiple of 1024)
     int loads;        // 16-byte loads per thread issued together (1, 2, 4, ..., 32)
+    int speculate;    // 1: first loads before the packed count is known (small logit tensors)
     size_t row_counters_off, keys_off;   // byte offsets in the workspace (sequence counters at 0)
     size_t total_bytes;                  // all of it must be zero between calls (and is left so)
 };
@@ -44,6 +45,9 @@ AccPlan acc_plan(int B, int N, int V)
     if (loads_env == 1 || loads_env == 2 || loads_env == 4 || loads_env == 8 || loads_env == 16 || loads_env == 32) loads = loads_env;
     while ((V + 1024 * loads - 1) / (1024 * loads) > kMaxChunks) loads *= 2;     // huge vocabularies: the kernel loops
     p.loads = loads > 32 ? 32 : loads;
+    static const int spec_env = rd::env_int("RD_ACCEPT_SPEC", -1);       // tuning builds only
+    p.speculate = ((double)B * N * V * sizeof(float) <= 8e6 && p.loads <= 8) ? 1 : 0;
+    if (spec_env >= 0) p.speculate = spec_env ? 1 : 0;
     int len = 1024 * loads;
     p.chunk_len = len;
     p.chunks = (V + len - 1) / len;
@@ -85,7 +89,10 @@ __device__ __forceinline__ bool arrive(uint32_t *counter, uint32_t expected)
     return prev + 1u == expected;
 }
 
-template <int U>
+// SPEC: the first batch of logit loads is issued before n_packed[b] is known (every row of the [B,N,V] tensor is
+// allocated, so a row beyond the packed count is read and dropped): one dependent round trip less in front
+// of the stream.  For launches whose whole logit tensor is a few MB, where the extra rows cost nothing.
+template <int U, bool SPEC>
 __global__ __launch_bounds__(kAccThreads) void rd_accept_kernel(
     const float *__restrict__ logits, const int32_t *__restrict__ beams,
     const int32_t *__restrict__ unpack_index, const int32_t *__restrict__ n_packed,
@@ -104,6 +111,17 @@ __global__ __launch_bounds__(kAccThreads) void rd_accept_kernel(
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int chunk = blockIdx.x, p = blockIdx.y, b = blockIdx.z;
     const int N = W * L;
+    const float *row = logits + ((size_t)b * N + p) * V;
+    const int v0 = chunk * chunk_len;
+    const int v1 = min(V, v0 + chunk_len);
+    float4 x0[U];
+    if (SPEC && (V & 3) == 0) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int v = v0 + (u * kAccThreads + tid) * 4;
+            x0[u] = *reinterpret_cast<const float4 *>(row + (v < v1 ? v : v0));
+        }
+    }
     int P = n_packed[b];
     P = P < 1 ? 1 : (P > N ? N : P);
     if (p >= P) return;                                   // whole workgroup: row is padding
@@ -124,9 +142,6 @@ __global__ __launch_bounds__(kAccThreads) void rd_accept_kernel(
     if (root_token != nullptr) my_root = root_token[b];
 
     // ---- phase 1: this chunk's (max, first index) -> the row's key ---------------------------------
-    const float *row = logits + ((size_t)b * N + p) * V;
-    const int v0 = chunk * chunk_len;
-    const int v1 = min(V, v0 + chunk_len);
     float bv = -INFINITY;
     int bi = 0x7fffffff;
     if ((V & 3) == 0) {
@@ -137,7 +152,8 @@ __global__ __launch_bounds__(kAccThreads) void rd_accept_kernel(
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int v = base + (u * kAccThreads + tid) * 4;
-                x[u] = *reinterpret_cast<const float4 *>(row + (v < v1 ? v : v0));
+                if (SPEC && base == v0) x[u] = x0[u];
+                else x[u] = *reinterpret_cast<const float4 *>(row + (v < v1 ? v : v0));
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {                              // ascending v per thread
@@ -277,19 +293,25 @@ static int accept_launch(const AccPlan &plan, const float *logits, const int32_t
     uint32_t *seq_counters = reinterpret_cast<uint32_t *>(ws);
     uint32_t *row_counters = reinterpret_cast<uint32_t *>(ws + plan.row_counters_off);
     unsigned long long *row_keys = reinterpret_cast<unsigned long long *>(ws + plan.keys_off);
-#define RD_ACCEPT_LAUNCH(U)                                                                                   \
-    hipLaunchKernelGGL(rd_accept_kernel<U>, grid, block, 0, stream, logits, beams, unpack_index,               \
+#define RD_ACCEPT_LAUNCH_(U, SPEC)                                                                            \
+    hipLaunchKernelGGL((rd_accept_kernel<U, SPEC>), grid, block, 0, stream, logits, beams, unpack_index,       \
                        n_packed, root_token, W, L, V, plan.chunks, plan.chunk_len, argmax_out, n_accept,       \
                        best_beam, best_len, next_token, accepted_idx, seq_counters, row_counters, row_keys)
+#define RD_ACCEPT_LAUNCH(U)                                 \
+    do {                                                    \
+        if (plan.speculate) RD_ACCEPT_LAUNCH_(U, true);     \
+        else RD_ACCEPT_LAUNCH_(U, false);                   \
+    } while (0)
     switch (plan.loads) {
     case 1: RD_ACCEPT_LAUNCH(1); break;
     case 2: RD_ACCEPT_LAUNCH(2); break;
     case 4: RD_ACCEPT_LAUNCH(4); break;
     case 8: RD_ACCEPT_LAUNCH(8); break;
-    case 16: RD_ACCEPT_LAUNCH(16); break;
-    default: RD_ACCEPT_LAUNCH(32); break;
+    case 16: RD_ACCEPT_LAUNCH_(16, false); break;
+    default: RD_ACCEPT_LAUNCH_(32, false); break;
     }
 #undef RD_ACCEPT_LAUNCH
+#undef RD_ACCEPT_LAUNCH_
     return rd_check_launch();
 }
 
